@@ -1,0 +1,470 @@
+/*
+ * OCTOPUS CPU oracle -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+ *
+ * A plain, slow, fp64 implementation of the OCTOPUS key codec and of
+ * attention over the reconstructed keys, written from the paper so that a
+ * reader can check it against the paper by eye.  It shares nothing with the
+ * HIP library (no headers, tables, helpers).  Only tests, the smoke check and
+ * the benchmark's cpu_baseline leg may load it.
+ *
+ * What follows what:
+ *   rotation            Eq. (rotation), Sec. 3.1: u = H diag(s) u~, H the
+ *                       normalised Sylvester Hadamard matrix, written out as
+ *                       the O(d^2) matrix product (no butterfly).
+ *   triplets            Sec. 3.2: ceil(d/3) contiguous triplets, zero padded.
+ *   Oct / Oct^-1        Eq. (oct-encode), Eq. (oct-decode), sign(0) = +1.
+ *   encoder             Alg. 1 (encoder with joint rounding), step by step.
+ *   stream packing      Alg. 1 last step; stream sizes are the ones the KV
+ *                       ratios of Table (kernel speed) imply.
+ *   scores, attention   Eq. (score-exact), Alg. 2: computed here as the plain
+ *                       definition softmax(scale * q K^T) V on the
+ *                       materialised reconstructed keys k^ = gamma R^T u^.
+ *
+ * Readings where the paper is silent (all listed in the design notes):
+ *   eps = 1e-20 for both clamped divisors; searchsorted counts boundaries
+ *   strictly below the value; candidate order dx outer, dy inner, each
+ *   -1,0,+1, strict '>' keeps the first maximum; streams are LSB-first;
+ *   index counts are padded with zeros to whole byte groups.
+ *
+ * Parity unpinned by the paper (fixed by this build's readings only): the
+ * two-class plans for half-integer bit widths, eps, tie order, bit order.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define OCT_EPS 1e-20
+#define OCT_MAXC 64
+
+typedef struct {
+    int32_t d;             /* head dimension, power of two                    */
+    int32_t n_tri;         /* ceil(d / 3)                                     */
+    int32_t n_class;       /* 1, or 2 for a half-integer nominal bit width    */
+    int32_t class_ntri[2]; /* class 0 = first class_ntri[0] triplets          */
+    int32_t b_dir[2];      /* bits per octahedral coordinate, per class       */
+    int32_t b_nrm[2];      /* bits per triplet norm, per class                */
+    double c_xi[2][OCT_MAXC];  /* C_xi centroids, ascending                   */
+    double b_xi[2][OCT_MAXC];  /* B_xi midpoints (2^b_dir - 1 used)           */
+    double c_rho[2][OCT_MAXC]; /* C_rho centroids, ascending                  */
+    double b_rho[2][OCT_MAXC]; /* B_rho midpoints (2^b_nrm - 1 used)          */
+} oracle_plan;
+
+/* ---- stream geometry (Table kernel-speed KV ratios) ---------------------- */
+
+static int gcd_int(int a, int b) { while (b) { int t = a % b; a = b; b = t; } return a; }
+
+/* bytes of a stream of n indices of b bits: the index count is padded to a
+ * whole number of byte groups, a group being the fewest indices that fill
+ * whole bytes. */
+int oracle_stream_bytes(int n, int b)
+{
+    if (b <= 0 || n <= 0) return 0;
+    int g = 8 / gcd_int(b, 8);
+    int groups = (n + g - 1) / g;
+    return groups * (g * b / 8);
+}
+
+int oracle_dir_bytes(const oracle_plan *p)
+{
+    int s = 0;
+    for (int c = 0; c < p->n_class; ++c) s += oracle_stream_bytes(2 * p->class_ntri[c], p->b_dir[c]);
+    return s;
+}
+
+int oracle_nrm_bytes(const oracle_plan *p)
+{
+    int s = 0;
+    for (int c = 0; c < p->n_class; ++c) s += oracle_stream_bytes(p->class_ntri[c], p->b_nrm[c]);
+    return s;
+}
+
+/* canonical record of one key: [gamma fp32][dir streams][nrm streams] */
+int oracle_record_bytes(const oracle_plan *p) { return 4 + oracle_dir_bytes(p) + oracle_nrm_bytes(p); }
+
+static int class_of(const oracle_plan *p, int i) { return (i < p->class_ntri[0]) ? 0 : 1; }
+
+/* ---- rotation: Eq. (rotation) ------------------------------------------- */
+
+/* y = H x with H[i][j] = (-1)^popcount(i & j) / sqrt(d), the definition. */
+void oracle_hadamard(const double *x, double *y, int d)
+{
+    double inv = 1.0 / sqrt((double)d);
+    for (int i = 0; i < d; ++i) {
+        double acc = 0.0;
+        for (int j = 0; j < d; ++j)
+            acc += (__builtin_parity((unsigned)(i & j)) ? -x[j] : x[j]);
+        y[i] = acc * inv;
+    }
+}
+
+/* u = R x = H (s . x) */
+void oracle_rotate(const double *x, const int8_t *s, double *u, int d)
+{
+    double *t = (double *)malloc(sizeof(double) * d);
+    for (int j = 0; j < d; ++j) t[j] = (double)s[j] * x[j];
+    oracle_hadamard(t, u, d);
+    free(t);
+}
+
+/* x = R^T u = s . (H u) */
+void oracle_rotate_inverse(const double *u, const int8_t *s, double *x, int d)
+{
+    oracle_hadamard(u, x, d);
+    for (int j = 0; j < d; ++j) x[j] *= (double)s[j];
+}
+
+/* ---- octahedral map: Eq. (oct-encode), Eq. (oct-decode) ------------------ */
+
+static double sgn1(double v) { return (v >= 0.0) ? 1.0 : -1.0; } /* sign(0) = +1 */
+
+void oracle_oct_encode(const double t[3], double *xi, double *eta)
+{
+    double l1 = fabs(t[0]) + fabs(t[1]) + fabs(t[2]);
+    double den = (l1 > OCT_EPS) ? l1 : OCT_EPS;
+    double px = t[0] / den, py = t[1] / den, pz = t[2] / den;
+    if (pz >= 0.0) { *xi = px; *eta = py; }
+    else { *xi = sgn1(px) * (1.0 - fabs(py)); *eta = sgn1(py) * (1.0 - fabs(px)); }
+}
+
+void oracle_oct_decode(double xi, double eta, double n[3])
+{
+    double r = 1.0 - fabs(xi) - fabs(eta);
+    double a = xi, b = eta;
+    if (r < 0.0) { a = sgn1(xi) * (1.0 - fabs(eta)); b = sgn1(eta) * (1.0 - fabs(xi)); }
+    double nn = sqrt(a * a + b * b + r * r);
+    n[0] = a / nn; n[1] = b / nn; n[2] = r / nn;
+}
+
+/* searchsorted: number of boundaries strictly below v */
+static int count_below(const double *bnd, int n, double v)
+{
+    int j = 0;
+    for (int k = 0; k < n; ++k) if (bnd[k] < v) ++j;
+    return j;
+}
+
+static double clip01(double v) { return v < 0.0 ? 0.0 : (v > 1.0 ? 1.0 : v); }
+static int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
+/* ---- encoder: Alg. 1 ----------------------------------------------------- */
+
+/* mode: 0 = Alg. 1 with Delta = {(0,0)}, 1 = local 3x3 (default),
+ *       2 = full K x K grid, 3 = three independent nearest-centroid rounds
+ *       (Sec. 3.5, first paragraph: the radius code is the centroid nearest
+ *       to rho_i itself, not to s*; this is what the "scalar" rows of the
+ *       rounding ablation print).
+ * Outputs per key: gamma, idx_dir[2*n_tri] (order (i,0),(i,1)), idx_nrm[n_tri];
+ * optional diagnostics (may be NULL): u[d], xi_eta[2*n_tri], s_star[n_tri]. */
+void oracle_encode_key(const oracle_plan *p, const double *k, const int8_t *s, int mode,
+                       double *gamma_out, int32_t *idx_dir, int32_t *idx_nrm,
+                       double *u_out, double *xi_eta_out, double *s_star_out)
+{
+    int d = p->d;
+    double *ut = (double *)calloc((size_t)3 * p->n_tri + d, sizeof(double));
+    double *u = ut;               /* 3*n_tri entries, zero padded */
+    double *tmp = ut + 3 * p->n_tri;
+
+    double g2 = 0.0;
+    for (int j = 0; j < d; ++j) g2 += k[j] * k[j];
+    double gamma = sqrt(g2);
+    double den = (gamma > OCT_EPS) ? gamma : OCT_EPS;
+    for (int j = 0; j < d; ++j) tmp[j] = k[j] / den;
+    oracle_rotate(tmp, s, u, d);
+    *gamma_out = gamma;
+    if (u_out) memcpy(u_out, u, sizeof(double) * d);
+
+    for (int i = 0; i < p->n_tri; ++i) {
+        int c = class_of(p, i);
+        int K = 1 << p->b_dir[c], M = 1 << p->b_nrm[c];
+        const double *cx = p->c_xi[c], *bx = p->b_xi[c];
+        const double *t = u + 3 * i;
+        double xi, eta;
+        oracle_oct_encode(t, &xi, &eta);
+        int jx = count_below(bx, K - 1, xi);
+        int jy = count_below(bx, K - 1, eta);
+        double s_star = -INFINITY;
+        int Jx = jx, Jy = jy;
+        if (mode == 2) {
+            for (int ax = 0; ax < K; ++ax)
+                for (int ay = 0; ay < K; ++ay) {
+                    double n[3];
+                    oracle_oct_decode(cx[ax], cx[ay], n);
+                    double sc = t[0] * n[0] + t[1] * n[1] + t[2] * n[2];
+                    if (sc > s_star) { s_star = sc; Jx = ax; Jy = ay; }
+                }
+        } else {
+            int r = (mode == 0 || mode == 3) ? 0 : 1;
+            for (int dx = -r; dx <= r; ++dx)
+                for (int dy = -r; dy <= r; ++dy) {
+                    int ax = clampi(jx + dx, 0, K - 1), ay = clampi(jy + dy, 0, K - 1);
+                    double n[3];
+                    oracle_oct_decode(cx[ax], cx[ay], n);
+                    double sc = t[0] * n[0] + t[1] * n[1] + t[2] * n[2];
+                    if (sc > s_star) { s_star = sc; Jx = ax; Jy = ay; }
+                }
+        }
+        idx_dir[2 * i] = Jx;
+        idx_dir[2 * i + 1] = Jy;
+        double radial = (mode == 3) ? sqrt(t[0] * t[0] + t[1] * t[1] + t[2] * t[2]) : s_star;
+        idx_nrm[i] = count_below(p->b_rho[c], M - 1, clip01(radial));
+        if (xi_eta_out) { xi_eta_out[2 * i] = xi; xi_eta_out[2 * i + 1] = eta; }
+        if (s_star_out) s_star_out[i] = s_star;
+    }
+    free(ut);
+}
+
+/* ---- bit streams --------------------------------------------------------- */
+
+static void put_bits(uint8_t *stream, int64_t bitpos, int nbits, uint32_t v)
+{
+    for (int b = 0; b < nbits; ++b, ++bitpos)
+        if ((v >> b) & 1u) stream[bitpos >> 3] |= (uint8_t)(1u << (bitpos & 7));
+}
+
+static uint32_t get_bits(const uint8_t *stream, int64_t bitpos, int nbits)
+{
+    uint32_t v = 0;
+    for (int b = 0; b < nbits; ++b, ++bitpos)
+        v |= (uint32_t)((stream[bitpos >> 3] >> (bitpos & 7)) & 1u) << b;
+    return v;
+}
+
+/* record = [gamma as fp32, little endian][dir c0][dir c1][nrm c0][nrm c1] */
+void oracle_pack_record(const oracle_plan *p, double gamma, const int32_t *idx_dir,
+                        const int32_t *idx_nrm, uint8_t *rec)
+{
+    memset(rec, 0, (size_t)oracle_record_bytes(p));
+    float g = (float)gamma;
+    memcpy(rec, &g, 4);
+    uint8_t *dir = rec + 4;
+    int t0 = 0;
+    for (int c = 0; c < p->n_class; ++c) {
+        for (int i = 0; i < p->class_ntri[c]; ++i) {
+            put_bits(dir, (int64_t)(2 * i) * p->b_dir[c], p->b_dir[c], (uint32_t)idx_dir[2 * (t0 + i)]);
+            put_bits(dir, (int64_t)(2 * i + 1) * p->b_dir[c], p->b_dir[c], (uint32_t)idx_dir[2 * (t0 + i) + 1]);
+        }
+        dir += oracle_stream_bytes(2 * p->class_ntri[c], p->b_dir[c]);
+        t0 += p->class_ntri[c];
+    }
+    uint8_t *nrm = dir;
+    t0 = 0;
+    for (int c = 0; c < p->n_class; ++c) {
+        for (int i = 0; i < p->class_ntri[c]; ++i)
+            put_bits(nrm, (int64_t)i * p->b_nrm[c], p->b_nrm[c], (uint32_t)idx_nrm[t0 + i]);
+        nrm += oracle_stream_bytes(p->class_ntri[c], p->b_nrm[c]);
+        t0 += p->class_ntri[c];
+    }
+}
+
+void oracle_unpack_record(const oracle_plan *p, const uint8_t *rec, double *gamma,
+                          int32_t *idx_dir, int32_t *idx_nrm)
+{
+    float g;
+    memcpy(&g, rec, 4);
+    *gamma = (double)g;
+    const uint8_t *dir = rec + 4;
+    int t0 = 0;
+    for (int c = 0; c < p->n_class; ++c) {
+        for (int i = 0; i < p->class_ntri[c]; ++i) {
+            idx_dir[2 * (t0 + i)] = (int32_t)get_bits(dir, (int64_t)(2 * i) * p->b_dir[c], p->b_dir[c]);
+            idx_dir[2 * (t0 + i) + 1] = (int32_t)get_bits(dir, (int64_t)(2 * i + 1) * p->b_dir[c], p->b_dir[c]);
+        }
+        dir += oracle_stream_bytes(2 * p->class_ntri[c], p->b_dir[c]);
+        t0 += p->class_ntri[c];
+    }
+    const uint8_t *nrm = dir;
+    t0 = 0;
+    for (int c = 0; c < p->n_class; ++c) {
+        for (int i = 0; i < p->class_ntri[c]; ++i)
+            idx_nrm[t0 + i] = (int32_t)get_bits(nrm, (int64_t)i * p->b_nrm[c], p->b_nrm[c]);
+        nrm += oracle_stream_bytes(p->class_ntri[c], p->b_nrm[c]);
+        t0 += p->class_ntri[c];
+    }
+}
+
+/* encode n_keys keys (row-major [n_keys][d]) to canonical records */
+void oracle_encode(const oracle_plan *p, const double *keys, int64_t n_keys, const int8_t *s,
+                   int mode, uint8_t *records)
+{
+    int rb = oracle_record_bytes(p);
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < n_keys; ++t) {
+        int32_t *idx = (int32_t *)malloc(sizeof(int32_t) * 3 * p->n_tri);
+        double gamma;
+        oracle_encode_key(p, keys + t * p->d, s, mode, &gamma, idx, idx + 2 * p->n_tri, NULL, NULL, NULL);
+        oracle_pack_record(p, gamma, idx, idx + 2 * p->n_tri, records + t * rb);
+        free(idx);
+    }
+}
+
+/* ---- decoder ------------------------------------------------------------- */
+
+/* rotated-frame reconstruction u^ (length 3*n_tri, caller uses first d) */
+void oracle_decode_rotated(const oracle_plan *p, const int32_t *idx_dir, const int32_t *idx_nrm,
+                           double *u_hat)
+{
+    for (int i = 0; i < p->n_tri; ++i) {
+        int c = class_of(p, i);
+        double n[3];
+        oracle_oct_decode(p->c_xi[c][idx_dir[2 * i]], p->c_xi[c][idx_dir[2 * i + 1]], n);
+        double rho = p->c_rho[c][idx_nrm[i]];
+        u_hat[3 * i] = rho * n[0];
+        u_hat[3 * i + 1] = rho * n[1];
+        u_hat[3 * i + 2] = rho * n[2];
+    }
+}
+
+/* materialised k^ = gamma * R^T u^ for n_keys records; coordinates >= d of the
+ * last triplet are dropped */
+void oracle_reconstruct(const oracle_plan *p, const uint8_t *records, int64_t n_keys,
+                        const int8_t *s, double *k_hat)
+{
+    int rb = oracle_record_bytes(p), d = p->d;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < n_keys; ++t) {
+        int32_t *idx = (int32_t *)malloc(sizeof(int32_t) * 3 * p->n_tri);
+        double *uh = (double *)malloc(sizeof(double) * 3 * p->n_tri);
+        double gamma;
+        oracle_unpack_record(p, records + t * rb, &gamma, idx, idx + 2 * p->n_tri);
+        oracle_decode_rotated(p, idx, idx + 2 * p->n_tri, uh);
+        oracle_rotate_inverse(uh, s, k_hat + t * d, d);
+        for (int j = 0; j < d; ++j) k_hat[t * d + j] *= gamma;
+        free(idx);
+        free(uh);
+    }
+}
+
+/* Attention of n_q queries (sharing one KV head) over the first n_keys
+ * records: scores[qi][t] = scale * q_qi . k^_t, p = softmax_t, out = p V.
+ * Also evaluates the rotated-frame form gamma * (R q) . u^ of Eq.
+ * (score-exact) and returns the largest absolute difference between the two
+ * forms in *form_gap (the oracle's self check of Prop. invariance). */
+void oracle_attention(const oracle_plan *p, const uint8_t *records, int64_t n_keys,
+                      const int8_t *s, const double *q, int n_q, const double *v, double scale,
+                      double *scores, double *out, double *form_gap)
+{
+    int d = p->d, rb = oracle_record_bytes(p);
+    double *q_rot = (double *)malloc(sizeof(double) * (size_t)n_q * d);
+    for (int qi = 0; qi < n_q; ++qi) oracle_rotate(q + (size_t)qi * d, s, q_rot + (size_t)qi * d, d);
+    double gap = 0.0;
+#pragma omp parallel for schedule(static) reduction(max : gap)
+    for (int64_t t = 0; t < n_keys; ++t) {
+        int32_t *idx = (int32_t *)malloc(sizeof(int32_t) * 3 * p->n_tri);
+        double *uh = (double *)malloc(sizeof(double) * 3 * p->n_tri);
+        double *kh = (double *)malloc(sizeof(double) * d);
+        double gamma;
+        oracle_unpack_record(p, records + t * rb, &gamma, idx, idx + 2 * p->n_tri);
+        oracle_decode_rotated(p, idx, idx + 2 * p->n_tri, uh);
+        oracle_rotate_inverse(uh, s, kh, d);
+        for (int qi = 0; qi < n_q; ++qi) {
+            double direct = 0.0, rotated = 0.0;
+            for (int j = 0; j < d; ++j) {
+                direct += q[(size_t)qi * d + j] * (gamma * kh[j]);
+                rotated += q_rot[(size_t)qi * d + j] * uh[j];
+            }
+            rotated *= gamma;
+            double g = fabs(direct - rotated);
+            if (g > gap) gap = g;
+            scores[(size_t)qi * n_keys + t] = scale * direct;
+        }
+        free(idx);
+        free(uh);
+        free(kh);
+    }
+    if (form_gap) *form_gap = gap;
+    for (int qi = 0; qi < n_q; ++qi) {
+        const double *sc = scores + (size_t)qi * n_keys;
+        double *o = out + (size_t)qi * d;
+        for (int j = 0; j < d; ++j) o[j] = 0.0;
+        if (n_keys == 0) continue;
+        double m = -INFINITY;
+        for (int64_t t = 0; t < n_keys; ++t) if (sc[t] > m) m = sc[t];
+        double l = 0.0;
+        for (int64_t t = 0; t < n_keys; ++t) {
+            double w = exp(sc[t] - m);
+            l += w;
+            for (int j = 0; j < d; ++j) o[j] += w * v[t * d + j];
+        }
+        for (int j = 0; j < d; ++j) o[j] /= l;
+    }
+    free(q_rot);
+}
+
+/* ---- classification of a foreign record against Alg. 1 ------------------- */
+
+/* For one key and a record produced elsewhere, decide per triplet whether the
+ * foreign codes are (0) the oracle's, (1) what Alg. 1 yields if every
+ * comparison whose two sides lie within tol of each other may go either way
+ * (a decision-boundary tie), or (2) neither.  counts[0..2] are incremented.
+ * Comparisons covered: xi / eta against B_xi (both seeds are tried), the
+ * candidate argmax (any window candidate within tol of the window maximum),
+ * clip(s) against B_rho. */
+void oracle_classify_key(const oracle_plan *p, const double *k, const int8_t *s,
+                         const uint8_t *foreign, double tol, int64_t counts[3])
+{
+    int nt = p->n_tri;
+    int32_t *idx = (int32_t *)malloc(sizeof(int32_t) * 6 * nt);
+    int32_t *o_dir = idx, *o_nrm = idx + 2 * nt, *f_dir = idx + 3 * nt, *f_nrm = idx + 5 * nt;
+    double *u = (double *)calloc((size_t)3 * nt + p->d, sizeof(double));
+    double *xe = (double *)malloc(sizeof(double) * 2 * nt);
+    double gamma, fg;
+    oracle_encode_key(p, k, s, 1, &gamma, o_dir, o_nrm, u, xe, NULL);
+    oracle_unpack_record(p, foreign, &fg, f_dir, f_nrm);
+    for (int i = 0; i < nt; ++i) {
+        if (o_dir[2 * i] == f_dir[2 * i] && o_dir[2 * i + 1] == f_dir[2 * i + 1] && o_nrm[i] == f_nrm[i]) {
+            counts[0]++;
+            continue;
+        }
+        int c = class_of(p, i);
+        int K = 1 << p->b_dir[c], M = 1 << p->b_nrm[c];
+        const double *cx = p->c_xi[c], *bx = p->b_xi[c];
+        const double *tt = u + 3 * i; /* u: d rotated coordinates, then zero padding */
+        int fx = f_dir[2 * i], fy = f_dir[2 * i + 1];
+        int ok = 0;
+        if (fx < K && fy < K && f_nrm[i] < M) {
+            double n[3];
+            oracle_oct_decode(cx[fx], cx[fy], n);
+            double sf = tt[0] * n[0] + tt[1] * n[1] + tt[2] * n[2];
+            int jx_lo = count_below(bx, K - 1, xe[2 * i] - tol), jx_hi = count_below(bx, K - 1, xe[2 * i] + tol);
+            int jy_lo = count_below(bx, K - 1, xe[2 * i + 1] - tol), jy_hi = count_below(bx, K - 1, xe[2 * i + 1] + tol);
+            for (int jx = jx_lo; jx <= jx_hi && !ok; ++jx)
+                for (int jy = jy_lo; jy <= jy_hi && !ok; ++jy) {
+                    int in_window = 0;
+                    double best = -INFINITY;
+                    for (int dx = -1; dx <= 1; ++dx)
+                        for (int dy = -1; dy <= 1; ++dy) {
+                            int ax = clampi(jx + dx, 0, K - 1), ay = clampi(jy + dy, 0, K - 1);
+                            oracle_oct_decode(cx[ax], cx[ay], n);
+                            double sc = tt[0] * n[0] + tt[1] * n[1] + tt[2] * n[2];
+                            if (sc > best) best = sc;
+                            if (ax == fx && ay == fy) in_window = 1;
+                        }
+                    if (in_window && sf >= best - tol) {
+                        double cs = clip01(sf);
+                        int lo = count_below(p->b_rho[c], M - 1, cs - tol);
+                        int hi = count_below(p->b_rho[c], M - 1, cs + tol);
+                        if (f_nrm[i] >= lo && f_nrm[i] <= hi) ok = 1;
+                    }
+                }
+        }
+        counts[ok ? 1 : 2]++;
+    }
+    free(idx);
+    free(u);
+    free(xe);
+}
+
+void oracle_classify(const oracle_plan *p, const double *keys, int64_t n_keys, const int8_t *s,
+                     const uint8_t *foreign_records, double tol, int64_t counts[3])
+{
+    int rb = oracle_record_bytes(p);
+    int64_t c0 = 0, c1 = 0, c2 = 0;
+#pragma omp parallel for schedule(static) reduction(+ : c0, c1, c2)
+    for (int64_t t = 0; t < n_keys; ++t) {
+        int64_t c[3] = { 0, 0, 0 };
+        oracle_classify_key(p, keys + t * p->d, s, foreign_records + t * rb, tol, c);
+        c0 += c[0]; c1 += c[1]; c2 += c[2];
+    }
+    counts[0] += c0; counts[1] += c1; counts[2] += c2;
+}

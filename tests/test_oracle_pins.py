@@ -1,0 +1,396 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix
+(no GPU, nothing from the HIP path).  Each test names the passage it pins."""
+import itertools
+
+import numpy as np
+import pytest
+import scipy.integrate
+import scipy.linalg
+import scipy.special
+
+import oracle
+from oracle import codebooks as cbk
+from paper_2605_21226_amd import synth
+
+
+def _signs(seed, d):
+    return synth.sign_vectors(seed, 1, d)[0]
+
+
+# ---- rotation: Eq. (rotation), Prop. (inner-product invariance) -------------------
+
+@pytest.mark.parametrize("d", [2, 4, 8, 16, 64, 128, 256])
+def test_hadamard_equals_library_matrix(d):
+    H = scipy.linalg.hadamard(d).astype(np.float64) / np.sqrt(d)   # Sylvester order
+    x = np.random.default_rng(d).standard_normal(d)
+    assert np.allclose(oracle.hadamard(x), H @ x, rtol=0, atol=1e-13)
+
+
+@pytest.mark.parametrize("d", [16, 128])
+def test_rotation_is_orthogonal_and_self_inverse(d):
+    rng = np.random.default_rng(1)
+    s = _signs(3, d)
+    x, q = rng.standard_normal(d), rng.standard_normal(d)
+    u = oracle.rotate(x, s)
+    assert abs(np.linalg.norm(u) - np.linalg.norm(x)) < 1e-12
+    assert np.allclose(oracle.hadamard(oracle.hadamard(x)), x, atol=1e-12)         # H H = I
+    assert np.allclose(oracle.rotate_inverse(u, s), x, atol=1e-12)                  # R^-1 = D_s H
+    assert abs(oracle.rotate(q, s) @ u - q @ x) < 1e-12                             # (Rq)^T(Rk) = q^T k
+    # R = H diag(s): the sign flip is applied before the transform, not after
+    assert np.allclose(u, oracle.hadamard(s * x), atol=1e-13)
+    assert not np.allclose(u, s * oracle.hadamard(x), atol=1e-6)
+
+
+# ---- triplets: Sec. 3.2 / App. Triplet Split --------------------------------------
+
+@pytest.mark.parametrize("d", [64, 128, 256])
+def test_triplet_norms_partition_unit_vector(d):
+    plan = oracle.make_plan(d, 3)
+    k = np.random.default_rng(5).standard_normal(d) * 3.0
+    e = oracle.encode_key(plan, k, _signs(1, d))
+    assert abs(e["gamma"] - np.linalg.norm(k)) < 1e-12
+    u = np.concatenate([e["u"], np.zeros(3 * plan.n_tri - d)])
+    rho = np.linalg.norm(u.reshape(-1, 3), axis=1)
+    assert plan.n_tri == -(-d // 3)
+    assert abs(np.sum(rho ** 2) - 1.0) < 1e-12 and np.all(rho >= 0) and np.all(rho <= 1)
+    # s* is a projection of t_i on a unit vector: never above rho_i
+    assert np.all(e["s_star"] <= rho + 1e-12)
+
+
+# ---- octahedral map: Eq. (oct-encode), Eq. (oct-decode) ---------------------------
+
+def test_oct_round_trip_random_and_axes():
+    rng = np.random.default_rng(7)
+    vs = [v / np.linalg.norm(v) for v in rng.standard_normal((500, 3))]
+    vs += [np.array(a, dtype=float) for a in [(1, 0, 0), (-1, 0, 0), (0, 1, 0), (0, -1, 0), (0, 0, 1), (0, 0, -1)]]
+    for n in vs:
+        xi, eta = oracle.oct_encode(n)
+        assert -1 <= xi <= 1 and -1 <= eta <= 1
+        back = oracle.oct_decode(xi, eta)
+        assert abs(np.linalg.norm(back) - 1) < 1e-14
+        assert np.allclose(back, n, atol=1e-12)
+
+
+def test_oct_known_points_and_sign_zero_convention():
+    assert oracle.oct_encode(np.array([0.0, 0.0, 1.0])) == (0.0, 0.0)
+    assert oracle.oct_encode(np.array([0.0, 0.0, -1.0])) == (1.0, 1.0)          # sign(0) = +1
+    assert oracle.oct_encode(np.array([1.0, 0.0, 0.0])) == (1.0, 0.0)
+    assert oracle.oct_encode(np.array([0.0, -2.0, 0.0])) == (0.0, -1.0)         # scale invariant
+    # lower hemisphere, hand-computed: n=(1,2,-2)/3 -> p=(.2,.4,-.4) -> (1-.4, 1-.2)
+    assert np.allclose(oracle.oct_encode(np.array([1.0, 2.0, -2.0]) / 3), (0.6, 0.8), atol=1e-15)
+    assert np.allclose(oracle.oct_encode(np.array([-1.0, 2.0, -2.0]) / 3), (-0.6, 0.8), atol=1e-15)
+    # decode of a folded point: (0.6, 0.8) -> r=-0.4 -> (1-.8, 1-.6, -.4) normalised = (1,2,-2)/3
+    assert np.allclose(oracle.oct_decode(0.6, 0.8), np.array([1.0, 2.0, -2.0]) / 3, atol=1e-15)
+    assert np.allclose(oracle.oct_decode(0.25, -0.25), np.array([0.25, -0.25, 0.5]) / np.sqrt(0.375), atol=1e-15)
+
+
+def test_oct_branches_agree_on_the_fold():
+    for px in np.linspace(-1, 1, 41):
+        py = 1 - abs(px)
+        up = oracle.oct_encode(np.array([px, py, 1e-300]))
+        dn = oracle.oct_encode(np.array([px, py, -1e-300]))
+        assert np.allclose(up, dn, atol=1e-12)
+
+
+def test_zero_triplet_gives_finite_placeholder():
+    assert oracle.oct_encode(np.zeros(3)) == (0.0, 0.0)
+
+
+# ---- marginals: Eq. (rho-pdf), Eq. (oct-marginal) ---------------------------------
+
+@pytest.mark.parametrize("d", [64, 128, 256])
+def test_rho_density_normalised_and_second_moment(d):
+    mass = scipy.integrate.quad(lambda r: cbk.f_rho(r, d), 0, 1, epsabs=1e-13)[0]
+    m2 = scipy.integrate.quad(lambda r: r * r * cbk.f_rho(r, d), 0, 1, epsabs=1e-13)[0]
+    assert abs(mass - 1) < 1e-10
+    assert abs(m2 - 3.0 / d) < 1e-10                                               # E[rho^2] = 3/d
+
+
+def test_xi_density_normalised_symmetric_and_matches_integral_form():
+    mass = 2 * scipy.integrate.quad(cbk.f_xi, 0, 1, epsabs=1e-13)[0]
+    assert abs(mass - 1) < 1e-10
+    for a in [0.0, 0.1, 0.37, 0.5, 0.8, 1.0]:
+        assert abs(cbk.f_xi(a) - cbk.f_xi(-a)) < 1e-15
+        assert abs(cbk.f_xi(a) - cbk.f_xi_integral_form(a)) < 1e-10
+        assert abs(cbk.f_xi(a) - cbk.f_xi(1 - a)) < 1e-12                          # mirror about |xi| = 1/2
+    assert abs(cbk.f_xi(0.0) - 1 / np.pi) < 1e-15
+
+
+def test_marginals_match_monte_carlo_through_the_oracle_pipeline():
+    d, n = 128, 1500
+    plan = oracle.make_plan(d, 3)
+    keys = synth.gaussian_keys(11, n, d)
+    s = _signs(2, d)
+    rho, xi = [], []
+    for k in keys:
+        e = oracle.encode_key(plan, k, s)
+        u = np.concatenate([e["u"], np.zeros(3 * plan.n_tri - d)]).reshape(-1, 3)
+        rho.append(np.linalg.norm(u[:-1], axis=1))        # full triplets only (the last one is padded)
+        xi.append(e["xi_eta"][:-2])
+    rho, xi = np.concatenate(rho), np.concatenate(xi)
+    edges = np.linspace(0, 0.4, 21)
+    h, _ = np.histogram(rho, bins=edges)
+    expect = np.array([scipy.integrate.quad(lambda r: cbk.f_rho(r, d), a, b)[0] for a, b in zip(edges[:-1], edges[1:])])
+    assert np.max(np.abs(h / rho.size - expect)) < 4e-3
+    edges = np.linspace(-1, 1, 21)
+    h, _ = np.histogram(xi, bins=edges)
+    expect = np.array([scipy.integrate.quad(cbk.f_xi, a, b)[0] for a, b in zip(edges[:-1], edges[1:])])
+    assert np.max(np.abs(h / xi.size - expect)) < 4e-3
+
+
+# ---- codebooks: Sec. 3.4 -----------------------------------------------------------
+
+def _check_lloyd_fixed_point(c, pdf, lo, hi, tol):
+    edges = np.concatenate(([lo], 0.5 * (c[:-1] + c[1:]), [hi]))
+    for k in range(len(c)):
+        m = scipy.integrate.quad(pdf, edges[k], edges[k + 1], epsabs=1e-14)[0]
+        mx = scipy.integrate.quad(lambda x: x * pdf(x), edges[k], edges[k + 1], epsabs=1e-14)[0]
+        assert abs(mx / m - c[k]) < tol                                            # centroid condition
+    assert np.all(np.diff(c) > 0)
+
+
+@pytest.mark.parametrize("b_dir", [1, 2, 3, 4, 5])
+def test_xi_codebook_is_a_lloyd_max_fixed_point(b_dir):
+    c = cbk.lloyd_max_xi_f64(b_dir)
+    assert len(c) == 1 << b_dir
+    assert np.allclose(c, -c[::-1], atol=0)                                         # symmetric
+    _check_lloyd_fixed_point(c, cbk.f_xi, -1.0, 1.0, 1e-8)
+    c32, b32 = cbk.lloyd_max_xi(b_dir)
+    assert c32.dtype == np.float32 and len(b32) == len(c32) - 1
+    assert np.array_equal(b32, (0.5 * (c32[:-1].astype(np.float64) + c32[1:])).astype(np.float32))  # midpoints
+    assert b32[len(b32) // 2] == 0.0
+
+
+def test_xi_one_bit_codebook_closed_form():
+    assert np.allclose(cbk.lloyd_max_xi_f64(1), [-0.5, 0.5], atol=1e-12)
+
+
+@pytest.mark.parametrize("d,b_nrm", [(128, 1), (128, 2), (128, 3), (64, 3), (256, 2)])
+def test_rho_codebook_is_a_lloyd_max_fixed_point(d, b_nrm):
+    c = cbk.lloyd_max_rho_f64(d, b_nrm)
+    assert len(c) == 1 << b_nrm and c[0] > 0 and c[-1] < 1
+    _check_lloyd_fixed_point(c, lambda r: cbk.f_rho(r, d), 0.0, 1.0, 1e-8)
+
+
+def test_rho_zero_bit_level_is_the_mean():
+    d = 128
+    mean = scipy.special.beta(2.0, (d - 3) / 2) / scipy.special.beta(1.5, (d - 3) / 2)
+    assert abs(cbk.lloyd_max_rho_f64(d, 0)[0] - mean) < 1e-12
+    assert abs(scipy.integrate.quad(lambda r: r * cbk.f_rho(r, d), 0, 1)[0] - mean) < 1e-10
+
+
+def test_codebook_sizes_and_bit_split():
+    assert [cbk.bit_split(b) for b in (2, 3, 4)] == [(3, 1), (4, 2), (5, 3)]        # Sec. 3.3
+    plan = oracle.make_plan(128, 4)
+    assert len(plan.c_xi[0]) + len(plan.c_rho[0]) == 32 + 8                          # Sec. 3.4: <= 32+8 centroids
+    n_tri, classes = cbk.class_layout(256, 2.5)
+    assert n_tri == 86 and classes == [(43, 4, 2), (43, 3, 1)]
+    assert cbk.class_layout(128, 1.5)[1] == [(22, 3, 1), (21, 1, 1)]
+
+
+# ---- joint rounding: Sec. 3.5 ------------------------------------------------------
+
+def _brute_force_best(plan, u_padded):
+    """exhaustive search over all (jx, jy, r) codes of every triplet, by squared error"""
+    K, M = len(plan.c_xi[0]), len(plan.c_rho[0])
+    errs = []
+    for t in u_padded.reshape(-1, 3):
+        best = np.inf
+        for jx, jy, r in itertools.product(range(K), range(K), range(M)):
+            n = oracle.oct_decode(plan.c_xi[0][jx], plan.c_xi[0][jy])
+            best = min(best, float(np.sum((t - float(plan.c_rho[0][r]) * n) ** 2)))
+        errs.append(best)
+    return np.array(errs)
+
+
+@pytest.mark.parametrize("d,pair", [(4, (2, 2)), (8, (3, 1)), (8, (2, 3))])
+def test_full_grid_rounding_is_the_exhaustive_joint_optimum(d, pair):
+    plan = oracle.make_plan_pair(d, *pair)
+    s = _signs(9, d)
+    for k in np.random.default_rng(13).standard_normal((12, d)):
+        e = oracle.encode_key(plan, k, s, mode=oracle.MODE_FULL)
+        u = np.concatenate([e["u"], np.zeros(3 * plan.n_tri - d)])
+        uh = np.zeros_like(u)
+        for i in range(plan.n_tri):
+            n = oracle.oct_decode(plan.c_xi[0][e["idx_dir"][2 * i]], plan.c_xi[0][e["idx_dir"][2 * i + 1]])
+            uh[3 * i:3 * i + 3] = float(plan.c_rho[0][e["idx_nrm"][i]]) * n
+        got = np.sum((u - uh).reshape(-1, 3) ** 2, axis=1)
+        assert np.allclose(got, _brute_force_best(plan, u), atol=1e-12)
+
+
+@pytest.mark.parametrize("b_dir", [2, 3, 4, 5])
+def test_local_3x3_matches_full_grid(b_dir):
+    """Sec. 3.5: the 3x3 search was byte-identical to the full grid on 1e4 rotated triplets."""
+    d, n = 128, 240                                                                 # 240 * 43 > 1e4 triplets
+    plan = oracle.make_plan_pair(d, b_dir, 2)
+    keys = synth.gaussian_keys(b_dir, n, d)
+    s = _signs(4, d)
+    a = oracle.encode(plan, keys, s, mode=oracle.MODE_LOCAL_3X3)
+    b = oracle.encode(plan, keys, s, mode=oracle.MODE_FULL)
+    differing = sum(int(np.any(oracle.unpack_record(plan, x)[1].reshape(-1, 2) != oracle.unpack_record(plan, y)[1].reshape(-1, 2)))
+                    for x, y in zip(a, b))
+    assert differing == 0
+
+
+def test_joint_rounding_never_worse_than_scalar_and_rho_rounds_to_s_star():
+    d = 128
+    plan = oracle.make_plan(d, 3)
+    s = _signs(6, d)
+    c_rho = plan.c_rho[0].astype(np.float64)
+    for k in synth.gaussian_keys(21, 20, d):
+        e0 = oracle.encode_key(plan, k, s, mode=oracle.MODE_SCALAR)
+        e1 = oracle.encode_key(plan, k, s, mode=oracle.MODE_LOCAL_3X3)
+        assert np.all(e1["s_star"] >= e0["s_star"] - 1e-15)
+        # Eq. (triplet-joint-expand): the radius code is the centroid nearest to clip(s*), not to rho
+        nearest = np.argmin(np.abs(c_rho[None, :] - np.clip(e1["s_star"], 0, 1)[:, None]), axis=1)
+        assert np.array_equal(nearest, e1["idx_nrm"])
+        # scalar seed = nearest centroid to (xi, eta)
+        c_xi = plan.c_xi[0].astype(np.float64)
+        seed = np.argmin(np.abs(c_xi[None, :] - e0["xi_eta"][:, None]), axis=1)
+        assert np.array_equal(seed, e0["idx_dir"])
+
+
+def test_zero_key_is_encoded_to_a_finite_placeholder():
+    plan = oracle.make_plan(128, 3)
+    e = oracle.encode_key(plan, np.zeros(128), _signs(1, 128))
+    assert e["gamma"] == 0.0 and np.all(e["s_star"] == 0.0)
+    K = 16
+    # xi = eta = 0 sits on the middle boundary -> lower bin K/2-1; first of the equal candidates wins
+    assert np.all(e["idx_dir"] == K // 2 - 2) and np.all(e["idx_nrm"] == 0)
+    rec = oracle.pack_record(plan, e["gamma"], e["idx_dir"], e["idx_nrm"])
+    assert np.all(oracle.reconstruct(plan, rec[None, :], _signs(1, 128)) == 0.0)
+
+
+# ---- streams: Alg. 1 last step, Table (kernel speed) -------------------------------
+
+def test_pack_unpack_round_trip_and_lsb_first_layout():
+    rng = np.random.default_rng(3)
+    for d, bits in [(128, 3), (128, 2), (64, 4), (256, 2.5), (128, 1.5), (128, 1)]:
+        plan = oracle.make_plan(d, bits)
+        dirs, nrms = [], []
+        for nt, bd, bn in plan.classes:
+            dirs.append(rng.integers(0, 1 << bd, size=2 * nt))
+            nrms.append(rng.integers(0, 1 << bn, size=nt))
+        idx_dir, idx_nrm = np.concatenate(dirs).astype(np.int32), np.concatenate(nrms).astype(np.int32)
+        rec = oracle.pack_record(plan, 2.5, idx_dir, idx_nrm)
+        assert len(rec) == plan.record_bytes == 4 + plan.dir_bytes + plan.nrm_bytes
+        g, a, b = oracle.unpack_record(plan, rec)
+        assert g == 2.5 and np.array_equal(a, idx_dir) and np.array_equal(b, idx_nrm)
+        assert rec[:4].tobytes() == np.float32(2.5).tobytes()
+        # independent re-packing of the first class's dir stream with numpy, LSB first
+        nt, bd, _ = plan.classes[0]
+        bits_arr = ((idx_dir[:2 * nt, None] >> np.arange(bd)[None, :]) & 1).astype(np.uint8).reshape(-1)
+        ref = np.packbits(bits_arr, bitorder="little")
+        assert np.array_equal(rec[4:4 + len(ref)], ref)
+
+
+def test_stream_sizes_reproduce_printed_kv_ratios(golden):
+    for workload, d, g, b, ratio in golden("kv_ratio.txt"):
+        d, g, b, ratio = int(d), int(g), int(b), float(ratio)
+        plan = oracle.make_plan(d, b)
+        k_bytes = plan.record_bytes
+        v_bytes = b * d // 8 + (d // g) * 8
+        assert round(4.0 * d / (k_bytes + v_bytes), 1) == ratio, (workload, d, b)
+    assert [oracle.make_plan(128, b).record_bytes for b in (2, 3, 4)] == [43, 58, 77]
+    assert [oracle.make_plan(64, b).record_bytes for b in (2, 3, 4)] == [25, 32, 43]
+
+
+# ---- attention: Eq. (score-exact), Alg. 2 ------------------------------------------
+
+@pytest.mark.parametrize("d,bits", [(128, 3), (64, 4), (256, 2.5)])
+def test_attention_equals_dense_softmax_on_reconstructed_keys(d, bits):
+    n, n_q = 300, 3
+    plan = oracle.make_plan(d, bits)
+    rng = np.random.default_rng(17)
+    keys, v, q = rng.standard_normal((n, d)) * 2, rng.standard_normal((n, d)), rng.standard_normal((n_q, d))
+    s = _signs(8, d)
+    rec = oracle.encode(plan, keys, s)
+    scale = 1 / np.sqrt(d)
+    scores, out, gap = oracle.attention(plan, rec, s, q, v, scale)
+    k_hat = oracle.reconstruct(plan, rec, s)
+    ref_scores = scale * q @ k_hat.T
+    p = scipy.special.softmax(ref_scores, axis=1)
+    assert np.allclose(scores, ref_scores, atol=1e-12)
+    assert np.allclose(out, p @ v, atol=1e-12)
+    assert gap < 1e-12                                   # rotated-frame form of Eq. (score-exact) agrees
+    # reconstruction is close to the keys and gets closer with more bits
+    assert np.mean((k_hat - keys) ** 2) / np.mean(keys ** 2) < 0.2
+
+
+def test_reconstruction_error_matches_joint_objective():
+    """||t - rho^ n^||^2 summed over triplets times gamma^2 is the key's squared error (R orthogonal)."""
+    d = 128
+    plan = oracle.make_plan(d, 3)
+    s = _signs(5, d)
+    k = synth.gaussian_keys(3, 1, d)[0]
+    e = oracle.encode_key(plan, k, s)
+    rec = oracle.pack_record(plan, e["gamma"], e["idx_dir"], e["idx_nrm"])
+    k_hat = oracle.reconstruct(plan, rec[None, :], s)[0]
+    u = np.concatenate([e["u"], np.zeros(3 * plan.n_tri - d)]).reshape(-1, 3)
+    rho2 = np.sum(u ** 2, axis=1)
+    rho_hat = plan.c_rho[0].astype(np.float64)[e["idx_nrm"]]
+    ell = rho2 - 2 * rho_hat * e["s_star"] + rho_hat ** 2                           # Eq. (triplet-joint-expand)
+    # the padded coordinate of the last triplet is dropped by the decoder: compare on full triplets
+    g = float(np.float32(e["gamma"]))
+    u_hat = oracle.rotate(k_hat / g, s)
+    err = np.sum((np.concatenate([u_hat, np.zeros(3 * plan.n_tri - d)]).reshape(-1, 3) - u) ** 2, axis=1)
+    assert np.allclose(err[:-1], ell[:-1], atol=1e-12)
+
+
+# ---- the classifier used for GPU parity ---------------------------------------------
+
+def test_classifier_accepts_own_codes_flags_ties_and_rejects_wrong_codes():
+    d = 128
+    plan = oracle.make_plan(d, 3)
+    s = _signs(2, d)
+    keys = synth.gaussian_keys(5, 64, d)
+    rec = oracle.encode(plan, keys, s)
+    assert oracle.classify(plan, keys, s, rec) == (64 * plan.n_tri, 0, 0)
+    # a wrong direction code far from the optimum is a hard mismatch
+    bad = rec.copy()
+    g, a, b = oracle.unpack_record(plan, bad[0])
+    a[0] = (a[0] + 8) % 16
+    bad[0] = oracle.pack_record(plan, g, a, b)
+    assert oracle.classify(plan, keys, s, bad) == (64 * plan.n_tri - 1, 0, 1)
+    # flipping the norm code of the triplet whose clip(s*) is nearest a rho boundary: a tie exactly
+    # when the tolerance exceeds that gap
+    b_rho = plan.b_rho[0].astype(np.float64)
+    best = None
+    for t, k in enumerate(keys):
+        e = oracle.encode_key(plan, k, s)
+        gaps = np.abs(np.clip(e["s_star"], 0, 1)[:, None] - b_rho[None, :])
+        i, j = np.unravel_index(np.argmin(gaps), gaps.shape)
+        if best is None or gaps[i, j] < best[0]:
+            best = (gaps[i, j], t, i, j, e)
+    gap, t, i, j, e = best
+    other = e["idx_nrm"].copy()
+    other[i] = j + 1 if e["idx_nrm"][i] == j else j
+    one = oracle.pack_record(plan, e["gamma"], e["idx_dir"], other)[None, :]
+    assert oracle.classify(plan, keys[t:t + 1], s, one, tol=gap * 1.01) == (plan.n_tri - 1, 1, 0)
+    assert oracle.classify(plan, keys[t:t + 1], s, one, tol=gap * 0.99) == (plan.n_tri - 1, 0, 1)
+    # the runner-up direction candidate of the triplet with the smallest best/second gap
+    best = None
+    c_xi = plan.c_xi[0].astype(np.float64)
+    for t, k in enumerate(keys[:16]):
+        e = oracle.encode_key(plan, k, s, mode=oracle.MODE_SCALAR)          # seeds
+        e1 = oracle.encode_key(plan, k, s)
+        u = np.concatenate([e["u"], np.zeros(1)]).reshape(-1, 3)
+        for i in range(plan.n_tri):
+            jx, jy = e["idx_dir"][2 * i], e["idx_dir"][2 * i + 1]
+            cand = {}
+            for dx in (-1, 0, 1):
+                for dy in (-1, 0, 1):
+                    ax, ay = min(max(jx + dx, 0), 15), min(max(jy + dy, 0), 15)
+                    cand[(ax, ay)] = float(u[i] @ oracle.oct_decode(c_xi[ax], c_xi[ay]))
+            order = sorted(cand.items(), key=lambda kv: -kv[1])
+            assert order[0][0] == (e1["idx_dir"][2 * i], e1["idx_dir"][2 * i + 1])
+            g = order[0][1] - order[1][1]
+            if best is None or g < best[0]:
+                best = (g, t, i, order[1], e1)
+    gap, t, i, (code, s2), e1 = best
+    dirs, nrms = e1["idx_dir"].copy(), e1["idx_nrm"].copy()
+    dirs[2 * i], dirs[2 * i + 1] = code
+    nrms[i] = int(np.sum(b_rho < np.clip(s2, 0, 1)))
+    one = oracle.pack_record(plan, e1["gamma"], dirs, nrms)[None, :]
+    assert oracle.classify(plan, keys[t:t + 1], s, one, tol=gap * 1.01 + 1e-15) == (plan.n_tri - 1, 1, 0)
+    assert oracle.classify(plan, keys[t:t + 1], s, one, tol=gap * 0.5) == (plan.n_tri - 1, 0, 1)
