@@ -1,0 +1,219 @@
+#!/usr/bin/env python3
+"""Benchmark of the OCTOPUS hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of synthetic input resident in HBM:
+prefill-time encode of every cached token (octopus_encode) followed by one decode-attention step
+over the compressed cache (octopus_attn_decode: query rotation, fused split-K kernel, merge).
+
+Workload: the Llama-3-8B-shaped GQA decode configuration (batch 16, 32 query heads over 8 KV heads,
+head_dim 128, 32768 cached tokens per sequence, bf16 keys / values / queries, 3 bits per coordinate).
+
+Prints ONE JSON line.  `value` is the effective HBM rate of the decode-attention call: algorithmic
+bytes (per key: the 58-byte canonical record + the 256-byte bf16 value row; plus queries and outputs)
+divided by the call's average duration, measured with events on the launch stream.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+FP32_VALU_PEAK_TFLOPS = 157.3  # MI355X published fp32 vector peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama3_8b_decode")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=0)
+    return ap.parse_args()
+
+
+def device_inputs(wl, seed, dev):
+    """Synthetic keys / values / queries generated on the device from a seeded generator, with the
+    recipe of paper_2605_21226_amd.synth (per-channel log-normal scales, outlier channels)."""
+    import numpy as np
+    import torch
+
+    from paper_2605_21226_amd import synth
+
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    dt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    sig = torch.from_numpy(synth.channel_scales(seed, wl).astype(np.float32)).to(dev)       # [n_kv, d]
+    keys = torch.empty((wl.n_seq, wl.n_tokens, wl.n_kv_heads, wl.head_dim), dtype=dt, device=dev)
+    vals = torch.empty((wl.n_seq, wl.n_kv_heads, wl.n_tokens, wl.head_dim), dtype=dt, device=dev)
+    chunk = 4096
+    for s in range(wl.n_seq):
+        for t0 in range(0, wl.n_tokens, chunk):
+            n = min(chunk, wl.n_tokens - t0)
+            z = torch.randn((n, wl.n_kv_heads, wl.head_dim), generator=gen, device=dev)
+            keys[s, t0:t0 + n] = (z * sig[None]).to(dt)
+            z = torch.randn((wl.n_kv_heads, n, wl.head_dim), generator=gen, device=dev)
+            vals[s, :, t0:t0 + n] = z.to(dt)
+    q = torch.randn((wl.n_seq, wl.n_q, wl.n_q_heads, wl.head_dim), generator=gen, device=dev).to(dt)
+    signs = synth.sign_vectors(seed, wl.n_kv_heads, wl.head_dim)
+    lens = synth.context_lengths(seed, wl)
+    return keys, vals, q, signs, lens
+
+
+def cpu_baseline(wl, keys, vals, q, signs, scale, cb_plan_bytes):
+    """The oracle as it stands, timed on this machine's host cores on a bounded sample of the workload:
+    sequence 0, all its KV heads, the first `n_tok` tokens (encode, then attention of the group's
+    query heads over those tokens)."""
+    import numpy as np
+
+    import oracle
+
+    n_tok = min(wl.n_tokens, 32768)
+    plan = oracle.make_plan(wl.head_dim, wl.bits)
+    g = wl.n_q_heads // wl.n_kv_heads
+    k_host = keys[0, :n_tok].float().cpu().numpy().astype(np.float64)        # [n_tok, n_kv, d]
+    v_host = vals[0, :, :n_tok].float().cpu().numpy().astype(np.float64)     # [n_kv, n_tok, d]
+    q_host = q[0, 0].float().cpu().numpy().astype(np.float64)                # [n_qh, d]
+    oracle.encode(plan, k_host[:64, 0], signs[0])                            # load the library
+    t0 = time.perf_counter()
+    recs = [oracle.encode(plan, np.ascontiguousarray(k_host[:, h]), signs[h]) for h in range(wl.n_kv_heads)]
+    t1 = time.perf_counter()
+    for h in range(wl.n_kv_heads):
+        oracle.attention(plan, recs[h], signs[h], q_host[h * g:(h + 1) * g], np.ascontiguousarray(v_host[h]), scale)
+    t2 = time.perf_counter()
+    n_keys = n_tok * wl.n_kv_heads
+    elt = 2 if wl.dtype == "bf16" else 4
+    dec_bytes = n_keys * (cb_plan_bytes + wl.head_dim * elt)
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {
+        "value": dec_bytes / (t2 - t1) / 1e9,
+        "unit": "GB/s",
+        "cores": min(threads, os.cpu_count() or threads),
+        "kind": "oracle",
+        "sample": f"sequence 0 of the workload: {wl.n_kv_heads} KV heads x {n_tok} tokens "
+                  f"({n_keys} keys), {g} query heads per KV head; fp64 oracle, OpenMP over keys",
+        "decode_seconds": t2 - t1,
+        "encode_seconds": t1 - t0,
+        "encode_mtokens_per_s": n_tok / (t1 - t0) / 1e6,
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (one process, no collectives); --gpus must be 1. "
+              "How the path would shard over several GPUs is described in DESIGN.md.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2605_21226_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    wl = synth.WORKLOADS[args.workload]
+    if wl.n_q != 1:
+        print("bench.py: only single-query decode workloads are timed here", file=sys.stderr)
+        sys.exit(2)
+
+    cb = binding.octopus_build_codebooks(wl.head_dim, wl.bits)
+    keys, vals, q, signs, lens = device_inputs(wl, args.seed, dev)
+    cap = wl.n_tokens
+    sbits = torch.from_numpy(synth.sign_bits(signs)).to(dev)
+    cache = torch.zeros(binding.octopus_cache_bytes(cb, wl.n_seq, wl.n_kv_heads, cap), dtype=torch.uint8, device=dev)
+    max_len = int(lens.max())
+    ws = torch.empty(binding.octopus_attn_decode_workspace(cb, wl.n_seq, wl.n_q_heads, wl.n_kv_heads, 1, max_len),
+                     dtype=torch.uint8, device=dev)
+    out = torch.zeros((wl.n_seq, 1, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device=dev)
+    lens_dev = torch.from_numpy(lens).to(dev)
+    scale = 1.0 / float(np.sqrt(wl.head_dim))
+    n_new = wl.n_tokens  # prefill-time encode of the whole cache
+
+    def step(ev=None):
+        if ev:
+            ev[0].record()
+        binding.octopus_encode(cb, keys[:, :n_new], sbits, cache, cap)
+        if ev:
+            ev[1].record()
+        binding.octopus_attn_decode(cb, q, sbits, cache, cap, vals, lens_dev, max_len, scale, out, ws)
+        if ev:
+            ev[2].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    enc_ms = np.array([e[0].elapsed_time(e[1]) for e in events])
+    dec_ms = np.array([e[1].elapsed_time(e[2]) for e in events])
+    assert bool(torch.isfinite(out).all())
+
+    elt = 2 if wl.dtype == "bf16" else 4
+    n_keys_dec = int(lens.astype(np.int64).sum()) * wl.n_kv_heads
+    n_keys_enc = wl.n_seq * n_new * wl.n_kv_heads
+    rec_bytes = cb.plan.record_bytes
+    q_out_bytes = wl.n_seq * wl.n_q_heads * wl.head_dim * (elt + 4)
+    dec_bytes = n_keys_dec * (rec_bytes + wl.head_dim * elt) + q_out_bytes
+    dec_s = float(dec_ms.mean()) * 1e-3
+    enc_s = float(enc_ms.mean()) * 1e-3
+    gbs = dec_bytes / dec_s / 1e9
+
+    result = {
+        "metric": "fused decode-attn effective HBM GB/s (% of peak); encode Mtokens/s",
+        "value": round(gbs, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(wall / args.steps * 1e3, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{wl.name}: batch {wl.n_seq}, {wl.n_q_heads} query / {wl.n_kv_heads} KV heads, head_dim "
+                        f"{wl.head_dim}, {wl.n_tokens} cached tokens, {wl.dtype} K/V/Q, {wl.bits:g} bits/coordinate "
+                        f"(b_dir {cb.plan.b_dir[0]}, b_nrm {cb.plan.b_nrm[0]}); step = encode of all "
+                        f"{wl.n_seq * n_new} tokens + one decode-attention call",
+            "record_bytes": rec_bytes,
+            "keys": n_keys_dec,
+        },
+        "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
+        "decode_ms": round(dec_s * 1e3, 4),
+        "decode_ms_median": round(float(np.median(dec_ms)), 4),
+        "encode_ms": round(enc_s * 1e3, 4),
+        "encode_mtokens_per_s": round(wl.n_seq * n_new / enc_s / 1e6, 3),
+        "encode_mkeys_per_s": round(n_keys_enc / enc_s / 1e6, 3),
+        "roofline": {
+            "kernel": "octopus_attn_decode (query rotation + fused split-K decode kernel + merge; the fused "
+                      "kernel is >95% of the call)",
+            "bound": "hbm",
+            "achieved": round(gbs, 2),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(gbs / HBM_PEAK_GBS, 4),
+            "traffic": None,
+            "algorithmic_bytes_per_launch": dec_bytes,
+        },
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, keys, vals, q, signs, scale, rec_bytes)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,172 @@
+/*
+ * octopus.h -- C ABI of the MI355X (gfx950) implementation of the OCTOPUS key
+ * codec and of fused decode attention over the compressed keys.
+ *
+ * The three operations are the ones the paper's problem statement names:
+ *   octopus_build_codebooks   Sec. 3.3 (bit split) + Sec. 3.4 (codebooks)
+ *   octopus_encode            Alg. 1 (encoder with joint rounding), Sec. 3.1-3.5
+ *   octopus_attn_decode       Alg. 2 (split-K flash decode), Eq. (score-exact)
+ *
+ * Conventions
+ *   - Plain C.  Every function returns 0 (OCTOPUS_OK) or a negative error
+ *     code; nothing throws.  octopus_strerror() names a code.
+ *   - "host" pointers are ordinary CPU memory; "device" pointers are HIP
+ *     device memory owned by the caller (e.g. the storage of a torch tensor).
+ *     The library never allocates or frees device memory, never copies
+ *     between host and device, and never synchronises: every launch goes to
+ *     the caller's stream (`stream` is a hipStream_t passed as void*; NULL is
+ *     the default stream) and the call returns once the work is enqueued.
+ *   - Arguments are validated on the host before anything is launched; a
+ *     call that returns an error has launched nothing.
+ *   - All multi-byte values are little endian.
+ *
+ * Compressed cache layout (device)
+ *   One region per (sequence, KV head), regions ordered [n_seq][n_kv_heads],
+ *   each holding t_capacity tokens, t_capacity a multiple of 64.  A key's
+ *   canonical record is the byte string of Alg. 1's return value,
+ *       [gamma: fp32][dir stream: dir_bytes][nrm stream: nrm_bytes]
+ *   (LSB-first packing, index n of a b-bit stream at bits [n*b, (n+1)*b);
+ *   direction indices ordered (i,0),(i,1); index counts padded with zero
+ *   indices to whole byte groups; two-class plans store
+ *   [dir class0][dir class1][nrm class0][nrm class1]),
+ *   zero-padded to plan.granules * 16 bytes.  Records are interleaved in
+ *   tiles of 64 tokens so that a wavefront with one key per lane loads 16
+ *   bytes per lane fully coalesced: byte x of the record of token t is at
+ *       region + ((t/64 * granules + x/16) * 64 + t%64) * 16 + x%16 .
+ *   octopus_cache_bytes() gives the size of the whole cache.
+ */
+#ifndef OCTOPUS_H_
+#define OCTOPUS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define OCTOPUS_OK            0
+#define OCTOPUS_EINVAL       (-1) /* null pointer, negative size, inconsistent shapes          */
+#define OCTOPUS_EUNSUPPORTED (-2) /* head_dim / bit width / dtype / head ratio not built in    */
+#define OCTOPUS_EWORKSPACE   (-3) /* workspace missing, misaligned or too small                */
+#define OCTOPUS_EHIP         (-4) /* the HIP runtime refused a launch                          */
+
+#define OCTOPUS_DTYPE_F32  0
+#define OCTOPUS_DTYPE_BF16 1
+
+#define OCTOPUS_MAX_LEVELS 64
+#define OCTOPUS_TILE       64     /* tokens per cache tile */
+
+/* Pure function of (head_dim, bits): Sec. 3.2 (triplets), Sec. 3.3 (split). */
+typedef struct octopus_plan {
+    int32_t head_dim;       /* d: 64, 128 or 256                                              */
+    int32_t n_tri;          /* ceil(d / 3) coordinate triplets, the last zero padded          */
+    int32_t n_class;        /* 1 for integer nominal bits, 2 for b + 1/2                      */
+    int32_t class_ntri[2];  /* class 0 = first class_ntri[0] triplets, class 1 = the rest     */
+    int32_t b_dir[2];       /* bits per octahedral coordinate (xi and eta each)               */
+    int32_t b_nrm[2];       /* bits per triplet norm                                          */
+    int32_t dir_bytes;      /* size of the direction stream(s) of one key                     */
+    int32_t nrm_bytes;      /* size of the norm stream(s) of one key                          */
+    int32_t record_bytes;   /* 4 + dir_bytes + nrm_bytes: canonical record                    */
+    int32_t granules;       /* ceil(record_bytes / 16): 16-byte units per key on the device   */
+} octopus_plan_t;
+
+/* Codebooks of Sec. 3.4: ascending fp32 centroids and the midpoints of
+ * adjacent centroids (Alg. 1, Require), per class.  Caller-owned host POD. */
+typedef struct octopus_codebooks {
+    octopus_plan_t plan;
+    float c_xi[2][OCTOPUS_MAX_LEVELS];   /* 2^b_dir centroids on [-1, 1], c[k] = -c[K-1-k]     */
+    float b_xi[2][OCTOPUS_MAX_LEVELS];   /* 2^b_dir - 1 boundaries                             */
+    float c_rho[2][OCTOPUS_MAX_LEVELS];  /* 2^b_nrm centroids on [0, 1]                        */
+    float b_rho[2][OCTOPUS_MAX_LEVELS];  /* 2^b_nrm - 1 boundaries                             */
+} octopus_codebooks_t;
+
+/* Sec. 3.3 + Sec. 3.4.  Host only, deterministic, no device work.
+ * bits: nominal bits per coordinate b in {1, 1.5, 2, 2.5, 3, 4}.  Integer b
+ * uses the implemented split (b_dir, b_nrm) = (b+1, b-1) for b = 2, 3, 4 and
+ * (1, 1) for b = 1; b + 1/2 gives the first ceil(n_tri/2) triplets the split
+ * of b + 1 and the rest the split of b.  C_rho is the Lloyd-Max quantiser of
+ * Eq. (rho-pdf), C_xi that of Eq. (oct-marginal), both iterated to their
+ * fixed point from equal-probability quantiles.
+ * head_dim: 64, 128 or 256.  out: host, caller-owned, fully overwritten.
+ * Errors: EINVAL (out NULL), EUNSUPPORTED (head_dim or bits not listed). */
+int octopus_build_codebooks(int32_t head_dim, float bits, octopus_codebooks_t *out);
+
+/* Same with an explicit single-class (b_dir, b_nrm), 1 <= b_dir <= 5,
+ * 1 <= b_nrm <= 3 (the pairs swept in App. D that the kernels are built for). */
+int octopus_build_codebooks_pair(int32_t head_dim, int32_t b_dir, int32_t b_nrm, octopus_codebooks_t *out);
+
+/* Bytes of a compressed cache of n_seq x n_kv_heads regions of t_capacity
+ * tokens (0 if an argument is invalid: t_capacity not a positive multiple of
+ * 64, counts < 1, cb NULL). */
+size_t octopus_cache_bytes(const octopus_codebooks_t *cb, int32_t n_seq, int32_t n_kv_heads, int64_t t_capacity);
+
+/* Alg. 1 with the local 3x3 candidate set, for n_new new tokens of every
+ * (sequence, KV head).
+ *   cb          host.  Codebooks (only c_* are read; boundaries are recomputed
+ *               as midpoints).
+ *   keys        device, element (s, t, h, c) at keys[s*stride_seq + t*stride_tok
+ *               + h*stride_head + c], t in [0, n_new), c in [0, d) contiguous;
+ *               strides in elements, multiples of 8 (rows are read 16 bytes
+ *               at a time); base 16-byte aligned.
+ *   key_dtype   OCTOPUS_DTYPE_F32 or OCTOPUS_DTYPE_BF16.
+ *   signs       device, [n_kv_heads][d/8] bytes: bit j%8 of byte j/8 set means
+ *               s_j = -1 (Eq. (rotation): one sign vector per head).
+ *   cache       device, 16-byte aligned, layout above; token t of sequence s is
+ *               written to slot start_pos[s] + t.  Other slots are untouched.
+ *   start_pos   device [n_seq] int32, or NULL for all zeros.  Slots beyond
+ *               t_capacity are not written (the caller must size the cache).
+ * Errors: EINVAL, EUNSUPPORTED (plan / dtype without a kernel), EHIP. */
+int octopus_encode(const octopus_codebooks_t *cb,
+                   const void *keys, int32_t key_dtype,
+                   int64_t stride_seq, int64_t stride_tok, int64_t stride_head,
+                   int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
+                   const uint8_t *signs,
+                   void *cache, int64_t t_capacity,
+                   const int32_t *start_pos,
+                   void *stream);
+
+/* Bytes of device workspace octopus_attn_decode needs for these shapes
+ * (rotated queries + split-K partials); 0 if an argument is invalid. */
+size_t octopus_attn_decode_workspace(const octopus_codebooks_t *cb, int32_t n_seq, int32_t n_q_heads,
+                                     int32_t n_kv_heads, int32_t n_q, int64_t max_len);
+
+/* Alg. 2 + the split merge: out = softmax_t(scale * q . k^_t) V over the
+ * tokens t < seq_lens[s] of each sequence, with k^ the key the codes define
+ * (Eq. (score-exact)); the uncompressed key is never written to memory.
+ * Every query of a sequence sees all seq_lens[s] tokens (no causal mask).
+ *   q           device, [n_seq][n_q][n_q_heads][d] contiguous, q_dtype F32/BF16.
+ *               Query head h uses KV head h / (n_q_heads / n_kv_heads).
+ *   signs       device, as for octopus_encode.
+ *   cache       device, as written by octopus_encode with the same cb.
+ *   v           device, [n_seq][n_kv_heads][t_capacity][d] contiguous, v_dtype
+ *               F32/BF16, 16-byte aligned.
+ *   seq_lens    device [n_seq] int32, 0 <= len <= t_capacity.  A sequence of
+ *               length 0 yields zeros.
+ *   max_len     host: an upper bound of seq_lens (sizes the grid); <= t_capacity.
+ *   scale       applied to q . k^ before the softmax (1/sqrt(d) in Alg. 2).
+ *   out         device fp32 [n_seq][n_q][n_q_heads][d].
+ *   scores_out  device fp32 [n_seq][n_q][n_q_heads][t_capacity] or NULL: the
+ *               scaled scores of tokens < len (other entries untouched).
+ *   workspace   device, 256-byte aligned, at least
+ *               octopus_attn_decode_workspace(...) bytes; contents are scratch.
+ * Errors: EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP. */
+int octopus_attn_decode(const octopus_codebooks_t *cb,
+                        const void *q, int32_t q_dtype,
+                        int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q,
+                        const uint8_t *signs,
+                        const void *cache, int64_t t_capacity,
+                        const void *v, int32_t v_dtype,
+                        const int32_t *seq_lens, int64_t max_len,
+                        float scale,
+                        float *out, float *scores_out,
+                        void *workspace, size_t workspace_bytes,
+                        void *stream);
+
+/* Static, human-readable name of an error code. */
+const char *octopus_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OCTOPUS_H_ */

@@ -1,0 +1,166 @@
+"""ctypes binding of liboctopus.so: argument marshalling only.
+
+Every step of the hot path runs in the HIP kernels behind the C ABI declared
+in include/octopus.h; torch is used for device memory and streams.  There is no
+CPU fallback: if the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "liboctopus.so")
+
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
+DTYPE_F32, DTYPE_BF16 = 0, 1
+MAX_LEVELS = 64
+TILE = 64
+
+EXPORTS = ("octopus_build_codebooks", "octopus_build_codebooks_pair", "octopus_cache_bytes", "octopus_encode",
+           "octopus_attn_decode_workspace", "octopus_attn_decode", "octopus_strerror")
+
+
+class Plan(ctypes.Structure):
+    _fields_ = [
+        ("head_dim", ctypes.c_int32),
+        ("n_tri", ctypes.c_int32),
+        ("n_class", ctypes.c_int32),
+        ("class_ntri", ctypes.c_int32 * 2),
+        ("b_dir", ctypes.c_int32 * 2),
+        ("b_nrm", ctypes.c_int32 * 2),
+        ("dir_bytes", ctypes.c_int32),
+        ("nrm_bytes", ctypes.c_int32),
+        ("record_bytes", ctypes.c_int32),
+        ("granules", ctypes.c_int32),
+    ]
+
+
+class Codebooks(ctypes.Structure):
+    _fields_ = [
+        ("plan", Plan),
+        ("c_xi", (ctypes.c_float * MAX_LEVELS) * 2),
+        ("b_xi", (ctypes.c_float * MAX_LEVELS) * 2),
+        ("c_rho", (ctypes.c_float * MAX_LEVELS) * 2),
+        ("b_rho", (ctypes.c_float * MAX_LEVELS) * 2),
+    ]
+
+
+class OctopusError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+
+
+_lib = None
+
+
+def load():
+    """Load liboctopus.so (built in-tree by paper_2605_21226_amd/build.py)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2605_21226_amd.build` "
+                           "(or __graft_entry__.build()); there is no fallback path")
+    try:
+        import torch  # noqa: F401  (its HIP runtime must be the one the library binds to)
+    except ImportError:
+        pass
+    lib = ctypes.CDLL(LIB_PATH)
+    CB = ctypes.POINTER(Codebooks)
+    vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+    lib.octopus_build_codebooks.argtypes = [i32, f32, CB]
+    lib.octopus_build_codebooks.restype = ctypes.c_int
+    lib.octopus_build_codebooks_pair.argtypes = [i32, i32, i32, CB]
+    lib.octopus_build_codebooks_pair.restype = ctypes.c_int
+    lib.octopus_cache_bytes.argtypes = [CB, i32, i32, i64]
+    lib.octopus_cache_bytes.restype = ctypes.c_size_t
+    lib.octopus_encode.argtypes = [CB, vp, i32, i64, i64, i64, i32, i32, i32, vp, vp, i64, vp, vp]
+    lib.octopus_encode.restype = ctypes.c_int
+    lib.octopus_attn_decode_workspace.argtypes = [CB, i32, i32, i32, i32, i64]
+    lib.octopus_attn_decode_workspace.restype = ctypes.c_size_t
+    lib.octopus_attn_decode.argtypes = [CB, vp, i32, i32, i32, i32, i32, vp, vp, i64, vp, i32, vp, i64, f32, vp, vp,
+                                        vp, ctypes.c_size_t, vp]
+    lib.octopus_attn_decode.restype = ctypes.c_int
+    lib.octopus_strerror.argtypes = [ctypes.c_int]
+    lib.octopus_strerror.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def strerror(code):
+    return load().octopus_strerror(int(code)).decode()
+
+
+def _check(code, where):
+    if code != OK:
+        raise OctopusError(code, where)
+
+
+def octopus_build_codebooks(head_dim, bits):
+    cb = Codebooks()
+    _check(load().octopus_build_codebooks(int(head_dim), float(bits), ctypes.byref(cb)), "octopus_build_codebooks")
+    return cb
+
+
+def octopus_build_codebooks_pair(head_dim, b_dir, b_nrm):
+    cb = Codebooks()
+    _check(load().octopus_build_codebooks_pair(int(head_dim), int(b_dir), int(b_nrm), ctypes.byref(cb)),
+           "octopus_build_codebooks_pair")
+    return cb
+
+
+def octopus_cache_bytes(cb, n_seq, n_kv_heads, t_capacity):
+    return int(load().octopus_cache_bytes(ctypes.byref(cb), int(n_seq), int(n_kv_heads), int(t_capacity)))
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.float32:
+        return DTYPE_F32
+    if t.dtype == torch.bfloat16:
+        return DTYPE_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _stream_ptr(stream):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+
+def octopus_encode(cb, keys, signs, cache, t_capacity, start_pos=None, stream=None):
+    """keys: device tensor [n_seq, n_new, n_kv_heads, d] (any strides with a contiguous last dim),
+    fp32 or bf16; signs: device uint8 [n_kv_heads, d/8]; cache: device uint8 buffer of
+    octopus_cache_bytes(...) bytes; start_pos: device int32 [n_seq] or None."""
+    assert keys.dim() == 4 and keys.stride(3) == 1
+    n_seq, n_new, n_kv, _ = keys.shape
+    code = load().octopus_encode(ctypes.byref(cb), _ptr(keys), _dtype_code(keys), keys.stride(0), keys.stride(1),
+                                 keys.stride(2), n_seq, n_kv, n_new, _ptr(signs), _ptr(cache), int(t_capacity),
+                                 _ptr(start_pos), _stream_ptr(stream))
+    _check(code, "octopus_encode")
+
+
+def octopus_attn_decode_workspace(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len):
+    return int(load().octopus_attn_decode_workspace(ctypes.byref(cb), int(n_seq), int(n_q_heads), int(n_kv_heads),
+                                                    int(n_q), int(max_len)))
+
+
+def octopus_attn_decode(cb, q, signs, cache, t_capacity, v, seq_lens, max_len, scale, out, workspace,
+                        scores_out=None, stream=None):
+    """q: device [n_seq, n_q, n_q_heads, d] contiguous; v: device [n_seq, n_kv_heads, t_capacity, d]
+    contiguous; seq_lens: device int32 [n_seq]; out: device fp32 [n_seq, n_q, n_q_heads, d];
+    workspace: device uint8 buffer; scores_out: device fp32 [n_seq, n_q, n_q_heads, t_capacity] or None."""
+    assert q.is_contiguous() and v.is_contiguous() and out.is_contiguous()
+    n_seq, n_q, n_qh, _ = q.shape
+    n_kv = v.shape[1]
+    code = load().octopus_attn_decode(ctypes.byref(cb), _ptr(q), _dtype_code(q), n_seq, n_qh, n_kv, n_q, _ptr(signs),
+                                      _ptr(cache), int(t_capacity), _ptr(v), _dtype_code(v), _ptr(seq_lens),
+                                      int(max_len), float(scale), _ptr(out), _ptr(scores_out), _ptr(workspace),
+                                      int(workspace.numel() * workspace.element_size()), _stream_ptr(stream))
+    _check(code, "octopus_attn_decode")

@@ -1,0 +1,91 @@
+// Dispatch by head dimension and the kernels that do not depend on the bit width.
+#include "octopus_decode.hpp"
+
+namespace octopus {
+
+bool plan_supported_d64(const octopus_plan_t &);
+bool plan_supported_d128(const octopus_plan_t &);
+bool plan_supported_d256(const octopus_plan_t &);
+#define OCTOPUS_DECL(D)                                                                                            \
+    int launch_decode_d##D(const octopus_codebooks_t &, const DecodeShape &, const float *, const void *,          \
+                           const void *, int, const int32_t *, float *, float *, float *, void *);                 \
+    int launch_encode_d##D(const octopus_codebooks_t &, const void *, int, int64_t, int64_t, int64_t, int32_t,     \
+                           int32_t, int32_t, const uint8_t *, void *, int64_t, const int32_t *, void *);
+OCTOPUS_DECL(64)
+OCTOPUS_DECL(128)
+OCTOPUS_DECL(256)
+#undef OCTOPUS_DECL
+
+bool plan_supported(const octopus_plan_t &plan) {
+    switch (plan.head_dim) {
+        case 64: return plan_supported_d64(plan);
+        case 128: return plan_supported_d128(plan);
+        case 256: return plan_supported_d256(plan);
+        default: return false;
+    }
+}
+
+int launch_decode(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
+                  const void *v, int v_dtype, const int32_t *seq_lens, float *part_ml, float *part_acc,
+                  float *scores_out, void *stream) {
+    switch (cb.plan.head_dim) {
+        case 64: return launch_decode_d64(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, stream);
+        case 128: return launch_decode_d128(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, stream);
+        case 256: return launch_decode_d256(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, stream);
+        default: return static_cast<int>(hipErrorInvalidValue);
+    }
+}
+
+int launch_encode(const octopus_codebooks_t &cb, const void *keys, int key_dtype, int64_t stride_seq,
+                  int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
+                  const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos, void *stream) {
+    switch (cb.plan.head_dim) {
+        case 64: return launch_encode_d64(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs, cache, t_capacity, start_pos, stream);
+        case 128: return launch_encode_d128(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs, cache, t_capacity, start_pos, stream);
+        case 256: return launch_encode_d256(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs, cache, t_capacity, start_pos, stream);
+        default: return static_cast<int>(hipErrorInvalidValue);
+    }
+}
+
+template <int D>
+static int rotate_d(const void *q, int q_dtype, const uint8_t *signs, const DecodeShape &s, float scale, float *q_rot,
+                    hipStream_t stream) {
+    constexpr int QS = (3 * ((D + 2) / 3) + 3) & ~3;
+    const int64_t rows = static_cast<int64_t>(s.n_seq) * s.n_kv_heads * s.n_row_groups * s.rows_per_pass;
+    hipLaunchKernelGGL((rotate_queries_kernel<D, QS>), dim3(static_cast<unsigned>(rows)), dim3(kWave), 0, stream, q,
+                       q_dtype == OCTOPUS_DTYPE_BF16 ? 1 : 0, signs, s, scale, q_rot);
+    return static_cast<int>(hipGetLastError());
+}
+
+int launch_rotate_queries(const octopus_plan_t &plan, const void *q, int q_dtype, const uint8_t *signs,
+                          const DecodeShape &s, float scale, float *q_rot, void *stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    switch (plan.head_dim) {
+        case 64: return rotate_d<64>(q, q_dtype, signs, s, scale, q_rot, st);
+        case 128: return rotate_d<128>(q, q_dtype, signs, s, scale, q_rot, st);
+        case 256: return rotate_d<256>(q, q_dtype, signs, s, scale, q_rot, st);
+        default: return static_cast<int>(hipErrorInvalidValue);
+    }
+}
+
+template <int D>
+static int merge_d(const DecodeShape &s, const int32_t *seq_lens, const float *part_ml, const float *part_acc,
+                   float *out, hipStream_t stream) {
+    const int64_t rows = static_cast<int64_t>(s.n_seq) * s.n_q * s.n_q_heads;
+    hipLaunchKernelGGL((merge_kernel<D>), dim3(static_cast<unsigned>(rows)), dim3(D), 0, stream, s, seq_lens, part_ml,
+                       part_acc, out);
+    return static_cast<int>(hipGetLastError());
+}
+
+int launch_merge(const octopus_plan_t &plan, const DecodeShape &s, const int32_t *seq_lens, const float *part_ml,
+                 const float *part_acc, float *out, void *stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    switch (plan.head_dim) {
+        case 64: return merge_d<64>(s, seq_lens, part_ml, part_acc, out, st);
+        case 128: return merge_d<128>(s, seq_lens, part_ml, part_acc, out, st);
+        case 256: return merge_d<256>(s, seq_lens, part_ml, part_acc, out, st);
+        default: return static_cast<int>(hipErrorInvalidValue);
+    }
+}
+
+}  // namespace octopus

@@ -1,0 +1,398 @@
+// Host side of the OCTOPUS library: plan (Sec. 3.2-3.3), Lloyd-Max codebooks
+// (Sec. 3.4), argument validation and launch dispatch for the C ABI.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <vector>
+
+#include "octopus_internal.h"
+
+namespace octopus {
+namespace {
+
+// ---- numerical integration ------------------------------------------------------------------
+// Composite 16-point Gauss-Legendre; nodes from Newton's iteration on the Legendre polynomial.
+struct GaussLegendre16 {
+    static constexpr int N = 16;
+    double x[N], w[N];
+    GaussLegendre16() {
+        const double pi = std::acos(-1.0);
+        for (int i = 0; i < N; ++i) {
+            double z = std::cos(pi * (i + 0.75) / (N + 0.5));
+            double dp = 0.0;
+            for (int it = 0; it < 100; ++it) {
+                double p0 = 1.0, p1 = z;
+                for (int k = 2; k <= N; ++k) {
+                    double p2 = ((2.0 * k - 1.0) * z * p1 - (k - 1.0) * p0) / k;
+                    p0 = p1;
+                    p1 = p2;
+                }
+                dp = N * (z * p1 - p0) / (z * z - 1.0);
+                double dz = p1 / dp;
+                z -= dz;
+                if (std::fabs(dz) < 1e-16) break;
+            }
+            x[i] = z;
+            w[i] = 2.0 / ((1.0 - z * z) * dp * dp);
+        }
+    }
+};
+
+const GaussLegendre16 &gl() {
+    static const GaussLegendre16 g;
+    return g;
+}
+
+// integral over [a, b] of f(t) and of t * f(t)
+template <class F>
+void mass_and_moment(const F &f, double a, double b, int panels, double *mass, double *moment) {
+    const GaussLegendre16 &g = gl();
+    double m = 0.0, mx = 0.0;
+    const double h = (b - a) / panels;
+    for (int p = 0; p < panels; ++p) {
+        const double mid = a + (p + 0.5) * h, half = 0.5 * h;
+        for (int i = 0; i < GaussLegendre16::N; ++i) {
+            const double t = mid + half * g.x[i];
+            const double ft = f(t) * g.w[i] * half;
+            m += ft;
+            mx += ft * t;
+        }
+    }
+    *mass = m;
+    *moment = mx;
+}
+
+// Lloyd-Max quantiser of density f on [lo, hi]: alternate "boundaries = midpoints of adjacent
+// centroids" and "centroids = conditional means" to the fixed point, from the equal-probability
+// quantiles F^-1((k + 1/2) / levels).
+template <class F>
+std::vector<double> lloyd_max(const F &f, int levels, double lo, double hi) {
+    double total, unused;
+    mass_and_moment(f, lo, hi, 256, &total, &unused);
+    std::vector<double> c(levels);
+    for (int k = 0; k < levels; ++k) {
+        const double target = total * (k + 0.5) / levels;
+        double a = lo, b = hi;
+        for (int it = 0; it < 200; ++it) {
+            const double mid = 0.5 * (a + b);
+            double m;
+            mass_and_moment(f, lo, mid, 64, &m, &unused);
+            if (m < target) a = mid; else b = mid;
+        }
+        c[k] = 0.5 * (a + b);
+    }
+    std::vector<double> edge(levels + 1);
+    for (int it = 0; it < 400000; ++it) {
+        edge[0] = lo;
+        edge[levels] = hi;
+        for (int k = 1; k < levels; ++k) edge[k] = 0.5 * (c[k - 1] + c[k]);
+        double move = 0.0;
+        for (int k = 0; k < levels; ++k) {
+            double m, mx;
+            mass_and_moment(f, edge[k], edge[k + 1], 8, &m, &mx);
+            const double cn = mx / m;
+            move = std::max(move, std::fabs(cn - c[k]));
+            c[k] = cn;
+        }
+        if (move < 1e-13) break;
+    }
+    return c;
+}
+
+// Eq. (rho-pdf)
+struct RhoDensity {
+    double expo, norm;
+    explicit RhoDensity(int d) : expo(0.5 * (d - 5)) {
+        const double a = 1.5, b = 0.5 * (d - 3);
+        norm = 2.0 / std::exp(std::lgamma(a) + std::lgamma(b) - std::lgamma(a + b));
+    }
+    double operator()(double r) const {
+        const double one_minus = 1.0 - r * r;
+        return one_minus <= 0.0 ? 0.0 : norm * r * r * std::pow(one_minus, expo);
+    }
+};
+
+// Eq. (oct-marginal), folded onto a = |xi| in [0, 1] (density doubled)
+struct XiHalfDensity {
+    double operator()(double a) const {
+        const double pi = std::acos(-1.0);
+        const double lead = 1.0 / (pi * std::sqrt(a * a + (1.0 - a) * (1.0 - a)));
+        return 2.0 * lead * ((1.0 - a) / (1.0 - 2.0 * a + 3.0 * a * a) + a / (2.0 - 4.0 * a + 3.0 * a * a));
+    }
+};
+
+std::mutex g_book_mutex;
+std::map<int, std::vector<float>> g_xi_books;                  // key: b_dir
+std::map<std::pair<int, int>, std::vector<float>> g_rho_books; // key: (d, b_nrm)
+
+std::vector<float> xi_centroids(int b_dir) {
+    std::lock_guard<std::mutex> lock(g_book_mutex);
+    auto it = g_xi_books.find(b_dir);
+    if (it != g_xi_books.end()) return it->second;
+    const int levels = 1 << b_dir, half = levels / 2;
+    std::vector<double> pos = lloyd_max(XiHalfDensity(), half, 0.0, 1.0);
+    std::vector<float> c(levels);
+    for (int k = 0; k < half; ++k) {
+        c[half + k] = static_cast<float>(pos[k]);
+        c[half - 1 - k] = -static_cast<float>(pos[k]);
+    }
+    g_xi_books[b_dir] = c;
+    return c;
+}
+
+std::vector<float> rho_centroids(int d, int b_nrm) {
+    std::lock_guard<std::mutex> lock(g_book_mutex);
+    auto key = std::make_pair(d, b_nrm);
+    auto it = g_rho_books.find(key);
+    if (it != g_rho_books.end()) return it->second;
+    std::vector<double> c64 = lloyd_max(RhoDensity(d), 1 << b_nrm, 0.0, 1.0);
+    std::vector<float> c(c64.begin(), c64.end());
+    g_rho_books[key] = c;
+    return c;
+}
+
+void midpoints(const float *c, int levels, float *b) {
+    for (int k = 0; k + 1 < levels; ++k)
+        b[k] = static_cast<float>(0.5 * (static_cast<double>(c[k]) + static_cast<double>(c[k + 1])));
+}
+
+int gcd_int(int a, int b) { return b == 0 ? a : gcd_int(b, a % b); }
+
+// Stream of n indices of b bits; the count is padded to whole byte groups (the sizes the KV
+// ratios of the paper's kernel-speed table imply).
+int stream_bytes(int n, int b) {
+    const int g = 8 / gcd_int(b, 8);
+    return ((n + g - 1) / g) * (g * b / 8);
+}
+
+bool head_dim_ok(int d) { return d == 64 || d == 128 || d == 256; }
+
+// Sec. 3.3: implemented split around nominal b; b = 1 -> (1, 1).
+bool split_of(int b, int *b_dir, int *b_nrm) {
+    if (b == 1) { *b_dir = 1; *b_nrm = 1; return true; }
+    if (b >= 2 && b <= 4) { *b_dir = b + 1; *b_nrm = b - 1; return true; }
+    return false;
+}
+
+void finish_plan(octopus_plan_t *p) {
+    p->dir_bytes = 0;
+    p->nrm_bytes = 0;
+    for (int c = 0; c < p->n_class; ++c) {
+        p->dir_bytes += stream_bytes(2 * p->class_ntri[c], p->b_dir[c]);
+        p->nrm_bytes += stream_bytes(p->class_ntri[c], p->b_nrm[c]);
+    }
+    p->record_bytes = 4 + p->dir_bytes + p->nrm_bytes;
+    p->granules = (p->record_bytes + 15) / 16;
+}
+
+void fill_books(octopus_codebooks_t *out) {
+    const octopus_plan_t &p = out->plan;
+    for (int c = 0; c < p.n_class; ++c) {
+        std::vector<float> cx = xi_centroids(p.b_dir[c]);
+        std::vector<float> cr = rho_centroids(p.head_dim, p.b_nrm[c]);
+        std::copy(cx.begin(), cx.end(), out->c_xi[c]);
+        std::copy(cr.begin(), cr.end(), out->c_rho[c]);
+        midpoints(out->c_xi[c], 1 << p.b_dir[c], out->b_xi[c]);
+        midpoints(out->c_rho[c], 1 << p.b_nrm[c], out->b_rho[c]);
+    }
+}
+
+bool plan_consistent(const octopus_plan_t &p) {
+    if (!head_dim_ok(p.head_dim) || p.n_tri != (p.head_dim + 2) / 3) return false;
+    if (p.n_class < 1 || p.n_class > 2) return false;
+    int total = 0;
+    for (int c = 0; c < p.n_class; ++c) {
+        if (p.class_ntri[c] < 1 || p.b_dir[c] < 1 || p.b_dir[c] > 5 || p.b_nrm[c] < 1 || p.b_nrm[c] > 3) return false;
+        total += p.class_ntri[c];
+    }
+    if (total != p.n_tri) return false;
+    octopus_plan_t q = p;
+    finish_plan(&q);
+    return q.dir_bytes == p.dir_bytes && q.nrm_bytes == p.nrm_bytes && q.record_bytes == p.record_bytes &&
+           q.granules == p.granules;
+}
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+}  // namespace
+
+DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads,
+                              int32_t n_q, int64_t max_len, int64_t t_capacity) {
+    (void)plan;
+    DecodeShape s{};
+    s.n_seq = n_seq;
+    s.n_q_heads = n_q_heads;
+    s.n_kv_heads = n_kv_heads;
+    s.n_q = n_q;
+    s.heads_per_kv = n_q_heads / n_kv_heads;
+    s.rows_per_kv = n_q * s.heads_per_kv;
+    // Query rows scored per key by one workgroup: the power of two covering rows_per_kv, at most 8.
+    // Rows beyond rows_per_kv in the last group are zero queries whose results are not stored.
+    s.rows_per_pass = 1;
+    while (s.rows_per_pass < s.rows_per_kv && s.rows_per_pass < 8) s.rows_per_pass *= 2;
+    s.n_row_groups = (s.rows_per_kv + s.rows_per_pass - 1) / s.rows_per_pass;
+    s.t_capacity = t_capacity;
+    // Split-K sizing: aim at ~8 workgroups per compute unit (256 CUs), at least one 256-token
+    // slab (4 wavefronts x one 64-token tile) per workgroup.
+    const int64_t slab = 256;
+    const int64_t len = std::max<int64_t>(max_len, 1);
+    const int64_t pairs = static_cast<int64_t>(n_seq) * n_kv_heads * s.n_row_groups;
+    const int64_t max_splits = (len + slab - 1) / slab;
+    int64_t want = (2048 + pairs - 1) / pairs;
+    want = std::max<int64_t>(1, std::min<int64_t>(want, max_splits));
+    int64_t split_len = (len + want - 1) / want;
+    split_len = ((split_len + slab - 1) / slab) * slab;
+    s.split_len = static_cast<int32_t>(split_len);
+    s.n_splits = static_cast<int32_t>((len + split_len - 1) / split_len);
+    return s;
+}
+
+Workspace make_workspace(const octopus_plan_t &plan, const DecodeShape &s) {
+    auto up = [](size_t x) { return (x + 255) & ~static_cast<size_t>(255); };
+    Workspace w{};
+    const size_t rows = static_cast<size_t>(s.n_seq) * s.n_kv_heads * s.n_row_groups * s.rows_per_pass;
+    w.q_rot_off = 0;
+    const size_t q_bytes = up(rows * q_row_stride(plan.n_tri) * sizeof(float));
+    w.part_ml_off = q_bytes;
+    const size_t ml_bytes = up(rows * s.n_splits * 2 * sizeof(float));
+    w.part_acc_off = w.part_ml_off + ml_bytes;
+    const size_t acc_bytes = up(rows * s.n_splits * static_cast<size_t>(plan.head_dim) * sizeof(float));
+    w.total = w.part_acc_off + acc_bytes;
+    return w;
+}
+
+}  // namespace octopus
+
+using namespace octopus;
+
+extern "C" {
+
+int octopus_build_codebooks(int32_t head_dim, float bits, octopus_codebooks_t *out) {
+    if (out == nullptr) return OCTOPUS_EINVAL;
+    if (!head_dim_ok(head_dim)) return OCTOPUS_EUNSUPPORTED;
+    const float twice_f = 2.0f * bits;
+    const int twice = static_cast<int>(std::lround(twice_f));
+    if (!(std::fabs(twice_f - twice) < 1e-6f) || twice < 2 || twice > 8) return OCTOPUS_EUNSUPPORTED;
+    if (twice == 7) return OCTOPUS_EUNSUPPORTED;  // 3.5 is not one of the built widths
+    std::memset(out, 0, sizeof(*out));
+    octopus_plan_t &p = out->plan;
+    p.head_dim = head_dim;
+    p.n_tri = (head_dim + 2) / 3;
+    if (twice % 2 == 0) {
+        p.n_class = 1;
+        p.class_ntri[0] = p.n_tri;
+        if (!split_of(twice / 2, &p.b_dir[0], &p.b_nrm[0])) return OCTOPUS_EUNSUPPORTED;
+    } else {
+        p.n_class = 2;
+        p.class_ntri[0] = (p.n_tri + 1) / 2;
+        p.class_ntri[1] = p.n_tri - p.class_ntri[0];
+        if (!split_of((twice + 1) / 2, &p.b_dir[0], &p.b_nrm[0])) return OCTOPUS_EUNSUPPORTED;
+        if (!split_of((twice - 1) / 2, &p.b_dir[1], &p.b_nrm[1])) return OCTOPUS_EUNSUPPORTED;
+    }
+    finish_plan(&p);
+    fill_books(out);
+    return OCTOPUS_OK;
+}
+
+int octopus_build_codebooks_pair(int32_t head_dim, int32_t b_dir, int32_t b_nrm, octopus_codebooks_t *out) {
+    if (out == nullptr) return OCTOPUS_EINVAL;
+    if (!head_dim_ok(head_dim) || b_dir < 1 || b_dir > 5 || b_nrm < 1 || b_nrm > 3) return OCTOPUS_EUNSUPPORTED;
+    std::memset(out, 0, sizeof(*out));
+    octopus_plan_t &p = out->plan;
+    p.head_dim = head_dim;
+    p.n_tri = (head_dim + 2) / 3;
+    p.n_class = 1;
+    p.class_ntri[0] = p.n_tri;
+    p.b_dir[0] = b_dir;
+    p.b_nrm[0] = b_nrm;
+    finish_plan(&p);
+    fill_books(out);
+    return OCTOPUS_OK;
+}
+
+size_t octopus_cache_bytes(const octopus_codebooks_t *cb, int32_t n_seq, int32_t n_kv_heads, int64_t t_capacity) {
+    if (cb == nullptr || n_seq < 1 || n_kv_heads < 1 || t_capacity < OCTOPUS_TILE || t_capacity % OCTOPUS_TILE != 0)
+        return 0;
+    if (!plan_consistent(cb->plan)) return 0;
+    return static_cast<size_t>(n_seq) * n_kv_heads * static_cast<size_t>(t_capacity) * cb->plan.granules * 16;
+}
+
+int octopus_encode(const octopus_codebooks_t *cb, const void *keys, int32_t key_dtype, int64_t stride_seq,
+                   int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
+                   const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos, void *stream) {
+    if (cb == nullptr || keys == nullptr || signs == nullptr || cache == nullptr) return OCTOPUS_EINVAL;
+    if (n_seq < 1 || n_kv_heads < 1 || n_new < 0) return OCTOPUS_EINVAL;
+    if (t_capacity < OCTOPUS_TILE || t_capacity % OCTOPUS_TILE != 0) return OCTOPUS_EINVAL;
+    if (!plan_consistent(cb->plan)) return OCTOPUS_EINVAL;
+    if (key_dtype != OCTOPUS_DTYPE_F32 && key_dtype != OCTOPUS_DTYPE_BF16) return OCTOPUS_EUNSUPPORTED;
+    if (!plan_supported(cb->plan)) return OCTOPUS_EUNSUPPORTED;
+    if (stride_seq < 0 || stride_tok < 0 || stride_head < 0) return OCTOPUS_EINVAL;
+    if (stride_seq % 8 != 0 || stride_tok % 8 != 0 || stride_head % 8 != 0) return OCTOPUS_EINVAL;
+    if (!aligned(keys, 16) || !aligned(cache, 16)) return OCTOPUS_EINVAL;
+    if (start_pos == nullptr && n_new > t_capacity) return OCTOPUS_EINVAL;
+    if (n_new == 0) return OCTOPUS_OK;
+    const int err = launch_encode(*cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads,
+                                  n_new, signs, cache, t_capacity, start_pos, stream);
+    return err == 0 ? OCTOPUS_OK : OCTOPUS_EHIP;
+}
+
+static int decode_args_ok(const octopus_codebooks_t *cb, int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads,
+                          int32_t n_q, int64_t max_len) {
+    if (cb == nullptr) return OCTOPUS_EINVAL;
+    if (n_seq < 1 || n_q_heads < 1 || n_kv_heads < 1 || n_q < 1 || max_len < 0) return OCTOPUS_EINVAL;
+    if (n_q_heads % n_kv_heads != 0) return OCTOPUS_EINVAL;
+    if (!plan_consistent(cb->plan)) return OCTOPUS_EINVAL;
+    if (!plan_supported(cb->plan)) return OCTOPUS_EUNSUPPORTED;
+    return OCTOPUS_OK;
+}
+
+size_t octopus_attn_decode_workspace(const octopus_codebooks_t *cb, int32_t n_seq, int32_t n_q_heads,
+                                     int32_t n_kv_heads, int32_t n_q, int64_t max_len) {
+    if (decode_args_ok(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len) != OCTOPUS_OK) return 0;
+    const DecodeShape s = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, 0);
+    return make_workspace(cb->plan, s).total;
+}
+
+int octopus_attn_decode(const octopus_codebooks_t *cb, const void *q, int32_t q_dtype, int32_t n_seq,
+                        int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q, const uint8_t *signs, const void *cache,
+                        int64_t t_capacity, const void *v, int32_t v_dtype, const int32_t *seq_lens,
+                        int64_t max_len, float scale, float *out, float *scores_out, void *workspace,
+                        size_t workspace_bytes, void *stream) {
+    const int ok = decode_args_ok(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len);
+    if (ok != OCTOPUS_OK) return ok;
+    if (q == nullptr || signs == nullptr || cache == nullptr || v == nullptr || seq_lens == nullptr || out == nullptr)
+        return OCTOPUS_EINVAL;
+    if (t_capacity < OCTOPUS_TILE || t_capacity % OCTOPUS_TILE != 0 || max_len > t_capacity) return OCTOPUS_EINVAL;
+    if ((q_dtype != OCTOPUS_DTYPE_F32 && q_dtype != OCTOPUS_DTYPE_BF16) ||
+        (v_dtype != OCTOPUS_DTYPE_F32 && v_dtype != OCTOPUS_DTYPE_BF16))
+        return OCTOPUS_EUNSUPPORTED;
+    if (!aligned(cache, 16) || !aligned(v, 16) || !aligned(q, 4) || !aligned(out, 4)) return OCTOPUS_EINVAL;
+    if (!std::isfinite(scale)) return OCTOPUS_EINVAL;
+    const DecodeShape s = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, t_capacity);
+    const Workspace w = make_workspace(cb->plan, s);
+    if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < w.total) return OCTOPUS_EWORKSPACE;
+    char *base = static_cast<char *>(workspace);
+    float *q_rot = reinterpret_cast<float *>(base + w.q_rot_off);
+    float *part_ml = reinterpret_cast<float *>(base + w.part_ml_off);
+    float *part_acc = reinterpret_cast<float *>(base + w.part_acc_off);
+    int err = launch_rotate_queries(cb->plan, q, q_dtype, signs, s, scale, q_rot, stream);
+    if (err == 0)
+        err = launch_decode(*cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, stream);
+    if (err == 0) err = launch_merge(cb->plan, s, seq_lens, part_ml, part_acc, out, stream);
+    return err == 0 ? OCTOPUS_OK : OCTOPUS_EHIP;
+}
+
+const char *octopus_strerror(int code) {
+    switch (code) {
+        case OCTOPUS_OK: return "ok";
+        case OCTOPUS_EINVAL: return "invalid argument";
+        case OCTOPUS_EUNSUPPORTED: return "unsupported head_dim, bit width, dtype or head ratio";
+        case OCTOPUS_EWORKSPACE: return "workspace missing, misaligned or too small";
+        case OCTOPUS_EHIP: return "HIP launch failed";
+        default: return "unknown error";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,59 @@
+// Internal declarations shared by the host dispatch code and the HIP kernels.
+#ifndef OCTOPUS_INTERNAL_H_
+#define OCTOPUS_INTERNAL_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#include "octopus.h"
+
+namespace octopus {
+
+// Centroids handed to kernels by value (kernel argument space); boundaries are
+// recomputed on the device as midpoints, exactly as the host computes them.
+struct DeviceBooks {
+    float c_xi[2][32];
+    float c_rho[2][8];
+};
+
+// Floats per rotated query row in the workspace: 3 * n_tri rounded up to 4.
+inline int q_row_stride(int n_tri) { return (3 * n_tri + 3) & ~3; }
+
+struct DecodeShape {
+    int32_t n_seq, n_q_heads, n_kv_heads, n_q;
+    int32_t heads_per_kv;   // n_q_heads / n_kv_heads
+    int32_t rows_per_kv;    // n_q * heads_per_kv query rows sharing one KV head
+    int32_t rows_per_pass;  // query rows one workgroup scores per key (1, 2, 4 or 8)
+    int32_t n_row_groups;   // ceil(rows_per_kv / rows_per_pass)
+    int32_t split_len;      // tokens per split (multiple of 64)
+    int32_t n_splits;       // ceil(max_len / split_len)
+    int64_t t_capacity;
+};
+
+// Workspace carve-up (all offsets multiples of 256 bytes).
+struct Workspace {
+    size_t q_rot_off, part_ml_off, part_acc_off, total;
+};
+
+DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads,
+                              int32_t n_q, int64_t max_len, int64_t t_capacity);
+Workspace make_workspace(const octopus_plan_t &plan, const DecodeShape &s);
+
+// Kernel launchers (defined in the .hip files).  Each returns a hipError_t cast to int.
+int launch_rotate_queries(const octopus_plan_t &plan, const void *q, int q_dtype, const uint8_t *signs,
+                          const DecodeShape &s, float scale, float *q_rot, void *stream);
+int launch_decode(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
+                  const void *v, int v_dtype, const int32_t *seq_lens, float *part_ml, float *part_acc,
+                  float *scores_out, void *stream);
+int launch_merge(const octopus_plan_t &plan, const DecodeShape &s, const int32_t *seq_lens, const float *part_ml,
+                 const float *part_acc, float *out, void *stream);
+int launch_encode(const octopus_codebooks_t &cb, const void *keys, int key_dtype, int64_t stride_seq,
+                  int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
+                  const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos, void *stream);
+
+// True when the kernels are instantiated for this plan.
+bool plan_supported(const octopus_plan_t &plan);
+
+}  // namespace octopus
+
+#endif

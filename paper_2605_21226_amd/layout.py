@@ -1,0 +1,32 @@
+"""Index arithmetic between canonical key records and the device cache layout
+declared in include/octopus.h (no codec arithmetic here).
+
+canonical: uint8 [n_seq, n_kv_heads, n_tokens, record_bytes]
+device:    uint8 [n_seq, n_kv_heads, t_capacity / 64, granules, 64, 16]
+           (byte x of token t at ((t // 64 * granules + x // 16) * 64 + t % 64) * 16 + x % 16)
+"""
+from __future__ import annotations
+
+import numpy as np
+
+TILE = 64
+
+
+def records_to_cache(records, granules, t_capacity):
+    """numpy uint8 canonical records -> numpy uint8 device image (flat)."""
+    records = np.asarray(records, dtype=np.uint8)
+    n_seq, n_kv, n_tok, rb = records.shape
+    assert t_capacity % TILE == 0 and n_tok <= t_capacity and rb <= granules * 16
+    padded = np.zeros((n_seq, n_kv, t_capacity, granules * 16), dtype=np.uint8)
+    padded[:, :, :n_tok, :rb] = records
+    tiles = padded.reshape(n_seq, n_kv, t_capacity // TILE, TILE, granules, 16)
+    return np.ascontiguousarray(tiles.transpose(0, 1, 2, 4, 3, 5)).reshape(-1)
+
+
+def cache_to_records(cache, n_seq, n_kv_heads, t_capacity, granules, record_bytes, n_tokens=None):
+    """numpy uint8 device image -> canonical records [n_seq, n_kv_heads, n_tokens, record_bytes]
+    and the padding bytes [.., granules * 16 - record_bytes] (which the encoder leaves zero)."""
+    cache = np.asarray(cache, dtype=np.uint8).reshape(n_seq, n_kv_heads, t_capacity // TILE, granules, TILE, 16)
+    rows = np.ascontiguousarray(cache.transpose(0, 1, 2, 4, 3, 5)).reshape(n_seq, n_kv_heads, t_capacity, granules * 16)
+    n_tokens = t_capacity if n_tokens is None else n_tokens
+    return rows[:, :, :n_tokens, :record_bytes].copy(), rows[:, :, :n_tokens, record_bytes:].copy()

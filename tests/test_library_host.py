@@ -1,0 +1,119 @@
+"""Host-side checks of the C-ABI library that need no GPU: the shared library loads and exports what
+include/octopus.h declares, plans and codebooks agree with the oracle's independent builder, and
+argument errors are reported before anything is launched."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2605_21226_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+ALL_BITS = (1, 1.5, 2, 2.5, 3, 4)
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2605_21226_amd import build
+        build.build(verbose=False)
+    return binding.load()
+
+
+def test_library_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "octopus.h")).read()
+    declared = set(re.findall(r"\b(octopus_[a-z_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_struct_layout_matches_header(lib):
+    assert ctypes.sizeof(binding.Plan) == 4 * 13
+    assert ctypes.sizeof(binding.Codebooks) == 4 * 13 + 4 * 2 * 64 * 4
+
+
+@pytest.mark.parametrize("d", [64, 128, 256])
+@pytest.mark.parametrize("bits", ALL_BITS)
+def test_plan_and_codebooks_match_the_oracle(lib, d, bits):
+    cb = binding.octopus_build_codebooks(d, bits)
+    ref = oracle.make_plan(d, bits)
+    p = cb.plan
+    assert (p.head_dim, p.n_tri, p.n_class) == (d, ref.n_tri, len(ref.classes))
+    assert (p.dir_bytes, p.nrm_bytes, p.record_bytes) == (ref.dir_bytes, ref.nrm_bytes, ref.record_bytes)
+    assert p.granules == -(-ref.record_bytes // 16)
+    for c, (nt, bd, bn) in enumerate(ref.classes):
+        assert (p.class_ntri[c], p.b_dir[c], p.b_nrm[c]) == (nt, bd, bn)
+        K, M = 1 << bd, 1 << bn
+        # two independent Lloyd-Max builders (different quadrature, different language)
+        assert np.max(np.abs(np.array(cb.c_xi[c][:K]) - ref.c_xi[c])) <= 1e-6
+        assert np.max(np.abs(np.array(cb.c_rho[c][:M]) - ref.c_rho[c])) <= 1e-6
+        assert np.max(np.abs(np.array(cb.b_xi[c][:K - 1]) - ref.b_xi[c]), initial=0) <= 1e-6
+        assert np.max(np.abs(np.array(cb.b_rho[c][:M - 1]) - ref.b_rho[c]), initial=0) <= 1e-6
+        cx = np.array(cb.c_xi[c][:K])
+        assert np.all(np.diff(cx) > 0) and np.array_equal(cx, -cx[::-1])
+
+
+def test_build_codebooks_errors(lib):
+    cb = binding.Codebooks()
+    assert lib.octopus_build_codebooks(128, 3.0, None) == binding.EINVAL
+    for d, bits in [(96, 3.0), (512, 3.0), (128, 0.5), (128, 3.5), (128, 5.0), (128, 2.25)]:
+        assert lib.octopus_build_codebooks(d, bits, ctypes.byref(cb)) == binding.EUNSUPPORTED
+    assert lib.octopus_build_codebooks_pair(128, 6, 2, ctypes.byref(cb)) == binding.EUNSUPPORTED
+    assert lib.octopus_build_codebooks_pair(128, 3, 3, ctypes.byref(cb)) == binding.OK
+    assert cb.plan.record_bytes == 4 + oracle.stream_bytes(86, 3) + oracle.stream_bytes(43, 3)
+    with pytest.raises(binding.OctopusError):
+        binding.octopus_build_codebooks(100, 3)
+
+
+def test_cache_bytes(lib):
+    cb = binding.octopus_build_codebooks(128, 3)
+    assert binding.octopus_cache_bytes(cb, 16, 8, 32768) == 16 * 8 * 32768 * 64
+    assert binding.octopus_cache_bytes(cb, 1, 1, 100) == 0          # capacity must be a multiple of 64
+    assert binding.octopus_cache_bytes(cb, 0, 1, 64) == 0
+
+
+def test_encode_and_decode_reject_bad_arguments_before_launching(lib):
+    cb = binding.octopus_build_codebooks(128, 3)
+    P = ctypes.byref(cb)
+    fake = ctypes.c_void_p(0x1000)      # never dereferenced: every call below must fail validation
+    null = ctypes.c_void_p(0)
+    enc = lib.octopus_encode
+    assert enc(P, null, 1, 1024, 1024, 128, 1, 8, 64, fake, fake, 64, null, null) == binding.EINVAL
+    assert enc(P, fake, 1, 1024, 1024, 128, 1, 8, 64, fake, fake, 100, null, null) == binding.EINVAL      # capacity
+    assert enc(P, fake, 1, 1024, 1023, 128, 1, 8, 64, fake, fake, 64, null, null) == binding.EINVAL       # stride
+    assert enc(P, fake, 7, 1024, 1024, 128, 1, 8, 64, fake, fake, 64, null, null) == binding.EUNSUPPORTED  # dtype
+    assert enc(P, fake, 1, 1024, 1024, 128, 1, 8, 128, fake, fake, 64, null, null) == binding.EINVAL      # overflow
+    assert enc(P, ctypes.c_void_p(0x1004), 1, 1024, 1024, 128, 1, 8, 64, fake, fake, 64, null, null) == binding.EINVAL
+    assert enc(P, fake, 1, 1024, 1024, 128, 1, 8, 0, fake, fake, 64, null, null) == binding.OK             # nothing to do
+    pair = binding.octopus_build_codebooks_pair(128, 3, 3)   # no kernel is built for this pair
+    assert enc(ctypes.byref(pair), fake, 1, 1024, 1024, 128, 1, 8, 64, fake, fake, 64, null, null) == binding.EUNSUPPORTED
+    broken = binding.octopus_build_codebooks(128, 3)
+    broken.plan.record_bytes = 57
+    assert enc(ctypes.byref(broken), fake, 1, 1024, 1024, 128, 1, 8, 64, fake, fake, 64, null, null) == binding.EINVAL
+
+    dec = lib.octopus_attn_decode
+    ws = binding.octopus_attn_decode_workspace(cb, 2, 32, 8, 1, 4096)
+    assert ws > 0 and ws % 256 == 0
+    assert binding.octopus_attn_decode_workspace(cb, 2, 30, 8, 1, 4096) == 0    # heads not divisible
+    args = lambda **k: [k.get("cb", P), k.get("q", fake), 1, 2, k.get("nq_heads", 32), 8, 1, fake, fake,
+                        k.get("cap", 4096), fake, 1, fake, k.get("max_len", 4096), ctypes.c_float(k.get("scale", 0.1)),
+                        fake, null, k.get("ws", ctypes.c_void_p(0x10000)), k.get("ws_bytes", ws), null]
+    assert dec(*args(q=null)) == binding.EINVAL
+    assert dec(*args(nq_heads=30)) == binding.EINVAL
+    assert dec(*args(max_len=8192)) == binding.EINVAL
+    assert dec(*args(ws=null)) == binding.EWORKSPACE
+    assert dec(*args(ws=ctypes.c_void_p(0x10010))) == binding.EWORKSPACE        # misaligned
+    assert dec(*args(ws_bytes=ws - 1)) == binding.EWORKSPACE
+    assert dec(*args(scale=float("nan"))) == binding.EINVAL
+    assert binding.strerror(binding.EWORKSPACE).startswith("workspace")
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "liboctopus.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        binding.load()
