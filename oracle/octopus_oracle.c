@@ -397,9 +397,42 @@ void oracle_attention(const oracle_plan *p, const uint8_t *records, int64_t n_ke
  * foreign codes are (0) the oracle's, (1) what Alg. 1 yields if every
  * comparison whose two sides lie within tol of each other may go either way
  * (a decision-boundary tie), or (2) neither.  counts[0..2] are incremented.
- * Comparisons covered: xi / eta against B_xi (both seeds are tried), the
+ * Comparisons covered: the sign tests of Eq. (oct-encode) (p_z >= 0 and, on
+ * the folded branch, sign(p_x), sign(p_y)), xi / eta against B_xi, the
  * candidate argmax (any window candidate within tol of the window maximum),
  * clip(s) against B_rho. */
+static int window_admits(const oracle_plan *p, int c, const double t[3], double xi, double eta,
+                         int fx, int fy, int fn, double tol)
+{
+    int K = 1 << p->b_dir[c], M = 1 << p->b_nrm[c];
+    const double *cx = p->c_xi[c], *bx = p->b_xi[c];
+    double n[3];
+    oracle_oct_decode(cx[fx], cx[fy], n);
+    double sf = t[0] * n[0] + t[1] * n[1] + t[2] * n[2];
+    int jx_lo = count_below(bx, K - 1, xi - tol), jx_hi = count_below(bx, K - 1, xi + tol);
+    int jy_lo = count_below(bx, K - 1, eta - tol), jy_hi = count_below(bx, K - 1, eta + tol);
+    for (int jx = jx_lo; jx <= jx_hi; ++jx)
+        for (int jy = jy_lo; jy <= jy_hi; ++jy) {
+            int in_window = 0;
+            double best = -INFINITY;
+            for (int dx = -1; dx <= 1; ++dx)
+                for (int dy = -1; dy <= 1; ++dy) {
+                    int ax = clampi(jx + dx, 0, K - 1), ay = clampi(jy + dy, 0, K - 1);
+                    oracle_oct_decode(cx[ax], cx[ay], n);
+                    double sc = t[0] * n[0] + t[1] * n[1] + t[2] * n[2];
+                    if (sc > best) best = sc;
+                    if (ax == fx && ay == fy) in_window = 1;
+                }
+            if (in_window && sf >= best - tol) {
+                double cs = clip01(sf);
+                int lo = count_below(p->b_rho[c], M - 1, cs - tol);
+                int hi = count_below(p->b_rho[c], M - 1, cs + tol);
+                if (fn >= lo && fn <= hi) return 1;
+            }
+        }
+    return 0;
+}
+
 void oracle_classify_key(const oracle_plan *p, const double *k, const int8_t *s,
                          const uint8_t *foreign, double tol, int64_t counts[3])
 {
@@ -407,9 +440,8 @@ void oracle_classify_key(const oracle_plan *p, const double *k, const int8_t *s,
     int32_t *idx = (int32_t *)malloc(sizeof(int32_t) * 6 * nt);
     int32_t *o_dir = idx, *o_nrm = idx + 2 * nt, *f_dir = idx + 3 * nt, *f_nrm = idx + 5 * nt;
     double *u = (double *)calloc((size_t)3 * nt + p->d, sizeof(double));
-    double *xe = (double *)malloc(sizeof(double) * 2 * nt);
     double gamma, fg;
-    oracle_encode_key(p, k, s, 1, &gamma, o_dir, o_nrm, u, xe, NULL);
+    oracle_encode_key(p, k, s, 1, &gamma, o_dir, o_nrm, u, NULL, NULL);
     oracle_unpack_record(p, foreign, &fg, f_dir, f_nrm);
     for (int i = 0; i < nt; ++i) {
         if (o_dir[2 * i] == f_dir[2 * i] && o_dir[2 * i + 1] == f_dir[2 * i + 1] && o_nrm[i] == f_nrm[i]) {
@@ -418,41 +450,27 @@ void oracle_classify_key(const oracle_plan *p, const double *k, const int8_t *s,
         }
         int c = class_of(p, i);
         int K = 1 << p->b_dir[c], M = 1 << p->b_nrm[c];
-        const double *cx = p->c_xi[c], *bx = p->b_xi[c];
-        const double *tt = u + 3 * i; /* u: d rotated coordinates, then zero padding */
-        int fx = f_dir[2 * i], fy = f_dir[2 * i + 1];
+        const double *t = u + 3 * i; /* u: d rotated coordinates, then zero padding */
+        int fx = f_dir[2 * i], fy = f_dir[2 * i + 1], fn = f_nrm[i];
         int ok = 0;
-        if (fx < K && fy < K && f_nrm[i] < M) {
-            double n[3];
-            oracle_oct_decode(cx[fx], cx[fy], n);
-            double sf = tt[0] * n[0] + tt[1] * n[1] + tt[2] * n[2];
-            int jx_lo = count_below(bx, K - 1, xe[2 * i] - tol), jx_hi = count_below(bx, K - 1, xe[2 * i] + tol);
-            int jy_lo = count_below(bx, K - 1, xe[2 * i + 1] - tol), jy_hi = count_below(bx, K - 1, xe[2 * i + 1] + tol);
-            for (int jx = jx_lo; jx <= jx_hi && !ok; ++jx)
-                for (int jy = jy_lo; jy <= jy_hi && !ok; ++jy) {
-                    int in_window = 0;
-                    double best = -INFINITY;
-                    for (int dx = -1; dx <= 1; ++dx)
-                        for (int dy = -1; dy <= 1; ++dy) {
-                            int ax = clampi(jx + dx, 0, K - 1), ay = clampi(jy + dy, 0, K - 1);
-                            oracle_oct_decode(cx[ax], cx[ay], n);
-                            double sc = tt[0] * n[0] + tt[1] * n[1] + tt[2] * n[2];
-                            if (sc > best) best = sc;
-                            if (ax == fx && ay == fy) in_window = 1;
-                        }
-                    if (in_window && sf >= best - tol) {
-                        double cs = clip01(sf);
-                        int lo = count_below(p->b_rho[c], M - 1, cs - tol);
-                        int hi = count_below(p->b_rho[c], M - 1, cs + tol);
-                        if (f_nrm[i] >= lo && f_nrm[i] <= hi) ok = 1;
+        if (fx < K && fy < K && fn < M) {
+            double l1 = fabs(t[0]) + fabs(t[1]) + fabs(t[2]);
+            double den = (l1 > OCT_EPS) ? l1 : OCT_EPS;
+            double px = t[0] / den, py = t[1] / den, pz = t[2] / den;
+            if (pz >= -tol) ok = window_admits(p, c, t, px, py, fx, fy, fn, tol);     /* unfolded branch */
+            if (!ok && pz < tol)                                                       /* folded branch */
+                for (int vx = 0; vx < 2 && !ok; ++vx)
+                    for (int vy = 0; vy < 2 && !ok; ++vy) {
+                        double sx = vx ? 1.0 : -1.0, sy = vy ? 1.0 : -1.0;
+                        if (fabs(px) > tol && sx != sgn1(px)) continue;
+                        if (fabs(py) > tol && sy != sgn1(py)) continue;
+                        ok = window_admits(p, c, t, sx * (1.0 - fabs(py)), sy * (1.0 - fabs(px)), fx, fy, fn, tol);
                     }
-                }
         }
         counts[ok ? 1 : 2]++;
     }
     free(idx);
     free(u);
-    free(xe);
 }
 
 void oracle_classify(const oracle_plan *p, const double *keys, int64_t n_keys, const int8_t *s,

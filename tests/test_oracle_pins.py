@@ -394,3 +394,30 @@ def test_classifier_accepts_own_codes_flags_ties_and_rejects_wrong_codes():
     one = oracle.pack_record(plan, e1["gamma"], dirs, nrms)[None, :]
     assert oracle.classify(plan, keys[t:t + 1], s, one, tol=gap * 1.01 + 1e-15) == (plan.n_tri - 1, 1, 0)
     assert oracle.classify(plan, keys[t:t + 1], s, one, tol=gap * 0.5) == (plan.n_tri - 1, 0, 1)
+
+
+def test_classifier_treats_octahedral_sign_decisions_near_zero_as_ties():
+    """A triplet on the axis x = 0 or at the south pole maps to mirrored codes depending on the sign
+    of a coordinate that is zero up to rounding: both codes name the same direction."""
+    d = 128
+    plan = oracle.make_plan(d, 3)
+    s = synth.sign_vectors(3, 1, d)[0]
+    k = np.ones(d)
+    e = oracle.encode_key(plan, k, s)
+    u = np.concatenate([e["u"], np.zeros(1)]).reshape(-1, 3)
+    hits = 0
+    for i in range(plan.n_tri):
+        px = u[i, 0] / max(np.sum(np.abs(u[i])), 1e-300)
+        if u[i, 2] < 0 and 0 < abs(px) < 1e-12:
+            jx, jy = e["idx_dir"][2 * i], e["idx_dir"][2 * i + 1]
+            dirs = e["idx_dir"].copy()
+            dirs[2 * i] = 15 - jx                                 # mirror xi -> -xi (codebook is symmetric)
+            n_a = oracle.oct_decode(plan.c_xi[0][jx], plan.c_xi[0][jy])
+            n_b = oracle.oct_decode(plan.c_xi[0][15 - jx], plan.c_xi[0][jy])
+            if abs(u[i] @ n_a - u[i] @ n_b) > 1e-9:
+                continue
+            rec = oracle.pack_record(plan, e["gamma"], dirs, e["idx_nrm"])[None, :]
+            assert oracle.classify(plan, k[None, :], s, rec, tol=1e-6) == (plan.n_tri - 1, 1, 0)
+            assert oracle.classify(plan, k[None, :], s, rec, tol=1e-20) == (plan.n_tri - 1, 0, 1)
+            hits += 1
+    assert hits >= 1
