@@ -9,12 +9,12 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
-OBJ = os.path.join(HERE, "_build")
-LIB = os.path.join(HERE, "liboctopus.so")
+OBJ = os.path.join(HERE, "_build" + os.environ.get("OCTOPUS_VARIANT", ""))
+LIB = os.environ.get("OCTOPUS_LIB_OUT", os.path.join(HERE, "liboctopus.so"))
 
 SOURCES = ["octopus_host.cpp", "octopus_common.hip", "octopus_d64.hip", "octopus_d128.hip", "octopus_d256.hip"]
 # -packed-fp32-ops is switched off on purpose: hipcc must not form packed fp32 instructions here.
-FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
+FLAGS = (["-D" + d for d in os.environ.get("OCTOPUS_DEFS", "").split(",") if d]) + ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 
 
@@ -35,10 +35,16 @@ def _compile(src):
     return obj
 
 
-def build(verbose=True):
+def build(verbose=True, only=None):
+    """Compile every source (or, for quick experiments, only those named in `only` / the environment
+    variable OCTOPUS_ONLY, reusing the other objects of the last full build) and link liboctopus.so."""
     os.makedirs(OBJ, exist_ok=True)
+    only = only or [s for s in os.environ.get("OCTOPUS_ONLY", "").split(",") if s]
+    todo = [s for s in SOURCES if not only or s in only or
+            not os.path.exists(os.path.join(OBJ, os.path.splitext(s)[0] + ".o"))]
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
-        objs = list(pool.map(_compile, SOURCES))
+        list(pool.map(_compile, todo))
+    objs = [os.path.join(OBJ, os.path.splitext(s)[0] + ".o") for s in SOURCES]
     tmp = LIB + f".tmp{os.getpid()}"
     res = subprocess.run([_hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp] + objs,
                          capture_output=True, text=True)

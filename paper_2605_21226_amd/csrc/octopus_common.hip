@@ -69,21 +69,21 @@ int launch_rotate_queries(const octopus_plan_t &plan, const void *q, int q_dtype
 }
 
 template <int D>
-static int merge_d(const DecodeShape &s, const int32_t *seq_lens, const float *part_ml, const float *part_acc,
-                   float *out, hipStream_t stream) {
+static int merge_d(const DecodeShape &s, const float *part_ml, const float *part_acc, float *out,
+                   hipStream_t stream) {
     const int64_t rows = static_cast<int64_t>(s.n_seq) * s.n_q * s.n_q_heads;
-    hipLaunchKernelGGL((merge_kernel<D>), dim3(static_cast<unsigned>(rows)), dim3(D), 0, stream, s, seq_lens, part_ml,
+    hipLaunchKernelGGL((merge_kernel<D>), dim3(static_cast<unsigned>(rows)), dim3(kWave), 0, stream, s, part_ml,
                        part_acc, out);
     return static_cast<int>(hipGetLastError());
 }
 
-int launch_merge(const octopus_plan_t &plan, const DecodeShape &s, const int32_t *seq_lens, const float *part_ml,
-                 const float *part_acc, float *out, void *stream) {
+int launch_merge(const octopus_plan_t &plan, const DecodeShape &s, const float *part_ml, const float *part_acc,
+                 float *out, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     switch (plan.head_dim) {
-        case 64: return merge_d<64>(s, seq_lens, part_ml, part_acc, out, st);
-        case 128: return merge_d<128>(s, seq_lens, part_ml, part_acc, out, st);
-        case 256: return merge_d<256>(s, seq_lens, part_ml, part_acc, out, st);
+        case 64: return merge_d<64>(s, part_ml, part_acc, out, st);
+        case 128: return merge_d<128>(s, part_ml, part_acc, out, st);
+        case 256: return merge_d<256>(s, part_ml, part_acc, out, st);
         default: return static_cast<int>(hipErrorInvalidValue);
     }
 }

@@ -1,5 +1,5 @@
 // Fused decode attention over compressed keys (Alg. 2, Eq. (score-exact)): query rotation,
-// split-K main kernel, split merge.
+// split-K main kernels, split merge.
 #ifndef OCTOPUS_DECODE_HPP_
 #define OCTOPUS_DECODE_HPP_
 
@@ -8,6 +8,7 @@
 namespace octopus {
 
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kDecodeWaves = 4;  // wavefronts per workgroup of the main kernels
 
 // ---- D0: q_rot = scale * H (s . q), one wavefront per query row ------------------------------
 // Output layout per (sequence, KV head, row group): [QS coordinates][RG rows], so that the RG
@@ -74,205 +75,190 @@ __global__ __launch_bounds__(kWave) void rotate_queries_kernel(const void *__res
 }
 
 // ---- D1-D7: split-K main kernels --------------------------------------------------------------
-// One workgroup of 4 wavefronts per (split, KV head x row group, sequence).  Each wavefront takes
-// 64-token tiles of the split round-robin with one key per lane: the lane loads its record (16
-// bytes at a time, coalesced thanks to the tile-interleaved layout), unpacks the code fields with
-// compile-time shifts, looks the direction up in an LDS table and accumulates the RG scores against
-// the wave-uniform rotated queries.  Wave results are merged in LDS and one partial (m, l, acc) is
-// written per row.  Two variants differ in P.V only: decode_kernel_valu (fp32 values) sends the
-// probabilities through LDS to a channel-per-lane mapping and multiplies on the vector ALUs;
-// decode_kernel_mfma (bf16 values) feeds them to the matrix cores.
-template <class P, int RG>
-struct DecodeSmem {
-    float4 lut0[P::LUT0];
-    float4 lut1[P::LUT1 > 0 ? P::LUT1 : 1];
-    float c_xi[2][32];
-    float rho[2][8];
-    float pbuf[4][kWave][RG];         // probabilities of the current tile, per wave
-    float wave_m[4][RG], wave_l[4][RG];
-    float red[4][RG][P::D];           // per-wave accumulators for the final merge
+// Work unit = one wavefront = one (sequence, KV head, row group, split): the wave walks the 64-token
+// tiles of its split with one key per lane, keeps its own running (m, l, acc) and writes one partial
+// per query row; nothing is shared between the waves of a workgroup but the LDS tables.  The tiles of
+// a sequence are divided over the splits as evenly as whole tiles allow.
+//
+// Per tile: the lane loads its record (16 bytes at a time, coalesced thanks to the tile-interleaved
+// layout, one tile ahead of use), unpacks the code fields with compile-time shifts, looks up the
+// direction (and the norm centroids, a group of codes at a time) in LDS tables and accumulates the RG
+// scores against the wave-uniform rotated queries, which arrive through scalar loads.  The tables
+// are replicated so that neighbouring lanes always read different LDS banks whatever their codes.
+// Two kernels differ in P.V only: decode_kernel_mfma (bf16 values) feeds the probabilities to the
+// matrix cores; decode_kernel_valu (fp32 values) multiplies on the vector ALUs.
+
+// Replication of a table of `bytes` bytes: up to 8 copies within a 32 KB budget.
+constexpr int table_rep(int bytes) {
+    return bytes * 8 <= 32768 ? 8 : (bytes * 4 <= 32768 ? 4 : (bytes * 2 <= 32768 ? 2 : 1));
+}
+
+template <int BD>
+struct DirTable {
+    static constexpr int ENTRIES = 1 << (2 * BD);
+    static constexpr int REP = table_rep(ENTRIES * 16);
+    static constexpr int FLOAT4S = ENTRIES * REP;
 };
 
+// Entry e of copy r sits at float4 index e * REP + r: lanes l and l' with l % REP != l' % REP never
+// share a bank, whatever e.
+template <int BD>
+__device__ __forceinline__ void build_dir_table(float4 *table, const float *c_xi, int tid, int nthreads) {
+    using T = DirTable<BD>;
+    constexpr int K = 1 << BD;
+    for (int e = tid; e < T::FLOAT4S; e += nthreads) {
+        const int code = e / T::REP;
+        table[e] = oct_decode(c_xi[code & (K - 1)], c_xi[code >> BD]);
+    }
+}
+
+// Norm codes are looked up a group at a time: NTG consecutive BN-bit indices form one table index and
+// the entry holds their NTG centroids (4 one-bit codes, or 2 two- or three-bit codes, per lookup).
+template <int BN>
+struct RhoTable {
+    static constexpr int NTG = BN == 1 ? 4 : 2;
+    static constexpr int BITS = BN * NTG;
+    static constexpr int ENTRIES = 1 << BITS;
+    static constexpr int REP = NTG == 4 ? 8 : 16;   // 8 x 16 bytes or 16 x 8 bytes = all 32 banks
+    static constexpr int FLOATS = ENTRIES * REP * NTG;
+};
+
+template <int BN>
+__device__ __forceinline__ void build_rho_table(float *table, const float *c_rho, int tid, int nthreads) {
+    using T = RhoTable<BN>;
+    for (int e = tid; e < T::FLOATS; e += nthreads) {
+        const int t = e % T::NTG, entry = e / (T::NTG * T::REP);
+        table[e] = c_rho[(entry >> (BN * t)) & ((1 << BN) - 1)];
+    }
+}
+
+template <class P>
+struct DecodeTables {
+    float4 dir0[DirTable<P::BD0>::FLOAT4S];
+    float4 dir1[P::NCLASS == 2 ? DirTable<(P::BD1 > 0 ? P::BD1 : 1)>::FLOAT4S : 1];
+    __attribute__((aligned(16))) float rho0[RhoTable<P::BN0>::FLOATS];
+    __attribute__((aligned(16))) float rho1[P::NCLASS == 2 ? RhoTable<(P::BN1 > 0 ? P::BN1 : 1)>::FLOATS : 4];
+    float c_xi[2][32];
+    float c_rho[2][8];
+};
+
+template <class P>
+__device__ __forceinline__ void build_tables(DecodeTables<P> &tb, const DeviceBooks &books, int tid, int nthreads) {
+    if (tid < kWave) copy_books(books, tb.c_xi, tb.c_rho);
+    __syncthreads();
+    build_dir_table<P::BD0>(tb.dir0, tb.c_xi[0], tid, nthreads);
+    build_rho_table<P::BN0>(tb.rho0, tb.c_rho[0], tid, nthreads);
+    if constexpr (P::NCLASS == 2) {
+        build_dir_table<P::BD1>(tb.dir1, tb.c_xi[1], tid, nthreads);
+        build_rho_table<P::BN1>(tb.rho1, tb.c_rho[1], tid, nthreads);
+    }
+    __syncthreads();
+}
+
+// Which (sequence, KV head, row group, split) a wavefront works on, and its tiles.  A workgroup takes
+// a contiguous range of tiles of one (sequence, KV head, row group); its four wavefronts walk that
+// range interleaved (tile_begin, tile_begin + 4, ...), so that the workgroup as a whole streams through
+// memory front to back, and each wavefront is one split with its own partial result.
+struct WaveWork {
+    int seq, kvh, grp, split;
+    int64_t pair, group_id;
+    int tile_begin, tile_end, tile_step, tile_last, len;
+};
+
+__device__ __forceinline__ bool wave_work(const DecodeShape &shp, const int32_t *seq_lens, int wave, WaveWork *ww) {
+    const int n_wg_splits = shp.n_splits / kDecodeWaves;
+    const int64_t wg = blockIdx.x;
+    const int wsplit = static_cast<int>(wg % n_wg_splits);
+    ww->group_id = wg / n_wg_splits;
+    ww->split = wsplit * kDecodeWaves + wave;
+    ww->grp = static_cast<int>(ww->group_id % shp.n_row_groups);
+    ww->pair = ww->group_id / shp.n_row_groups;
+    ww->kvh = static_cast<int>(ww->pair % shp.n_kv_heads);
+    ww->seq = static_cast<int>(ww->pair / shp.n_kv_heads);
+    ww->len = min(max(seq_lens[ww->seq], 0), shp.max_len);
+    const int n_tiles = (ww->len + kWave - 1) / kWave;
+    const int base = n_tiles / n_wg_splits, rem = n_tiles % n_wg_splits;
+    const int wb = wsplit * base + min(wsplit, rem);
+    ww->tile_end = wb + base + (wsplit < rem ? 1 : 0);
+    ww->tile_begin = wb + wave;
+    ww->tile_step = kDecodeWaves;
+    ww->tile_last = ww->tile_begin +
+                    (ww->tile_begin < ww->tile_end ? (ww->tile_end - 1 - ww->tile_begin) / ww->tile_step : 0) * ww->tile_step;
+    return true;
+}
+
+// D2-D4 for one tile: RG scores of this lane's key (without gamma).
+//
+// The rotated queries are wave-uniform and come through scalar loads; directions and norm centroids
+// come from the LDS tables.  Triplets are processed in chunks of 48 query floats with a scheduling
+// barrier in between, so that the scalar registers hold one chunk at a time instead of the whole
+// query.  (Scalar loads return out of order, so each chunk costs one full wait on the scalar and LDS
+// queues; the other wavefronts of the SIMD cover it.  Prefetching a chunk ahead was measured slower.)
 template <class P, int RG>
 __device__ __forceinline__ void tile_scores(const uint32_t (&w)[P::NWORDS], const float *__restrict__ qg,
-                                            const DecodeSmem<P, RG> &sm, float (&s)[RG]) {
+                                            const DecodeTables<P> &tb, int lane, float (&s)[RG]) {
+    constexpr int CT = 16 / RG;
+    constexpr int NCHUNK = (P::NTRI + CT - 1) / CT;
 #pragma unroll
     for (int r = 0; r < RG; ++r) s[r] = 0.0f;
-    static_for<0, P::NTRI>([&](auto ic) {
-        constexpr int i = decltype(ic)::value;
-        constexpr int c = P::cls(i);
-        const uint32_t code = field<P::dir_bit(i), 2 * P::bdir(i)>(w);
-        const uint32_t ridx = field<P::nrm_bit(i), P::bnrm(i)>(w);
-        const float4 n = c ? sm.lut1[code] : sm.lut0[code];
-        const float rho = sm.rho[c][ridx];
-        const float tx = rho * n.x, ty = rho * n.y, tz = rho * n.z;
+    float rgv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    static_for<0, NCHUNK>([&](auto cc) {
+        constexpr int c0 = decltype(cc)::value * CT;
+        constexpr int cn = (P::NTRI - c0) < CT ? (P::NTRI - c0) : CT;
+        float qv[cn * 3 * RG];
 #pragma unroll
-        for (int r = 0; r < RG; ++r) {
-            s[r] = fmaf(qg[(3 * i) * RG + r], tx, s[r]);
-            s[r] = fmaf(qg[(3 * i + 1) * RG + r], ty, s[r]);
-            s[r] = fmaf(qg[(3 * i + 2) * RG + r], tz, s[r]);  // rotated queries are zero past d
-        }
+        for (int k = 0; k < cn * 3 * RG; ++k) qv[k] = qg[c0 * 3 * RG + k];
+        static_for<0, cn>([&](auto tt) {
+            constexpr int t = decltype(tt)::value;
+            constexpr int i = c0 + t;
+            constexpr int c = P::cls(i);
+            constexpr int ii = c ? i - P::NT0 : i;   // index within the class
+            constexpr int bn = P::bnrm(i);
+            constexpr int bd = P::bdir(i);
+            using RT = RhoTable<bn>;
+            using DT = DirTable<bd>;
+            if constexpr (ii % RT::NTG == 0) {
+                constexpr int gbit = (c ? P::NRM1_BIT : P::NRM0_BIT) + ii * bn;
+                // the streams are padded to whole bytes, a whole number of groups; the last group may
+                // reach past the class's triplets, never past its stream
+                const uint32_t gi = field_clamped<gbit, RT::BITS, P::NWORDS>(w);
+                const float *entry = (c ? tb.rho1 : tb.rho0) + (gi * RT::REP + (lane & (RT::REP - 1))) * RT::NTG;
+                if constexpr (RT::NTG == 4) {
+                    const float4 e = *reinterpret_cast<const float4 *>(entry);
+                    rgv[0] = e.x; rgv[1] = e.y; rgv[2] = e.z; rgv[3] = e.w;
+                } else {
+                    const float2 e = *reinterpret_cast<const float2 *>(entry);
+                    rgv[0] = e.x; rgv[1] = e.y;
+                }
+            }
+            const uint32_t code = field<P::dir_bit(i), 2 * bd>(w);
+            const float4 n = (c ? tb.dir1 : tb.dir0)[code * DT::REP + (lane & (DT::REP - 1))];
+            const float rho = rgv[ii % RT::NTG];
+            const float tx = rho * n.x, ty = rho * n.y, tz = rho * n.z;
+#pragma unroll
+            for (int r = 0; r < RG; ++r) {
+                s[r] = fmaf(qv[(3 * t) * RG + r], tx, s[r]);
+                s[r] = fmaf(qv[(3 * t + 1) * RG + r], ty, s[r]);
+                s[r] = fmaf(qv[(3 * t + 2) * RG + r], tz, s[r]);  // rotated queries are zero past d
+            }
+        });
+        __builtin_amdgcn_sched_barrier(0);
     });
 }
 
-template <class P, int RG>
-__global__ __launch_bounds__(256) void decode_kernel_valu(DeviceBooks books, DecodeShape shp,
-                                                      const float *__restrict__ q_rot,
-                                                      const uint4 *__restrict__ cache, const void *__restrict__ v,
-                                                      int v_is_bf16, const int32_t *__restrict__ seq_lens,
-                                                      float *__restrict__ part_ml, float *__restrict__ part_acc,
-                                                      float *__restrict__ scores_out) {
-    constexpr int D = P::D;
-    constexpr int LPR = D / 8;          // lanes per V row (8 channels per lane)
-    constexpr int KPL = kWave / LPR;    // V rows per wave-wide load
-    __shared__ DecodeSmem<P, RG> sm;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int split = blockIdx.x;
-    const int kvh = blockIdx.y / shp.n_row_groups, grp = blockIdx.y % shp.n_row_groups;
-    const int seq = blockIdx.z;
-    const int len = seq_lens[seq];
-    const int t_begin = split * shp.split_len;
-    if (t_begin >= len) return;  // the merge only reads splits that start below len
-    const int t_end = min(len, t_begin + shp.split_len);
-
-    if (wave == 0) copy_books(books, sm.c_xi, sm.rho);
-    __syncthreads();
-    build_dir_lut<P::BD0>(sm.lut0, sm.c_xi[0], tid, 256);
-    if constexpr (P::NCLASS == 2) build_dir_lut<P::BD1>(sm.lut1, sm.c_xi[1], tid, 256);
-    __syncthreads();
-
-    const int64_t pair = static_cast<int64_t>(seq) * shp.n_kv_heads + kvh;
-    const int64_t group_id = pair * shp.n_row_groups + grp;
-    const float *qg = q_rot + group_id * (P::QS * RG);
-    const uint4 *region = cache + pair * (shp.t_capacity * P::GRANULES);
-    const int64_t v_row0 = pair * shp.t_capacity;
-
-    float m_run[RG], l_lane[RG], acc[RG][8];
+template <int RG>
+__device__ __forceinline__ void store_scores(const DecodeShape &shp, const WaveWork &ww, float *scores_out, int tok,
+                                             const float (&s)[RG]) {
 #pragma unroll
     for (int r = 0; r < RG; ++r) {
-        m_run[r] = -INFINITY;
-        l_lane[r] = 0.0f;
-#pragma unroll
-        for (int c = 0; c < 8; ++c) acc[r][c] = 0.0f;
-    }
-    const int rl = lane % LPR, ko = lane / LPR;
-
-    for (int t0 = t_begin + wave * kWave; t0 < t_end; t0 += 4 * kWave) {
-        // D1: this lane's record
-        uint32_t w[P::NWORDS];
-        const uint4 *tile = region + static_cast<int64_t>(t0 / kWave) * (P::GRANULES * kWave) + lane;
-#pragma unroll
-        for (int g = 0; g < P::GRANULES; ++g) {
-            const uint4 x = tile[g * kWave];
-            w[4 * g] = x.x; w[4 * g + 1] = x.y; w[4 * g + 2] = x.z; w[4 * g + 3] = x.w;
+        const int row = ww.grp * RG + r;
+        if (row < shp.rows_per_kv) {
+            const int qi = row / shp.heads_per_kv, head = ww.kvh * shp.heads_per_kv + row % shp.heads_per_kv;
+            scores_out[((static_cast<int64_t>(ww.seq) * shp.n_q + qi) * shp.n_q_heads + head) * shp.t_capacity + tok] =
+                s[r];
         }
-        // D2-D4: scores (queries carry the softmax scale already)
-        float s[RG];
-        tile_scores<P, RG>(w, qg, sm, s);
-        const float gamma = __uint_as_float(w[0]);
-        const bool valid = (t0 + lane) < t_end;
-#pragma unroll
-        for (int r = 0; r < RG; ++r) s[r] = valid ? s[r] * gamma : -INFINITY;
-        if (scores_out != nullptr && valid) {
-#pragma unroll
-            for (int r = 0; r < RG; ++r) {
-                const int row = grp * RG + r;
-                if (row < shp.rows_per_kv) {
-                    const int qi = row / shp.heads_per_kv, head = kvh * shp.heads_per_kv + row % shp.heads_per_kv;
-                    scores_out[((static_cast<int64_t>(seq) * shp.n_q + qi) * shp.n_q_heads + head) * shp.t_capacity +
-                               t0 + lane] = s[r];
-                }
-            }
-        }
-        // D5: online softmax, one running maximum per row for the whole wave
-        float alpha[RG];
-        bool rescale = false;
-#pragma unroll
-        for (int r = 0; r < RG; ++r) {
-            const float m_new = fmaxf(m_run[r], wave_max(s[r]));
-            alpha[r] = exp2f((m_run[r] - m_new) * kLog2e);
-            rescale |= (m_new != m_run[r]);
-            m_run[r] = m_new;
-            const float p = exp2f((s[r] - m_new) * kLog2e);
-            l_lane[r] = l_lane[r] * alpha[r] + p;
-            sm.pbuf[wave][lane][r] = p;
-        }
-        if (rescale) {
-#pragma unroll
-            for (int r = 0; r < RG; ++r)
-#pragma unroll
-                for (int c = 0; c < 8; ++c) acc[r][c] *= alpha[r];
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        // D6: P.V with 8 channels per lane; lanes with the same ko walk the same keys
-        const int n_valid = min(kWave, t_end - t0);
-        for (int kb = 0; kb < n_valid; kb += KPL) {
-            const int key = kb + ko;
-            float pv[RG];
-#pragma unroll
-            for (int r = 0; r < RG; ++r) pv[r] = sm.pbuf[wave][key][r];
-            float vals[8];
-            const int64_t vrow = v_row0 + t0 + key;
-            if (key < n_valid) {
-                if (v_is_bf16) {
-                    const uint4 x = static_cast<const uint4 *>(v)[vrow * (D / 8) + rl];
-                    vals[0] = bf16_lo(x.x); vals[1] = bf16_hi(x.x); vals[2] = bf16_lo(x.y); vals[3] = bf16_hi(x.y);
-                    vals[4] = bf16_lo(x.z); vals[5] = bf16_hi(x.z); vals[6] = bf16_lo(x.w); vals[7] = bf16_hi(x.w);
-                } else {
-                    const float4 a = static_cast<const float4 *>(v)[vrow * (D / 4) + 2 * rl];
-                    const float4 b = static_cast<const float4 *>(v)[vrow * (D / 4) + 2 * rl + 1];
-                    vals[0] = a.x; vals[1] = a.y; vals[2] = a.z; vals[3] = a.w;
-                    vals[4] = b.x; vals[5] = b.y; vals[6] = b.z; vals[7] = b.w;
-                }
-#pragma unroll
-                for (int r = 0; r < RG; ++r)
-#pragma unroll
-                    for (int c = 0; c < 8; ++c) acc[r][c] = fmaf(pv[r], vals[c], acc[r][c]);
-            }
-        }
-        __builtin_amdgcn_wave_barrier();
-    }
-
-    // D7: fold the KPL lane groups, then the 4 wavefronts, and emit one partial per row
-#pragma unroll
-    for (int o = LPR; o < kWave; o <<= 1)
-#pragma unroll
-        for (int r = 0; r < RG; ++r)
-#pragma unroll
-            for (int c = 0; c < 8; ++c) acc[r][c] += __shfl_xor(acc[r][c], o, kWave);
-#pragma unroll
-    for (int r = 0; r < RG; ++r) {
-        const float l = wave_sum(l_lane[r]);
-        if (lane == 0) { sm.wave_m[wave][r] = m_run[r]; sm.wave_l[wave][r] = l; }
-        if (ko == 0) {
-#pragma unroll
-            for (int c = 0; c < 8; ++c) sm.red[wave][r][rl * 8 + c] = acc[r][c];
-        }
-    }
-    __syncthreads();
-    for (int e = tid; e < RG * D; e += 256) {
-        const int r = e / D, c = e % D;
-        const int row = grp * RG + r;
-        if (row >= shp.rows_per_kv) continue;
-        float m = sm.wave_m[0][r];
-#pragma unroll
-        for (int wv = 1; wv < 4; ++wv) m = fmaxf(m, sm.wave_m[wv][r]);
-        float l = 0.0f, a = 0.0f;
-#pragma unroll
-        for (int wv = 0; wv < 4; ++wv) {
-            const float mw = sm.wave_m[wv][r];
-            const float f = (mw == -INFINITY) ? 0.0f : exp2f((mw - m) * kLog2e);
-            l += f * sm.wave_l[wv][r];
-            a += f * sm.red[wv][r][c];
-        }
-        const int64_t prow = (group_id * RG + r) * shp.n_splits + split;
-        part_acc[prow * D + c] = a;
-        if (c == 0) { part_ml[prow * 2] = m; part_ml[prow * 2 + 1] = l; }
     }
 }
-
 
 // ---- bf16 values: P.V on the matrix cores -------------------------------------------------------
 // v_mfma_f32_16x16x32_bf16 computes D[16x16] += A[16x32] B[32x16]; lane l holds row l%16 of A and
@@ -291,77 +277,81 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 constexpr int kPRow = 72;  // bf16 per probability row in LDS: 64 keys + 8 pad (144-byte stride)
 
-template <class P, int RG>
+template <class P>
 struct DecodeSmemMfma {
-    float4 lut0[P::LUT0];
-    float4 lut1[P::LUT1 > 0 ? P::LUT1 : 1];
-    float c_xi[2][32];
-    float rho[2][8];
-    uint16_t pbuf[4][16][kPRow];
-    float wave_m[4][RG], wave_l[4][RG];
-    float red[4][RG][P::D];
+    DecodeTables<P> tb;
+    uint16_t pbuf[kDecodeWaves][16][kPRow];
 };
 
-template <class P, int RG, class SM>
-__device__ __forceinline__ void tile_scores_t(const uint32_t (&w)[P::NWORDS], const float *__restrict__ qg,
-                                              const SM &sm, float (&s)[RG]) {
-#pragma unroll
-    for (int r = 0; r < RG; ++r) s[r] = 0.0f;
-    static_for<0, P::NTRI>([&](auto ic) {
-        constexpr int i = decltype(ic)::value;
-        constexpr int c = P::cls(i);
-        const uint32_t code = field<P::dir_bit(i), 2 * P::bdir(i)>(w);
-        const uint32_t ridx = field<P::nrm_bit(i), P::bnrm(i)>(w);
-        const float4 n = c ? sm.lut1[code] : sm.lut0[code];
-        const float rho = sm.rho[c][ridx];
-        const float tx = rho * n.x, ty = rho * n.y, tz = rho * n.z;
-#pragma unroll
-        for (int r = 0; r < RG; ++r) {
-            s[r] = fmaf(qg[(3 * i) * RG + r], tx, s[r]);
-            s[r] = fmaf(qg[(3 * i + 1) * RG + r], ty, s[r]);
-            s[r] = fmaf(qg[(3 * i + 2) * RG + r], tz, s[r]);  // rotated queries are zero past d
-        }
-    });
-}
-
 template <class P, int RG>
-__global__ __launch_bounds__(256) void decode_kernel_mfma(DeviceBooks books, DecodeShape shp,
-                                                           const float *__restrict__ q_rot,
-                                                           const uint4 *__restrict__ cache,
-                                                           const uint32_t *__restrict__ v,
-                                                           const int32_t *__restrict__ seq_lens,
-                                                           float *__restrict__ part_ml, float *__restrict__ part_acc,
-                                                           float *__restrict__ scores_out) {
+__global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_per_eu(2))) void decode_kernel_mfma(
+    DeviceBooks books, DecodeShape shp, const float *__restrict__ q_rot, const uint4 *__restrict__ cache,
+    const uint32_t *__restrict__ v, const int32_t *__restrict__ seq_lens, float *__restrict__ part_ml,
+    float *__restrict__ part_acc, float *__restrict__ scores_out) {
     constexpr int D = P::D;
     constexpr int CPL = D / 16;            // channels per lane chunk = N-blocks
     constexpr int CW = CPL / 2;            // 32-bit words per chunk
     constexpr int RP = RG < 4 ? 4 : RG;    // probability rows padded to a multiple of 4
-    __shared__ DecodeSmemMfma<P, RG> sm;
+    constexpr int ROWB = D * 2;            // bytes per value row
+    constexpr int TILEB = P::GRANULES * kWave * 16;  // bytes per cache tile
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    DecodeSmemMfma<P> &sm = *reinterpret_cast<DecodeSmemMfma<P> *>(smem_raw);
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int split = blockIdx.x;
-    const int kvh = blockIdx.y / shp.n_row_groups, grp = blockIdx.y % shp.n_row_groups;
-    const int seq = blockIdx.z;
-    const int len = seq_lens[seq];
-    const int t_begin = split * shp.split_len;
-    if (t_begin >= len) return;  // the merge only reads splits that start below len
-    const int t_end = min(len, t_begin + shp.split_len);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
+    for (int e = tid; e < kDecodeWaves * 16 * kPRow; e += kDecodeWaves * kWave) (&sm.pbuf[0][0][0])[e] = 0;
+    build_tables<P>(sm.tb, books, tid, kDecodeWaves * kWave);
 
-    if (wave == 0) copy_books(books, sm.c_xi, sm.rho);
-    for (int e = tid; e < 4 * 16 * kPRow; e += 256) (&sm.pbuf[0][0][0])[e] = 0;
-    __syncthreads();
-    build_dir_lut<P::BD0>(sm.lut0, sm.c_xi[0], tid, 256);
-    if constexpr (P::NCLASS == 2) build_dir_lut<P::BD1>(sm.lut1, sm.c_xi[1], tid, 256);
-    __syncthreads();
-
-    const int64_t pair = static_cast<int64_t>(seq) * shp.n_kv_heads + kvh;
-    const int64_t group_id = pair * shp.n_row_groups + grp;
-    const float *qg = q_rot + group_id * (P::QS * RG);
-    const uint4 *region = cache + pair * (shp.t_capacity * P::GRANULES);
+    WaveWork ww;
+    if (!wave_work(shp, seq_lens, wave, &ww)) return;
+    const float *qg = q_rot + ww.group_id * (P::QS * RG);
     const int n16 = lane & 15, g4 = lane >> 4;
-    // value words of this lane: row stride D/2 words, chunk at word CW * n16
-    const uint32_t *v_lane = v + pair * shp.t_capacity * (D / 2) + CW * n16;
+    // Addresses are a wave-uniform base (scalar registers) plus a small per-lane byte offset.
+    const char *k_region = reinterpret_cast<const char *>(cache) + ww.pair * shp.t_capacity * (P::GRANULES * 16);
+    const uint32_t k_lane = lane * 16u;
+    const char *v_pair = reinterpret_cast<const char *>(v) + ww.pair * shp.t_capacity * ROWB;
+    const uint32_t v_lane = g4 * ROWB + n16 * (CPL * 2);
     const int ppos = (lane & 32) + 8 * (lane & 3) + ((lane & 31) >> 2);  // slot of key `lane` in a pbuf row
+
+    // Only the words that hold record bytes are loaded: a register written by a load but never read
+    // may be reused at once by the compiler, which then has to wait for that load first.
+    auto load_record = [&](int tile, uint32_t (&w)[P::NWORDS]) {
+        typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+        typedef uint32_t u32x3_t __attribute__((ext_vector_type(3)));
+        constexpr int USED = (P::RECORD_BYTES + 3) / 4;
+        const char *src = k_region + static_cast<int64_t>(tile) * TILEB;
+#pragma unroll
+        for (int g = 0; g < P::GRANULES; ++g) {
+            const char *gp = src + g * (kWave * 16) + k_lane;
+            constexpr int kFull = 4;
+            const int n = (USED - 4 * g) < kFull ? (USED - 4 * g) : kFull;
+            if (n == 4) {
+                const uint4 x = *reinterpret_cast<const uint4 *>(gp);
+                w[4 * g] = x.x; w[4 * g + 1] = x.y; w[4 * g + 2] = x.z; w[4 * g + 3] = x.w;
+            } else if (n == 3) {
+                const u32x3_t x = *reinterpret_cast<const u32x3_t *>(gp);
+                w[4 * g] = x.x; w[4 * g + 1] = x.y; w[4 * g + 2] = x.z; w[4 * g + 3] = 0u;
+            } else if (n == 2) {
+                const u32x2_t x = *reinterpret_cast<const u32x2_t *>(gp);
+                w[4 * g] = x.x; w[4 * g + 1] = x.y; w[4 * g + 2] = 0u; w[4 * g + 3] = 0u;
+            } else {
+                w[4 * g] = *reinterpret_cast<const uint32_t *>(gp);
+                w[4 * g + 1] = 0u; w[4 * g + 2] = 0u; w[4 * g + 3] = 0u;
+            }
+        }
+    };
+    auto load_chunk = [&](const char *src, uint32_t (&dst)[CW]) {
+        if constexpr (CW == 2) {
+            const uint2 x = *reinterpret_cast<const uint2 *>(src);
+            dst[0] = x.x; dst[1] = x.y;
+        } else {
+#pragma unroll
+            for (int q4 = 0; q4 < CW / 4; ++q4) {
+                const uint4 x = reinterpret_cast<const uint4 *>(src)[q4];
+                dst[4 * q4] = x.x; dst[4 * q4 + 1] = x.y; dst[4 * q4 + 2] = x.z; dst[4 * q4 + 3] = x.w;
+            }
+        }
+    };
 
     float m_run[RG], l_lane[RG];
     f32x4_t acc[CPL];
@@ -370,68 +360,52 @@ __global__ __launch_bounds__(256) void decode_kernel_mfma(DeviceBooks books, Dec
 #pragma unroll
     for (int c = 0; c < CPL; ++c) acc[c] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
 
-    for (int t0 = t_begin + wave * kWave; t0 < t_end; t0 += 4 * kWave) {
-        const int n_valid = min(kWave, t_end - t0);
-        // D6 operands first, so that they are in flight during the score phase: 8 keys x CPL channels
-        // per k-step and lane
-        uint32_t vr[2][8][CW];
+    // Values of tile `tile` for this lane: 8 keys x CPL channels per k-step.  Rows past the end of a
+    // ragged last tile are replaced by the last valid row; their probabilities are zero, and no memory
+    // outside [0, len) is read.
+    auto load_values = [&](int tile, uint32_t (&vr)[2][8][CW]) {
+        const int t0 = tile * kWave;
+        const int n_valid = min(kWave, ww.len - t0);
+        const char *vtile = v_pair + static_cast<int64_t>(t0) * ROWB;
+        const int row_limit = (n_valid - 1 - g4) * ROWB;  // min(c, limit) + g4 == min(c + g4, n_valid - 1)
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int key = 32 * ks + 4 * j + g4;
-                const uint32_t *src = v_lane + static_cast<int64_t>(t0 + key) * (D / 2);
-                if (n_valid == kWave || key < n_valid) {
-                    if constexpr (CW == 2) {
-                        const uint2 x = *reinterpret_cast<const uint2 *>(src);
-                        vr[ks][j][0] = x.x; vr[ks][j][1] = x.y;
-                    } else {
-#pragma unroll
-                        for (int q4 = 0; q4 < CW / 4; ++q4) {
-                            const uint4 x = reinterpret_cast<const uint4 *>(src)[q4];
-                            vr[ks][j][4 * q4] = x.x; vr[ks][j][4 * q4 + 1] = x.y;
-                            vr[ks][j][4 * q4 + 2] = x.z; vr[ks][j][4 * q4 + 3] = x.w;
-                        }
-                    }
-                } else {
-#pragma unroll
-                    for (int cw = 0; cw < CW; ++cw) vr[ks][j][cw] = 0u;
-                }
-            }
-        // D1: this lane's record
-        uint32_t w[P::NWORDS];
-        const uint4 *tile = region + static_cast<int64_t>(t0 / kWave) * (P::GRANULES * kWave) + lane;
-#pragma unroll
-        for (int g = 0; g < P::GRANULES; ++g) {
-            const uint4 x = tile[g * kWave];
-            w[4 * g] = x.x; w[4 * g + 1] = x.y; w[4 * g + 2] = x.z; w[4 * g + 3] = x.w;
-        }
-        // D2-D4: scores (queries carry the softmax scale already)
+            for (int j = 0; j < 8; ++j)
+                load_chunk(vtile + static_cast<uint32_t>(min((32 * ks + 4 * j) * ROWB, row_limit) +
+                                                         static_cast<int>(v_lane)), vr[ks][j]);
+    };
+    // One tile.  Its values are requested first, so that they are in flight during the score phase;
+    // the record of the wave's next tile is requested right after and is used one call later.  The tile
+    // loop below is unrolled by two with the two record buffers swapping roles, so that no register
+    // copies (and no full memory wait in front of them) carry the prefetched record over.
+    auto process_tile = [&](int tile, const uint32_t (&w)[P::NWORDS], uint32_t (&w_next)[P::NWORDS])
+                            __attribute__((always_inline)) {
+        const int t0 = tile * kWave;
+        const int n_valid = min(kWave, ww.len - t0);
+        uint32_t vr[2][8][CW];
+        load_values(tile, vr);
+        // always issued (the wave's last tile re-reads itself): a branch here would make the compiler wait
+        // for every outstanding load before the scores instead of only for this tile's record
+        load_record(min(tile + ww.tile_step, ww.tile_last), w_next);
+        // D2-D4: scores (queries carry the softmax scale already).  The query offset (always 0) is
+        // laundered per tile: otherwise the loop-invariant scalar loads of the whole query are hoisted
+        // out of the tile loop and hundreds of scalar registers spill.
         float s[RG];
-        tile_scores_t<P, RG>(w, qg, sm, s);
+        int q_off = 0;
+        asm volatile("" : "+s"(q_off));
+        tile_scores<P, RG>(w, qg + q_off, sm.tb, lane, s);
         const float gamma = __uint_as_float(w[0]);
         const bool valid = lane < n_valid;
 #pragma unroll
         for (int r = 0; r < RG; ++r) s[r] = valid ? s[r] * gamma : -INFINITY;
-        if (scores_out != nullptr && valid) {
-#pragma unroll
-            for (int r = 0; r < RG; ++r) {
-                const int row = grp * RG + r;
-                if (row < shp.rows_per_kv) {
-                    const int qi = row / shp.heads_per_kv, head = kvh * shp.heads_per_kv + row % shp.heads_per_kv;
-                    scores_out[((static_cast<int64_t>(seq) * shp.n_q + qi) * shp.n_q_heads + head) * shp.t_capacity +
-                               t0 + lane] = s[r];
-                }
-            }
-        }
+        if (scores_out != nullptr && valid) store_scores<RG>(shp, ww, scores_out, t0 + lane, s);
         // D5: online softmax, one running maximum per row for the whole wave
         float alpha[RG];
-        bool rescale = false;
 #pragma unroll
         for (int r = 0; r < RG; ++r) {
             const float m_new = fmaxf(m_run[r], wave_max(s[r]));
             alpha[r] = exp2f((m_run[r] - m_new) * kLog2e);
-            rescale |= (m_new != m_run[r]);
             m_run[r] = m_new;
             const float p = exp2f((s[r] - m_new) * kLog2e);
             l_lane[r] = fmaf(l_lane[r], alpha[r], p);
@@ -440,19 +414,17 @@ __global__ __launch_bounds__(256) void decode_kernel_mfma(DeviceBooks books, Dec
             sm.pbuf[wave][r][ppos] = static_cast<uint16_t>(pb >> 16);
             sm.pbuf[wave][RP + r][ppos] = static_cast<uint16_t>(__float_as_uint(lo) >> 16);
         }
-        if (rescale) {
-            // accumulator rows of this lane: m = 4 * g4 + i, probability row r = m % RP
+        // accumulator rows of this lane: m = 4 * g4 + i, probability row r = m % RP
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                float a;
-                if constexpr (RP == 4) {
-                    a = i < RG ? alpha[i < RG ? i : 0] : 1.0f;
-                } else {
-                    a = (g4 & 1) ? alpha[4 + i] : alpha[i];
-                }
-#pragma unroll
-                for (int c = 0; c < CPL; ++c) acc[c][i] *= a;
+        for (int i = 0; i < 4; ++i) {
+            float a;
+            if constexpr (RP == 4) {
+                a = i < RG ? alpha[i < RG ? i : 0] : 1.0f;
+            } else {
+                a = (g4 & 1) ? alpha[4 + i] : alpha[i];
             }
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) acc[c][i] *= a;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -473,50 +445,157 @@ __global__ __launch_bounds__(256) void decode_kernel_mfma(DeviceBooks books, Dec
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         __builtin_amdgcn_wave_barrier();
+    };
+    uint32_t w_a[P::NWORDS], w_b[P::NWORDS];
+    if (ww.tile_begin < ww.tile_end) load_record(ww.tile_begin, w_a);
+    for (int tile = ww.tile_begin; tile < ww.tile_end; tile += 2 * ww.tile_step) {
+        process_tile(tile, w_a, w_b);
+        if (tile + ww.tile_step < ww.tile_end) process_tile(tile + ww.tile_step, w_b, w_a);
     }
 
-    // D7: add the hi and lo partial results (lane groups RP/4 apart), then fold the 4 wavefronts
+    // D7: add the hi and lo partial results (lane groups RP/4 apart) and emit the wave's partial
 #pragma unroll
     for (int c = 0; c < CPL; ++c)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const float tot = acc[c][i] + __shfl_down(acc[c][i], RP * 4, kWave);
             const int r = 4 * g4 + i;
-            if (r < RG) sm.red[wave][r][CPL * n16 + c] = tot;
+            if (r < RG && ww.grp * RG + r < shp.rows_per_kv)
+                part_acc[((ww.group_id * RG + r) * shp.n_splits + ww.split) * D + CPL * n16 + c] = tot;
         }
 #pragma unroll
     for (int r = 0; r < RG; ++r) {
         const float l = wave_sum(l_lane[r]);
-        if (lane == 0) { sm.wave_m[wave][r] = m_run[r]; sm.wave_l[wave][r] = l; }
-    }
-    __syncthreads();
-    for (int e = tid; e < RG * D; e += 256) {
-        const int r = e / D, c = e % D;
-        const int row = grp * RG + r;
-        if (row >= shp.rows_per_kv) continue;
-        float m = sm.wave_m[0][r];
-#pragma unroll
-        for (int wv = 1; wv < 4; ++wv) m = fmaxf(m, sm.wave_m[wv][r]);
-        float l = 0.0f, a = 0.0f;
-#pragma unroll
-        for (int wv = 0; wv < 4; ++wv) {
-            const float mw = sm.wave_m[wv][r];
-            const float f = (mw == -INFINITY) ? 0.0f : exp2f((mw - m) * kLog2e);
-            l += f * sm.wave_l[wv][r];
-            a += f * sm.red[wv][r][c];
+        if (lane == 0) {
+            const int64_t prow = (ww.group_id * RG + r) * shp.n_splits + ww.split;
+            part_ml[prow * 2] = m_run[r];
+            part_ml[prow * 2 + 1] = l;
         }
-        const int64_t prow = (group_id * RG + r) * shp.n_splits + split;
-        part_acc[prow * D + c] = a;
-        if (c == 0) { part_ml[prow * 2] = m; part_ml[prow * 2 + 1] = l; }
     }
 }
 
-// ---- D8: merge of the split partials ----------------------------------------------------------
+// ---- fp32 values: P.V on the vector ALUs --------------------------------------------------------
+// The probabilities go through LDS to a mapping with 8 channels per lane; lanes with the same
+// lane / (d / 8) walk the same keys.
+template <class P, int RG>
+struct DecodeSmemValu {
+    DecodeTables<P> tb;
+    float pbuf[kDecodeWaves][kWave][RG];
+};
+
+template <class P, int RG>
+__global__ __launch_bounds__(kDecodeWaves *kWave) void decode_kernel_valu(
+    DeviceBooks books, DecodeShape shp, const float *__restrict__ q_rot, const uint4 *__restrict__ cache,
+    const float4 *__restrict__ v, const int32_t *__restrict__ seq_lens, float *__restrict__ part_ml,
+    float *__restrict__ part_acc, float *__restrict__ scores_out) {
+    constexpr int D = P::D;
+    constexpr int LPR = D / 8;          // lanes per value row (8 channels per lane)
+    constexpr int KPL = kWave / LPR;    // value rows per wave-wide load
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    DecodeSmemValu<P, RG> &sm = *reinterpret_cast<DecodeSmemValu<P, RG> *>(smem_raw);
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    build_tables<P>(sm.tb, books, tid, kDecodeWaves * kWave);
+    WaveWork ww;
+    if (!wave_work(shp, seq_lens, wave, &ww)) return;
+    const float *qg = q_rot + ww.group_id * (P::QS * RG);
+    const uint4 *region = cache + ww.pair * (shp.t_capacity * P::GRANULES);
+    const int64_t v_row0 = ww.pair * shp.t_capacity;
+
+    float m_run[RG], l_lane[RG], acc[RG][8];
+#pragma unroll
+    for (int r = 0; r < RG; ++r) {
+        m_run[r] = -INFINITY;
+        l_lane[r] = 0.0f;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[r][c] = 0.0f;
+    }
+    const int rl = lane % LPR, ko = lane / LPR;
+
+    for (int tile = ww.tile_begin; tile < ww.tile_end; tile += ww.tile_step) {
+        const int t0 = tile * kWave;
+        const int n_valid = min(kWave, ww.len - t0);
+        uint32_t w[P::NWORDS];
+        const uint4 *src = region + static_cast<int64_t>(tile) * (P::GRANULES * kWave) + lane;
+#pragma unroll
+        for (int g = 0; g < P::GRANULES; ++g) {
+            const uint4 x = src[g * kWave];
+            w[4 * g] = x.x; w[4 * g + 1] = x.y; w[4 * g + 2] = x.z; w[4 * g + 3] = x.w;
+        }
+        float s[RG];
+        int q_off = 0;
+        asm volatile("" : "+s"(q_off));
+        tile_scores<P, RG>(w, qg + q_off, sm.tb, lane, s);
+        const float gamma = __uint_as_float(w[0]);
+        const bool valid = lane < n_valid;
+#pragma unroll
+        for (int r = 0; r < RG; ++r) s[r] = valid ? s[r] * gamma : -INFINITY;
+        if (scores_out != nullptr && valid) store_scores<RG>(shp, ww, scores_out, t0 + lane, s);
+        float alpha[RG];
+#pragma unroll
+        for (int r = 0; r < RG; ++r) {
+            const float m_new = fmaxf(m_run[r], wave_max(s[r]));
+            alpha[r] = exp2f((m_run[r] - m_new) * kLog2e);
+            m_run[r] = m_new;
+            const float p = exp2f((s[r] - m_new) * kLog2e);
+            l_lane[r] = fmaf(l_lane[r], alpha[r], p);
+            sm.pbuf[wave][lane][r] = p;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) acc[r][c] *= alpha[r];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        for (int kb = 0; kb < n_valid; kb += KPL) {
+            const int key = kb + ko;
+            if (key < n_valid) {
+                float pv[RG];
+#pragma unroll
+                for (int r = 0; r < RG; ++r) pv[r] = sm.pbuf[wave][key][r];
+                const int64_t vrow = v_row0 + t0 + key;
+                const float4 a = v[vrow * (D / 4) + 2 * rl];
+                const float4 b = v[vrow * (D / 4) + 2 * rl + 1];
+                const float vals[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+                for (int r = 0; r < RG; ++r)
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) acc[r][c] = fmaf(pv[r], vals[c], acc[r][c]);
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+
+    // D7: fold the KPL lane groups and emit the wave's partial
+#pragma unroll
+    for (int o = LPR; o < kWave; o <<= 1)
+#pragma unroll
+        for (int r = 0; r < RG; ++r)
+#pragma unroll
+            for (int c = 0; c < 8; ++c) acc[r][c] += __shfl_xor(acc[r][c], o, kWave);
+#pragma unroll
+    for (int r = 0; r < RG; ++r) {
+        const float l = wave_sum(l_lane[r]);
+        if (ww.grp * RG + r >= shp.rows_per_kv) continue;
+        const int64_t prow = (ww.group_id * RG + r) * shp.n_splits + ww.split;
+        if (ko == 0) {
+#pragma unroll
+            for (int c = 0; c < 8; ++c) part_acc[prow * D + rl * 8 + c] = acc[r][c];
+        }
+        if (lane == 0) { part_ml[prow * 2] = m_run[r]; part_ml[prow * 2 + 1] = l; }
+    }
+}
+
+// ---- D8: merge of the split partials, one wavefront per output row -----------------------------------
+// out = sum_j w_j acc_j / sum_j w_j l_j with w_j = exp(m_j - max_j m_j) (the flash-decoding identity).
+// A split without tokens has m = -inf, l = 0 and a zero accumulator, so it needs no special case.
 template <int D>
-__global__ __launch_bounds__(D) void merge_kernel(DecodeShape shp, const int32_t *__restrict__ seq_lens,
-                                                   const float *__restrict__ part_ml,
-                                                   const float *__restrict__ part_acc, float *__restrict__ out) {
-    const int c = threadIdx.x;
+__global__ __launch_bounds__(kWave) void merge_kernel(DecodeShape shp, const float *__restrict__ part_ml,
+                                                      const float *__restrict__ part_acc, float *__restrict__ out) {
+    constexpr int CPT = D / kWave;  // channels per lane
+    constexpr int UN = 8;           // partial rows in flight per lane
+    __shared__ float wgt[kWave];
+    const int lane = threadIdx.x;
     const int64_t orow = blockIdx.x;  // (seq, qi, head)
     const int head = static_cast<int>(orow % shp.n_q_heads);
     const int qi = static_cast<int>((orow / shp.n_q_heads) % shp.n_q);
@@ -527,17 +606,43 @@ __global__ __launch_bounds__(D) void merge_kernel(DecodeShape shp, const int32_t
     const int64_t prow0 =
         (((static_cast<int64_t>(seq) * shp.n_kv_heads + kvh) * shp.n_row_groups + grp) * shp.rows_per_pass + r) *
         shp.n_splits;
-    const int len = seq_lens[seq];
-    const int n_valid = min((len + shp.split_len - 1) / shp.split_len, shp.n_splits);  // splits that start below len
     float m = -INFINITY;
-    for (int j = 0; j < n_valid; ++j) m = fmaxf(m, part_ml[(prow0 + j) * 2]);
-    float l = 0.0f, a = 0.0f;
-    for (int j = 0; j < n_valid; ++j) {
-        const float f = exp2f((part_ml[(prow0 + j) * 2] - m) * kLog2e);
-        l += f * part_ml[(prow0 + j) * 2 + 1];
-        a += f * part_acc[(prow0 + j) * D + c];
+    for (int j = lane; j < shp.n_splits; j += kWave) m = fmaxf(m, part_ml[(prow0 + j) * 2]);
+    m = wave_max(m);
+    float a[CPT];
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) a[c] = 0.0f;
+    float l = 0.0f;
+    for (int j0 = 0; j0 < shp.n_splits; j0 += kWave) {
+        const int j = j0 + lane;
+        float f = 0.0f;
+        if (j < shp.n_splits) {
+            const float2 ml = *reinterpret_cast<const float2 *>(part_ml + (prow0 + j) * 2);
+            f = (ml.x == -INFINITY) ? 0.0f : exp2f((ml.x - m) * kLog2e);
+            l += f * ml.y;
+        }
+        __syncthreads();
+        wgt[lane] = f;
+        __syncthreads();
+        const int nj = min(kWave, shp.n_splits - j0);
+        for (int jj = 0; jj < nj; jj += UN) {
+            float x[UN][CPT];
+#pragma unroll
+            for (int u = 0; u < UN; ++u)
+#pragma unroll
+                for (int c = 0; c < CPT; ++c)
+                    x[u][c] = part_acc[(prow0 + j0 + min(jj + u, nj - 1)) * D + c * kWave + lane];
+#pragma unroll
+            for (int u = 0; u < UN; ++u) {
+                const float fj = (jj + u < nj) ? wgt[jj + u] : 0.0f;
+#pragma unroll
+                for (int c = 0; c < CPT; ++c) a[c] = fmaf(fj, x[u][c], a[c]);
+            }
+        }
     }
-    out[orow * D + c] = n_valid > 0 ? a / l : 0.0f;
+    l = wave_sum(l);
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) out[orow * D + c * kWave + lane] = (l > 0.0f) ? a[c] / l : 0.0f;
 }
 
 // ---- launch helpers -----------------------------------------------------------------------------
@@ -550,14 +655,28 @@ int launch_decode_rg(const octopus_codebooks_t &cb, const DecodeShape &s, const 
         for (int k = 0; k < 32; ++k) books.c_xi[c][k] = cb.c_xi[c][k];
         for (int k = 0; k < 8; ++k) books.c_rho[c][k] = cb.c_rho[c][k];
     }
-    const dim3 grid(s.n_splits, s.n_kv_heads * s.n_row_groups, s.n_seq);
-    if (v_dtype == OCTOPUS_DTYPE_BF16)
-        hipLaunchKernelGGL((decode_kernel_mfma<P, RG>), grid, dim3(256), 0, stream, books, s, q_rot,
+    // n_splits is a multiple of the wavefronts per workgroup
+    const int64_t wgs = static_cast<int64_t>(s.n_seq) * s.n_kv_heads * s.n_row_groups * (s.n_splits / kDecodeWaves);
+    const dim3 grid(static_cast<unsigned>(wgs));
+    const dim3 block(kDecodeWaves * kWave);
+    hipError_t err;
+    if (v_dtype == OCTOPUS_DTYPE_BF16) {
+        const size_t smem = sizeof(DecodeSmemMfma<P>);
+        err = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel_mfma<P, RG>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem));
+        if (err != hipSuccess) return static_cast<int>(err);
+        hipLaunchKernelGGL((decode_kernel_mfma<P, RG>), grid, block, smem, stream, books, s, q_rot,
                            static_cast<const uint4 *>(cache), static_cast<const uint32_t *>(v), seq_lens, part_ml,
                            part_acc, scores_out);
-    else
-        hipLaunchKernelGGL((decode_kernel_valu<P, RG>), grid, dim3(256), 0, stream, books, s, q_rot,
-                           static_cast<const uint4 *>(cache), v, 0, seq_lens, part_ml, part_acc, scores_out);
+    } else {
+        const size_t smem = sizeof(DecodeSmemValu<P, RG>);
+        err = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel_valu<P, RG>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem));
+        if (err != hipSuccess) return static_cast<int>(err);
+        hipLaunchKernelGGL((decode_kernel_valu<P, RG>), grid, block, smem, stream, books, s, q_rot,
+                           static_cast<const uint4 *>(cache), static_cast<const float4 *>(v), seq_lens, part_ml,
+                           part_acc, scores_out);
+    }
     return static_cast<int>(hipGetLastError());
 }
 

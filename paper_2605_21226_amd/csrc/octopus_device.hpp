@@ -79,6 +79,18 @@ __device__ __forceinline__ uint32_t field(const uint32_t (&w)[NW]) {
     }
 }
 
+// Same for a field whose upper bits may lie past the last word of the record (they read as zero).
+template <int BITPOS, int NBITS, int NW>
+__device__ __forceinline__ uint32_t field_clamped(const uint32_t (&w)[NW]) {
+    constexpr int wi = BITPOS >> 5, sh = BITPOS & 31;
+    constexpr uint32_t mask = (1u << NBITS) - 1u;
+    if constexpr (sh + NBITS <= 32 || wi + 1 >= NW) {
+        return (w[wi] >> sh) & mask;
+    } else {
+        return ((w[wi] >> sh) | (w[wi + 1] << (32 - sh))) & mask;
+    }
+}
+
 // Eq. (oct-decode): unit vector of a point of the square, sign(0) = +1.
 __device__ __forceinline__ float4 oct_decode(float xi, float eta) {
     const float r = 1.0f - fabsf(xi) - fabsf(eta);
@@ -113,10 +125,22 @@ __device__ __forceinline__ void copy_books(const DeviceBooks &books, float (*c_x
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
 
+// Wave-wide reductions on the data-parallel-primitive path (no LDS traffic): shifts within rows of 16
+// lanes, then row broadcasts; lane 63 ends up with the total, which is returned wave-uniform.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_take(float v) {
+    // lanes whose source lane does not exist, or whose row is masked off, keep their own value
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
+}
+
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
-    return v;
+    v = fmaxf(v, dpp_take<0x111, 0xf>(v));  // row_shr:1
+    v = fmaxf(v, dpp_take<0x112, 0xf>(v));  // row_shr:2
+    v = fmaxf(v, dpp_take<0x114, 0xf>(v));  // row_shr:4
+    v = fmaxf(v, dpp_take<0x118, 0xf>(v));  // row_shr:8
+    v = fmaxf(v, dpp_take<0x142, 0xa>(v));  // row_bcast:15 into rows 1 and 3
+    v = fmaxf(v, dpp_take<0x143, 0xc>(v));  // row_bcast:31 into rows 2 and 3
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
 __device__ __forceinline__ float wave_sum(float v) {

@@ -234,18 +234,18 @@ DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t
     while (s.rows_per_pass < s.rows_per_kv && s.rows_per_pass < 8) s.rows_per_pass *= 2;
     s.n_row_groups = (s.rows_per_kv + s.rows_per_pass - 1) / s.rows_per_pass;
     s.t_capacity = t_capacity;
-    // Split-K sizing: aim at ~8 workgroups per compute unit (256 CUs), at least one 256-token
-    // slab (4 wavefronts x one 64-token tile) per workgroup.
-    const int64_t slab = 256;
+    // Split-K sizing: one wavefront per split.  The chip holds 256 compute units x 8 wavefronts of the
+    // decode kernel at once; the tiles of each (sequence, KV head, row group) are divided over as many
+    // splits as fill those slots once, so that all wavefronts start together and end together.
     const int64_t len = std::max<int64_t>(max_len, 1);
-    const int64_t pairs = static_cast<int64_t>(n_seq) * n_kv_heads * s.n_row_groups;
-    const int64_t max_splits = (len + slab - 1) / slab;
-    int64_t want = (2048 + pairs - 1) / pairs;
-    want = std::max<int64_t>(1, std::min<int64_t>(want, max_splits));
-    int64_t split_len = (len + want - 1) / want;
-    split_len = ((split_len + slab - 1) / slab) * slab;
-    s.split_len = static_cast<int32_t>(split_len);
-    s.n_splits = static_cast<int32_t>((len + split_len - 1) / split_len);
+    const int64_t groups = static_cast<int64_t>(n_seq) * n_kv_heads * s.n_row_groups;
+    const int64_t max_tiles = (len + OCTOPUS_TILE - 1) / OCTOPUS_TILE;
+    const int64_t slots = 256 * 8;
+    // workgroups of 4 wavefronts: splits come in fours
+    int64_t want = (slots / 4 + groups / 2) / groups;
+    want = std::max<int64_t>(1, std::min<int64_t>(want, (max_tiles + 3) / 4));
+    s.n_splits = static_cast<int32_t>(4 * want);
+    s.max_len = static_cast<int32_t>(max_len);
     return s;
 }
 
@@ -341,7 +341,8 @@ int octopus_encode(const octopus_codebooks_t *cb, const void *keys, int32_t key_
 static int decode_args_ok(const octopus_codebooks_t *cb, int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads,
                           int32_t n_q, int64_t max_len) {
     if (cb == nullptr) return OCTOPUS_EINVAL;
-    if (n_seq < 1 || n_q_heads < 1 || n_kv_heads < 1 || n_q < 1 || max_len < 0) return OCTOPUS_EINVAL;
+    if (n_seq < 1 || n_q_heads < 1 || n_kv_heads < 1 || n_q < 1 || max_len < 0 || max_len > INT32_MAX)
+        return OCTOPUS_EINVAL;
     if (n_q_heads % n_kv_heads != 0) return OCTOPUS_EINVAL;
     if (!plan_consistent(cb->plan)) return OCTOPUS_EINVAL;
     if (!plan_supported(cb->plan)) return OCTOPUS_EUNSUPPORTED;
@@ -380,7 +381,7 @@ int octopus_attn_decode(const octopus_codebooks_t *cb, const void *q, int32_t q_
     int err = launch_rotate_queries(cb->plan, q, q_dtype, signs, s, scale, q_rot, stream);
     if (err == 0)
         err = launch_decode(*cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, stream);
-    if (err == 0) err = launch_merge(cb->plan, s, seq_lens, part_ml, part_acc, out, stream);
+    if (err == 0) err = launch_merge(cb->plan, s, part_ml, part_acc, out, stream);
     return err == 0 ? OCTOPUS_OK : OCTOPUS_EHIP;
 }
 

@@ -25,8 +25,8 @@ struct DecodeShape {
     int32_t rows_per_kv;    // n_q * heads_per_kv query rows sharing one KV head
     int32_t rows_per_pass;  // query rows one workgroup scores per key (1, 2, 4 or 8)
     int32_t n_row_groups;   // ceil(rows_per_kv / rows_per_pass)
-    int32_t split_len;      // tokens per split (multiple of 64)
-    int32_t n_splits;       // ceil(max_len / split_len)
+    int32_t n_splits;       // wavefronts sharing the tiles of one (sequence, KV head, row group)
+    int32_t max_len;        // host-side bound of the sequence lengths
     int64_t t_capacity;
 };
 
@@ -45,8 +45,8 @@ int launch_rotate_queries(const octopus_plan_t &plan, const void *q, int q_dtype
 int launch_decode(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
                   const void *v, int v_dtype, const int32_t *seq_lens, float *part_ml, float *part_acc,
                   float *scores_out, void *stream);
-int launch_merge(const octopus_plan_t &plan, const DecodeShape &s, const int32_t *seq_lens, const float *part_ml,
-                 const float *part_acc, float *out, void *stream);
+int launch_merge(const octopus_plan_t &plan, const DecodeShape &s, const float *part_ml, const float *part_acc,
+                 float *out, void *stream);
 int launch_encode(const octopus_codebooks_t &cb, const void *keys, int key_dtype, int64_t stride_seq,
                   int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
                   const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos, void *stream);
