@@ -10,7 +10,9 @@ head_dim 128, 32768 cached tokens per sequence, bf16 keys / values / queries, 3 
 
 Prints ONE JSON line.  `value` is the effective HBM rate of the decode-attention call: algorithmic
 bytes (per key: the 58-byte canonical record + the 256-byte bf16 value row; plus queries and outputs)
-divided by the call's average duration, measured with events on the launch stream.
+divided by the call's average duration, measured with events on the launch stream.  `roofline`
+is the same byte count over the fused kernel's own duration (events recorded by the library around
+its launch), against the published 8 TB/s.
 """
 import argparse
 import json
@@ -34,6 +36,9 @@ def parse():
     ap.add_argument("--workload", default="llama3_8b_decode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a plain 1 GiB device-to-device copy (torch) three times, so that a rocprofv3 "
+                         "--pmc run of this command can scale FETCH_SIZE / WRITE_SIZE by a kernel of known size")
     return ap.parse_args()
 
 
@@ -112,6 +117,23 @@ def cpu_baseline(wl, keys, vals, q, signs, scale, record_bytes, budget_s=12.0):
     }
 
 
+def measured_traffic(workload):
+    """HBM bytes per launch of the fused decode kernel as measured with rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE (scaled by a plain copy of known size); read from the committed profile summary of this
+    workload, None if there is none."""
+    path = os.path.join(ROOT, "profiles", f"decode_kernel_mfma_{workload}_traffic.txt")
+    try:
+        vals = {}
+        with open(path) as f:
+            for line in f:
+                if "=" in line and not line.startswith("#"):
+                    k, v = line.split("=", 1)
+                    vals[k.strip()] = v.strip()
+        return int(float(vals["FETCH_BYTES_PER_LAUNCH"]) + float(vals["WRITE_BYTES_PER_LAUNCH"]))
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -153,6 +175,7 @@ def main():
         binding.octopus_encode(cb, keys[:, :n_new], sbits, cache, cap)
         if ev:
             ev[1].record()
+            binding.octopus_profile_events(ev[3], ev[4])  # around the fused kernel inside the next call
         binding.octopus_attn_decode(cb, q, sbits, cache, cap, vals, lens_dev, max_len, scale, out, ws)
         if ev:
             ev[2].record()
@@ -160,7 +183,11 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    for ev in events:          # a first record creates the HIP handles the library records into
+        ev[3].record()
+        ev[4].record()
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(events[i])
@@ -168,6 +195,7 @@ def main():
     wall = time.perf_counter() - t0
     enc_ms = np.array([e[0].elapsed_time(e[1]) for e in events])
     dec_ms = np.array([e[1].elapsed_time(e[2]) for e in events])
+    ker_ms = np.array([e[3].elapsed_time(e[4]) for e in events])
     assert bool(torch.isfinite(out).all())
 
     elt = 2 if wl.dtype == "bf16" else 4
@@ -179,6 +207,8 @@ def main():
     dec_s = float(dec_ms.mean()) * 1e-3
     enc_s = float(enc_ms.mean()) * 1e-3
     gbs = dec_bytes / dec_s / 1e9
+    ker_s = float(ker_ms.mean()) * 1e-3
+    ker_gbs = dec_bytes / ker_s / 1e9
 
     result = {
         "metric": "fused decode-attn effective HBM GB/s (% of peak); encode Mtokens/s",
@@ -208,17 +238,25 @@ def main():
         "encode_mtokens_per_s": round(wl.n_seq * n_new / enc_s / 1e6, 3),
         "encode_mkeys_per_s": round(n_keys_enc / enc_s / 1e6, 3),
         "roofline": {
-            "kernel": "octopus_attn_decode (query rotation + fused split-K decode kernel + merge; the fused "
-                      "kernel is >95% of the call)",
+            "kernel": "decode_kernel_mfma (the fused split-K decode kernel inside octopus_attn_decode), timed "
+                      "with HIP events recorded by the library around its launch on the launch stream",
             "bound": "hbm",
-            "achieved": round(gbs, 2),
+            "achieved": round(ker_gbs, 2),
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
-            "frac": round(gbs / HBM_PEAK_GBS, 4),
+            "frac": round(ker_gbs / HBM_PEAK_GBS, 4),
             "traffic": None,
             "algorithmic_bytes_per_launch": dec_bytes,
+            "kernel_ms": round(ker_s * 1e3, 4),
         },
     }
+    result["roofline"]["traffic"] = measured_traffic(wl.name)
+    if args.calibration_copy:
+        src = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, keys, vals, q, signs, scale, rec_bytes)
     print(json.dumps(result))

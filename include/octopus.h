@@ -163,6 +163,14 @@ int octopus_attn_decode(const octopus_codebooks_t *cb,
                         void *workspace, size_t workspace_bytes,
                         void *stream);
 
+/* Measurement aid (not part of the method): the next octopus_attn_decode call made by this thread
+ * records the HIP events `before` and `after` (hipEvent_t passed as void*, caller-owned, created
+ * with timing enabled) on the call's stream immediately before and after the launch of the fused
+ * split-K decode kernel, i.e. around Alg. 2 proper without the query rotation and the split merge.
+ * The handles are forgotten after that call; NULL, NULL cancels.  Returns OCTOPUS_OK, or
+ * OCTOPUS_EINVAL if only one of the two is NULL. */
+int octopus_profile_events(void *before, void *after);
+
 /* Static, human-readable name of an error code. */
 const char *octopus_strerror(int code);
 

@@ -18,7 +18,7 @@ MAX_LEVELS = 64
 TILE = 64
 
 EXPORTS = ("octopus_build_codebooks", "octopus_build_codebooks_pair", "octopus_cache_bytes", "octopus_encode",
-           "octopus_attn_decode_workspace", "octopus_attn_decode", "octopus_strerror")
+           "octopus_attn_decode_workspace", "octopus_attn_decode", "octopus_profile_events", "octopus_strerror")
 
 
 class Plan(ctypes.Structure):
@@ -83,6 +83,8 @@ def load():
     lib.octopus_attn_decode.argtypes = [CB, vp, i32, i32, i32, i32, i32, vp, vp, i64, vp, i32, vp, i64, f32, vp, vp,
                                         vp, ctypes.c_size_t, vp]
     lib.octopus_attn_decode.restype = ctypes.c_int
+    lib.octopus_profile_events.argtypes = [vp, vp]
+    lib.octopus_profile_events.restype = ctypes.c_int
     lib.octopus_strerror.argtypes = [ctypes.c_int]
     lib.octopus_strerror.restype = ctypes.c_char_p
     _lib = lib
@@ -164,3 +166,11 @@ def octopus_attn_decode(cb, q, signs, cache, t_capacity, v, seq_lens, max_len, s
                                       int(max_len), float(scale), _ptr(out), _ptr(scores_out), _ptr(workspace),
                                       int(workspace.numel() * workspace.element_size()), _stream_ptr(stream))
     _check(code, "octopus_attn_decode")
+
+
+def octopus_profile_events(before, after):
+    """before / after: torch.cuda.Event(enable_timing=True) that have been recorded once (so that their
+    HIP handles exist), or None, None to cancel.  See include/octopus.h."""
+    b = ctypes.c_void_p(before.cuda_event) if before is not None else ctypes.c_void_p(0)
+    a = ctypes.c_void_p(after.cuda_event) if after is not None else ctypes.c_void_p(0)
+    _check(load().octopus_profile_events(b, a), "octopus_profile_events")

@@ -16,6 +16,10 @@ OCTOPUS_DECL(128)
 OCTOPUS_DECL(256)
 #undef OCTOPUS_DECL
 
+int record_event(void *event, void *stream) {
+    return static_cast<int>(hipEventRecord(static_cast<hipEvent_t>(event), static_cast<hipStream_t>(stream)));
+}
+
 bool plan_supported(const octopus_plan_t &plan) {
     switch (plan.head_dim) {
         case 64: return plan_supported_d64(plan);

@@ -267,7 +267,19 @@ Workspace make_workspace(const octopus_plan_t &plan, const DecodeShape &s) {
 
 using namespace octopus;
 
+namespace {
+thread_local void *g_event_before = nullptr;
+thread_local void *g_event_after = nullptr;
+}  // namespace
+
 extern "C" {
+
+int octopus_profile_events(void *before, void *after) {
+    if ((before == nullptr) != (after == nullptr)) return OCTOPUS_EINVAL;
+    g_event_before = before;
+    g_event_after = after;
+    return OCTOPUS_OK;
+}
 
 int octopus_build_codebooks(int32_t head_dim, float bits, octopus_codebooks_t *out) {
     if (out == nullptr) return OCTOPUS_EINVAL;
@@ -379,8 +391,12 @@ int octopus_attn_decode(const octopus_codebooks_t *cb, const void *q, int32_t q_
     float *part_ml = reinterpret_cast<float *>(base + w.part_ml_off);
     float *part_acc = reinterpret_cast<float *>(base + w.part_acc_off);
     int err = launch_rotate_queries(cb->plan, q, q_dtype, signs, s, scale, q_rot, stream);
+    void *ev_before = g_event_before, *ev_after = g_event_after;
+    g_event_before = g_event_after = nullptr;
+    if (err == 0 && ev_before != nullptr) err = record_event(ev_before, stream);
     if (err == 0)
         err = launch_decode(*cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, stream);
+    if (err == 0 && ev_after != nullptr) err = record_event(ev_after, stream);
     if (err == 0) err = launch_merge(cb->plan, s, part_ml, part_acc, out, stream);
     return err == 0 ? OCTOPUS_OK : OCTOPUS_EHIP;
 }

@@ -51,6 +51,9 @@ int launch_encode(const octopus_codebooks_t &cb, const void *keys, int key_dtype
                   int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
                   const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos, void *stream);
 
+// hipEventRecord(event, stream); returns a hipError_t cast to int.
+int record_event(void *event, void *stream);
+
 // True when the kernels are instantiated for this plan.
 bool plan_supported(const octopus_plan_t &plan);
 
