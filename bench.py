@@ -42,34 +42,6 @@ def parse():
     return ap.parse_args()
 
 
-def device_inputs(wl, seed, dev):
-    """Synthetic keys / values / queries generated on the device from a seeded generator, with the
-    recipe of paper_2605_21226_amd.synth (per-channel log-normal scales, outlier channels)."""
-    import numpy as np
-    import torch
-
-    from paper_2605_21226_amd import synth
-
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(seed)
-    dt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
-    sig = torch.from_numpy(synth.channel_scales(seed, wl).astype(np.float32)).to(dev)       # [n_kv, d]
-    keys = torch.empty((wl.n_seq, wl.n_tokens, wl.n_kv_heads, wl.head_dim), dtype=dt, device=dev)
-    vals = torch.empty((wl.n_seq, wl.n_kv_heads, wl.n_tokens, wl.head_dim), dtype=dt, device=dev)
-    chunk = 4096
-    for s in range(wl.n_seq):
-        for t0 in range(0, wl.n_tokens, chunk):
-            n = min(chunk, wl.n_tokens - t0)
-            z = torch.randn((n, wl.n_kv_heads, wl.head_dim), generator=gen, device=dev)
-            keys[s, t0:t0 + n] = (z * sig[None]).to(dt)
-            z = torch.randn((wl.n_kv_heads, n, wl.head_dim), generator=gen, device=dev)
-            vals[s, :, t0:t0 + n] = z.to(dt)
-    q = torch.randn((wl.n_seq, wl.n_q, wl.n_q_heads, wl.head_dim), generator=gen, device=dev).to(dt)
-    signs = synth.sign_vectors(seed, wl.n_kv_heads, wl.head_dim)
-    lens = synth.context_lengths(seed, wl)
-    return keys, vals, q, signs, lens
-
-
 def cpu_baseline(wl, keys, vals, q, signs, scale, record_bytes, budget_s=12.0):
     """The oracle as it stands, timed on this machine's host cores on a bounded sample of the workload:
     whole sequences (all KV heads, all cached tokens; encode, then attention of each KV head's group of
@@ -145,6 +117,7 @@ def main():
     import torch
 
     from paper_2605_21226_amd import binding, synth
+    from paper_2605_21226_amd.synth_device import device_inputs
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)

@@ -400,17 +400,24 @@ void oracle_attention(const oracle_plan *p, const uint8_t *records, int64_t n_ke
  * Comparisons covered: the sign tests of Eq. (oct-encode) (p_z >= 0 and, on
  * the folded branch, sign(p_x), sign(p_y)), xi / eta against B_xi, the
  * candidate argmax (any window candidate within tol of the window maximum),
- * clip(s) against B_rho. */
+ * clip(s) against B_rho.
+ * tol is a distance in the coordinates of the rotated unit key u, the quantity
+ * every decision of Alg. 1 derives from.  Scores and clip(s) are in those
+ * units; the octahedral coordinates are not: p = t / l1, so a coordinate
+ * change of tol moves p_x, p_y, p_z, xi and eta by about tol / l1.  Their
+ * comparisons therefore use tol_p = tol / min(l1, 1), and a triplet whose l1
+ * is itself below tol (numerically zero, its direction rounding noise) admits
+ * every sign pattern and every seed. */
 static int window_admits(const oracle_plan *p, int c, const double t[3], double xi, double eta,
-                         int fx, int fy, int fn, double tol)
+                         int fx, int fy, int fn, double tol, double tol_p)
 {
     int K = 1 << p->b_dir[c], M = 1 << p->b_nrm[c];
     const double *cx = p->c_xi[c], *bx = p->b_xi[c];
     double n[3];
     oracle_oct_decode(cx[fx], cx[fy], n);
     double sf = t[0] * n[0] + t[1] * n[1] + t[2] * n[2];
-    int jx_lo = count_below(bx, K - 1, xi - tol), jx_hi = count_below(bx, K - 1, xi + tol);
-    int jy_lo = count_below(bx, K - 1, eta - tol), jy_hi = count_below(bx, K - 1, eta + tol);
+    int jx_lo = count_below(bx, K - 1, xi - tol_p), jx_hi = count_below(bx, K - 1, xi + tol_p);
+    int jy_lo = count_below(bx, K - 1, eta - tol_p), jy_hi = count_below(bx, K - 1, eta + tol_p);
     for (int jx = jx_lo; jx <= jx_hi; ++jx)
         for (int jy = jy_lo; jy <= jy_hi; ++jy) {
             int in_window = 0;
@@ -457,14 +464,16 @@ void oracle_classify_key(const oracle_plan *p, const double *k, const int8_t *s,
             double l1 = fabs(t[0]) + fabs(t[1]) + fabs(t[2]);
             double den = (l1 > OCT_EPS) ? l1 : OCT_EPS;
             double px = t[0] / den, py = t[1] / den, pz = t[2] / den;
-            if (pz >= -tol) ok = window_admits(p, c, t, px, py, fx, fy, fn, tol);     /* unfolded branch */
-            if (!ok && pz < tol)                                                       /* folded branch */
+            double tol_p = (l1 > tol) ? tol / (l1 < 1.0 ? l1 : 1.0) : 4.0;
+            if (pz >= -tol_p) ok = window_admits(p, c, t, px, py, fx, fy, fn, tol, tol_p); /* unfolded branch */
+            if (!ok && pz < tol_p)                                                     /* folded branch */
                 for (int vx = 0; vx < 2 && !ok; ++vx)
                     for (int vy = 0; vy < 2 && !ok; ++vy) {
                         double sx = vx ? 1.0 : -1.0, sy = vy ? 1.0 : -1.0;
-                        if (fabs(px) > tol && sx != sgn1(px)) continue;
-                        if (fabs(py) > tol && sy != sgn1(py)) continue;
-                        ok = window_admits(p, c, t, sx * (1.0 - fabs(py)), sy * (1.0 - fabs(px)), fx, fy, fn, tol);
+                        if (fabs(px) > tol_p && sx != sgn1(px)) continue;
+                        if (fabs(py) > tol_p && sy != sgn1(py)) continue;
+                        ok = window_admits(p, c, t, sx * (1.0 - fabs(py)), sy * (1.0 - fabs(px)), fx, fy, fn, tol,
+                                           tol_p);
                     }
         }
         counts[ok ? 1 : 2]++;

@@ -421,3 +421,65 @@ def test_classifier_treats_octahedral_sign_decisions_near_zero_as_ties():
             assert oracle.classify(plan, k[None, :], s, rec, tol=1e-20) == (plan.n_tri - 1, 0, 1)
             hits += 1
     assert hits >= 1
+
+
+def test_classifier_admits_any_direction_for_a_numerically_zero_triplet():
+    """At d = 64 the last triplet holds one real coordinate and two pads.  When that coordinate is zero
+    up to rounding, its direction is noise (any implementation's rounding decides it): every direction
+    code is a tie there, while its norm code and every other triplet stay strict."""
+    d = 64
+    plan = oracle.make_plan(d, 4)
+    s = synth.sign_vectors(9, 1, d)[0]
+    u = synth.gaussian_keys(9, 1, d)[0]
+    u[d - 1] = 0.0
+    k = 3.0 * oracle.rotate_inverse(u / np.linalg.norm(u), s)
+    e = oracle.encode_key(plan, k, s)
+    assert abs(e["u"][d - 1]) < 1e-15
+    i = plan.n_tri - 1
+    for code in ((3, 20), (31, 15), (14, 14), (0, 0)):
+        dirs = e["idx_dir"].copy()
+        dirs[2 * i], dirs[2 * i + 1] = code
+        if tuple(dirs[2 * i:2 * i + 2]) == tuple(e["idx_dir"][2 * i:2 * i + 2]):
+            continue
+        rec = oracle.pack_record(plan, e["gamma"], dirs, e["idx_nrm"])[None, :]
+        assert oracle.classify(plan, k[None, :], s, rec, tol=1e-6) == (plan.n_tri - 1, 1, 0)
+        nrm = e["idx_nrm"].copy()
+        nrm[i] = 3
+        rec = oracle.pack_record(plan, e["gamma"], dirs, nrm)[None, :]
+        assert oracle.classify(plan, k[None, :], s, rec, tol=1e-6) == (plan.n_tri - 1, 0, 1)
+    # the same foreign direction on an ordinary triplet is a hard mismatch
+    dirs = e["idx_dir"].copy()
+    dirs[0] = (dirs[0] + 16) % 32
+    rec = oracle.pack_record(plan, e["gamma"], dirs, e["idx_nrm"])[None, :]
+    assert oracle.classify(plan, k[None, :], s, rec, tol=1e-6) == (plan.n_tri - 1, 0, 1)
+
+
+def test_classifier_scales_the_octahedral_tolerance_with_the_triplet_l1_norm():
+    """xi = x / l1, so a coordinate tolerance tol is tol / l1 in xi.  Last triplet of d = 64 set to
+    (1e-5, 0, 0): xi = 1, and with tol = 1e-6 the admissible seeds are those whose cell reaches
+    xi >= 1 - 0.1, i.e. the top two of the 32 levels (boundaries 0.9297 and 0.8629); their windows hold
+    the codes 29..31.  Scores of all these candidates differ by far less than tol."""
+    d = 64
+    plan = oracle.make_plan(d, 4)
+    assert 0.86 < plan.b_xi[0][29] < 0.87 and 0.92 < plan.b_xi[0][30] < 0.93
+    s = synth.sign_vectors(9, 1, d)[0]
+    u = synth.gaussian_keys(10, 1, d)[0]
+    u[d - 1] = 0.0
+    u /= np.linalg.norm(u)
+    u[d - 1] = 1e-5
+    k = oracle.rotate_inverse(u, s)
+    e = oracle.encode_key(plan, k, s)
+    i = plan.n_tri - 1
+    assert e["idx_dir"][2 * i] == 31 and e["idx_nrm"][i] == 0
+    for code, expect in ((30, 1), (29, 1), (28, 2), (20, 2)):
+        dirs = e["idx_dir"].copy()
+        dirs[2 * i] = code
+        rec = oracle.pack_record(plan, e["gamma"], dirs, e["idx_nrm"])[None, :]
+        want = [plan.n_tri - 1, 0, 0]
+        want[expect] = 1
+        assert oracle.classify(plan, k[None, :], s, rec, tol=1e-6) == tuple(want), code
+    # with a tolerance 100 times smaller only the neighbour inside the oracle's own window remains a tie
+    dirs = e["idx_dir"].copy()
+    dirs[2 * i] = 29
+    rec = oracle.pack_record(plan, e["gamma"], dirs, e["idx_nrm"])[None, :]
+    assert oracle.classify(plan, k[None, :], s, rec, tol=1e-8) == (plan.n_tri - 1, 0, 1)
