@@ -132,12 +132,49 @@ __device__ __forceinline__ void build_rho_table(float *table, const float *c_rho
     }
 }
 
+// Where the direction and norm codes of a triplet together have at most 10 bits (every plan up to 3 bits
+// per coordinate), one table indexed by (norm code, xi code, eta code) holds the products
+// rho^ * n^ themselves: one lookup per triplet, no multiply.  Otherwise (5 + 5 + 3 bits) directions and
+// norm centroids come from the two tables above.
+constexpr bool joint_codes(int bd, int bn) { return 2 * bd + bn <= 10; }
+
+// The table is not replicated: the byte offset of an entry is then (direction code << 4) | (norm code
+// << (4 + 2 BD)), three instructions per triplet, and the bank conflicts of the lookups are hidden by
+// requesting them a chunk ahead.
+template <int BD, int BN>
+struct JointTable {
+    static constexpr int BITS = 2 * BD + BN;
+    static constexpr int ENTRIES = 1 << BITS;
+    static constexpr int REP = 1;
+    static constexpr int FLOAT4S = ENTRIES * REP;
+};
+
+template <int BD, int BN>
+__device__ __forceinline__ void build_joint_table(float4 *table, const float *c_xi, const float *c_rho, int tid,
+                                                  int nthreads) {
+    using T = JointTable<BD, BN>;
+    constexpr int K = 1 << BD;
+    for (int e = tid; e < T::FLOAT4S; e += nthreads) {
+        const int code = e / T::REP;
+        const float4 n = oct_decode(c_xi[code & (K - 1)], c_xi[(code >> BD) & (K - 1)]);
+        const float rho = c_rho[code >> (2 * BD)];
+        table[e] = make_float4(rho * n.x, rho * n.y, rho * n.z, 0.0f);
+    }
+}
+
+template <int BD, int BN>
+constexpr int dir_table_float4s() {
+    return joint_codes(BD, BN) ? JointTable<BD, BN>::FLOAT4S : DirTable<BD>::FLOAT4S;
+}
+
 template <class P>
 struct DecodeTables {
-    float4 dir0[DirTable<P::BD0>::FLOAT4S];
-    float4 dir1[P::NCLASS == 2 ? DirTable<(P::BD1 > 0 ? P::BD1 : 1)>::FLOAT4S : 1];
-    __attribute__((aligned(16))) float rho0[RhoTable<P::BN0>::FLOATS];
-    __attribute__((aligned(16))) float rho1[P::NCLASS == 2 ? RhoTable<(P::BN1 > 0 ? P::BN1 : 1)>::FLOATS : 4];
+    static constexpr bool J0 = joint_codes(P::BD0, P::BN0);
+    static constexpr bool J1 = P::NCLASS == 2 && joint_codes(P::BD1, P::BN1);
+    float4 dir0[dir_table_float4s<P::BD0, P::BN0>()];
+    float4 dir1[P::NCLASS == 2 ? dir_table_float4s<(P::BD1 > 0 ? P::BD1 : 1), (P::BN1 > 0 ? P::BN1 : 1)>() : 1];
+    __attribute__((aligned(16))) float rho0[J0 ? 4 : RhoTable<P::BN0>::FLOATS];
+    __attribute__((aligned(16))) float rho1[P::NCLASS == 2 && !J1 ? RhoTable<(P::BN1 > 0 ? P::BN1 : 1)>::FLOATS : 4];
     float c_xi[2][32];
     float c_rho[2][8];
 };
@@ -146,26 +183,36 @@ template <class P>
 __device__ __forceinline__ void build_tables(DecodeTables<P> &tb, const DeviceBooks &books, int tid, int nthreads) {
     if (tid < kWave) copy_books(books, tb.c_xi, tb.c_rho);
     __syncthreads();
-    build_dir_table<P::BD0>(tb.dir0, tb.c_xi[0], tid, nthreads);
-    build_rho_table<P::BN0>(tb.rho0, tb.c_rho[0], tid, nthreads);
+    if constexpr (DecodeTables<P>::J0) {
+        build_joint_table<P::BD0, P::BN0>(tb.dir0, tb.c_xi[0], tb.c_rho[0], tid, nthreads);
+    } else {
+        build_dir_table<P::BD0>(tb.dir0, tb.c_xi[0], tid, nthreads);
+        build_rho_table<P::BN0>(tb.rho0, tb.c_rho[0], tid, nthreads);
+    }
     if constexpr (P::NCLASS == 2) {
-        build_dir_table<P::BD1>(tb.dir1, tb.c_xi[1], tid, nthreads);
-        build_rho_table<P::BN1>(tb.rho1, tb.c_rho[1], tid, nthreads);
+        if constexpr (DecodeTables<P>::J1) {
+            build_joint_table<P::BD1, P::BN1>(tb.dir1, tb.c_xi[1], tb.c_rho[1], tid, nthreads);
+        } else {
+            build_dir_table<P::BD1>(tb.dir1, tb.c_xi[1], tid, nthreads);
+            build_rho_table<P::BN1>(tb.rho1, tb.c_rho[1], tid, nthreads);
+        }
     }
     __syncthreads();
 }
 
 // Which (sequence, KV head, row group, split) a wavefront works on, and its tiles.  A workgroup takes
 // a contiguous range of tiles of one (sequence, KV head, row group); its four wavefronts walk that
-// range interleaved (tile_begin, tile_begin + 4, ...), so that the workgroup as a whole streams through
+// range interleaved (step_begin, step_begin + 4, ...), so that the workgroup as a whole streams through
 // memory front to back, and each wavefront is one split with its own partial result.
 struct WaveWork {
     int seq, kvh, grp, split;
     int64_t pair, group_id;
-    int tile_begin, tile_end, tile_step, tile_last, len;
+    int step_begin, step_end, step_stride, step_last, len, n_tiles;
 };
 
-__device__ __forceinline__ bool wave_work(const DecodeShape &shp, const int32_t *seq_lens, int wave, WaveWork *ww) {
+// A step is `tiles_per_step` consecutive 64-token tiles, handled in one pass over the rotated query.
+__device__ __forceinline__ void wave_work(const DecodeShape &shp, const int32_t *seq_lens, int wave, int tiles_per_step,
+                                          WaveWork *ww) {
     const int n_wg_splits = shp.n_splits / kDecodeWaves;
     const int64_t wg = blockIdx.x;
     const int wsplit = static_cast<int>(wg % n_wg_splits);
@@ -176,38 +223,55 @@ __device__ __forceinline__ bool wave_work(const DecodeShape &shp, const int32_t 
     ww->kvh = static_cast<int>(ww->pair % shp.n_kv_heads);
     ww->seq = static_cast<int>(ww->pair / shp.n_kv_heads);
     ww->len = min(max(seq_lens[ww->seq], 0), shp.max_len);
-    const int n_tiles = (ww->len + kWave - 1) / kWave;
-    const int base = n_tiles / n_wg_splits, rem = n_tiles % n_wg_splits;
+    ww->n_tiles = (ww->len + kWave - 1) / kWave;
+    const int n_steps = (ww->n_tiles + tiles_per_step - 1) / tiles_per_step;
+    const int base = n_steps / n_wg_splits, rem = n_steps % n_wg_splits;
     const int wb = wsplit * base + min(wsplit, rem);
-    ww->tile_end = wb + base + (wsplit < rem ? 1 : 0);
-    ww->tile_begin = wb + wave;
-    ww->tile_step = kDecodeWaves;
-    ww->tile_last = ww->tile_begin +
-                    (ww->tile_begin < ww->tile_end ? (ww->tile_end - 1 - ww->tile_begin) / ww->tile_step : 0) * ww->tile_step;
-    return true;
+    ww->step_end = wb + base + (wsplit < rem ? 1 : 0);
+    ww->step_begin = wb + wave;
+    ww->step_stride = kDecodeWaves;
+    ww->step_last = ww->step_begin + (ww->step_begin < ww->step_end
+                                          ? (ww->step_end - 1 - ww->step_begin) / ww->step_stride
+                                          : 0) * ww->step_stride;
 }
 
-// D2-D4 for one tile: RG scores of this lane's key (without gamma).
+// D2-D4 for one step: RG scores (without gamma) of each of this lane's KPL keys, key k of the lane
+// being in tile k of the step.
 //
 // The rotated queries are wave-uniform and come through scalar loads; directions and norm centroids
-// come from the LDS tables.  Triplets are processed in chunks of 48 query floats with a scheduling
-// barrier in between, so that the scalar registers hold one chunk at a time instead of the whole
-// query.  (Scalar loads return out of order, so each chunk costs one full wait on the scalar and LDS
-// queues; the other wavefronts of the SIMD cover it.  Prefetching a chunk ahead was measured slower.)
-template <class P, int RG>
-__device__ __forceinline__ void tile_scores(const uint32_t (&w)[P::NWORDS], const float *__restrict__ qg,
-                                            const DecodeTables<P> &tb, int lane, float (&s)[RG]) {
-    constexpr int CT = 16 / RG;
+// come from the LDS tables.  The kernel runs one wavefront per SIMD, so nothing else hides the latency
+// of those loads: the triplets are processed in chunks of 24 query floats, software pipelined by one
+// chunk.  At the top of chunk c an explicit wait makes the inputs of chunk c (requested one chunk
+// earlier) complete, then the inputs of chunk c + 1 are requested (unpack, table reads, scalar query
+// loads into the other half of a double buffer), then chunk c is computed.  The explicit wait comes
+// before the new requests because scalar loads return out of order: any later wait on that queue
+// would have to drain it completely, the new requests included.
+template <class P, int RG, int KPL>
+__device__ __forceinline__ void tile_scores(const uint32_t (&w)[KPL][P::NWORDS], const float *__restrict__ qg,
+                                            const DecodeTables<P> &tb, int lane, float (&s)[KPL][RG]) {
+    constexpr int CT = 8 / RG;                       // triplets per chunk
     constexpr int NCHUNK = (P::NTRI + CT - 1) / CT;
+    constexpr int QC = CT * 3 * RG;                  // query floats per chunk
 #pragma unroll
-    for (int r = 0; r < RG; ++r) s[r] = 0.0f;
-    float rgv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-    static_for<0, NCHUNK>([&](auto cc) {
-        constexpr int c0 = decltype(cc)::value * CT;
+    for (int k = 0; k < KPL; ++k)
+#pragma unroll
+        for (int r = 0; r < RG; ++r) s[k][r] = 0.0f;
+    float rgv[KPL][4];                               // the norm centroids of the group last looked up
+#pragma unroll
+    for (int k = 0; k < KPL; ++k)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) rgv[k][e] = 0.0f;
+    float qv[2][QC];
+    float4 nv[2][CT][KPL];
+    float rv[2][CT][KPL];
+
+    auto request = [&](auto cc) __attribute__((always_inline)) {
+        constexpr int ci = decltype(cc)::value;
+        constexpr int c0 = ci * CT;
         constexpr int cn = (P::NTRI - c0) < CT ? (P::NTRI - c0) : CT;
-        float qv[cn * 3 * RG];
+        constexpr int buf = ci & 1;
 #pragma unroll
-        for (int k = 0; k < cn * 3 * RG; ++k) qv[k] = qg[c0 * 3 * RG + k];
+        for (int e = 0; e < cn * 3 * RG; ++e) qv[buf][e] = qg[c0 * 3 * RG + e];
         static_for<0, cn>([&](auto tt) {
             constexpr int t = decltype(tt)::value;
             constexpr int i = c0 + t;
@@ -217,31 +281,83 @@ __device__ __forceinline__ void tile_scores(const uint32_t (&w)[P::NWORDS], cons
             constexpr int bd = P::bdir(i);
             using RT = RhoTable<bn>;
             using DT = DirTable<bd>;
-            if constexpr (ii % RT::NTG == 0) {
-                constexpr int gbit = (c ? P::NRM1_BIT : P::NRM0_BIT) + ii * bn;
-                // the streams are padded to whole bytes, a whole number of groups; the last group may
-                // reach past the class's triplets, never past its stream
-                const uint32_t gi = field_clamped<gbit, RT::BITS, P::NWORDS>(w);
-                const float *entry = (c ? tb.rho1 : tb.rho0) + (gi * RT::REP + (lane & (RT::REP - 1))) * RT::NTG;
-                if constexpr (RT::NTG == 4) {
-                    const float4 e = *reinterpret_cast<const float4 *>(entry);
-                    rgv[0] = e.x; rgv[1] = e.y; rgv[2] = e.z; rgv[3] = e.w;
+            static_for<0, KPL>([&](auto kk) {
+                constexpr int k = decltype(kk)::value;
+                const uint32_t code = field<P::dir_bit(i), 2 * bd>(w[k]);
+                if constexpr (joint_codes(bd, bn)) {
+                    using JT = JointTable<bd, bn>;
+                    static_assert(JT::REP == 1, "byte offsets below assume one copy of the table");
+                    // norm code by bit-field extract, then shift-and-or with the direction part: one
+                    // instruction each (written out: the compiler's own choice takes four per triplet)
+                    constexpr int nb = P::nrm_bit(i);
+                    uint32_t off;
+                    if constexpr ((nb & 31) + bn <= 32) {
+                        uint32_t nrm;
+                        asm("v_bfe_u32 %0, %1, %2, %3" : "=v"(nrm) : "v"(w[k][nb >> 5]), "n"(nb & 31), "n"(bn));
+                        asm("v_lshl_or_b32 %0, %1, %2, %3" : "=v"(off) : "v"(nrm), "n"(4 + 2 * bd), "v"(code << 4));
+                    } else {
+                        off = (field<nb, bn>(w[k]) << (4 + 2 * bd)) | (code << 4);
+                    }
+                    nv[buf][t][k] = *reinterpret_cast<const float4 *>(
+                        reinterpret_cast<const char *>(c ? tb.dir1 : tb.dir0) + off);
+                    rv[buf][t][k] = 1.0f;
                 } else {
-                    const float2 e = *reinterpret_cast<const float2 *>(entry);
-                    rgv[0] = e.x; rgv[1] = e.y;
+                    if constexpr (ii % RT::NTG == 0) {
+                        constexpr int gbit = (c ? P::NRM1_BIT : P::NRM0_BIT) + ii * bn;
+                        // the streams are padded to whole bytes, a whole number of groups; the last group
+                        // may reach past the class's triplets, never past its stream
+                        const uint32_t gi = field_clamped<gbit, RT::BITS, P::NWORDS>(w[k]);
+                        const float *entry =
+                            (c ? tb.rho1 : tb.rho0) + (gi * RT::REP + (lane & (RT::REP - 1))) * RT::NTG;
+                        if constexpr (RT::NTG == 4) {
+                            const float4 e = *reinterpret_cast<const float4 *>(entry);
+                            rgv[k][0] = e.x; rgv[k][1] = e.y; rgv[k][2] = e.z; rgv[k][3] = e.w;
+                        } else {
+                            const float2 e = *reinterpret_cast<const float2 *>(entry);
+                            rgv[k][0] = e.x; rgv[k][1] = e.y;
+                        }
+                    }
+                    nv[buf][t][k] = (c ? tb.dir1 : tb.dir0)[code * DT::REP + (lane & (DT::REP - 1))];
+                    rv[buf][t][k] = rgv[k][ii % RT::NTG];
                 }
-            }
-            const uint32_t code = field<P::dir_bit(i), 2 * bd>(w);
-            const float4 n = (c ? tb.dir1 : tb.dir0)[code * DT::REP + (lane & (DT::REP - 1))];
-            const float rho = rgv[ii % RT::NTG];
-            const float tx = rho * n.x, ty = rho * n.y, tz = rho * n.z;
-#pragma unroll
-            for (int r = 0; r < RG; ++r) {
-                s[r] = fmaf(qv[(3 * t) * RG + r], tx, s[r]);
-                s[r] = fmaf(qv[(3 * t + 1) * RG + r], ty, s[r]);
-                s[r] = fmaf(qv[(3 * t + 2) * RG + r], tz, s[r]);  // rotated queries are zero past d
-            }
+            });
         });
+    };
+
+    request(std::integral_constant<int, 0>{});
+    static_for<0, NCHUNK>([&](auto cc) {
+        constexpr int ci = decltype(cc)::value;
+        constexpr int c0 = ci * CT;
+        constexpr int cn = (P::NTRI - c0) < CT ? (P::NTRI - c0) : CT;
+        constexpr int buf = ci & 1;
+        __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0): the inputs of this chunk have arrived
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (ci + 1 < NCHUNK) request(std::integral_constant<int, ci + 1>{});
+        static_for<0, cn>([&](auto tt) {
+            constexpr int t = decltype(tt)::value;
+            static_for<0, KPL>([&](auto kk) {
+                constexpr int k = decltype(kk)::value;
+                const float4 n = nv[buf][t][k];
+                float tx = n.x, ty = n.y, tz = n.z;
+                if constexpr (!joint_codes(P::bdir(c0 + t), P::bnrm(c0 + t))) {
+                    const float rho = rv[buf][t][k];
+                    tx *= rho; ty *= rho; tz *= rho;
+                }
+#pragma unroll
+                for (int r = 0; r < RG; ++r) {
+                    s[k][r] = fmaf(qv[buf][(3 * t) * RG + r], tx, s[k][r]);
+                    s[k][r] = fmaf(qv[buf][(3 * t + 1) * RG + r], ty, s[k][r]);
+                    s[k][r] = fmaf(qv[buf][(3 * t + 2) * RG + r], tz, s[k][r]);  // rotated queries are zero past d
+                }
+            });
+        });
+        // The accumulators pass through an empty volatile asm at the end of each chunk: instruction
+        // selection orders side-effect-free arithmetic freely within the block, and without this anchor it
+        // may defer every multiply-add past the last chunk, keeping the whole query live (spilled).
+#pragma unroll
+        for (int k = 0; k < KPL; ++k)
+#pragma unroll
+            for (int r = 0; r < RG; ++r) asm volatile("" : "+v"(s[k][r]));
         __builtin_amdgcn_sched_barrier(0);
     });
 }
@@ -275,35 +391,57 @@ __device__ __forceinline__ void store_scores(const DecodeShape &shp, const WaveW
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
-constexpr int kPRow = 72;  // bf16 per probability row in LDS: 64 keys + 8 pad (144-byte stride)
+// Keys per lane and step of the bf16-value kernel.  The kernel runs one wavefront per SIMD (all 512
+// vector registers of a lane): measured faster than two wavefronts with half the registers each,
+// because a step's values (16 KB per 64 keys at d = 128) stay in flight in registers during the whole
+// score phase without spilling.  Up to d = 128 a lane carries two keys, so that every scalar query
+// chunk, every wave-wide maximum and every accumulator rescale serves 128 keys.
+template <int D>
+#ifndef OCTO_KPL
+#define OCTO_KPL 2
+#endif
+#ifndef OCTO_VAHEAD
+#define OCTO_VAHEAD(D) 0
+#endif
+constexpr int decode_keys_per_lane() { return D <= 128 ? OCTO_KPL : 1; }
+// Whether the values of a step are requested a whole step ahead (a second value buffer in registers).
+template <int D>
+constexpr bool decode_values_ahead() { return OCTO_VAHEAD(D); }
 
-template <class P>
+template <int KPL>
+constexpr int prob_row() { return KPL * kWave + 8; }  // bf16 per probability row in LDS: keys + 8 pad
+
+template <class P, int KPL>
 struct DecodeSmemMfma {
     DecodeTables<P> tb;
-    uint16_t pbuf[kDecodeWaves][16][kPRow];
+    uint16_t pbuf[kDecodeWaves][16][prob_row<KPL>()];
 };
 
 template <class P, int RG>
-__global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_per_eu(2))) void decode_kernel_mfma(
+__global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) void decode_kernel_mfma(
     DeviceBooks books, DecodeShape shp, const float *__restrict__ q_rot, const uint4 *__restrict__ cache,
     const uint32_t *__restrict__ v, const int32_t *__restrict__ seq_lens, float *__restrict__ part_ml,
     float *__restrict__ part_acc, float *__restrict__ scores_out) {
     constexpr int D = P::D;
+    constexpr int KPL = decode_keys_per_lane<D>();
+    constexpr bool VAHEAD = decode_values_ahead<D>();
+    constexpr int KS = 2 * KPL;            // k-steps of 32 keys per step
     constexpr int CPL = D / 16;            // channels per lane chunk = N-blocks
     constexpr int CW = CPL / 2;            // 32-bit words per chunk
     constexpr int RP = RG < 4 ? 4 : RG;    // probability rows padded to a multiple of 4
     constexpr int ROWB = D * 2;            // bytes per value row
     constexpr int TILEB = P::GRANULES * kWave * 16;  // bytes per cache tile
-    extern __shared__ __align__(16) unsigned char smem_raw[];
-    DecodeSmemMfma<P> &sm = *reinterpret_cast<DecodeSmemMfma<P> *>(smem_raw);
+    constexpr int PROW = prob_row<KPL>();
+    // static, so that table addresses are compile-time constants that fold into the LDS instructions
+    __shared__ DecodeSmemMfma<P, KPL> sm;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
-    for (int e = tid; e < kDecodeWaves * 16 * kPRow; e += kDecodeWaves * kWave) (&sm.pbuf[0][0][0])[e] = 0;
+    for (int e = tid; e < kDecodeWaves * 16 * PROW; e += kDecodeWaves * kWave) (&sm.pbuf[0][0][0])[e] = 0;
     build_tables<P>(sm.tb, books, tid, kDecodeWaves * kWave);
 
     WaveWork ww;
-    if (!wave_work(shp, seq_lens, wave, &ww)) return;
+    wave_work(shp, seq_lens, wave, KPL, &ww);
     const float *qg = q_rot + ww.group_id * (P::QS * RG);
     const int n16 = lane & 15, g4 = lane >> 4;
     // Addresses are a wave-uniform base (scalar registers) plus a small per-lane byte offset.
@@ -340,6 +478,12 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
             }
         }
     };
+    // The records of a step; a tile past the sequence's last one is replaced by the last one (its keys
+    // are masked out by position), so that nothing outside the tiles that hold tokens is read.
+    auto load_records = [&](int step, uint32_t (&w)[KPL][P::NWORDS]) {
+#pragma unroll
+        for (int k = 0; k < KPL; ++k) load_record(min(step * KPL + k, ww.n_tiles - 1), w[k]);
+    };
     auto load_chunk = [&](const char *src, uint32_t (&dst)[CW]) {
         if constexpr (CW == 2) {
             const uint2 x = *reinterpret_cast<const uint2 *>(src);
@@ -360,59 +504,80 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
 #pragma unroll
     for (int c = 0; c < CPL; ++c) acc[c] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
 
-    // Values of tile `tile` for this lane: 8 keys x CPL channels per k-step.  Rows past the end of a
-    // ragged last tile are replaced by the last valid row; their probabilities are zero, and no memory
-    // outside [0, len) is read.
-    auto load_values = [&](int tile, uint32_t (&vr)[2][8][CW]) {
-        const int t0 = tile * kWave;
-        const int n_valid = min(kWave, ww.len - t0);
-        const char *vtile = v_pair + static_cast<int64_t>(t0) * ROWB;
-        const int row_limit = (n_valid - 1 - g4) * ROWB;  // min(c, limit) + g4 == min(c + g4, n_valid - 1)
+    // Values of a step for this lane: 8 keys x CPL channels per k-step.  Rows past the end of a ragged
+    // last step are replaced by the last valid row; their probabilities are zero, and no memory outside
+    // [0, len) is read.  With `real` false (there is no such step) every lane reads the first 16 bytes of
+    // step `step` instead: the loads are still issued, so that the code has no branch around them, but
+    // they move one cache line.
+    auto load_values = [&](int step, bool real, uint32_t (&vr)[KS][8][CW]) {
+        const int t0 = step * (KPL * kWave);
+        const int n_valid = min(KPL * kWave, ww.len - t0);
+        const char *vstep = v_pair + static_cast<int64_t>(t0) * ROWB;
+        const int row_limit = real ? (n_valid - 1 - g4) * ROWB : -static_cast<int>(g4 * ROWB);
+        const int lane_off = real ? static_cast<int>(v_lane) : static_cast<int>(g4 * ROWB);
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
+        for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
             for (int j = 0; j < 8; ++j)
-                load_chunk(vtile + static_cast<uint32_t>(min((32 * ks + 4 * j) * ROWB, row_limit) +
-                                                         static_cast<int>(v_lane)), vr[ks][j]);
+                load_chunk(vstep + static_cast<uint32_t>(min((32 * ks + 4 * j) * ROWB, row_limit) + lane_off),
+                           vr[ks][j]);
     };
-    // One tile.  Its values are requested first, so that they are in flight during the score phase;
-    // the record of the wave's next tile is requested right after and is used one call later.  The tile
-    // loop below is unrolled by two with the two record buffers swapping roles, so that no register
-    // copies (and no full memory wait in front of them) carry the prefetched record over.
-    auto process_tile = [&](int tile, const uint32_t (&w)[P::NWORDS], uint32_t (&w_next)[P::NWORDS])
+    // One step.  The values and the records of the wave's next step are requested first and are used
+    // one call later: they are in flight during this step's score phase and its P.V, so that the
+    // wavefront always has a step's worth of loads outstanding.  The step loop below is unrolled by two
+    // with the two record buffers and the two value buffers swapping roles, so that no register copies
+    // (and no full memory wait in front of them) carry the prefetched data over.
+    auto process_step = [&](int step, const uint32_t (&w)[KPL][P::NWORDS], uint32_t (&w_next)[KPL][P::NWORDS],
+                            const uint32_t (&vr_ahead)[KS][8][CW], uint32_t (&vr_next)[KS][8][CW])
                             __attribute__((always_inline)) {
-        const int t0 = tile * kWave;
-        const int n_valid = min(kWave, ww.len - t0);
-        uint32_t vr[2][8][CW];
-        load_values(tile, vr);
-        // always issued (the wave's last tile re-reads itself): a branch here would make the compiler wait
-        // for every outstanding load before the scores instead of only for this tile's record
-        load_record(min(tile + ww.tile_step, ww.tile_last), w_next);
+        const int t0 = step * (KPL * kWave);
+        const int n_valid = min(KPL * kWave, ww.len - t0);
+        // always issued (after the wave's last step: one cache line of values, the last step's records
+        // again): a branch here would make the compiler wait for every outstanding load first
+        const bool has_next = step + ww.step_stride < ww.step_end;
+        if constexpr (VAHEAD) {
+            load_values(has_next ? step + ww.step_stride : step, has_next, vr_next);
+        } else {
+            load_values(step, true, vr_next);
+        }
+        load_records(min(step + ww.step_stride, ww.step_last), w_next);
+        const uint32_t (&vr)[KS][8][CW] = VAHEAD ? vr_ahead : vr_next;
         // D2-D4: scores (queries carry the softmax scale already).  The query offset (always 0) is
-        // laundered per tile: otherwise the loop-invariant scalar loads of the whole query are hoisted
-        // out of the tile loop and hundreds of scalar registers spill.
-        float s[RG];
+        // laundered per step: otherwise the loop-invariant scalar loads of the whole query are hoisted
+        // out of the step loop and hundreds of scalar registers spill.
+        float s[KPL][RG];
         int q_off = 0;
         asm volatile("" : "+s"(q_off));
-        tile_scores<P, RG>(w, qg + q_off, sm.tb, lane, s);
-        const float gamma = __uint_as_float(w[0]);
-        const bool valid = lane < n_valid;
+        tile_scores<P, RG, KPL>(w, qg + q_off, sm.tb, lane, s);
 #pragma unroll
-        for (int r = 0; r < RG; ++r) s[r] = valid ? s[r] * gamma : -INFINITY;
-        if (scores_out != nullptr && valid) store_scores<RG>(shp, ww, scores_out, t0 + lane, s);
+        for (int k = 0; k < KPL; ++k) {
+            const float gamma = __uint_as_float(w[k][0]);
+            const bool valid = k * kWave + lane < n_valid;
+#pragma unroll
+            for (int r = 0; r < RG; ++r) s[k][r] = valid ? s[k][r] * gamma : -INFINITY;
+            if (scores_out != nullptr && valid) store_scores<RG>(shp, ww, scores_out, t0 + k * kWave + lane, s[k]);
+        }
         // D5: online softmax, one running maximum per row for the whole wave
         float alpha[RG];
 #pragma unroll
         for (int r = 0; r < RG; ++r) {
-            const float m_new = fmaxf(m_run[r], wave_max(s[r]));
+            float mx = s[0][r];
+#pragma unroll
+            for (int k = 1; k < KPL; ++k) mx = fmaxf(mx, s[k][r]);
+            const float m_new = fmaxf(m_run[r], wave_max(mx));
             alpha[r] = exp2f((m_run[r] - m_new) * kLog2e);
             m_run[r] = m_new;
-            const float p = exp2f((s[r] - m_new) * kLog2e);
-            l_lane[r] = fmaf(l_lane[r], alpha[r], p);
-            const uint32_t pb = __float_as_uint(p);
-            const float lo = p - __uint_as_float(pb & 0xffff0000u);
-            sm.pbuf[wave][r][ppos] = static_cast<uint16_t>(pb >> 16);
-            sm.pbuf[wave][RP + r][ppos] = static_cast<uint16_t>(__float_as_uint(lo) >> 16);
+            float psum = 0.0f;
+#pragma unroll
+            for (int k = 0; k < KPL; ++k) {
+                const float p = exp2f((s[k][r] - m_new) * kLog2e);
+                psum += p;
+                const uint32_t pb = __float_as_uint(p);
+                const float lo = p - __uint_as_float(pb & 0xffff0000u);
+                sm.pbuf[wave][r][k * kWave + ppos] = static_cast<uint16_t>(pb >> 16);
+                sm.pbuf[wave][RP + r][k * kWave + ppos] = static_cast<uint16_t>(__float_as_uint(lo) >> 16);
+            }
+            l_lane[r] = fmaf(l_lane[r], alpha[r], psum);
         }
         // accumulator rows of this lane: m = 4 * g4 + i, probability row r = m % RP
 #pragma unroll
@@ -430,7 +595,7 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
         __builtin_amdgcn_wave_barrier();
         // D6: P.V
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
+        for (int ks = 0; ks < KS; ++ks) {
             union { uint4 u; bf16x8_t b; } pa;
             pa.u = *reinterpret_cast<const uint4 *>(&sm.pbuf[wave][n16][32 * ks + 8 * g4]);
 #pragma unroll
@@ -446,11 +611,15 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         __builtin_amdgcn_wave_barrier();
     };
-    uint32_t w_a[P::NWORDS], w_b[P::NWORDS];
-    if (ww.tile_begin < ww.tile_end) load_record(ww.tile_begin, w_a);
-    for (int tile = ww.tile_begin; tile < ww.tile_end; tile += 2 * ww.tile_step) {
-        process_tile(tile, w_a, w_b);
-        if (tile + ww.tile_step < ww.tile_end) process_tile(tile + ww.tile_step, w_b, w_a);
+    uint32_t w_a[KPL][P::NWORDS], w_b[KPL][P::NWORDS];
+    uint32_t v_a[KS][8][CW], v_b[KS][8][CW];
+    if (ww.step_begin < ww.step_end) {
+        load_records(ww.step_begin, w_a);
+        if constexpr (VAHEAD) load_values(ww.step_begin, true, v_a);
+    }
+    for (int step = ww.step_begin; step < ww.step_end; step += 2 * ww.step_stride) {
+        process_step(step, w_a, w_b, v_a, v_b);
+        if (step + ww.step_stride < ww.step_end) process_step(step + ww.step_stride, w_b, w_a, v_b, v_a);
     }
 
     // D7: add the hi and lo partial results (lane groups RP/4 apart) and emit the wave's partial
@@ -491,6 +660,7 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) void decode_kernel_valu(
     constexpr int D = P::D;
     constexpr int LPR = D / 8;          // lanes per value row (8 channels per lane)
     constexpr int KPL = kWave / LPR;    // value rows per wave-wide load
+    constexpr int TPS = decode_keys_per_lane<D>();  // tiles per step of the split sizing
     extern __shared__ __align__(16) unsigned char smem_raw[];
     DecodeSmemValu<P, RG> &sm = *reinterpret_cast<DecodeSmemValu<P, RG> *>(smem_raw);
 
@@ -498,7 +668,7 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) void decode_kernel_valu(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     build_tables<P>(sm.tb, books, tid, kDecodeWaves * kWave);
     WaveWork ww;
-    if (!wave_work(shp, seq_lens, wave, &ww)) return;
+    wave_work(shp, seq_lens, wave, TPS, &ww);
     const float *qg = q_rot + ww.group_id * (P::QS * RG);
     const uint4 *region = cache + ww.pair * (shp.t_capacity * P::GRANULES);
     const int64_t v_row0 = ww.pair * shp.t_capacity;
@@ -513,20 +683,25 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) void decode_kernel_valu(
     }
     const int rl = lane % LPR, ko = lane / LPR;
 
-    for (int tile = ww.tile_begin; tile < ww.tile_end; tile += ww.tile_step) {
+    // the splits are sized in steps of TPS tiles (shared with the bf16-value kernel); here a step is
+    // simply TPS tiles one after the other
+    for (int step = ww.step_begin; step < ww.step_end; step += ww.step_stride)
+    for (int tile = step * TPS; tile < min((step + 1) * TPS, ww.n_tiles); ++tile) {
         const int t0 = tile * kWave;
         const int n_valid = min(kWave, ww.len - t0);
-        uint32_t w[P::NWORDS];
+        uint32_t w1[1][P::NWORDS];
+        uint32_t (&w)[P::NWORDS] = w1[0];
         const uint4 *src = region + static_cast<int64_t>(tile) * (P::GRANULES * kWave) + lane;
 #pragma unroll
         for (int g = 0; g < P::GRANULES; ++g) {
             const uint4 x = src[g * kWave];
             w[4 * g] = x.x; w[4 * g + 1] = x.y; w[4 * g + 2] = x.z; w[4 * g + 3] = x.w;
         }
-        float s[RG];
+        float s1[1][RG];
+        float (&s)[RG] = s1[0];
         int q_off = 0;
         asm volatile("" : "+s"(q_off));
-        tile_scores<P, RG>(w, qg + q_off, sm.tb, lane, s);
+        tile_scores<P, RG, 1>(w1, qg + q_off, sm.tb, lane, s1);
         const float gamma = __uint_as_float(w[0]);
         const bool valid = lane < n_valid;
 #pragma unroll
@@ -661,11 +836,7 @@ int launch_decode_rg(const octopus_codebooks_t &cb, const DecodeShape &s, const 
     const dim3 block(kDecodeWaves * kWave);
     hipError_t err;
     if (v_dtype == OCTOPUS_DTYPE_BF16) {
-        const size_t smem = sizeof(DecodeSmemMfma<P>);
-        err = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel_mfma<P, RG>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem));
-        if (err != hipSuccess) return static_cast<int>(err);
-        hipLaunchKernelGGL((decode_kernel_mfma<P, RG>), grid, block, smem, stream, books, s, q_rot,
+        hipLaunchKernelGGL((decode_kernel_mfma<P, RG>), grid, block, 0, stream, books, s, q_rot,
                            static_cast<const uint4 *>(cache), static_cast<const uint32_t *>(v), seq_lens, part_ml,
                            part_acc, scores_out);
     } else {

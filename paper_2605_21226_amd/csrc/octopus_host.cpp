@@ -220,7 +220,6 @@ bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 
 DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads,
                               int32_t n_q, int64_t max_len, int64_t t_capacity) {
-    (void)plan;
     DecodeShape s{};
     s.n_seq = n_seq;
     s.n_q_heads = n_q_heads;
@@ -234,16 +233,18 @@ DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t
     while (s.rows_per_pass < s.rows_per_kv && s.rows_per_pass < 8) s.rows_per_pass *= 2;
     s.n_row_groups = (s.rows_per_kv + s.rows_per_pass - 1) / s.rows_per_pass;
     s.t_capacity = t_capacity;
-    // Split-K sizing: one wavefront per split.  The chip holds 256 compute units x 8 wavefronts of the
-    // decode kernel at once; the tiles of each (sequence, KV head, row group) are divided over as many
-    // splits as fill those slots once, so that all wavefronts start together and end together.
+    // Split-K sizing: one wavefront per split.  The decode kernel runs one wavefront per SIMD, 256
+    // compute units x 4 at once; the steps (128 keys up to d = 128, 64 keys at d = 256) of each
+    // (sequence, KV head, row group) are divided over as many splits as fill those slots once, so that
+    // all wavefronts start together and end together.
     const int64_t len = std::max<int64_t>(max_len, 1);
     const int64_t groups = static_cast<int64_t>(n_seq) * n_kv_heads * s.n_row_groups;
-    const int64_t max_tiles = (len + OCTOPUS_TILE - 1) / OCTOPUS_TILE;
-    const int64_t slots = 256 * 8;
+    const int64_t step_keys = OCTOPUS_TILE * (plan.head_dim <= 128 ? 2 : 1);
+    const int64_t max_steps = (len + step_keys - 1) / step_keys;
+    const int64_t slots = 256 * 4;
     // workgroups of 4 wavefronts: splits come in fours
     int64_t want = (slots / 4 + groups / 2) / groups;
-    want = std::max<int64_t>(1, std::min<int64_t>(want, (max_tiles + 3) / 4));
+    want = std::max<int64_t>(1, std::min<int64_t>(want, (max_steps + 3) / 4));
     s.n_splits = static_cast<int32_t>(4 * want);
     s.max_len = static_cast<int32_t>(max_len);
     return s;
