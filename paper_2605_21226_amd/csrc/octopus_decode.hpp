@@ -88,9 +88,10 @@ __global__ __launch_bounds__(kWave) void rotate_queries_kernel(const void *__res
 // Two kernels differ in P.V only: decode_kernel_mfma (bf16 values) feeds the probabilities to the
 // matrix cores; decode_kernel_valu (fp32 values) multiplies on the vector ALUs.
 
-// Replication of a table of `bytes` bytes: up to 8 copies within a 32 KB budget.
+// Replication of a table of `bytes` bytes: up to 8 copies within a 64 KB budget (one workgroup runs
+// per compute unit and may use most of its 160 KB of LDS).
 constexpr int table_rep(int bytes) {
-    return bytes * 8 <= 32768 ? 8 : (bytes * 4 <= 32768 ? 4 : (bytes * 2 <= 32768 ? 2 : 1));
+    return bytes * 8 <= 65536 ? 8 : (bytes * 4 <= 65536 ? 4 : (bytes * 2 <= 65536 ? 2 : 1));
 }
 
 template <int BD>
@@ -138,15 +139,21 @@ __device__ __forceinline__ void build_rho_table(float *table, const float *c_rho
 // norm centroids come from the two tables above.
 constexpr bool joint_codes(int bd, int bn) { return 2 * bd + bn <= 10; }
 
-// The table is not replicated: the byte offset of an entry is then (direction code << 4) | (norm code
-// << (4 + 2 BD)), three instructions per triplet, and the bank conflicts of the lookups are hidden by
-// requesting them a chunk ahead.
+// Layout [direction code][norm code][copy]: the byte offset of the entry lane l reads is
+//   (direction code << CS) | (norm code << NS) | ((l % REP) << 4),
+// the copies making neighbouring lanes hit different banks.  For 4 + 4 + 2 bits with 4 copies CS is 8
+// and the direction code is a whole byte of the record: one byte permute puts it in place together with
+// the lane part, a bit-field extract and a shift-or add the norm code -- three instructions per triplet.
 template <int BD, int BN>
 struct JointTable {
     static constexpr int BITS = 2 * BD + BN;
     static constexpr int ENTRIES = 1 << BITS;
-    static constexpr int REP = 1;
+    static constexpr int REP = table_rep(ENTRIES * 16);
+    static constexpr int LOG_REP = REP == 8 ? 3 : (REP == 4 ? 2 : (REP == 2 ? 1 : 0));
+    static constexpr int NS = 4 + LOG_REP;
+    static constexpr int CS = NS + BN;
     static constexpr int FLOAT4S = ENTRIES * REP;
+    static constexpr bool BYTE_CODES = (2 * BD == 8) && (CS == 8);
 };
 
 template <int BD, int BN>
@@ -154,11 +161,13 @@ __device__ __forceinline__ void build_joint_table(float4 *table, const float *c_
                                                   int nthreads) {
     using T = JointTable<BD, BN>;
     constexpr int K = 1 << BD;
-    for (int e = tid; e < T::FLOAT4S; e += nthreads) {
-        const int code = e / T::REP;
-        const float4 n = oct_decode(c_xi[code & (K - 1)], c_xi[(code >> BD) & (K - 1)]);
-        const float rho = c_rho[code >> (2 * BD)];
-        table[e] = make_float4(rho * n.x, rho * n.y, rho * n.z, 0.0f);
+    for (int e = tid; e < T::ENTRIES; e += nthreads) {
+        const int dir = e >> BN, nrm = e & ((1 << BN) - 1);
+        const float4 n = oct_decode(c_xi[dir & (K - 1)], c_xi[dir >> BD]);
+        const float rho = c_rho[nrm];
+        const float4 val = make_float4(rho * n.x, rho * n.y, rho * n.z, 0.0f);
+#pragma unroll
+        for (int r = 0; r < T::REP; ++r) table[e * T::REP + r] = val;
     }
 }
 
@@ -246,6 +255,9 @@ __device__ __forceinline__ void wave_work(const DecodeShape &shp, const int32_t 
 // loads into the other half of a double buffer), then chunk c is computed.  The explicit wait comes
 // before the new requests because scalar loads return out of order: any later wait on that queue
 // would have to drain it completely, the new requests included.
+template <int REP>
+__device__ __forceinline__ uint32_t lane_part(int lane) { return (static_cast<uint32_t>(lane) & (REP - 1)) << 4; }
+
 template <class P, int RG, int KPL>
 __device__ __forceinline__ void tile_scores(const uint32_t (&w)[KPL][P::NWORDS], const float *__restrict__ qg,
                                             const DecodeTables<P> &tb, int lane, float (&s)[KPL][RG]) {
@@ -286,17 +298,17 @@ __device__ __forceinline__ void tile_scores(const uint32_t (&w)[KPL][P::NWORDS],
                 const uint32_t code = field<P::dir_bit(i), 2 * bd>(w[k]);
                 if constexpr (joint_codes(bd, bn)) {
                     using JT = JointTable<bd, bn>;
-                    static_assert(JT::REP == 1, "byte offsets below assume one copy of the table");
-                    // norm code by bit-field extract, then shift-and-or with the direction part: one
-                    // instruction each (written out: the compiler's own choice takes four per triplet)
-                    constexpr int nb = P::nrm_bit(i);
+                    constexpr int nb = P::nrm_bit(i), db = P::dir_bit(i);
                     uint32_t off;
-                    if constexpr ((nb & 31) + bn <= 32) {
+                    if constexpr (JT::BYTE_CODES && (nb & 31) + bn <= 32) {
+                        // written out: the compiler's own choice takes four or five instructions
+                        const uint32_t dl = __builtin_amdgcn_perm(w[k][db >> 5], lane_part<JT::REP>(lane),
+                                                                  0x0c0c0000u | ((4u + ((db & 31) >> 3)) << 8));
                         uint32_t nrm;
                         asm("v_bfe_u32 %0, %1, %2, %3" : "=v"(nrm) : "v"(w[k][nb >> 5]), "n"(nb & 31), "n"(bn));
-                        asm("v_lshl_or_b32 %0, %1, %2, %3" : "=v"(off) : "v"(nrm), "n"(4 + 2 * bd), "v"(code << 4));
+                        asm("v_lshl_or_b32 %0, %1, %2, %3" : "=v"(off) : "v"(nrm), "n"(JT::NS), "v"(dl));
                     } else {
-                        off = (field<nb, bn>(w[k]) << (4 + 2 * bd)) | (code << 4);
+                        off = (code << JT::CS) | (field<nb, bn>(w[k]) << JT::NS) | lane_part<JT::REP>(lane);
                     }
                     nv[buf][t][k] = *reinterpret_cast<const float4 *>(
                         reinterpret_cast<const char *>(c ? tb.dir1 : tb.dir0) + off);
@@ -381,10 +393,13 @@ __device__ __forceinline__ void store_scores(const DecodeShape &shp, const WaveW
 // column l%16 of B, each for the 8 k-slots of lane group l/16, and rows 4*(l/16)..+3 of column l%16
 // of D.  Here M = probability rows, K = keys, N = channels:
 //   * a 64-key tile is two k-steps; k-slot (g, j) of step ks is key 32*ks + 4*j + g, so that one
-//     wave-wide value load (fixed j) reads 4 consecutive value rows;
+//     wave-wide value load (fixed j) reads 4 consecutive value rows (measured faster than 4 rows that
+//     lie 8 apart);
 //   * lane (n, g) loads CPL = d/16 adjacent channels [CPL*n, CPL*n + CPL) of its 8 keys per k-step;
 //     N-block c of the MFMA is the channel set {CPL*n + c}, so B operands are byte permutes of the
 //     loaded registers and values are never converted;
+//   * values come through buffer loads whose descriptor ends at the sequence's last token: rows past
+//     it read as zeros without any address clamping;
 //   * a probability is split into two bf16 numbers, hi = its upper 16 bits and lo = the rest, which
 //     occupy rows r and RP + r of A; the two partial results are added at the end.  The relative
 //     error of hi + lo is below 2^-16.
@@ -397,16 +412,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 // score phase without spilling.  Up to d = 128 a lane carries two keys, so that every scalar query
 // chunk, every wave-wide maximum and every accumulator rescale serves 128 keys.
 template <int D>
-#ifndef OCTO_KPL
-#define OCTO_KPL 2
-#endif
-#ifndef OCTO_VAHEAD
-#define OCTO_VAHEAD(D) 0
-#endif
-constexpr int decode_keys_per_lane() { return D <= 128 ? OCTO_KPL : 1; }
-// Whether the values of a step are requested a whole step ahead (a second value buffer in registers).
-template <int D>
-constexpr bool decode_values_ahead() { return OCTO_VAHEAD(D); }
+constexpr int decode_keys_per_lane() { return D <= 128 ? 2 : 1; }
 
 template <int KPL>
 constexpr int prob_row() { return KPL * kWave + 8; }  // bf16 per probability row in LDS: keys + 8 pad
@@ -417,14 +423,16 @@ struct DecodeSmemMfma {
     uint16_t pbuf[kDecodeWaves][16][prob_row<KPL>()];
 };
 
-template <class P, int RG>
+// SCORES: also store the scaled scores (a second instantiation, so that the usual one carries none of
+// the addressing state of that store through its loop).
+template <class P, int RG, bool SCORES>
 __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) void decode_kernel_mfma(
     DeviceBooks books, DecodeShape shp, const float *__restrict__ q_rot, const uint4 *__restrict__ cache,
     const uint32_t *__restrict__ v, const int32_t *__restrict__ seq_lens, float *__restrict__ part_ml,
     float *__restrict__ part_acc, float *__restrict__ scores_out) {
     constexpr int D = P::D;
     constexpr int KPL = decode_keys_per_lane<D>();
-    constexpr bool VAHEAD = decode_values_ahead<D>();
+    constexpr bool AHEAD = D <= 128;       // request a step's values during the previous step's P.V
     constexpr int KS = 2 * KPL;            // k-steps of 32 keys per step
     constexpr int CPL = D / 16;            // channels per lane chunk = N-blocks
     constexpr int CW = CPL / 2;            // 32-bit words per chunk
@@ -448,7 +456,14 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
     const char *k_region = reinterpret_cast<const char *>(cache) + ww.pair * shp.t_capacity * (P::GRANULES * 16);
     const uint32_t k_lane = lane * 16u;
     const char *v_pair = reinterpret_cast<const char *>(v) + ww.pair * shp.t_capacity * ROWB;
-    const uint32_t v_lane = g4 * ROWB + n16 * (CPL * 2);
+    // Byte offsets of this lane's channels in its rows 32 ks + 4 j + g4: one register per JB values of j,
+    // the others reached by immediate offsets (below 4096).
+    constexpr int JB = 4096 / (4 * ROWB) < 8 ? 4096 / (4 * ROWB) : 8;
+    int v_lane[KS][8 / JB];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+        for (int h = 0; h < 8 / JB; ++h) v_lane[ks][h] = (32 * ks + 4 * JB * h + g4) * ROWB + n16 * (CPL * 2);
     const int ppos = (lane & 32) + 8 * (lane & 3) + ((lane & 31) >> 2);  // slot of key `lane` in a pbuf row
 
     // Only the words that hold record bytes are loaded: a register written by a load but never read
@@ -484,19 +499,6 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
 #pragma unroll
         for (int k = 0; k < KPL; ++k) load_record(min(step * KPL + k, ww.n_tiles - 1), w[k]);
     };
-    auto load_chunk = [&](const char *src, uint32_t (&dst)[CW]) {
-        if constexpr (CW == 2) {
-            const uint2 x = *reinterpret_cast<const uint2 *>(src);
-            dst[0] = x.x; dst[1] = x.y;
-        } else {
-#pragma unroll
-            for (int q4 = 0; q4 < CW / 4; ++q4) {
-                const uint4 x = reinterpret_cast<const uint4 *>(src)[q4];
-                dst[4 * q4] = x.x; dst[4 * q4 + 1] = x.y; dst[4 * q4 + 2] = x.z; dst[4 * q4 + 3] = x.w;
-            }
-        }
-    };
-
     float m_run[RG], l_lane[RG];
     f32x4_t acc[CPL];
 #pragma unroll
@@ -504,44 +506,57 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
 #pragma unroll
     for (int c = 0; c < CPL; ++c) acc[c] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
 
-    // Values of a step for this lane: 8 keys x CPL channels per k-step.  Rows past the end of a ragged
-    // last step are replaced by the last valid row; their probabilities are zero, and no memory outside
-    // [0, len) is read.  With `real` false (there is no such step) every lane reads the first 16 bytes of
-    // step `step` instead: the loads are still issued, so that the code has no branch around them, but
-    // they move one cache line.
-    auto load_values = [&](int step, bool real, uint32_t (&vr)[KS][8][CW]) {
+    // Values come through a buffer descriptor that covers a step's rows up to the sequence's last token
+    // (rows past it read as zero; their probabilities are zero too); the descriptor of a step that does
+    // not exist is empty, its loads move nothing.
+    auto values_of = [&](int step, bool exists) {
         const int t0 = step * (KPL * kWave);
-        const int n_valid = min(KPL * kWave, ww.len - t0);
-        const char *vstep = v_pair + static_cast<int64_t>(t0) * ROWB;
-        const int row_limit = real ? (n_valid - 1 - g4) * ROWB : -static_cast<int>(g4 * ROWB);
-        const int lane_off = real ? static_cast<int>(v_lane) : static_cast<int>(g4 * ROWB);
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                load_chunk(vstep + static_cast<uint32_t>(min((32 * ks + 4 * j) * ROWB, row_limit) + lane_off),
-                           vr[ks][j]);
+        const int n_valid = exists ? min(KPL * kWave, ww.len - t0) : 0;
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(v_pair + static_cast<int64_t>(t0) * ROWB), 0,
+                                                 n_valid * ROWB, 0x00020000);
     };
-    // One step.  The values and the records of the wave's next step are requested first and are used
-    // one call later: they are in flight during this step's score phase and its P.V, so that the
-    // wavefront always has a step's worth of loads outstanding.  The step loop below is unrolled by two
-    // with the two record buffers and the two value buffers swapping roles, so that no register copies
-    // (and no full memory wait in front of them) carry the prefetched data over.
-    auto process_step = [&](int step, const uint32_t (&w)[KPL][P::NWORDS], uint32_t (&w_next)[KPL][P::NWORDS],
-                            const uint32_t (&vr_ahead)[KS][8][CW], uint32_t (&vr_next)[KS][8][CW])
+    // this lane's part of k-step ks: 8 rows x CPL channels
+    auto load_values = [&](__amdgpu_buffer_rsrc_t rsrc, int ks, uint32_t (&vk)[8][CW]) {
+        typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+        typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if constexpr (CW == 2) {
+                const u32x2_t x =
+                    __builtin_amdgcn_raw_buffer_load_b64(rsrc, v_lane[ks][j / JB] + (j % JB) * (4 * ROWB), 0, 0);
+                vk[j][0] = x.x; vk[j][1] = x.y;
+            } else {
+#pragma unroll
+                for (int q4 = 0; q4 < CW / 4; ++q4) {
+                    const u32x4_t x = __builtin_amdgcn_raw_buffer_load_b128(
+                        rsrc, v_lane[ks][j / JB] + (j % JB) * (4 * ROWB) + 16 * q4, 0, 0);
+                    vk[j][4 * q4] = x.x; vk[j][4 * q4 + 1] = x.y; vk[j][4 * q4 + 2] = x.z; vk[j][4 * q4 + 3] = x.w;
+                }
+            }
+        }
+    };
+    uint32_t vr[KS][8][CW];  // the values of the step being worked on, then of the wave's next step
+    // One step.  Up to d = 128 its values were requested during the previous step's P.V, k-step by k-step
+    // as the registers became free, so that they are in flight during the whole score phase and the
+    // wavefront has loads outstanding at all times (at d = 256 they are requested at the top of the
+    // step: holding them longer costs register spills there); the records of the wave's next step are requested first thing
+    // and are used one call later.  The step loop below is unrolled by two with the two record buffers
+    // swapping roles, so that no register copies (and no full memory wait in front of them) carry the
+    // prefetched records over.
+    auto process_step = [&](int step, const uint32_t (&w)[KPL][P::NWORDS], uint32_t (&w_next)[KPL][P::NWORDS])
                             __attribute__((always_inline)) {
         const int t0 = step * (KPL * kWave);
         const int n_valid = min(KPL * kWave, ww.len - t0);
-        // always issued (after the wave's last step: one cache line of values, the last step's records
-        // again): a branch here would make the compiler wait for every outstanding load first
+        // always issued (the wave's last step re-reads its own records, and requests values through an
+        // empty descriptor): a branch here would make the compiler wait for every outstanding load first
         const bool has_next = step + ww.step_stride < ww.step_end;
-        if constexpr (VAHEAD) {
-            load_values(has_next ? step + ww.step_stride : step, has_next, vr_next);
-        } else {
-            load_values(step, true, vr_next);
+        const __amdgpu_buffer_rsrc_t v_next =
+            AHEAD ? values_of(has_next ? step + ww.step_stride : step, has_next) : values_of(step, true);
+        if constexpr (!AHEAD) {   // d = 256: the registers hold one step's values only while it is worked on
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) load_values(v_next, ks, vr[ks]);
         }
         load_records(min(step + ww.step_stride, ww.step_last), w_next);
-        const uint32_t (&vr)[KS][8][CW] = VAHEAD ? vr_ahead : vr_next;
         // D2-D4: scores (queries carry the softmax scale already).  The query offset (always 0) is
         // laundered per step: otherwise the loop-invariant scalar loads of the whole query are hoisted
         // out of the step loop and hundreds of scalar registers spill.
@@ -555,7 +570,9 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
             const bool valid = k * kWave + lane < n_valid;
 #pragma unroll
             for (int r = 0; r < RG; ++r) s[k][r] = valid ? s[k][r] * gamma : -INFINITY;
-            if (scores_out != nullptr && valid) store_scores<RG>(shp, ww, scores_out, t0 + k * kWave + lane, s[k]);
+            if constexpr (SCORES) {
+                if (valid) store_scores<RG>(shp, ww, scores_out, t0 + k * kWave + lane, s[k]);
+            }
         }
         // D5: online softmax, one running maximum per row for the whole wave
         float alpha[RG];
@@ -593,33 +610,39 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        // D6: P.V
+        // D6: P.V.  Per k-step: build the B operands, request the same k-step of the next step's values
+        // into the registers just read, multiply.
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             union { uint4 u; bf16x8_t b; } pa;
             pa.u = *reinterpret_cast<const uint4 *>(&sm.pbuf[wave][n16][32 * ks + 8 * g4]);
+            union { uint32_t u[4]; bf16x8_t b; } vb[CPL];
 #pragma unroll
-            for (int c = 0; c < CPL; ++c) {
-                union { uint32_t u[4]; bf16x8_t b; } vb;
+            for (int c = 0; c < CPL; ++c)
 #pragma unroll
                 for (int jj = 0; jj < 4; ++jj)
-                    vb.u[jj] = __builtin_amdgcn_perm(vr[ks][2 * jj + 1][c / 2], vr[ks][2 * jj][c / 2],
-                                                     (c & 1) ? 0x07060302u : 0x05040100u);
-                acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa.b, vb.b, acc[c], 0, 0, 0);
-            }
+                    vb[c].u[jj] = __builtin_amdgcn_perm(vr[ks][2 * jj + 1][c / 2], vr[ks][2 * jj][c / 2],
+                                                        (c & 1) ? 0x07060302u : 0x05040100u);
+            if constexpr (AHEAD) load_values(v_next, ks, vr[ks]);
+#pragma unroll
+            for (int c = 0; c < CPL; ++c)
+                acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa.b, vb[c].b, acc[c], 0, 0, 0);
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         __builtin_amdgcn_wave_barrier();
     };
     uint32_t w_a[KPL][P::NWORDS], w_b[KPL][P::NWORDS];
-    uint32_t v_a[KS][8][CW], v_b[KS][8][CW];
     if (ww.step_begin < ww.step_end) {
         load_records(ww.step_begin, w_a);
-        if constexpr (VAHEAD) load_values(ww.step_begin, true, v_a);
+        if constexpr (AHEAD) {
+            const __amdgpu_buffer_rsrc_t v_first = values_of(ww.step_begin, true);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) load_values(v_first, ks, vr[ks]);
+        }
     }
     for (int step = ww.step_begin; step < ww.step_end; step += 2 * ww.step_stride) {
-        process_step(step, w_a, w_b, v_a, v_b);
-        if (step + ww.step_stride < ww.step_end) process_step(step + ww.step_stride, w_b, w_a, v_b, v_a);
+        process_step(step, w_a, w_b);
+        if (step + ww.step_stride < ww.step_end) process_step(step + ww.step_stride, w_b, w_a);
     }
 
     // D7: add the hi and lo partial results (lane groups RP/4 apart) and emit the wave's partial
@@ -836,9 +859,15 @@ int launch_decode_rg(const octopus_codebooks_t &cb, const DecodeShape &s, const 
     const dim3 block(kDecodeWaves * kWave);
     hipError_t err;
     if (v_dtype == OCTOPUS_DTYPE_BF16) {
-        hipLaunchKernelGGL((decode_kernel_mfma<P, RG>), grid, block, 0, stream, books, s, q_rot,
-                           static_cast<const uint4 *>(cache), static_cast<const uint32_t *>(v), seq_lens, part_ml,
-                           part_acc, scores_out);
+        if (scores_out != nullptr) {
+            hipLaunchKernelGGL((decode_kernel_mfma<P, RG, true>), grid, block, 0, stream, books, s, q_rot,
+                               static_cast<const uint4 *>(cache), static_cast<const uint32_t *>(v), seq_lens,
+                               part_ml, part_acc, scores_out);
+        } else {
+            hipLaunchKernelGGL((decode_kernel_mfma<P, RG, false>), grid, block, 0, stream, books, s, q_rot,
+                               static_cast<const uint4 *>(cache), static_cast<const uint32_t *>(v), seq_lens,
+                               part_ml, part_acc, scores_out);
+        }
     } else {
         const size_t smem = sizeof(DecodeSmemValu<P, RG>);
         err = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel_valu<P, RG>),
