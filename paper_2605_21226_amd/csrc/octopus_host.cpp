@@ -332,6 +332,26 @@ size_t octopus_cache_bytes(const octopus_codebooks_t *cb, int32_t n_seq, int32_t
     return static_cast<size_t>(n_seq) * n_kv_heads * static_cast<size_t>(t_capacity) * cb->plan.granules * 16;
 }
 
+// The encoder finds the scalar seed through a grid of 8 * 2^b_dir cells over [-1, 1] and one compare; that
+// is exact when no cell holds two boundaries of C_xi (true of every Lloyd-Max codebook this library builds;
+// a caller-edited codebook may violate it).  Same fp32 arithmetic as the kernel.
+static bool seed_grid_ok(const octopus_codebooks_t &cb) {
+    for (int c = 0; c < cb.plan.n_class; ++c) {
+        const int K = 1 << cb.plan.b_dir[c];
+        const int ncell = 8 * K;
+        int last = -1;
+        for (int k = 0; k + 1 < K; ++k) {
+            if (!(cb.c_xi[c][k] < cb.c_xi[c][k + 1])) return false;
+            const float b = 0.5f * (cb.c_xi[c][k] + cb.c_xi[c][k + 1]);
+            int cell = static_cast<int>(std::floor((b + 1.0f) * (0.5f * static_cast<float>(ncell))));
+            cell = std::min(std::max(cell, 0), ncell - 1);
+            if (cell <= last) return false;
+            last = cell;
+        }
+    }
+    return true;
+}
+
 int octopus_encode(const octopus_codebooks_t *cb, const void *keys, int32_t key_dtype, int64_t stride_seq,
                    int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
                    const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos, void *stream) {
@@ -340,7 +360,7 @@ int octopus_encode(const octopus_codebooks_t *cb, const void *keys, int32_t key_
     if (t_capacity < OCTOPUS_TILE || t_capacity % OCTOPUS_TILE != 0) return OCTOPUS_EINVAL;
     if (!plan_consistent(cb->plan)) return OCTOPUS_EINVAL;
     if (key_dtype != OCTOPUS_DTYPE_F32 && key_dtype != OCTOPUS_DTYPE_BF16) return OCTOPUS_EUNSUPPORTED;
-    if (!plan_supported(cb->plan)) return OCTOPUS_EUNSUPPORTED;
+    if (!plan_supported(cb->plan) || !seed_grid_ok(*cb)) return OCTOPUS_EUNSUPPORTED;
     if (stride_seq < 0 || stride_tok < 0 || stride_head < 0) return OCTOPUS_EINVAL;
     if (stride_seq % 8 != 0 || stride_tok % 8 != 0 || stride_head % 8 != 0) return OCTOPUS_EINVAL;
     if (!aligned(keys, 16) || !aligned(cache, 16)) return OCTOPUS_EINVAL;

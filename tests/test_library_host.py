@@ -117,3 +117,19 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "liboctopus.so"))
     with pytest.raises(RuntimeError, match="no fallback"):
         binding.load()
+
+
+def test_encode_refuses_a_codebook_too_fine_for_the_seed_grid():
+    """Host-side validation only (nothing is launched): two boundaries of C_xi within one grid cell."""
+    import ctypes
+    lib = binding.load()
+    cb = binding.octopus_build_codebooks(128, 3)
+    bad = binding.Codebooks.from_buffer_copy(cb)
+    bad.c_xi[0][8] = bad.c_xi[0][7] + 1e-4          # boundaries 7 and 8 now share a cell
+    bad.c_xi[0][9] = bad.c_xi[0][7] + 2e-4
+    dummy = ctypes.c_void_p(0x1000)                  # 16-byte aligned, never dereferenced on the host
+    args = (dummy, binding.DTYPE_BF16, 0, 1024, 128, 1, 1, 64, dummy, dummy, 64, None, None)
+    assert lib.octopus_encode(ctypes.byref(bad), *args) == binding.EUNSUPPORTED
+    bad2 = binding.Codebooks.from_buffer_copy(cb)
+    bad2.c_xi[0][3], bad2.c_xi[0][4] = bad2.c_xi[0][4], bad2.c_xi[0][3]   # not ascending
+    assert lib.octopus_encode(ctypes.byref(bad2), *args) == binding.EUNSUPPORTED
