@@ -844,6 +844,10 @@ __global__ __launch_bounds__(kWave) void merge_kernel(DecodeShape shp, const flo
 }
 
 // ---- launch helpers -----------------------------------------------------------------------------
+template <class P>
+int launch_decode_mq(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
+                     const void *v, const int32_t *seq_lens, float *part_ml, float *part_acc, hipStream_t stream);
+
 template <class P, int RG>
 int launch_decode_rg(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
                      const void *v, int v_dtype, const int32_t *seq_lens, float *part_ml, float *part_acc,
@@ -889,6 +893,12 @@ int launch_decode_plan(const octopus_codebooks_t &cb, const DecodeShape &s, cons
         case 2: return launch_decode_rg<P, 2>(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, stream);
         case 4: return launch_decode_rg<P, 4>(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, stream);
         case 8: return launch_decode_rg<P, 8>(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, stream);
+        case 128:
+            if constexpr (P::D <= 128) {
+                if (v_dtype == OCTOPUS_DTYPE_BF16 && scores_out == nullptr)
+                    return launch_decode_mq<P>(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, stream);
+            }
+            return static_cast<int>(hipErrorInvalidValue);
         default: return static_cast<int>(hipErrorInvalidValue);
     }
 }

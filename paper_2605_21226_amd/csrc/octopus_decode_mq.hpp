@@ -1,0 +1,309 @@
+// Decode attention for many query rows per KV head (a chunk of queries against the whole cache, e.g. the
+// 3600 queries of a video frame): Alg. 2 with the roles of a dense attention kernel.  Here the work per
+// key is a dense contraction over hundreds of rows, so both products run on the matrix cores; the keys
+// are still decoded on the fly from the packed records, once per 128 query rows, into an LDS tile and
+// never reach memory.
+//
+// A workgroup of 4 wavefronts owns 128 query rows of one (sequence, KV head) (32 per wavefront) and a
+// range of 64-token tiles.  Per tile:
+//   * stage (all 256 threads, one tile ahead, double-buffered LDS): lane = key; the record is unpacked,
+//     gamma * rho^ * n^ is looked up and multiplied, split into two bf16 numbers (hi = upper 16 bits,
+//     lo = the rest) and written to the key tile [key][coordinate]; the values of the tile are written
+//     transposed [channel][key];
+//   * S^T = K^ Q^T (keys x rows) with v_mfma_f32_32x32x16_bf16, three products per k-step (hi hi, hi lo,
+//     lo hi: relative error below 2^-16); a lane then holds 32 scores of ONE query row, so the softmax
+//     statistics of a row live in one lane (and its partner lane + 32);
+//   * O^T += V^T P^T (channels x rows): the probabilities go from the accumulators of the first product
+//     straight into the B operand of the second (k-slot j of lane group h is key 4h + j, or 8 + 4h + j - 4
+//     for j >= 4, of each group of 16 keys, which is how the first product left them), again as hi + lo.
+// The partial (m, l, acc) of each row goes to the split-K workspace and through the same merge kernel as
+// the single-query path.
+#ifndef OCTOPUS_DECODE_MQ_HPP_
+#define OCTOPUS_DECODE_MQ_HPP_
+
+#include "octopus_decode.hpp"
+
+namespace octopus {
+
+constexpr int kMqRows = 128;  // query rows per workgroup
+
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+
+template <class P>
+struct MqSmem {
+    static constexpr int D = P::D;
+    static constexpr int KST = D + 8;       // bf16 per row of the key tile: 16-byte reads of 8 lanes hit 8 bank groups
+    static constexpr int VST = kWave + 4;   // bf16 per row of the transposed value tile (8-byte aligned rows)
+    float4 dir0[1 << (2 * P::BD0)];
+    float4 dir1[P::NCLASS == 2 ? 1 << (2 * P::BD1) : 1];
+    float c_xi[2][32];
+    float c_rho[2][8];
+    uint16_t kh[2][kWave][KST];
+    uint16_t kl[2][kWave][KST];
+    uint16_t vt[2][D][VST];
+};
+
+template <class P>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(P::D <= 64 ? 2 : 1))) void decode_kernel_mq(DeviceBooks books, DecodeShape shp,
+                                                         const float *__restrict__ q_rot,
+                                                         const uint4 *__restrict__ cache,
+                                                         const uint16_t *__restrict__ v,
+                                                         const int32_t *__restrict__ seq_lens,
+                                                         float *__restrict__ part_ml, float *__restrict__ part_acc) {
+    constexpr int D = P::D;
+    constexpr int KK = D / 16;               // k-steps of the score product
+    constexpr int NB = D / 32;               // 32-channel blocks of the output
+    constexpr int ROWB = D * 2;              // bytes per value row
+    constexpr int TILEB = P::GRANULES * kWave * 16;
+    constexpr int VP = D / 8 / 4;            // 16-byte value pieces per thread and tile
+    using S = MqSmem<P>;
+    __shared__ S sm;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 31, h = lane >> 5;
+
+    // tables (one copy: the lookups are a small part of this kernel)
+    if (tid < kWave) copy_books(books, sm.c_xi, sm.c_rho);
+    __syncthreads();
+    build_dir_lut<P::BD0>(sm.dir0, sm.c_xi[0], tid, 256);
+    if constexpr (P::NCLASS == 2) build_dir_lut<P::BD1>(sm.dir1, sm.c_xi[1], tid, 256);
+
+    // work: (sequence, KV head, block of 128 rows, split) and the split's tiles
+    const int64_t wg = blockIdx.x;
+    const int split = static_cast<int>(wg % shp.n_splits);
+    const int64_t group_id = wg / shp.n_splits;
+    const int64_t pair = group_id / shp.n_row_groups;
+    const int seq = static_cast<int>(pair / shp.n_kv_heads);
+    const int len = min(max(seq_lens[seq], 0), shp.max_len);
+    const int n_tiles = (len + kWave - 1) / kWave;
+    const int base = n_tiles / shp.n_splits, rem = n_tiles % shp.n_splits;
+    const int tile_begin = split * base + min(split, rem);
+    const int tile_end = tile_begin + base + (split < rem ? 1 : 0);
+
+    const char *k_region = reinterpret_cast<const char *>(cache) + pair * shp.t_capacity * (P::GRANULES * 16);
+    const char *v_pair = reinterpret_cast<const char *>(v) + pair * shp.t_capacity * ROWB;
+
+    // Q^T operands of this wave's 32 rows: lane (n, h) holds coordinates 16 kk + 8 h .. + 8 of row n as
+    // bf16 hi and lo.  The rotated queries lie [coordinate][row] with the 128 rows of the block adjacent.
+    const float *qg = q_rot + group_id * (static_cast<int64_t>(P::QS) * kMqRows) + wave * 32 + n;
+    union BF8 { uint32_t u[4]; bf16x8_t b; };
+    BF8 qh[KK], ql[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float a = qg[(16 * kk + 8 * h + 2 * e) * kMqRows], b = qg[(16 * kk + 8 * h + 2 * e + 1) * kMqRows];
+            const uint32_t ab = __float_as_uint(a), bb = __float_as_uint(b);
+            qh[kk].u[e] = __builtin_amdgcn_perm(bb, ab, 0x07060302u);
+            const float al = a - __uint_as_float(ab & 0xffff0000u), bl = b - __uint_as_float(bb & 0xffff0000u);
+            ql[kk].u[e] = __builtin_amdgcn_perm(__float_as_uint(bl), __float_as_uint(al), 0x07060302u);
+        }
+
+    // ---- staging: global -> registers -> LDS tile ---------------------------------------------------
+    uint32_t w[P::NWORDS];          // this lane's record of the tile being staged
+    uint4 vp[VP];                   // its value pieces: key `lane`, channels 8 (wave + 4 i) .. + 8
+    auto load_tile = [&](int tile) {
+        typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+        typedef uint32_t u32x3_t __attribute__((ext_vector_type(3)));
+        constexpr int USED = (P::RECORD_BYTES + 3) / 4;
+        const char *src = k_region + static_cast<int64_t>(tile) * TILEB + lane * 16;
+#pragma unroll
+        for (int g = 0; g < P::GRANULES; ++g) {
+            const char *gp = src + g * (kWave * 16);
+            const int nw = (USED - 4 * g) < 4 ? (USED - 4 * g) : 4;
+            if (nw == 4) {
+                const uint4 x = *reinterpret_cast<const uint4 *>(gp);
+                w[4 * g] = x.x; w[4 * g + 1] = x.y; w[4 * g + 2] = x.z; w[4 * g + 3] = x.w;
+            } else if (nw == 3) {
+                const u32x3_t x = *reinterpret_cast<const u32x3_t *>(gp);
+                w[4 * g] = x.x; w[4 * g + 1] = x.y; w[4 * g + 2] = x.z; w[4 * g + 3] = 0u;
+            } else if (nw == 2) {
+                const u32x2_t x = *reinterpret_cast<const u32x2_t *>(gp);
+                w[4 * g] = x.x; w[4 * g + 1] = x.y; w[4 * g + 2] = 0u; w[4 * g + 3] = 0u;
+            } else {
+                w[4 * g] = *reinterpret_cast<const uint32_t *>(gp);
+                w[4 * g + 1] = 0u; w[4 * g + 2] = 0u; w[4 * g + 3] = 0u;
+            }
+        }
+        // value rows past the sequence's end are replaced by its last row (their probabilities are zero)
+        const int row = min(tile * kWave + lane, len - 1);
+        const char *vrow = v_pair + static_cast<int64_t>(row) * ROWB;
+#pragma unroll
+        for (int i = 0; i < VP; ++i) vp[i] = *reinterpret_cast<const uint4 *>(vrow + (wave + 4 * i) * 16);
+    };
+    // one triplet of this lane's key into the key tile
+    auto stage_triplet = [&](auto ii, int buf) __attribute__((always_inline)) {
+        constexpr int i = decltype(ii)::value;
+        constexpr int c = P::cls(i);
+        constexpr int bd = P::bdir(i), bn = P::bnrm(i);
+        const uint32_t code = field<P::dir_bit(i), 2 * bd>(w);
+        const uint32_t nrm = field<P::nrm_bit(i), bn>(w);
+        const float4 dir = (c ? sm.dir1 : sm.dir0)[code];
+        const float g = __uint_as_float(w[0]) * sm.c_rho[c][nrm];
+        const float val[3] = {g * dir.x, g * dir.y, g * dir.z};
+#pragma unroll
+        for (int e = 0; e < 3; ++e) {
+            if (3 * i + e < D) {   // the padded coordinates of the last triplet are dropped
+                const uint32_t bits = __float_as_uint(val[e]);
+                const float lo = val[e] - __uint_as_float(bits & 0xffff0000u);
+                sm.kh[buf][lane][3 * i + e] = static_cast<uint16_t>(bits >> 16);
+                sm.kl[buf][lane][3 * i + e] = static_cast<uint16_t>(__float_as_uint(lo) >> 16);
+            }
+        }
+    };
+    // wave wv takes the triplets i = wv (mod 4): compile-time field positions per case
+    auto stage_tile = [&](int buf) {
+        constexpr int PER = (P::NTRI + 3) / 4;
+        auto part = [&](auto ww) __attribute__((always_inline)) {
+            constexpr int wv = decltype(ww)::value;
+            static_for<0, PER>([&](auto jj) {
+                constexpr int i = wv + 4 * decltype(jj)::value;
+                if constexpr (i < P::NTRI) stage_triplet(std::integral_constant<int, i>{}, buf);
+            });
+        };
+        switch (wave) {
+            case 0: part(std::integral_constant<int, 0>{}); break;
+            case 1: part(std::integral_constant<int, 1>{}); break;
+            case 2: part(std::integral_constant<int, 2>{}); break;
+            default: part(std::integral_constant<int, 3>{}); break;
+        }
+#pragma unroll
+        for (int i = 0; i < VP; ++i) {
+            const int c0 = (wave + 4 * i) * 8;
+            const uint32_t x[4] = {vp[i].x, vp[i].y, vp[i].z, vp[i].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                sm.vt[buf][c0 + 2 * e][lane] = static_cast<uint16_t>(x[e] & 0xffffu);
+                sm.vt[buf][c0 + 2 * e + 1][lane] = static_cast<uint16_t>(x[e] >> 16);
+            }
+        }
+    };
+
+    float m_run = -INFINITY, l_run = 0.0f;
+    f32x16_t oacc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) oacc[nb][e] = 0.0f;
+
+    if (tile_begin < tile_end) {
+        load_tile(tile_begin);
+        __syncthreads();                       // tables complete
+        stage_tile(0);
+        load_tile(min(tile_begin + 1, tile_end - 1));
+    }
+    __syncthreads();
+
+    for (int tile = tile_begin; tile < tile_end; ++tile) {
+        const int buf = (tile - tile_begin) & 1;
+        // S^T = K^ Q^T for the tile's two blocks of 32 keys
+        f32x16_t sacc[2];
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) sacc[mb][e] = 0.0f;
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) {
+                BF8 ah, al;
+                *reinterpret_cast<uint4 *>(ah.u) = *reinterpret_cast<const uint4 *>(&sm.kh[buf][32 * mb + n][16 * kk + 8 * h]);
+                *reinterpret_cast<uint4 *>(al.u) = *reinterpret_cast<const uint4 *>(&sm.kl[buf][32 * mb + n][16 * kk + 8 * h]);
+                sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah.b, qh[kk].b, sacc[mb], 0, 0, 0);
+                sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah.b, ql[kk].b, sacc[mb], 0, 0, 0);
+                sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al.b, qh[kk].b, sacc[mb], 0, 0, 0);
+            }
+        }
+        // keys past the end of the sequence (last tile only): element e of block mb is key
+        // 32 mb + 8 (e / 4) + 4 h + e % 4
+        const int n_valid = len - tile * kWave;
+        if (n_valid < kWave) {
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    if (32 * mb + 8 * (e / 4) + 4 * h + (e % 4) >= n_valid) sacc[mb][e] = -INFINITY;
+        }
+        // online softmax of this lane's row (its other 32 keys of the tile are in lane + 32)
+        float mx = sacc[0][0];
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[mb][e]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = exp2f((m_run - m_new) * kLog2e);
+        m_run = m_new;
+        float psum = 0.0f;
+        BF8 ph[4], pl[4];   // per group of 16 keys: the 8 k-slots of this lane, hi and lo
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int e = 0; e < 16; e += 2) {
+                const float p0 = exp2f((sacc[mb][e] - m_new) * kLog2e), p1 = exp2f((sacc[mb][e + 1] - m_new) * kLog2e);
+                psum += p0 + p1;
+                const uint32_t b0 = __float_as_uint(p0), b1 = __float_as_uint(p1);
+                const float l0 = p0 - __uint_as_float(b0 & 0xffff0000u), l1 = p1 - __uint_as_float(b1 & 0xffff0000u);
+                ph[2 * mb + e / 8].u[(e % 8) / 2] = __builtin_amdgcn_perm(b1, b0, 0x07060302u);
+                pl[2 * mb + e / 8].u[(e % 8) / 2] = __builtin_amdgcn_perm(__float_as_uint(l1), __float_as_uint(l0), 0x07060302u);
+            }
+        l_run = fmaf(l_run, alpha, psum);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) oacc[nb][e] *= alpha;
+        // O^T += V^T P^T
+#pragma unroll
+        for (int g16 = 0; g16 < 4; ++g16)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                BF8 va;
+                const uint16_t *vrow = &sm.vt[buf][32 * nb + n][16 * g16 + 4 * h];
+                const uint2 x0 = *reinterpret_cast<const uint2 *>(vrow), x1 = *reinterpret_cast<const uint2 *>(vrow + 8);
+                va.u[0] = x0.x; va.u[1] = x0.y; va.u[2] = x1.x; va.u[3] = x1.y;
+                oacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.b, ph[g16].b, oacc[nb], 0, 0, 0);
+                oacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.b, pl[g16].b, oacc[nb], 0, 0, 0);
+            }
+        // stage the next tile into the other buffer, request the one after
+        if (tile + 1 < tile_end) {
+            stage_tile(buf ^ 1);
+            load_tile(min(tile + 2, tile_end - 1));
+        }
+        __syncthreads();
+    }
+
+    // partial of each row: element e of block nb is channel 32 nb + 8 (e / 4) + 4 h + e % 4 of row n
+    const int row = wave * 32 + n;
+    const int grp = static_cast<int>(group_id % shp.n_row_groups);
+    if (grp * kMqRows + row < shp.rows_per_kv) {
+        const int64_t prow = (group_id * kMqRows + row) * shp.n_splits + split;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4)
+                *reinterpret_cast<float4 *>(part_acc + prow * D + 32 * nb + 8 * q4 + 4 * h) =
+                    make_float4(oacc[nb][4 * q4], oacc[nb][4 * q4 + 1], oacc[nb][4 * q4 + 2], oacc[nb][4 * q4 + 3]);
+        const float l = l_run + __shfl_xor(l_run, 32, kWave);
+        if (h == 0) {
+            part_ml[prow * 2] = m_run;
+            part_ml[prow * 2 + 1] = l;
+        }
+    }
+}
+
+template <class P>
+int launch_decode_mq(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
+                     const void *v, const int32_t *seq_lens, float *part_ml, float *part_acc, hipStream_t stream) {
+    DeviceBooks books;
+    for (int c = 0; c < 2; ++c) {
+        for (int k = 0; k < 32; ++k) books.c_xi[c][k] = cb.c_xi[c][k];
+        for (int k = 0; k < 8; ++k) books.c_rho[c][k] = cb.c_rho[c][k];
+    }
+    const int64_t wgs = static_cast<int64_t>(s.n_seq) * s.n_kv_heads * s.n_row_groups * s.n_splits;
+    hipLaunchKernelGGL((decode_kernel_mq<P>), dim3(static_cast<unsigned>(wgs)), dim3(256), 0, stream, books, s, q_rot,
+                       static_cast<const uint4 *>(cache), static_cast<const uint16_t *>(v), seq_lens, part_ml, part_acc);
+    return static_cast<int>(hipGetLastError());
+}
+
+}  // namespace octopus
+
+#endif

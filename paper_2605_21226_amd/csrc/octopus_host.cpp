@@ -219,7 +219,7 @@ bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 }  // namespace
 
 DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads,
-                              int32_t n_q, int64_t max_len, int64_t t_capacity) {
+                              int32_t n_q, int64_t max_len, int64_t t_capacity, bool many_rows) {
     DecodeShape s{};
     s.n_seq = n_seq;
     s.n_q_heads = n_q_heads;
@@ -227,17 +227,30 @@ DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t
     s.n_q = n_q;
     s.heads_per_kv = n_q_heads / n_kv_heads;
     s.rows_per_kv = n_q * s.heads_per_kv;
+    s.t_capacity = t_capacity;
+    s.max_len = static_cast<int32_t>(max_len);
+    const int64_t len = std::max<int64_t>(max_len, 1);
+    if (many_rows) {
+        // Matrix-core kernel for many query rows: blocks of 128 rows, one workgroup per (block, split);
+        // two workgroups fit a compute unit at d = 64, one at d = 128.
+        s.rows_per_pass = 128;
+        s.n_row_groups = (s.rows_per_kv + 127) / 128;
+        const int64_t groups = static_cast<int64_t>(n_seq) * n_kv_heads * s.n_row_groups;
+        const int64_t max_tiles = (len + OCTOPUS_TILE - 1) / OCTOPUS_TILE;
+        const int64_t slots = 256 * (plan.head_dim <= 64 ? 2 : 1);
+        const int64_t want = (slots + groups / 2) / groups;
+        s.n_splits = static_cast<int32_t>(std::max<int64_t>(1, std::min<int64_t>(want, max_tiles)));
+        return s;
+    }
     // Query rows scored per key by one workgroup: the power of two covering rows_per_kv, at most 8.
     // Rows beyond rows_per_kv in the last group are zero queries whose results are not stored.
     s.rows_per_pass = 1;
     while (s.rows_per_pass < s.rows_per_kv && s.rows_per_pass < 8) s.rows_per_pass *= 2;
     s.n_row_groups = (s.rows_per_kv + s.rows_per_pass - 1) / s.rows_per_pass;
-    s.t_capacity = t_capacity;
     // Split-K sizing: one wavefront per split.  The decode kernel runs one wavefront per SIMD, 256
     // compute units x 4 at once; the steps (128 keys up to d = 128, 64 keys at d = 256) of each
     // (sequence, KV head, row group) are divided over as many splits as fill those slots once, so that
     // all wavefronts start together and end together.
-    const int64_t len = std::max<int64_t>(max_len, 1);
     const int64_t groups = static_cast<int64_t>(n_seq) * n_kv_heads * s.n_row_groups;
     const int64_t step_keys = OCTOPUS_TILE * (plan.head_dim <= 128 ? 2 : 1);
     const int64_t max_steps = (len + step_keys - 1) / step_keys;
@@ -246,8 +259,12 @@ DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t
     int64_t want = (slots / 4 + groups / 2) / groups;
     want = std::max<int64_t>(1, std::min<int64_t>(want, (max_steps + 3) / 4));
     s.n_splits = static_cast<int32_t>(4 * want);
-    s.max_len = static_cast<int32_t>(max_len);
     return s;
+}
+
+// The matrix-core kernel for many query rows serves bf16 values without score output at d <= 128.
+bool many_rows_shape(const octopus_plan_t &plan, int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q) {
+    return plan.head_dim <= 128 && static_cast<int64_t>(n_q) * (n_q_heads / n_kv_heads) >= 32;
 }
 
 Workspace make_workspace(const octopus_plan_t &plan, const DecodeShape &s) {
@@ -385,8 +402,13 @@ static int decode_args_ok(const octopus_codebooks_t *cb, int32_t n_seq, int32_t 
 size_t octopus_attn_decode_workspace(const octopus_codebooks_t *cb, int32_t n_seq, int32_t n_q_heads,
                                      int32_t n_kv_heads, int32_t n_q, int64_t max_len) {
     if (decode_args_ok(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len) != OCTOPUS_OK) return 0;
-    const DecodeShape s = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, 0);
-    return make_workspace(cb->plan, s).total;
+    const DecodeShape s = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, 0, false);
+    size_t total = make_workspace(cb->plan, s).total;
+    if (many_rows_shape(cb->plan, n_q_heads, n_kv_heads, n_q)) {   // the larger of the two kernels' needs
+        const DecodeShape m = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, 0, true);
+        total = std::max(total, make_workspace(cb->plan, m).total);
+    }
+    return total;
 }
 
 int octopus_attn_decode(const octopus_codebooks_t *cb, const void *q, int32_t q_dtype, int32_t n_seq,
@@ -404,7 +426,9 @@ int octopus_attn_decode(const octopus_codebooks_t *cb, const void *q, int32_t q_
         return OCTOPUS_EUNSUPPORTED;
     if (!aligned(cache, 16) || !aligned(v, 16) || !aligned(q, 4) || !aligned(out, 4)) return OCTOPUS_EINVAL;
     if (!std::isfinite(scale)) return OCTOPUS_EINVAL;
-    const DecodeShape s = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, t_capacity);
+    const bool many_rows = many_rows_shape(cb->plan, n_q_heads, n_kv_heads, n_q) && v_dtype == OCTOPUS_DTYPE_BF16 &&
+                           scores_out == nullptr;
+    const DecodeShape s = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, t_capacity, many_rows);
     const Workspace w = make_workspace(cb->plan, s);
     if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < w.total) return OCTOPUS_EWORKSPACE;
     char *base = static_cast<char *>(workspace);

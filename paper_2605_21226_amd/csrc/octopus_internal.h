@@ -23,9 +23,9 @@ struct DecodeShape {
     int32_t n_seq, n_q_heads, n_kv_heads, n_q;
     int32_t heads_per_kv;   // n_q_heads / n_kv_heads
     int32_t rows_per_kv;    // n_q * heads_per_kv query rows sharing one KV head
-    int32_t rows_per_pass;  // query rows one workgroup scores per key (1, 2, 4 or 8)
+    int32_t rows_per_pass;  // query rows one workgroup scores per key (1, 2, 4 or 8; 128: matrix-core kernel)
     int32_t n_row_groups;   // ceil(rows_per_kv / rows_per_pass)
-    int32_t n_splits;       // wavefronts sharing the tiles of one (sequence, KV head, row group)
+    int32_t n_splits;       // wavefronts (workgroups at 128 rows) sharing the tiles of one (sequence, KV head, row group)
     int32_t max_len;        // host-side bound of the sequence lengths
     int64_t t_capacity;
 };
@@ -36,7 +36,7 @@ struct Workspace {
 };
 
 DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads,
-                              int32_t n_q, int64_t max_len, int64_t t_capacity);
+                              int32_t n_q, int64_t max_len, int64_t t_capacity, bool many_rows);
 Workspace make_workspace(const octopus_plan_t &plan, const DecodeShape &s);
 
 // Kernel launchers (defined in the .hip files).  Each returns a hipError_t cast to int.

@@ -140,7 +140,7 @@ def oracle_attention_all(plan, records, signs, q, v, lens, scale):
     return out, scores
 
 
-def run_decode_case(d, bits, n_seq, n_qh, n_kv, n_q, lens, dtype, seed, t_capacity=None):
+def run_decode_case(d, bits, n_seq, n_qh, n_kv, n_q, lens, dtype, seed, t_capacity=None, want_scores=True):
     cb = binding.octopus_build_codebooks(d, bits)
     plan = oracle.make_plan(d, bits)
     T = max(int(max(lens)), 1)
@@ -154,7 +154,7 @@ def run_decode_case(d, bits, n_seq, n_qh, n_kv, n_q, lens, dtype, seed, t_capaci
     v[:, :, :T] = vals
     scale = 1.0 / np.sqrt(d)
     cache = cache_from_records(cb, records, t_capacity)      # the oracle's codes in the device layout
-    out, scores = gpu_decode(cb, q, dtype, signs, cache, t_capacity, v, dtype, lens, scale)
+    out, scores = gpu_decode(cb, q, dtype, signs, cache, t_capacity, v, dtype, lens, scale, want_scores=want_scores)
     ref_out, ref_scores = oracle_attention_all(plan, records, signs, q, v, lens, scale)
     g = n_qh // n_kv
     worst_s = worst_o = 0.0
@@ -165,9 +165,11 @@ def run_decode_case(d, bits, n_seq, n_qh, n_kv, n_q, lens, dtype, seed, t_capaci
                 if L == 0:
                     assert np.all(out[s, qi, h] == 0.0)
                     continue
-                worst_s = max(worst_s, check_scores(scores[s, qi, h, :L], ref_scores[(s, h // g)][qi, h % g]))
+                if want_scores:
+                    worst_s = max(worst_s, check_scores(scores[s, qi, h, :L], ref_scores[(s, h // g)][qi, h % g]))
                 worst_o = max(worst_o, check_out(out[s, qi, h], ref_out[s, qi, h]))
-        assert np.all(np.isnan(scores[s, :, :, L:]))          # scores past len are not written
+        if want_scores:
+            assert np.all(np.isnan(scores[s, :, :, L:]))      # scores past len are not written
     print(f"[attn] d={d} b={bits} lens={list(lens)}: worst score err {worst_s:.3g} x tol, worst out err {worst_o:.3g}")
 
 
@@ -193,6 +195,25 @@ def test_decode_gqa2_ragged_d256(bits):
 def test_decode_rows_not_a_power_of_two_and_many_row_groups():
     run_decode_case(128, 3, 1, 6, 2, 1, [300], "bf16", seed=7)       # 3 query heads per KV head
     run_decode_case(64, 4, 1, 2, 2, 11, [300], "bf16", seed=8)       # 11 query rows -> two groups of 8
+
+
+@pytest.mark.parametrize("bits", ALL_BITS)
+def test_decode_many_query_rows_d64(bits):
+    """40 and 200 query rows per KV head (the matrix-core kernel: blocks of 128 rows), ragged lengths"""
+    run_decode_case(64, bits, 2, 2, 2, 40, [700, 65], "bf16", seed=int(300 + 10 * bits), want_scores=False)
+    if bits == 4:
+        run_decode_case(64, bits, 1, 3, 3, 200, [1000], "bf16", seed=341, want_scores=False)
+
+
+@pytest.mark.parametrize("bits", ALL_BITS)
+def test_decode_many_query_rows_gqa_d128(bits):
+    """16 queries x 4 heads per KV head = 64 rows; a sequence of length 0 and a ragged last tile"""
+    run_decode_case(128, bits, 3, 8, 2, 16, [0, 130, 513], "bf16", seed=int(400 + 10 * bits), want_scores=False)
+
+
+def test_decode_many_query_rows_with_scores_or_fp32_values_uses_the_row_group_kernels():
+    run_decode_case(64, 4, 1, 2, 2, 40, [300], "bf16", seed=351)                    # scores requested
+    run_decode_case(64, 4, 1, 2, 2, 40, [300], "fp32", seed=352, want_scores=False)  # fp32 values
 
 
 def test_decode_is_independent_of_the_split_count():
