@@ -8,7 +8,7 @@ bool plan_supported_d128(const octopus_plan_t &);
 bool plan_supported_d256(const octopus_plan_t &);
 #define OCTOPUS_DECL(D)                                                                                            \
     int launch_decode_d##D(const octopus_codebooks_t &, const DecodeShape &, const float *, const void *,          \
-                           const void *, int, const int32_t *, float *, float *, float *, void *);                 \
+                           const void *, int, const int32_t *, float *, float *, float *, int32_t *, void *);      \
     int launch_encode_d##D(const octopus_codebooks_t &, const void *, int, int64_t, int64_t, int64_t, int32_t,     \
                            int32_t, int32_t, const uint8_t *, void *, int64_t, const int32_t *, void *);
 OCTOPUS_DECL(64)
@@ -31,11 +31,11 @@ bool plan_supported(const octopus_plan_t &plan) {
 
 int launch_decode(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
                   const void *v, int v_dtype, const int32_t *seq_lens, float *part_ml, float *part_acc,
-                  float *scores_out, void *stream) {
+                  float *scores_out, int32_t *work_plan, void *stream) {
     switch (cb.plan.head_dim) {
-        case 64: return launch_decode_d64(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, stream);
-        case 128: return launch_decode_d128(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, stream);
-        case 256: return launch_decode_d256(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, stream);
+        case 64: return launch_decode_d64(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, work_plan, stream);
+        case 128: return launch_decode_d128(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, work_plan, stream);
+        case 256: return launch_decode_d256(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, work_plan, stream);
         default: return static_cast<int>(hipErrorInvalidValue);
     }
 }
@@ -53,41 +53,42 @@ int launch_encode(const octopus_codebooks_t &cb, const void *keys, int key_dtype
 
 template <int D>
 static int rotate_d(const void *q, int q_dtype, const uint8_t *signs, const DecodeShape &s, float scale, float *q_rot,
-                    hipStream_t stream) {
+                    const int32_t *seq_lens, int32_t *work_plan, hipStream_t stream) {
     constexpr int QS = (3 * ((D + 2) / 3) + 3) & ~3;
     const int64_t rows = static_cast<int64_t>(s.n_seq) * s.n_kv_heads * s.n_row_groups * s.rows_per_pass;
     hipLaunchKernelGGL((rotate_queries_kernel<D, QS>), dim3(static_cast<unsigned>(rows)), dim3(kWave), 0, stream, q,
-                       q_dtype == OCTOPUS_DTYPE_BF16 ? 1 : 0, signs, s, scale, q_rot);
+                       q_dtype == OCTOPUS_DTYPE_BF16 ? 1 : 0, signs, s, scale, q_rot, seq_lens, work_plan);
     return static_cast<int>(hipGetLastError());
 }
 
 int launch_rotate_queries(const octopus_plan_t &plan, const void *q, int q_dtype, const uint8_t *signs,
-                          const DecodeShape &s, float scale, float *q_rot, void *stream) {
+                          const DecodeShape &s, float scale, float *q_rot, const int32_t *seq_lens,
+                          int32_t *work_plan, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     switch (plan.head_dim) {
-        case 64: return rotate_d<64>(q, q_dtype, signs, s, scale, q_rot, st);
-        case 128: return rotate_d<128>(q, q_dtype, signs, s, scale, q_rot, st);
-        case 256: return rotate_d<256>(q, q_dtype, signs, s, scale, q_rot, st);
+        case 64: return rotate_d<64>(q, q_dtype, signs, s, scale, q_rot, seq_lens, work_plan, st);
+        case 128: return rotate_d<128>(q, q_dtype, signs, s, scale, q_rot, seq_lens, work_plan, st);
+        case 256: return rotate_d<256>(q, q_dtype, signs, s, scale, q_rot, seq_lens, work_plan, st);
         default: return static_cast<int>(hipErrorInvalidValue);
     }
 }
 
 template <int D>
-static int merge_d(const DecodeShape &s, const float *part_ml, const float *part_acc, float *out,
-                   hipStream_t stream) {
+static int merge_d(const DecodeShape &s, const float *part_ml, const float *part_acc, const int32_t *work_plan,
+                   float *out, hipStream_t stream) {
     const int64_t rows = static_cast<int64_t>(s.n_seq) * s.n_q * s.n_q_heads;
     hipLaunchKernelGGL((merge_kernel<D>), dim3(static_cast<unsigned>(rows)), dim3(kWave), 0, stream, s, part_ml,
-                       part_acc, out);
+                       part_acc, work_plan, out);
     return static_cast<int>(hipGetLastError());
 }
 
 int launch_merge(const octopus_plan_t &plan, const DecodeShape &s, const float *part_ml, const float *part_acc,
-                 float *out, void *stream) {
+                 const int32_t *work_plan, float *out, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     switch (plan.head_dim) {
-        case 64: return merge_d<64>(s, part_ml, part_acc, out, st);
-        case 128: return merge_d<128>(s, part_ml, part_acc, out, st);
-        case 256: return merge_d<256>(s, part_ml, part_acc, out, st);
+        case 64: return merge_d<64>(s, part_ml, part_acc, work_plan, out, st);
+        case 128: return merge_d<128>(s, part_ml, part_acc, work_plan, out, st);
+        case 256: return merge_d<256>(s, part_ml, part_acc, work_plan, out, st);
         default: return static_cast<int>(hipErrorInvalidValue);
     }
 }

@@ -10,70 +10,6 @@ namespace octopus {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kDecodeWaves = 4;  // wavefronts per workgroup of the main kernels
 
-// ---- D0: q_rot = scale * H (s . q), one wavefront per query row ------------------------------
-// Output layout per (sequence, KV head, row group): [QS coordinates][RG rows], so that the RG
-// values a key needs for one coordinate are adjacent.  Rows past rows_per_kv and coordinates
-// past d are written as zeros.
-template <int D, int QS>
-__global__ __launch_bounds__(kWave) void rotate_queries_kernel(const void *__restrict__ q, int q_is_bf16,
-                                                                const uint8_t *__restrict__ signs, DecodeShape s,
-                                                                float scale, float *__restrict__ q_rot) {
-    constexpr int EPL = D / kWave;  // elements per lane (1, 2, 4)
-    const int lane = threadIdx.x;
-    const int rg = s.rows_per_pass;
-    const int padded_rows = s.n_row_groups * rg;
-    const int64_t gid = blockIdx.x;  // (seq, kvh, padded row)
-    const int row = static_cast<int>(gid % padded_rows);
-    const int kvh = static_cast<int>((gid / padded_rows) % s.n_kv_heads);
-    const int seq = static_cast<int>(gid / (static_cast<int64_t>(padded_rows) * s.n_kv_heads));
-    float *dst = q_rot + (gid / rg) * (static_cast<int64_t>(QS) * rg) + (row % rg);
-
-    float x[EPL];
-    if (row < s.rows_per_kv) {
-        const int qi = row / s.heads_per_kv;
-        const int head = kvh * s.heads_per_kv + row % s.heads_per_kv;
-        const int64_t base = ((static_cast<int64_t>(seq) * s.n_q + qi) * s.n_q_heads + head) * D + lane * EPL;
-#pragma unroll
-        for (int j = 0; j < EPL; ++j) {
-            const int e = lane * EPL + j;
-            float val = q_is_bf16 ? __uint_as_float(static_cast<uint32_t>(static_cast<const uint16_t *>(q)[base + j]) << 16)
-                                  : static_cast<const float *>(q)[base + j];
-            const bool neg = (signs[kvh * (D / 8) + (e >> 3)] >> (e & 7)) & 1;
-            x[j] = neg ? -val : val;
-        }
-        // butterflies over the in-lane bits of the element index ...
-#pragma unroll
-        for (int h = 1; h < EPL; h <<= 1) {
-#pragma unroll
-            for (int j = 0; j < EPL; ++j) {
-                if ((j & h) == 0) {
-                    const float a = x[j], b = x[j | h];
-                    x[j] = a + b;
-                    x[j | h] = a - b;
-                }
-            }
-        }
-        // ... then over the lane bits: the element with the bit clear takes a + b, the other a - b
-#pragma unroll
-        for (int m = 1; m < kWave; m <<= 1) {
-#pragma unroll
-            for (int j = 0; j < EPL; ++j) {
-                const float other = __shfl_xor(x[j], m, kWave);
-                x[j] = (lane & m) ? other - x[j] : x[j] + other;
-            }
-        }
-        const float norm = scale * (D == 64 ? 0.125f : (D == 128 ? 0.08838834764831845f : 0.0625f));
-#pragma unroll
-        for (int j = 0; j < EPL; ++j) x[j] *= norm;
-    } else {
-#pragma unroll
-        for (int j = 0; j < EPL; ++j) x[j] = 0.0f;
-    }
-#pragma unroll
-    for (int j = 0; j < EPL; ++j) dst[static_cast<int64_t>(lane * EPL + j) * rg] = x[j];
-    for (int e = D + lane; e < QS; e += kWave) dst[static_cast<int64_t>(e) * rg] = 0.0f;
-}
-
 // ---- D1-D7: split-K main kernels --------------------------------------------------------------
 // Work unit = one wavefront = one (sequence, KV head, row group, split): the wave walks the 64-token
 // tiles of its split with one key per lane, keeps its own running (m, l, acc) and writes one partial
@@ -209,34 +145,109 @@ __device__ __forceinline__ void build_tables(DecodeTables<P> &tb, const DeviceBo
     __syncthreads();
 }
 
-// Which (sequence, KV head, row group, split) a wavefront works on, and its tiles.  A workgroup takes
-// a contiguous range of tiles of one (sequence, KV head, row group); its four wavefronts walk that
-// range interleaved (step_begin, step_begin + 4, ...), so that the workgroup as a whole streams through
-// memory front to back, and each wavefront is one split with its own partial result.
+// Work distribution of the split-K kernels.  The kernels are launched with one workgroup per compute
+// unit; the workgroups take ITEMS from a counter until none is left.  An item is a contiguous range of
+// steps (a step = tiles_per_step 64-token tiles) of one (sequence, KV head, row group); its four
+// wavefronts walk that range interleaved (step_begin, step_begin + 4, ...), so that the workgroup
+// streams through memory front to back, and each wavefront writes its own partial result, addressed by
+// (item, wavefront).  The items are cut on the device from the actual sequence lengths (plan below), so
+// that ragged batches are balanced; a batch of equal lengths yields exactly one item per workgroup.
+//
+// plan[0] item counter, plan[1] number of items, plan[2] steps per item (target), plan[3] = 1 when there
+// is at most one item per workgroup (then workgroup b takes item b),
+// plan[4 + s], s = 0 .. n_seq: items before sequence s.  Sequence s has c_s items per (KV head, row
+// group), (KV head, row group) pairs in order, the steps of a pair divided evenly over its c_s items.
+constexpr int kPlanHeader = 4;
+constexpr int kDecodeWorkgroups = 256;   // one per compute unit
+constexpr int kItemOversubscription = 8; // items per workgroup when one item each cannot balance the batch
+
+__device__ __forceinline__ int steps_of(int len, int max_len, int tiles_per_step) {
+    const int l = min(max(len, 0), max_len);
+    const int tiles = (l + kWave - 1) / kWave;
+    return (tiles + tiles_per_step - 1) / tiles_per_step;
+}
+
+// Executed by one wavefront (block 0 of the query rotation kernel, which precedes the split-K kernel on
+// the stream).
+__device__ __forceinline__ void build_plan(const DecodeShape &shp, const int32_t *seq_lens, int tiles_per_step,
+                                           int32_t *plan, int lane) {
+    const int G = shp.n_kv_heads * shp.n_row_groups;
+    long long total = 0;
+    for (int s0 = 0; s0 < shp.n_seq; s0 += kWave) {
+        const int s = s0 + lane;
+        total += s < shp.n_seq ? steps_of(seq_lens[s], shp.max_len, tiles_per_step) : 0;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) total += __shfl_xor(total, o, kWave);
+    total *= G;
+    auto count_items = [&](int item) {
+        long long cnt = 0;
+        for (int s0 = 0; s0 < shp.n_seq; s0 += kWave) {
+            const int s = s0 + lane;
+            const int st = s < shp.n_seq ? steps_of(seq_lens[s], shp.max_len, tiles_per_step) : 0;
+            cnt += static_cast<long long>((st + item - 1) / item) * G;
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, kWave);
+        return cnt;
+    };
+    int item = static_cast<int>(max(1LL, (total + kDecodeWorkgroups - 1) / kDecodeWorkgroups));
+    if (count_items(item) > kDecodeWorkgroups)
+        item = static_cast<int>(max(1LL, (total + kDecodeWorkgroups * kItemOversubscription - 1) /
+                                             (kDecodeWorkgroups * kItemOversubscription)));
+    int running = 0;
+    for (int s0 = 0; s0 < shp.n_seq; s0 += kWave) {
+        const int s = s0 + lane;
+        const int st = s < shp.n_seq ? steps_of(seq_lens[s], shp.max_len, tiles_per_step) : 0;
+        const int mine = ((st + item - 1) / item) * G;
+        int incl = mine;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) {
+            const int other = __shfl_up(incl, o, kWave);
+            if (lane >= o) incl += other;
+        }
+        if (s < shp.n_seq) plan[kPlanHeader + s] = running + incl - mine;
+        running += __shfl(incl, kWave - 1, kWave);
+    }
+    if (lane == 0) {
+        plan[kPlanHeader + shp.n_seq] = running;
+        plan[0] = 0;
+        plan[1] = running;
+        plan[2] = item;
+        plan[3] = running <= kDecodeWorkgroups ? 1 : 0;
+    }
+}
+
 struct WaveWork {
-    int seq, kvh, grp, split;
+    int seq, kvh, grp;
     int64_t pair, group_id;
     int step_begin, step_end, step_stride, step_last, len, n_tiles;
 };
 
-// A step is `tiles_per_step` consecutive 64-token tiles, handled in one pass over the rotated query.
-__device__ __forceinline__ void wave_work(const DecodeShape &shp, const int32_t *seq_lens, int wave, int tiles_per_step,
-                                          WaveWork *ww) {
-    const int n_wg_splits = shp.n_splits / kDecodeWaves;
-    const int64_t wg = blockIdx.x;
-    const int wsplit = static_cast<int>(wg % n_wg_splits);
-    ww->group_id = wg / n_wg_splits;
-    ww->split = wsplit * kDecodeWaves + wave;
-    ww->grp = static_cast<int>(ww->group_id % shp.n_row_groups);
-    ww->pair = ww->group_id / shp.n_row_groups;
-    ww->kvh = static_cast<int>(ww->pair % shp.n_kv_heads);
-    ww->seq = static_cast<int>(ww->pair / shp.n_kv_heads);
-    ww->len = min(max(seq_lens[ww->seq], 0), shp.max_len);
+// Item `it` (wave-uniform) -> the wavefront's work.
+__device__ __forceinline__ void item_work(const DecodeShape &shp, const int32_t *plan, const int32_t *seq_lens, int it,
+                                          int wave, int tiles_per_step, WaveWork *ww) {
+    const int32_t *before = plan + kPlanHeader;
+    int lo = 0, hi = shp.n_seq;          // largest s with before[s] <= it (before[n_seq] > it)
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (before[mid] <= it) lo = mid; else hi = mid;
+    }
+    const int G = shp.n_kv_heads * shp.n_row_groups;
+    const int c_s = (before[lo + 1] - before[lo]) / G;   // > 0, or `it` would not fall here
+    const int local = it - before[lo];
+    const int gis = local / c_s, chunk = local % c_s;
+    ww->seq = lo;
+    ww->group_id = static_cast<int64_t>(lo) * G + gis;
+    ww->grp = gis % shp.n_row_groups;
+    ww->kvh = gis / shp.n_row_groups;
+    ww->pair = static_cast<int64_t>(lo) * shp.n_kv_heads + ww->kvh;
+    ww->len = min(max(seq_lens[lo], 0), shp.max_len);
     ww->n_tiles = (ww->len + kWave - 1) / kWave;
     const int n_steps = (ww->n_tiles + tiles_per_step - 1) / tiles_per_step;
-    const int base = n_steps / n_wg_splits, rem = n_steps % n_wg_splits;
-    const int wb = wsplit * base + min(wsplit, rem);
-    ww->step_end = wb + base + (wsplit < rem ? 1 : 0);
+    const int base = n_steps / c_s, rem = n_steps % c_s;
+    const int wb = chunk * base + min(chunk, rem);
+    ww->step_end = wb + base + (chunk < rem ? 1 : 0);
     ww->step_begin = wb + wave;
     ww->step_stride = kDecodeWaves;
     ww->step_last = ww->step_begin + (ww->step_begin < ww->step_end
@@ -244,17 +255,95 @@ __device__ __forceinline__ void wave_work(const DecodeShape &shp, const int32_t 
                                           : 0) * ww->step_stride;
 }
 
-// D2-D4 for one step: RG scores (without gamma) of each of this lane's KPL keys, key k of the lane
-// being in tile k of the step.
-//
-// The rotated queries are wave-uniform and come through scalar loads; directions and norm centroids
-// come from the LDS tables.  The kernel runs one wavefront per SIMD, so nothing else hides the latency
-// of those loads: the triplets are processed in chunks of 24 query floats, software pipelined by one
-// chunk.  At the top of chunk c an explicit wait makes the inputs of chunk c (requested one chunk
-// earlier) complete, then the inputs of chunk c + 1 are requested (unpack, table reads, scalar query
-// loads into the other half of a double buffer), then chunk c is computed.  The explicit wait comes
-// before the new requests because scalar loads return out of order: any later wait on that queue
-// would have to drain it completely, the new requests included.
+// Takes the next item for the whole workgroup; false when none is left.  `taken` counts the calls of
+// this workgroup.  With at most one item per workgroup (plan[3] = 1: every batch of equal lengths)
+// workgroup b simply takes item b, without touching the counter.
+__device__ __forceinline__ bool next_item(int32_t *plan, int *slot, int tid, int *taken, int *it) {
+    const int n_items = plan[1];
+    if (plan[3] != 0) {
+        *it = static_cast<int>(blockIdx.x);
+        return (*taken)++ == 0 && *it < n_items;
+    }
+    ++*taken;
+    if (tid == 0) *slot = atomicAdd(&plan[0], 1);
+    __syncthreads();
+    *it = __builtin_amdgcn_readfirstlane(*slot);
+    __syncthreads();
+    return *it < n_items;
+}
+
+// Tiles per step of the split-K kernels: up to d = 128 a lane carries two keys (see the kernel).
+template <int D>
+constexpr int decode_keys_per_lane() { return D <= 128 ? 2 : 1; }
+
+// ---- D0: q_rot = scale * H (s . q), one wavefront per query row ------------------------------
+// Output layout per (sequence, KV head, row group): [QS coordinates][RG rows], so that the RG
+// values a key needs for one coordinate are adjacent.  Rows past rows_per_kv and coordinates
+// past d are written as zeros.
+template <int D, int QS>
+__global__ __launch_bounds__(kWave) void rotate_queries_kernel(const void *__restrict__ q, int q_is_bf16,
+                                                                const uint8_t *__restrict__ signs, DecodeShape s,
+                                                                float scale, float *__restrict__ q_rot,
+                                                                const int32_t *__restrict__ seq_lens,
+                                                                int32_t *__restrict__ plan) {
+    constexpr int EPL = D / kWave;  // elements per lane (1, 2, 4)
+    const int lane = threadIdx.x;
+    // block 0 also cuts the work items of the split-K kernel that follows (not used with 128-row blocks)
+    if (blockIdx.x == 0 && plan != nullptr) build_plan(s, seq_lens, decode_keys_per_lane<D>(), plan, lane);
+    const int rg = s.rows_per_pass;
+    const int padded_rows = s.n_row_groups * rg;
+    const int64_t gid = blockIdx.x;  // (seq, kvh, padded row)
+    const int row = static_cast<int>(gid % padded_rows);
+    const int kvh = static_cast<int>((gid / padded_rows) % s.n_kv_heads);
+    const int seq = static_cast<int>(gid / (static_cast<int64_t>(padded_rows) * s.n_kv_heads));
+    float *dst = q_rot + (gid / rg) * (static_cast<int64_t>(QS) * rg) + (row % rg);
+
+    float x[EPL];
+    if (row < s.rows_per_kv) {
+        const int qi = row / s.heads_per_kv;
+        const int head = kvh * s.heads_per_kv + row % s.heads_per_kv;
+        const int64_t base = ((static_cast<int64_t>(seq) * s.n_q + qi) * s.n_q_heads + head) * D + lane * EPL;
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) {
+            const int e = lane * EPL + j;
+            float val = q_is_bf16 ? __uint_as_float(static_cast<uint32_t>(static_cast<const uint16_t *>(q)[base + j]) << 16)
+                                  : static_cast<const float *>(q)[base + j];
+            const bool neg = (signs[kvh * (D / 8) + (e >> 3)] >> (e & 7)) & 1;
+            x[j] = neg ? -val : val;
+        }
+        // butterflies over the in-lane bits of the element index ...
+#pragma unroll
+        for (int h = 1; h < EPL; h <<= 1) {
+#pragma unroll
+            for (int j = 0; j < EPL; ++j) {
+                if ((j & h) == 0) {
+                    const float a = x[j], b = x[j | h];
+                    x[j] = a + b;
+                    x[j | h] = a - b;
+                }
+            }
+        }
+        // ... then over the lane bits: the element with the bit clear takes a + b, the other a - b
+#pragma unroll
+        for (int m = 1; m < kWave; m <<= 1) {
+#pragma unroll
+            for (int j = 0; j < EPL; ++j) {
+                const float other = __shfl_xor(x[j], m, kWave);
+                x[j] = (lane & m) ? other - x[j] : x[j] + other;
+            }
+        }
+        const float norm = scale * (D == 64 ? 0.125f : (D == 128 ? 0.08838834764831845f : 0.0625f));
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) x[j] *= norm;
+    } else {
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) x[j] = 0.0f;
+    }
+#pragma unroll
+    for (int j = 0; j < EPL; ++j) dst[static_cast<int64_t>(lane * EPL + j) * rg] = x[j];
+    for (int e = D + lane; e < QS; e += kWave) dst[static_cast<int64_t>(e) * rg] = 0.0f;
+}
+
 template <int REP>
 __device__ __forceinline__ uint32_t lane_part(int lane) { return (static_cast<uint32_t>(lane) & (REP - 1)) << 4; }
 
@@ -411,9 +500,6 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 // because a step's values (16 KB per 64 keys at d = 128) stay in flight in registers during the whole
 // score phase without spilling.  Up to d = 128 a lane carries two keys, so that every scalar query
 // chunk, every wave-wide maximum and every accumulator rescale serves 128 keys.
-template <int D>
-constexpr int decode_keys_per_lane() { return D <= 128 ? 2 : 1; }
-
 template <int KPL>
 constexpr int prob_row() { return KPL * kWave + 8; }  // bf16 per probability row in LDS: keys + 8 pad
 
@@ -429,7 +515,7 @@ template <class P, int RG, bool SCORES>
 __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) void decode_kernel_mfma(
     DeviceBooks books, DecodeShape shp, const float *__restrict__ q_rot, const uint4 *__restrict__ cache,
     const uint32_t *__restrict__ v, const int32_t *__restrict__ seq_lens, float *__restrict__ part_ml,
-    float *__restrict__ part_acc, float *__restrict__ scores_out) {
+    float *__restrict__ part_acc, float *__restrict__ scores_out, int32_t *__restrict__ plan) {
     constexpr int D = P::D;
     constexpr int KPL = decode_keys_per_lane<D>();
     constexpr bool AHEAD = D <= 128;       // request a step's values during the previous step's P.V
@@ -448,14 +534,14 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
     for (int e = tid; e < kDecodeWaves * 16 * PROW; e += kDecodeWaves * kWave) (&sm.pbuf[0][0][0])[e] = 0;
     build_tables<P>(sm.tb, books, tid, kDecodeWaves * kWave);
 
+    __shared__ int item_slot;
+    // per item (set in the item loop below; the helpers capture them by reference)
     WaveWork ww;
-    wave_work(shp, seq_lens, wave, KPL, &ww);
-    const float *qg = q_rot + ww.group_id * (P::QS * RG);
+    const float *qg = q_rot;
+    const char *k_region = reinterpret_cast<const char *>(cache);
+    const char *v_pair = reinterpret_cast<const char *>(v);
     const int n16 = lane & 15, g4 = lane >> 4;
-    // Addresses are a wave-uniform base (scalar registers) plus a small per-lane byte offset.
-    const char *k_region = reinterpret_cast<const char *>(cache) + ww.pair * shp.t_capacity * (P::GRANULES * 16);
     const uint32_t k_lane = lane * 16u;
-    const char *v_pair = reinterpret_cast<const char *>(v) + ww.pair * shp.t_capacity * ROWB;
     // Byte offsets of this lane's channels in its rows 32 ks + 4 j + g4: one register per JB values of j,
     // the others reached by immediate offsets (below 4096).
     constexpr int JB = 4096 / (4 * ROWB) < 8 ? 4096 / (4 * ROWB) : 8;
@@ -501,10 +587,6 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
     };
     float m_run[RG], l_lane[RG];
     f32x4_t acc[CPL];
-#pragma unroll
-    for (int r = 0; r < RG; ++r) { m_run[r] = -INFINITY; l_lane[r] = 0.0f; }
-#pragma unroll
-    for (int c = 0; c < CPL; ++c) acc[c] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
 
     // Values come through a buffer descriptor that covers a step's rows up to the sequence's last token
     // (rows past it read as zero; their probabilities are zero too); the descriptor of a step that does
@@ -632,36 +714,49 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
         __builtin_amdgcn_wave_barrier();
     };
     uint32_t w_a[KPL][P::NWORDS], w_b[KPL][P::NWORDS];
-    if (ww.step_begin < ww.step_end) {
-        load_records(ww.step_begin, w_a);
-        if constexpr (AHEAD) {
-            const __amdgpu_buffer_rsrc_t v_first = values_of(ww.step_begin, true);
+    int it, taken = 0;
+    while (next_item(plan, &item_slot, tid, &taken, &it)) {
+        item_work(shp, plan, seq_lens, it, wave, KPL, &ww);
+        qg = q_rot + ww.group_id * (P::QS * RG);
+        // Addresses are a wave-uniform base (scalar registers) plus a small per-lane byte offset.
+        k_region = reinterpret_cast<const char *>(cache) + ww.pair * shp.t_capacity * (P::GRANULES * 16);
+        v_pair = reinterpret_cast<const char *>(v) + ww.pair * shp.t_capacity * ROWB;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) load_values(v_first, ks, vr[ks]);
-        }
-    }
-    for (int step = ww.step_begin; step < ww.step_end; step += 2 * ww.step_stride) {
-        process_step(step, w_a, w_b);
-        if (step + ww.step_stride < ww.step_end) process_step(step + ww.step_stride, w_b, w_a);
-    }
+        for (int r = 0; r < RG; ++r) { m_run[r] = -INFINITY; l_lane[r] = 0.0f; }
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) acc[c] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
 
-    // D7: add the hi and lo partial results (lane groups RP/4 apart) and emit the wave's partial
+        if (ww.step_begin < ww.step_end) {
+            load_records(ww.step_begin, w_a);
+            if constexpr (AHEAD) {
+                const __amdgpu_buffer_rsrc_t v_first = values_of(ww.step_begin, true);
 #pragma unroll
-    for (int c = 0; c < CPL; ++c)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float tot = acc[c][i] + __shfl_down(acc[c][i], RP * 4, kWave);
-            const int r = 4 * g4 + i;
-            if (r < RG && ww.grp * RG + r < shp.rows_per_kv)
-                part_acc[((ww.group_id * RG + r) * shp.n_splits + ww.split) * D + CPL * n16 + c] = tot;
+                for (int ks = 0; ks < KS; ++ks) load_values(v_first, ks, vr[ks]);
+            }
         }
+        for (int step = ww.step_begin; step < ww.step_end; step += 2 * ww.step_stride) {
+            process_step(step, w_a, w_b);
+            if (step + ww.step_stride < ww.step_end) process_step(step + ww.step_stride, w_b, w_a);
+        }
+
+        // D7: add the hi and lo partial results (lane groups RP/4 apart) and emit the wave's partial of
+        // this item
+        const int64_t pbase = (static_cast<int64_t>(it) * kDecodeWaves + wave) * RG;
 #pragma unroll
-    for (int r = 0; r < RG; ++r) {
-        const float l = wave_sum(l_lane[r]);
-        if (lane == 0) {
-            const int64_t prow = (ww.group_id * RG + r) * shp.n_splits + ww.split;
-            part_ml[prow * 2] = m_run[r];
-            part_ml[prow * 2 + 1] = l;
+        for (int c = 0; c < CPL; ++c)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float tot = acc[c][i] + __shfl_down(acc[c][i], RP * 4, kWave);
+                const int r = 4 * g4 + i;
+                if (r < RG && ww.grp * RG + r < shp.rows_per_kv) part_acc[(pbase + r) * D + CPL * n16 + c] = tot;
+            }
+#pragma unroll
+        for (int r = 0; r < RG; ++r) {
+            const float l = wave_sum(l_lane[r]);
+            if (lane == 0) {
+                part_ml[(pbase + r) * 2] = m_run[r];
+                part_ml[(pbase + r) * 2 + 1] = l;
+            }
         }
     }
 }
@@ -679,7 +774,7 @@ template <class P, int RG>
 __global__ __launch_bounds__(kDecodeWaves *kWave) void decode_kernel_valu(
     DeviceBooks books, DecodeShape shp, const float *__restrict__ q_rot, const uint4 *__restrict__ cache,
     const float4 *__restrict__ v, const int32_t *__restrict__ seq_lens, float *__restrict__ part_ml,
-    float *__restrict__ part_acc, float *__restrict__ scores_out) {
+    float *__restrict__ part_acc, float *__restrict__ scores_out, int32_t *__restrict__ plan) {
     constexpr int D = P::D;
     constexpr int LPR = D / 8;          // lanes per value row (8 channels per lane)
     constexpr int KPL = kWave / LPR;    // value rows per wave-wide load
@@ -690,8 +785,12 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) void decode_kernel_valu(
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     build_tables<P>(sm.tb, books, tid, kDecodeWaves * kWave);
+    __shared__ int item_slot;
+    const int rl = lane % LPR, ko = lane / LPR;
+    int it, taken = 0;
+    while (next_item(plan, &item_slot, tid, &taken, &it)) {
     WaveWork ww;
-    wave_work(shp, seq_lens, wave, TPS, &ww);
+    item_work(shp, plan, seq_lens, it, wave, TPS, &ww);
     const float *qg = q_rot + ww.group_id * (P::QS * RG);
     const uint4 *region = cache + ww.pair * (shp.t_capacity * P::GRANULES);
     const int64_t v_row0 = ww.pair * shp.t_capacity;
@@ -704,7 +803,6 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) void decode_kernel_valu(
 #pragma unroll
         for (int c = 0; c < 8; ++c) acc[r][c] = 0.0f;
     }
-    const int rl = lane % LPR, ko = lane / LPR;
 
     // the splits are sized in steps of TPS tiles (shared with the bf16-value kernel); here a step is
     // simply TPS tiles one after the other
@@ -774,14 +872,15 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) void decode_kernel_valu(
 #pragma unroll
     for (int r = 0; r < RG; ++r) {
         const float l = wave_sum(l_lane[r]);
+        const int64_t prow = (static_cast<int64_t>(it) * kDecodeWaves + wave) * RG + r;
+        if (lane == 0) { part_ml[prow * 2] = m_run[r]; part_ml[prow * 2 + 1] = l; }
         if (ww.grp * RG + r >= shp.rows_per_kv) continue;
-        const int64_t prow = (ww.group_id * RG + r) * shp.n_splits + ww.split;
         if (ko == 0) {
 #pragma unroll
             for (int c = 0; c < 8; ++c) part_acc[prow * D + rl * 8 + c] = acc[r][c];
         }
-        if (lane == 0) { part_ml[prow * 2] = m_run[r]; part_ml[prow * 2 + 1] = l; }
     }
+    }   // items
 }
 
 // ---- D8: merge of the split partials, one wavefront per output row -----------------------------------
@@ -789,7 +888,8 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) void decode_kernel_valu(
 // A split without tokens has m = -inf, l = 0 and a zero accumulator, so it needs no special case.
 template <int D>
 __global__ __launch_bounds__(kWave) void merge_kernel(DecodeShape shp, const float *__restrict__ part_ml,
-                                                      const float *__restrict__ part_acc, float *__restrict__ out) {
+                                                      const float *__restrict__ part_acc,
+                                                      const int32_t *__restrict__ plan, float *__restrict__ out) {
     constexpr int CPT = D / kWave;  // channels per lane
     constexpr int UN = 8;           // partial rows in flight per lane
     __shared__ float wgt[kWave];
@@ -801,35 +901,52 @@ __global__ __launch_bounds__(kWave) void merge_kernel(DecodeShape shp, const flo
     const int kvh = head / shp.heads_per_kv;
     const int row = qi * shp.heads_per_kv + head % shp.heads_per_kv;
     const int grp = row / shp.rows_per_pass, r = row % shp.rows_per_pass;
-    const int64_t prow0 =
-        (((static_cast<int64_t>(seq) * shp.n_kv_heads + kvh) * shp.n_row_groups + grp) * shp.rows_per_pass + r) *
-        shp.n_splits;
+    // Partial j of this row is at prow0 + j * pstride, j < n_part.  Blocks of 128 rows (matrix-core kernel):
+    // one partial per split, adjacent.  Otherwise: the items of this row's (sequence, KV head, row group)
+    // are consecutive, each with one partial per wavefront, RG rows apart.
+    int64_t prow0;
+    int n_part, pstride;
+    if (plan == nullptr) {
+        prow0 = (((static_cast<int64_t>(seq) * shp.n_kv_heads + kvh) * shp.n_row_groups + grp) * shp.rows_per_pass + r) *
+                shp.n_splits;
+        n_part = shp.n_splits;
+        pstride = 1;
+    } else {
+        const int G = shp.n_kv_heads * shp.n_row_groups;
+        const int before = plan[kPlanHeader + seq];
+        const int c_s = (plan[kPlanHeader + seq + 1] - before) / G;
+        const int64_t first = before + static_cast<int64_t>(kvh * shp.n_row_groups + grp) * c_s;
+        prow0 = first * kDecodeWaves * shp.rows_per_pass + r;
+        n_part = c_s * kDecodeWaves;
+        pstride = shp.rows_per_pass;
+    }
     float m = -INFINITY;
-    for (int j = lane; j < shp.n_splits; j += kWave) m = fmaxf(m, part_ml[(prow0 + j) * 2]);
+    for (int j = lane; j < n_part; j += kWave) m = fmaxf(m, part_ml[(prow0 + static_cast<int64_t>(j) * pstride) * 2]);
     m = wave_max(m);
     float a[CPT];
 #pragma unroll
     for (int c = 0; c < CPT; ++c) a[c] = 0.0f;
     float l = 0.0f;
-    for (int j0 = 0; j0 < shp.n_splits; j0 += kWave) {
+    for (int j0 = 0; j0 < n_part; j0 += kWave) {
         const int j = j0 + lane;
         float f = 0.0f;
-        if (j < shp.n_splits) {
-            const float2 ml = *reinterpret_cast<const float2 *>(part_ml + (prow0 + j) * 2);
+        if (j < n_part) {
+            const float2 ml = *reinterpret_cast<const float2 *>(part_ml + (prow0 + static_cast<int64_t>(j) * pstride) * 2);
             f = (ml.x == -INFINITY) ? 0.0f : exp2f((ml.x - m) * kLog2e);
             l += f * ml.y;
         }
         __syncthreads();
         wgt[lane] = f;
         __syncthreads();
-        const int nj = min(kWave, shp.n_splits - j0);
+        const int nj = min(kWave, n_part - j0);
         for (int jj = 0; jj < nj; jj += UN) {
             float x[UN][CPT];
 #pragma unroll
             for (int u = 0; u < UN; ++u)
 #pragma unroll
                 for (int c = 0; c < CPT; ++c)
-                    x[u][c] = part_acc[(prow0 + j0 + min(jj + u, nj - 1)) * D + c * kWave + lane];
+                    x[u][c] = part_acc[(prow0 + static_cast<int64_t>(j0 + min(jj + u, nj - 1)) * pstride) * D +
+                                       c * kWave + lane];
 #pragma unroll
             for (int u = 0; u < UN; ++u) {
                 const float fj = (jj + u < nj) ? wgt[jj + u] : 0.0f;
@@ -851,26 +968,25 @@ int launch_decode_mq(const octopus_codebooks_t &cb, const DecodeShape &s, const 
 template <class P, int RG>
 int launch_decode_rg(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
                      const void *v, int v_dtype, const int32_t *seq_lens, float *part_ml, float *part_acc,
-                     float *scores_out, hipStream_t stream) {
+                     float *scores_out, int32_t *plan, hipStream_t stream) {
     DeviceBooks books;
     for (int c = 0; c < 2; ++c) {
         for (int k = 0; k < 32; ++k) books.c_xi[c][k] = cb.c_xi[c][k];
         for (int k = 0; k < 8; ++k) books.c_rho[c][k] = cb.c_rho[c][k];
     }
-    // n_splits is a multiple of the wavefronts per workgroup
-    const int64_t wgs = static_cast<int64_t>(s.n_seq) * s.n_kv_heads * s.n_row_groups * (s.n_splits / kDecodeWaves);
-    const dim3 grid(static_cast<unsigned>(wgs));
+    // one workgroup per compute unit; they share the items of the plan
+    const dim3 grid(kDecodeWorkgroups);
     const dim3 block(kDecodeWaves * kWave);
     hipError_t err;
     if (v_dtype == OCTOPUS_DTYPE_BF16) {
         if (scores_out != nullptr) {
             hipLaunchKernelGGL((decode_kernel_mfma<P, RG, true>), grid, block, 0, stream, books, s, q_rot,
                                static_cast<const uint4 *>(cache), static_cast<const uint32_t *>(v), seq_lens,
-                               part_ml, part_acc, scores_out);
+                               part_ml, part_acc, scores_out, plan);
         } else {
             hipLaunchKernelGGL((decode_kernel_mfma<P, RG, false>), grid, block, 0, stream, books, s, q_rot,
                                static_cast<const uint4 *>(cache), static_cast<const uint32_t *>(v), seq_lens,
-                               part_ml, part_acc, scores_out);
+                               part_ml, part_acc, scores_out, plan);
         }
     } else {
         const size_t smem = sizeof(DecodeSmemValu<P, RG>);
@@ -879,7 +995,7 @@ int launch_decode_rg(const octopus_codebooks_t &cb, const DecodeShape &s, const 
         if (err != hipSuccess) return static_cast<int>(err);
         hipLaunchKernelGGL((decode_kernel_valu<P, RG>), grid, block, smem, stream, books, s, q_rot,
                            static_cast<const uint4 *>(cache), static_cast<const float4 *>(v), seq_lens, part_ml,
-                           part_acc, scores_out);
+                           part_acc, scores_out, plan);
     }
     return static_cast<int>(hipGetLastError());
 }
@@ -887,12 +1003,12 @@ int launch_decode_rg(const octopus_codebooks_t &cb, const DecodeShape &s, const 
 template <class P>
 int launch_decode_plan(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
                        const void *v, int v_dtype, const int32_t *seq_lens, float *part_ml, float *part_acc,
-                       float *scores_out, hipStream_t stream) {
+                       float *scores_out, int32_t *plan, hipStream_t stream) {
     switch (s.rows_per_pass) {
-        case 1: return launch_decode_rg<P, 1>(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, stream);
-        case 2: return launch_decode_rg<P, 2>(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, stream);
-        case 4: return launch_decode_rg<P, 4>(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, stream);
-        case 8: return launch_decode_rg<P, 8>(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, stream);
+        case 1: return launch_decode_rg<P, 1>(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, plan, stream);
+        case 2: return launch_decode_rg<P, 2>(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, plan, stream);
+        case 4: return launch_decode_rg<P, 4>(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, plan, stream);
+        case 8: return launch_decode_rg<P, 8>(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, plan, stream);
         case 128:
             if constexpr (P::D <= 128) {
                 if (v_dtype == OCTOPUS_DTYPE_BF16 && scores_out == nullptr)

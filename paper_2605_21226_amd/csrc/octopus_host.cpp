@@ -238,8 +238,16 @@ DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t
         const int64_t groups = static_cast<int64_t>(n_seq) * n_kv_heads * s.n_row_groups;
         const int64_t max_tiles = (len + OCTOPUS_TILE - 1) / OCTOPUS_TILE;
         const int64_t slots = 256 * (plan.head_dim <= 64 ? 2 : 1);
-        const int64_t want = (slots + groups / 2) / groups;
-        s.n_splits = static_cast<int32_t>(std::max<int64_t>(1, std::min<int64_t>(want, max_tiles)));
+        // The workgroups run in rounds of `slots`; pick the split count (each split keeping at least 16
+        // tiles) whose last round is fullest, the smallest such count on ties.
+        int64_t best = 1;
+        double best_eff = 0.0;
+        for (int64_t n = 1; n <= 32 && (n == 1 || max_tiles / n >= 16); ++n) {
+            const int64_t wgs = groups * n, rounds = (wgs + slots - 1) / slots;
+            const double eff = static_cast<double>(wgs) / static_cast<double>(rounds * slots);
+            if (eff > best_eff + 1e-9) { best_eff = eff; best = n; }
+        }
+        s.n_splits = static_cast<int32_t>(best);
         return s;
     }
     // Query rows scored per key by one workgroup: the power of two covering rows_per_kv, at most 8.
@@ -258,7 +266,10 @@ DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t
     // workgroups of 4 wavefronts: splits come in fours
     int64_t want = (slots / 4 + groups / 2) / groups;
     want = std::max<int64_t>(1, std::min<int64_t>(want, (max_steps + 3) / 4));
-    s.n_splits = static_cast<int32_t>(4 * want);
+    s.n_splits = static_cast<int32_t>(4 * want);   // kept for reference; the device cuts the items itself
+    // The device cuts the work into at most 256 * 8 items plus one more per (sequence, KV head, row group)
+    // (the rounding of each one's share), see the plan in the kernels.
+    s.max_items = static_cast<int32_t>(std::min<int64_t>(256 * 8 + groups, groups * std::max<int64_t>(max_steps, 1)));
     return s;
 }
 
@@ -271,13 +282,18 @@ Workspace make_workspace(const octopus_plan_t &plan, const DecodeShape &s) {
     auto up = [](size_t x) { return (x + 255) & ~static_cast<size_t>(255); };
     Workspace w{};
     const size_t rows = static_cast<size_t>(s.n_seq) * s.n_kv_heads * s.n_row_groups * s.rows_per_pass;
+    // partial results: one per (row, split) with 128-row blocks, else one per (item, wavefront, row of the group)
+    const size_t partials = s.rows_per_pass == 128 ? rows * s.n_splits
+                                                   : static_cast<size_t>(s.max_items) * 4 * s.rows_per_pass;
     w.q_rot_off = 0;
     const size_t q_bytes = up(rows * q_row_stride(plan.n_tri) * sizeof(float));
     w.part_ml_off = q_bytes;
-    const size_t ml_bytes = up(rows * s.n_splits * 2 * sizeof(float));
+    const size_t ml_bytes = up(partials * 2 * sizeof(float));
     w.part_acc_off = w.part_ml_off + ml_bytes;
-    const size_t acc_bytes = up(rows * s.n_splits * static_cast<size_t>(plan.head_dim) * sizeof(float));
-    w.total = w.part_acc_off + acc_bytes;
+    const size_t acc_bytes = up(partials * static_cast<size_t>(plan.head_dim) * sizeof(float));
+    w.plan_off = w.part_acc_off + acc_bytes;
+    const size_t plan_bytes = up((static_cast<size_t>(s.n_seq) + 5) * sizeof(int32_t));
+    w.total = w.plan_off + plan_bytes;
     return w;
 }
 
@@ -435,14 +451,16 @@ int octopus_attn_decode(const octopus_codebooks_t *cb, const void *q, int32_t q_
     float *q_rot = reinterpret_cast<float *>(base + w.q_rot_off);
     float *part_ml = reinterpret_cast<float *>(base + w.part_ml_off);
     float *part_acc = reinterpret_cast<float *>(base + w.part_acc_off);
-    int err = launch_rotate_queries(cb->plan, q, q_dtype, signs, s, scale, q_rot, stream);
+    int32_t *work_plan = many_rows ? nullptr : reinterpret_cast<int32_t *>(base + w.plan_off);
+    int err = launch_rotate_queries(cb->plan, q, q_dtype, signs, s, scale, q_rot, seq_lens, work_plan, stream);
     void *ev_before = g_event_before, *ev_after = g_event_after;
     g_event_before = g_event_after = nullptr;
     if (err == 0 && ev_before != nullptr) err = record_event(ev_before, stream);
     if (err == 0)
-        err = launch_decode(*cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, stream);
+        err = launch_decode(*cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, work_plan,
+                            stream);
     if (err == 0 && ev_after != nullptr) err = record_event(ev_after, stream);
-    if (err == 0) err = launch_merge(cb->plan, s, part_ml, part_acc, out, stream);
+    if (err == 0) err = launch_merge(cb->plan, s, part_ml, part_acc, work_plan, out, stream);
     return err == 0 ? OCTOPUS_OK : OCTOPUS_EHIP;
 }
 

@@ -26,13 +26,14 @@ struct DecodeShape {
     int32_t rows_per_pass;  // query rows one workgroup scores per key (1, 2, 4 or 8; 128: matrix-core kernel)
     int32_t n_row_groups;   // ceil(rows_per_kv / rows_per_pass)
     int32_t n_splits;       // wavefronts (workgroups at 128 rows) sharing the tiles of one (sequence, KV head, row group)
+    int32_t max_items;      // bound of the work items the device cuts (row groups of at most 8)
     int32_t max_len;        // host-side bound of the sequence lengths
     int64_t t_capacity;
 };
 
 // Workspace carve-up (all offsets multiples of 256 bytes).
 struct Workspace {
-    size_t q_rot_off, part_ml_off, part_acc_off, total;
+    size_t q_rot_off, part_ml_off, part_acc_off, plan_off, total;
 };
 
 DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads,
@@ -40,13 +41,16 @@ DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t
 Workspace make_workspace(const octopus_plan_t &plan, const DecodeShape &s);
 
 // Kernel launchers (defined in the .hip files).  Each returns a hipError_t cast to int.
+// `work_plan`: device array the rotation kernel fills with the work items of the split-K kernel (NULL with
+// 128-row blocks, which are split on the host).
 int launch_rotate_queries(const octopus_plan_t &plan, const void *q, int q_dtype, const uint8_t *signs,
-                          const DecodeShape &s, float scale, float *q_rot, void *stream);
+                          const DecodeShape &s, float scale, float *q_rot, const int32_t *seq_lens,
+                          int32_t *work_plan, void *stream);
 int launch_decode(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
                   const void *v, int v_dtype, const int32_t *seq_lens, float *part_ml, float *part_acc,
-                  float *scores_out, void *stream);
+                  float *scores_out, int32_t *work_plan, void *stream);
 int launch_merge(const octopus_plan_t &plan, const DecodeShape &s, const float *part_ml, const float *part_acc,
-                 float *out, void *stream);
+                 const int32_t *work_plan, float *out, void *stream);
 int launch_encode(const octopus_codebooks_t &cb, const void *keys, int key_dtype, int64_t stride_seq,
                   int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
                   const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos, void *stream);
