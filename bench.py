@@ -26,6 +26,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 FP32_VALU_PEAK_TFLOPS = 157.3  # MI355X published fp32 vector peak
+BF16_MFMA_PEAK_TFLOPS = 2500.0 # MI355X published dense bf16 matrix peak
 
 
 def parse():
@@ -57,15 +58,17 @@ def cpu_baseline(wl, keys, vals, q, signs, scale, record_bytes, budget_s=12.0):
     enc_s = dec_s = 0.0
     n_seq_done = 0
     for s in range(wl.n_seq):
-        k_host = keys[s].float().cpu().numpy().astype(np.float64)            # [n_tok, n_kv, d]
+        k_host = keys[s, :n_tok].float().cpu().numpy().astype(np.float64)    # [n_tok, n_kv, d]
         v_host = vals[s].float().cpu().numpy().astype(np.float64)            # [n_kv, n_tok, d]
-        q_host = q[s, 0].float().cpu().numpy().astype(np.float64)            # [n_qh, d]
+        nq_s = min(wl.n_q, 4)                                                # a few queries of a chunk
+        q_host = q[s, :nq_s].float().cpu().numpy().astype(np.float64)        # [nq_s, n_qh, d]
         k_heads = [np.ascontiguousarray(k_host[:, h]) for h in range(wl.n_kv_heads)]
         t0 = time.perf_counter()
         recs = [oracle.encode(plan, k_heads[h], signs[h]) for h in range(wl.n_kv_heads)]
         t1 = time.perf_counter()
         for h in range(wl.n_kv_heads):
-            oracle.attention(plan, recs[h], signs[h], q_host[h * g:(h + 1) * g], v_host[h], scale)
+            oracle.attention(plan, recs[h], signs[h], q_host[:, h * g:(h + 1) * g].reshape(-1, wl.head_dim),
+                             v_host[h][:n_tok], scale)
         t2 = time.perf_counter()
         enc_s += t1 - t0
         dec_s += t2 - t1
@@ -82,7 +85,9 @@ def cpu_baseline(wl, keys, vals, q, signs, scale, record_bytes, budget_s=12.0):
         "cores": min(threads, os.cpu_count() or threads),
         "kind": "oracle",
         "sample": f"{n_seq_done} of {wl.n_seq} sequences of the workload, each {wl.n_kv_heads} KV heads x {n_tok} "
-                  f"tokens ({n_keys} keys in all), {g} query heads per KV head; fp64 oracle, OpenMP over keys",
+                  f"tokens ({n_keys} keys in all), {g} query heads per KV head"
+                  + (f", {min(wl.n_q, 4)} of the {wl.n_q} queries" if wl.n_q > 1 else "")
+                  + "; fp64 oracle, OpenMP over keys",
         "decode_seconds": round(dec_s, 3),
         "encode_seconds": round(enc_s, 3),
         "encode_mtokens_per_s": round(n_seq_done * n_tok / enc_s / 1e6, 4),
@@ -125,27 +130,36 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     wl = synth.WORKLOADS[args.workload]
-    if wl.n_q != 1:
-        print("bench.py: only single-query decode workloads are timed here", file=sys.stderr)
-        sys.exit(2)
+    many_rows = wl.n_q > 1
 
     cb = binding.octopus_build_codebooks(wl.head_dim, wl.bits)
     keys, vals, q, signs, lens = device_inputs(wl, args.seed, dev)
-    cap = wl.n_tokens
+    cap = -(-wl.n_tokens // 64) * 64
+    if cap != wl.n_tokens:                      # the values need t_capacity rows
+        padded = torch.zeros((wl.n_seq, wl.n_kv_heads, cap, wl.head_dim), dtype=vals.dtype, device=dev)
+        padded[:, :, :wl.n_tokens] = vals
+        vals = padded
     sbits = torch.from_numpy(synth.sign_bits(signs)).to(dev)
     cache = torch.zeros(binding.octopus_cache_bytes(cb, wl.n_seq, wl.n_kv_heads, cap), dtype=torch.uint8, device=dev)
     max_len = int(lens.max())
-    ws = torch.empty(binding.octopus_attn_decode_workspace(cb, wl.n_seq, wl.n_q_heads, wl.n_kv_heads, 1, max_len),
+    ws = torch.empty(binding.octopus_attn_decode_workspace(cb, wl.n_seq, wl.n_q_heads, wl.n_kv_heads, wl.n_q, max_len),
                      dtype=torch.uint8, device=dev)
-    out = torch.zeros((wl.n_seq, 1, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device=dev)
+    out = torch.zeros((wl.n_seq, wl.n_q, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device=dev)
     lens_dev = torch.from_numpy(lens).to(dev)
     scale = 1.0 / float(np.sqrt(wl.head_dim))
-    n_new = wl.n_tokens  # prefill-time encode of the whole cache
+    # single-query workloads: prefill-time encode of the whole cache; a chunk workload: the cache is
+    # filled up to the chunk once, and a step encodes the chunk's tokens at their position
+    n_new = wl.n_new if many_rows else wl.n_tokens
+    first = wl.n_tokens - n_new
+    start_dev = None
+    if first > 0:
+        binding.octopus_encode(cb, keys[:, :first], sbits, cache, cap)
+        start_dev = torch.full((wl.n_seq,), first, dtype=torch.int32, device=dev)
 
     def step(ev=None):
         if ev:
             ev[0].record()
-        binding.octopus_encode(cb, keys[:, :n_new], sbits, cache, cap)
+        binding.octopus_encode(cb, keys[:, first:], sbits, cache, cap, start_dev)
         if ev:
             ev[1].record()
             binding.octopus_profile_events(ev[3], ev[4])  # around the fused kernel inside the next call
@@ -175,7 +189,7 @@ def main():
     n_keys_dec = int(lens.astype(np.int64).sum()) * wl.n_kv_heads
     n_keys_enc = wl.n_seq * n_new * wl.n_kv_heads
     rec_bytes = cb.plan.record_bytes
-    q_out_bytes = wl.n_seq * wl.n_q_heads * wl.head_dim * (elt + 4)
+    q_out_bytes = wl.n_seq * wl.n_q * wl.n_q_heads * wl.head_dim * (elt + 4)
     dec_bytes = n_keys_dec * (rec_bytes + wl.head_dim * elt) + q_out_bytes
     dec_s = float(dec_ms.mean()) * 1e-3
     enc_s = float(enc_ms.mean()) * 1e-3
@@ -199,8 +213,9 @@ def main():
         "config": {
             "workload": f"{wl.name}: batch {wl.n_seq}, {wl.n_q_heads} query / {wl.n_kv_heads} KV heads, head_dim "
                         f"{wl.head_dim}, {wl.n_tokens} cached tokens, {wl.dtype} K/V/Q, {wl.bits:g} bits/coordinate "
-                        f"(b_dir {cb.plan.b_dir[0]}, b_nrm {cb.plan.b_nrm[0]}); step = encode of all "
-                        f"{wl.n_seq * n_new} tokens + one decode-attention call",
+                        f"(b_dir {cb.plan.b_dir[0]}, b_nrm {cb.plan.b_nrm[0]}); step = encode of "
+                        f"{wl.n_seq * n_new} tokens + one decode-attention call"
+                        + (f" of {wl.n_q} queries per sequence" if many_rows else ""),
             "record_bytes": rec_bytes,
             "keys": n_keys_dec,
         },
@@ -224,6 +239,18 @@ def main():
         },
     }
     result["roofline"]["traffic"] = measured_traffic(wl.name)
+    if many_rows and wl.head_dim <= 128 and wl.n_q * (wl.n_q_heads // wl.n_kv_heads) >= 32 and wl.dtype == "bf16":
+        # hundreds of query rows per key: a dense contraction on the matrix cores, 4 d flops per (query row, key)
+        flops = 4.0 * wl.head_dim * wl.n_q * wl.n_q_heads * float(lens.astype(np.int64).sum())
+        tf = flops / ker_s / 1e12
+        result["roofline"].update({
+            "kernel": "decode_kernel_mq (decode attention for many query rows on the matrix cores), timed with HIP "
+                      "events recorded by the library around its launch on the launch stream",
+            "bound": "mfma", "achieved": round(tf, 2), "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(tf / BF16_MFMA_PEAK_TFLOPS, 4), "dense_flops_per_launch": flops,
+            "note": "achieved counts the flops of dense attention on the reconstructed keys (2 d for q.k and 2 d for "
+                    "p.v per query row and key); the kernel issues 2.5 times as many bf16 matrix flops, because "
+                    "scores and probabilities go through the bf16 units as hi + lo pairs to keep fp32 accuracy"})
     if args.calibration_copy:
         src = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
