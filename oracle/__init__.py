@@ -77,6 +77,17 @@ def _load():
         lib.oracle_attention.argtypes = [P, vp, ctypes.c_int64, vp, vp, ctypes.c_int, vp,
                                          ctypes.c_double, vp, vp, vp]
         lib.oracle_classify.argtypes = [P, vp, ctypes.c_int64, vp, vp, ctypes.c_double, vp]
+        lib.oracle_round_fp16.argtypes = [ctypes.c_double]
+        lib.oracle_round_fp16.restype = ctypes.c_double
+        lib.oracle_qjl_encode_key.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp]
+        lib.oracle_qjl_encode_key.restype = None
+        lib.oracle_qjl_encode.argtypes = [P, vp, ctypes.c_int64, vp, vp, vp, vp, vp]
+        lib.oracle_qjl_encode.restype = None
+        lib.oracle_qjl_estimate.argtypes = [vp, vp, vp, ctypes.c_double, ctypes.c_int]
+        lib.oracle_qjl_estimate.restype = ctypes.c_double
+        lib.oracle_attention_qjl.argtypes = [P, vp, ctypes.c_int64, vp, vp, vp, vp, vp, ctypes.c_int, vp,
+                                             ctypes.c_double, vp, vp]
+        lib.oracle_attention_qjl.restype = None
         for name in ("oracle_hadamard", "oracle_rotate", "oracle_rotate_inverse", "oracle_oct_encode",
                      "oracle_oct_decode", "oracle_encode_key", "oracle_pack_record",
                      "oracle_unpack_record", "oracle_encode", "oracle_reconstruct",
@@ -295,3 +306,55 @@ def classify(plan, keys, signs, foreign_records, tol=1e-6):
     counts = np.zeros(3, dtype=np.int64)
     _load().oracle_classify(plan.cptr, _ptr(keys), keys.shape[0], _ptr(s), _ptr(fr), float(tol), _ptr(counts))
     return int(counts[0]), int(counts[1]), int(counts[2])
+
+
+# ---- optional 1-bit QJL residual (Sec. 3.6) -------------------------------------------------------
+
+def round_fp16(x):
+    return _load().oracle_round_fp16(float(x))
+
+
+def qjl_encode(plan, keys, signs, signs2, records):
+    """keys [n, d], canonical records [n, record_bytes] -> (sigma [n, d] int8 of +-1, gamma_r [n] fp16 values)."""
+    keys, s, s2 = _f64(keys), signs_pm1(signs), signs_pm1(signs2)
+    rec = np.ascontiguousarray(records, dtype=np.uint8)
+    n = keys.shape[0]
+    assert rec.shape == (n, plan.record_bytes)
+    sigma = np.zeros((n, plan.d), dtype=np.int8)
+    gamma_r = np.zeros(n, dtype=np.float64)
+    _load().oracle_qjl_encode(plan.cptr, _ptr(keys), n, _ptr(s), _ptr(s2), _ptr(rec), _ptr(sigma), _ptr(gamma_r))
+    return sigma, gamma_r
+
+
+def qjl_residual(plan, k, signs, signs2, idx_dir, idx_nrm):
+    """One key -> (sigma [d], gamma_r, r [d]) from explicit codes."""
+    k, s, s2 = _f64(k), signs_pm1(signs), signs_pm1(signs2)
+    a = np.ascontiguousarray(idx_dir, dtype=np.int32)
+    b = np.ascontiguousarray(idx_nrm, dtype=np.int32)
+    sigma = np.zeros(plan.d, dtype=np.int8)
+    r = np.zeros(plan.d, dtype=np.float64)
+    g = ctypes.c_double()
+    _load().oracle_qjl_encode_key(plan.cptr, _ptr(k), _ptr(s), _ptr(s2), _ptr(a), _ptr(b), _ptr(sigma), ctypes.byref(g),
+                                  _ptr(r))
+    return sigma, g.value, r
+
+
+def qjl_estimate(q_rot, signs2, sigma, gamma_r):
+    q_rot, s2 = _f64(q_rot), signs_pm1(signs2)
+    sg = np.ascontiguousarray(sigma, dtype=np.int8)
+    return _load().oracle_qjl_estimate(_ptr(q_rot), _ptr(s2), _ptr(sg), float(gamma_r), int(q_rot.shape[0]))
+
+
+def attention_qjl(plan, records, signs, signs2, sigma, gamma_r, q, v, scale):
+    """-> (scores [n_q, n], out [n_q, d]) with scores scale * (q . k^ + gamma * estimate)."""
+    records, s, s2 = np.ascontiguousarray(records, dtype=np.uint8), signs_pm1(signs), signs_pm1(signs2)
+    q, v = _f64(np.atleast_2d(q)), _f64(v)
+    n = records.shape[0]
+    sg = np.ascontiguousarray(sigma, dtype=np.int8)
+    gr = _f64(gamma_r)
+    assert sg.shape == (n, plan.d) and gr.shape == (n,) and v.shape == (n, plan.d)
+    scores = np.zeros((q.shape[0], n), dtype=np.float64)
+    out = np.zeros((q.shape[0], plan.d), dtype=np.float64)
+    _load().oracle_attention_qjl(plan.cptr, _ptr(records), n, _ptr(s), _ptr(s2), _ptr(sg), _ptr(gr), _ptr(q), q.shape[0],
+                                 _ptr(v), float(scale), _ptr(scores), _ptr(out))
+    return scores, out

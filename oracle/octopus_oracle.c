@@ -19,6 +19,10 @@
  *   scores, attention   Eq. (score-exact), Alg. 2: computed here as the plain
  *                       definition softmax(scale * q K^T) V on the
  *                       materialised reconstructed keys k^ = gamma R^T u^.
+ *   QJL side-car        Sec. 3.6 "1-bit QJL residual" and App. "QJL Residual
+ *                       Estimator": sign sketch of the rotated-frame residual
+ *                       under a second sign-flipped Hadamard rotation, residual
+ *                       norm rounded to fp16, corrected score.
  *
  * Readings where the paper is silent (all listed in the design notes):
  *   eps = 1e-20 for both clamped divisors; searchsorted counts boundaries
@@ -373,6 +377,123 @@ void oracle_attention(const oracle_plan *p, const uint8_t *records, int64_t n_ke
         free(kh);
     }
     if (form_gap) *form_gap = gap;
+    for (int qi = 0; qi < n_q; ++qi) {
+        const double *sc = scores + (size_t)qi * n_keys;
+        double *o = out + (size_t)qi * d;
+        for (int j = 0; j < d; ++j) o[j] = 0.0;
+        if (n_keys == 0) continue;
+        double m = -INFINITY;
+        for (int64_t t = 0; t < n_keys; ++t) if (sc[t] > m) m = sc[t];
+        double l = 0.0;
+        for (int64_t t = 0; t < n_keys; ++t) {
+            double w = exp(sc[t] - m);
+            l += w;
+            for (int j = 0; j < d; ++j) o[j] += w * v[t * d + j];
+        }
+        for (int j = 0; j < d; ++j) o[j] /= l;
+    }
+    free(q_rot);
+}
+
+/* ---- optional 1-bit QJL residual (Sec. 3.6) ------------------------------ */
+
+/* Nearest binary16 value (ties to even), returned as a double; values beyond
+ * the fp16 range saturate to the largest finite fp16. */
+double oracle_round_fp16(double x)
+{
+    if (x == 0.0 || x != x) return x;
+    double a = fabs(x);
+    if (a >= 65520.0) return (x < 0 ? -65504.0 : 65504.0);
+    int e;
+    frexp(a, &e);                 /* a = m * 2^e, m in [0.5, 1) */
+    int ulp_exp = e - 11;         /* 11 significant bits for normal numbers */
+    if (ulp_exp < -24) ulp_exp = -24; /* subnormal spacing 2^-24 */
+    double ulp = ldexp(1.0, ulp_exp);
+    double r = nearbyint(a / ulp) * ulp; /* default rounding mode: ties to even */
+    return x < 0 ? -r : r;
+}
+
+/* Side-car of one key from its codes: r = u - u^ in the rotated frame (u the
+ * rotated unit key, u^ the reconstruction the codes define, d coordinates),
+ * sigma = sign(H diag(s2) r) with sign(0) = +1, gamma_r = fp16(||r||_2).
+ * sigma_out[j] in {+1, -1}. */
+void oracle_qjl_encode_key(const oracle_plan *p, const double *k, const int8_t *s, const int8_t *s2,
+                           const int32_t *idx_dir, const int32_t *idx_nrm, int8_t *sigma_out,
+                           double *gamma_r_out, double *r_out)
+{
+    int d = p->d;
+    double *buf = (double *)calloc((size_t)3 * p->n_tri + 3 * d, sizeof(double));
+    double *uh = buf, *ku = buf + 3 * p->n_tri, *u = ku + d, *y = u + d;
+    double g2 = 0.0;
+    for (int j = 0; j < d; ++j) g2 += k[j] * k[j];
+    double gamma = sqrt(g2);
+    double den = (gamma > OCT_EPS) ? gamma : OCT_EPS;
+    for (int j = 0; j < d; ++j) ku[j] = k[j] / den;
+    oracle_rotate(ku, s, u, d);
+    oracle_decode_rotated(p, idx_dir, idx_nrm, uh);
+    double n2 = 0.0;
+    for (int j = 0; j < d; ++j) { ku[j] = u[j] - uh[j]; n2 += ku[j] * ku[j]; }   /* ku now holds r */
+    if (r_out) memcpy(r_out, ku, sizeof(double) * d);
+    oracle_rotate(ku, s2, y, d);
+    for (int j = 0; j < d; ++j) sigma_out[j] = (y[j] >= 0.0) ? 1 : -1;
+    *gamma_r_out = oracle_round_fp16(sqrt(n2));
+    free(buf);
+}
+
+/* Side-cars of n_keys keys whose codes are in `records` (canonical layout). */
+void oracle_qjl_encode(const oracle_plan *p, const double *keys, int64_t n_keys, const int8_t *s,
+                       const int8_t *s2, const uint8_t *records, int8_t *sigma, double *gamma_r)
+{
+    int rb = oracle_record_bytes(p), d = p->d;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < n_keys; ++t) {
+        int32_t *idx = (int32_t *)malloc(sizeof(int32_t) * 3 * p->n_tri);
+        double gamma;
+        oracle_unpack_record(p, records + t * rb, &gamma, idx, idx + 2 * p->n_tri);
+        oracle_qjl_encode_key(p, keys + t * d, s, s2, idx, idx + 2 * p->n_tri, sigma + t * d, gamma_r + t, NULL);
+        free(idx);
+    }
+}
+
+/* QJL estimate of q_rot . r:  sqrt(pi / (2 d)) * gamma_r * (H diag(s2) q_rot) . sigma */
+double oracle_qjl_estimate(const double *q_rot, const int8_t *s2, const int8_t *sigma, double gamma_r, int d)
+{
+    double *y = (double *)malloc(sizeof(double) * d);
+    oracle_rotate(q_rot, s2, y, d);
+    double acc = 0.0;
+    for (int j = 0; j < d; ++j) acc += y[j] * (double)sigma[j];
+    free(y);
+    return sqrt(M_PI / (2.0 * d)) * gamma_r * acc;
+}
+
+/* Attention with corrected scores: scale * (q . k^_t + gamma_t * estimate_t).
+ * sigma: [n_keys][d] of +-1, gamma_r: [n_keys]. */
+void oracle_attention_qjl(const oracle_plan *p, const uint8_t *records, int64_t n_keys, const int8_t *s,
+                          const int8_t *s2, const int8_t *sigma, const double *gamma_r, const double *q,
+                          int n_q, const double *v, double scale, double *scores, double *out)
+{
+    int d = p->d, rb = oracle_record_bytes(p);
+    double *q_rot = (double *)malloc(sizeof(double) * (size_t)n_q * d);
+    for (int qi = 0; qi < n_q; ++qi) oracle_rotate(q + (size_t)qi * d, s, q_rot + (size_t)qi * d, d);
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < n_keys; ++t) {
+        int32_t *idx = (int32_t *)malloc(sizeof(int32_t) * 3 * p->n_tri);
+        double *uh = (double *)malloc(sizeof(double) * 3 * p->n_tri);
+        double *kh = (double *)malloc(sizeof(double) * d);
+        double gamma;
+        oracle_unpack_record(p, records + t * rb, &gamma, idx, idx + 2 * p->n_tri);
+        oracle_decode_rotated(p, idx, idx + 2 * p->n_tri, uh);
+        oracle_rotate_inverse(uh, s, kh, d);
+        for (int qi = 0; qi < n_q; ++qi) {
+            double direct = 0.0;
+            for (int j = 0; j < d; ++j) direct += q[(size_t)qi * d + j] * (gamma * kh[j]);
+            double est = oracle_qjl_estimate(q_rot + (size_t)qi * d, s2, sigma + t * d, gamma_r[t], d);
+            scores[(size_t)qi * n_keys + t] = scale * (direct + gamma * est);
+        }
+        free(idx);
+        free(uh);
+        free(kh);
+    }
     for (int qi = 0; qi < n_q; ++qi) {
         const double *sc = scores + (size_t)qi * n_keys;
         double *o = out + (size_t)qi * d;
