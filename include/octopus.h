@@ -129,6 +129,32 @@ int octopus_encode(const octopus_codebooks_t *cb,
                    const int32_t *start_pos,
                    void *stream);
 
+/* ---- optional 1-bit QJL residual (Sec. 3.6, "OCTOPUS-QJL") ----
+ * Side-car of a key: sigma = sign(H diag(s') r) for the residual r = u - u^ of
+ * the rotated unit key (d bits) and gamma_r = ||r||_2 as fp16.  Device layout,
+ * one region per (sequence, KV head) ordered like the cache, per tile of 64
+ * tokens: [d/32 words][64 tokens] uint32 (bit j%32 of word j/32 set when
+ * sigma_j = -1; sign(0) = +1), then [64 tokens] fp16 gamma_r:
+ * 64 * (d/8 + 2) bytes per tile. */
+
+/* Bytes of the side-car buffer (0 if an argument is invalid). */
+size_t octopus_qjl_bytes(const octopus_codebooks_t *cb, int32_t n_seq, int32_t n_kv_heads, int64_t t_capacity);
+
+/* octopus_encode that also writes the side-car of every encoded token.
+ *   signs2      device, [n_kv_heads][d/8] bytes like signs: the sign vector s'
+ *               of the second rotation, drawn independently of s.
+ *   qjl         device, 4-byte aligned, octopus_qjl_bytes(...) bytes; slots of
+ *               other tokens are untouched.
+ * Other arguments and errors as octopus_encode; EINVAL if signs2 or qjl is NULL. */
+int octopus_encode_qjl(const octopus_codebooks_t *cb,
+                       const void *keys, int32_t key_dtype,
+                       int64_t stride_seq, int64_t stride_tok, int64_t stride_head,
+                       int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
+                       const uint8_t *signs, const uint8_t *signs2,
+                       void *cache, void *qjl, int64_t t_capacity,
+                       const int32_t *start_pos,
+                       void *stream);
+
 /* Bytes of device workspace octopus_attn_decode needs for these shapes
  * (rotated queries + split-K partials); 0 if an argument is invalid. */
 size_t octopus_attn_decode_workspace(const octopus_codebooks_t *cb, int32_t n_seq, int32_t n_q_heads,

@@ -18,7 +18,8 @@ MAX_LEVELS = 64
 TILE = 64
 
 EXPORTS = ("octopus_build_codebooks", "octopus_build_codebooks_pair", "octopus_cache_bytes", "octopus_encode",
-           "octopus_attn_decode_workspace", "octopus_attn_decode", "octopus_profile_events", "octopus_strerror")
+           "octopus_attn_decode_workspace", "octopus_attn_decode", "octopus_profile_events", "octopus_strerror",
+           "octopus_qjl_bytes", "octopus_encode_qjl")
 
 
 class Plan(ctypes.Structure):
@@ -78,6 +79,10 @@ def load():
     lib.octopus_cache_bytes.restype = ctypes.c_size_t
     lib.octopus_encode.argtypes = [CB, vp, i32, i64, i64, i64, i32, i32, i32, vp, vp, i64, vp, vp]
     lib.octopus_encode.restype = ctypes.c_int
+    lib.octopus_qjl_bytes.argtypes = [CB, i32, i32, i64]
+    lib.octopus_qjl_bytes.restype = ctypes.c_size_t
+    lib.octopus_encode_qjl.argtypes = [CB, vp, i32, i64, i64, i64, i32, i32, i32, vp, vp, vp, vp, i64, vp, vp]
+    lib.octopus_encode_qjl.restype = ctypes.c_int
     lib.octopus_attn_decode_workspace.argtypes = [CB, i32, i32, i32, i32, i64]
     lib.octopus_attn_decode_workspace.restype = ctypes.c_size_t
     lib.octopus_attn_decode.argtypes = [CB, vp, i32, i32, i32, i32, i32, vp, vp, i64, vp, i32, vp, i64, f32, vp, vp,
@@ -146,6 +151,21 @@ def octopus_encode(cb, keys, signs, cache, t_capacity, start_pos=None, stream=No
                                  keys.stride(2), n_seq, n_kv, n_new, _ptr(signs), _ptr(cache), int(t_capacity),
                                  _ptr(start_pos), _stream_ptr(stream))
     _check(code, "octopus_encode")
+
+
+def octopus_qjl_bytes(cb, n_seq, n_kv_heads, t_capacity):
+    return int(load().octopus_qjl_bytes(ctypes.byref(cb), int(n_seq), int(n_kv_heads), int(t_capacity)))
+
+
+def octopus_encode_qjl(cb, keys, signs, signs2, cache, qjl, t_capacity, start_pos=None, stream=None):
+    """octopus_encode plus the QJL side-car; signs2: device uint8 [n_kv_heads, d/8]; qjl: device uint8 buffer of
+    octopus_qjl_bytes(...) bytes."""
+    assert keys.dim() == 4 and keys.stride(3) == 1
+    n_seq, n_new, n_kv, _ = keys.shape
+    code = load().octopus_encode_qjl(ctypes.byref(cb), _ptr(keys), _dtype_code(keys), keys.stride(0), keys.stride(1),
+                                     keys.stride(2), n_seq, n_kv, n_new, _ptr(signs), _ptr(signs2), _ptr(cache),
+                                     _ptr(qjl), int(t_capacity), _ptr(start_pos), _stream_ptr(stream))
+    _check(code, "octopus_encode_qjl")
 
 
 def octopus_attn_decode_workspace(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len):

@@ -2,6 +2,7 @@
 #ifndef OCTOPUS_DEVICE_HPP_
 #define OCTOPUS_DEVICE_HPP_
 
+#include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
 #include <type_traits>

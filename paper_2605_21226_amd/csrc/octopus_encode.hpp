@@ -49,6 +49,7 @@ struct EncodeSmem {
     float bnd_xi[2][33];                   // boundaries, +inf padded
     float bnd_rho[2][8];
     float inv_norm[kWave];
+    float res_sq[4][kWave];                // QJL side-car: squared residual norm, partial per wavefront
 };
 
 template <int BD, int REP>
@@ -157,12 +158,18 @@ __device__ __forceinline__ void or_bits(uint32_t (*rec)[kWave], int key, int bit
 
 constexpr int kEncodeTilesPerGroup = 4;  // consecutive cache tiles per workgroup (tables are built once)
 
-template <class P, bool BF16>
+// QJL: also write the optional side-car of Sec. 3.6 (1-bit QJL residual): the residual r = u - u^ of the
+// rotated unit key replaces u in LDS as the triplets are encoded, a second sign-flipped Hadamard
+// transform follows, and the signs of its output (bit set = negative) plus ||r|| as fp16 are stored per
+// key: per tile of 64 tokens [d/32 words][64 keys] uint32, then [64 keys] fp16.
+template <class P, bool BF16, bool QJL>
 __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const void *__restrict__ keys,
                                                       int64_t stride_seq, int64_t stride_tok, int64_t stride_head,
                                                       int32_t n_new, const uint8_t *__restrict__ signs,
                                                       uint4 *__restrict__ cache, int64_t t_capacity,
-                                                      const int32_t *__restrict__ start_pos, int32_t n_kv_heads) {
+                                                      const int32_t *__restrict__ start_pos, int32_t n_kv_heads,
+                                                      const uint8_t *__restrict__ signs2,
+                                                      unsigned char *__restrict__ qjl) {
     constexpr int D = P::D;
     constexpr int LPR = D / 8;        // threads per key row in the load phase
     constexpr int RPP = 256 / LPR;    // key rows per load pass
@@ -270,23 +277,37 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
         {
             constexpr int CHUNK = (P::NTRI + 3) / 4;
             const int i_end = min(P::NTRI, (wave + 1) * CHUNK);
+            float rsq = 0.0f;
             for (int i = wave * CHUNK; i < i_end; ++i) {
                 const float x = sm.u[3 * i][lane], y = sm.u[3 * i + 1][lane], z = sm.u[3 * i + 2][lane];
                 uint32_t dir_field, nrm_index;
+                float4 nhat;
+                float rho;
                 if (P::NCLASS == 1 || i < P::NT0) {
                     encode_triplet<P::BD0, P::BN0, REP>(x, y, z, sm.lut0, sm.cell0, sm.bnd_xi[0], sm.bnd_rho[0], lane,
-                                                   &dir_field, &nrm_index);
+                                                        &dir_field, &nrm_index);
                     or_bits(sm.rec, lane, P::DIR0_BIT + i * 2 * P::BD0, 2 * P::BD0, dir_field);
                     or_bits(sm.rec, lane, P::NRM0_BIT + i * P::BN0, P::BN0, nrm_index);
+                    if constexpr (QJL) { nhat = sm.lut0[dir_field * REP + (lane & (REP - 1))]; rho = sm.c_rho[0][nrm_index]; }
                 } else {
                     if constexpr (P::NCLASS == 2) {
-                        encode_triplet<P::BD1, P::BN1, REP>(x, y, z, sm.lut1, sm.cell1, sm.bnd_xi[1], sm.bnd_rho[1], lane,
-                                                       &dir_field, &nrm_index);
+                        encode_triplet<P::BD1, P::BN1, REP>(x, y, z, sm.lut1, sm.cell1, sm.bnd_xi[1], sm.bnd_rho[1],
+                                                            lane, &dir_field, &nrm_index);
                         or_bits(sm.rec, lane, P::DIR1_BIT + (i - P::NT0) * 2 * P::BD1, 2 * P::BD1, dir_field);
                         or_bits(sm.rec, lane, P::NRM1_BIT + (i - P::NT0) * P::BN1, P::BN1, nrm_index);
+                        if constexpr (QJL) { nhat = sm.lut1[dir_field * REP + (lane & (REP - 1))]; rho = sm.c_rho[1][nrm_index]; }
                     }
                 }
+                if constexpr (QJL) {
+                    // r = u - rho^ n^ in place; the padded coordinates of the last triplet stay out of it
+                    const float r0 = x - rho * nhat.x, r1 = y - rho * nhat.y, r2 = z - rho * nhat.z;
+                    sm.u[3 * i][lane] = r0;
+                    rsq = fmaf(r0, r0, rsq);
+                    if (3 * i + 1 < D) { sm.u[3 * i + 1][lane] = r1; rsq = fmaf(r1, r1, rsq); }
+                    if (3 * i + 2 < D) { sm.u[3 * i + 2][lane] = r2; rsq = fmaf(r2, r2, rsq); }
+                }
             }
+            if constexpr (QJL) sm.res_sq[wave][lane] = rsq;
         }
         __syncthreads();
 
@@ -299,6 +320,47 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
                 dst[e] = make_uint4(sm.rec[4 * g][key], sm.rec[4 * g + 1][key], sm.rec[4 * g + 2][key],
                                     sm.rec[4 * g + 3][key]);
         }
+
+        if constexpr (QJL) {
+            // sigma = sign(H diag(s2) r): the same two radix passes, signs applied on the way in, no scaling
+            constexpr int R2 = D / 16;
+            for (int g = wave; g < D / 16; g += 4) {
+                const uint32_t sb = signs2[kvh * (D / 8) + 2 * g] | (static_cast<uint32_t>(signs2[kvh * (D / 8) + 2 * g + 1]) << 8);
+                float x[16];
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const float val = sm.u[g * 16 + e][lane];
+                    x[e] = ((sb >> e) & 1u) ? -val : val;
+                }
+                butterflies<16>(x);
+#pragma unroll
+                for (int e = 0; e < 16; ++e) sm.u[g * 16 + e][lane] = x[e];
+            }
+            __syncthreads();
+            for (int lo = wave; lo < 16; lo += 4) {
+                float x[R2];
+#pragma unroll
+                for (int e = 0; e < R2; ++e) x[e] = sm.u[e * 16 + lo][lane];
+                butterflies<R2>(x);
+#pragma unroll
+                for (int e = 0; e < R2; ++e) sm.u[e * 16 + lo][lane] = x[e];
+            }
+            __syncthreads();
+            constexpr int TQ = kWave * (D / 8 + 2);   // side-car bytes per tile
+            unsigned char *qt = qjl + ((static_cast<int64_t>(seq) * n_kv_heads + kvh) * (t_capacity / kWave) + tile) * TQ;
+            const int64_t tok = tile * kWave + lane;
+            const bool valid = tok >= tok_lo && tok < tok_hi;
+            for (int wd = wave; wd < D / 32; wd += 4) {
+                uint32_t bits = 0u;
+#pragma unroll
+                for (int e = 0; e < 32; ++e) bits |= (sm.u[32 * wd + e][lane] < 0.0f ? 1u : 0u) << e;
+                if (valid) reinterpret_cast<uint32_t *>(qt)[wd * kWave + lane] = bits;
+            }
+            if (wave == 0 && valid) {
+                const float n2 = (sm.res_sq[0][lane] + sm.res_sq[1][lane]) + (sm.res_sq[2][lane] + sm.res_sq[3][lane]);
+                reinterpret_cast<__half *>(qt + (D / 8) * kWave)[lane] = __float2half_rn(sqrtf(n2));
+            }
+        }
     }
 }
 
@@ -306,7 +368,7 @@ template <class P>
 int launch_encode_plan(const octopus_codebooks_t &cb, const void *keys, int key_dtype, int64_t stride_seq,
                        int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
                        const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos,
-                       hipStream_t stream) {
+                       const uint8_t *signs2, void *qjl, hipStream_t stream) {
     DeviceBooks books;
     for (int c = 0; c < 2; ++c) {
         for (int k = 0; k < 32; ++k) books.c_xi[c][k] = cb.c_xi[c][k];
@@ -315,12 +377,16 @@ int launch_encode_plan(const octopus_codebooks_t &cb, const void *keys, int key_
     // a start that is not a multiple of 64 makes the new tokens straddle one more tile
     const int tiles = (n_new + kWave - 1) / kWave + (start_pos ? 1 : 0);
     const dim3 grid((tiles + kEncodeTilesPerGroup - 1) / kEncodeTilesPerGroup, n_kv_heads, n_seq);
-    if (key_dtype == OCTOPUS_DTYPE_BF16) {
-        hipLaunchKernelGGL((encode_kernel<P, true>), grid, dim3(256), 0, stream, books, keys, stride_seq, stride_tok,
-                           stride_head, n_new, signs, static_cast<uint4 *>(cache), t_capacity, start_pos, n_kv_heads);
+    const bool bf16 = key_dtype == OCTOPUS_DTYPE_BF16;
+    auto go = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, grid, dim3(256), 0, stream, books, keys, stride_seq, stride_tok, stride_head, n_new,
+                           signs, static_cast<uint4 *>(cache), t_capacity, start_pos, n_kv_heads, signs2,
+                           static_cast<unsigned char *>(qjl));
+    };
+    if (qjl != nullptr) {
+        if (bf16) go(encode_kernel<P, true, true>); else go(encode_kernel<P, false, true>);
     } else {
-        hipLaunchKernelGGL((encode_kernel<P, false>), grid, dim3(256), 0, stream, books, keys, stride_seq, stride_tok,
-                           stride_head, n_new, signs, static_cast<uint4 *>(cache), t_capacity, start_pos, n_kv_heads);
+        if (bf16) go(encode_kernel<P, true, false>); else go(encode_kernel<P, false, false>);
     }
     return static_cast<int>(hipGetLastError());
 }

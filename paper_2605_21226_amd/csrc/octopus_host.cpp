@@ -385,9 +385,10 @@ static bool seed_grid_ok(const octopus_codebooks_t &cb) {
     return true;
 }
 
-int octopus_encode(const octopus_codebooks_t *cb, const void *keys, int32_t key_dtype, int64_t stride_seq,
-                   int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
-                   const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos, void *stream) {
+static int encode_checked(const octopus_codebooks_t *cb, const void *keys, int32_t key_dtype, int64_t stride_seq,
+                          int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
+                          const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos,
+                          const uint8_t *signs2, void *qjl, void *stream) {
     if (cb == nullptr || keys == nullptr || signs == nullptr || cache == nullptr) return OCTOPUS_EINVAL;
     if (n_seq < 1 || n_kv_heads < 1 || n_new < 0) return OCTOPUS_EINVAL;
     if (t_capacity < OCTOPUS_TILE || t_capacity % OCTOPUS_TILE != 0) return OCTOPUS_EINVAL;
@@ -397,11 +398,35 @@ int octopus_encode(const octopus_codebooks_t *cb, const void *keys, int32_t key_
     if (stride_seq < 0 || stride_tok < 0 || stride_head < 0) return OCTOPUS_EINVAL;
     if (stride_seq % 8 != 0 || stride_tok % 8 != 0 || stride_head % 8 != 0) return OCTOPUS_EINVAL;
     if (!aligned(keys, 16) || !aligned(cache, 16)) return OCTOPUS_EINVAL;
+    if (qjl != nullptr && !aligned(qjl, 4)) return OCTOPUS_EINVAL;
     if (start_pos == nullptr && n_new > t_capacity) return OCTOPUS_EINVAL;
     if (n_new == 0) return OCTOPUS_OK;
     const int err = launch_encode(*cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads,
-                                  n_new, signs, cache, t_capacity, start_pos, stream);
+                                  n_new, signs, cache, t_capacity, start_pos, signs2, qjl, stream);
     return err == 0 ? OCTOPUS_OK : OCTOPUS_EHIP;
+}
+
+int octopus_encode(const octopus_codebooks_t *cb, const void *keys, int32_t key_dtype, int64_t stride_seq,
+                   int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
+                   const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos, void *stream) {
+    return encode_checked(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs,
+                          cache, t_capacity, start_pos, nullptr, nullptr, stream);
+}
+
+size_t octopus_qjl_bytes(const octopus_codebooks_t *cb, int32_t n_seq, int32_t n_kv_heads, int64_t t_capacity) {
+    if (cb == nullptr || n_seq < 1 || n_kv_heads < 1 || t_capacity < OCTOPUS_TILE || t_capacity % OCTOPUS_TILE != 0)
+        return 0;
+    if (!plan_consistent(cb->plan)) return 0;
+    return static_cast<size_t>(n_seq) * n_kv_heads * static_cast<size_t>(t_capacity) * (cb->plan.head_dim / 8 + 2);
+}
+
+int octopus_encode_qjl(const octopus_codebooks_t *cb, const void *keys, int32_t key_dtype, int64_t stride_seq,
+                       int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
+                       const uint8_t *signs, const uint8_t *signs2, void *cache, void *qjl, int64_t t_capacity,
+                       const int32_t *start_pos, void *stream) {
+    if (signs2 == nullptr || qjl == nullptr) return OCTOPUS_EINVAL;
+    return encode_checked(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs,
+                          cache, t_capacity, start_pos, signs2, qjl, stream);
 }
 
 static int decode_args_ok(const octopus_codebooks_t *cb, int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads,

@@ -53,7 +53,8 @@ int launch_merge(const octopus_plan_t &plan, const DecodeShape &s, const float *
                  const int32_t *work_plan, float *out, void *stream);
 int launch_encode(const octopus_codebooks_t &cb, const void *keys, int key_dtype, int64_t stride_seq,
                   int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
-                  const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos, void *stream);
+                  const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos,
+                  const uint8_t *signs2, void *qjl, void *stream);   // qjl NULL: no side-car
 
 // hipEventRecord(event, stream); returns a hipError_t cast to int.
 int record_event(void *event, void *stream);

@@ -30,3 +30,17 @@ def cache_to_records(cache, n_seq, n_kv_heads, t_capacity, granules, record_byte
     rows = np.ascontiguousarray(cache.transpose(0, 1, 2, 4, 3, 5)).reshape(n_seq, n_kv_heads, t_capacity, granules * 16)
     n_tokens = t_capacity if n_tokens is None else n_tokens
     return rows[:, :, :n_tokens, :record_bytes].copy(), rows[:, :, :n_tokens, record_bytes:].copy()
+
+
+def qjl_to_canonical(qjl, n_seq, n_kv_heads, t_capacity, head_dim):
+    """numpy uint8 side-car image -> (sign bits uint8 [n_seq, n_kv_heads, t_capacity, d/8], bit j%8 of byte j/8
+    set when sigma_j = -1; gamma_r float16 [n_seq, n_kv_heads, t_capacity])."""
+    nw = head_dim // 32
+    tq = TILE * (head_dim // 8 + 2)
+    img = np.asarray(qjl, dtype=np.uint8).reshape(n_seq, n_kv_heads, t_capacity // TILE, tq)
+    words = np.ascontiguousarray(img[..., :nw * TILE * 4]).view(np.uint32).reshape(n_seq, n_kv_heads, t_capacity // TILE,
+                                                                                   nw, TILE)
+    words = np.ascontiguousarray(words.transpose(0, 1, 2, 4, 3)).reshape(n_seq, n_kv_heads, t_capacity, nw)
+    bits = words.view(np.uint8).reshape(n_seq, n_kv_heads, t_capacity, nw * 4)
+    gamma_r = np.ascontiguousarray(img[..., nw * TILE * 4:]).view(np.float16).reshape(n_seq, n_kv_heads, t_capacity)
+    return bits, gamma_r
