@@ -192,6 +192,30 @@ int octopus_attn_decode(const octopus_codebooks_t *cb,
                         void *workspace, size_t workspace_bytes,
                         void *stream);
 
+/* octopus_attn_decode with the QJL-corrected score of Sec. 3.6:
+ *   score_t = scale * (q . k^_t + gamma_t * sqrt(pi / (2 d)) * gamma_r,t * (H diag(s') q_rot) . sigma_t),
+ * q_rot = H diag(s) q, over a cache and side-car written by octopus_encode_qjl
+ * with the same cb, signs and signs2.
+ *   signs2, qjl as for octopus_encode_qjl (read only here).
+ *   v_dtype     BF16 only (EUNSUPPORTED otherwise).
+ * Query rows sharing a KV head (n_q * n_q_heads / n_kv_heads) are served in
+ * groups of 8, 4 or 2 rows (the most whose lookup table fits on-chip memory
+ * for this head dimension and bit width: 4 at d = 128, b = 3; 2 at d = 256,
+ * b = 3); each group reads the head's keys once.  Workspace: octopus_attn_decode_workspace(...) of the
+ * same shapes.  Other arguments and errors as octopus_attn_decode; EINVAL if
+ * signs2 or qjl is NULL. */
+int octopus_attn_decode_qjl(const octopus_codebooks_t *cb,
+                            const void *q, int32_t q_dtype,
+                            int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q,
+                            const uint8_t *signs, const uint8_t *signs2,
+                            const void *cache, const void *qjl, int64_t t_capacity,
+                            const void *v, int32_t v_dtype,
+                            const int32_t *seq_lens, int64_t max_len,
+                            float scale,
+                            float *out, float *scores_out,
+                            void *workspace, size_t workspace_bytes,
+                            void *stream);
+
 /* Measurement aid (not part of the method): the next octopus_attn_decode call made by this thread
  * records the HIP events `before` and `after` (hipEvent_t passed as void*, caller-owned, created
  * with timing enabled) on the call's stream immediately before and after the launch of the fused

@@ -19,7 +19,7 @@ TILE = 64
 
 EXPORTS = ("octopus_build_codebooks", "octopus_build_codebooks_pair", "octopus_cache_bytes", "octopus_encode",
            "octopus_attn_decode_workspace", "octopus_attn_decode", "octopus_profile_events", "octopus_strerror",
-           "octopus_qjl_bytes", "octopus_encode_qjl")
+           "octopus_qjl_bytes", "octopus_encode_qjl", "octopus_attn_decode_qjl")
 
 
 class Plan(ctypes.Structure):
@@ -88,6 +88,9 @@ def load():
     lib.octopus_attn_decode.argtypes = [CB, vp, i32, i32, i32, i32, i32, vp, vp, i64, vp, i32, vp, i64, f32, vp, vp,
                                         vp, ctypes.c_size_t, vp]
     lib.octopus_attn_decode.restype = ctypes.c_int
+    lib.octopus_attn_decode_qjl.argtypes = [CB, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, i64, vp, i32, vp, i64, f32,
+                                            vp, vp, vp, ctypes.c_size_t, vp]
+    lib.octopus_attn_decode_qjl.restype = ctypes.c_int
     lib.octopus_profile_events.argtypes = [vp, vp]
     lib.octopus_profile_events.restype = ctypes.c_int
     lib.octopus_strerror.argtypes = [ctypes.c_int]
@@ -186,6 +189,20 @@ def octopus_attn_decode(cb, q, signs, cache, t_capacity, v, seq_lens, max_len, s
                                       int(max_len), float(scale), _ptr(out), _ptr(scores_out), _ptr(workspace),
                                       int(workspace.numel() * workspace.element_size()), _stream_ptr(stream))
     _check(code, "octopus_attn_decode")
+
+
+def octopus_attn_decode_qjl(cb, q, signs, signs2, cache, qjl, t_capacity, v, seq_lens, max_len, scale, out, workspace,
+                            scores_out=None, stream=None):
+    """octopus_attn_decode with the QJL-corrected score; signs2 and qjl as for octopus_encode_qjl; v: bf16."""
+    assert q.is_contiguous() and v.is_contiguous() and out.is_contiguous()
+    n_seq, n_q, n_qh, _ = q.shape
+    n_kv = v.shape[1]
+    code = load().octopus_attn_decode_qjl(ctypes.byref(cb), _ptr(q), _dtype_code(q), n_seq, n_qh, n_kv, n_q,
+                                          _ptr(signs), _ptr(signs2), _ptr(cache), _ptr(qjl), int(t_capacity), _ptr(v),
+                                          _dtype_code(v), _ptr(seq_lens), int(max_len), float(scale), _ptr(out),
+                                          _ptr(scores_out), _ptr(workspace),
+                                          int(workspace.numel() * workspace.element_size()), _stream_ptr(stream))
+    _check(code, "octopus_attn_decode_qjl")
 
 
 def octopus_profile_events(before, after):

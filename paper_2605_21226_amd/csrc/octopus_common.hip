@@ -11,7 +11,11 @@ bool plan_supported_d256(const octopus_plan_t &);
                            const void *, int, const int32_t *, float *, float *, float *, int32_t *, void *);      \
     int launch_encode_d##D(const octopus_codebooks_t &, const void *, int, int64_t, int64_t, int64_t, int32_t,     \
                            int32_t, int32_t, const uint8_t *, void *, int64_t, const int32_t *, const uint8_t *, void *, \
-                           void *);
+                           void *);                                                                                \
+    int launch_decode_qjl_d##D(const octopus_codebooks_t &, const DecodeShape &, const float *, const void *,      \
+                               const void *, const float *, const void *, const int32_t *, float *, float *,       \
+                               float *, int32_t *, void *);                                                        \
+    int qjl_rows_cap_d##D(const octopus_plan_t &);
 OCTOPUS_DECL(64)
 OCTOPUS_DECL(128)
 OCTOPUS_DECL(256)
@@ -41,6 +45,26 @@ int launch_decode(const octopus_codebooks_t &cb, const DecodeShape &s, const flo
     }
 }
 
+int qjl_rows_cap(const octopus_plan_t &plan) {
+    switch (plan.head_dim) {
+        case 64: return qjl_rows_cap_d64(plan);
+        case 128: return qjl_rows_cap_d128(plan);
+        case 256: return qjl_rows_cap_d256(plan);
+        default: return 0;
+    }
+}
+
+int launch_decode_qjl(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
+                      const void *qjl, const float *q2, const void *v, const int32_t *seq_lens, float *part_ml,
+                      float *part_acc, float *scores_out, int32_t *work_plan, void *stream) {
+    switch (cb.plan.head_dim) {
+        case 64: return launch_decode_qjl_d64(cb, s, q_rot, cache, qjl, q2, v, seq_lens, part_ml, part_acc, scores_out, work_plan, stream);
+        case 128: return launch_decode_qjl_d128(cb, s, q_rot, cache, qjl, q2, v, seq_lens, part_ml, part_acc, scores_out, work_plan, stream);
+        case 256: return launch_decode_qjl_d256(cb, s, q_rot, cache, qjl, q2, v, seq_lens, part_ml, part_acc, scores_out, work_plan, stream);
+        default: return static_cast<int>(hipErrorInvalidValue);
+    }
+}
+
 int launch_encode(const octopus_codebooks_t &cb, const void *keys, int key_dtype, int64_t stride_seq,
                   int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
                   const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos,
@@ -55,22 +79,23 @@ int launch_encode(const octopus_codebooks_t &cb, const void *keys, int key_dtype
 
 template <int D>
 static int rotate_d(const void *q, int q_dtype, const uint8_t *signs, const DecodeShape &s, float scale, float *q_rot,
-                    const int32_t *seq_lens, int32_t *work_plan, hipStream_t stream) {
+                    const int32_t *seq_lens, int32_t *work_plan, const uint8_t *signs2, float *q2,
+                    hipStream_t stream) {
     constexpr int QS = (3 * ((D + 2) / 3) + 3) & ~3;
     const int64_t rows = static_cast<int64_t>(s.n_seq) * s.n_kv_heads * s.n_row_groups * s.rows_per_pass;
     hipLaunchKernelGGL((rotate_queries_kernel<D, QS>), dim3(static_cast<unsigned>(rows)), dim3(kWave), 0, stream, q,
-                       q_dtype == OCTOPUS_DTYPE_BF16 ? 1 : 0, signs, s, scale, q_rot, seq_lens, work_plan);
+                       q_dtype == OCTOPUS_DTYPE_BF16 ? 1 : 0, signs, s, scale, q_rot, seq_lens, work_plan, signs2, q2);
     return static_cast<int>(hipGetLastError());
 }
 
 int launch_rotate_queries(const octopus_plan_t &plan, const void *q, int q_dtype, const uint8_t *signs,
                           const DecodeShape &s, float scale, float *q_rot, const int32_t *seq_lens,
-                          int32_t *work_plan, void *stream) {
+                          int32_t *work_plan, const uint8_t *signs2, float *q2, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     switch (plan.head_dim) {
-        case 64: return rotate_d<64>(q, q_dtype, signs, s, scale, q_rot, seq_lens, work_plan, st);
-        case 128: return rotate_d<128>(q, q_dtype, signs, s, scale, q_rot, seq_lens, work_plan, st);
-        case 256: return rotate_d<256>(q, q_dtype, signs, s, scale, q_rot, seq_lens, work_plan, st);
+        case 64: return rotate_d<64>(q, q_dtype, signs, s, scale, q_rot, seq_lens, work_plan, signs2, q2, st);
+        case 128: return rotate_d<128>(q, q_dtype, signs, s, scale, q_rot, seq_lens, work_plan, signs2, q2, st);
+        case 256: return rotate_d<256>(q, q_dtype, signs, s, scale, q_rot, seq_lens, work_plan, signs2, q2, st);
         default: return static_cast<int>(hipErrorInvalidValue);
     }
 }

@@ -285,7 +285,9 @@ __global__ __launch_bounds__(kWave) void rotate_queries_kernel(const void *__res
                                                                 const uint8_t *__restrict__ signs, DecodeShape s,
                                                                 float scale, float *__restrict__ q_rot,
                                                                 const int32_t *__restrict__ seq_lens,
-                                                                int32_t *__restrict__ plan) {
+                                                                int32_t *__restrict__ plan,
+                                                                const uint8_t *__restrict__ signs2,
+                                                                float *__restrict__ q2) {
     constexpr int EPL = D / kWave;  // elements per lane (1, 2, 4)
     const int lane = threadIdx.x;
     // block 0 also cuts the work items of the split-K kernel that follows (not used with 128-row blocks)
@@ -342,6 +344,39 @@ __global__ __launch_bounds__(kWave) void rotate_queries_kernel(const void *__res
 #pragma unroll
     for (int j = 0; j < EPL; ++j) dst[static_cast<int64_t>(lane * EPL + j) * rg] = x[j];
     for (int e = D + lane; e < QS; e += kWave) dst[static_cast<int64_t>(e) * rg] = 0.0f;
+
+    // Optional 1-bit QJL residual (Sec. 3.6): q2 = sqrt(pi / (2 d)) * H diag(s') q_rot per row, [row][d]
+    if (q2 != nullptr) {
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) {
+            const int e = lane * EPL + j;
+            const bool neg = (signs2[kvh * (D / 8) + (e >> 3)] >> (e & 7)) & 1;
+            x[j] = neg ? -x[j] : x[j];
+        }
+#pragma unroll
+        for (int h = 1; h < EPL; h <<= 1) {
+#pragma unroll
+            for (int j = 0; j < EPL; ++j) {
+                if ((j & h) == 0) {
+                    const float a = x[j], b = x[j | h];
+                    x[j] = a + b;
+                    x[j | h] = a - b;
+                }
+            }
+        }
+#pragma unroll
+        for (int m = 1; m < kWave; m <<= 1) {
+#pragma unroll
+            for (int j = 0; j < EPL; ++j) {
+                const float other = __shfl_xor(x[j], m, kWave);
+                x[j] = (lane & m) ? other - x[j] : x[j] + other;
+            }
+        }
+        // 1 / sqrt(d) of the Hadamard matrix times sqrt(pi / (2 d)) of the estimator = sqrt(pi / 2) / d
+        const float c = 1.2533141373155003f / static_cast<float>(D);
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) q2[gid * D + lane * EPL + j] = x[j] * c;
+    }
 }
 
 template <int REP>
@@ -509,13 +544,26 @@ struct DecodeSmemMfma {
     uint16_t pbuf[kDecodeWaves][16][prob_row<KPL>()];
 };
 
+// Optional 1-bit QJL residual (Sec. 3.6).  The correction of a key, sum_j sigma_j q2_j per query row, is
+// looked up a byte of sign bits at a time: entry [position][byte value][row] holds the signed sum of the 8
+// q2 coordinates of that byte.  The table is rebuilt per work item (it depends on the queries).
+template <class P, int RG>
+constexpr int qjl_table_floats() { return (P::D / 8) * 256 * RG; }
+template <class P, int RG>
+constexpr bool qjl_fits() {
+    return sizeof(DecodeSmemMfma<P, decode_keys_per_lane<P::D>()>) + qjl_table_floats<P, RG>() * 4 + 64 <= 160 * 1024;
+}
+
 // SCORES: also store the scaled scores (a second instantiation, so that the usual one carries none of
 // the addressing state of that store through its loop).
-template <class P, int RG, bool SCORES>
+// QJL: add the 1-bit QJL residual correction of Sec. 3.6 to every score (side-car `qjl`, second rotated
+// queries `q2`).
+template <class P, int RG, bool SCORES, bool QJL>
 __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) void decode_kernel_mfma(
     DeviceBooks books, DecodeShape shp, const float *__restrict__ q_rot, const uint4 *__restrict__ cache,
     const uint32_t *__restrict__ v, const int32_t *__restrict__ seq_lens, float *__restrict__ part_ml,
-    float *__restrict__ part_acc, float *__restrict__ scores_out, int32_t *__restrict__ plan) {
+    float *__restrict__ part_acc, float *__restrict__ scores_out, int32_t *__restrict__ plan,
+    const unsigned char *__restrict__ qjl, const float *__restrict__ q2) {
     constexpr int D = P::D;
     constexpr int KPL = decode_keys_per_lane<D>();
     constexpr bool AHEAD = D <= 128;       // request a step's values during the previous step's P.V
@@ -526,8 +574,11 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
     constexpr int ROWB = D * 2;            // bytes per value row
     constexpr int TILEB = P::GRANULES * kWave * 16;  // bytes per cache tile
     constexpr int PROW = prob_row<KPL>();
+    constexpr int QW = D / 32;             // sign words per key of the QJL side-car
+    constexpr int TQ = kWave * (D / 8 + 2);  // side-car bytes per tile
     // static, so that table addresses are compile-time constants that fold into the LDS instructions
     __shared__ DecodeSmemMfma<P, KPL> sm;
+    __shared__ __attribute__((aligned(16))) float qtab[QJL ? qjl_table_floats<P, RG>() : 4];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
@@ -585,6 +636,43 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
 #pragma unroll
         for (int k = 0; k < KPL; ++k) load_record(min(step * KPL + k, ww.n_tiles - 1), w[k]);
     };
+    // QJL side-car of a step: per key d / 32 words of sign bits (bit set: negative) and the fp16 residual
+    // norm; tile layout [word][key] then [key].
+    const char *j_region = reinterpret_cast<const char *>(qjl);
+    auto load_sidecar = [&](int step, uint32_t (&sc)[KPL][QW + 1]) {
+#pragma unroll
+        for (int k = 0; k < KPL; ++k) {
+            const char *src = j_region + static_cast<int64_t>(min(step * KPL + k, ww.n_tiles - 1)) * TQ;
+#pragma unroll
+            for (int wq = 0; wq < QW; ++wq)
+                sc[k][wq] = *reinterpret_cast<const uint32_t *>(src + wq * (kWave * 4) + lane * 4);
+            sc[k][QW] = *reinterpret_cast<const uint16_t *>(src + QW * (kWave * 4) + lane * 2);
+        }
+    };
+    // Sum over the d / 8 sign bytes of a key of the table rows they select: q2 . sigma per query row.
+    auto qjl_dot = [&](const uint32_t (&sc)[QW + 1], float (&corr)[RG]) {
+#pragma unroll
+        for (int r = 0; r < RG; ++r) corr[r] = 0.0f;
+#pragma unroll
+        for (int wq = 0; wq < QW; ++wq)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const uint32_t byte = (sc[wq] >> (8 * b)) & 0xffu;
+                const float *row = &qtab[((4 * wq + b) * 256 + byte) * RG];
+                if constexpr (RG == 1) {
+                    corr[0] += row[0];
+                } else if constexpr (RG == 2) {
+                    const float2 t = *reinterpret_cast<const float2 *>(row);
+                    corr[0] += t.x; corr[1] += t.y;
+                } else {
+#pragma unroll
+                    for (int h = 0; h < RG / 4; ++h) {
+                        const float4 t = *reinterpret_cast<const float4 *>(row + 4 * h);
+                        corr[4 * h] += t.x; corr[4 * h + 1] += t.y; corr[4 * h + 2] += t.z; corr[4 * h + 3] += t.w;
+                    }
+                }
+            }
+    };
     float m_run[RG], l_lane[RG];
     f32x4_t acc[CPL];
 
@@ -625,7 +713,8 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
     // and are used one call later.  The step loop below is unrolled by two with the two record buffers
     // swapping roles, so that no register copies (and no full memory wait in front of them) carry the
     // prefetched records over.
-    auto process_step = [&](int step, const uint32_t (&w)[KPL][P::NWORDS], uint32_t (&w_next)[KPL][P::NWORDS])
+    auto process_step = [&](int step, const uint32_t (&w)[KPL][P::NWORDS], uint32_t (&w_next)[KPL][P::NWORDS],
+                            const uint32_t (&sc)[KPL][QW + 1], uint32_t (&sc_next)[KPL][QW + 1])
                             __attribute__((always_inline)) {
         const int t0 = step * (KPL * kWave);
         const int n_valid = min(KPL * kWave, ww.len - t0);
@@ -639,6 +728,7 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
             for (int ks = 0; ks < KS; ++ks) load_values(v_next, ks, vr[ks]);
         }
         load_records(min(step + ww.step_stride, ww.step_last), w_next);
+        if constexpr (QJL) load_sidecar(min(step + ww.step_stride, ww.step_last), sc_next);
         // D2-D4: scores (queries carry the softmax scale already).  The query offset (always 0) is
         // laundered per step: otherwise the loop-invariant scalar loads of the whole query are hoisted
         // out of the step loop and hundreds of scalar registers spill.
@@ -650,10 +740,20 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
         for (int k = 0; k < KPL; ++k) {
             const float gamma = __uint_as_float(w[k][0]);
             const bool valid = k * kWave + lane < n_valid;
+            if constexpr (QJL) {
+                // Sec. 3.6: q . k = gamma (q_rot . u^ + gamma_r q2 . sigma), the estimator's constant is in q2
+                float corr[RG];
+                qjl_dot(sc[k], corr);
+                const float gamma_r = __half2float(__ushort_as_half(static_cast<unsigned short>(sc[k][QW])));
+#pragma unroll
+                for (int r = 0; r < RG; ++r) s[k][r] = fmaf(gamma_r, corr[r], s[k][r]);
+            }
 #pragma unroll
             for (int r = 0; r < RG; ++r) s[k][r] = valid ? s[k][r] * gamma : -INFINITY;
             if constexpr (SCORES) {
-                if (valid) store_scores<RG>(shp, ww, scores_out, t0 + k * kWave + lane, s[k]);
+                // the kernel with the residual is built once; it looks at the pointer
+                if (valid && (!QJL || scores_out != nullptr))
+                    store_scores<RG>(shp, ww, scores_out, t0 + k * kWave + lane, s[k]);
             }
         }
         // D5: online softmax, one running maximum per row for the whole wave
@@ -714,10 +814,30 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
         __builtin_amdgcn_wave_barrier();
     };
     uint32_t w_a[KPL][P::NWORDS], w_b[KPL][P::NWORDS];
+    uint32_t sc_a[KPL][QW + 1], sc_b[KPL][QW + 1];
     int it, taken = 0;
     while (next_item(plan, &item_slot, tid, &taken, &it)) {
         item_work(shp, plan, seq_lens, it, wave, KPL, &ww);
         qg = q_rot + ww.group_id * (P::QS * RG);
+        if constexpr (QJL) {
+            // Every wavefront is past the previous item here (next_item's barriers, or this is the
+            // workgroup's only item).  Thread `tid` is the byte value: entry [pos][tid][r] is the sum of
+            // the 8 coordinates of q2 at position pos, each negated where tid has its bit set.
+            const float *q2g = q2 + ww.group_id * (RG * D);
+            for (int pos = 0; pos < D / 8; ++pos)
+#pragma unroll
+                for (int r = 0; r < RG; ++r) {
+                    float t = 0.0f;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float x = q2g[r * D + 8 * pos + e];
+                        t += ((tid >> e) & 1) ? -x : x;
+                    }
+                    qtab[(pos * 256 + tid) * RG + r] = t;
+                }
+            __syncthreads();
+            j_region = reinterpret_cast<const char *>(qjl) + ww.pair * (shp.t_capacity / kWave) * TQ;
+        }
         // Addresses are a wave-uniform base (scalar registers) plus a small per-lane byte offset.
         k_region = reinterpret_cast<const char *>(cache) + ww.pair * shp.t_capacity * (P::GRANULES * 16);
         v_pair = reinterpret_cast<const char *>(v) + ww.pair * shp.t_capacity * ROWB;
@@ -728,6 +848,7 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
 
         if (ww.step_begin < ww.step_end) {
             load_records(ww.step_begin, w_a);
+            if constexpr (QJL) load_sidecar(ww.step_begin, sc_a);
             if constexpr (AHEAD) {
                 const __amdgpu_buffer_rsrc_t v_first = values_of(ww.step_begin, true);
 #pragma unroll
@@ -735,8 +856,8 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
             }
         }
         for (int step = ww.step_begin; step < ww.step_end; step += 2 * ww.step_stride) {
-            process_step(step, w_a, w_b);
-            if (step + ww.step_stride < ww.step_end) process_step(step + ww.step_stride, w_b, w_a);
+            process_step(step, w_a, w_b, sc_a, sc_b);
+            if (step + ww.step_stride < ww.step_end) process_step(step + ww.step_stride, w_b, w_a, sc_b, sc_a);
         }
 
         // D7: add the hi and lo partial results (lane groups RP/4 apart) and emit the wave's partial of
@@ -980,13 +1101,13 @@ int launch_decode_rg(const octopus_codebooks_t &cb, const DecodeShape &s, const 
     hipError_t err;
     if (v_dtype == OCTOPUS_DTYPE_BF16) {
         if (scores_out != nullptr) {
-            hipLaunchKernelGGL((decode_kernel_mfma<P, RG, true>), grid, block, 0, stream, books, s, q_rot,
+            hipLaunchKernelGGL((decode_kernel_mfma<P, RG, true, false>), grid, block, 0, stream, books, s, q_rot,
                                static_cast<const uint4 *>(cache), static_cast<const uint32_t *>(v), seq_lens,
-                               part_ml, part_acc, scores_out, plan);
+                               part_ml, part_acc, scores_out, plan, nullptr, nullptr);
         } else {
-            hipLaunchKernelGGL((decode_kernel_mfma<P, RG, false>), grid, block, 0, stream, books, s, q_rot,
+            hipLaunchKernelGGL((decode_kernel_mfma<P, RG, false, false>), grid, block, 0, stream, books, s, q_rot,
                                static_cast<const uint4 *>(cache), static_cast<const uint32_t *>(v), seq_lens,
-                               part_ml, part_acc, scores_out, plan);
+                               part_ml, part_acc, scores_out, plan, nullptr, nullptr);
         }
     } else {
         const size_t smem = sizeof(DecodeSmemValu<P, RG>);
@@ -1015,6 +1136,42 @@ int launch_decode_plan(const octopus_codebooks_t &cb, const DecodeShape &s, cons
                     return launch_decode_mq<P>(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, stream);
             }
             return static_cast<int>(hipErrorInvalidValue);
+        default: return static_cast<int>(hipErrorInvalidValue);
+    }
+}
+
+// Largest row group whose sign-byte table fits LDS beside the codebook tables (8 at d = 64, 4 at
+// d = 128, 2 at d = 256).
+template <class P, int RG>
+int launch_decode_qjl_rg(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
+                         const void *qjl, const float *q2, const void *v, const int32_t *seq_lens, float *part_ml,
+                         float *part_acc, float *scores_out, int32_t *plan, hipStream_t stream) {
+    if constexpr (qjl_fits<P, RG>()) {
+        DeviceBooks books;
+        for (int c = 0; c < 2; ++c) {
+            for (int k = 0; k < 32; ++k) books.c_xi[c][k] = cb.c_xi[c][k];
+            for (int k = 0; k < 8; ++k) books.c_rho[c][k] = cb.c_rho[c][k];
+        }
+        hipLaunchKernelGGL((decode_kernel_mfma<P, RG, true, true>), dim3(kDecodeWorkgroups),
+                           dim3(kDecodeWaves * kWave), 0, stream, books, s, q_rot, static_cast<const uint4 *>(cache),
+                           static_cast<const uint32_t *>(v), seq_lens, part_ml, part_acc, scores_out, plan,
+                           static_cast<const unsigned char *>(qjl), q2);
+        return static_cast<int>(hipGetLastError());
+    } else {
+        return static_cast<int>(hipErrorInvalidValue);
+    }
+}
+
+template <class P>
+int launch_decode_qjl_plan(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot,
+                           const void *cache, const void *qjl, const float *q2, const void *v,
+                           const int32_t *seq_lens, float *part_ml, float *part_acc, float *scores_out,
+                           int32_t *plan, hipStream_t stream) {
+    switch (s.rows_per_pass) {
+        case 1: return launch_decode_qjl_rg<P, 1>(cb, s, q_rot, cache, qjl, q2, v, seq_lens, part_ml, part_acc, scores_out, plan, stream);
+        case 2: return launch_decode_qjl_rg<P, 2>(cb, s, q_rot, cache, qjl, q2, v, seq_lens, part_ml, part_acc, scores_out, plan, stream);
+        case 4: return launch_decode_qjl_rg<P, 4>(cb, s, q_rot, cache, qjl, q2, v, seq_lens, part_ml, part_acc, scores_out, plan, stream);
+        case 8: return launch_decode_qjl_rg<P, 8>(cb, s, q_rot, cache, qjl, q2, v, seq_lens, part_ml, part_acc, scores_out, plan, stream);
         default: return static_cast<int>(hipErrorInvalidValue);
     }
 }

@@ -219,7 +219,7 @@ bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 }  // namespace
 
 DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads,
-                              int32_t n_q, int64_t max_len, int64_t t_capacity, bool many_rows) {
+                              int32_t n_q, int64_t max_len, int64_t t_capacity, bool many_rows, int32_t rows_cap) {
     DecodeShape s{};
     s.n_seq = n_seq;
     s.n_q_heads = n_q_heads;
@@ -250,10 +250,11 @@ DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t
         s.n_splits = static_cast<int32_t>(best);
         return s;
     }
-    // Query rows scored per key by one workgroup: the power of two covering rows_per_kv, at most 8.
-    // Rows beyond rows_per_kv in the last group are zero queries whose results are not stored.
+    // Query rows scored per key by one workgroup: the power of two covering rows_per_kv, at most 8
+    // (fewer with the QJL residual).  Rows beyond rows_per_kv in the last group are zero queries whose
+    // results are not stored.
     s.rows_per_pass = 1;
-    while (s.rows_per_pass < s.rows_per_kv && s.rows_per_pass < 8) s.rows_per_pass *= 2;
+    while (s.rows_per_pass < s.rows_per_kv && s.rows_per_pass < rows_cap) s.rows_per_pass *= 2;
     s.n_row_groups = (s.rows_per_kv + s.rows_per_pass - 1) / s.rows_per_pass;
     // Split-K sizing: one wavefront per split.  The decode kernel runs one wavefront per SIMD, 256
     // compute units x 4 at once; the steps (128 keys up to d = 128, 64 keys at d = 256) of each
@@ -293,7 +294,8 @@ Workspace make_workspace(const octopus_plan_t &plan, const DecodeShape &s) {
     const size_t acc_bytes = up(partials * static_cast<size_t>(plan.head_dim) * sizeof(float));
     w.plan_off = w.part_acc_off + acc_bytes;
     const size_t plan_bytes = up((static_cast<size_t>(s.n_seq) + 5) * sizeof(int32_t));
-    w.total = w.plan_off + plan_bytes;
+    w.q2_off = w.plan_off + plan_bytes;   // second rotation of the queries (QJL residual only)
+    w.total = w.q2_off + up(rows * static_cast<size_t>(plan.head_dim) * sizeof(float));
     return w;
 }
 
@@ -449,7 +451,61 @@ size_t octopus_attn_decode_workspace(const octopus_codebooks_t *cb, int32_t n_se
         const DecodeShape m = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, 0, true);
         total = std::max(total, make_workspace(cb->plan, m).total);
     }
+    // ... and of the kernel with the QJL residual, which serves smaller row groups
+    const int cap = qjl_rows_cap(cb->plan);
+    if (cap > 0) {
+        const DecodeShape j = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, 0, false, cap);
+        total = std::max(total, make_workspace(cb->plan, j).total);
+    }
     return total;
+}
+
+static int attn_decode(const octopus_codebooks_t *cb, const void *q, int32_t q_dtype, int32_t n_seq,
+                       int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q, const uint8_t *signs, const void *cache,
+                       int64_t t_capacity, const void *v, int32_t v_dtype, const int32_t *seq_lens, int64_t max_len,
+                       float scale, float *out, float *scores_out, void *workspace, size_t workspace_bytes,
+                       void *stream, bool with_qjl, const uint8_t *signs2, const void *qjl) {
+    const int ok = decode_args_ok(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len);
+    if (ok != OCTOPUS_OK) return ok;
+    if (q == nullptr || signs == nullptr || cache == nullptr || v == nullptr || seq_lens == nullptr || out == nullptr)
+        return OCTOPUS_EINVAL;
+    if (with_qjl && (signs2 == nullptr || qjl == nullptr)) return OCTOPUS_EINVAL;
+    if (t_capacity < OCTOPUS_TILE || t_capacity % OCTOPUS_TILE != 0 || max_len > t_capacity) return OCTOPUS_EINVAL;
+    if ((q_dtype != OCTOPUS_DTYPE_F32 && q_dtype != OCTOPUS_DTYPE_BF16) ||
+        (v_dtype != OCTOPUS_DTYPE_F32 && v_dtype != OCTOPUS_DTYPE_BF16))
+        return OCTOPUS_EUNSUPPORTED;
+    if (with_qjl && v_dtype != OCTOPUS_DTYPE_BF16) return OCTOPUS_EUNSUPPORTED;
+    if (!aligned(cache, 16) || !aligned(v, 16) || !aligned(q, 4) || !aligned(out, 4)) return OCTOPUS_EINVAL;
+    if (with_qjl && !aligned(qjl, 4)) return OCTOPUS_EINVAL;
+    if (!std::isfinite(scale)) return OCTOPUS_EINVAL;
+    const bool many_rows = !with_qjl && many_rows_shape(cb->plan, n_q_heads, n_kv_heads, n_q) &&
+                           v_dtype == OCTOPUS_DTYPE_BF16 && scores_out == nullptr;
+    const int rows_cap = with_qjl ? qjl_rows_cap(cb->plan) : 8;
+    if (rows_cap <= 0) return OCTOPUS_EUNSUPPORTED;
+    const DecodeShape s = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, t_capacity, many_rows,
+                                            rows_cap);
+    const Workspace w = make_workspace(cb->plan, s);
+    if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < w.total) return OCTOPUS_EWORKSPACE;
+    char *base = static_cast<char *>(workspace);
+    float *q_rot = reinterpret_cast<float *>(base + w.q_rot_off);
+    float *part_ml = reinterpret_cast<float *>(base + w.part_ml_off);
+    float *part_acc = reinterpret_cast<float *>(base + w.part_acc_off);
+    float *q2 = with_qjl ? reinterpret_cast<float *>(base + w.q2_off) : nullptr;
+    int32_t *work_plan = many_rows ? nullptr : reinterpret_cast<int32_t *>(base + w.plan_off);
+    int err = launch_rotate_queries(cb->plan, q, q_dtype, signs, s, scale, q_rot, seq_lens, work_plan, signs2, q2,
+                                    stream);
+    void *ev_before = g_event_before, *ev_after = g_event_after;
+    g_event_before = g_event_after = nullptr;
+    if (err == 0 && ev_before != nullptr) err = record_event(ev_before, stream);
+    if (err == 0) {
+        err = with_qjl ? launch_decode_qjl(*cb, s, q_rot, cache, qjl, q2, v, seq_lens, part_ml, part_acc, scores_out,
+                                           work_plan, stream)
+                       : launch_decode(*cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out,
+                                       work_plan, stream);
+    }
+    if (err == 0 && ev_after != nullptr) err = record_event(ev_after, stream);
+    if (err == 0) err = launch_merge(cb->plan, s, part_ml, part_acc, work_plan, out, stream);
+    return err == 0 ? OCTOPUS_OK : OCTOPUS_EHIP;
 }
 
 int octopus_attn_decode(const octopus_codebooks_t *cb, const void *q, int32_t q_dtype, int32_t n_seq,
@@ -457,36 +513,19 @@ int octopus_attn_decode(const octopus_codebooks_t *cb, const void *q, int32_t q_
                         int64_t t_capacity, const void *v, int32_t v_dtype, const int32_t *seq_lens,
                         int64_t max_len, float scale, float *out, float *scores_out, void *workspace,
                         size_t workspace_bytes, void *stream) {
-    const int ok = decode_args_ok(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len);
-    if (ok != OCTOPUS_OK) return ok;
-    if (q == nullptr || signs == nullptr || cache == nullptr || v == nullptr || seq_lens == nullptr || out == nullptr)
-        return OCTOPUS_EINVAL;
-    if (t_capacity < OCTOPUS_TILE || t_capacity % OCTOPUS_TILE != 0 || max_len > t_capacity) return OCTOPUS_EINVAL;
-    if ((q_dtype != OCTOPUS_DTYPE_F32 && q_dtype != OCTOPUS_DTYPE_BF16) ||
-        (v_dtype != OCTOPUS_DTYPE_F32 && v_dtype != OCTOPUS_DTYPE_BF16))
-        return OCTOPUS_EUNSUPPORTED;
-    if (!aligned(cache, 16) || !aligned(v, 16) || !aligned(q, 4) || !aligned(out, 4)) return OCTOPUS_EINVAL;
-    if (!std::isfinite(scale)) return OCTOPUS_EINVAL;
-    const bool many_rows = many_rows_shape(cb->plan, n_q_heads, n_kv_heads, n_q) && v_dtype == OCTOPUS_DTYPE_BF16 &&
-                           scores_out == nullptr;
-    const DecodeShape s = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, t_capacity, many_rows);
-    const Workspace w = make_workspace(cb->plan, s);
-    if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < w.total) return OCTOPUS_EWORKSPACE;
-    char *base = static_cast<char *>(workspace);
-    float *q_rot = reinterpret_cast<float *>(base + w.q_rot_off);
-    float *part_ml = reinterpret_cast<float *>(base + w.part_ml_off);
-    float *part_acc = reinterpret_cast<float *>(base + w.part_acc_off);
-    int32_t *work_plan = many_rows ? nullptr : reinterpret_cast<int32_t *>(base + w.plan_off);
-    int err = launch_rotate_queries(cb->plan, q, q_dtype, signs, s, scale, q_rot, seq_lens, work_plan, stream);
-    void *ev_before = g_event_before, *ev_after = g_event_after;
-    g_event_before = g_event_after = nullptr;
-    if (err == 0 && ev_before != nullptr) err = record_event(ev_before, stream);
-    if (err == 0)
-        err = launch_decode(*cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, work_plan,
-                            stream);
-    if (err == 0 && ev_after != nullptr) err = record_event(ev_after, stream);
-    if (err == 0) err = launch_merge(cb->plan, s, part_ml, part_acc, work_plan, out, stream);
-    return err == 0 ? OCTOPUS_OK : OCTOPUS_EHIP;
+    return attn_decode(cb, q, q_dtype, n_seq, n_q_heads, n_kv_heads, n_q, signs, cache, t_capacity, v, v_dtype,
+                       seq_lens, max_len, scale, out, scores_out, workspace, workspace_bytes, stream, false, nullptr,
+                       nullptr);
+}
+
+int octopus_attn_decode_qjl(const octopus_codebooks_t *cb, const void *q, int32_t q_dtype, int32_t n_seq,
+                            int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q, const uint8_t *signs,
+                            const uint8_t *signs2, const void *cache, const void *qjl, int64_t t_capacity,
+                            const void *v, int32_t v_dtype, const int32_t *seq_lens, int64_t max_len, float scale,
+                            float *out, float *scores_out, void *workspace, size_t workspace_bytes, void *stream) {
+    return attn_decode(cb, q, q_dtype, n_seq, n_q_heads, n_kv_heads, n_q, signs, cache, t_capacity, v, v_dtype,
+                       seq_lens, max_len, scale, out, scores_out, workspace, workspace_bytes, stream, true, signs2,
+                       qjl);
 }
 
 const char *octopus_strerror(int code) {

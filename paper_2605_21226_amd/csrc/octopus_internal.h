@@ -33,22 +33,30 @@ struct DecodeShape {
 
 // Workspace carve-up (all offsets multiples of 256 bytes).
 struct Workspace {
-    size_t q_rot_off, part_ml_off, part_acc_off, plan_off, total;
+    size_t q_rot_off, part_ml_off, part_acc_off, plan_off, q2_off, total;
 };
 
 DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads,
-                              int32_t n_q, int64_t max_len, int64_t t_capacity, bool many_rows);
+                              int32_t n_q, int64_t max_len, int64_t t_capacity, bool many_rows, int32_t rows_cap = 8);
 Workspace make_workspace(const octopus_plan_t &plan, const DecodeShape &s);
 
 // Kernel launchers (defined in the .hip files).  Each returns a hipError_t cast to int.
 // `work_plan`: device array the rotation kernel fills with the work items of the split-K kernel (NULL with
-// 128-row blocks, which are split on the host).
+// 128-row blocks, which are split on the host).  `q2` (NULL: not wanted): the queries rotated a second time
+// with `signs2` for the QJL residual, [padded row][head_dim].
 int launch_rotate_queries(const octopus_plan_t &plan, const void *q, int q_dtype, const uint8_t *signs,
                           const DecodeShape &s, float scale, float *q_rot, const int32_t *seq_lens,
-                          int32_t *work_plan, void *stream);
+                          int32_t *work_plan, const uint8_t *signs2, float *q2, void *stream);
 int launch_decode(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
                   const void *v, int v_dtype, const int32_t *seq_lens, float *part_ml, float *part_acc,
                   float *scores_out, int32_t *work_plan, void *stream);
+// bf16 values, row groups of at most qjl_rows_cap(plan)
+int launch_decode_qjl(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
+                      const void *qjl, const float *q2, const void *v, const int32_t *seq_lens, float *part_ml,
+                      float *part_acc, float *scores_out, int32_t *work_plan, void *stream);
+// Query rows one workgroup of the QJL decode kernel serves: the largest of 8, 4, 2, 1 whose sign-byte table
+// fits LDS beside the plan's decode tables; 0 if the plan is not built.
+int qjl_rows_cap(const octopus_plan_t &plan);
 int launch_merge(const octopus_plan_t &plan, const DecodeShape &s, const float *part_ml, const float *part_acc,
                  const int32_t *work_plan, float *out, void *stream);
 int launch_encode(const octopus_codebooks_t &cb, const void *keys, int key_dtype, int64_t stride_seq,

@@ -44,3 +44,19 @@ def qjl_to_canonical(qjl, n_seq, n_kv_heads, t_capacity, head_dim):
     bits = words.view(np.uint8).reshape(n_seq, n_kv_heads, t_capacity, nw * 4)
     gamma_r = np.ascontiguousarray(img[..., nw * TILE * 4:]).view(np.float16).reshape(n_seq, n_kv_heads, t_capacity)
     return bits, gamma_r
+
+
+def qjl_from_canonical(bits, gamma_r, t_capacity):
+    """Inverse of qjl_to_canonical: sign bits uint8 [n_seq, n_kv_heads, n_tokens, d/8] and gamma_r float16
+    [n_seq, n_kv_heads, n_tokens] -> numpy uint8 side-car image for t_capacity tokens (other slots zero)."""
+    bits = np.asarray(bits, dtype=np.uint8)
+    n_seq, n_kv, n_tok, nb = bits.shape
+    nw = nb // 4
+    full = np.zeros((n_seq, n_kv, t_capacity, nb), dtype=np.uint8)
+    full[:, :, :n_tok] = bits
+    g = np.zeros((n_seq, n_kv, t_capacity), dtype=np.float16)
+    g[:, :, :n_tok] = np.asarray(gamma_r, dtype=np.float16)
+    words = full.view(np.uint32).reshape(n_seq, n_kv, t_capacity // TILE, TILE, nw).transpose(0, 1, 2, 4, 3)
+    img = np.concatenate([np.ascontiguousarray(words).view(np.uint8).reshape(n_seq, n_kv, t_capacity // TILE, -1),
+                          g.reshape(n_seq, n_kv, t_capacity // TILE, TILE).view(np.uint8)], axis=-1)
+    return np.ascontiguousarray(img).reshape(-1)

@@ -111,6 +111,35 @@ def test_encode_and_decode_reject_bad_arguments_before_launching(lib):
     assert dec(*args(scale=float("nan"))) == binding.EINVAL
     assert binding.strerror(binding.EWORKSPACE).startswith("workspace")
 
+    # the variant with the QJL residual: same validation, plus its own arguments
+    decq = lib.octopus_attn_decode_qjl
+    argsq = lambda **k: [P, fake, 1, 2, 32, 8, 1, fake, k.get("signs2", fake), fake, k.get("qjl", fake), 4096, fake,
+                         k.get("v_dtype", 1), fake, k.get("max_len", 4096), ctypes.c_float(0.1), fake, null,
+                         k.get("ws", ctypes.c_void_p(0x10000)), k.get("ws_bytes", ws), null]
+    assert decq(*argsq(signs2=null)) == binding.EINVAL
+    assert decq(*argsq(qjl=null)) == binding.EINVAL
+    assert decq(*argsq(qjl=ctypes.c_void_p(0x1002))) == binding.EINVAL          # misaligned side-car
+    assert decq(*argsq(v_dtype=0)) == binding.EUNSUPPORTED                      # fp32 values
+    assert decq(*argsq(max_len=8192)) == binding.EINVAL
+    assert decq(*argsq(ws_bytes=ws - 1)) == binding.EWORKSPACE
+
+
+def test_qjl_sidecar_layout_round_trip():
+    from paper_2605_21226_amd import layout
+    rng = np.random.default_rng(0)
+    bits = rng.integers(0, 256, (2, 3, 100, 16), dtype=np.uint8)
+    g = rng.random((2, 3, 100)).astype(np.float16)
+    img = layout.qjl_from_canonical(bits, g, 128)
+    assert img.size == 2 * 3 * 128 * (128 // 8 + 2)
+    b2, g2 = layout.qjl_to_canonical(img, 2, 3, 128, 128)
+    assert np.array_equal(b2[:, :, :100], bits) and np.array_equal(g2[:, :, :100], g)
+    assert not b2[:, :, 100:].any() and not g2[:, :, 100:].any()
+    # word w of key t in tile T sits at byte ((T * tile_bytes) + (w * 64 + t) * 4): bit 0 of byte 4 of key 1
+    one = np.zeros((1, 1, 64, 16), dtype=np.uint8)
+    one[0, 0, 1, 4] = 1
+    img1 = layout.qjl_from_canonical(one, np.zeros((1, 1, 64), dtype=np.float16), 64)
+    assert np.flatnonzero(img1).tolist() == [(1 * 64 + 1) * 4]
+
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_lib", None)
