@@ -37,13 +37,16 @@ def parse():
     ap.add_argument("--workload", default="llama3_8b_decode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--qjl", action="store_true",
+                    help="time the variant with the 1-bit QJL residual (octopus_encode_qjl + octopus_attn_decode_qjl); "
+                         "single-query workloads only")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy (torch) three times, so that a rocprofv3 "
                          "--pmc run of this command can scale FETCH_SIZE / WRITE_SIZE by a kernel of known size")
     return ap.parse_args()
 
 
-def cpu_baseline(wl, keys, vals, q, signs, scale, record_bytes, budget_s=12.0):
+def cpu_baseline(wl, keys, vals, q, signs, scale, record_bytes, budget_s=12.0, signs2=None):
     """The oracle as it stands, timed on this machine's host cores on a bounded sample of the workload:
     whole sequences (all KV heads, all cached tokens; encode, then attention of each KV head's group of
     query heads over its tokens), one sequence after another until about `budget_s` seconds are spent."""
@@ -65,10 +68,16 @@ def cpu_baseline(wl, keys, vals, q, signs, scale, record_bytes, budget_s=12.0):
         k_heads = [np.ascontiguousarray(k_host[:, h]) for h in range(wl.n_kv_heads)]
         t0 = time.perf_counter()
         recs = [oracle.encode(plan, k_heads[h], signs[h]) for h in range(wl.n_kv_heads)]
+        if signs2 is not None:
+            side = [oracle.qjl_encode(plan, k_heads[h], signs[h], signs2[h], recs[h]) for h in range(wl.n_kv_heads)]
         t1 = time.perf_counter()
         for h in range(wl.n_kv_heads):
-            oracle.attention(plan, recs[h], signs[h], q_host[:, h * g:(h + 1) * g].reshape(-1, wl.head_dim),
-                             v_host[h][:n_tok], scale)
+            qq = q_host[:, h * g:(h + 1) * g].reshape(-1, wl.head_dim)
+            if signs2 is not None:
+                oracle.attention_qjl(plan, recs[h], signs[h], signs2[h], side[h][0], side[h][1], qq, v_host[h][:n_tok],
+                                     scale)
+            else:
+                oracle.attention(plan, recs[h], signs[h], qq, v_host[h][:n_tok], scale)
         t2 = time.perf_counter()
         enc_s += t1 - t0
         dec_s += t2 - t1
@@ -77,7 +86,7 @@ def cpu_baseline(wl, keys, vals, q, signs, scale, record_bytes, budget_s=12.0):
             break
     n_keys = n_seq_done * n_tok * wl.n_kv_heads
     elt = 2 if wl.dtype == "bf16" else 4
-    dec_bytes = n_keys * (record_bytes + wl.head_dim * elt)
+    dec_bytes = n_keys * (record_bytes + wl.head_dim * elt + (wl.head_dim // 8 + 2 if signs2 is not None else 0))
     threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     return {
         "value": round(dec_bytes / dec_s / 1e9, 4),
@@ -131,6 +140,9 @@ def main():
     torch.cuda.set_device(0)
     wl = synth.WORKLOADS[args.workload]
     many_rows = wl.n_q > 1
+    if args.qjl and many_rows:
+        print("bench.py: --qjl times single-query workloads only", file=sys.stderr)
+        sys.exit(2)
 
     cb = binding.octopus_build_codebooks(wl.head_dim, wl.bits)
     keys, vals, q, signs, lens = device_inputs(wl, args.seed, dev)
@@ -156,14 +168,26 @@ def main():
         binding.octopus_encode(cb, keys[:, :first], sbits, cache, cap)
         start_dev = torch.full((wl.n_seq,), first, dtype=torch.int32, device=dev)
 
+    signs2 = s2bits = side = None
+    if args.qjl:
+        signs2 = synth.sign_vectors(args.seed + 1, wl.n_kv_heads, wl.head_dim)
+        s2bits = torch.from_numpy(synth.sign_bits(signs2)).to(dev)
+        side = torch.zeros(binding.octopus_qjl_bytes(cb, wl.n_seq, wl.n_kv_heads, cap), dtype=torch.uint8, device=dev)
+
     def step(ev=None):
         if ev:
             ev[0].record()
-        binding.octopus_encode(cb, keys[:, first:], sbits, cache, cap, start_dev)
+        if args.qjl:
+            binding.octopus_encode_qjl(cb, keys[:, first:], sbits, s2bits, cache, side, cap, start_dev)
+        else:
+            binding.octopus_encode(cb, keys[:, first:], sbits, cache, cap, start_dev)
         if ev:
             ev[1].record()
             binding.octopus_profile_events(ev[3], ev[4])  # around the fused kernel inside the next call
-        binding.octopus_attn_decode(cb, q, sbits, cache, cap, vals, lens_dev, max_len, scale, out, ws)
+        if args.qjl:
+            binding.octopus_attn_decode_qjl(cb, q, sbits, s2bits, cache, side, cap, vals, lens_dev, max_len, scale, out, ws)
+        else:
+            binding.octopus_attn_decode(cb, q, sbits, cache, cap, vals, lens_dev, max_len, scale, out, ws)
         if ev:
             ev[2].record()
 
@@ -190,7 +214,8 @@ def main():
     n_keys_enc = wl.n_seq * n_new * wl.n_kv_heads
     rec_bytes = cb.plan.record_bytes
     q_out_bytes = wl.n_seq * wl.n_q * wl.n_q_heads * wl.head_dim * (elt + 4)
-    dec_bytes = n_keys_dec * (rec_bytes + wl.head_dim * elt) + q_out_bytes
+    side_bytes = wl.head_dim // 8 + 2 if args.qjl else 0     # sign bits + fp16 residual norm per key
+    dec_bytes = n_keys_dec * (rec_bytes + side_bytes + wl.head_dim * elt) + q_out_bytes
     dec_s = float(dec_ms.mean()) * 1e-3
     enc_s = float(enc_ms.mean()) * 1e-3
     gbs = dec_bytes / dec_s / 1e9
@@ -211,12 +236,13 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {
-            "workload": f"{wl.name}: batch {wl.n_seq}, {wl.n_q_heads} query / {wl.n_kv_heads} KV heads, head_dim "
+            "workload": f"{wl.name}{' + QJL residual' if args.qjl else ''}: batch {wl.n_seq}, {wl.n_q_heads} query / {wl.n_kv_heads} KV heads, head_dim "
                         f"{wl.head_dim}, {wl.n_tokens} cached tokens, {wl.dtype} K/V/Q, {wl.bits:g} bits/coordinate "
                         f"(b_dir {cb.plan.b_dir[0]}, b_nrm {cb.plan.b_nrm[0]}); step = encode of "
                         f"{wl.n_seq * n_new} tokens + one decode-attention call"
                         + (f" of {wl.n_q} queries per sequence" if many_rows else ""),
             "record_bytes": rec_bytes,
+            "qjl_sidecar_bytes": side_bytes,
             "keys": n_keys_dec,
         },
         "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
@@ -238,7 +264,7 @@ def main():
             "kernel_ms": round(ker_s * 1e3, 4),
         },
     }
-    result["roofline"]["traffic"] = measured_traffic(wl.name)
+    result["roofline"]["traffic"] = measured_traffic(wl.name + ("_qjl" if args.qjl else ""))
     if many_rows and wl.head_dim <= 128 and wl.n_q * (wl.n_q_heads // wl.n_kv_heads) >= 32 and wl.dtype == "bf16":
         # hundreds of query rows per key: a dense contraction on the matrix cores, 4 d flops per (query row, key)
         flops = 4.0 * wl.head_dim * wl.n_q * wl.n_q_heads * float(lens.astype(np.int64).sum())
@@ -258,7 +284,7 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(wl, keys, vals, q, signs, scale, rec_bytes)
+        result["cpu_baseline"] = cpu_baseline(wl, keys, vals, q, signs, scale, rec_bytes, signs2=signs2)
     print(json.dumps(result))
 
 
