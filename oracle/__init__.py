@@ -23,7 +23,7 @@ _SRC = os.path.join(_HERE, "octopus_oracle.c")
 _LIB = os.path.join(_HERE, "liboctopus_oracle.so")
 _MAXC = 64
 
-MODE_SCALAR, MODE_LOCAL_3X3, MODE_FULL, MODE_INDEPENDENT = 0, 1, 2, 3
+MODE_SCALAR, MODE_LOCAL_3X3, MODE_FULL, MODE_INDEPENDENT, MODE_LOCAL_2X2 = 0, 1, 2, 3, 4
 
 
 def build(force=False):
@@ -77,6 +77,7 @@ def _load():
         lib.oracle_attention.argtypes = [P, vp, ctypes.c_int64, vp, vp, ctypes.c_int, vp,
                                          ctypes.c_double, vp, vp, vp]
         lib.oracle_classify.argtypes = [P, vp, ctypes.c_int64, vp, vp, ctypes.c_double, vp]
+        lib.oracle_classify_mode.argtypes = [P, vp, ctypes.c_int64, vp, ctypes.c_int, vp, ctypes.c_double, vp]
         lib.oracle_round_fp16.argtypes = [ctypes.c_double]
         lib.oracle_round_fp16.restype = ctypes.c_double
         lib.oracle_qjl_encode_key.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp]
@@ -297,14 +298,15 @@ def attention(plan, records, signs, q, v, scale):
     return scores, out, gap.value
 
 
-def classify(plan, keys, signs, foreign_records, tol=1e-6):
-    """Per-triplet comparison of foreign records with Alg. 1:
+def classify(plan, keys, signs, foreign_records, tol=1e-6, mode=MODE_LOCAL_3X3):
+    """Per-triplet comparison of foreign records with Alg. 1 (in the given rounding mode):
     returns (n_equal, n_boundary_tie, n_hard)."""
     keys, s = _f64(keys), signs_pm1(signs)
     fr = np.ascontiguousarray(foreign_records, dtype=np.uint8)
     assert fr.shape == (keys.shape[0], plan.record_bytes)
     counts = np.zeros(3, dtype=np.int64)
-    _load().oracle_classify(plan.cptr, _ptr(keys), keys.shape[0], _ptr(s), _ptr(fr), float(tol), _ptr(counts))
+    _load().oracle_classify_mode(plan.cptr, _ptr(keys), keys.shape[0], _ptr(s), int(mode), _ptr(fr), float(tol),
+                                 _ptr(counts))
     return int(counts[0]), int(counts[1]), int(counts[2])
 
 

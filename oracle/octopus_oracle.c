@@ -157,7 +157,12 @@ static int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v
  *       2 = full K x K grid, 3 = three independent nearest-centroid rounds
  *       (Sec. 3.5, first paragraph: the radius code is the centroid nearest
  *       to rho_i itself, not to s*; this is what the "scalar" rows of the
- *       rounding ablation print).
+ *       rounding ablation print), 4 = local 2x2 (App. E names it without
+ *       defining it; read as the window of offsets {0, +1} per axis: the
+ *       seed cell and its upper neighbour, clamped at the end.  This window
+ *       reproduces the printed local 2x2 rows; the window of the two
+ *       centroids that bracket the coordinate reproduces the 3x3 rows
+ *       instead).
  * Outputs per key: gamma, idx_dir[2*n_tri] (order (i,0),(i,1)), idx_nrm[n_tri];
  * optional diagnostics (may be NULL): u[d], xi_eta[2*n_tri], s_star[n_tri]. */
 void oracle_encode_key(const oracle_plan *p, const double *k, const int8_t *s, int mode,
@@ -201,6 +206,7 @@ void oracle_encode_key(const oracle_plan *p, const double *k, const int8_t *s, i
             int r = (mode == 0 || mode == 3) ? 0 : 1;
             for (int dx = -r; dx <= r; ++dx)
                 for (int dy = -r; dy <= r; ++dy) {
+                    if (mode == 4 && (dx < 0 || dy < 0)) continue;
                     int ax = clampi(jx + dx, 0, K - 1), ay = clampi(jy + dy, 0, K - 1);
                     double n[3];
                     oracle_oct_decode(cx[ax], cx[ay], n);
@@ -530,7 +536,7 @@ void oracle_attention_qjl(const oracle_plan *p, const uint8_t *records, int64_t 
  * is itself below tol (numerically zero, its direction rounding noise) admits
  * every sign pattern and every seed. */
 static int window_admits(const oracle_plan *p, int c, const double t[3], double xi, double eta,
-                         int fx, int fy, int fn, double tol, double tol_p)
+                         int fx, int fy, int fn, double tol, double tol_p, int mode)
 {
     int K = 1 << p->b_dir[c], M = 1 << p->b_nrm[c];
     const double *cx = p->c_xi[c], *bx = p->b_xi[c];
@@ -539,37 +545,49 @@ static int window_admits(const oracle_plan *p, int c, const double t[3], double 
     double sf = t[0] * n[0] + t[1] * n[1] + t[2] * n[2];
     int jx_lo = count_below(bx, K - 1, xi - tol_p), jx_hi = count_below(bx, K - 1, xi + tol_p);
     int jy_lo = count_below(bx, K - 1, eta - tol_p), jy_hi = count_below(bx, K - 1, eta + tol_p);
+    /* the radius code: from clip(s*) of the chosen direction, in mode 3 from rho_i itself */
+    double radial = (mode == 3) ? sqrt(t[0] * t[0] + t[1] * t[1] + t[2] * t[2]) : sf;
+    double cs = clip01(radial);
+    int n_lo = count_below(p->b_rho[c], M - 1, cs - tol), n_hi = count_below(p->b_rho[c], M - 1, cs + tol);
+    if (fn < n_lo || fn > n_hi) return 0;
+    if (mode == 2) { /* full grid: the seeds play no part */
+        double best = -INFINITY;
+        for (int ax = 0; ax < K; ++ax)
+            for (int ay = 0; ay < K; ++ay) {
+                oracle_oct_decode(cx[ax], cx[ay], n);
+                double sc = t[0] * n[0] + t[1] * n[1] + t[2] * n[2];
+                if (sc > best) best = sc;
+            }
+        return sf >= best - tol;
+    }
+    int r = (mode == 0 || mode == 3) ? 0 : 1;
     for (int jx = jx_lo; jx <= jx_hi; ++jx)
         for (int jy = jy_lo; jy <= jy_hi; ++jy) {
             int in_window = 0;
             double best = -INFINITY;
-            for (int dx = -1; dx <= 1; ++dx)
-                for (int dy = -1; dy <= 1; ++dy) {
+            for (int dx = -r; dx <= r; ++dx)
+                for (int dy = -r; dy <= r; ++dy) {
+                    if (mode == 4 && (dx < 0 || dy < 0)) continue;
                     int ax = clampi(jx + dx, 0, K - 1), ay = clampi(jy + dy, 0, K - 1);
                     oracle_oct_decode(cx[ax], cx[ay], n);
                     double sc = t[0] * n[0] + t[1] * n[1] + t[2] * n[2];
                     if (sc > best) best = sc;
                     if (ax == fx && ay == fy) in_window = 1;
                 }
-            if (in_window && sf >= best - tol) {
-                double cs = clip01(sf);
-                int lo = count_below(p->b_rho[c], M - 1, cs - tol);
-                int hi = count_below(p->b_rho[c], M - 1, cs + tol);
-                if (fn >= lo && fn <= hi) return 1;
-            }
+            if (in_window && sf >= best - tol) return 1;
         }
     return 0;
 }
 
-void oracle_classify_key(const oracle_plan *p, const double *k, const int8_t *s,
-                         const uint8_t *foreign, double tol, int64_t counts[3])
+void oracle_classify_key_mode(const oracle_plan *p, const double *k, const int8_t *s, int mode,
+                              const uint8_t *foreign, double tol, int64_t counts[3])
 {
     int nt = p->n_tri;
     int32_t *idx = (int32_t *)malloc(sizeof(int32_t) * 6 * nt);
     int32_t *o_dir = idx, *o_nrm = idx + 2 * nt, *f_dir = idx + 3 * nt, *f_nrm = idx + 5 * nt;
     double *u = (double *)calloc((size_t)3 * nt + p->d, sizeof(double));
     double gamma, fg;
-    oracle_encode_key(p, k, s, 1, &gamma, o_dir, o_nrm, u, NULL, NULL);
+    oracle_encode_key(p, k, s, mode, &gamma, o_dir, o_nrm, u, NULL, NULL);
     oracle_unpack_record(p, foreign, &fg, f_dir, f_nrm);
     for (int i = 0; i < nt; ++i) {
         if (o_dir[2 * i] == f_dir[2 * i] && o_dir[2 * i + 1] == f_dir[2 * i + 1] && o_nrm[i] == f_nrm[i]) {
@@ -586,7 +604,7 @@ void oracle_classify_key(const oracle_plan *p, const double *k, const int8_t *s,
             double den = (l1 > OCT_EPS) ? l1 : OCT_EPS;
             double px = t[0] / den, py = t[1] / den, pz = t[2] / den;
             double tol_p = (l1 > tol) ? tol / (l1 < 1.0 ? l1 : 1.0) : 4.0;
-            if (pz >= -tol_p) ok = window_admits(p, c, t, px, py, fx, fy, fn, tol, tol_p); /* unfolded branch */
+            if (pz >= -tol_p) ok = window_admits(p, c, t, px, py, fx, fy, fn, tol, tol_p, mode); /* unfolded branch */
             if (!ok && pz < tol_p)                                                     /* folded branch */
                 for (int vx = 0; vx < 2 && !ok; ++vx)
                     for (int vy = 0; vy < 2 && !ok; ++vy) {
@@ -594,13 +612,33 @@ void oracle_classify_key(const oracle_plan *p, const double *k, const int8_t *s,
                         if (fabs(px) > tol_p && sx != sgn1(px)) continue;
                         if (fabs(py) > tol_p && sy != sgn1(py)) continue;
                         ok = window_admits(p, c, t, sx * (1.0 - fabs(py)), sy * (1.0 - fabs(px)), fx, fy, fn, tol,
-                                           tol_p);
+                                           tol_p, mode);
                     }
         }
         counts[ok ? 1 : 2]++;
     }
     free(idx);
     free(u);
+}
+
+void oracle_classify_key(const oracle_plan *p, const double *k, const int8_t *s,
+                         const uint8_t *foreign, double tol, int64_t counts[3])
+{
+    oracle_classify_key_mode(p, k, s, 1, foreign, tol, counts);
+}
+
+void oracle_classify_mode(const oracle_plan *p, const double *keys, int64_t n_keys, const int8_t *s, int mode,
+                          const uint8_t *foreign_records, double tol, int64_t counts[3])
+{
+    int rb = oracle_record_bytes(p);
+    int64_t c0 = 0, c1 = 0, c2 = 0;
+#pragma omp parallel for schedule(static) reduction(+ : c0, c1, c2)
+    for (int64_t t = 0; t < n_keys; ++t) {
+        int64_t c[3] = { 0, 0, 0 };
+        oracle_classify_key_mode(p, keys + t * p->d, s, mode, foreign_records + t * rb, tol, c);
+        c0 += c[0]; c1 += c[1]; c2 += c[2];
+    }
+    counts[0] += c0; counts[1] += c1; counts[2] += c2;
 }
 
 void oracle_classify(const oracle_plan *p, const double *keys, int64_t n_keys, const int8_t *s,

@@ -483,3 +483,57 @@ def test_classifier_scales_the_octahedral_tolerance_with_the_triplet_l1_norm():
     dirs[2 * i] = 29
     rec = oracle.pack_record(plan, e["gamma"], dirs, e["idx_nrm"])[None, :]
     assert oracle.classify(plan, k[None, :], s, rec, tol=1e-8) == (plan.n_tri - 1, 0, 1)
+
+
+def test_classifier_follows_the_rounding_mode():
+    """Each mode's own records are all 'equal' under that mode; records of a weaker window are hard
+    mismatches under a wider one wherever the codes differ (the windows really differ), and a record of
+    any mode passes as 'equal' only where its codes equal that mode's."""
+    d = 128
+    plan = oracle.make_plan(d, 3)
+    s = _signs(7, d)
+    keys = synth.gaussian_keys(11, 128, d)
+    n = 128 * plan.n_tri
+    recs = {m: oracle.encode(plan, keys, s, mode=m) for m in range(5)}
+    for m in range(5):
+        assert oracle.classify(plan, keys, s, recs[m], mode=m) == (n, 0, 0), m
+    # seed-only (mode 0) codes judged as 3x3 output: every differing triplet is a hard mismatch
+    eq, tie, hard = oracle.classify(plan, keys, s, recs[0], mode=oracle.MODE_LOCAL_3X3)
+    assert tie <= 3 and hard > 0.1 * n and eq + tie + hard == n     # (a near-equal pair of scores is a tie)
+    # 3x3 codes judged as seed-only output: the same triplets differ
+    eq1, tie1, hard1 = oracle.classify(plan, keys, s, recs[1], mode=oracle.MODE_SCALAR)
+    assert eq1 == eq and tie1 <= 3 and tie1 + hard1 == tie + hard
+    # 2x2 sits between: fewer differences from 3x3 than the seed has, more than none
+    eq2, tie2, hard2 = oracle.classify(plan, keys, s, recs[4], mode=oracle.MODE_LOCAL_3X3)
+    assert tie2 <= 3 and 0 < hard2 < hard
+    # independent rounds differ from seed-only in the norm code only
+    a = np.array([np.concatenate(oracle.unpack_record(plan, r)[1:]) for r in recs[0]])
+    b = np.array([np.concatenate(oracle.unpack_record(plan, r)[1:]) for r in recs[3]])
+    assert np.array_equal(a[:, :2 * plan.n_tri], b[:, :2 * plan.n_tri]) and not np.array_equal(a, b)
+    # full grid equals 3x3 here (Sec. 3.5), so each passes under the other's mode
+    assert oracle.classify(plan, keys, s, recs[2], mode=oracle.MODE_LOCAL_3X3) == (n, 0, 0)
+
+
+def test_local_2x2_window_is_the_seed_and_its_upper_neighbour():
+    """Brute force on single triplets: the 2x2 choice is the best of the four candidates
+    (jx + {0,1}, jy + {0,1}) clamped, first maximum in that order."""
+    d = 4
+    plan = oracle.make_plan_pair(d, 3, 2)
+    s = np.ones(d, dtype=np.int8)
+    rng = np.random.default_rng(0)
+    cx, bx = plan.c_xi[0].astype(np.float64), plan.b_xi[0].astype(np.float64)
+    for _ in range(200):
+        k = rng.standard_normal(d)
+        e = oracle.encode_key(plan, k, s, mode=oracle.MODE_LOCAL_2X2)
+        u = np.concatenate([e["u"], np.zeros(3 * plan.n_tri - d)]).reshape(-1, 3)
+        for i in range(plan.n_tri):
+            xi, eta = e["xi_eta"][2 * i], e["xi_eta"][2 * i + 1]
+            jx, jy = int(np.sum(bx[:7] < xi)), int(np.sum(bx[:7] < eta))
+            best, arg = -np.inf, None
+            for dx in (0, 1):
+                for dy in (0, 1):
+                    ax, ay = min(jx + dx, 7), min(jy + dy, 7)
+                    sc = float(u[i] @ oracle.oct_decode(cx[ax], cx[ay]))
+                    if sc > best:
+                        best, arg = sc, (ax, ay)
+            assert (e["idx_dir"][2 * i], e["idx_dir"][2 * i + 1]) == arg

@@ -56,11 +56,14 @@ def test_implemented_split_is_the_diagonal_minimum(golden):
 
 @pytest.mark.parametrize("b", [1, 2, 3, 4])
 def test_rounding_ablation_table(golden, b):
-    """App. E: scalar vs local 3x3 rounding at matched bits, n = 4096, 64 queries, 5 seeds.
-    The printed "scalar" rows are three independent nearest-centroid rounds (Sec. 3.5)."""
+    """App. E: scalar vs local 3x3 vs local 2x2 rounding at matched bits, n = 4096, 64 queries, 5 seeds.
+    The printed "scalar" rows are three independent nearest-centroid rounds (Sec. 3.5); local 2x2 is read
+    as the seed cell and its upper neighbour per axis (App. E does not define it; the bracketing pair of
+    centroids would reproduce the 3x3 rows instead)."""
     rows = {r[1]: [float(x) for x in r[2:]] for r in golden("rounding_ablation.txt") if int(r[0]) == b}
     plan = oracle.make_plan(D, b)
-    for name, mode in (("scalar", oracle.MODE_INDEPENDENT), ("local_3x3", oracle.MODE_LOCAL_3X3)):
+    for name, mode in (("scalar", oracle.MODE_INDEPENDENT), ("local_3x3", oracle.MODE_LOCAL_3X3),
+                       ("local_2x2", oracle.MODE_LOCAL_2X2)):
         cos, mse, tail95, ip = rows[name]
         m = _avg(plan, mode, range(5), 4096, 64)
         assert _close(m["cos"], cos, 0.002, 3), (b, name, m)
