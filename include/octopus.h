@@ -129,6 +129,34 @@ int octopus_encode(const octopus_codebooks_t *cb,
                    const int32_t *start_pos,
                    void *stream);
 
+/* ---- encoder rounding variants (App. E, "Rounding ablation") ----
+ * Encoder-only: the bitstream and the decoder are those of octopus_encode.
+ *   SEED         Alg. 1 with the candidate window {(0,0)}: the direction codes are the
+ *                scalar seeds, the norm code comes from clip(s) of that direction.
+ *   LOCAL_3X3    Alg. 1 as printed (what octopus_encode does).
+ *   FULL         all 2^b_dir x 2^b_dir direction candidates.
+ *   INDEPENDENT  three independent nearest-centroid rounds (Sec. 3.5, first paragraph):
+ *                seeds for the direction, the centroid nearest to rho_i for the norm.
+ *   LOCAL_2X2    the seed cell and its upper neighbour per axis (4 candidates).
+ * Candidates are visited first index outer, second inner, ascending; the first maximum wins. */
+#define OCTOPUS_ROUND_SEED        0
+#define OCTOPUS_ROUND_LOCAL_3X3   1
+#define OCTOPUS_ROUND_FULL        2
+#define OCTOPUS_ROUND_INDEPENDENT 3
+#define OCTOPUS_ROUND_LOCAL_2X2   4
+
+/* octopus_encode with the rounding mode `rounding` (OCTOPUS_ROUND_*); EINVAL for another
+ * value.  Other arguments and errors as octopus_encode. */
+int octopus_encode_rounding(const octopus_codebooks_t *cb,
+                            const void *keys, int32_t key_dtype,
+                            int64_t stride_seq, int64_t stride_tok, int64_t stride_head,
+                            int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
+                            const uint8_t *signs,
+                            void *cache, int64_t t_capacity,
+                            const int32_t *start_pos,
+                            int32_t rounding,
+                            void *stream);
+
 /* ---- optional 1-bit QJL residual (Sec. 3.6, "OCTOPUS-QJL") ----
  * Side-car of a key: sigma = sign(H diag(s') r) for the residual r = u - u^ of
  * the rotated unit key (d bits) and gamma_r = ||r||_2 as fp16.  Device layout,

@@ -19,7 +19,8 @@ TILE = 64
 
 EXPORTS = ("octopus_build_codebooks", "octopus_build_codebooks_pair", "octopus_cache_bytes", "octopus_encode",
            "octopus_attn_decode_workspace", "octopus_attn_decode", "octopus_profile_events", "octopus_strerror",
-           "octopus_qjl_bytes", "octopus_encode_qjl", "octopus_attn_decode_qjl")
+           "octopus_qjl_bytes", "octopus_encode_qjl", "octopus_attn_decode_qjl",
+           "octopus_encode_rounding")
 
 
 class Plan(ctypes.Structure):
@@ -81,6 +82,8 @@ def load():
     lib.octopus_encode.restype = ctypes.c_int
     lib.octopus_qjl_bytes.argtypes = [CB, i32, i32, i64]
     lib.octopus_qjl_bytes.restype = ctypes.c_size_t
+    lib.octopus_encode_rounding.argtypes = [CB, vp, i32, i64, i64, i64, i32, i32, i32, vp, vp, i64, vp, i32, vp]
+    lib.octopus_encode_rounding.restype = ctypes.c_int
     lib.octopus_encode_qjl.argtypes = [CB, vp, i32, i64, i64, i64, i32, i32, i32, vp, vp, vp, vp, i64, vp, vp]
     lib.octopus_encode_qjl.restype = ctypes.c_int
     lib.octopus_attn_decode_workspace.argtypes = [CB, i32, i32, i32, i32, i64]
@@ -158,6 +161,19 @@ def octopus_encode(cb, keys, signs, cache, t_capacity, start_pos=None, stream=No
 
 def octopus_qjl_bytes(cb, n_seq, n_kv_heads, t_capacity):
     return int(load().octopus_qjl_bytes(ctypes.byref(cb), int(n_seq), int(n_kv_heads), int(t_capacity)))
+
+
+ROUND_SEED, ROUND_LOCAL_3X3, ROUND_FULL, ROUND_INDEPENDENT, ROUND_LOCAL_2X2 = 0, 1, 2, 3, 4
+
+
+def octopus_encode_rounding(cb, keys, signs, cache, t_capacity, rounding, start_pos=None, stream=None):
+    """octopus_encode with one of the rounding modes ROUND_* (App. E)."""
+    assert keys.dim() == 4 and keys.stride(3) == 1
+    n_seq, n_new, n_kv, _ = keys.shape
+    code = load().octopus_encode_rounding(ctypes.byref(cb), _ptr(keys), _dtype_code(keys), keys.stride(0),
+                                          keys.stride(1), keys.stride(2), n_seq, n_kv, n_new, _ptr(signs), _ptr(cache),
+                                          int(t_capacity), _ptr(start_pos), int(rounding), _stream_ptr(stream))
+    _check(code, "octopus_encode_rounding")
 
 
 def octopus_encode_qjl(cb, keys, signs, signs2, cache, qjl, t_capacity, start_pos=None, stream=None):

@@ -15,7 +15,10 @@ bool plan_supported_d256(const octopus_plan_t &);
     int launch_decode_qjl_d##D(const octopus_codebooks_t &, const DecodeShape &, const float *, const void *,      \
                                const void *, const float *, const void *, const int32_t *, float *, float *,       \
                                float *, int32_t *, void *);                                                        \
-    int qjl_rows_cap_d##D(const octopus_plan_t &);
+    int qjl_rows_cap_d##D(const octopus_plan_t &);                                                                 \
+    int launch_encode_rounding_d##D(const octopus_codebooks_t &, const void *, int, int64_t, int64_t, int64_t,     \
+                                    int32_t, int32_t, int32_t, const uint8_t *, void *, int64_t, const int32_t *,  \
+                                    int32_t, void *);
 OCTOPUS_DECL(64)
 OCTOPUS_DECL(128)
 OCTOPUS_DECL(256)
@@ -73,6 +76,18 @@ int launch_encode(const octopus_codebooks_t &cb, const void *keys, int key_dtype
         case 64: return launch_encode_d64(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs, cache, t_capacity, start_pos, signs2, qjl, stream);
         case 128: return launch_encode_d128(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs, cache, t_capacity, start_pos, signs2, qjl, stream);
         case 256: return launch_encode_d256(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs, cache, t_capacity, start_pos, signs2, qjl, stream);
+        default: return static_cast<int>(hipErrorInvalidValue);
+    }
+}
+
+int launch_encode_rounding(const octopus_codebooks_t &cb, const void *keys, int key_dtype, int64_t stride_seq,
+                           int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
+                           const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos,
+                           int32_t mode, void *stream) {
+    switch (cb.plan.head_dim) {
+        case 64: return launch_encode_rounding_d64(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs, cache, t_capacity, start_pos, mode, stream);
+        case 128: return launch_encode_rounding_d128(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs, cache, t_capacity, start_pos, mode, stream);
+        case 256: return launch_encode_rounding_d256(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs, cache, t_capacity, start_pos, mode, stream);
         default: return static_cast<int>(hipErrorInvalidValue);
     }
 }

@@ -150,6 +150,56 @@ __device__ __forceinline__ void encode_triplet(float x, float y, float z, const 
     *nrm_index = static_cast<uint32_t>(r);
 }
 
+// The encoder-only rounding variants of App. E (same bitstream, same decoder); `mode` as in octopus.h:
+// 0 seed only (Alg. 1 with the window {(0,0)}), 1 local 3x3, 2 full K x K grid, 3 three independent
+// nearest-centroid rounds (the norm code from rho_i itself), 4 local 2x2 (the seed and its upper neighbour).
+// Candidates are visited dx outer, dy inner (full grid: x index outer); the first maximum wins.
+template <int BD, int BN, int REP>
+__device__ __forceinline__ void encode_triplet_any(float x, float y, float z, const float4 *lut, const float2 *cell,
+                                                   const float *bnd_xi, const float *bnd_rho, int lane, int mode,
+                                                   uint32_t *dir_field, uint32_t *nrm_index) {
+    constexpr int K = 1 << BD, M = 1 << BN;
+    const float l1 = fabsf(x) + fabsf(y) + fabsf(z);
+    const float inv = __builtin_amdgcn_rcpf(fmaxf(l1, kEps));
+    const float px = x * inv, py = y * inv;
+    float xi = px, eta = py;
+    if (z < 0.0f) {
+        const float fx = 1.0f - fabsf(py), fy = 1.0f - fabsf(px);
+        xi = (px >= 0.0f) ? fx : -fx;
+        eta = (py >= 0.0f) ? fy : -fy;
+    }
+    const int jx = seed_index<BD, REP>(cell, bnd_xi, xi, lane);
+    const int jy = seed_index<BD, REP>(cell, bnd_xi, eta, lane);
+    float best = -INFINITY;
+    uint32_t best_code = 0u;
+    auto consider = [&](int ax, int ay) {
+        const uint32_t code = static_cast<uint32_t>(ax | (ay << BD));
+        const float4 n = lut[code * REP + (lane & (REP - 1))];
+        const float sc = fmaf(z, n.z, fmaf(y, n.y, x * n.x));
+        if (sc > best) { best = sc; best_code = code; }
+    };
+    // rolled loops on purpose: these variants are for ablations, and unrolling K x K candidates per
+    // triplet of every class blows the code up
+    if (mode == 2) {
+#pragma clang loop unroll(disable)
+        for (int c = 0; c < K * K; ++c) consider(c >> BD, c & (K - 1));
+    } else {
+        const int lo = (mode == 1) ? -1 : 0;
+        const int hi = (mode == 1 || mode == 4) ? 1 : 0;
+#pragma clang loop unroll(disable)
+        for (int dx = lo; dx <= hi; ++dx)
+#pragma clang loop unroll(disable)
+            for (int dy = lo; dy <= hi; ++dy) consider(min(max(jx + dx, 0), K - 1), min(max(jy + dy, 0), K - 1));
+    }
+    const float radial = (mode == 3) ? sqrtf(fmaf(z, z, fmaf(y, y, x * x))) : best;
+    const float cs = fminf(fmaxf(radial, 0.0f), 1.0f);
+    int r = 0;
+#pragma unroll
+    for (int k = 0; k < M - 1; ++k) r += (bnd_rho[k] < cs) ? 1 : 0;
+    *dir_field = best_code;
+    *nrm_index = static_cast<uint32_t>(r);
+}
+
 __device__ __forceinline__ void or_bits(uint32_t (*rec)[kWave], int key, int bitpos, int nbits, uint32_t v) {
     const int wi = bitpos >> 5, sh = bitpos & 31;
     atomicOr(&rec[wi][key], v << sh);
@@ -162,14 +212,15 @@ constexpr int kEncodeTilesPerGroup = 4;  // consecutive cache tiles per workgrou
 // rotated unit key replaces u in LDS as the triplets are encoded, a second sign-flipped Hadamard
 // transform follows, and the signs of its output (bit set = negative) plus ||r|| as fp16 are stored per
 // key: per tile of 64 tokens [d/32 words][64 keys] uint32, then [64 keys] fp16.
-template <class P, bool BF16, bool QJL>
+// ANY: the rounding mode is the run-time argument `mode` (the default encoder is built without it).
+template <class P, bool BF16, bool QJL, bool ANY = false>
 __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const void *__restrict__ keys,
                                                       int64_t stride_seq, int64_t stride_tok, int64_t stride_head,
                                                       int32_t n_new, const uint8_t *__restrict__ signs,
                                                       uint4 *__restrict__ cache, int64_t t_capacity,
                                                       const int32_t *__restrict__ start_pos, int32_t n_kv_heads,
                                                       const uint8_t *__restrict__ signs2,
-                                                      unsigned char *__restrict__ qjl) {
+                                                      unsigned char *__restrict__ qjl, int32_t mode) {
     constexpr int D = P::D;
     constexpr int LPR = D / 8;        // threads per key row in the load phase
     constexpr int RPP = 256 / LPR;    // key rows per load pass
@@ -284,15 +335,23 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
                 float4 nhat;
                 float rho;
                 if (P::NCLASS == 1 || i < P::NT0) {
-                    encode_triplet<P::BD0, P::BN0, REP>(x, y, z, sm.lut0, sm.cell0, sm.bnd_xi[0], sm.bnd_rho[0], lane,
-                                                        &dir_field, &nrm_index);
+                    if constexpr (ANY)
+                        encode_triplet_any<P::BD0, P::BN0, REP>(x, y, z, sm.lut0, sm.cell0, sm.bnd_xi[0], sm.bnd_rho[0],
+                                                                lane, mode, &dir_field, &nrm_index);
+                    else
+                        encode_triplet<P::BD0, P::BN0, REP>(x, y, z, sm.lut0, sm.cell0, sm.bnd_xi[0], sm.bnd_rho[0],
+                                                            lane, &dir_field, &nrm_index);
                     or_bits(sm.rec, lane, P::DIR0_BIT + i * 2 * P::BD0, 2 * P::BD0, dir_field);
                     or_bits(sm.rec, lane, P::NRM0_BIT + i * P::BN0, P::BN0, nrm_index);
                     if constexpr (QJL) { nhat = sm.lut0[dir_field * REP + (lane & (REP - 1))]; rho = sm.c_rho[0][nrm_index]; }
                 } else {
                     if constexpr (P::NCLASS == 2) {
-                        encode_triplet<P::BD1, P::BN1, REP>(x, y, z, sm.lut1, sm.cell1, sm.bnd_xi[1], sm.bnd_rho[1],
-                                                            lane, &dir_field, &nrm_index);
+                        if constexpr (ANY)
+                            encode_triplet_any<P::BD1, P::BN1, REP>(x, y, z, sm.lut1, sm.cell1, sm.bnd_xi[1],
+                                                                    sm.bnd_rho[1], lane, mode, &dir_field, &nrm_index);
+                        else
+                            encode_triplet<P::BD1, P::BN1, REP>(x, y, z, sm.lut1, sm.cell1, sm.bnd_xi[1],
+                                                                sm.bnd_rho[1], lane, &dir_field, &nrm_index);
                         or_bits(sm.rec, lane, P::DIR1_BIT + (i - P::NT0) * 2 * P::BD1, 2 * P::BD1, dir_field);
                         or_bits(sm.rec, lane, P::NRM1_BIT + (i - P::NT0) * P::BN1, P::BN1, nrm_index);
                         if constexpr (QJL) { nhat = sm.lut1[dir_field * REP + (lane & (REP - 1))]; rho = sm.c_rho[1][nrm_index]; }
@@ -381,13 +440,35 @@ int launch_encode_plan(const octopus_codebooks_t &cb, const void *keys, int key_
     auto go = [&](auto kernel) {
         hipLaunchKernelGGL(kernel, grid, dim3(256), 0, stream, books, keys, stride_seq, stride_tok, stride_head, n_new,
                            signs, static_cast<uint4 *>(cache), t_capacity, start_pos, n_kv_heads, signs2,
-                           static_cast<unsigned char *>(qjl));
+                           static_cast<unsigned char *>(qjl), 1);
     };
     if (qjl != nullptr) {
         if (bf16) go(encode_kernel<P, true, true>); else go(encode_kernel<P, false, true>);
     } else {
         if (bf16) go(encode_kernel<P, true, false>); else go(encode_kernel<P, false, false>);
     }
+    return static_cast<int>(hipGetLastError());
+}
+
+// The encoder with the rounding mode chosen at run time (no side-car).
+template <class P>
+int launch_encode_rounding_plan(const octopus_codebooks_t &cb, const void *keys, int key_dtype, int64_t stride_seq,
+                                int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads,
+                                int32_t n_new, const uint8_t *signs, void *cache, int64_t t_capacity,
+                                const int32_t *start_pos, int32_t mode, hipStream_t stream) {
+    DeviceBooks books;
+    for (int c = 0; c < 2; ++c) {
+        for (int k = 0; k < 32; ++k) books.c_xi[c][k] = cb.c_xi[c][k];
+        for (int k = 0; k < 8; ++k) books.c_rho[c][k] = cb.c_rho[c][k];
+    }
+    const int tiles = (n_new + kWave - 1) / kWave + (start_pos ? 1 : 0);
+    const dim3 grid((tiles + kEncodeTilesPerGroup - 1) / kEncodeTilesPerGroup, n_kv_heads, n_seq);
+    auto go = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, grid, dim3(256), 0, stream, books, keys, stride_seq, stride_tok, stride_head, n_new,
+                           signs, static_cast<uint4 *>(cache), t_capacity, start_pos, n_kv_heads, nullptr, nullptr, mode);
+    };
+    if (key_dtype == OCTOPUS_DTYPE_BF16) go(encode_kernel<P, true, false, true>);
+    else go(encode_kernel<P, false, false, true>);
     return static_cast<int>(hipGetLastError());
 }
 

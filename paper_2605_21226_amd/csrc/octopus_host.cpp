@@ -390,8 +390,9 @@ static bool seed_grid_ok(const octopus_codebooks_t &cb) {
 static int encode_checked(const octopus_codebooks_t *cb, const void *keys, int32_t key_dtype, int64_t stride_seq,
                           int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
                           const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos,
-                          const uint8_t *signs2, void *qjl, void *stream) {
+                          const uint8_t *signs2, void *qjl, void *stream, int32_t rounding = OCTOPUS_ROUND_LOCAL_3X3) {
     if (cb == nullptr || keys == nullptr || signs == nullptr || cache == nullptr) return OCTOPUS_EINVAL;
+    if (rounding < OCTOPUS_ROUND_SEED || rounding > OCTOPUS_ROUND_LOCAL_2X2) return OCTOPUS_EINVAL;
     if (n_seq < 1 || n_kv_heads < 1 || n_new < 0) return OCTOPUS_EINVAL;
     if (t_capacity < OCTOPUS_TILE || t_capacity % OCTOPUS_TILE != 0) return OCTOPUS_EINVAL;
     if (!plan_consistent(cb->plan)) return OCTOPUS_EINVAL;
@@ -403,8 +404,12 @@ static int encode_checked(const octopus_codebooks_t *cb, const void *keys, int32
     if (qjl != nullptr && !aligned(qjl, 4)) return OCTOPUS_EINVAL;
     if (start_pos == nullptr && n_new > t_capacity) return OCTOPUS_EINVAL;
     if (n_new == 0) return OCTOPUS_OK;
-    const int err = launch_encode(*cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads,
-                                  n_new, signs, cache, t_capacity, start_pos, signs2, qjl, stream);
+    const int err = rounding == OCTOPUS_ROUND_LOCAL_3X3
+                        ? launch_encode(*cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads,
+                                        n_new, signs, cache, t_capacity, start_pos, signs2, qjl, stream)
+                        : launch_encode_rounding(*cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq,
+                                                 n_kv_heads, n_new, signs, cache, t_capacity, start_pos, rounding,
+                                                 stream);
     return err == 0 ? OCTOPUS_OK : OCTOPUS_EHIP;
 }
 
@@ -413,6 +418,14 @@ int octopus_encode(const octopus_codebooks_t *cb, const void *keys, int32_t key_
                    const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos, void *stream) {
     return encode_checked(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs,
                           cache, t_capacity, start_pos, nullptr, nullptr, stream);
+}
+
+int octopus_encode_rounding(const octopus_codebooks_t *cb, const void *keys, int32_t key_dtype, int64_t stride_seq,
+                            int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
+                            const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos,
+                            int32_t rounding, void *stream) {
+    return encode_checked(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs,
+                          cache, t_capacity, start_pos, nullptr, nullptr, stream, rounding);
 }
 
 size_t octopus_qjl_bytes(const octopus_codebooks_t *cb, int32_t n_seq, int32_t n_kv_heads, int64_t t_capacity) {

@@ -64,6 +64,12 @@ int launch_encode(const octopus_codebooks_t &cb, const void *keys, int key_dtype
                   const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos,
                   const uint8_t *signs2, void *qjl, void *stream);   // qjl NULL: no side-car
 
+// The encoder with one of the rounding modes of App. E (OCTOPUS_ROUND_*), no side-car.
+int launch_encode_rounding(const octopus_codebooks_t &cb, const void *keys, int key_dtype, int64_t stride_seq,
+                           int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
+                           const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos,
+                           int32_t mode, void *stream);
+
 // hipEventRecord(event, stream); returns a hipError_t cast to int.
 int record_event(void *event, void *stream);
 

@@ -29,22 +29,22 @@ def make_inputs(seed, n_seq, n_kv, n_tok, d, dtype, sigma_ln=0.5, n_outlier=4):
     return keys, vals, signs
 
 
-def compare_records(plan, keys, signs, rec, tag, max_tie_rate=2e-4):
-    """keys [n_seq, n_tok, n_kv, d]; rec [n_seq, n_kv, >= n_tok, rb] from the GPU"""
+def compare_records(plan, keys, signs, rec, tag, max_tie_rate=2e-4, mode=oracle.MODE_LOCAL_3X3):
+    """keys [n_seq, n_tok, n_kv, d]; rec [n_seq, n_kv, >= n_tok, rb] from the GPU; mode: the oracle's rounding mode"""
     n_seq, n_tok, n_kv, d = keys.shape
     total = np.zeros(3, dtype=np.int64)
     for s in range(n_seq):
         for h in range(n_kv):
             k = keys[s, :, h, :].astype(np.float64)
             got = rec[s, h, :n_tok]
-            ref = oracle.encode(plan, k, signs[h])
+            ref = oracle.encode(plan, k, signs[h], mode=mode)
             g_got = got[:, :4].copy().view(np.float32)[:, 0].astype(np.float64)
             g_ref = ref[:, :4].copy().view(np.float32)[:, 0].astype(np.float64)
             assert np.all(np.abs(g_got - g_ref) <= 1e-6 * np.maximum(g_ref, 1e-30)), tag   # gamma: fp32 norm
             if np.array_equal(got[:, 4:], ref[:, 4:]):
                 total[0] += n_tok * plan.n_tri
             else:
-                total += np.array(oracle.classify(plan, k, signs[h], got, tol=1e-6))
+                total += np.array(oracle.classify(plan, k, signs[h], got, tol=1e-6, mode=mode))
     print(f"[codes] {tag}: triplets equal={total[0]} boundary_ties={total[1]} hard={total[2]}")
     assert total[2] == 0, f"{tag}: {total[2]} code mismatches away from any decision boundary"
     assert total[1] <= max(2, max_tie_rate * total.sum()), f"{tag}: too many boundary ties ({total[1]})"

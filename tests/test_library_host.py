@@ -95,6 +95,12 @@ def test_encode_and_decode_reject_bad_arguments_before_launching(lib):
     broken.plan.record_bytes = 57
     assert enc(ctypes.byref(broken), fake, 1, 1024, 1024, 128, 1, 8, 64, fake, fake, 64, null, null) == binding.EINVAL
 
+    rnd = lib.octopus_encode_rounding
+    assert rnd(P, fake, 1, 1024, 1024, 128, 1, 8, 64, fake, fake, 64, null, 5, null) == binding.EINVAL    # mode
+    assert rnd(P, fake, 1, 1024, 1024, 128, 1, 8, 64, fake, fake, 64, null, -1, null) == binding.EINVAL
+    assert rnd(P, null, 1, 1024, 1024, 128, 1, 8, 64, fake, fake, 64, null, 2, null) == binding.EINVAL
+    assert rnd(P, fake, 1, 1024, 1024, 128, 1, 8, 0, fake, fake, 64, null, 2, null) == binding.OK         # nothing to do
+
     dec = lib.octopus_attn_decode
     ws = binding.octopus_attn_decode_workspace(cb, 2, 32, 8, 1, 4096)
     assert ws > 0 and ws % 256 == 0
