@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--workload", default="llama3_8b_decode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--rounding", type=int, default=1,
+                    help="encoder rounding mode (App. E): 0 seed only, 1 local 3x3 (default), 2 full grid, "
+                         "3 independent rounds, 4 local 2x2; the decoder is the same")
     ap.add_argument("--qjl", action="store_true",
                     help="time the variant with the 1-bit QJL residual (octopus_encode_qjl + octopus_attn_decode_qjl); "
                          "single-query workloads only")
@@ -46,7 +49,7 @@ def parse():
     return ap.parse_args()
 
 
-def cpu_baseline(wl, keys, vals, q, signs, scale, record_bytes, budget_s=12.0, signs2=None):
+def cpu_baseline(wl, keys, vals, q, signs, scale, record_bytes, budget_s=12.0, signs2=None, mode=1):
     """The oracle as it stands, timed on this machine's host cores on a bounded sample of the workload:
     whole sequences (all KV heads, all cached tokens; encode, then attention of each KV head's group of
     query heads over its tokens), one sequence after another until about `budget_s` seconds are spent."""
@@ -67,7 +70,7 @@ def cpu_baseline(wl, keys, vals, q, signs, scale, record_bytes, budget_s=12.0, s
         q_host = q[s, :nq_s].float().cpu().numpy().astype(np.float64)        # [nq_s, n_qh, d]
         k_heads = [np.ascontiguousarray(k_host[:, h]) for h in range(wl.n_kv_heads)]
         t0 = time.perf_counter()
-        recs = [oracle.encode(plan, k_heads[h], signs[h]) for h in range(wl.n_kv_heads)]
+        recs = [oracle.encode(plan, k_heads[h], signs[h], mode=mode) for h in range(wl.n_kv_heads)]   # same numbering
         if signs2 is not None:
             side = [oracle.qjl_encode(plan, k_heads[h], signs[h], signs2[h], recs[h]) for h in range(wl.n_kv_heads)]
         t1 = time.perf_counter()
@@ -140,6 +143,9 @@ def main():
     torch.cuda.set_device(0)
     wl = synth.WORKLOADS[args.workload]
     many_rows = wl.n_q > 1
+    if args.qjl and args.rounding != 1:
+        print("bench.py: --qjl goes with the default rounding", file=sys.stderr)
+        sys.exit(2)
     if args.qjl and many_rows:
         print("bench.py: --qjl times single-query workloads only", file=sys.stderr)
         sys.exit(2)
@@ -179,6 +185,8 @@ def main():
             ev[0].record()
         if args.qjl:
             binding.octopus_encode_qjl(cb, keys[:, first:], sbits, s2bits, cache, side, cap, start_dev)
+        elif args.rounding != 1:
+            binding.octopus_encode_rounding(cb, keys[:, first:], sbits, cache, cap, args.rounding, start_dev)
         else:
             binding.octopus_encode(cb, keys[:, first:], sbits, cache, cap, start_dev)
         if ev:
@@ -243,6 +251,7 @@ def main():
                         + (f" of {wl.n_q} queries per sequence" if many_rows else ""),
             "record_bytes": rec_bytes,
             "qjl_sidecar_bytes": side_bytes,
+            "encoder_rounding": args.rounding,
             "keys": n_keys_dec,
         },
         "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
@@ -284,7 +293,7 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(wl, keys, vals, q, signs, scale, rec_bytes, signs2=signs2)
+        result["cpu_baseline"] = cpu_baseline(wl, keys, vals, q, signs, scale, rec_bytes, signs2=signs2, mode=args.rounding)
     print(json.dumps(result))
 
 
