@@ -30,7 +30,7 @@ def build(force=False):
     """Compile the oracle's C file (gcc, -O2, OpenMP over keys)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + f".tmp{os.getpid()}"
-        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-o", tmp, _SRC, "-lm"])
+        subprocess.check_call(["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC", "-o", tmp, _SRC, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -78,6 +78,12 @@ def _load():
                                          ctypes.c_double, vp, vp, vp]
         lib.oracle_classify.argtypes = [P, vp, ctypes.c_int64, vp, vp, ctypes.c_double, vp]
         lib.oracle_classify_mode.argtypes = [P, vp, ctypes.c_int64, vp, ctypes.c_int, vp, ctypes.c_double, vp]
+        lib.oracle_vq_row_bytes.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int]
+        lib.oracle_vq_row_bytes.restype = ctypes.c_int
+        lib.oracle_vq_encode.argtypes = [vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp]
+        lib.oracle_vq_encode.restype = None
+        lib.oracle_vq_decode.argtypes = [vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp]
+        lib.oracle_vq_decode.restype = None
         lib.oracle_round_fp16.argtypes = [ctypes.c_double]
         lib.oracle_round_fp16.restype = ctypes.c_double
         lib.oracle_qjl_encode_key.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp]
@@ -360,3 +366,28 @@ def attention_qjl(plan, records, signs, signs2, sigma, gamma_r, q, v, scale):
     _load().oracle_attention_qjl(plan.cptr, _ptr(records), n, _ptr(s), _ptr(s2), _ptr(sg), _ptr(gr), _ptr(q), q.shape[0],
                                  _ptr(v), float(scale), _ptr(scores), _ptr(out))
     return scores, out
+
+
+# ---- value codec: per-group uniform quantisation (Sec. 4; parity unpinned by the paper) ----------------
+
+def vq_row_bytes(d, bits, group):
+    return int(_load().oracle_vq_row_bytes(int(d), int(bits), int(group)))
+
+
+def vq_encode(v, bits, group):
+    """v [n, d] (fp32 values) -> rows uint8 [n, vq_row_bytes]"""
+    v = np.ascontiguousarray(v, dtype=np.float32)
+    n, d = v.shape
+    assert d % group == 0 and group % 8 == 0
+    rows = np.zeros((n, vq_row_bytes(d, bits, group)), dtype=np.uint8)
+    _load().oracle_vq_encode(_ptr(v), n, d, int(bits), int(group), _ptr(rows))
+    return rows
+
+
+def vq_decode(rows, d, bits, group):
+    """rows uint8 [n, vq_row_bytes] -> v^ float64 [n, d]"""
+    rows = np.ascontiguousarray(rows, dtype=np.uint8)
+    assert rows.shape[1] == vq_row_bytes(d, bits, group)
+    out = np.zeros((rows.shape[0], d), dtype=np.float64)
+    _load().oracle_vq_decode(_ptr(rows), rows.shape[0], d, int(bits), int(group), _ptr(out))
+    return out

@@ -24,6 +24,15 @@
  *                       under a second sign-flipped Hadamard rotation, residual
  *                       norm rounded to fp16, corrected score.
  *
+ *   value codec         Sec. 4 ("value-side group size in {16, 32}") and the
+ *                       "value dequantization" step of Alg. 2's description.
+ *                       The paper gives the group size and (through the KV
+ *                       ratios of Table (kernel speed)) the size, b d / 8
+ *                       code bytes + 8 bytes per group, and nothing else: the
+ *                       codec here is uniform asymmetric min/max quantisation
+ *                       per group with an fp32 scale and an fp32 zero point.
+ *                       PARITY UNPINNED by the paper beyond the byte count.
+ *
  * Readings where the paper is silent (all listed in the design notes):
  *   eps = 1e-20 for both clamped divisors; searchsorted counts boundaries
  *   strictly below the value; candidate order dx outer, dy inner, each
@@ -653,4 +662,68 @@ void oracle_classify(const oracle_plan *p, const double *keys, int64_t n_keys, c
         c0 += c[0]; c1 += c[1]; c2 += c[2];
     }
     counts[0] += c0; counts[1] += c1; counts[2] += c2;
+}
+
+/* ---- value codec: per-group uniform quantisation ------------------------- */
+
+/* The paper fixes the group size g in {16, 32}, the bit width b (that of the
+ * keys) and, through the printed KV ratios, the size b d / 8 + 8 d / g bytes
+ * per value row.  Everything else is this build's reading (parity unpinned by
+ * the paper): per group of g consecutive channels
+ *     lo = min v, hi = max v, scale = (hi - lo) / (2^b - 1), zero = lo,
+ *     code_j = clamp(rint((v_j - lo) / scale), 0, 2^b - 1)   (0 if scale = 0),
+ *     v^_j = zero + scale * code_j,
+ * scale and zero stored as fp32.  The integer decision (rint, ties to even) is
+ * taken in fp32, the precision of the stored metadata and of the kernel: every
+ * operation below is a single correctly rounded fp32 operation, so that an
+ * IEEE fp32 implementation reproduces the codes bit for bit.
+ * Row layout: [codes, channel j at bit b j, LSB first][per group: scale, zero]. */
+int oracle_vq_row_bytes(int d, int b, int g) { return b * d / 8 + (d / g) * 8; }
+
+void oracle_vq_encode(const float *v, int64_t n, int d, int b, int g, uint8_t *rows)
+{
+    int rb = oracle_vq_row_bytes(d, b, g), levels = (1 << b) - 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < n; ++t) {
+        uint8_t *row = rows + t * rb;
+        memset(row, 0, (size_t)rb);
+        for (int grp = 0; grp < d / g; ++grp) {
+            const float *x = v + t * d + grp * g;
+            float lo = x[0], hi = x[0];
+            for (int j = 1; j < g; ++j) {
+                if (x[j] < lo) lo = x[j];
+                if (x[j] > hi) hi = x[j];
+            }
+            volatile float range = hi - lo;               /* volatile: one rounding per operation */
+            volatile float scale = range / (float)levels;
+            for (int j = 0; j < g; ++j) {
+                uint32_t code = 0;
+                if (scale > 0.0f) {
+                    volatile float off = x[j] - lo;
+                    volatile float r = off / scale;
+                    float c = nearbyintf(r);              /* default rounding mode: ties to even */
+                    if (c < 0.0f) c = 0.0f;
+                    if (c > (float)levels) c = (float)levels;
+                    code = (uint32_t)c;
+                }
+                put_bits(row, (int64_t)b * (grp * g + j), b, code);
+            }
+            float meta[2] = { scale, lo };
+            memcpy(row + b * d / 8 + grp * 8, meta, 8);
+        }
+    }
+}
+
+void oracle_vq_decode(const uint8_t *rows, int64_t n, int d, int b, int g, double *v_hat)
+{
+    int rb = oracle_vq_row_bytes(d, b, g);
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < n; ++t) {
+        const uint8_t *row = rows + t * rb;
+        for (int j = 0; j < d; ++j) {
+            float meta[2];
+            memcpy(meta, row + b * d / 8 + (j / g) * 8, 8);
+            v_hat[t * d + j] = (double)meta[1] + (double)meta[0] * (double)get_bits(row, (int64_t)b * j, b);
+        }
+    }
 }
