@@ -244,6 +244,53 @@ int octopus_attn_decode_qjl(const octopus_codebooks_t *cb,
                             void *workspace, size_t workspace_bytes,
                             void *stream);
 
+/* ---- value codec: per-group quantised values (Sec. 4, "value-side group size in {16, 32}") ----
+ * The paper fixes the group size g, the bit width b (that of the keys) and, through the KV
+ * ratios of Table (kernel speed), the row size b d / 8 + 8 d / g bytes; the codec is this
+ * library's reading: per token, KV head and group of g consecutive channels
+ *     lo = min v, hi = max v, scale = (hi - lo) / (2^b - 1) (fp32), zero = lo (fp32),
+ *     code_j = clamp(rint((v_j - lo) / scale), 0, 2^b - 1)  (0 when scale = 0; ties to even),
+ *     v^_j = zero + scale * code_j.
+ * Device layout: [n_seq][n_kv_heads][t_capacity] rows of
+ *     [codes: channel j at bit b j of the row, LSB first, b d / 8 bytes][per group: scale, zero]. */
+
+/* Row size in bytes (0 if head_dim is not 64/128/256, bits not 2..4 or group not 16/32). */
+size_t octopus_vq_row_bytes(int32_t head_dim, int32_t bits, int32_t group);
+/* Bytes of the quantised value buffer (0 if an argument is invalid). */
+size_t octopus_vq_bytes(int32_t head_dim, int32_t bits, int32_t group, int32_t n_seq, int32_t n_kv_heads,
+                        int64_t t_capacity);
+
+/* Quantises n_new value rows per (sequence, KV head) into rows start_pos[s] + i of vq.
+ *   v           device, element (s, i, h, j) at s*stride_seq + i*stride_tok + h*stride_head + j
+ *               (element strides), v_dtype F32/BF16, 4-byte aligned.
+ *   vq          device, 16-byte aligned, octopus_vq_bytes(...) bytes; other rows untouched.
+ *   start_pos   device [n_seq] int32 or NULL (all zero); rows at or past t_capacity are dropped.
+ * Errors: EINVAL, EUNSUPPORTED (dtype, head_dim, bits, group), EHIP. */
+int octopus_encode_values(const void *v, int32_t v_dtype,
+                          int64_t stride_seq, int64_t stride_tok, int64_t stride_head,
+                          int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
+                          int32_t head_dim, int32_t bits, int32_t group,
+                          void *vq, int64_t t_capacity,
+                          const int32_t *start_pos,
+                          void *stream);
+
+/* octopus_attn_decode over quantised values: out = softmax_t(scale * q . k^_t) V^ with V^ the
+ * rows vq dequantised on the fly (the "value dequantization" of Alg. 2).
+ *   vq, v_bits, v_group   as written by octopus_encode_values for the same head_dim.
+ * Workspace: octopus_attn_decode_workspace(...) of the same shapes.  Other arguments and errors
+ * as octopus_attn_decode; EUNSUPPORTED for v_bits outside 2..4 or v_group not 16/32. */
+int octopus_attn_decode_vq(const octopus_codebooks_t *cb,
+                           const void *q, int32_t q_dtype,
+                           int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q,
+                           const uint8_t *signs,
+                           const void *cache, int64_t t_capacity,
+                           const void *vq, int32_t v_bits, int32_t v_group,
+                           const int32_t *seq_lens, int64_t max_len,
+                           float scale,
+                           float *out, float *scores_out,
+                           void *workspace, size_t workspace_bytes,
+                           void *stream);
+
 /* Measurement aid (not part of the method): the next octopus_attn_decode call made by this thread
  * records the HIP events `before` and `after` (hipEvent_t passed as void*, caller-owned, created
  * with timing enabled) on the call's stream immediately before and after the launch of the fused

@@ -391,3 +391,21 @@ def vq_decode(rows, d, bits, group):
     out = np.zeros((rows.shape[0], d), dtype=np.float64)
     _load().oracle_vq_decode(_ptr(rows), rows.shape[0], d, int(bits), int(group), _ptr(out))
     return out
+
+
+# ---- hybrid cache: compressed tokens followed by a native-precision window (Sec. 4, default recipe) ----
+
+def attention_hybrid(plan, records, signs, k_window, q, v, scale):
+    """Attention over n compressed tokens (canonical records) followed by w tokens whose keys are kept at
+    native precision (k_window [w, d]); v [n + w, d].  Written as the definition: the key matrix is the
+    reconstructed keys stacked on the window's keys, then softmax(scale * q K^T) V.
+    -> (scores [n_q, n + w], out [n_q, d])."""
+    q, v, kw = _f64(np.atleast_2d(q)), _f64(v), _f64(k_window).reshape(-1, plan.d)
+    k_all = np.concatenate([reconstruct(plan, records, signs), kw], axis=0)
+    assert v.shape == k_all.shape
+    scores = scale * (q @ k_all.T)
+    out = np.zeros((q.shape[0], plan.d))
+    if k_all.shape[0]:
+        w = np.exp(scores - scores.max(axis=1, keepdims=True))
+        out = (w / w.sum(axis=1, keepdims=True)) @ v
+    return scores, out

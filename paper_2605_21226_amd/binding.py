@@ -20,7 +20,8 @@ TILE = 64
 EXPORTS = ("octopus_build_codebooks", "octopus_build_codebooks_pair", "octopus_cache_bytes", "octopus_encode",
            "octopus_attn_decode_workspace", "octopus_attn_decode", "octopus_profile_events", "octopus_strerror",
            "octopus_qjl_bytes", "octopus_encode_qjl", "octopus_attn_decode_qjl",
-           "octopus_encode_rounding")
+           "octopus_encode_rounding", "octopus_vq_row_bytes", "octopus_vq_bytes", "octopus_encode_values",
+           "octopus_attn_decode_vq")
 
 
 class Plan(ctypes.Structure):
@@ -84,6 +85,15 @@ def load():
     lib.octopus_qjl_bytes.restype = ctypes.c_size_t
     lib.octopus_encode_rounding.argtypes = [CB, vp, i32, i64, i64, i64, i32, i32, i32, vp, vp, i64, vp, i32, vp]
     lib.octopus_encode_rounding.restype = ctypes.c_int
+    lib.octopus_vq_row_bytes.argtypes = [i32, i32, i32]
+    lib.octopus_vq_row_bytes.restype = ctypes.c_size_t
+    lib.octopus_vq_bytes.argtypes = [i32, i32, i32, i32, i32, i64]
+    lib.octopus_vq_bytes.restype = ctypes.c_size_t
+    lib.octopus_encode_values.argtypes = [vp, i32, i64, i64, i64, i32, i32, i32, i32, i32, i32, vp, i64, vp, vp]
+    lib.octopus_encode_values.restype = ctypes.c_int
+    lib.octopus_attn_decode_vq.argtypes = [CB, vp, i32, i32, i32, i32, i32, vp, vp, i64, vp, i32, i32, vp, i64, f32,
+                                           vp, vp, vp, ctypes.c_size_t, vp]
+    lib.octopus_attn_decode_vq.restype = ctypes.c_int
     lib.octopus_encode_qjl.argtypes = [CB, vp, i32, i64, i64, i64, i32, i32, i32, vp, vp, vp, vp, i64, vp, vp]
     lib.octopus_encode_qjl.restype = ctypes.c_int
     lib.octopus_attn_decode_workspace.argtypes = [CB, i32, i32, i32, i32, i64]
@@ -219,6 +229,39 @@ def octopus_attn_decode_qjl(cb, q, signs, signs2, cache, qjl, t_capacity, v, seq
                                           _ptr(scores_out), _ptr(workspace),
                                           int(workspace.numel() * workspace.element_size()), _stream_ptr(stream))
     _check(code, "octopus_attn_decode_qjl")
+
+
+def octopus_vq_row_bytes(head_dim, bits, group):
+    return int(load().octopus_vq_row_bytes(int(head_dim), int(bits), int(group)))
+
+
+def octopus_vq_bytes(head_dim, bits, group, n_seq, n_kv_heads, t_capacity):
+    return int(load().octopus_vq_bytes(int(head_dim), int(bits), int(group), int(n_seq), int(n_kv_heads),
+                                       int(t_capacity)))
+
+
+def octopus_encode_values(v, bits, group, vq, t_capacity, start_pos=None, stream=None):
+    """v: device [n_seq, n_new, n_kv_heads, d] (fp32 or bf16, channels contiguous); vq: device uint8 buffer of
+    octopus_vq_bytes(...) bytes."""
+    assert v.dim() == 4 and v.stride(3) == 1
+    n_seq, n_new, n_kv, d = v.shape
+    code = load().octopus_encode_values(_ptr(v), _dtype_code(v), v.stride(0), v.stride(1), v.stride(2), n_seq, n_kv,
+                                        n_new, d, int(bits), int(group), _ptr(vq), int(t_capacity), _ptr(start_pos),
+                                        _stream_ptr(stream))
+    _check(code, "octopus_encode_values")
+
+
+def octopus_attn_decode_vq(cb, q, signs, cache, t_capacity, vq, v_bits, v_group, n_kv_heads, seq_lens, max_len, scale,
+                           out, workspace, scores_out=None, stream=None):
+    """octopus_attn_decode over the quantised value rows vq (octopus_encode_values)."""
+    assert q.is_contiguous() and out.is_contiguous()
+    n_seq, n_q, n_qh, _ = q.shape
+    code = load().octopus_attn_decode_vq(ctypes.byref(cb), _ptr(q), _dtype_code(q), n_seq, n_qh, int(n_kv_heads), n_q,
+                                         _ptr(signs), _ptr(cache), int(t_capacity), _ptr(vq), int(v_bits), int(v_group),
+                                         _ptr(seq_lens), int(max_len), float(scale), _ptr(out), _ptr(scores_out),
+                                         _ptr(workspace), int(workspace.numel() * workspace.element_size()),
+                                         _stream_ptr(stream))
+    _check(code, "octopus_attn_decode_vq")
 
 
 def octopus_profile_events(before, after):

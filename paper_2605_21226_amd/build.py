@@ -14,7 +14,8 @@ LIB = os.environ.get("OCTOPUS_LIB_OUT", os.path.join(HERE, "liboctopus.so"))
 
 SOURCES = ["octopus_host.cpp", "octopus_common.hip", "octopus_d64.hip", "octopus_d128.hip", "octopus_d256.hip",
            "octopus_qjl_d64.hip", "octopus_qjl_d128.hip", "octopus_qjl_d256.hip",
-           "octopus_round_d64.hip", "octopus_round_d128.hip", "octopus_round_d256.hip"]
+           "octopus_round_d64.hip", "octopus_round_d128.hip", "octopus_round_d256.hip",
+           "octopus_vq_d64.hip", "octopus_vq_d128.hip", "octopus_vq_d256.hip", "octopus_values.hip"]
 # -packed-fp32-ops is switched off on purpose: hipcc must not form packed fp32 instructions here.
 FLAGS = (["-D" + d for d in os.environ.get("OCTOPUS_DEFS", "").split(",") if d]) + ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]

@@ -891,11 +891,15 @@ struct DecodeSmemValu {
     float pbuf[kDecodeWaves][kWave][RG];
 };
 
-template <class P, int RG>
+// VQ: the values are group-quantised rows (Sec. 4, "value-side group size"; the "value dequantization" of
+// Alg. 2): per token [v_bits-bit codes, channel j at bit v_bits * j][per group of v_group channels: fp32
+// scale, fp32 zero point], dequantised as zero + scale * code while they are accumulated.
+template <class P, int RG, bool VQ = false>
 __global__ __launch_bounds__(kDecodeWaves *kWave) void decode_kernel_valu(
     DeviceBooks books, DecodeShape shp, const float *__restrict__ q_rot, const uint4 *__restrict__ cache,
     const float4 *__restrict__ v, const int32_t *__restrict__ seq_lens, float *__restrict__ part_ml,
-    float *__restrict__ part_acc, float *__restrict__ scores_out, int32_t *__restrict__ plan) {
+    float *__restrict__ part_acc, float *__restrict__ scores_out, int32_t *__restrict__ plan, int v_bits,
+    int v_group) {
     constexpr int D = P::D;
     constexpr int LPR = D / 8;          // lanes per value row (8 channels per lane)
     constexpr int KPL = kWave / LPR;    // value rows per wave-wide load
@@ -970,9 +974,27 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) void decode_kernel_valu(
 #pragma unroll
                 for (int r = 0; r < RG; ++r) pv[r] = sm.pbuf[wave][key][r];
                 const int64_t vrow = v_row0 + t0 + key;
-                const float4 a = v[vrow * (D / 4) + 2 * rl];
-                const float4 b = v[vrow * (D / 4) + 2 * rl + 1];
-                const float vals[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+                float vals[8];
+                if constexpr (VQ) {
+                    // this lane's 8 channels: 8 * v_bits bits at byte rl * v_bits of the row, fetched as the two
+                    // aligned words around them (the second may reach into the row's own metadata)
+                    const int code_bytes = v_bits * (D / 8);
+                    const unsigned char *row = reinterpret_cast<const unsigned char *>(v) +
+                                               vrow * (code_bytes + (D / v_group) * 8);
+                    const int boff = rl * v_bits;
+                    const uint32_t *wp = reinterpret_cast<const uint32_t *>(row) + (boff >> 2);
+                    const uint32_t bits = __builtin_amdgcn_alignbyte(wp[1], wp[0], static_cast<uint32_t>(boff & 3));
+                    const float2 meta = *reinterpret_cast<const float2 *>(row + code_bytes + ((rl * 8) / v_group) * 8);
+                    const uint32_t mask = (1u << v_bits) - 1u;
+#pragma unroll
+                    for (int c = 0; c < 8; ++c)
+                        vals[c] = fmaf(meta.x, static_cast<float>((bits >> (c * v_bits)) & mask), meta.y);
+                } else {
+                    const float4 a = v[vrow * (D / 4) + 2 * rl];
+                    const float4 b = v[vrow * (D / 4) + 2 * rl + 1];
+                    vals[0] = a.x; vals[1] = a.y; vals[2] = a.z; vals[3] = a.w;
+                    vals[4] = b.x; vals[5] = b.y; vals[6] = b.z; vals[7] = b.w;
+                }
 #pragma unroll
                 for (int r = 0; r < RG; ++r)
 #pragma unroll
@@ -1116,7 +1138,7 @@ int launch_decode_rg(const octopus_codebooks_t &cb, const DecodeShape &s, const 
         if (err != hipSuccess) return static_cast<int>(err);
         hipLaunchKernelGGL((decode_kernel_valu<P, RG>), grid, block, smem, stream, books, s, q_rot,
                            static_cast<const uint4 *>(cache), static_cast<const float4 *>(v), seq_lens, part_ml,
-                           part_acc, scores_out, plan);
+                           part_acc, scores_out, plan, 0, 0);
     }
     return static_cast<int>(hipGetLastError());
 }
@@ -1136,6 +1158,39 @@ int launch_decode_plan(const octopus_codebooks_t &cb, const DecodeShape &s, cons
                     return launch_decode_mq<P>(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, stream);
             }
             return static_cast<int>(hipErrorInvalidValue);
+        default: return static_cast<int>(hipErrorInvalidValue);
+    }
+}
+
+// Decode attention over group-quantised values.
+template <class P, int RG>
+int launch_decode_vq_rg(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
+                        const void *vq, int v_bits, int v_group, const int32_t *seq_lens, float *part_ml,
+                        float *part_acc, float *scores_out, int32_t *plan, hipStream_t stream) {
+    DeviceBooks books;
+    for (int c = 0; c < 2; ++c) {
+        for (int k = 0; k < 32; ++k) books.c_xi[c][k] = cb.c_xi[c][k];
+        for (int k = 0; k < 8; ++k) books.c_rho[c][k] = cb.c_rho[c][k];
+    }
+    const size_t smem = sizeof(DecodeSmemValu<P, RG>);
+    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel_valu<P, RG, true>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem));
+    if (err != hipSuccess) return static_cast<int>(err);
+    hipLaunchKernelGGL((decode_kernel_valu<P, RG, true>), dim3(kDecodeWorkgroups), dim3(kDecodeWaves * kWave), smem,
+                       stream, books, s, q_rot, static_cast<const uint4 *>(cache), static_cast<const float4 *>(vq),
+                       seq_lens, part_ml, part_acc, scores_out, plan, v_bits, v_group);
+    return static_cast<int>(hipGetLastError());
+}
+
+template <class P>
+int launch_decode_vq_plan(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
+                          const void *vq, int v_bits, int v_group, const int32_t *seq_lens, float *part_ml,
+                          float *part_acc, float *scores_out, int32_t *plan, hipStream_t stream) {
+    switch (s.rows_per_pass) {
+        case 1: return launch_decode_vq_rg<P, 1>(cb, s, q_rot, cache, vq, v_bits, v_group, seq_lens, part_ml, part_acc, scores_out, plan, stream);
+        case 2: return launch_decode_vq_rg<P, 2>(cb, s, q_rot, cache, vq, v_bits, v_group, seq_lens, part_ml, part_acc, scores_out, plan, stream);
+        case 4: return launch_decode_vq_rg<P, 4>(cb, s, q_rot, cache, vq, v_bits, v_group, seq_lens, part_ml, part_acc, scores_out, plan, stream);
+        case 8: return launch_decode_vq_rg<P, 8>(cb, s, q_rot, cache, vq, v_bits, v_group, seq_lens, part_ml, part_acc, scores_out, plan, stream);
         default: return static_cast<int>(hipErrorInvalidValue);
     }
 }

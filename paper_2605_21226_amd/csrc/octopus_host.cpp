@@ -477,9 +477,15 @@ static int attn_decode(const octopus_codebooks_t *cb, const void *q, int32_t q_d
                        int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q, const uint8_t *signs, const void *cache,
                        int64_t t_capacity, const void *v, int32_t v_dtype, const int32_t *seq_lens, int64_t max_len,
                        float scale, float *out, float *scores_out, void *workspace, size_t workspace_bytes,
-                       void *stream, bool with_qjl, const uint8_t *signs2, const void *qjl) {
+                       void *stream, bool with_qjl, const uint8_t *signs2, const void *qjl, int v_bits = 0,
+                       int v_group = 0) {
+    const bool with_vq = v_bits != 0;    // v: group-quantised rows (v_dtype is not looked at)
     const int ok = decode_args_ok(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len);
     if (ok != OCTOPUS_OK) return ok;
+    if (with_vq) {
+        if (v_bits < 2 || v_bits > 4 || (v_group != 16 && v_group != 32)) return OCTOPUS_EUNSUPPORTED;
+        v_dtype = OCTOPUS_DTYPE_F32;     // served by the kernel that accumulates on the vector units
+    }
     if (q == nullptr || signs == nullptr || cache == nullptr || v == nullptr || seq_lens == nullptr || out == nullptr)
         return OCTOPUS_EINVAL;
     if (with_qjl && (signs2 == nullptr || qjl == nullptr)) return OCTOPUS_EINVAL;
@@ -491,7 +497,7 @@ static int attn_decode(const octopus_codebooks_t *cb, const void *q, int32_t q_d
     if (!aligned(cache, 16) || !aligned(v, 16) || !aligned(q, 4) || !aligned(out, 4)) return OCTOPUS_EINVAL;
     if (with_qjl && !aligned(qjl, 4)) return OCTOPUS_EINVAL;
     if (!std::isfinite(scale)) return OCTOPUS_EINVAL;
-    const bool many_rows = !with_qjl && many_rows_shape(cb->plan, n_q_heads, n_kv_heads, n_q) &&
+    const bool many_rows = !with_qjl && !with_vq && many_rows_shape(cb->plan, n_q_heads, n_kv_heads, n_q) &&
                            v_dtype == OCTOPUS_DTYPE_BF16 && scores_out == nullptr;
     const int rows_cap = with_qjl ? qjl_rows_cap(cb->plan) : 8;
     if (rows_cap <= 0) return OCTOPUS_EUNSUPPORTED;
@@ -511,10 +517,15 @@ static int attn_decode(const octopus_codebooks_t *cb, const void *q, int32_t q_d
     g_event_before = g_event_after = nullptr;
     if (err == 0 && ev_before != nullptr) err = record_event(ev_before, stream);
     if (err == 0) {
-        err = with_qjl ? launch_decode_qjl(*cb, s, q_rot, cache, qjl, q2, v, seq_lens, part_ml, part_acc, scores_out,
-                                           work_plan, stream)
-                       : launch_decode(*cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out,
-                                       work_plan, stream);
+        if (with_qjl)
+            err = launch_decode_qjl(*cb, s, q_rot, cache, qjl, q2, v, seq_lens, part_ml, part_acc, scores_out, work_plan,
+                                    stream);
+        else if (with_vq)
+            err = launch_decode_vq(*cb, s, q_rot, cache, v, v_bits, v_group, seq_lens, part_ml, part_acc, scores_out,
+                                   work_plan, stream);
+        else
+            err = launch_decode(*cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, work_plan,
+                                stream);
     }
     if (err == 0 && ev_after != nullptr) err = record_event(ev_after, stream);
     if (err == 0) err = launch_merge(cb->plan, s, part_ml, part_acc, work_plan, out, stream);
@@ -539,6 +550,50 @@ int octopus_attn_decode_qjl(const octopus_codebooks_t *cb, const void *q, int32_
     return attn_decode(cb, q, q_dtype, n_seq, n_q_heads, n_kv_heads, n_q, signs, cache, t_capacity, v, v_dtype,
                        seq_lens, max_len, scale, out, scores_out, workspace, workspace_bytes, stream, true, signs2,
                        qjl);
+}
+
+static bool vq_params_ok(int32_t head_dim, int32_t bits, int32_t group) {
+    return (head_dim == 64 || head_dim == 128 || head_dim == 256) && bits >= 2 && bits <= 4 &&
+           (group == 16 || group == 32);
+}
+
+size_t octopus_vq_row_bytes(int32_t head_dim, int32_t bits, int32_t group) {
+    if (!vq_params_ok(head_dim, bits, group)) return 0;
+    return static_cast<size_t>(bits) * head_dim / 8 + static_cast<size_t>(head_dim / group) * 8;
+}
+
+size_t octopus_vq_bytes(int32_t head_dim, int32_t bits, int32_t group, int32_t n_seq, int32_t n_kv_heads,
+                        int64_t t_capacity) {
+    if (n_seq < 1 || n_kv_heads < 1 || t_capacity < 1) return 0;
+    return octopus_vq_row_bytes(head_dim, bits, group) * n_seq * n_kv_heads * static_cast<size_t>(t_capacity);
+}
+
+int octopus_encode_values(const void *v, int32_t v_dtype, int64_t stride_seq, int64_t stride_tok, int64_t stride_head,
+                          int32_t n_seq, int32_t n_kv_heads, int32_t n_new, int32_t head_dim, int32_t bits,
+                          int32_t group, void *vq, int64_t t_capacity, const int32_t *start_pos, void *stream) {
+    if (v == nullptr || vq == nullptr) return OCTOPUS_EINVAL;
+    if (n_seq < 1 || n_kv_heads < 1 || n_new < 0 || t_capacity < 1) return OCTOPUS_EINVAL;
+    if (v_dtype != OCTOPUS_DTYPE_F32 && v_dtype != OCTOPUS_DTYPE_BF16) return OCTOPUS_EUNSUPPORTED;
+    if (!vq_params_ok(head_dim, bits, group)) return OCTOPUS_EUNSUPPORTED;
+    if (stride_seq < 0 || stride_tok < 0 || stride_head < 0) return OCTOPUS_EINVAL;
+    if (!aligned(v, 4) || !aligned(vq, 16)) return OCTOPUS_EINVAL;
+    if (start_pos == nullptr && n_new > t_capacity) return OCTOPUS_EINVAL;
+    if (static_cast<int64_t>(n_seq) * n_new * n_kv_heads * (head_dim / group) > (int64_t{1} << 38)) return OCTOPUS_EINVAL;
+    if (n_new == 0) return OCTOPUS_OK;
+    const int err = launch_encode_values(v, v_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new,
+                                         head_dim, bits, group, vq, t_capacity, start_pos, stream);
+    return err == 0 ? OCTOPUS_OK : OCTOPUS_EHIP;
+}
+
+int octopus_attn_decode_vq(const octopus_codebooks_t *cb, const void *q, int32_t q_dtype, int32_t n_seq,
+                           int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q, const uint8_t *signs, const void *cache,
+                           int64_t t_capacity, const void *vq, int32_t v_bits, int32_t v_group,
+                           const int32_t *seq_lens, int64_t max_len, float scale, float *out, float *scores_out,
+                           void *workspace, size_t workspace_bytes, void *stream) {
+    if (v_bits == 0) return OCTOPUS_EUNSUPPORTED;
+    return attn_decode(cb, q, q_dtype, n_seq, n_q_heads, n_kv_heads, n_q, signs, cache, t_capacity, vq,
+                       OCTOPUS_DTYPE_F32, seq_lens, max_len, scale, out, scores_out, workspace, workspace_bytes, stream,
+                       false, nullptr, nullptr, v_bits, v_group);
 }
 
 const char *octopus_strerror(int code) {

@@ -70,6 +70,14 @@ int launch_encode_rounding(const octopus_codebooks_t &cb, const void *keys, int 
                            const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos,
                            int32_t mode, void *stream);
 
+// Value codec (group-quantised value rows) and decode attention over it.
+int launch_encode_values(const void *v, int v_dtype, int64_t stride_seq, int64_t stride_tok, int64_t stride_head,
+                         int32_t n_seq, int32_t n_kv_heads, int32_t n_new, int32_t head_dim, int32_t bits,
+                         int32_t group, void *vq, int64_t t_capacity, const int32_t *start_pos, void *stream);
+int launch_decode_vq(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
+                     const void *vq, int v_bits, int v_group, const int32_t *seq_lens, float *part_ml,
+                     float *part_acc, float *scores_out, int32_t *work_plan, void *stream);
+
 // hipEventRecord(event, stream); returns a hipError_t cast to int.
 int record_event(void *event, void *stream);
 

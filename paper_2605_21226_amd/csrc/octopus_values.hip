@@ -1,0 +1,96 @@
+// Value codec: per-group uniform quantisation of value rows (Sec. 4, "value-side group size in {16, 32}").
+// The paper fixes the group size, the bit width and (through the KV ratios of Table (kernel speed)) the row
+// size b d / 8 + 8 d / g bytes; the codec itself is this library's reading: asymmetric min/max quantisation
+// per group with an fp32 scale and an fp32 zero point.
+#include <hip/hip_runtime.h>
+
+#include "octopus_internal.h"
+
+namespace octopus {
+
+// One thread per (token, KV head, group): min and max of the group's g values, scale = (max - min) /
+// (2^b - 1), code = rint((v - min) / scale) clamped; each a single correctly rounded fp32 operation.
+template <bool BF16>
+__global__ __launch_bounds__(256) void encode_values_kernel(const void *__restrict__ v, int64_t stride_seq,
+                                                             int64_t stride_tok, int64_t stride_head, int32_t n_seq,
+                                                             int32_t n_kv_heads, int32_t n_new, int32_t d, int32_t bits,
+                                                             int32_t group, unsigned char *__restrict__ vq,
+                                                             int64_t t_capacity,
+                                                             const int32_t *__restrict__ start_pos) {
+    const int n_groups = d / group;
+    const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    const int64_t total = static_cast<int64_t>(n_seq) * n_new * n_kv_heads * n_groups;
+    if (idx >= total) return;
+    const int grp = static_cast<int>(idx % n_groups);
+    const int kvh = static_cast<int>((idx / n_groups) % n_kv_heads);
+    const int tok = static_cast<int>((idx / (static_cast<int64_t>(n_groups) * n_kv_heads)) % n_new);
+    const int seq = static_cast<int>(idx / (static_cast<int64_t>(n_groups) * n_kv_heads * n_new));
+    const int64_t pos = (start_pos ? start_pos[seq] : 0) + tok;
+    if (pos >= t_capacity) return;
+
+    const int64_t src = seq * stride_seq + tok * stride_tok + kvh * stride_head + static_cast<int64_t>(grp) * group;
+    float x[32];
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+        if (j < group) {
+            x[j] = BF16 ? __uint_as_float(static_cast<uint32_t>(static_cast<const uint16_t *>(v)[src + j]) << 16)
+                        : static_cast<const float *>(v)[src + j];
+        } else {
+            x[j] = x[0];
+        }
+    }
+    float lo = x[0], hi = x[0];
+#pragma unroll
+    for (int j = 1; j < 32; ++j) {
+        lo = x[j] < lo ? x[j] : lo;
+        hi = x[j] > hi ? x[j] : hi;
+    }
+    const int levels = (1 << bits) - 1;
+    const float scale = __fdiv_rn(__fsub_rn(hi, lo), static_cast<float>(levels));
+
+    const int row_bytes = bits * d / 8 + n_groups * 8;
+    unsigned char *row = vq + ((static_cast<int64_t>(seq) * n_kv_heads + kvh) * t_capacity + pos) * row_bytes;
+    // the group's codes: group * bits bits = 2 * bits (g = 16) or 4 * bits (g = 32) bytes, written as 16-bit words
+    uint16_t *dst = reinterpret_cast<uint16_t *>(row + grp * (group * bits / 8));
+    uint32_t word = 0u;
+    int filled = 0, out = 0;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+        if (j < group) {
+            uint32_t code = 0u;
+            if (scale > 0.0f) {
+                float c = rintf(__fdiv_rn(__fsub_rn(x[j], lo), scale));
+                c = fminf(fmaxf(c, 0.0f), static_cast<float>(levels));
+                code = static_cast<uint32_t>(c);
+            }
+            word |= code << filled;
+            filled += bits;
+            if (filled >= 16) {
+                dst[out++] = static_cast<uint16_t>(word & 0xffffu);
+                word >>= 16;
+                filled -= 16;
+            }
+        }
+    }
+    float2 *meta = reinterpret_cast<float2 *>(row + bits * d / 8 + grp * 8);
+    *meta = make_float2(scale, lo);
+}
+
+int launch_encode_values(const void *v, int v_dtype, int64_t stride_seq, int64_t stride_tok, int64_t stride_head,
+                         int32_t n_seq, int32_t n_kv_heads, int32_t n_new, int32_t head_dim, int32_t bits,
+                         int32_t group, void *vq, int64_t t_capacity, const int32_t *start_pos, void *stream) {
+    const int64_t total = static_cast<int64_t>(n_seq) * n_new * n_kv_heads * (head_dim / group);
+    const dim3 grid(static_cast<unsigned>((total + 255) / 256));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (v_dtype == OCTOPUS_DTYPE_BF16)
+        hipLaunchKernelGGL(encode_values_kernel<true>, grid, dim3(256), 0, st, v, stride_seq, stride_tok, stride_head,
+                           n_seq, n_kv_heads, n_new, head_dim, bits, group, static_cast<unsigned char *>(vq),
+                           t_capacity, start_pos);
+    else
+        hipLaunchKernelGGL(encode_values_kernel<false>, grid, dim3(256), 0, st, v, stride_seq, stride_tok, stride_head,
+                           n_seq, n_kv_heads, n_new, head_dim, bits, group, static_cast<unsigned char *>(vq),
+                           t_capacity, start_pos);
+    return static_cast<int>(hipGetLastError());
+}
+
+}  // namespace octopus

@@ -168,3 +168,33 @@ def test_encode_refuses_a_codebook_too_fine_for_the_seed_grid():
     bad2 = binding.Codebooks.from_buffer_copy(cb)
     bad2.c_xi[0][3], bad2.c_xi[0][4] = bad2.c_xi[0][4], bad2.c_xi[0][3]   # not ascending
     assert lib.octopus_encode(ctypes.byref(bad2), *args) == binding.EUNSUPPORTED
+
+
+def test_value_codec_sizes_and_argument_checks(lib):
+    for d in (64, 128, 256):
+        for b in (2, 3, 4):
+            for g in (16, 32):
+                assert binding.octopus_vq_row_bytes(d, b, g) == oracle.vq_row_bytes(d, b, g) == b * d // 8 + 8 * d // g
+    assert binding.octopus_vq_row_bytes(128, 1, 32) == 0 and binding.octopus_vq_row_bytes(128, 3, 64) == 0
+    assert binding.octopus_vq_bytes(128, 3, 32, 16, 8, 32768) == 80 * 16 * 8 * 32768
+    assert binding.octopus_vq_bytes(128, 3, 32, 0, 8, 64) == 0
+    fake, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+    enc = lib.octopus_encode_values
+    assert enc(null, 1, 1024, 1024, 128, 1, 8, 64, 128, 3, 32, fake, 64, null, null) == binding.EINVAL
+    assert enc(fake, 1, 1024, 1024, 128, 1, 8, 64, 128, 3, 32, null, 64, null, null) == binding.EINVAL
+    assert enc(fake, 1, 1024, 1024, 128, 1, 8, 64, 128, 5, 32, fake, 64, null, null) == binding.EUNSUPPORTED
+    assert enc(fake, 1, 1024, 1024, 128, 1, 8, 64, 96, 3, 32, fake, 64, null, null) == binding.EUNSUPPORTED
+    assert enc(fake, 7, 1024, 1024, 128, 1, 8, 64, 128, 3, 32, fake, 64, null, null) == binding.EUNSUPPORTED
+    assert enc(fake, 1, 1024, 1024, 128, 1, 8, 128, 128, 3, 32, fake, 64, null, null) == binding.EINVAL    # overflow
+    assert enc(fake, 1, 1024, 1024, 128, 1, 8, 64, 128, 3, 32, ctypes.c_void_p(0x1008), 64, null, null) == binding.EINVAL
+    assert enc(fake, 1, 1024, 1024, 128, 1, 8, 0, 128, 3, 32, fake, 64, null, null) == binding.OK          # nothing to do
+    cb = binding.octopus_build_codebooks(128, 3)
+    ws = binding.octopus_attn_decode_workspace(cb, 2, 32, 8, 1, 4096)
+    dec = lib.octopus_attn_decode_vq
+    args = lambda **k: [ctypes.byref(cb), fake, 1, 2, 32, 8, 1, fake, fake, 4096, k.get("vq", fake), k.get("bits", 3),
+                        k.get("group", 32), fake, 4096, ctypes.c_float(0.1), fake, null, ctypes.c_void_p(0x10000),
+                        k.get("ws_bytes", ws), null]
+    assert dec(*args(vq=null)) == binding.EINVAL
+    assert dec(*args(bits=1)) == binding.EUNSUPPORTED
+    assert dec(*args(group=8)) == binding.EUNSUPPORTED
+    assert dec(*args(ws_bytes=ws - 1)) == binding.EWORKSPACE
