@@ -1,0 +1,83 @@
+// Native-precision window of a hybrid cache (Sec. 4, default recipe: a short residual window of recent
+// tokens kept uncompressed).  The window's tokens follow the compressed ones of their sequence; their
+// keys are read as stored, their scores are the plain scale * q . k, and the partial (m, l, acc) of the
+// window joins the split partials of the compressed part in the merge (flash-decoding identity, App. A).
+#ifndef OCTOPUS_WINDOW_HPP_
+#define OCTOPUS_WINDOW_HPP_
+
+#include "octopus_device.hpp"
+#include "octopus_internal.h"
+
+namespace octopus {
+
+// One wavefront per output row (sequence, query, query head).  Keys: [n_seq][n_kv_heads][w_capacity][D],
+// values: rows seq_lens[s] + j of the value buffer [n_seq][n_kv_heads][t_capacity][D] (bf16 or fp32 each).
+// Chunks of 64 window tokens, one token per lane for the scores (the query sits in LDS), then every lane
+// accumulates its D / 64 channels over the chunk's tokens.
+template <int D>
+__global__ __launch_bounds__(kWave) void window_kernel(DecodeShape shp, const void *__restrict__ q, int q_is_bf16,
+                                                       const void *__restrict__ k_win, int k_is_bf16,
+                                                       int64_t w_capacity, const int32_t *__restrict__ win_lens,
+                                                       const void *__restrict__ v, int v_is_bf16,
+                                                       const int32_t *__restrict__ seq_lens, float scale,
+                                                       float *__restrict__ win_ml, float *__restrict__ win_acc,
+                                                       float *__restrict__ scores_out) {
+    constexpr int CPT = D / kWave;  // channels per lane: c * 64 + lane
+    __shared__ float qs[D];
+    const int lane = threadIdx.x;
+    const int64_t orow = blockIdx.x;  // (seq, qi, head)
+    const int head = static_cast<int>(orow % shp.n_q_heads);
+    const int seq = static_cast<int>(orow / (static_cast<int64_t>(shp.n_q_heads) * shp.n_q));
+    const int kvh = head / shp.heads_per_kv;
+    auto load = [](const void *p, int is_bf16, int64_t i) {
+        return is_bf16 ? __uint_as_float(static_cast<uint32_t>(static_cast<const uint16_t *>(p)[i]) << 16)
+                       : static_cast<const float *>(p)[i];
+    };
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) qs[c * kWave + lane] = load(q, q_is_bf16, orow * D + c * kWave + lane) * scale;
+    __syncthreads();
+
+    const int64_t len = seq_lens[seq];
+    // the window's tokens must fit behind the compressed ones in the value buffer
+    const int64_t n_win = max(int64_t{0}, min(min(static_cast<int64_t>(win_lens[seq]), w_capacity), shp.t_capacity - len));
+    const int64_t pair = static_cast<int64_t>(seq) * shp.n_kv_heads + kvh;
+    const int64_t k_row0 = pair * w_capacity, v_row0 = pair * shp.t_capacity + len;
+
+    float m_run = -INFINITY, l_run = 0.0f, acc[CPT];
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) acc[c] = 0.0f;
+    for (int64_t j0 = 0; j0 < n_win; j0 += kWave) {
+        const int nj = static_cast<int>(min(static_cast<int64_t>(kWave), n_win - j0));
+        float s = -INFINITY;
+        if (lane < nj) {
+            float dot = 0.0f;
+            const int64_t kb = (k_row0 + j0 + lane) * D;
+            for (int e = 0; e < D; ++e) dot = fmaf(qs[e], load(k_win, k_is_bf16, kb + e), dot);
+            s = dot;
+            if (scores_out != nullptr) scores_out[orow * shp.t_capacity + len + j0 + lane] = s;
+        }
+        const float m_new = fmaxf(m_run, wave_max(s));
+        const float alpha = exp2f((m_run - m_new) * kLog2e);
+        const float p = (lane < nj) ? exp2f((s - m_new) * kLog2e) : 0.0f;
+        m_run = m_new;
+        l_run = fmaf(l_run, alpha, wave_sum(p));
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) acc[c] *= alpha;
+        for (int j = 0; j < nj; ++j) {
+            const float pj = __shfl(p, j, kWave);
+#pragma unroll
+            for (int c = 0; c < CPT; ++c)
+                acc[c] = fmaf(pj, load(v, v_is_bf16, (v_row0 + j0 + j) * D + c * kWave + lane), acc[c]);
+        }
+    }
+    if (lane == 0) {
+        win_ml[orow * 2] = m_run;
+        win_ml[orow * 2 + 1] = l_run;
+    }
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) win_acc[orow * D + c * kWave + lane] = acc[c];
+}
+
+}  // namespace octopus
+
+#endif
