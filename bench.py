@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--rounding", type=int, default=1,
                     help="encoder rounding mode (App. E): 0 seed only, 1 local 3x3 (default), 2 full grid, "
                          "3 independent rounds, 4 local 2x2; the decoder is the same")
+    ap.add_argument("--vq", default="",
+                    help="BITS:GROUP, e.g. 3:32 - quantise the values per group (octopus_encode_values in the encode "
+                         "phase) and decode over them (octopus_attn_decode_vq); single-query workloads only")
     ap.add_argument("--qjl", action="store_true",
                     help="time the variant with the 1-bit QJL residual (octopus_encode_qjl + octopus_attn_decode_qjl); "
                          "single-query workloads only")
@@ -49,7 +52,7 @@ def parse():
     return ap.parse_args()
 
 
-def cpu_baseline(wl, keys, vals, q, signs, scale, record_bytes, budget_s=12.0, signs2=None, mode=1):
+def cpu_baseline(wl, keys, vals, q, signs, scale, record_bytes, budget_s=12.0, signs2=None, mode=1, vq=None):
     """The oracle as it stands, timed on this machine's host cores on a bounded sample of the workload:
     whole sequences (all KV heads, all cached tokens; encode, then attention of each KV head's group of
     query heads over its tokens), one sequence after another until about `budget_s` seconds are spent."""
@@ -71,6 +74,9 @@ def cpu_baseline(wl, keys, vals, q, signs, scale, record_bytes, budget_s=12.0, s
         k_heads = [np.ascontiguousarray(k_host[:, h]) for h in range(wl.n_kv_heads)]
         t0 = time.perf_counter()
         recs = [oracle.encode(plan, k_heads[h], signs[h], mode=mode) for h in range(wl.n_kv_heads)]   # same numbering
+        if vq is not None:      # quantise and dequantise the values as the value codec does
+            v_host = [oracle.vq_decode(oracle.vq_encode(v_host[h][:n_tok], vq[0], vq[1]), wl.head_dim, vq[0], vq[1])
+                      for h in range(wl.n_kv_heads)]
         if signs2 is not None:
             side = [oracle.qjl_encode(plan, k_heads[h], signs[h], signs2[h], recs[h]) for h in range(wl.n_kv_heads)]
         t1 = time.perf_counter()
@@ -89,7 +95,8 @@ def cpu_baseline(wl, keys, vals, q, signs, scale, record_bytes, budget_s=12.0, s
             break
     n_keys = n_seq_done * n_tok * wl.n_kv_heads
     elt = 2 if wl.dtype == "bf16" else 4
-    dec_bytes = n_keys * (record_bytes + wl.head_dim * elt + (wl.head_dim // 8 + 2 if signs2 is not None else 0))
+    v_bytes = oracle.vq_row_bytes(wl.head_dim, vq[0], vq[1]) if vq is not None else wl.head_dim * elt
+    dec_bytes = n_keys * (record_bytes + v_bytes + (wl.head_dim // 8 + 2 if signs2 is not None else 0))
     threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     return {
         "value": round(dec_bytes / dec_s / 1e9, 4),
@@ -143,6 +150,10 @@ def main():
     torch.cuda.set_device(0)
     wl = synth.WORKLOADS[args.workload]
     many_rows = wl.n_q > 1
+    v_bits, v_group = (int(x) for x in args.vq.split(":")) if args.vq else (0, 0)
+    if args.vq and (many_rows or args.qjl):
+        print("bench.py: --vq times single-query workloads without --qjl", file=sys.stderr)
+        sys.exit(2)
     if args.qjl and args.rounding != 1:
         print("bench.py: --qjl goes with the default rounding", file=sys.stderr)
         sys.exit(2)
@@ -180,9 +191,17 @@ def main():
         s2bits = torch.from_numpy(synth.sign_bits(signs2)).to(dev)
         side = torch.zeros(binding.octopus_qjl_bytes(cb, wl.n_seq, wl.n_kv_heads, cap), dtype=torch.uint8, device=dev)
 
+    vq = vals_tok = None
+    if args.vq:
+        vq = torch.zeros(binding.octopus_vq_bytes(wl.head_dim, v_bits, v_group, wl.n_seq, wl.n_kv_heads, cap),
+                         dtype=torch.uint8, device=dev)
+        vals_tok = vals.permute(0, 2, 1, 3)[:, :wl.n_tokens]      # [n_seq, n_tokens, n_kv_heads, d] view
+
     def step(ev=None):
         if ev:
             ev[0].record()
+        if args.vq:
+            binding.octopus_encode_values(vals_tok, v_bits, v_group, vq, cap)
         if args.qjl:
             binding.octopus_encode_qjl(cb, keys[:, first:], sbits, s2bits, cache, side, cap, start_dev)
         elif args.rounding != 1:
@@ -194,6 +213,9 @@ def main():
             binding.octopus_profile_events(ev[3], ev[4])  # around the fused kernel inside the next call
         if args.qjl:
             binding.octopus_attn_decode_qjl(cb, q, sbits, s2bits, cache, side, cap, vals, lens_dev, max_len, scale, out, ws)
+        elif args.vq:
+            binding.octopus_attn_decode_vq(cb, q, sbits, cache, cap, vq, v_bits, v_group, wl.n_kv_heads, lens_dev, max_len,
+                                           scale, out, ws)
         else:
             binding.octopus_attn_decode(cb, q, sbits, cache, cap, vals, lens_dev, max_len, scale, out, ws)
         if ev:
@@ -223,7 +245,8 @@ def main():
     rec_bytes = cb.plan.record_bytes
     q_out_bytes = wl.n_seq * wl.n_q * wl.n_q_heads * wl.head_dim * (elt + 4)
     side_bytes = wl.head_dim // 8 + 2 if args.qjl else 0     # sign bits + fp16 residual norm per key
-    dec_bytes = n_keys_dec * (rec_bytes + side_bytes + wl.head_dim * elt) + q_out_bytes
+    v_row_bytes = binding.octopus_vq_row_bytes(wl.head_dim, v_bits, v_group) if args.vq else wl.head_dim * elt
+    dec_bytes = n_keys_dec * (rec_bytes + side_bytes + v_row_bytes) + q_out_bytes
     dec_s = float(dec_ms.mean()) * 1e-3
     enc_s = float(enc_ms.mean()) * 1e-3
     gbs = dec_bytes / dec_s / 1e9
@@ -244,7 +267,8 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {
-            "workload": f"{wl.name}{' + QJL residual' if args.qjl else ''}: batch {wl.n_seq}, {wl.n_q_heads} query / {wl.n_kv_heads} KV heads, head_dim "
+            "workload": f"{wl.name}{' + QJL residual' if args.qjl else ''}"
+                        f"{f' + values quantised to {v_bits} bits in groups of {v_group}' if args.vq else ''}: batch {wl.n_seq}, {wl.n_q_heads} query / {wl.n_kv_heads} KV heads, head_dim "
                         f"{wl.head_dim}, {wl.n_tokens} cached tokens, {wl.dtype} K/V/Q, {wl.bits:g} bits/coordinate "
                         f"(b_dir {cb.plan.b_dir[0]}, b_nrm {cb.plan.b_nrm[0]}); step = encode of "
                         f"{wl.n_seq * n_new} tokens + one decode-attention call"
@@ -252,6 +276,8 @@ def main():
             "record_bytes": rec_bytes,
             "qjl_sidecar_bytes": side_bytes,
             "encoder_rounding": args.rounding,
+            "value_row_bytes": v_row_bytes,
+            "encode_phase_includes_value_quantisation": bool(args.vq),
             "keys": n_keys_dec,
         },
         "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
@@ -273,7 +299,10 @@ def main():
             "kernel_ms": round(ker_s * 1e3, 4),
         },
     }
-    result["roofline"]["traffic"] = measured_traffic(wl.name + ("_qjl" if args.qjl else ""))
+    result["roofline"]["traffic"] = measured_traffic(wl.name + ("_qjl" if args.qjl else "") +
+                                                     (f"_vq{v_bits}g{v_group}" if args.vq else ""))
+    if args.vq:
+        result["roofline"]["kernel"] = result["roofline"]["kernel"].replace("decode_kernel_mfma", "decode_kernel_valu")
     if many_rows and wl.head_dim <= 128 and wl.n_q * (wl.n_q_heads // wl.n_kv_heads) >= 32 and wl.dtype == "bf16":
         # hundreds of query rows per key: a dense contraction on the matrix cores, 4 d flops per (query row, key)
         flops = 4.0 * wl.head_dim * wl.n_q * wl.n_q_heads * float(lens.astype(np.int64).sum())
@@ -293,7 +322,8 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(wl, keys, vals, q, signs, scale, rec_bytes, signs2=signs2, mode=args.rounding)
+        result["cpu_baseline"] = cpu_baseline(wl, keys, vals, q, signs, scale, rec_bytes, signs2=signs2, mode=args.rounding,
+                                              vq=(v_bits, v_group) if args.vq else None)
     print(json.dumps(result))
 
 
