@@ -244,6 +244,34 @@ int octopus_attn_decode_qjl(const octopus_codebooks_t *cb,
                             void *workspace, size_t workspace_bytes,
                             void *stream);
 
+/* ---- hybrid cache: compressed tokens + a native-precision window (Sec. 4, default recipe) ----
+ * The most recent tokens of a sequence are kept uncompressed.  Sequence s holds seq_lens[s]
+ * compressed tokens (cache rows 0 .. seq_lens[s]-1) followed by win_lens[s] window tokens whose
+ * keys are k_window[s][h][0 .. win_lens[s]-1]; the value buffer holds all of them in order, the
+ * window's at rows seq_lens[s] + j.  out = softmax over both parts of scale * q . k (the true key
+ * for window tokens, k^ for compressed ones) times the values: the window's partial (m, l, acc)
+ * joins the split partials in the merge (flash-decoding identity, App. A).
+ *   k_window    device, [n_seq][n_kv_heads][w_capacity][d] contiguous, k_dtype F32/BF16.
+ *   win_lens    device [n_seq] int32, 0 <= win_lens[s] <= w_capacity; window tokens that would
+ *               not fit below t_capacity in the value buffer are ignored.
+ *   scores_out  window scores are written at positions seq_lens[s] + j.
+ * Other arguments, workspace and errors as octopus_attn_decode; EINVAL if k_window or win_lens
+ * is NULL or w_capacity < 1.  Moving a token out of the window is an octopus_encode call for it
+ * (start_pos = its position) by the caller. */
+int octopus_attn_decode_hybrid(const octopus_codebooks_t *cb,
+                               const void *q, int32_t q_dtype,
+                               int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q,
+                               const uint8_t *signs,
+                               const void *cache, int64_t t_capacity,
+                               const void *v, int32_t v_dtype,
+                               const int32_t *seq_lens, int64_t max_len,
+                               const void *k_window, int32_t k_dtype, int64_t w_capacity,
+                               const int32_t *win_lens,
+                               float scale,
+                               float *out, float *scores_out,
+                               void *workspace, size_t workspace_bytes,
+                               void *stream);
+
 /* ---- value codec: per-group quantised values (Sec. 4, "value-side group size in {16, 32}") ----
  * The paper fixes the group size g, the bit width b (that of the keys) and, through the KV
  * ratios of Table (kernel speed), the row size b d / 8 + 8 d / g bytes; the codec is this

@@ -21,7 +21,7 @@ EXPORTS = ("octopus_build_codebooks", "octopus_build_codebooks_pair", "octopus_c
            "octopus_attn_decode_workspace", "octopus_attn_decode", "octopus_profile_events", "octopus_strerror",
            "octopus_qjl_bytes", "octopus_encode_qjl", "octopus_attn_decode_qjl",
            "octopus_encode_rounding", "octopus_vq_row_bytes", "octopus_vq_bytes", "octopus_encode_values",
-           "octopus_attn_decode_vq")
+           "octopus_attn_decode_vq", "octopus_attn_decode_hybrid")
 
 
 class Plan(ctypes.Structure):
@@ -104,6 +104,9 @@ def load():
     lib.octopus_attn_decode_qjl.argtypes = [CB, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, i64, vp, i32, vp, i64, f32,
                                             vp, vp, vp, ctypes.c_size_t, vp]
     lib.octopus_attn_decode_qjl.restype = ctypes.c_int
+    lib.octopus_attn_decode_hybrid.argtypes = [CB, vp, i32, i32, i32, i32, i32, vp, vp, i64, vp, i32, vp, i64, vp, i32,
+                                               i64, vp, f32, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.octopus_attn_decode_hybrid.restype = ctypes.c_int
     lib.octopus_profile_events.argtypes = [vp, vp]
     lib.octopus_profile_events.restype = ctypes.c_int
     lib.octopus_strerror.argtypes = [ctypes.c_int]
@@ -262,6 +265,23 @@ def octopus_attn_decode_vq(cb, q, signs, cache, t_capacity, vq, v_bits, v_group,
                                          _ptr(workspace), int(workspace.numel() * workspace.element_size()),
                                          _stream_ptr(stream))
     _check(code, "octopus_attn_decode_vq")
+
+
+def octopus_attn_decode_hybrid(cb, q, signs, cache, t_capacity, v, seq_lens, max_len, k_window, win_lens, scale, out,
+                               workspace, scores_out=None, stream=None):
+    """octopus_attn_decode plus a native-precision window: k_window device [n_seq, n_kv_heads, w_capacity, d]
+    contiguous (fp32 or bf16), win_lens device int32 [n_seq]; the window's values follow the compressed tokens'
+    in v."""
+    assert q.is_contiguous() and v.is_contiguous() and out.is_contiguous() and k_window.is_contiguous()
+    n_seq, n_q, n_qh, _ = q.shape
+    n_kv = v.shape[1]
+    code = load().octopus_attn_decode_hybrid(ctypes.byref(cb), _ptr(q), _dtype_code(q), n_seq, n_qh, n_kv, n_q,
+                                             _ptr(signs), _ptr(cache), int(t_capacity), _ptr(v), _dtype_code(v),
+                                             _ptr(seq_lens), int(max_len), _ptr(k_window), _dtype_code(k_window),
+                                             int(k_window.shape[2]), _ptr(win_lens), float(scale), _ptr(out),
+                                             _ptr(scores_out), _ptr(workspace),
+                                             int(workspace.numel() * workspace.element_size()), _stream_ptr(stream))
+    _check(code, "octopus_attn_decode_hybrid")
 
 
 def octopus_profile_events(before, after):

@@ -1,5 +1,6 @@
 // Dispatch by head dimension and the kernels that do not depend on the bit width.
 #include "octopus_decode.hpp"
+#include "octopus_window.hpp"
 
 namespace octopus {
 
@@ -131,20 +132,44 @@ int launch_rotate_queries(const octopus_plan_t &plan, const void *q, int q_dtype
 
 template <int D>
 static int merge_d(const DecodeShape &s, const float *part_ml, const float *part_acc, const int32_t *work_plan,
-                   float *out, hipStream_t stream) {
+                   float *out, const float *win_ml, const float *win_acc, hipStream_t stream) {
     const int64_t rows = static_cast<int64_t>(s.n_seq) * s.n_q * s.n_q_heads;
     hipLaunchKernelGGL((merge_kernel<D>), dim3(static_cast<unsigned>(rows)), dim3(kWave), 0, stream, s, part_ml,
-                       part_acc, work_plan, out);
+                       part_acc, work_plan, out, win_ml, win_acc);
     return static_cast<int>(hipGetLastError());
 }
 
 int launch_merge(const octopus_plan_t &plan, const DecodeShape &s, const float *part_ml, const float *part_acc,
-                 const int32_t *work_plan, float *out, void *stream) {
+                 const int32_t *work_plan, float *out, const float *win_ml, const float *win_acc, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     switch (plan.head_dim) {
-        case 64: return merge_d<64>(s, part_ml, part_acc, work_plan, out, st);
-        case 128: return merge_d<128>(s, part_ml, part_acc, work_plan, out, st);
-        case 256: return merge_d<256>(s, part_ml, part_acc, work_plan, out, st);
+        case 64: return merge_d<64>(s, part_ml, part_acc, work_plan, out, win_ml, win_acc, st);
+        case 128: return merge_d<128>(s, part_ml, part_acc, work_plan, out, win_ml, win_acc, st);
+        case 256: return merge_d<256>(s, part_ml, part_acc, work_plan, out, win_ml, win_acc, st);
+        default: return static_cast<int>(hipErrorInvalidValue);
+    }
+}
+
+template <int D>
+static int window_d(const DecodeShape &s, const void *q, int q_dtype, const void *k_win, int k_dtype,
+                    int64_t w_capacity, const int32_t *win_lens, const void *v, int v_dtype, const int32_t *seq_lens,
+                    float scale, float *win_ml, float *win_acc, float *scores_out, hipStream_t stream) {
+    const int64_t rows = static_cast<int64_t>(s.n_seq) * s.n_q * s.n_q_heads;
+    hipLaunchKernelGGL((window_kernel<D>), dim3(static_cast<unsigned>(rows)), dim3(kWave), 0, stream, s, q,
+                       q_dtype == OCTOPUS_DTYPE_BF16 ? 1 : 0, k_win, k_dtype == OCTOPUS_DTYPE_BF16 ? 1 : 0, w_capacity,
+                       win_lens, v, v_dtype == OCTOPUS_DTYPE_BF16 ? 1 : 0, seq_lens, scale, win_ml, win_acc, scores_out);
+    return static_cast<int>(hipGetLastError());
+}
+
+int launch_window(const octopus_plan_t &plan, const DecodeShape &s, const void *q, int q_dtype, const void *k_win,
+                  int k_dtype, int64_t w_capacity, const int32_t *win_lens, const void *v, int v_dtype,
+                  const int32_t *seq_lens, float scale, float *win_ml, float *win_acc, float *scores_out,
+                  void *stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    switch (plan.head_dim) {
+        case 64: return window_d<64>(s, q, q_dtype, k_win, k_dtype, w_capacity, win_lens, v, v_dtype, seq_lens, scale, win_ml, win_acc, scores_out, st);
+        case 128: return window_d<128>(s, q, q_dtype, k_win, k_dtype, w_capacity, win_lens, v, v_dtype, seq_lens, scale, win_ml, win_acc, scores_out, st);
+        case 256: return window_d<256>(s, q, q_dtype, k_win, k_dtype, w_capacity, win_lens, v, v_dtype, seq_lens, scale, win_ml, win_acc, scores_out, st);
         default: return static_cast<int>(hipErrorInvalidValue);
     }
 }

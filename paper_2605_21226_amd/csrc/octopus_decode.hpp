@@ -1032,7 +1032,10 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) void decode_kernel_valu(
 template <int D>
 __global__ __launch_bounds__(kWave) void merge_kernel(DecodeShape shp, const float *__restrict__ part_ml,
                                                       const float *__restrict__ part_acc,
-                                                      const int32_t *__restrict__ plan, float *__restrict__ out) {
+                                                      const int32_t *__restrict__ plan, float *__restrict__ out,
+                                                      const float *__restrict__ win_ml,
+                                                      const float *__restrict__ win_acc) {
+    // win_ml / win_acc (or NULL): one more partial per output row, that of a native-precision window
     constexpr int CPT = D / kWave;  // channels per lane
     constexpr int UN = 8;           // partial rows in flight per lane
     __shared__ float wgt[kWave];
@@ -1066,10 +1069,18 @@ __global__ __launch_bounds__(kWave) void merge_kernel(DecodeShape shp, const flo
     float m = -INFINITY;
     for (int j = lane; j < n_part; j += kWave) m = fmaxf(m, part_ml[(prow0 + static_cast<int64_t>(j) * pstride) * 2]);
     m = wave_max(m);
+    if (win_ml != nullptr) m = fmaxf(m, win_ml[orow * 2]);
     float a[CPT];
 #pragma unroll
     for (int c = 0; c < CPT; ++c) a[c] = 0.0f;
     float l = 0.0f;
+    if (win_ml != nullptr) {
+        const float mw = win_ml[orow * 2];
+        const float f = (mw == -INFINITY) ? 0.0f : exp2f((mw - m) * kLog2e);
+        if (lane == 0) l = f * win_ml[orow * 2 + 1];
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) a[c] = f * win_acc[orow * D + c * kWave + lane];
+    }
     for (int j0 = 0; j0 < n_part; j0 += kWave) {
         const int j = j0 + lane;
         float f = 0.0f;

@@ -295,7 +295,11 @@ Workspace make_workspace(const octopus_plan_t &plan, const DecodeShape &s) {
     w.plan_off = w.part_acc_off + acc_bytes;
     const size_t plan_bytes = up((static_cast<size_t>(s.n_seq) + 5) * sizeof(int32_t));
     w.q2_off = w.plan_off + plan_bytes;   // second rotation of the queries (QJL residual only)
-    w.total = w.q2_off + up(rows * static_cast<size_t>(plan.head_dim) * sizeof(float));
+    w.win_ml_off = w.q2_off + up(rows * static_cast<size_t>(plan.head_dim) * sizeof(float));
+    // partial of a native-precision window, one per output row (hybrid cache only)
+    const size_t out_rows = static_cast<size_t>(s.n_seq) * s.n_q * s.n_q_heads;
+    w.win_acc_off = w.win_ml_off + up(out_rows * 2 * sizeof(float));
+    w.total = w.win_acc_off + up(out_rows * static_cast<size_t>(plan.head_dim) * sizeof(float));
     return w;
 }
 
@@ -473,12 +477,22 @@ size_t octopus_attn_decode_workspace(const octopus_codebooks_t *cb, int32_t n_se
     return total;
 }
 
+namespace {
+// Native-precision window of a hybrid cache (all NULL / 0: none).
+struct WindowArgs {
+    const void *k_window = nullptr;
+    int32_t k_dtype = 0;
+    int64_t w_capacity = 0;
+    const int32_t *win_lens = nullptr;
+};
+}  // namespace
+
 static int attn_decode(const octopus_codebooks_t *cb, const void *q, int32_t q_dtype, int32_t n_seq,
                        int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q, const uint8_t *signs, const void *cache,
                        int64_t t_capacity, const void *v, int32_t v_dtype, const int32_t *seq_lens, int64_t max_len,
                        float scale, float *out, float *scores_out, void *workspace, size_t workspace_bytes,
                        void *stream, bool with_qjl, const uint8_t *signs2, const void *qjl, int v_bits = 0,
-                       int v_group = 0) {
+                       int v_group = 0, const WindowArgs *win = nullptr) {
     const bool with_vq = v_bits != 0;    // v: group-quantised rows (v_dtype is not looked at)
     const int ok = decode_args_ok(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len);
     if (ok != OCTOPUS_OK) return ok;
@@ -497,6 +511,11 @@ static int attn_decode(const octopus_codebooks_t *cb, const void *q, int32_t q_d
     if (!aligned(cache, 16) || !aligned(v, 16) || !aligned(q, 4) || !aligned(out, 4)) return OCTOPUS_EINVAL;
     if (with_qjl && !aligned(qjl, 4)) return OCTOPUS_EINVAL;
     if (!std::isfinite(scale)) return OCTOPUS_EINVAL;
+    if (win != nullptr) {
+        if (win->k_window == nullptr || win->win_lens == nullptr || win->w_capacity < 1) return OCTOPUS_EINVAL;
+        if (win->k_dtype != OCTOPUS_DTYPE_F32 && win->k_dtype != OCTOPUS_DTYPE_BF16) return OCTOPUS_EUNSUPPORTED;
+        if (!aligned(win->k_window, 4)) return OCTOPUS_EINVAL;
+    }
     const bool many_rows = !with_qjl && !with_vq && many_rows_shape(cb->plan, n_q_heads, n_kv_heads, n_q) &&
                            v_dtype == OCTOPUS_DTYPE_BF16 && scores_out == nullptr;
     const int rows_cap = with_qjl ? qjl_rows_cap(cb->plan) : 8;
@@ -528,7 +547,14 @@ static int attn_decode(const octopus_codebooks_t *cb, const void *q, int32_t q_d
                                 stream);
     }
     if (err == 0 && ev_after != nullptr) err = record_event(ev_after, stream);
-    if (err == 0) err = launch_merge(cb->plan, s, part_ml, part_acc, work_plan, out, stream);
+    float *win_ml = nullptr, *win_acc = nullptr;
+    if (err == 0 && win != nullptr) {
+        win_ml = reinterpret_cast<float *>(base + w.win_ml_off);
+        win_acc = reinterpret_cast<float *>(base + w.win_acc_off);
+        err = launch_window(cb->plan, s, q, q_dtype, win->k_window, win->k_dtype, win->w_capacity, win->win_lens, v,
+                            v_dtype, seq_lens, scale, win_ml, win_acc, scores_out, stream);
+    }
+    if (err == 0) err = launch_merge(cb->plan, s, part_ml, part_acc, work_plan, out, win_ml, win_acc, stream);
     return err == 0 ? OCTOPUS_OK : OCTOPUS_EHIP;
 }
 
@@ -540,6 +566,22 @@ int octopus_attn_decode(const octopus_codebooks_t *cb, const void *q, int32_t q_
     return attn_decode(cb, q, q_dtype, n_seq, n_q_heads, n_kv_heads, n_q, signs, cache, t_capacity, v, v_dtype,
                        seq_lens, max_len, scale, out, scores_out, workspace, workspace_bytes, stream, false, nullptr,
                        nullptr);
+}
+
+int octopus_attn_decode_hybrid(const octopus_codebooks_t *cb, const void *q, int32_t q_dtype, int32_t n_seq,
+                               int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q, const uint8_t *signs,
+                               const void *cache, int64_t t_capacity, const void *v, int32_t v_dtype,
+                               const int32_t *seq_lens, int64_t max_len, const void *k_window, int32_t k_dtype,
+                               int64_t w_capacity, const int32_t *win_lens, float scale, float *out, float *scores_out,
+                               void *workspace, size_t workspace_bytes, void *stream) {
+    WindowArgs win;
+    win.k_window = k_window;
+    win.k_dtype = k_dtype;
+    win.w_capacity = w_capacity;
+    win.win_lens = win_lens;
+    return attn_decode(cb, q, q_dtype, n_seq, n_q_heads, n_kv_heads, n_q, signs, cache, t_capacity, v, v_dtype,
+                       seq_lens, max_len, scale, out, scores_out, workspace, workspace_bytes, stream, false, nullptr,
+                       nullptr, 0, 0, &win);
 }
 
 int octopus_attn_decode_qjl(const octopus_codebooks_t *cb, const void *q, int32_t q_dtype, int32_t n_seq,

@@ -33,7 +33,7 @@ struct DecodeShape {
 
 // Workspace carve-up (all offsets multiples of 256 bytes).
 struct Workspace {
-    size_t q_rot_off, part_ml_off, part_acc_off, plan_off, q2_off, total;
+    size_t q_rot_off, part_ml_off, part_acc_off, plan_off, q2_off, win_ml_off, win_acc_off, total;
 };
 
 DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads,
@@ -57,8 +57,15 @@ int launch_decode_qjl(const octopus_codebooks_t &cb, const DecodeShape &s, const
 // Query rows one workgroup of the QJL decode kernel serves: the largest of 8, 4, 2, 1 whose sign-byte table
 // fits LDS beside the plan's decode tables; 0 if the plan is not built.
 int qjl_rows_cap(const octopus_plan_t &plan);
+// win_ml / win_acc: the partial of a native-precision window per output row, or NULL
 int launch_merge(const octopus_plan_t &plan, const DecodeShape &s, const float *part_ml, const float *part_acc,
-                 const int32_t *work_plan, float *out, void *stream);
+                 const int32_t *work_plan, float *out, const float *win_ml, const float *win_acc, void *stream);
+// Attention partial (m, l, acc) per output row over the native-precision window that follows the
+// compressed tokens of each sequence.
+int launch_window(const octopus_plan_t &plan, const DecodeShape &s, const void *q, int q_dtype, const void *k_win,
+                  int k_dtype, int64_t w_capacity, const int32_t *win_lens, const void *v, int v_dtype,
+                  const int32_t *seq_lens, float scale, float *win_ml, float *win_acc, float *scores_out,
+                  void *stream);
 int launch_encode(const octopus_codebooks_t &cb, const void *keys, int key_dtype, int64_t stride_seq,
                   int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
                   const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos,

@@ -5,8 +5,7 @@
 #ifndef OCTOPUS_WINDOW_HPP_
 #define OCTOPUS_WINDOW_HPP_
 
-#include "octopus_device.hpp"
-#include "octopus_internal.h"
+#include "octopus_decode.hpp"
 
 namespace octopus {
 

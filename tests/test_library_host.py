@@ -198,3 +198,18 @@ def test_value_codec_sizes_and_argument_checks(lib):
     assert dec(*args(bits=1)) == binding.EUNSUPPORTED
     assert dec(*args(group=8)) == binding.EUNSUPPORTED
     assert dec(*args(ws_bytes=ws - 1)) == binding.EWORKSPACE
+
+
+def test_hybrid_decode_argument_checks(lib):
+    cb = binding.octopus_build_codebooks(128, 3)
+    ws = binding.octopus_attn_decode_workspace(cb, 2, 32, 8, 1, 4096)
+    fake, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+    dec = lib.octopus_attn_decode_hybrid
+    args = lambda **k: [ctypes.byref(cb), fake, 1, 2, 32, 8, 1, fake, fake, 4096, fake, 1, fake, 4096,
+                        k.get("k_window", fake), k.get("k_dtype", 1), k.get("w_capacity", 32), k.get("win_lens", fake),
+                        ctypes.c_float(0.1), fake, null, ctypes.c_void_p(0x10000), k.get("ws_bytes", ws), null]
+    assert dec(*args(k_window=null)) == binding.EINVAL
+    assert dec(*args(win_lens=null)) == binding.EINVAL
+    assert dec(*args(w_capacity=0)) == binding.EINVAL
+    assert dec(*args(k_dtype=5)) == binding.EUNSUPPORTED
+    assert dec(*args(ws_bytes=ws - 1)) == binding.EWORKSPACE
