@@ -43,6 +43,9 @@ def parse():
     ap.add_argument("--vq", default="",
                     help="BITS:GROUP, e.g. 3:32 - quantise the values per group (octopus_encode_values in the encode "
                          "phase) and decode over them (octopus_attn_decode_vq); single-query workloads only")
+    ap.add_argument("--window", type=int, default=0,
+                    help="hybrid cache: keep the last WINDOW tokens of every sequence at native precision "
+                         "(octopus_attn_decode_hybrid); single-query workloads, plain variant only")
     ap.add_argument("--qjl", action="store_true",
                     help="time the variant with the 1-bit QJL residual (octopus_encode_qjl + octopus_attn_decode_qjl); "
                          "single-query workloads only")
@@ -154,6 +157,9 @@ def main():
     if args.vq and (many_rows or args.qjl):
         print("bench.py: --vq times single-query workloads without --qjl", file=sys.stderr)
         sys.exit(2)
+    if args.window and (many_rows or args.qjl or args.vq):
+        print("bench.py: --window times single-query workloads of the plain variant", file=sys.stderr)
+        sys.exit(2)
     if args.qjl and args.rounding != 1:
         print("bench.py: --qjl goes with the default rounding", file=sys.stderr)
         sys.exit(2)
@@ -170,6 +176,16 @@ def main():
         vals = padded
     sbits = torch.from_numpy(synth.sign_bits(signs)).to(dev)
     cache = torch.zeros(binding.octopus_cache_bytes(cb, wl.n_seq, wl.n_kv_heads, cap), dtype=torch.uint8, device=dev)
+    k_win = win_dev = None
+    if args.window:
+        # the last `window` tokens of every sequence stay uncompressed; the compressed part shrinks by as much
+        win = np.minimum(lens, args.window).astype(np.int32)
+        k_win = torch.zeros((wl.n_seq, wl.n_kv_heads, args.window, wl.head_dim), dtype=keys.dtype, device=dev)
+        for s_i in range(wl.n_seq):
+            a, b = int(lens[s_i] - win[s_i]), int(lens[s_i])
+            k_win[s_i, :, :b - a] = keys[s_i, a:b].permute(1, 0, 2)
+        lens = (lens - win).astype(np.int32)
+        win_dev = torch.from_numpy(win).to(dev)
     max_len = int(lens.max())
     ws = torch.empty(binding.octopus_attn_decode_workspace(cb, wl.n_seq, wl.n_q_heads, wl.n_kv_heads, wl.n_q, max_len),
                      dtype=torch.uint8, device=dev)
@@ -213,6 +229,9 @@ def main():
             binding.octopus_profile_events(ev[3], ev[4])  # around the fused kernel inside the next call
         if args.qjl:
             binding.octopus_attn_decode_qjl(cb, q, sbits, s2bits, cache, side, cap, vals, lens_dev, max_len, scale, out, ws)
+        elif args.window:
+            binding.octopus_attn_decode_hybrid(cb, q, sbits, cache, cap, vals, lens_dev, max_len, k_win, win_dev, scale,
+                                               out, ws)
         elif args.vq:
             binding.octopus_attn_decode_vq(cb, q, sbits, cache, cap, vq, v_bits, v_group, wl.n_kv_heads, lens_dev, max_len,
                                            scale, out, ws)
@@ -247,6 +266,8 @@ def main():
     side_bytes = wl.head_dim // 8 + 2 if args.qjl else 0     # sign bits + fp16 residual norm per key
     v_row_bytes = binding.octopus_vq_row_bytes(wl.head_dim, v_bits, v_group) if args.vq else wl.head_dim * elt
     dec_bytes = n_keys_dec * (rec_bytes + side_bytes + v_row_bytes) + q_out_bytes
+    n_keys_win = int(win_dev.sum().item()) * wl.n_kv_heads if args.window else 0
+    dec_bytes += n_keys_win * 2 * wl.head_dim * elt          # window tokens: native key and value rows
     dec_s = float(dec_ms.mean()) * 1e-3
     enc_s = float(enc_ms.mean()) * 1e-3
     gbs = dec_bytes / dec_s / 1e9
@@ -277,6 +298,7 @@ def main():
             "qjl_sidecar_bytes": side_bytes,
             "encoder_rounding": args.rounding,
             "value_row_bytes": v_row_bytes,
+            "window_tokens": args.window,
             "encode_phase_includes_value_quantisation": bool(args.vq),
             "keys": n_keys_dec,
         },
@@ -321,7 +343,7 @@ def main():
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.window:      # (the baseline leg times the plain variants)
         result["cpu_baseline"] = cpu_baseline(wl, keys, vals, q, signs, scale, rec_bytes, signs2=signs2, mode=args.rounding,
                                               vq=(v_bits, v_group) if args.vq else None)
     print(json.dumps(result))

@@ -251,7 +251,8 @@ int octopus_attn_decode_qjl(const octopus_codebooks_t *cb,
  * window's at rows seq_lens[s] + j.  out = softmax over both parts of scale * q . k (the true key
  * for window tokens, k^ for compressed ones) times the values: the window's partial (m, l, acc)
  * joins the split partials in the merge (flash-decoding identity, App. A).
- *   k_window    device, [n_seq][n_kv_heads][w_capacity][d] contiguous, k_dtype F32/BF16.
+ *   k_window    device, 16-byte aligned, [n_seq][n_kv_heads][w_capacity][d] contiguous,
+ *               k_dtype F32/BF16.
  *   win_lens    device [n_seq] int32, 0 <= win_lens[s] <= w_capacity; window tokens that would
  *               not fit below t_capacity in the value buffer are ignored.
  *   scores_out  window scores are written at positions seq_lens[s] + j.

@@ -155,9 +155,16 @@ static int window_d(const DecodeShape &s, const void *q, int q_dtype, const void
                     int64_t w_capacity, const int32_t *win_lens, const void *v, int v_dtype, const int32_t *seq_lens,
                     float scale, float *win_ml, float *win_acc, float *scores_out, hipStream_t stream) {
     const int64_t rows = static_cast<int64_t>(s.n_seq) * s.n_q * s.n_q_heads;
-    hipLaunchKernelGGL((window_kernel<D>), dim3(static_cast<unsigned>(rows)), dim3(kWave), 0, stream, s, q,
-                       q_dtype == OCTOPUS_DTYPE_BF16 ? 1 : 0, k_win, k_dtype == OCTOPUS_DTYPE_BF16 ? 1 : 0, w_capacity,
-                       win_lens, v, v_dtype == OCTOPUS_DTYPE_BF16 ? 1 : 0, seq_lens, scale, win_ml, win_acc, scores_out);
+    auto go = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(rows)), dim3(kWave), 0, stream, s, q,
+                           q_dtype == OCTOPUS_DTYPE_BF16 ? 1 : 0, k_win, w_capacity, win_lens, v, seq_lens, scale, win_ml,
+                           win_acc, scores_out);
+    };
+    const bool kb = k_dtype == OCTOPUS_DTYPE_BF16, vb = v_dtype == OCTOPUS_DTYPE_BF16;
+    if (kb && vb) go(window_kernel<D, true, true>);
+    else if (kb) go(window_kernel<D, true, false>);
+    else if (vb) go(window_kernel<D, false, true>);
+    else go(window_kernel<D, false, false>);
     return static_cast<int>(hipGetLastError());
 }
 

@@ -514,7 +514,7 @@ static int attn_decode(const octopus_codebooks_t *cb, const void *q, int32_t q_d
     if (win != nullptr) {
         if (win->k_window == nullptr || win->win_lens == nullptr || win->w_capacity < 1) return OCTOPUS_EINVAL;
         if (win->k_dtype != OCTOPUS_DTYPE_F32 && win->k_dtype != OCTOPUS_DTYPE_BF16) return OCTOPUS_EUNSUPPORTED;
-        if (!aligned(win->k_window, 4)) return OCTOPUS_EINVAL;
+        if (!aligned(win->k_window, 16)) return OCTOPUS_EINVAL;
     }
     const bool many_rows = !with_qjl && !with_vq && many_rows_shape(cb->plan, n_q_heads, n_kv_heads, n_q) &&
                            v_dtype == OCTOPUS_DTYPE_BF16 && scores_out == nullptr;

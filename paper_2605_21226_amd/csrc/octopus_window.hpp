@@ -13,11 +13,11 @@ namespace octopus {
 // values: rows seq_lens[s] + j of the value buffer [n_seq][n_kv_heads][t_capacity][D] (bf16 or fp32 each).
 // Chunks of 64 window tokens, one token per lane for the scores (the query sits in LDS), then every lane
 // accumulates its D / 64 channels over the chunk's tokens.
-template <int D>
+template <int D, bool k_is_bf16, bool v_is_bf16>
 __global__ __launch_bounds__(kWave) void window_kernel(DecodeShape shp, const void *__restrict__ q, int q_is_bf16,
-                                                       const void *__restrict__ k_win, int k_is_bf16,
+                                                       const void *__restrict__ k_win,
                                                        int64_t w_capacity, const int32_t *__restrict__ win_lens,
-                                                       const void *__restrict__ v, int v_is_bf16,
+                                                       const void *__restrict__ v,
                                                        const int32_t *__restrict__ seq_lens, float scale,
                                                        float *__restrict__ win_ml, float *__restrict__ win_acc,
                                                        float *__restrict__ scores_out) {
@@ -49,10 +49,33 @@ __global__ __launch_bounds__(kWave) void window_kernel(DecodeShape shp, const vo
         const int nj = static_cast<int>(min(static_cast<int64_t>(kWave), n_win - j0));
         float s = -INFINITY;
         if (lane < nj) {
-            float dot = 0.0f;
+            // this lane's key row, 16 bytes at a time (rows are 2 D or 4 D bytes: multiples of 16)
+            float dot[4] = {0.0f, 0.0f, 0.0f, 0.0f};
             const int64_t kb = (k_row0 + j0 + lane) * D;
-            for (int e = 0; e < D; ++e) dot = fmaf(qs[e], load(k_win, k_is_bf16, kb + e), dot);
-            s = dot;
+            if (k_is_bf16) {
+                const uint4 *kp = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(k_win) + kb);
+#pragma unroll
+                for (int e = 0; e < D / 8; ++e) {
+                    const uint4 x = kp[e];
+                    const uint32_t w4[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+                    for (int h = 0; h < 4; ++h) {
+                        dot[h] = fmaf(qs[8 * e + 2 * h], __uint_as_float(w4[h] << 16), dot[h]);
+                        dot[h] = fmaf(qs[8 * e + 2 * h + 1], __uint_as_float(w4[h] & 0xffff0000u), dot[h]);
+                    }
+                }
+            } else {
+                const float4 *kp = reinterpret_cast<const float4 *>(static_cast<const float *>(k_win) + kb);
+#pragma unroll 16
+                for (int e = 0; e < D / 4; ++e) {
+                    const float4 x = kp[e];
+                    dot[0] = fmaf(qs[4 * e], x.x, dot[0]);
+                    dot[1] = fmaf(qs[4 * e + 1], x.y, dot[1]);
+                    dot[2] = fmaf(qs[4 * e + 2], x.z, dot[2]);
+                    dot[3] = fmaf(qs[4 * e + 3], x.w, dot[3]);
+                }
+            }
+            s = (dot[0] + dot[1]) + (dot[2] + dot[3]);
             if (scores_out != nullptr) scores_out[orow * shp.t_capacity + len + j0 + lane] = s;
         }
         const float m_new = fmaxf(m_run, wave_max(s));
@@ -62,11 +85,21 @@ __global__ __launch_bounds__(kWave) void window_kernel(DecodeShape shp, const vo
         l_run = fmaf(l_run, alpha, wave_sum(p));
 #pragma unroll
         for (int c = 0; c < CPT; ++c) acc[c] *= alpha;
-        for (int j = 0; j < nj; ++j) {
-            const float pj = __shfl(p, j, kWave);
+        // eight value rows in flight; rows past the chunk's end are re-reads of its last row with weight zero
+        for (int jb = 0; jb < nj; jb += 8) {
+            float x[8][CPT];
 #pragma unroll
-            for (int c = 0; c < CPT; ++c)
-                acc[c] = fmaf(pj, load(v, v_is_bf16, (v_row0 + j0 + j) * D + c * kWave + lane), acc[c]);
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int c = 0; c < CPT; ++c)
+                    x[u][c] = load(v, v_is_bf16, (v_row0 + j0 + min(jb + u, nj - 1)) * D + c * kWave + lane);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float pj = __shfl(p, min(jb + u, kWave - 1), kWave);   // p is zero in lanes >= nj
+                const float wj = (jb + u < nj) ? pj : 0.0f;
+#pragma unroll
+                for (int c = 0; c < CPT; ++c) acc[c] = fmaf(wj, x[u][c], acc[c]);
+            }
         }
     }
     if (lane == 0) {
