@@ -228,21 +228,43 @@ struct WaveWork {
 __device__ __forceinline__ void item_work(const DecodeShape &shp, const int32_t *plan, const int32_t *seq_lens, int it,
                                           int wave, int tiles_per_step, WaveWork *ww) {
     const int32_t *before = plan + kPlanHeader;
-    int lo = 0, hi = shp.n_seq;          // largest s with before[s] <= it (before[n_seq] > it)
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (before[mid] <= it) lo = mid; else hi = mid;
+    int lo, b_lo, b_next, len_lo;        // lo: largest s with before[s] <= it (before[n_seq] > it)
+    if (shp.n_seq < kWave) {
+        // one round of loads instead of a chain of dependent ones: lane l holds before[l] and the length of
+        // sequence l; the lanes whose entry is <= it are counted
+        const int l = static_cast<int>(threadIdx.x) & (kWave - 1);
+        const int mine = l <= shp.n_seq ? before[l] : 0x7fffffff;
+        const int my_len = l < shp.n_seq ? seq_lens[l] : 0;
+        const uint64_t le = __ballot(l < shp.n_seq && mine <= it);
+        lo = max(__popcll(le) - 1, 0);
+        b_lo = __shfl(mine, lo, kWave);
+        b_next = __shfl(mine, lo + 1, kWave);
+        len_lo = __shfl(my_len, lo, kWave);
+        lo = __builtin_amdgcn_readfirstlane(lo);
+        b_lo = __builtin_amdgcn_readfirstlane(b_lo);
+        b_next = __builtin_amdgcn_readfirstlane(b_next);
+        len_lo = __builtin_amdgcn_readfirstlane(len_lo);
+    } else {
+        int hi = shp.n_seq;
+        lo = 0;
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (before[mid] <= it) lo = mid; else hi = mid;
+        }
+        b_lo = before[lo];
+        b_next = before[lo + 1];
+        len_lo = seq_lens[lo];
     }
     const int G = shp.n_kv_heads * shp.n_row_groups;
-    const int c_s = (before[lo + 1] - before[lo]) / G;   // > 0, or `it` would not fall here
-    const int local = it - before[lo];
+    const int c_s = (b_next - b_lo) / G;   // > 0, or `it` would not fall here
+    const int local = it - b_lo;
     const int gis = local / c_s, chunk = local % c_s;
     ww->seq = lo;
     ww->group_id = static_cast<int64_t>(lo) * G + gis;
     ww->grp = gis % shp.n_row_groups;
     ww->kvh = gis / shp.n_row_groups;
     ww->pair = static_cast<int64_t>(lo) * shp.n_kv_heads + ww->kvh;
-    ww->len = min(max(seq_lens[lo], 0), shp.max_len);
+    ww->len = min(max(len_lo, 0), shp.max_len);
     ww->n_tiles = (ww->len + kWave - 1) / kWave;
     const int n_steps = (ww->n_tiles + tiles_per_step - 1) / tiles_per_step;
     const int base = n_steps / c_s, rem = n_steps % c_s;
@@ -583,7 +605,9 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
     for (int e = tid; e < kDecodeWaves * 16 * PROW; e += kDecodeWaves * kWave) (&sm.pbuf[0][0][0])[e] = 0;
-    build_tables<P>(sm.tb, books, tid, kDecodeWaves * kWave);
+    // The tables are built inside the item loop, after the first item's first loads have been issued:
+    // those do not depend on the tables, and their latency covers the build.
+    bool tables_built = false;
 
     __shared__ int item_slot;
     // per item (set in the item loop below; the helpers capture them by reference)
@@ -855,6 +879,10 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
                 for (int ks = 0; ks < KS; ++ks) load_values(v_first, ks, vr[ks]);
             }
         }
+        if (!tables_built) {   // workgroup-uniform
+            build_tables<P>(sm.tb, books, tid, kDecodeWaves * kWave);
+            tables_built = true;
+        }
         for (int step = ww.step_begin; step < ww.step_end; step += 2 * ww.step_stride) {
             process_step(step, w_a, w_b, sc_a, sc_b);
             if (step + ww.step_stride < ww.step_end) process_step(step + ww.step_stride, w_b, w_a, sc_b, sc_a);
@@ -943,6 +971,27 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) void decode_kernel_valu(
             const uint4 x = src[g * kWave];
             w[4 * g] = x.x; w[4 * g + 1] = x.y; w[4 * g + 2] = x.z; w[4 * g + 3] = x.w;
         }
+        // VQ: the tile's quantised value words are requested here, so that they arrive during the scores.
+        // This lane's 8 channels of a row are 8 * v_bits bits at byte rl * v_bits, fetched as the two aligned
+        // words around them (the second may reach into the row's own metadata); rows past the last token
+        // are re-reads of the last one (their probabilities are zero).
+        constexpr int NIT = VQ ? kWave / KPL : 1;   // key rows per lane and tile
+        uint32_t q_lo[NIT], q_hi[NIT];
+        float2 q_meta[NIT];
+        if constexpr (VQ) {
+            const int code_bytes = v_bits * (D / 8);
+            const int row_bytes = code_bytes + (D / v_group) * 8;
+            const int boff = rl * v_bits;
+            const unsigned char *base = reinterpret_cast<const unsigned char *>(v) + (v_row0 + t0) * row_bytes;
+#pragma unroll
+            for (int i = 0; i < NIT; ++i) {
+                const unsigned char *row = base + static_cast<int64_t>(min(i * KPL + ko, n_valid - 1)) * row_bytes;
+                const uint32_t *wp = reinterpret_cast<const uint32_t *>(row) + (boff >> 2);
+                q_lo[i] = wp[0];
+                q_hi[i] = wp[1];
+                q_meta[i] = *reinterpret_cast<const float2 *>(row + code_bytes + ((rl * 8) / v_group) * 8);
+            }
+        }
         float s1[1][RG];
         float (&s)[RG] = s1[0];
         int q_off = 0;
@@ -967,38 +1016,39 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) void decode_kernel_valu(
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        for (int kb = 0; kb < n_valid; kb += KPL) {
-            const int key = kb + ko;
-            if (key < n_valid) {
+        if constexpr (VQ) {
+            const uint32_t mask = (1u << v_bits) - 1u;
+            const uint32_t sh = static_cast<uint32_t>((rl * v_bits) & 3);
+#pragma unroll
+            for (int i = 0; i < NIT; ++i) {
+                const int key = i * KPL + ko;           // probabilities of lanes past n_valid are zero
                 float pv[RG];
 #pragma unroll
                 for (int r = 0; r < RG; ++r) pv[r] = sm.pbuf[wave][key][r];
-                const int64_t vrow = v_row0 + t0 + key;
-                float vals[8];
-                if constexpr (VQ) {
-                    // this lane's 8 channels: 8 * v_bits bits at byte rl * v_bits of the row, fetched as the two
-                    // aligned words around them (the second may reach into the row's own metadata)
-                    const int code_bytes = v_bits * (D / 8);
-                    const unsigned char *row = reinterpret_cast<const unsigned char *>(v) +
-                                               vrow * (code_bytes + (D / v_group) * 8);
-                    const int boff = rl * v_bits;
-                    const uint32_t *wp = reinterpret_cast<const uint32_t *>(row) + (boff >> 2);
-                    const uint32_t bits = __builtin_amdgcn_alignbyte(wp[1], wp[0], static_cast<uint32_t>(boff & 3));
-                    const float2 meta = *reinterpret_cast<const float2 *>(row + code_bytes + ((rl * 8) / v_group) * 8);
-                    const uint32_t mask = (1u << v_bits) - 1u;
+                const uint32_t bits = __builtin_amdgcn_alignbyte(q_hi[i], q_lo[i], sh);
 #pragma unroll
-                    for (int c = 0; c < 8; ++c)
-                        vals[c] = fmaf(meta.x, static_cast<float>((bits >> (c * v_bits)) & mask), meta.y);
-                } else {
+                for (int c = 0; c < 8; ++c) {
+                    const float val = fmaf(q_meta[i].x, static_cast<float>((bits >> (c * v_bits)) & mask), q_meta[i].y);
+#pragma unroll
+                    for (int r = 0; r < RG; ++r) acc[r][c] = fmaf(pv[r], val, acc[r][c]);
+                }
+            }
+        } else {
+            for (int kb = 0; kb < n_valid; kb += KPL) {
+                const int key = kb + ko;
+                if (key < n_valid) {
+                    float pv[RG];
+#pragma unroll
+                    for (int r = 0; r < RG; ++r) pv[r] = sm.pbuf[wave][key][r];
+                    const int64_t vrow = v_row0 + t0 + key;
                     const float4 a = v[vrow * (D / 4) + 2 * rl];
                     const float4 b = v[vrow * (D / 4) + 2 * rl + 1];
-                    vals[0] = a.x; vals[1] = a.y; vals[2] = a.z; vals[3] = a.w;
-                    vals[4] = b.x; vals[5] = b.y; vals[6] = b.z; vals[7] = b.w;
+                    const float vals[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+                    for (int r = 0; r < RG; ++r)
+#pragma unroll
+                        for (int c = 0; c < 8; ++c) acc[r][c] = fmaf(pv[r], vals[c], acc[r][c]);
                 }
-#pragma unroll
-                for (int r = 0; r < RG; ++r)
-#pragma unroll
-                    for (int c = 0; c < 8; ++c) acc[r][c] = fmaf(pv[r], vals[c], acc[r][c]);
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");

@@ -16,7 +16,7 @@ __global__ __launch_bounds__(256) void encode_values_kernel(const void *__restri
                                                              int32_t n_kv_heads, int32_t n_new, int32_t d, int32_t bits,
                                                              int32_t group, unsigned char *__restrict__ vq,
                                                              int64_t t_capacity,
-                                                             const int32_t *__restrict__ start_pos) {
+                                                             const int32_t *__restrict__ start_pos, int vec16) {
     const int n_groups = d / group;
     const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
     const int64_t total = static_cast<int64_t>(n_seq) * n_new * n_kv_heads * n_groups;
@@ -30,13 +30,42 @@ __global__ __launch_bounds__(256) void encode_values_kernel(const void *__restri
 
     const int64_t src = seq * stride_seq + tok * stride_tok + kvh * stride_head + static_cast<int64_t>(grp) * group;
     float x[32];
+    if (vec16) {   // the group's elements start on a 16-byte boundary: 16-byte loads
+        if (BF16) {
+            const uint4 *p4 = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(v) + src);
 #pragma unroll
-    for (int j = 0; j < 32; ++j) {
-        if (j < group) {
-            x[j] = BF16 ? __uint_as_float(static_cast<uint32_t>(static_cast<const uint16_t *>(v)[src + j]) << 16)
-                        : static_cast<const float *>(v)[src + j];
+            for (int j = 0; j < 4; ++j) {
+                if (8 * j < group) {
+                    const uint4 w = p4[j];
+                    const uint32_t w4[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+                    for (int h = 0; h < 4; ++h) {
+                        x[8 * j + 2 * h] = __uint_as_float(w4[h] << 16);
+                        x[8 * j + 2 * h + 1] = __uint_as_float(w4[h] & 0xffff0000u);
+                    }
+                }
+            }
         } else {
-            x[j] = x[0];
+            const float4 *p4 = reinterpret_cast<const float4 *>(static_cast<const float *>(v) + src);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if (4 * j < group) {
+                    const float4 w = p4[j];
+                    x[4 * j] = w.x; x[4 * j + 1] = w.y; x[4 * j + 2] = w.z; x[4 * j + 3] = w.w;
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 16; j < 32; ++j) x[j] = (j < group) ? x[j] : x[0];
+    } else {
+#pragma unroll
+        for (int j = 0; j < 32; ++j) {
+            if (j < group) {
+                x[j] = BF16 ? __uint_as_float(static_cast<uint32_t>(static_cast<const uint16_t *>(v)[src + j]) << 16)
+                            : static_cast<const float *>(v)[src + j];
+            } else {
+                x[j] = x[0];
+            }
         }
     }
     float lo = x[0], hi = x[0];
@@ -82,14 +111,18 @@ int launch_encode_values(const void *v, int v_dtype, int64_t stride_seq, int64_t
     const int64_t total = static_cast<int64_t>(n_seq) * n_new * n_kv_heads * (head_dim / group);
     const dim3 grid(static_cast<unsigned>((total + 255) / 256));
     hipStream_t st = static_cast<hipStream_t>(stream);
+    // 16-byte loads when every group starts on a 16-byte boundary
+    const int64_t per16 = v_dtype == OCTOPUS_DTYPE_BF16 ? 8 : 4;
+    const int vec16 = (reinterpret_cast<uintptr_t>(v) % 16 == 0 && stride_seq % per16 == 0 && stride_tok % per16 == 0 &&
+                       stride_head % per16 == 0) ? 1 : 0;
     if (v_dtype == OCTOPUS_DTYPE_BF16)
         hipLaunchKernelGGL(encode_values_kernel<true>, grid, dim3(256), 0, st, v, stride_seq, stride_tok, stride_head,
                            n_seq, n_kv_heads, n_new, head_dim, bits, group, static_cast<unsigned char *>(vq),
-                           t_capacity, start_pos);
+                           t_capacity, start_pos, vec16);
     else
         hipLaunchKernelGGL(encode_values_kernel<false>, grid, dim3(256), 0, st, v, stride_seq, stride_tok, stride_head,
                            n_seq, n_kv_heads, n_new, head_dim, bits, group, static_cast<unsigned char *>(vq),
-                           t_capacity, start_pos);
+                           t_capacity, start_pos, vec16);
     return static_cast<int>(hipGetLastError());
 }
 
