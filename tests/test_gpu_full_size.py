@@ -1,7 +1,9 @@
 """GPU parity at the full sizes of the named workloads, in the launch configuration bench.py times:
 the whole batch is generated in device memory, encoded and attended by the HIP path in one call each,
-and sampled (sequence, KV head) pairs are read back and checked against the CPU oracle — every key
-of a sampled pair for the packed codes, every query head of the pair's group for the output."""
+and sampled (sequence, KV head) pairs are checked against the CPU oracle run on the same inputs — every
+key of a sampled pair for the packed codes (bit-exact, 1e-6 ties counted), every query head of the pair's
+group for the output (the oracle attends over its own codes).  The variants (QJL residual, quantised
+values, native-precision window) run on the Llama-shaped workload in the same way."""
 import numpy as np
 import pytest
 
@@ -33,12 +35,13 @@ def check_pair_codes(plan, k, signs_h, got, tag):
     assert np.all(np.abs(g_got - g_ref) <= 1e-6 * np.maximum(g_ref, 1e-30)), tag
     n = k.shape[0] * plan.n_tri
     if np.array_equal(got[:, 4:], ref[:, 4:]):
-        return np.array([n, 0, 0], dtype=np.int64)
-    return np.array(oracle.classify(plan, k, signs_h, got, tol=1e-6), dtype=np.int64)
+        return np.array([n, 0, 0], dtype=np.int64), ref
+    return np.array(oracle.classify(plan, k, signs_h, got, tol=1e-6), dtype=np.int64), ref
 
 
-def run_full_size(name, bits, pairs, q_rows, seed=0, chunked_encode=False):
-    """pairs: (sequence, KV head) pairs to check; q_rows: query positions (of n_q) to check"""
+def run_full_size(name, bits, pairs, q_rows, seed=0, chunked_encode=False, variant=None):
+    """pairs: (sequence, KV head) pairs to check; q_rows: query positions (of n_q) to check;
+    variant: None, "qjl", ("vq", bits, group) or ("window", tokens)"""
     base = synth.WORKLOADS[name]
     wl = synth.Workload(**{**base.__dict__, "bits": bits})
     cb = binding.octopus_build_codebooks(wl.head_dim, bits)
@@ -53,8 +56,27 @@ def run_full_size(name, bits, pairs, q_rows, seed=0, chunked_encode=False):
         vals = v2
     sbits = torch.from_numpy(synth.sign_bits(signs)).to(DEV)
     cache = torch.zeros(binding.octopus_cache_bytes(cb, wl.n_seq, n_kv, cap), dtype=torch.uint8, device=DEV)
-    print(f"[full] {name} b={bits}: encode", flush=True)
-    if chunked_encode:            # bulk prefill, then the workload's chunk appended at its position
+    kind = variant if isinstance(variant, str) or variant is None else variant[0]
+    signs2 = s2bits = side = vq = k_win = win_dev = None
+    if kind == "qjl":
+        signs2 = synth.sign_vectors(seed + 1, n_kv, d)
+        s2bits = torch.from_numpy(synth.sign_bits(signs2)).to(DEV)
+        side = torch.zeros(binding.octopus_qjl_bytes(cb, wl.n_seq, n_kv, cap), dtype=torch.uint8, device=DEV)
+    if kind == "vq":
+        _, v_bits, v_group = variant
+        vq = torch.zeros(binding.octopus_vq_bytes(d, v_bits, v_group, wl.n_seq, n_kv, cap), dtype=torch.uint8, device=DEV)
+        binding.octopus_encode_values(vals.permute(0, 2, 1, 3), v_bits, v_group, vq, cap)
+    if kind == "window":
+        W = variant[1]
+        assert lens.min() > W
+        k_win = torch.stack([keys[s_i, int(lens[s_i]) - W:int(lens[s_i])].permute(1, 0, 2) for s_i in range(wl.n_seq)])
+        k_win = k_win.contiguous()
+        win_dev = torch.full((wl.n_seq,), W, dtype=torch.int32, device=DEV)
+        lens = (lens - W).astype(np.int32)                 # the compressed part
+    print(f"[full] {name} b={bits} {variant or ''}: encode", flush=True)
+    if kind == "qjl":
+        binding.octopus_encode_qjl(cb, keys, sbits, s2bits, cache, side, cap)
+    elif chunked_encode:            # bulk prefill, then the workload's chunk appended at its position
         n0 = wl.n_tokens - wl.n_new
         binding.octopus_encode(cb, keys[:, :n0], sbits, cache, cap)
         sp = torch.full((wl.n_seq,), n0, dtype=torch.int32, device=DEV)
@@ -67,25 +89,70 @@ def run_full_size(name, bits, pairs, q_rows, seed=0, chunked_encode=False):
                      dtype=torch.uint8, device=DEV)
     out = torch.full((wl.n_seq, wl.n_q, wl.n_q_heads, d), float("nan"), dtype=torch.float32, device=DEV)
     scale = 1.0 / float(np.sqrt(d))
-    print(f"[full] {name} b={bits}: decode attention", flush=True)
-    binding.octopus_attn_decode(cb, q, sbits, cache, cap, vals, torch.from_numpy(lens).to(DEV), max_len, scale, out, ws)
-    torch.cuda.synchronize()
-    assert bool(torch.isfinite(out).all())
-
+    # Stage 1, before the decode call: the GPU's codes of the sampled pairs against the oracle's, then the
+    # oracle's own records (and side-car) are written over those pairs' regions in the device layouts, so
+    # that the attention check below compares the decoder with the oracle on the oracle's codes; the other
+    # pairs keep what the GPU encoded.
     g = wl.n_q_heads // n_kv
     total = np.zeros(3, dtype=np.int64)
-    worst = 0.0
+    ref_recs, ref_side = {}, {}
+    region_bytes = cap * cb.plan.granules * 16
     for (s, h) in pairs:
-        print(f"[full] {name} b={bits}: oracle on sequence {s}, KV head {h}", flush=True)
-        L = int(lens[s])
+        print(f"[full] {name} b={bits}: oracle encode of sequence {s}, KV head {h}", flush=True)
         k = keys[s, :, h].float().cpu().numpy().astype(np.float64)             # every cached token of the pair
         rec, pad = region_records(cb, cache, n_kv, cap, s, h, wl.n_tokens)
         assert not pad.any()
-        total += check_pair_codes(plan, k, signs[h], rec, f"{name} b={bits} ({s},{h})")
-        v = vals[s, h, :L].float().cpu().numpy().astype(np.float64)
+        counts, ref_rec = check_pair_codes(plan, k, signs[h], rec, f"{name} b={bits} ({s},{h})")
+        total += counts
+        ref_recs[(s, h)] = ref_rec
+        img = layout.records_to_cache(ref_rec[None, None], cb.plan.granules, cap)
+        cache[(s * n_kv + h) * region_bytes:(s * n_kv + h + 1) * region_bytes] = torch.from_numpy(img.reshape(-1)).to(DEV)
+        if kind == "qjl":
+            sigma, gamma_r = oracle.qjl_encode(plan, k, signs[h], signs2[h], ref_rec)
+            ref_side[(s, h)] = (sigma, gamma_r)
+            sb = np.zeros((1, 1, wl.n_tokens, d // 8), dtype=np.uint8)
+            sb[0, 0] = np.packbits((sigma < 0).astype(np.uint8), axis=-1, bitorder="little")
+            img = layout.qjl_from_canonical(sb, gamma_r.astype(np.float16)[None, None], cap)
+            side[(s * n_kv + h) * img.size:(s * n_kv + h + 1) * img.size] = torch.from_numpy(img).to(DEV)
+    print(f"[full] {name} b={bits} {variant or ''}: decode attention", flush=True)
+    lens_dev = torch.from_numpy(lens).to(DEV)
+    if kind == "qjl":
+        binding.octopus_attn_decode_qjl(cb, q, sbits, s2bits, cache, side, cap, vals, lens_dev, max_len, scale, out, ws)
+    elif kind == "vq":
+        binding.octopus_attn_decode_vq(cb, q, sbits, cache, cap, vq, v_bits, v_group, n_kv, lens_dev, max_len, scale, out, ws)
+    elif kind == "window":
+        binding.octopus_attn_decode_hybrid(cb, q, sbits, cache, cap, vals, lens_dev, max_len, k_win, win_dev, scale, out, ws)
+    else:
+        binding.octopus_attn_decode(cb, q, sbits, cache, cap, vals, lens_dev, max_len, scale, out, ws)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all())
+
+    worst = 0.0
+    for (s, h) in pairs:
+        print(f"[full] {name} b={bits}: oracle attention on sequence {s}, KV head {h}", flush=True)
+        L = int(lens[s])
+        k = keys[s, :, h].float().cpu().numpy().astype(np.float64)
+        ref_rec = ref_recs[(s, h)]
         qq = q[s][q_rows][:, h * g:(h + 1) * g].float().cpu().numpy().astype(np.float64).reshape(-1, d)
-        _, ref, gap = oracle.attention(plan, rec[:L], signs[h], qq, v, scale)    # the codes the GPU wrote
-        assert gap < 1e-9
+        if kind == "qjl":
+            sigma, gamma_r = ref_side[(s, h)]
+            v = vals[s, h, :L].float().cpu().numpy().astype(np.float64)
+            _, ref = oracle.attention_qjl(plan, ref_rec[:L], signs[h], signs2[h], sigma[:L], gamma_r[:L], qq, v, scale)
+        elif kind == "vq":
+            v32 = vals[s, h, :wl.n_tokens].float().cpu().numpy()
+            rows_ref = oracle.vq_encode(v32, v_bits, v_group)
+            rb = rows_ref.shape[1]
+            got_rows = vq[(s * n_kv + h) * cap * rb:((s * n_kv + h) * cap + wl.n_tokens) * rb].cpu().numpy().reshape(-1, rb)
+            assert np.array_equal(got_rows, rows_ref), f"value rows of ({s},{h}) differ"
+            _, ref, _ = oracle.attention(plan, ref_rec[:L], signs[h], qq, oracle.vq_decode(rows_ref[:L], d, v_bits, v_group),
+                                         scale)
+        elif kind == "window":
+            v = vals[s, h, :L + W].float().cpu().numpy().astype(np.float64)
+            _, ref = oracle.attention_hybrid(plan, ref_rec[:L], signs[h], k[L:L + W], qq, v, scale)
+        else:
+            v = vals[s, h, :L].float().cpu().numpy().astype(np.float64)
+            _, ref, gap = oracle.attention(plan, ref_rec[:L], signs[h], qq, v, scale)
+            assert gap < 1e-9
         got = out[s][q_rows][:, h * g:(h + 1) * g].cpu().numpy().reshape(-1, d)
         for r in range(ref.shape[0]):
             worst = max(worst, check_out(got[r], ref[r]))
@@ -114,3 +181,15 @@ def test_full_ragged_d256(bits):
     lens = synth.context_lengths(0, synth.WORKLOADS["ragged_d256"])
     s_short, s_long = int(np.argmin(lens)), int(np.argmax(lens))
     run_full_size("ragged_d256", float(bits), [(s_short, 0), (s_long, 7)], [0])
+
+
+def test_full_llama3_8b_decode_qjl():
+    run_full_size("llama3_8b_decode", 3.0, [(2, 1), (12, 6)], [0], variant="qjl")
+
+
+def test_full_llama3_8b_decode_quantised_values():
+    run_full_size("llama3_8b_decode", 3.0, [(4, 2), (13, 0)], [0], variant=("vq", 3, 32))
+
+
+def test_full_llama3_8b_decode_window():
+    run_full_size("llama3_8b_decode", 3.0, [(1, 4), (14, 3)], [0], variant=("window", 32))
