@@ -252,3 +252,14 @@ def test_encode_then_decode_end_to_end():
     for s in range(n_seq):
         for h in range(n_qh):
             check_out(out[s, 0, h], ref_out[s, 0, h])
+
+
+def test_decode_more_sequences_than_lanes():
+    """70 short ragged sequences (some empty): the work plan is looked up by binary search beyond 63
+    sequences, by one round of loads below."""
+    rng = np.random.default_rng(12)
+    lens = [int(x) for x in rng.integers(0, 400, size=70)]
+    lens[3] = 0
+    lens[69] = 399
+    run_decode_case(64, 3, 70, 2, 1, 1, lens, "bf16", seed=501, want_scores=False)
+    run_decode_case(64, 3, 63, 2, 1, 1, lens[:63], "bf16", seed=502, want_scores=False)
