@@ -6,6 +6,11 @@
  *   octopus_build_codebooks   Sec. 3.3 (bit split) + Sec. 3.4 (codebooks)
  *   octopus_encode            Alg. 1 (encoder with joint rounding), Sec. 3.1-3.5
  *   octopus_attn_decode       Alg. 2 (split-K flash decode), Eq. (score-exact)
+ * Further entry points, each documented where it is declared below:
+ *   octopus_encode_rounding   the encoder's rounding variants (App. E)
+ *   octopus_encode_qjl, octopus_attn_decode_qjl    the 1-bit QJL residual (Sec. 3.6)
+ *   octopus_encode_values, octopus_attn_decode_vq  group-quantised values (Sec. 4, Alg. 2)
+ *   octopus_attn_decode_hybrid                     native-precision window (Sec. 4)
  *
  * Conventions
  *   - Plain C.  Every function returns 0 (OCTOPUS_OK) or a negative error

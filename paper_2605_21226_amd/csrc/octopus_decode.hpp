@@ -11,10 +11,10 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kDecodeWaves = 4;  // wavefronts per workgroup of the main kernels
 
 // ---- D1-D7: split-K main kernels --------------------------------------------------------------
-// Work unit = one wavefront = one (sequence, KV head, row group, split): the wave walks the 64-token
-// tiles of its split with one key per lane, keeps its own running (m, l, acc) and writes one partial
-// per query row; nothing is shared between the waves of a workgroup but the LDS tables.  The tiles of
-// a sequence are divided over the splits as evenly as whole tiles allow.
+// Work unit = one wavefront over a range of steps of one (sequence, KV head, row group): the wave walks
+// its 64-token tiles with one key per lane (two tiles per step up to d = 128), keeps its own running
+// (m, l, acc) and writes one partial per query row; nothing is shared between the waves of a workgroup
+// but the LDS tables.  How the ranges are cut (items) is described with the work plan below.
 //
 // Per tile: the lane loads its record (16 bytes at a time, coalesced thanks to the tile-interleaved
 // layout, one tile ahead of use), unpacks the code fields with compile-time shifts, looks up the
