@@ -8,6 +8,11 @@
 namespace octopus {
 
 constexpr float kLog2e = 1.4426950408889634f;
+
+// 2^x as the bare v_exp_f32 (about one ulp; results below 2^-126 become zero, which is all a softmax
+// weight that small is worth).  exp2f() wraps the same instruction in a range fix-up for denormal
+// results that costs five more instructions per value.
+__device__ __forceinline__ float exp2_raw(float x) { return __builtin_amdgcn_exp2f(x); }
 constexpr int kDecodeWaves = 4;  // wavefronts per workgroup of the main kernels
 
 // ---- D1-D7: split-K main kernels --------------------------------------------------------------
@@ -788,12 +793,12 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
 #pragma unroll
             for (int k = 1; k < KPL; ++k) mx = fmaxf(mx, s[k][r]);
             const float m_new = fmaxf(m_run[r], wave_max(mx));
-            alpha[r] = exp2f((m_run[r] - m_new) * kLog2e);
+            alpha[r] = exp2_raw((m_run[r] - m_new) * kLog2e);
             m_run[r] = m_new;
             float psum = 0.0f;
 #pragma unroll
             for (int k = 0; k < KPL; ++k) {
-                const float p = exp2f((s[k][r] - m_new) * kLog2e);
+                const float p = exp2_raw((s[k][r] - m_new) * kLog2e);
                 psum += p;
                 const uint32_t pb = __float_as_uint(p);
                 const float lo = p - __uint_as_float(pb & 0xffff0000u);
@@ -1006,9 +1011,9 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) void decode_kernel_valu(
 #pragma unroll
         for (int r = 0; r < RG; ++r) {
             const float m_new = fmaxf(m_run[r], wave_max(s[r]));
-            alpha[r] = exp2f((m_run[r] - m_new) * kLog2e);
+            alpha[r] = exp2_raw((m_run[r] - m_new) * kLog2e);
             m_run[r] = m_new;
-            const float p = exp2f((s[r] - m_new) * kLog2e);
+            const float p = exp2_raw((s[r] - m_new) * kLog2e);
             l_lane[r] = fmaf(l_lane[r], alpha[r], p);
             sm.pbuf[wave][lane][r] = p;
 #pragma unroll
@@ -1126,7 +1131,7 @@ __global__ __launch_bounds__(kWave) void merge_kernel(DecodeShape shp, const flo
     float l = 0.0f;
     if (win_ml != nullptr) {
         const float mw = win_ml[orow * 2];
-        const float f = (mw == -INFINITY) ? 0.0f : exp2f((mw - m) * kLog2e);
+        const float f = (mw == -INFINITY) ? 0.0f : exp2_raw((mw - m) * kLog2e);
         if (lane == 0) l = f * win_ml[orow * 2 + 1];
 #pragma unroll
         for (int c = 0; c < CPT; ++c) a[c] = f * win_acc[orow * D + c * kWave + lane];
@@ -1136,7 +1141,7 @@ __global__ __launch_bounds__(kWave) void merge_kernel(DecodeShape shp, const flo
         float f = 0.0f;
         if (j < n_part) {
             const float2 ml = *reinterpret_cast<const float2 *>(part_ml + (prow0 + static_cast<int64_t>(j) * pstride) * 2);
-            f = (ml.x == -INFINITY) ? 0.0f : exp2f((ml.x - m) * kLog2e);
+            f = (ml.x == -INFINITY) ? 0.0f : exp2_raw((ml.x - m) * kLog2e);
             l += f * ml.y;
         }
         __syncthreads();

@@ -231,7 +231,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(P::D <= 64 
             for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[mb][e]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
         const float m_new = fmaxf(m_run, mx);
-        const float alpha = exp2f((m_run - m_new) * kLog2e);
+        const float alpha = exp2_raw((m_run - m_new) * kLog2e);
         m_run = m_new;
         float psum = 0.0f;
         BF8 ph[4], pl[4];   // per group of 16 keys: the 8 k-slots of this lane, hi and lo
@@ -239,7 +239,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(P::D <= 64 
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
             for (int e = 0; e < 16; e += 2) {
-                const float p0 = exp2f((sacc[mb][e] - m_new) * kLog2e), p1 = exp2f((sacc[mb][e + 1] - m_new) * kLog2e);
+                const float p0 = exp2_raw((sacc[mb][e] - m_new) * kLog2e), p1 = exp2_raw((sacc[mb][e + 1] - m_new) * kLog2e);
                 psum += p0 + p1;
                 const uint32_t b0 = __float_as_uint(p0), b1 = __float_as_uint(p1);
                 const float l0 = p0 - __uint_as_float(b0 & 0xffff0000u), l1 = p1 - __uint_as_float(b1 & 0xffff0000u);

@@ -79,8 +79,8 @@ __global__ __launch_bounds__(kWave) void window_kernel(DecodeShape shp, const vo
             if (scores_out != nullptr) scores_out[orow * shp.t_capacity + len + j0 + lane] = s;
         }
         const float m_new = fmaxf(m_run, wave_max(s));
-        const float alpha = exp2f((m_run - m_new) * kLog2e);
-        const float p = (lane < nj) ? exp2f((s - m_new) * kLog2e) : 0.0f;
+        const float alpha = exp2_raw((m_run - m_new) * kLog2e);
+        const float p = (lane < nj) ? exp2_raw((s - m_new) * kLog2e) : 0.0f;
         m_run = m_new;
         l_run = fmaf(l_run, alpha, wave_sum(p));
 #pragma unroll
