@@ -12,10 +12,13 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build" + os.environ.get("OCTOPUS_VARIANT", ""))
 LIB = os.environ.get("OCTOPUS_LIB_OUT", os.path.join(HERE, "liboctopus.so"))
 
-SOURCES = ["octopus_host.cpp", "octopus_common.hip", "octopus_d64.hip", "octopus_d128.hip", "octopus_d256.hip",
-           "octopus_qjl_d64.hip", "octopus_qjl_d128.hip", "octopus_qjl_d256.hip",
-           "octopus_round_d64.hip", "octopus_round_d128.hip", "octopus_round_d256.hip",
-           "octopus_vq_d64.hip", "octopus_vq_d128.hip", "octopus_vq_d256.hip", "octopus_values.hip"]
+# one translation unit per head dimension and kernel family; a pool of workers compiles them in this order,
+# the slowest (d = 256, then the matrix-core decode kernels) first
+SOURCES = []
+for _d in ("256", "128", "64"):
+    SOURCES += [_family + _d + ".hip" for _family in ("octopus_d", "octopus_vq_d", "octopus_valu_d", "octopus_qjl_d",
+                                                      "octopus_enc_d", "octopus_round_d")]
+SOURCES += ["octopus_common.hip", "octopus_values.hip", "octopus_host.cpp"]
 # -packed-fp32-ops is switched off on purpose: hipcc must not form packed fp32 instructions here.
 FLAGS = (["-D" + d for d in os.environ.get("OCTOPUS_DEFS", "").split(",") if d]) + ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]

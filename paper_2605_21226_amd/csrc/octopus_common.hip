@@ -8,8 +8,10 @@ bool plan_supported_d64(const octopus_plan_t &);
 bool plan_supported_d128(const octopus_plan_t &);
 bool plan_supported_d256(const octopus_plan_t &);
 #define OCTOPUS_DECL(D)                                                                                            \
-    int launch_decode_d##D(const octopus_codebooks_t &, const DecodeShape &, const float *, const void *,          \
-                           const void *, int, const int32_t *, float *, float *, float *, int32_t *, void *);      \
+    int launch_decode_mfma_d##D(const octopus_codebooks_t &, const DecodeShape &, const float *, const void *,     \
+                                const void *, const int32_t *, float *, float *, float *, int32_t *, void *);      \
+    int launch_decode_valu_d##D(const octopus_codebooks_t &, const DecodeShape &, const float *, const void *,     \
+                                const void *, const int32_t *, float *, float *, float *, int32_t *, void *);      \
     int launch_encode_d##D(const octopus_codebooks_t &, const void *, int, int64_t, int64_t, int64_t, int32_t,     \
                            int32_t, int32_t, const uint8_t *, void *, int64_t, const int32_t *, const uint8_t *, void *, \
                            void *);                                                                                \
@@ -44,10 +46,17 @@ bool plan_supported(const octopus_plan_t &plan) {
 int launch_decode(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
                   const void *v, int v_dtype, const int32_t *seq_lens, float *part_ml, float *part_acc,
                   float *scores_out, int32_t *work_plan, void *stream) {
+    const bool bf16 = v_dtype == OCTOPUS_DTYPE_BF16;
     switch (cb.plan.head_dim) {
-        case 64: return launch_decode_d64(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, work_plan, stream);
-        case 128: return launch_decode_d128(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, work_plan, stream);
-        case 256: return launch_decode_d256(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, work_plan, stream);
+        case 64:
+            return bf16 ? launch_decode_mfma_d64(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, work_plan, stream)
+                        : launch_decode_valu_d64(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, work_plan, stream);
+        case 128:
+            return bf16 ? launch_decode_mfma_d128(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, work_plan, stream)
+                        : launch_decode_valu_d128(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, work_plan, stream);
+        case 256:
+            return bf16 ? launch_decode_mfma_d256(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, work_plan, stream)
+                        : launch_decode_valu_d256(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, work_plan, stream);
         default: return static_cast<int>(hipErrorInvalidValue);
     }
 }

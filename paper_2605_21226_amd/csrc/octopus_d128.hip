@@ -1,2 +1,3 @@
 #define OCTOPUS_D 128
+#define OCTOPUS_PART 1
 #include "octopus_plans.inc"

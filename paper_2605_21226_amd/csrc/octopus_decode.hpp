@@ -1174,10 +1174,11 @@ template <class P>
 int launch_decode_mq(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
                      const void *v, const int32_t *seq_lens, float *part_ml, float *part_acc, hipStream_t stream);
 
+// bf16 values: the matrix-core kernels
 template <class P, int RG>
-int launch_decode_rg(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
-                     const void *v, int v_dtype, const int32_t *seq_lens, float *part_ml, float *part_acc,
-                     float *scores_out, int32_t *plan, hipStream_t stream) {
+int launch_decode_mfma_rg(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
+                          const void *v, const int32_t *seq_lens, float *part_ml, float *part_acc, float *scores_out,
+                          int32_t *plan, hipStream_t stream) {
     DeviceBooks books;
     for (int c = 0; c < 2; ++c) {
         for (int k = 0; k < 32; ++k) books.c_xi[c][k] = cb.c_xi[c][k];
@@ -1186,44 +1187,66 @@ int launch_decode_rg(const octopus_codebooks_t &cb, const DecodeShape &s, const 
     // one workgroup per compute unit; they share the items of the plan
     const dim3 grid(kDecodeWorkgroups);
     const dim3 block(kDecodeWaves * kWave);
-    hipError_t err;
-    if (v_dtype == OCTOPUS_DTYPE_BF16) {
-        if (scores_out != nullptr) {
-            hipLaunchKernelGGL((decode_kernel_mfma<P, RG, true, false>), grid, block, 0, stream, books, s, q_rot,
-                               static_cast<const uint4 *>(cache), static_cast<const uint32_t *>(v), seq_lens,
-                               part_ml, part_acc, scores_out, plan, nullptr, nullptr);
-        } else {
-            hipLaunchKernelGGL((decode_kernel_mfma<P, RG, false, false>), grid, block, 0, stream, books, s, q_rot,
-                               static_cast<const uint4 *>(cache), static_cast<const uint32_t *>(v), seq_lens,
-                               part_ml, part_acc, scores_out, plan, nullptr, nullptr);
-        }
+    if (scores_out != nullptr) {
+        hipLaunchKernelGGL((decode_kernel_mfma<P, RG, true, false>), grid, block, 0, stream, books, s, q_rot,
+                           static_cast<const uint4 *>(cache), static_cast<const uint32_t *>(v), seq_lens, part_ml,
+                           part_acc, scores_out, plan, nullptr, nullptr);
     } else {
-        const size_t smem = sizeof(DecodeSmemValu<P, RG>);
-        err = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel_valu<P, RG>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem));
-        if (err != hipSuccess) return static_cast<int>(err);
-        hipLaunchKernelGGL((decode_kernel_valu<P, RG>), grid, block, smem, stream, books, s, q_rot,
-                           static_cast<const uint4 *>(cache), static_cast<const float4 *>(v), seq_lens, part_ml,
-                           part_acc, scores_out, plan, 0, 0);
+        hipLaunchKernelGGL((decode_kernel_mfma<P, RG, false, false>), grid, block, 0, stream, books, s, q_rot,
+                           static_cast<const uint4 *>(cache), static_cast<const uint32_t *>(v), seq_lens, part_ml,
+                           part_acc, scores_out, plan, nullptr, nullptr);
     }
     return static_cast<int>(hipGetLastError());
 }
 
 template <class P>
-int launch_decode_plan(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
-                       const void *v, int v_dtype, const int32_t *seq_lens, float *part_ml, float *part_acc,
-                       float *scores_out, int32_t *plan, hipStream_t stream) {
+int launch_decode_mfma_plan(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot,
+                            const void *cache, const void *v, const int32_t *seq_lens, float *part_ml,
+                            float *part_acc, float *scores_out, int32_t *plan, hipStream_t stream) {
     switch (s.rows_per_pass) {
-        case 1: return launch_decode_rg<P, 1>(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, plan, stream);
-        case 2: return launch_decode_rg<P, 2>(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, plan, stream);
-        case 4: return launch_decode_rg<P, 4>(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, plan, stream);
-        case 8: return launch_decode_rg<P, 8>(cb, s, q_rot, cache, v, v_dtype, seq_lens, part_ml, part_acc, scores_out, plan, stream);
+        case 1: return launch_decode_mfma_rg<P, 1>(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, plan, stream);
+        case 2: return launch_decode_mfma_rg<P, 2>(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, plan, stream);
+        case 4: return launch_decode_mfma_rg<P, 4>(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, plan, stream);
+        case 8: return launch_decode_mfma_rg<P, 8>(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, plan, stream);
         case 128:
             if constexpr (P::D <= 128) {
-                if (v_dtype == OCTOPUS_DTYPE_BF16 && scores_out == nullptr)
+                if (scores_out == nullptr)
                     return launch_decode_mq<P>(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, stream);
             }
             return static_cast<int>(hipErrorInvalidValue);
+        default: return static_cast<int>(hipErrorInvalidValue);
+    }
+}
+
+// fp32 values: P.V on the vector units
+template <class P, int RG>
+int launch_decode_valu_rg(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
+                          const void *v, const int32_t *seq_lens, float *part_ml, float *part_acc, float *scores_out,
+                          int32_t *plan, hipStream_t stream) {
+    DeviceBooks books;
+    for (int c = 0; c < 2; ++c) {
+        for (int k = 0; k < 32; ++k) books.c_xi[c][k] = cb.c_xi[c][k];
+        for (int k = 0; k < 8; ++k) books.c_rho[c][k] = cb.c_rho[c][k];
+    }
+    const size_t smem = sizeof(DecodeSmemValu<P, RG>);
+    const hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel_valu<P, RG>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem));
+    if (err != hipSuccess) return static_cast<int>(err);
+    hipLaunchKernelGGL((decode_kernel_valu<P, RG>), dim3(kDecodeWorkgroups), dim3(kDecodeWaves * kWave), smem, stream,
+                       books, s, q_rot, static_cast<const uint4 *>(cache), static_cast<const float4 *>(v), seq_lens,
+                       part_ml, part_acc, scores_out, plan, 0, 0);
+    return static_cast<int>(hipGetLastError());
+}
+
+template <class P>
+int launch_decode_valu_plan(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot,
+                            const void *cache, const void *v, const int32_t *seq_lens, float *part_ml,
+                            float *part_acc, float *scores_out, int32_t *plan, hipStream_t stream) {
+    switch (s.rows_per_pass) {
+        case 1: return launch_decode_valu_rg<P, 1>(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, plan, stream);
+        case 2: return launch_decode_valu_rg<P, 2>(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, plan, stream);
+        case 4: return launch_decode_valu_rg<P, 4>(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, plan, stream);
+        case 8: return launch_decode_valu_rg<P, 8>(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, plan, stream);
         default: return static_cast<int>(hipErrorInvalidValue);
     }
 }
