@@ -10,6 +10,9 @@ bool plan_supported_d256(const octopus_plan_t &);
 #define OCTOPUS_DECL(D)                                                                                            \
     int launch_decode_mfma_d##D(const octopus_codebooks_t &, const DecodeShape &, const float *, const void *,     \
                                 const void *, const int32_t *, float *, float *, float *, int32_t *, void *);      \
+    int launch_decode_mfma_scores_d##D(const octopus_codebooks_t &, const DecodeShape &, const float *,            \
+                                       const void *, const void *, const int32_t *, float *, float *, float *,     \
+                                       int32_t *, void *);                                                         \
     int launch_decode_valu_d##D(const octopus_codebooks_t &, const DecodeShape &, const float *, const void *,     \
                                 const void *, const int32_t *, float *, float *, float *, int32_t *, void *);      \
     int launch_encode_d##D(const octopus_codebooks_t &, const void *, int, int64_t, int64_t, int64_t, int32_t,     \
@@ -46,19 +49,23 @@ bool plan_supported(const octopus_plan_t &plan) {
 int launch_decode(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
                   const void *v, int v_dtype, const int32_t *seq_lens, float *part_ml, float *part_acc,
                   float *scores_out, int32_t *work_plan, void *stream) {
-    const bool bf16 = v_dtype == OCTOPUS_DTYPE_BF16;
+    // kernel family: 0 matrix cores, 1 matrix cores with score output, 2 vector units (fp32 values)
+    const int family = v_dtype == OCTOPUS_DTYPE_BF16 ? (scores_out != nullptr ? 1 : 0) : 2;
+#define OCTOPUS_GO(D)                                                                                                   \
+    case D:                                                                                                             \
+        return family == 0   ? launch_decode_mfma_d##D(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out,  \
+                                                       work_plan, stream)                                               \
+               : family == 1 ? launch_decode_mfma_scores_d##D(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc,       \
+                                                              scores_out, work_plan, stream)                            \
+                             : launch_decode_valu_d##D(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out,  \
+                                                       work_plan, stream);
     switch (cb.plan.head_dim) {
-        case 64:
-            return bf16 ? launch_decode_mfma_d64(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, work_plan, stream)
-                        : launch_decode_valu_d64(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, work_plan, stream);
-        case 128:
-            return bf16 ? launch_decode_mfma_d128(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, work_plan, stream)
-                        : launch_decode_valu_d128(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, work_plan, stream);
-        case 256:
-            return bf16 ? launch_decode_mfma_d256(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, work_plan, stream)
-                        : launch_decode_valu_d256(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, work_plan, stream);
+        OCTOPUS_GO(64)
+        OCTOPUS_GO(128)
+        OCTOPUS_GO(256)
         default: return static_cast<int>(hipErrorInvalidValue);
     }
+#undef OCTOPUS_GO
 }
 
 int launch_decode_vq(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,

@@ -1174,8 +1174,9 @@ template <class P>
 int launch_decode_mq(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
                      const void *v, const int32_t *seq_lens, float *part_ml, float *part_acc, hipStream_t stream);
 
-// bf16 values: the matrix-core kernels
-template <class P, int RG>
+// bf16 values: the matrix-core kernels.  SCORES: the instantiation that also writes the scores (built in
+// a translation unit of its own).
+template <class P, int RG, bool SCORES>
 int launch_decode_mfma_rg(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
                           const void *v, const int32_t *seq_lens, float *part_ml, float *part_acc, float *scores_out,
                           int32_t *plan, hipStream_t stream) {
@@ -1185,34 +1186,25 @@ int launch_decode_mfma_rg(const octopus_codebooks_t &cb, const DecodeShape &s, c
         for (int k = 0; k < 8; ++k) books.c_rho[c][k] = cb.c_rho[c][k];
     }
     // one workgroup per compute unit; they share the items of the plan
-    const dim3 grid(kDecodeWorkgroups);
-    const dim3 block(kDecodeWaves * kWave);
-    if (scores_out != nullptr) {
-        hipLaunchKernelGGL((decode_kernel_mfma<P, RG, true, false>), grid, block, 0, stream, books, s, q_rot,
-                           static_cast<const uint4 *>(cache), static_cast<const uint32_t *>(v), seq_lens, part_ml,
-                           part_acc, scores_out, plan, nullptr, nullptr);
-    } else {
-        hipLaunchKernelGGL((decode_kernel_mfma<P, RG, false, false>), grid, block, 0, stream, books, s, q_rot,
-                           static_cast<const uint4 *>(cache), static_cast<const uint32_t *>(v), seq_lens, part_ml,
-                           part_acc, scores_out, plan, nullptr, nullptr);
-    }
+    hipLaunchKernelGGL((decode_kernel_mfma<P, RG, SCORES, false>), dim3(kDecodeWorkgroups), dim3(kDecodeWaves * kWave),
+                       0, stream, books, s, q_rot, static_cast<const uint4 *>(cache), static_cast<const uint32_t *>(v),
+                       seq_lens, part_ml, part_acc, scores_out, plan, nullptr, nullptr);
     return static_cast<int>(hipGetLastError());
 }
 
-template <class P>
+template <class P, bool SCORES>
 int launch_decode_mfma_plan(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot,
                             const void *cache, const void *v, const int32_t *seq_lens, float *part_ml,
                             float *part_acc, float *scores_out, int32_t *plan, hipStream_t stream) {
+    if ((scores_out != nullptr) != SCORES) return static_cast<int>(hipErrorInvalidValue);
     switch (s.rows_per_pass) {
-        case 1: return launch_decode_mfma_rg<P, 1>(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, plan, stream);
-        case 2: return launch_decode_mfma_rg<P, 2>(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, plan, stream);
-        case 4: return launch_decode_mfma_rg<P, 4>(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, plan, stream);
-        case 8: return launch_decode_mfma_rg<P, 8>(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, plan, stream);
+        case 1: return launch_decode_mfma_rg<P, 1, SCORES>(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, plan, stream);
+        case 2: return launch_decode_mfma_rg<P, 2, SCORES>(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, plan, stream);
+        case 4: return launch_decode_mfma_rg<P, 4, SCORES>(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, plan, stream);
+        case 8: return launch_decode_mfma_rg<P, 8, SCORES>(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, plan, stream);
         case 128:
-            if constexpr (P::D <= 128) {
-                if (scores_out == nullptr)
-                    return launch_decode_mq<P>(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, stream);
-            }
+            if constexpr (P::D <= 128 && !SCORES)
+                return launch_decode_mq<P>(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, stream);
             return static_cast<int>(hipErrorInvalidValue);
         default: return static_cast<int>(hipErrorInvalidValue);
     }
