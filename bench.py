@@ -116,11 +116,11 @@ def cpu_baseline(wl, keys, vals, q, signs, scale, record_bytes, budget_s=12.0, s
     }
 
 
-def measured_traffic(workload):
-    """HBM bytes per launch of the fused decode kernel as measured with rocprofv3 --pmc FETCH_SIZE /
+def measured_traffic(workload, kernel="decode_kernel_mfma"):
+    """HBM bytes per launch of the dominant decode kernel as measured with rocprofv3 --pmc FETCH_SIZE /
     WRITE_SIZE (scaled by a plain copy of known size); read from the committed profile summary of this
-    workload, None if there is none."""
-    path = os.path.join(ROOT, "profiles", f"decode_kernel_mfma_{workload}_traffic.txt")
+    kernel and workload, None if there is none."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_traffic.txt")
     try:
         vals = {}
         with open(path) as f:
@@ -321,11 +321,14 @@ def main():
             "kernel_ms": round(ker_s * 1e3, 4),
         },
     }
-    result["roofline"]["traffic"] = measured_traffic(wl.name + ("_qjl" if args.qjl else "") +
-                                                     (f"_vq{v_bits}g{v_group}" if args.vq else ""))
+    uses_mq = (many_rows and wl.head_dim <= 128 and wl.n_q * (wl.n_q_heads // wl.n_kv_heads) >= 32 and
+               wl.dtype == "bf16")
+    dominant = "decode_kernel_valu" if args.vq else ("decode_kernel_mq" if uses_mq else "decode_kernel_mfma")
+    result["roofline"]["traffic"] = None if args.window else measured_traffic(
+        wl.name + ("_qjl" if args.qjl else "") + (f"_vq{v_bits}g{v_group}" if args.vq else ""), dominant)
     if args.vq:
         result["roofline"]["kernel"] = result["roofline"]["kernel"].replace("decode_kernel_mfma", "decode_kernel_valu")
-    if many_rows and wl.head_dim <= 128 and wl.n_q * (wl.n_q_heads // wl.n_kv_heads) >= 32 and wl.dtype == "bf16":
+    if uses_mq:
         # hundreds of query rows per key: a dense contraction on the matrix cores, 4 d flops per (query row, key)
         flops = 4.0 * wl.head_dim * wl.n_q * wl.n_q_heads * float(lens.astype(np.int64).sum())
         tf = flops / ker_s / 1e12
