@@ -8,16 +8,19 @@
 
 namespace octopus {
 
-// One thread per (token, KV head, group): min and max of the group's g values, scale = (max - min) /
-// (2^b - 1), code = rint((v - min) / scale) clamped; each a single correctly rounded fp32 operation.
-template <bool BF16>
+// One thread per (token, KV head, group): min and max of the group's G values, scale = (max - min) /
+// (2^B - 1), code = rint((v - min) / scale) clamped; each a single correctly rounded fp32 operation.
+// VEC16: every group starts on a 16-byte boundary of the input (16-byte loads).
+template <bool BF16, int B, int G>
 __global__ __launch_bounds__(256) void encode_values_kernel(const void *__restrict__ v, int64_t stride_seq,
                                                              int64_t stride_tok, int64_t stride_head, int32_t n_seq,
-                                                             int32_t n_kv_heads, int32_t n_new, int32_t d, int32_t bits,
-                                                             int32_t group, unsigned char *__restrict__ vq,
-                                                             int64_t t_capacity,
+                                                             int32_t n_kv_heads, int32_t n_new, int32_t d,
+                                                             unsigned char *__restrict__ vq, int64_t t_capacity,
                                                              const int32_t *__restrict__ start_pos, int vec16) {
-    const int n_groups = d / group;
+    constexpr int LEVELS = (1 << B) - 1;
+    constexpr int CODE_WORDS = G * B / 32 + ((G * B) % 32 ? 1 : 0);   // 1, 2, 3 or 4
+    constexpr int CODE_BYTES = G * B / 8;                             // the group's codes: 4 .. 16 bytes
+    const int n_groups = d / G;
     const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
     const int64_t total = static_cast<int64_t>(n_seq) * n_new * n_kv_heads * n_groups;
     if (idx >= total) return;
@@ -28,80 +31,71 @@ __global__ __launch_bounds__(256) void encode_values_kernel(const void *__restri
     const int64_t pos = (start_pos ? start_pos[seq] : 0) + tok;
     if (pos >= t_capacity) return;
 
-    const int64_t src = seq * stride_seq + tok * stride_tok + kvh * stride_head + static_cast<int64_t>(grp) * group;
-    float x[32];
-    if (vec16) {   // the group's elements start on a 16-byte boundary: 16-byte loads
-        if (BF16) {
+    const int64_t src = seq * stride_seq + tok * stride_tok + kvh * stride_head + static_cast<int64_t>(grp) * G;
+    float x[G];
+    if (vec16) {
+        if constexpr (BF16) {
             const uint4 *p4 = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(v) + src);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (8 * j < group) {
-                    const uint4 w = p4[j];
-                    const uint32_t w4[4] = {w.x, w.y, w.z, w.w};
+            for (int j = 0; j < G / 8; ++j) {
+                const uint4 w = p4[j];
+                const uint32_t w4[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
-                    for (int h = 0; h < 4; ++h) {
-                        x[8 * j + 2 * h] = __uint_as_float(w4[h] << 16);
-                        x[8 * j + 2 * h + 1] = __uint_as_float(w4[h] & 0xffff0000u);
-                    }
+                for (int h = 0; h < 4; ++h) {
+                    x[8 * j + 2 * h] = __uint_as_float(w4[h] << 16);
+                    x[8 * j + 2 * h + 1] = __uint_as_float(w4[h] & 0xffff0000u);
                 }
             }
         } else {
             const float4 *p4 = reinterpret_cast<const float4 *>(static_cast<const float *>(v) + src);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                if (4 * j < group) {
-                    const float4 w = p4[j];
-                    x[4 * j] = w.x; x[4 * j + 1] = w.y; x[4 * j + 2] = w.z; x[4 * j + 3] = w.w;
-                }
+            for (int j = 0; j < G / 4; ++j) {
+                const float4 w = p4[j];
+                x[4 * j] = w.x; x[4 * j + 1] = w.y; x[4 * j + 2] = w.z; x[4 * j + 3] = w.w;
             }
         }
-#pragma unroll
-        for (int j = 16; j < 32; ++j) x[j] = (j < group) ? x[j] : x[0];
     } else {
 #pragma unroll
-        for (int j = 0; j < 32; ++j) {
-            if (j < group) {
-                x[j] = BF16 ? __uint_as_float(static_cast<uint32_t>(static_cast<const uint16_t *>(v)[src + j]) << 16)
-                            : static_cast<const float *>(v)[src + j];
-            } else {
-                x[j] = x[0];
-            }
-        }
+        for (int j = 0; j < G; ++j)
+            x[j] = BF16 ? __uint_as_float(static_cast<uint32_t>(static_cast<const uint16_t *>(v)[src + j]) << 16)
+                        : static_cast<const float *>(v)[src + j];
     }
     float lo = x[0], hi = x[0];
 #pragma unroll
-    for (int j = 1; j < 32; ++j) {
+    for (int j = 1; j < G; ++j) {
         lo = x[j] < lo ? x[j] : lo;
         hi = x[j] > hi ? x[j] : hi;
     }
-    const int levels = (1 << bits) - 1;
-    const float scale = __fdiv_rn(__fsub_rn(hi, lo), static_cast<float>(levels));
+    const float scale = __fdiv_rn(__fsub_rn(hi, lo), static_cast<float>(LEVELS));
 
-    const int row_bytes = bits * d / 8 + n_groups * 8;
-    unsigned char *row = vq + ((static_cast<int64_t>(seq) * n_kv_heads + kvh) * t_capacity + pos) * row_bytes;
-    // the group's codes: group * bits bits = 2 * bits (g = 16) or 4 * bits (g = 32) bytes, written as 16-bit words
-    uint16_t *dst = reinterpret_cast<uint16_t *>(row + grp * (group * bits / 8));
-    uint32_t word = 0u;
-    int filled = 0, out = 0;
+    // the codes, channel j of the group at bit B * j (compile-time positions)
+    uint32_t words[CODE_WORDS];
 #pragma unroll
-    for (int j = 0; j < 32; ++j) {
-        if (j < group) {
-            uint32_t code = 0u;
-            if (scale > 0.0f) {
-                float c = rintf(__fdiv_rn(__fsub_rn(x[j], lo), scale));
-                c = fminf(fmaxf(c, 0.0f), static_cast<float>(levels));
-                code = static_cast<uint32_t>(c);
-            }
-            word |= code << filled;
-            filled += bits;
-            if (filled >= 16) {
-                dst[out++] = static_cast<uint16_t>(word & 0xffffu);
-                word >>= 16;
-                filled -= 16;
-            }
+    for (int k = 0; k < CODE_WORDS; ++k) words[k] = 0u;
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        uint32_t code = 0u;
+        if (scale > 0.0f) {
+            float c = rintf(__fdiv_rn(__fsub_rn(x[j], lo), scale));
+            c = fminf(fmaxf(c, 0.0f), static_cast<float>(LEVELS));
+            code = static_cast<uint32_t>(c);
         }
+        const int bit = B * j, wi = bit >> 5, sh = bit & 31;   // constants after unrolling
+        words[wi] |= code << sh;
+        if (sh + B > 32) words[wi + 1] |= code >> (32 - sh);
     }
-    float2 *meta = reinterpret_cast<float2 *>(row + bits * d / 8 + grp * 8);
+    const int row_bytes = B * d / 8 + n_groups * 8;
+    unsigned char *row = vq + ((static_cast<int64_t>(seq) * n_kv_heads + kvh) * t_capacity + pos) * row_bytes;
+    unsigned char *dst = row + grp * CODE_BYTES;
+    if constexpr (CODE_BYTES % 4 == 0) {          // rows are multiples of 8 bytes: the group starts on a word
+#pragma unroll
+        for (int k = 0; k < CODE_BYTES / 4; ++k) reinterpret_cast<uint32_t *>(dst)[k] = words[k];
+    } else {                                      // 16 codes of 3 bits: 6 bytes, on a 2-byte boundary
+#pragma unroll
+        for (int k = 0; k < CODE_BYTES / 2; ++k)
+            reinterpret_cast<uint16_t *>(dst)[k] = static_cast<uint16_t>(words[k / 2] >> (16 * (k & 1)));
+    }
+    float2 *meta = reinterpret_cast<float2 *>(row + B * d / 8 + grp * 8);
     *meta = make_float2(scale, lo);
 }
 
@@ -115,15 +109,19 @@ int launch_encode_values(const void *v, int v_dtype, int64_t stride_seq, int64_t
     const int64_t per16 = v_dtype == OCTOPUS_DTYPE_BF16 ? 8 : 4;
     const int vec16 = (reinterpret_cast<uintptr_t>(v) % 16 == 0 && stride_seq % per16 == 0 && stride_tok % per16 == 0 &&
                        stride_head % per16 == 0) ? 1 : 0;
-    if (v_dtype == OCTOPUS_DTYPE_BF16)
-        hipLaunchKernelGGL(encode_values_kernel<true>, grid, dim3(256), 0, st, v, stride_seq, stride_tok, stride_head,
-                           n_seq, n_kv_heads, n_new, head_dim, bits, group, static_cast<unsigned char *>(vq),
-                           t_capacity, start_pos, vec16);
-    else
-        hipLaunchKernelGGL(encode_values_kernel<false>, grid, dim3(256), 0, st, v, stride_seq, stride_tok, stride_head,
-                           n_seq, n_kv_heads, n_new, head_dim, bits, group, static_cast<unsigned char *>(vq),
-                           t_capacity, start_pos, vec16);
-    return static_cast<int>(hipGetLastError());
+    auto go = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, grid, dim3(256), 0, st, v, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new,
+                           head_dim, static_cast<unsigned char *>(vq), t_capacity, start_pos, vec16);
+    };
+    const bool bf16 = v_dtype == OCTOPUS_DTYPE_BF16;
+#define OCTOPUS_CASE(B, G)                                                                                          \
+    if (bits == B && group == G) {                                                                                  \
+        if (bf16) go(encode_values_kernel<true, B, G>); else go(encode_values_kernel<false, B, G>);                 \
+        return static_cast<int>(hipGetLastError());                                                                 \
+    }
+    OCTOPUS_CASE(2, 16) OCTOPUS_CASE(3, 16) OCTOPUS_CASE(4, 16) OCTOPUS_CASE(2, 32) OCTOPUS_CASE(3, 32) OCTOPUS_CASE(4, 32)
+#undef OCTOPUS_CASE
+    return static_cast<int>(hipErrorInvalidValue);
 }
 
 }  // namespace octopus
