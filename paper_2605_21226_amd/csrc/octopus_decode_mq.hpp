@@ -233,13 +233,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(P::D <= 64 
         const float m_new = fmaxf(m_run, mx);
         const float alpha = exp2_raw((m_run - m_new) * kLog2e);
         m_run = m_new;
+        const float m_log2 = -m_new * kLog2e;     // p = 2^(s log2(e) - m log2(e)): one fma per score
         float psum = 0.0f;
         BF8 ph[4], pl[4];   // per group of 16 keys: the 8 k-slots of this lane, hi and lo
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
             for (int e = 0; e < 16; e += 2) {
-                const float p0 = exp2_raw((sacc[mb][e] - m_new) * kLog2e), p1 = exp2_raw((sacc[mb][e + 1] - m_new) * kLog2e);
+                const float p0 = exp2_raw(fmaf(sacc[mb][e], kLog2e, m_log2)), p1 = exp2_raw(fmaf(sacc[mb][e + 1], kLog2e, m_log2));
                 psum += p0 + p1;
                 const uint32_t b0 = __float_as_uint(p0), b1 = __float_as_uint(p1);
                 const float l0 = p0 - __uint_as_float(b0 & 0xffff0000u), l1 = p1 - __uint_as_float(b1 & 0xffff0000u);
@@ -247,10 +248,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(P::D <= 64 
                 pl[2 * mb + e / 8].u[(e % 8) / 2] = __builtin_amdgcn_perm(__float_as_uint(l1), __float_as_uint(l0), 0x07060302u);
             }
         l_run = fmaf(l_run, alpha, psum);
+        // the running maxima stop moving after the first tiles: skip the rescale when no row of the wave needs it
+        if (__ballot(alpha != 1.0f) != 0) {
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
+            for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) oacc[nb][e] *= alpha;
+                for (int e = 0; e < 16; ++e) oacc[nb][e] *= alpha;
+        }
         // O^T += V^T P^T
 #pragma unroll
         for (int g16 = 0; g16 < 4; ++g16)
