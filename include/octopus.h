@@ -121,8 +121,8 @@ size_t octopus_cache_bytes(const octopus_codebooks_t *cb, int32_t n_seq, int32_t
  *               written to slot start_pos[s] + t.  Other slots are untouched.
  *   start_pos   device [n_seq] int32, or NULL for all zeros.  Slots beyond
  *               t_capacity are not written (the caller must size the cache).
- * Errors: EINVAL, EUNSUPPORTED (plan / dtype without a kernel; centroids not
- * ascending, or two boundaries of C_xi closer than 1 / (4 * 2^b_dir), which the
+ * Errors: EINVAL (also n_seq or n_kv_heads above 65535), EUNSUPPORTED (plan /
+ * dtype without a kernel; centroids not ascending, or two boundaries of C_xi closer than 1 / (4 * 2^b_dir), which the
  * kernel's seed search does not resolve -- never the case for the codebooks
  * octopus_build_codebooks returns), EHIP. */
 int octopus_encode(const octopus_codebooks_t *cb,

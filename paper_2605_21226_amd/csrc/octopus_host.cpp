@@ -398,6 +398,7 @@ static int encode_checked(const octopus_codebooks_t *cb, const void *keys, int32
     if (cb == nullptr || keys == nullptr || signs == nullptr || cache == nullptr) return OCTOPUS_EINVAL;
     if (rounding < OCTOPUS_ROUND_SEED || rounding > OCTOPUS_ROUND_LOCAL_2X2) return OCTOPUS_EINVAL;
     if (n_seq < 1 || n_kv_heads < 1 || n_new < 0) return OCTOPUS_EINVAL;
+    if (n_seq > 65535 || n_kv_heads > 65535) return OCTOPUS_EINVAL;   // they are grid dimensions of the launch
     if (t_capacity < OCTOPUS_TILE || t_capacity % OCTOPUS_TILE != 0) return OCTOPUS_EINVAL;
     if (!plan_consistent(cb->plan)) return OCTOPUS_EINVAL;
     if (key_dtype != OCTOPUS_DTYPE_F32 && key_dtype != OCTOPUS_DTYPE_BF16) return OCTOPUS_EUNSUPPORTED;

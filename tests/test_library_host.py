@@ -89,6 +89,7 @@ def test_encode_and_decode_reject_bad_arguments_before_launching(lib):
     assert enc(P, fake, 1, 1024, 1024, 128, 1, 8, 128, fake, fake, 64, null, null) == binding.EINVAL      # overflow
     assert enc(P, ctypes.c_void_p(0x1004), 1, 1024, 1024, 128, 1, 8, 64, fake, fake, 64, null, null) == binding.EINVAL
     assert enc(P, fake, 1, 1024, 1024, 128, 1, 8, 0, fake, fake, 64, null, null) == binding.OK             # nothing to do
+    assert enc(P, fake, 1, 1024, 1024, 128, 65536, 8, 64, fake, fake, 64, null, null) == binding.EINVAL   # grid limit
     pair = binding.octopus_build_codebooks_pair(128, 3, 3)   # no kernel is built for this pair
     assert enc(ctypes.byref(pair), fake, 1, 1024, 1024, 128, 1, 8, 64, fake, fake, 64, null, null) == binding.EUNSUPPORTED
     broken = binding.octopus_build_codebooks(128, 3)
