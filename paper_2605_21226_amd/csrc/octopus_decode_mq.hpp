@@ -132,41 +132,50 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(P::D <= 64 
 #pragma unroll
         for (int i = 0; i < VP; ++i) vp[i] = *reinterpret_cast<const uint4 *>(vrow + (wave + 4 * i) * 16);
     };
-    // one triplet of this lane's key into the key tile
-    auto stage_triplet = [&](auto ii, int buf) __attribute__((always_inline)) {
-        constexpr int i = decltype(ii)::value;
-        constexpr int c = P::cls(i);
-        constexpr int bd = P::bdir(i), bn = P::bnrm(i);
-        const uint32_t code = field<P::dir_bit(i), 2 * bd>(w);
-        const uint32_t nrm = field<P::nrm_bit(i), bn>(w);
-        const float4 dir = (c ? sm.dir1 : sm.dir0)[code];
-        const float g = __uint_as_float(w[0]) * sm.c_rho[c][nrm];
-        const float val[3] = {g * dir.x, g * dir.y, g * dir.z};
+    // Wave wv writes the coordinates [wv * D / 4, (wv + 1) * D / 4) of its lane's key: it decodes the triplets
+    // that cover them (one or two of them are decoded by the neighbouring wave as well) and writes whole
+    // 16-byte pieces of the key tile.  (Two-byte writes, one per coordinate, land on 8 banks for the 64 lanes
+    // of a wavefront and were a third of this kernel's time.)
+    auto stage_block = [&](auto ww, int buf) __attribute__((always_inline)) {
+        constexpr int wv = decltype(ww)::value;
+        constexpr int CW = D / 4;                       // coordinates per wave: 16 or 32
+        constexpr int T_LO = (wv * CW) / 3, T_HI = ((wv + 1) * CW - 1) / 3;
+        constexpr int NT = T_HI - T_LO + 1;
+        float val[3 * NT];
+        static_for<0, NT>([&](auto jj) {
+            constexpr int i = T_LO + decltype(jj)::value;
+            constexpr int c = P::cls(i);
+            constexpr int bd = P::bdir(i), bn = P::bnrm(i);
+            const uint32_t code = field<P::dir_bit(i), 2 * bd>(w);
+            const uint32_t nrm = field<P::nrm_bit(i), bn>(w);
+            const float4 dir = (c ? sm.dir1 : sm.dir0)[code];
+            const float g = __uint_as_float(w[0]) * sm.c_rho[c][nrm];
+            val[3 * decltype(jj)::value] = g * dir.x;
+            val[3 * decltype(jj)::value + 1] = g * dir.y;
+            val[3 * decltype(jj)::value + 2] = g * dir.z;
+        });
 #pragma unroll
-        for (int e = 0; e < 3; ++e) {
-            if (3 * i + e < D) {   // the padded coordinates of the last triplet are dropped
-                const uint32_t bits = __float_as_uint(val[e]);
-                const float lo = val[e] - __uint_as_float(bits & 0xffff0000u);
-                sm.kh[buf][lane][3 * i + e] = static_cast<uint16_t>(bits >> 16);
-                sm.kl[buf][lane][3 * i + e] = static_cast<uint16_t>(__float_as_uint(lo) >> 16);
+        for (int g8 = 0; g8 < CW / 8; ++g8) {
+            uint32_t hi[4], lo[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int j = wv * CW + 8 * g8 + 2 * k - 3 * T_LO;      // index into val of the pair's first value
+                const uint32_t b0 = __float_as_uint(val[j]), b1 = __float_as_uint(val[j + 1]);
+                const float l0 = val[j] - __uint_as_float(b0 & 0xffff0000u);
+                const float l1 = val[j + 1] - __uint_as_float(b1 & 0xffff0000u);
+                hi[k] = __builtin_amdgcn_perm(b1, b0, 0x07060302u);
+                lo[k] = __builtin_amdgcn_perm(__float_as_uint(l1), __float_as_uint(l0), 0x07060302u);
             }
+            *reinterpret_cast<uint4 *>(&sm.kh[buf][lane][wv * CW + 8 * g8]) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+            *reinterpret_cast<uint4 *>(&sm.kl[buf][lane][wv * CW + 8 * g8]) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
         }
     };
-    // wave wv takes the triplets i = wv (mod 4): compile-time field positions per case
     auto stage_tile = [&](int buf) {
-        constexpr int PER = (P::NTRI + 3) / 4;
-        auto part = [&](auto ww) __attribute__((always_inline)) {
-            constexpr int wv = decltype(ww)::value;
-            static_for<0, PER>([&](auto jj) {
-                constexpr int i = wv + 4 * decltype(jj)::value;
-                if constexpr (i < P::NTRI) stage_triplet(std::integral_constant<int, i>{}, buf);
-            });
-        };
         switch (wave) {
-            case 0: part(std::integral_constant<int, 0>{}); break;
-            case 1: part(std::integral_constant<int, 1>{}); break;
-            case 2: part(std::integral_constant<int, 2>{}); break;
-            default: part(std::integral_constant<int, 3>{}); break;
+            case 0: stage_block(std::integral_constant<int, 0>{}, buf); break;
+            case 1: stage_block(std::integral_constant<int, 1>{}, buf); break;
+            case 2: stage_block(std::integral_constant<int, 2>{}, buf); break;
+            default: stage_block(std::integral_constant<int, 3>{}, buf); break;
         }
 #pragma unroll
         for (int i = 0; i < VP; ++i) {
