@@ -317,7 +317,7 @@ __global__ __launch_bounds__(kWave) void rotate_queries_kernel(const void *__res
                                                                 float *__restrict__ q2) {
     constexpr int EPL = D / kWave;  // elements per lane (1, 2, 4)
     const int lane = threadIdx.x;
-    // block 0 also cuts the work items of the split-K kernel that follows (not used with 128-row blocks)
+    // block 0 also cuts the work items of the split-K kernel that follows (not used by the many-row kernel)
     if (blockIdx.x == 0 && plan != nullptr) build_plan(s, seq_lens, decode_keys_per_lane<D>(), plan, lane);
     const int rg = s.rows_per_pass;
     const int padded_rows = s.n_row_groups * rg;
@@ -1102,7 +1102,7 @@ __global__ __launch_bounds__(kWave) void merge_kernel(DecodeShape shp, const flo
     const int kvh = head / shp.heads_per_kv;
     const int row = qi * shp.heads_per_kv + head % shp.heads_per_kv;
     const int grp = row / shp.rows_per_pass, r = row % shp.rows_per_pass;
-    // Partial j of this row is at prow0 + j * pstride, j < n_part.  Blocks of 128 rows (matrix-core kernel):
+    // Partial j of this row is at prow0 + j * pstride, j < n_part.  The many-row kernel (blocks of 128 or 256 rows):
     // one partial per split, adjacent.  Otherwise: the items of this row's (sequence, KV head, row group)
     // are consecutive, each with one partial per wavefront, RG rows apart.
     int64_t prow0;
@@ -1203,6 +1203,7 @@ int launch_decode_mfma_plan(const octopus_codebooks_t &cb, const DecodeShape &s,
         case 4: return launch_decode_mfma_rg<P, 4, SCORES>(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, plan, stream);
         case 8: return launch_decode_mfma_rg<P, 8, SCORES>(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, scores_out, plan, stream);
         case 128:
+        case 256:   // the many-row kernel: 256 rows per workgroup at d = 64, 128 at d = 128
             if constexpr (P::D <= 128 && !SCORES)
                 return launch_decode_mq<P>(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, stream);
             return static_cast<int>(hipErrorInvalidValue);

@@ -25,7 +25,9 @@
 
 namespace octopus {
 
-constexpr int kMqRows = 128;  // query rows per workgroup
+// Query rows per workgroup: 32 per wavefront, NW = 4 wavefronts (128 rows) or, at d = 64 where the
+// registers allow two wavefronts per SIMD, NW = 8 (256 rows).  The keys of a tile are decoded once per
+// workgroup, so more rows mean less decoding; the host picks 256 when there are rows enough to fill them.
 
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 
@@ -43,8 +45,8 @@ struct MqSmem {
     uint16_t vt[2][D][VST];
 };
 
-template <class P>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(P::D <= 64 ? 2 : 1))) void decode_kernel_mq(DeviceBooks books, DecodeShape shp,
+template <class P, int NW>
+__global__ __launch_bounds__(kWave *NW) __attribute__((amdgpu_waves_per_eu(P::D <= 64 ? 2 : 1))) void decode_kernel_mq(DeviceBooks books, DecodeShape shp,
                                                          const float *__restrict__ q_rot,
                                                          const uint4 *__restrict__ cache,
                                                          const uint16_t *__restrict__ v,
@@ -55,7 +57,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(P::D <= 64 
     constexpr int NB = D / 32;               // 32-channel blocks of the output
     constexpr int ROWB = D * 2;              // bytes per value row
     constexpr int TILEB = P::GRANULES * kWave * 16;
-    constexpr int VP = D / 8 / 4;            // 16-byte value pieces per thread and tile
+    constexpr int ROWS = 32 * NW;            // query rows per workgroup
+    constexpr int VP = D / 8 / NW;           // 16-byte value pieces per thread and tile
     using S = MqSmem<P>;
     __shared__ S sm;
 
@@ -66,10 +69,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(P::D <= 64 
     // tables (one copy: the lookups are a small part of this kernel)
     if (tid < kWave) copy_books(books, sm.c_xi, sm.c_rho);
     __syncthreads();
-    build_dir_lut<P::BD0>(sm.dir0, sm.c_xi[0], tid, 256);
-    if constexpr (P::NCLASS == 2) build_dir_lut<P::BD1>(sm.dir1, sm.c_xi[1], tid, 256);
+    build_dir_lut<P::BD0>(sm.dir0, sm.c_xi[0], tid, kWave * NW);
+    if constexpr (P::NCLASS == 2) build_dir_lut<P::BD1>(sm.dir1, sm.c_xi[1], tid, kWave * NW);
 
-    // work: (sequence, KV head, block of 128 rows, split) and the split's tiles
+    // work: (sequence, KV head, block of ROWS rows, split) and the split's tiles
     const int64_t wg = blockIdx.x;
     const int split = static_cast<int>(wg % shp.n_splits);
     const int64_t group_id = wg / shp.n_splits;
@@ -85,15 +88,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(P::D <= 64 
     const char *v_pair = reinterpret_cast<const char *>(v) + pair * shp.t_capacity * ROWB;
 
     // Q^T operands of this wave's 32 rows: lane (n, h) holds coordinates 16 kk + 8 h .. + 8 of row n as
-    // bf16 hi and lo.  The rotated queries lie [coordinate][row] with the 128 rows of the block adjacent.
-    const float *qg = q_rot + group_id * (static_cast<int64_t>(P::QS) * kMqRows) + wave * 32 + n;
+    // bf16 hi and lo.  The rotated queries lie [coordinate][row] with the ROWS rows of the block adjacent.
+    const float *qg = q_rot + group_id * (static_cast<int64_t>(P::QS) * ROWS) + wave * 32 + n;
     union BF8 { uint32_t u[4]; bf16x8_t b; };
     BF8 qh[KK], ql[KK];
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const float a = qg[(16 * kk + 8 * h + 2 * e) * kMqRows], b = qg[(16 * kk + 8 * h + 2 * e + 1) * kMqRows];
+            const float a = qg[(16 * kk + 8 * h + 2 * e) * ROWS], b = qg[(16 * kk + 8 * h + 2 * e + 1) * ROWS];
             const uint32_t ab = __float_as_uint(a), bb = __float_as_uint(b);
             qh[kk].u[e] = __builtin_amdgcn_perm(bb, ab, 0x07060302u);
             const float al = a - __uint_as_float(ab & 0xffff0000u), bl = b - __uint_as_float(bb & 0xffff0000u);
@@ -130,15 +133,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(P::D <= 64 
         const int row = min(tile * kWave + lane, len - 1);
         const char *vrow = v_pair + static_cast<int64_t>(row) * ROWB;
 #pragma unroll
-        for (int i = 0; i < VP; ++i) vp[i] = *reinterpret_cast<const uint4 *>(vrow + (wave + 4 * i) * 16);
+        for (int i = 0; i < VP; ++i) vp[i] = *reinterpret_cast<const uint4 *>(vrow + (wave + NW * i) * 16);
     };
-    // Wave wv writes the coordinates [wv * D / 4, (wv + 1) * D / 4) of its lane's key: it decodes the triplets
+    // Wave wv writes the coordinates [wv * D / NW, (wv + 1) * D / NW) of its lane's key: it decodes the triplets
     // that cover them (one or two of them are decoded by the neighbouring wave as well) and writes whole
     // 16-byte pieces of the key tile.  (Two-byte writes, one per coordinate, land on 8 banks for the 64 lanes
     // of a wavefront and were a third of this kernel's time.)
     auto stage_block = [&](auto ww, int buf) __attribute__((always_inline)) {
         constexpr int wv = decltype(ww)::value;
-        constexpr int CW = D / 4;                       // coordinates per wave: 16 or 32
+        constexpr int CW = D / NW;                      // coordinates per wave: 8 (d = 64) or 32 (d = 128)
         constexpr int T_LO = (wv * CW) / 3, T_HI = ((wv + 1) * CW - 1) / 3;
         constexpr int NT = T_HI - T_LO + 1;
         float val[3 * NT];
@@ -175,11 +178,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(P::D <= 64 
             case 0: stage_block(std::integral_constant<int, 0>{}, buf); break;
             case 1: stage_block(std::integral_constant<int, 1>{}, buf); break;
             case 2: stage_block(std::integral_constant<int, 2>{}, buf); break;
-            default: stage_block(std::integral_constant<int, 3>{}, buf); break;
+            case 3: stage_block(std::integral_constant<int, 3>{}, buf); break;
+            default:
+                if constexpr (NW == 8) {
+                    switch (wave) {
+                        case 4: stage_block(std::integral_constant<int, 4>{}, buf); break;
+                        case 5: stage_block(std::integral_constant<int, 5>{}, buf); break;
+                        case 6: stage_block(std::integral_constant<int, 6>{}, buf); break;
+                        default: stage_block(std::integral_constant<int, 7>{}, buf); break;
+                    }
+                }
+                break;
         }
 #pragma unroll
         for (int i = 0; i < VP; ++i) {
-            const int c0 = (wave + 4 * i) * 8;
+            const int c0 = (wave + NW * i) * 8;
             const uint32_t x[4] = {vp[i].x, vp[i].y, vp[i].z, vp[i].w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -287,8 +300,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(P::D <= 64 
     // partial of each row: element e of block nb is channel 32 nb + 8 (e / 4) + 4 h + e % 4 of row n
     const int row = wave * 32 + n;
     const int grp = static_cast<int>(group_id % shp.n_row_groups);
-    if (grp * kMqRows + row < shp.rows_per_kv) {
-        const int64_t prow = (group_id * kMqRows + row) * shp.n_splits + split;
+    if (grp * ROWS + row < shp.rows_per_kv) {
+        const int64_t prow = (group_id * ROWS + row) * shp.n_splits + split;
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -312,8 +325,18 @@ int launch_decode_mq(const octopus_codebooks_t &cb, const DecodeShape &s, const 
         for (int k = 0; k < 8; ++k) books.c_rho[c][k] = cb.c_rho[c][k];
     }
     const int64_t wgs = static_cast<int64_t>(s.n_seq) * s.n_kv_heads * s.n_row_groups * s.n_splits;
-    hipLaunchKernelGGL((decode_kernel_mq<P>), dim3(static_cast<unsigned>(wgs)), dim3(256), 0, stream, books, s, q_rot,
-                       static_cast<const uint4 *>(cache), static_cast<const uint16_t *>(v), seq_lens, part_ml, part_acc);
+    auto go = [&](auto kernel, int waves) {
+        hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(wgs)), dim3(kWave * waves), 0, stream, books, s, q_rot,
+                           static_cast<const uint4 *>(cache), static_cast<const uint16_t *>(v), seq_lens, part_ml, part_acc);
+    };
+    if (s.rows_per_pass == 128) {
+        go(decode_kernel_mq<P, 4>, 4);
+    } else if (s.rows_per_pass == 256) {
+        if constexpr (P::D <= 64) go(decode_kernel_mq<P, 8>, 8);
+        else return static_cast<int>(hipErrorInvalidValue);
+    } else {
+        return static_cast<int>(hipErrorInvalidValue);
+    }
     return static_cast<int>(hipGetLastError());
 }
 

@@ -231,13 +231,14 @@ DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t
     s.max_len = static_cast<int32_t>(max_len);
     const int64_t len = std::max<int64_t>(max_len, 1);
     if (many_rows) {
-        // Matrix-core kernel for many query rows: blocks of 128 rows, one workgroup per (block, split);
-        // two workgroups fit a compute unit at d = 64, one at d = 128.
-        s.rows_per_pass = 128;
-        s.n_row_groups = (s.rows_per_kv + 127) / 128;
+        // Matrix-core kernel for many query rows: blocks of 128 rows (4 wavefronts), or of 256 rows (8
+        // wavefronts) at d = 64 when there are rows enough; one workgroup per (block, split).  A compute unit
+        // runs 8 of these wavefronts at d = 64 and 4 at d = 128.
+        s.rows_per_pass = (plan.head_dim <= 64 && s.rows_per_kv >= 192) ? 256 : 128;
+        s.n_row_groups = (s.rows_per_kv + s.rows_per_pass - 1) / s.rows_per_pass;
         const int64_t groups = static_cast<int64_t>(n_seq) * n_kv_heads * s.n_row_groups;
         const int64_t max_tiles = (len + OCTOPUS_TILE - 1) / OCTOPUS_TILE;
-        const int64_t slots = 256 * (plan.head_dim <= 64 ? 2 : 1);
+        const int64_t slots = (plan.head_dim <= 64 && s.rows_per_pass == 128) ? 512 : 256;
         // The workgroups run in rounds of `slots`; pick the split count (each split keeping at least 16
         // tiles) whose last round is fullest, the smallest such count on ties.
         int64_t best = 1;
@@ -283,8 +284,9 @@ Workspace make_workspace(const octopus_plan_t &plan, const DecodeShape &s) {
     auto up = [](size_t x) { return (x + 255) & ~static_cast<size_t>(255); };
     Workspace w{};
     const size_t rows = static_cast<size_t>(s.n_seq) * s.n_kv_heads * s.n_row_groups * s.rows_per_pass;
-    // partial results: one per (row, split) with 128-row blocks, else one per (item, wavefront, row of the group)
-    const size_t partials = s.rows_per_pass == 128 ? rows * s.n_splits
+    // partial results: one per (row, split) with blocks of 128 or 256 rows, else one per (item, wavefront, row of
+    // the group)
+    const size_t partials = s.rows_per_pass >= 128 ? rows * s.n_splits
                                                    : static_cast<size_t>(s.max_items) * 4 * s.rows_per_pass;
     w.q_rot_off = 0;
     const size_t q_bytes = up(rows * q_row_stride(plan.n_tri) * sizeof(float));

@@ -23,9 +23,9 @@ struct DecodeShape {
     int32_t n_seq, n_q_heads, n_kv_heads, n_q;
     int32_t heads_per_kv;   // n_q_heads / n_kv_heads
     int32_t rows_per_kv;    // n_q * heads_per_kv query rows sharing one KV head
-    int32_t rows_per_pass;  // query rows one workgroup scores per key (1, 2, 4 or 8; 128: matrix-core kernel)
+    int32_t rows_per_pass;  // query rows one workgroup scores per key (1, 2, 4 or 8; 128 or 256: many-row kernel)
     int32_t n_row_groups;   // ceil(rows_per_kv / rows_per_pass)
-    int32_t n_splits;       // wavefronts (workgroups at 128 rows) sharing the tiles of one (sequence, KV head, row group)
+    int32_t n_splits;       // wavefronts (workgroups of the many-row kernel) sharing the tiles of one (sequence, KV head, row group)
     int32_t max_items;      // bound of the work items the device cuts (row groups of at most 8)
     int32_t max_len;        // host-side bound of the sequence lengths
     int64_t t_capacity;
@@ -42,7 +42,7 @@ Workspace make_workspace(const octopus_plan_t &plan, const DecodeShape &s);
 
 // Kernel launchers (defined in the .hip files).  Each returns a hipError_t cast to int.
 // `work_plan`: device array the rotation kernel fills with the work items of the split-K kernel (NULL with
-// 128-row blocks, which are split on the host).  `q2` (NULL: not wanted): the queries rotated a second time
+// the many-row kernel, whose blocks are split on the host).  `q2` (NULL: not wanted): the queries rotated a second time
 // with `signs2` for the QJL residual, [padded row][head_dim].
 int launch_rotate_queries(const octopus_plan_t &plan, const void *q, int q_dtype, const uint8_t *signs,
                           const DecodeShape &s, float scale, float *q_rot, const int32_t *seq_lens,
