@@ -217,8 +217,16 @@ __global__ __launch_bounds__(kWave *NW) __attribute__((amdgpu_waves_per_eu(P::D 
     }
     __syncthreads();
 
+    // With 8 wavefronts (two per SIMD: w and w + 4) the upper four stage the next tile BEFORE they work on
+    // the current one, the lower four after: the two wavefronts of a SIMD are then in opposite phases, one
+    // on the matrix cores while the other decodes keys on the vector units.
+    const bool stage_first = NW == 8 && wave >= 4;
     for (int tile = tile_begin; tile < tile_end; ++tile) {
         const int buf = (tile - tile_begin) & 1;
+        if (stage_first && tile + 1 < tile_end) {
+            stage_tile(buf ^ 1);
+            load_tile(min(tile + 2, tile_end - 1));
+        }
         // S^T = K^ Q^T for the tile's two blocks of 32 keys
         f32x16_t sacc[2];
 #pragma unroll
@@ -290,7 +298,7 @@ __global__ __launch_bounds__(kWave *NW) __attribute__((amdgpu_waves_per_eu(P::D 
                 oacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.b, pl[g16].b, oacc[nb], 0, 0, 0);
             }
         // stage the next tile into the other buffer, request the one after
-        if (tile + 1 < tile_end) {
+        if (!stage_first && tile + 1 < tile_end) {
             stage_tile(buf ^ 1);
             load_tile(min(tile + 2, tile_end - 1));
         }
