@@ -25,6 +25,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+KERNEL_EVENT_STRIDE = 4        # every 4th timed step carries the event pair around the dominant kernel
 FP32_VALU_PEAK_TFLOPS = 157.3  # MI355X published fp32 vector peak
 BF16_MFMA_PEAK_TFLOPS = 2500.0 # MI355X published dense bf16 matrix peak
 
@@ -213,7 +214,7 @@ def main():
                          dtype=torch.uint8, device=dev)
         vals_tok = vals.permute(0, 2, 1, 3)[:, :wl.n_tokens]      # [n_seq, n_tokens, n_kv_heads, d] view
 
-    def step(ev=None):
+    def step(ev=None, kernel_events=False):
         if ev:
             ev[0].record()
         if args.vq:
@@ -226,7 +227,8 @@ def main():
             binding.octopus_encode(cb, keys[:, first:], sbits, cache, cap, start_dev)
         if ev:
             ev[1].record()
-            binding.octopus_profile_events(ev[3], ev[4])  # around the fused kernel inside the next call
+            if kernel_events:
+                binding.octopus_profile_events(ev[3], ev[4])  # around the fused kernel inside the next call
         if args.qjl:
             binding.octopus_attn_decode_qjl(cb, q, sbits, s2bits, cache, side, cap, vals, lens_dev, max_len, scale, out, ws)
         elif args.window:
@@ -249,13 +251,19 @@ def main():
         ev[4].record()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    # The pair of events around the kernel sits between the call's launches and costs the call about 7 us
+    # (measured: 0.2658 ms with it on every step, 0.2584 ms without).  Every KERNEL_EVENT_STRIDE-th step of the
+    # timed region carries it; the call time is taken over the other steps (over all of them when there are
+    # no others), the kernel time over those that carry it.
+    with_kernel_events = np.array([i % KERNEL_EVENT_STRIDE == 0 for i in range(args.steps)])
     for i in range(args.steps):
-        step(events[i])
+        step(events[i], bool(with_kernel_events[i]))
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     enc_ms = np.array([e[0].elapsed_time(e[1]) for e in events])
-    dec_ms = np.array([e[1].elapsed_time(e[2]) for e in events])
-    ker_ms = np.array([e[3].elapsed_time(e[4]) for e in events])
+    dec_ms_all = np.array([e[1].elapsed_time(e[2]) for e in events])
+    dec_ms = dec_ms_all[~with_kernel_events] if (~with_kernel_events).any() else dec_ms_all
+    ker_ms = np.array([e[3].elapsed_time(e[4]) for e, k in zip(events, with_kernel_events) if k])
     assert bool(torch.isfinite(out).all())
 
     elt = 2 if wl.dtype == "bf16" else 4
@@ -305,12 +313,15 @@ def main():
         "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
         "decode_ms": round(dec_s * 1e3, 4),
         "decode_ms_median": round(float(np.median(dec_ms)), 4),
+        "decode_ms_steps_with_kernel_events": round(float(dec_ms_all[with_kernel_events].mean()), 4),
+        "kernel_event_steps": int(with_kernel_events.sum()),
         "encode_ms": round(enc_s * 1e3, 4),
         "encode_mtokens_per_s": round(wl.n_seq * n_new / enc_s / 1e6, 3),
         "encode_mkeys_per_s": round(n_keys_enc / enc_s / 1e6, 3),
         "roofline": {
             "kernel": "decode_kernel_mfma (the fused split-K decode kernel inside octopus_attn_decode), timed "
-                      "with HIP events recorded by the library around its launch on the launch stream",
+                      "with HIP events recorded by the library around its launch on the launch stream, on every "
+                      f"{KERNEL_EVENT_STRIDE}th step of the timed region",
             "bound": "hbm",
             "achieved": round(ker_gbs, 2),
             "peak": HBM_PEAK_GBS,
