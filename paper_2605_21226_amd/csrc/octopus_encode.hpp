@@ -255,6 +255,32 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
     const uint32_t sbits = signs[kvh * (D / 8) + col / 8];
     uint4 *region = cache + (static_cast<int64_t>(seq) * n_kv_heads + kvh) * (t_capacity * P::GRANULES);
 
+    // A tile's key rows as loaded: 8 coordinates per thread and pass (bf16: one 16-byte word; fp32: two);
+    // rows outside [start, tok_end) and tiles past the group's last one read as zeros.  The next tile's rows
+    // are requested as soon as the current ones sit in LDS, so that they arrive during its transform and
+    // triplet phases.
+    constexpr int NPASS = kWave / RPP;
+    uint4 raw[NPASS][BF16 ? 1 : 2];
+    auto fetch_tile = [&](int64_t tile) {
+#pragma unroll
+        for (int pass = 0; pass < NPASS; ++pass) {
+            const int64_t tok = tile * kWave + pass * RPP + tid / LPR;
+            const bool valid = tok >= start && tok < tok_end;
+#pragma unroll
+            for (int h = 0; h < (BF16 ? 1 : 2); ++h) raw[pass][h] = make_uint4(0u, 0u, 0u, 0u);
+            if (valid) {
+                const int64_t off = head_base + (tok - start) * stride_tok + col;
+                if constexpr (BF16) {
+                    raw[pass][0] = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(keys) + off);
+                } else {
+                    raw[pass][0] = *reinterpret_cast<const uint4 *>(static_cast<const float *>(keys) + off);
+                    raw[pass][BF16 ? 0 : 1] = *reinterpret_cast<const uint4 *>(static_cast<const float *>(keys) + off + 4);
+                }
+            }
+        }
+    };
+    fetch_tile(first_tile);
+
     for (int tg = 0; tg < kEncodeTilesPerGroup; ++tg) {
         const int64_t tile = first_tile + tg;
         const int64_t tok_lo = max(tile * kWave, start);
@@ -264,26 +290,20 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
         // word 0 (gamma) is written whole by the load phase below; the code words are OR-ed into
         for (int e = kWave + tid; e < P::NWORDS * kWave; e += 256) sm.rec[e / kWave][e % kWave] = 0u;
 
-        // E1-E2: load, squared norm, sign flip
+        // E1-E2: squared norm, sign flip
 #pragma unroll
-        for (int pass = 0; pass < kWave / RPP; ++pass) {
+        for (int pass = 0; pass < NPASS; ++pass) {
             const int key = pass * RPP + tid / LPR;
-            const int64_t tok = tile * kWave + key;
-            const bool valid = tok >= tok_lo && tok < tok_hi;
             float x[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) x[e] = 0.0f;
-            if (valid) {
-                const int64_t off = head_base + (tok - start) * stride_tok + col;
-                if constexpr (BF16) {
-                    const uint4 r = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(keys) + off);
-                    x[0] = bf16_lo(r.x); x[1] = bf16_hi(r.x); x[2] = bf16_lo(r.y); x[3] = bf16_hi(r.y);
-                    x[4] = bf16_lo(r.z); x[5] = bf16_hi(r.z); x[6] = bf16_lo(r.w); x[7] = bf16_hi(r.w);
-                } else {
-                    const float4 a = *reinterpret_cast<const float4 *>(static_cast<const float *>(keys) + off);
-                    const float4 b = *reinterpret_cast<const float4 *>(static_cast<const float *>(keys) + off + 4);
-                    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
-                }
+            if constexpr (BF16) {
+                const uint4 r = raw[pass][0];
+                x[0] = bf16_lo(r.x); x[1] = bf16_hi(r.x); x[2] = bf16_lo(r.y); x[3] = bf16_hi(r.y);
+                x[4] = bf16_lo(r.z); x[5] = bf16_hi(r.z); x[6] = bf16_lo(r.w); x[7] = bf16_hi(r.w);
+            } else {
+                const uint4 a = raw[pass][0], b = raw[pass][BF16 ? 0 : 1];
+                x[0] = __uint_as_float(a.x); x[1] = __uint_as_float(a.y); x[2] = __uint_as_float(a.z);
+                x[3] = __uint_as_float(a.w); x[4] = __uint_as_float(b.x); x[5] = __uint_as_float(b.y);
+                x[6] = __uint_as_float(b.z); x[7] = __uint_as_float(b.w);
             }
             float ss = 0.0f;
 #pragma unroll
@@ -298,6 +318,7 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
                 sm.inv_norm[key] = (1.0f / fmaxf(gamma, kEps)) * inv_sqrt_dim<D>();
             }
         }
+        if (tg + 1 < kEncodeTilesPerGroup) fetch_tile(tile + 1);
         __syncthreads();
 
         // E3: Walsh-Hadamard transform, one key per lane, two radix passes through LDS
