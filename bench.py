@@ -50,6 +50,9 @@ def parse():
     ap.add_argument("--qjl", action="store_true",
                     help="time the variant with the 1-bit QJL residual (octopus_encode_qjl + octopus_attn_decode_qjl); "
                          "single-query workloads only")
+    ap.add_argument("--paged", action="store_true",
+                    help="paged cache: 64-token pages handed out in a random order from pools (octopus_encode_paged + "
+                         "octopus_attn_decode_paged); single-query bf16 workloads, plain variant only")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy (torch) three times, so that a rocprofv3 "
                          "--pmc run of this command can scale FETCH_SIZE / WRITE_SIZE by a kernel of known size")
@@ -161,6 +164,9 @@ def main():
     if args.window and (many_rows or args.qjl or args.vq):
         print("bench.py: --window times single-query workloads of the plain variant", file=sys.stderr)
         sys.exit(2)
+    if args.paged and (many_rows or args.qjl or args.vq or args.window or args.rounding != 1 or wl.dtype != "bf16"):
+        print("bench.py: --paged times single-query bf16 workloads of the plain variant", file=sys.stderr)
+        sys.exit(2)
     if args.qjl and args.rounding != 1:
         print("bench.py: --qjl goes with the default rounding", file=sys.stderr)
         sys.exit(2)
@@ -214,6 +220,17 @@ def main():
                          dtype=torch.uint8, device=dev)
         vals_tok = vals.permute(0, 2, 1, 3)[:, :wl.n_tokens]      # [n_seq, n_tokens, n_kv_heads, d] view
 
+    table = k_pool = v_pool = None
+    if args.paged:
+        tiles = cap // 64
+        n_pages = wl.n_seq * tiles + 7
+        gen = torch.Generator(device="cpu").manual_seed(args.seed + 5)
+        table = torch.randperm(n_pages, generator=gen)[:wl.n_seq * tiles].to(torch.int32).reshape(wl.n_seq, tiles).to(dev)
+        k_pool = torch.zeros(binding.octopus_paged_pool_bytes(cb, n_pages, wl.n_kv_heads), dtype=torch.uint8, device=dev)
+        v_pool = torch.zeros((n_pages, wl.n_kv_heads, 64, wl.head_dim), dtype=vals.dtype, device=dev)
+        v_pool[table.reshape(-1).long()] = (vals.reshape(wl.n_seq, wl.n_kv_heads, tiles, 64, wl.head_dim)
+                                            .permute(0, 2, 1, 3, 4).reshape(-1, wl.n_kv_heads, 64, wl.head_dim))
+
     def step(ev=None, kernel_events=False):
         if ev:
             ev[0].record()
@@ -221,6 +238,8 @@ def main():
             binding.octopus_encode_values(vals_tok, v_bits, v_group, vq, cap)
         if args.qjl:
             binding.octopus_encode_qjl(cb, keys[:, first:], sbits, s2bits, cache, side, cap, start_dev)
+        elif args.paged:
+            binding.octopus_encode_paged(cb, keys, sbits, k_pool, n_pages, table)
         elif args.rounding != 1:
             binding.octopus_encode_rounding(cb, keys[:, first:], sbits, cache, cap, args.rounding, start_dev)
         else:
@@ -237,6 +256,8 @@ def main():
         elif args.vq:
             binding.octopus_attn_decode_vq(cb, q, sbits, cache, cap, vq, v_bits, v_group, wl.n_kv_heads, lens_dev, max_len,
                                            scale, out, ws)
+        elif args.paged:
+            binding.octopus_attn_decode_paged(cb, q, sbits, k_pool, v_pool, table, lens_dev, max_len, scale, out, ws)
         else:
             binding.octopus_attn_decode(cb, q, sbits, cache, cap, vals, lens_dev, max_len, scale, out, ws)
         if ev:
@@ -297,7 +318,8 @@ def main():
         "data": "synthetic",
         "config": {
             "workload": f"{wl.name}{' + QJL residual' if args.qjl else ''}"
-                        f"{f' + values quantised to {v_bits} bits in groups of {v_group}' if args.vq else ''}: batch {wl.n_seq}, {wl.n_q_heads} query / {wl.n_kv_heads} KV heads, head_dim "
+                        f"{f' + values quantised to {v_bits} bits in groups of {v_group}' if args.vq else ''}"
+                        f"{' + paged cache (64-token pages in random order)' if args.paged else ''}: batch {wl.n_seq}, {wl.n_q_heads} query / {wl.n_kv_heads} KV heads, head_dim "
                         f"{wl.head_dim}, {wl.n_tokens} cached tokens, {wl.dtype} K/V/Q, {wl.bits:g} bits/coordinate "
                         f"(b_dir {cb.plan.b_dir[0]}, b_nrm {cb.plan.b_nrm[0]}); step = encode of "
                         f"{wl.n_seq * n_new} tokens + one decode-attention call"
@@ -335,7 +357,7 @@ def main():
     uses_mq = (many_rows and wl.head_dim <= 128 and wl.n_q * (wl.n_q_heads // wl.n_kv_heads) >= 32 and
                wl.dtype == "bf16")
     dominant = "decode_kernel_valu" if args.vq else ("decode_kernel_mq" if uses_mq else "decode_kernel_mfma")
-    result["roofline"]["traffic"] = None if args.window else measured_traffic(
+    result["roofline"]["traffic"] = None if (args.window or args.paged) else measured_traffic(
         wl.name + ("_qjl" if args.qjl else "") + (f"_vq{v_bits}g{v_group}" if args.vq else ""), dominant)
     if args.vq:
         result["roofline"]["kernel"] = result["roofline"]["kernel"].replace("decode_kernel_mfma", "decode_kernel_valu")

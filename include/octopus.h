@@ -11,6 +11,7 @@
  *   octopus_encode_qjl, octopus_attn_decode_qjl    the 1-bit QJL residual (Sec. 3.6)
  *   octopus_encode_values, octopus_attn_decode_vq  group-quantised values (Sec. 4, Alg. 2)
  *   octopus_attn_decode_hybrid                     native-precision window (Sec. 4)
+ *   octopus_encode_paged, octopus_attn_decode_paged  the same codec and attention over a paged cache
  *
  * Conventions
  *   - Plain C.  Every function returns 0 (OCTOPUS_OK) or a negative error
@@ -334,6 +335,50 @@ int octopus_attn_decode_vq(const octopus_codebooks_t *cb,
 int octopus_profile_events(void *before, void *after);
 
 /* Static, human-readable name of an error code. */
+/* ---- paged cache (an integration layout; the paper's Sec. 4 recipe leaves the cache's storage open) ----
+ * The cache of a sequence need not be contiguous: tokens live in pages of 64 (one tile of the layout
+ * above), handed out from pools shared by all sequences, and a block table maps a sequence's logical
+ * tile j to its page.  Codes, records and attention are exactly those of octopus_encode /
+ * octopus_attn_decode (Alg. 1, Alg. 2); only addresses differ.
+ *   k_pool       device, 16-byte aligned: [n_pages][n_kv_heads] key tiles, each the 64-token tile of
+ *                the compressed cache layout (granules * 64 * 16 bytes; octopus_paged_pool_bytes).
+ *   v_pool       device, 16-byte aligned, bf16: [n_pages][n_kv_heads][64][d] value rows, written by
+ *                the caller (token t of a sequence is row t % 64 of page block_table[s][t / 64]).
+ *   block_table  device int32 [n_seq][max_pages_per_seq]; entry [s][j] is the page of tokens
+ *                64 j .. 64 j + 63 of sequence s.  Only entries below ceil(len / 64) are read.  Ids
+ *                are clamped to [0, n_pages): a wrong table yields wrong results, never an access
+ *                outside the pools.  Two sequences may share a page (a common prefix).
+ * octopus_encode_paged: arguments as octopus_encode with (cache, t_capacity) replaced by the pool and
+ * the table; a sequence can hold max_pages_per_seq * 64 tokens, tokens past that are dropped.
+ * octopus_attn_decode_paged: arguments as octopus_attn_decode (bf16 values only, no scores_out);
+ * max_len <= max_pages_per_seq * 64; query rows are served in groups of at most 8 per KV head (the
+ * many-row kernel is not built for pages).  Workspace: octopus_attn_decode_workspace of the same
+ * shapes.  Errors: EINVAL for NULL / misaligned pointers, n_pages < 1, max_pages_per_seq < 1 and the
+ * conditions of the contiguous calls; EUNSUPPORTED / EWORKSPACE / EHIP as there. */
+size_t octopus_paged_pool_bytes(const octopus_codebooks_t *cb, int32_t n_pages, int32_t n_kv_heads);
+
+int octopus_encode_paged(const octopus_codebooks_t *cb,
+                         const void *keys, int32_t key_dtype,
+                         int64_t stride_seq, int64_t stride_tok, int64_t stride_head,
+                         int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
+                         const uint8_t *signs,
+                         void *k_pool, int32_t n_pages,
+                         const int32_t *block_table, int32_t max_pages_per_seq,
+                         const int32_t *start_pos,
+                         void *stream);
+
+int octopus_attn_decode_paged(const octopus_codebooks_t *cb,
+                              const void *q, int32_t q_dtype,
+                              int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q,
+                              const uint8_t *signs,
+                              const void *k_pool, const void *v_pool, int32_t n_pages,
+                              const int32_t *block_table, int32_t max_pages_per_seq,
+                              const int32_t *seq_lens, int64_t max_len,
+                              float scale,
+                              float *out,
+                              void *workspace, size_t workspace_bytes,
+                              void *stream);
+
 const char *octopus_strerror(int code);
 
 #ifdef __cplusplus

@@ -21,7 +21,8 @@ EXPORTS = ("octopus_build_codebooks", "octopus_build_codebooks_pair", "octopus_c
            "octopus_attn_decode_workspace", "octopus_attn_decode", "octopus_profile_events", "octopus_strerror",
            "octopus_qjl_bytes", "octopus_encode_qjl", "octopus_attn_decode_qjl",
            "octopus_encode_rounding", "octopus_vq_row_bytes", "octopus_vq_bytes", "octopus_encode_values",
-           "octopus_attn_decode_vq", "octopus_attn_decode_hybrid")
+           "octopus_attn_decode_vq", "octopus_attn_decode_hybrid",
+           "octopus_paged_pool_bytes", "octopus_encode_paged", "octopus_attn_decode_paged")
 
 
 class Plan(ctypes.Structure):
@@ -107,6 +108,13 @@ def load():
     lib.octopus_attn_decode_hybrid.argtypes = [CB, vp, i32, i32, i32, i32, i32, vp, vp, i64, vp, i32, vp, i64, vp, i32,
                                                i64, vp, f32, vp, vp, vp, ctypes.c_size_t, vp]
     lib.octopus_attn_decode_hybrid.restype = ctypes.c_int
+    lib.octopus_paged_pool_bytes.argtypes = [CB, i32, i32]
+    lib.octopus_paged_pool_bytes.restype = ctypes.c_size_t
+    lib.octopus_encode_paged.argtypes = [CB, vp, i32, i64, i64, i64, i32, i32, i32, vp, vp, i32, vp, i32, vp, vp]
+    lib.octopus_encode_paged.restype = ctypes.c_int
+    lib.octopus_attn_decode_paged.argtypes = [CB, vp, i32, i32, i32, i32, i32, vp, vp, vp, i32, vp, i32, vp, i64, f32,
+                                              vp, vp, ctypes.c_size_t, vp]
+    lib.octopus_attn_decode_paged.restype = ctypes.c_int
     lib.octopus_profile_events.argtypes = [vp, vp]
     lib.octopus_profile_events.restype = ctypes.c_int
     lib.octopus_strerror.argtypes = [ctypes.c_int]
@@ -282,6 +290,38 @@ def octopus_attn_decode_hybrid(cb, q, signs, cache, t_capacity, v, seq_lens, max
                                              _ptr(scores_out), _ptr(workspace),
                                              int(workspace.numel() * workspace.element_size()), _stream_ptr(stream))
     _check(code, "octopus_attn_decode_hybrid")
+
+
+def octopus_paged_pool_bytes(cb, n_pages, n_kv_heads):
+    return int(load().octopus_paged_pool_bytes(ctypes.byref(cb), int(n_pages), int(n_kv_heads)))
+
+
+def octopus_encode_paged(cb, keys, signs, k_pool, n_pages, block_table, start_pos=None, stream=None):
+    """octopus_encode into a paged cache: k_pool device uint8 buffer of octopus_paged_pool_bytes(...) bytes,
+    block_table device int32 [n_seq, max_pages_per_seq] contiguous."""
+    assert keys.dim() == 4 and keys.stride(3) == 1 and block_table.is_contiguous()
+    n_seq, n_new, n_kv, _ = keys.shape
+    assert block_table.shape[0] == n_seq
+    code = load().octopus_encode_paged(ctypes.byref(cb), _ptr(keys), _dtype_code(keys), keys.stride(0), keys.stride(1),
+                                       keys.stride(2), n_seq, n_kv, n_new, _ptr(signs), _ptr(k_pool), int(n_pages),
+                                       _ptr(block_table), int(block_table.shape[1]), _ptr(start_pos),
+                                       _stream_ptr(stream))
+    _check(code, "octopus_encode_paged")
+
+
+def octopus_attn_decode_paged(cb, q, signs, k_pool, v_pool, block_table, seq_lens, max_len, scale, out, workspace,
+                              stream=None):
+    """octopus_attn_decode over a paged cache: v_pool device bf16 [n_pages, n_kv_heads, 64, d] contiguous."""
+    assert q.is_contiguous() and v_pool.is_contiguous() and out.is_contiguous() and block_table.is_contiguous()
+    n_seq, n_q, n_qh, _ = q.shape
+    n_pages, n_kv = v_pool.shape[0], v_pool.shape[1]
+    assert block_table.shape[0] == n_seq and v_pool.shape[2] == 64 and _dtype_code(v_pool) == DTYPE_BF16
+    code = load().octopus_attn_decode_paged(ctypes.byref(cb), _ptr(q), _dtype_code(q), n_seq, n_qh, n_kv, n_q,
+                                            _ptr(signs), _ptr(k_pool), _ptr(v_pool), int(n_pages), _ptr(block_table),
+                                            int(block_table.shape[1]), _ptr(seq_lens), int(max_len), float(scale),
+                                            _ptr(out), _ptr(workspace),
+                                            int(workspace.numel() * workspace.element_size()), _stream_ptr(stream))
+    _check(code, "octopus_attn_decode_paged")
 
 
 def octopus_profile_events(before, after):

@@ -16,8 +16,8 @@ LIB = os.environ.get("OCTOPUS_LIB_OUT", os.path.join(HERE, "liboctopus.so"))
 # the slowest (d = 256, then the matrix-core decode kernels) first
 SOURCES = []
 for _d in ("256", "128", "64"):
-    SOURCES += [_family + _d + ".hip" for _family in ("octopus_d", "octopus_scores_d", "octopus_vq_d", "octopus_valu_d", "octopus_qjl_d",
-                                                      "octopus_enc_d", "octopus_round_d")]
+    SOURCES += [_family + _d + ".hip" for _family in ("octopus_d", "octopus_paged_d", "octopus_scores_d", "octopus_vq_d", "octopus_valu_d",
+                                                      "octopus_qjl_d", "octopus_enc_d", "octopus_round_d")]
 SOURCES += ["octopus_common.hip", "octopus_values.hip", "octopus_host.cpp"]
 # -packed-fp32-ops is switched off on purpose: hipcc must not form packed fp32 instructions here.
 FLAGS = (["-D" + d for d in os.environ.get("OCTOPUS_DEFS", "").split(",") if d]) + ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,

@@ -27,7 +27,13 @@ bool plan_supported_d256(const octopus_plan_t &);
                               void *);                                                                             \
     int launch_encode_rounding_d##D(const octopus_codebooks_t &, const void *, int, int64_t, int64_t, int64_t,     \
                                     int32_t, int32_t, int32_t, const uint8_t *, void *, int64_t, const int32_t *,  \
-                                    int32_t, void *);
+                                    int32_t, void *);                                                              \
+    int launch_decode_paged_d##D(const octopus_codebooks_t &, const DecodeShape &, const float *, const void *,    \
+                                 const void *, const PageTable &, const int32_t *, float *, float *, int32_t *,    \
+                                 void *);                                                                          \
+    int launch_encode_paged_d##D(const octopus_codebooks_t &, const void *, int, int64_t, int64_t, int64_t,        \
+                                 int32_t, int32_t, int32_t, const uint8_t *, void *, const PageTable &,            \
+                                 const int32_t *, void *);
 OCTOPUS_DECL(64)
 OCTOPUS_DECL(128)
 OCTOPUS_DECL(256)
@@ -107,6 +113,29 @@ int launch_encode(const octopus_codebooks_t &cb, const void *keys, int key_dtype
         case 64: return launch_encode_d64(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs, cache, t_capacity, start_pos, signs2, qjl, stream);
         case 128: return launch_encode_d128(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs, cache, t_capacity, start_pos, signs2, qjl, stream);
         case 256: return launch_encode_d256(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs, cache, t_capacity, start_pos, signs2, qjl, stream);
+        default: return static_cast<int>(hipErrorInvalidValue);
+    }
+}
+
+int launch_decode_paged(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *k_pool,
+                        const void *v_pool, const PageTable &pt, const int32_t *seq_lens, float *part_ml,
+                        float *part_acc, int32_t *work_plan, void *stream) {
+    switch (cb.plan.head_dim) {
+        case 64: return launch_decode_paged_d64(cb, s, q_rot, k_pool, v_pool, pt, seq_lens, part_ml, part_acc, work_plan, stream);
+        case 128: return launch_decode_paged_d128(cb, s, q_rot, k_pool, v_pool, pt, seq_lens, part_ml, part_acc, work_plan, stream);
+        case 256: return launch_decode_paged_d256(cb, s, q_rot, k_pool, v_pool, pt, seq_lens, part_ml, part_acc, work_plan, stream);
+        default: return static_cast<int>(hipErrorInvalidValue);
+    }
+}
+
+int launch_encode_paged(const octopus_codebooks_t &cb, const void *keys, int key_dtype, int64_t stride_seq,
+                        int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
+                        const uint8_t *signs, void *k_pool, const PageTable &pt, const int32_t *start_pos,
+                        void *stream) {
+    switch (cb.plan.head_dim) {
+        case 64: return launch_encode_paged_d64(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs, k_pool, pt, start_pos, stream);
+        case 128: return launch_encode_paged_d128(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs, k_pool, pt, start_pos, stream);
+        case 256: return launch_encode_paged_d256(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs, k_pool, pt, start_pos, stream);
         default: return static_cast<int>(hipErrorInvalidValue);
     }
 }

@@ -585,12 +585,19 @@ constexpr bool qjl_fits() {
 // the addressing state of that store through its loop).
 // QJL: add the 1-bit QJL residual correction of Sec. 3.6 to every score (side-car `qjl`, second rotated
 // queries `q2`).
-template <class P, int RG, bool SCORES, bool QJL>
+// PAGED: `cache` and `v` are pools of 64-token pages, [page][KV head] tiles each (a key tile in the device
+// layout of the contiguous cache, a value tile of 64 rows), and logical tile j of sequence s lives in page
+// pt_table[s * pt_stride + j] (ids outside [0, pt_pages) are clamped: a bad table reads wrong pages, never
+// outside the pools).  The page ids of a step are read one step before its loads are issued.
+template <class P, int RG, bool SCORES, bool QJL, bool PAGED = false>
 __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) void decode_kernel_mfma(
     DeviceBooks books, DecodeShape shp, const float *__restrict__ q_rot, const uint4 *__restrict__ cache,
     const uint32_t *__restrict__ v, const int32_t *__restrict__ seq_lens, float *__restrict__ part_ml,
     float *__restrict__ part_acc, float *__restrict__ scores_out, int32_t *__restrict__ plan,
-    const unsigned char *__restrict__ qjl, const float *__restrict__ q2) {
+    const unsigned char *__restrict__ qjl, const float *__restrict__ q2, const int32_t *__restrict__ pt_table,
+    int32_t pt_stride, int32_t pt_pages) {
+    // (the table as a restrict-qualified kernel argument of its own: its loads are then known not to be
+    // clobbered by the kernel's stores and become scalar loads)
     constexpr int D = P::D;
     constexpr int KPL = decode_keys_per_lane<D>();
     constexpr bool AHEAD = D <= 128;       // request a step's values during the previous step's P.V
@@ -634,11 +641,11 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
 
     // Only the words that hold record bytes are loaded: a register written by a load but never read
     // may be reused at once by the compiler, which then has to wait for that load first.
-    auto load_record = [&](int tile, uint32_t (&w)[P::NWORDS]) {
+    auto load_record = [&](int64_t tile, uint32_t (&w)[P::NWORDS]) {
         typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
         typedef uint32_t u32x3_t __attribute__((ext_vector_type(3)));
         constexpr int USED = (P::RECORD_BYTES + 3) / 4;
-        const char *src = k_region + static_cast<int64_t>(tile) * TILEB;
+        const char *src = k_region + tile * TILEB;
 #pragma unroll
         for (int g = 0; g < P::GRANULES; ++g) {
             const char *gp = src + g * (kWave * 16) + k_lane;
@@ -665,6 +672,27 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
 #pragma unroll
         for (int k = 0; k < KPL; ++k) load_record(min(step * KPL + k, ww.n_tiles - 1), w[k]);
     };
+    // PAGED: the page ids of the tiles of a step (the last tile's for tiles past it) are read as they are, one
+    // step ahead; the position in the pools (in tiles) is computed from them when the step's loads are issued,
+    // so that nothing waits for the table right after asking it.
+    auto page_ids = [&](int step, int (&page)[KPL]) {
+#pragma unroll
+        for (int k = 0; k < KPL; ++k) {
+            const int tile = max(min(step * KPL + k, ww.n_tiles - 1), 0);
+            page[k] = pt_table[static_cast<int64_t>(ww.seq) * pt_stride + tile];
+        }
+    };
+    auto page_slots = [&](const int (&page)[KPL], int64_t (&slot)[KPL]) {
+#pragma unroll
+        for (int k = 0; k < KPL; ++k)
+            slot[k] = static_cast<int64_t>(min(max(page[k], 0), pt_pages - 1)) * shp.n_kv_heads + ww.kvh;
+    };
+    auto load_records_at = [&](const int64_t (&slot)[KPL], uint32_t (&w)[KPL][P::NWORDS]) {
+#pragma unroll
+        for (int k = 0; k < KPL; ++k) load_record(slot[k], w[k]);
+    };
+    int64_t slot_cur[KPL];   // PAGED: pool positions of the step being worked on
+    int page_nxt[KPL];       // PAGED: page ids of the wave's next step
     // QJL side-car of a step: per key d / 32 words of sign bits (bit set: negative) and the fp16 residual
     // norm; tile layout [word][key] then [key].
     const char *j_region = reinterpret_cast<const char *>(qjl);
@@ -714,6 +742,21 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
         return __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(v_pair + static_cast<int64_t>(t0) * ROWB), 0,
                                                  n_valid * ROWB, 0x00020000);
     };
+    // PAGED: tile k of a step has a descriptor of its own.  The lanes address rows relative to the step's
+    // first row, so the descriptor starts 64 k rows before the tile (nothing below the tile is addressed
+    // through it) and ends with the tile's last token.
+    auto values_at = [&](int step, int k, int64_t slot, bool exists) {
+        // (wave-uniform by construction; said so explicitly, or the descriptor may end up in vector registers
+        // and every load through it in a loop over its distinct values)
+        const int n_valid =
+            __builtin_amdgcn_readfirstlane(exists ? min(max(ww.len - (step * KPL + k) * kWave, 0), kWave) : 0);
+        const int64_t off = (slot - k) * (kWave * ROWB);
+        const uint32_t off_lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(off));
+        const uint32_t off_hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(static_cast<uint64_t>(off) >> 32));
+        const char *base = v_pair + static_cast<int64_t>((static_cast<uint64_t>(off_hi) << 32) | off_lo);
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(base), 0,
+                                                 n_valid > 0 ? (k * kWave + n_valid) * ROWB : 0, 0x00020000);
+    };
     // this lane's part of k-step ks: 8 rows x CPL channels
     auto load_values = [&](__amdgpu_buffer_rsrc_t rsrc, int ks, uint32_t (&vk)[8][CW]) {
         typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
@@ -750,13 +793,29 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
         // always issued (the wave's last step re-reads its own records, and requests values through an
         // empty descriptor): a branch here would make the compiler wait for every outstanding load first
         const bool has_next = step + ww.step_stride < ww.step_end;
-        const __amdgpu_buffer_rsrc_t v_next =
-            AHEAD ? values_of(has_next ? step + ww.step_stride : step, has_next) : values_of(step, true);
+        const int step_nx = min(step + ww.step_stride, ww.step_last);
+        __amdgpu_buffer_rsrc_t v_next[KPL];   // per tile of the step (all the same unless PAGED)
+        int64_t slot_nxt[KPL];
+        if constexpr (PAGED) page_slots(page_nxt, slot_nxt);
+#pragma unroll
+        for (int k = 0; k < KPL; ++k) {
+            if constexpr (PAGED)
+                v_next[k] = AHEAD ? values_at(step_nx, k, slot_nxt[k], has_next) : values_at(step, k, slot_cur[k], true);
+            else
+                v_next[k] = AHEAD ? values_of(has_next ? step + ww.step_stride : step, has_next) : values_of(step, true);
+        }
         if constexpr (!AHEAD) {   // d = 256: the registers hold one step's values only while it is worked on
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) load_values(v_next, ks, vr[ks]);
+            for (int ks = 0; ks < KS; ++ks) load_values(v_next[ks / 2], ks, vr[ks]);
         }
-        load_records(min(step + ww.step_stride, ww.step_last), w_next);
+        if constexpr (PAGED) {
+            load_records_at(slot_nxt, w_next);
+#pragma unroll
+            for (int k = 0; k < KPL; ++k) slot_cur[k] = slot_nxt[k];
+            page_ids(min(step_nx + ww.step_stride, ww.step_last), page_nxt);   // used one step from here
+        } else {
+            load_records(step_nx, w_next);
+        }
         if constexpr (QJL) load_sidecar(min(step + ww.step_stride, ww.step_last), sc_next);
         // D2-D4: scores (queries carry the softmax scale already).  The query offset (always 0) is
         // laundered per step: otherwise the loop-invariant scalar loads of the whole query are hoisted
@@ -834,7 +893,7 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
                 for (int jj = 0; jj < 4; ++jj)
                     vb[c].u[jj] = __builtin_amdgcn_perm(vr[ks][2 * jj + 1][c / 2], vr[ks][2 * jj][c / 2],
                                                         (c & 1) ? 0x07060302u : 0x05040100u);
-            if constexpr (AHEAD) load_values(v_next, ks, vr[ks]);
+            if constexpr (AHEAD) load_values(v_next[ks / 2], ks, vr[ks]);
 #pragma unroll
             for (int c = 0; c < CPL; ++c)
                 acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa.b, vb[c].b, acc[c], 0, 0, 0);
@@ -868,20 +927,36 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
             j_region = reinterpret_cast<const char *>(qjl) + ww.pair * (shp.t_capacity / kWave) * TQ;
         }
         // Addresses are a wave-uniform base (scalar registers) plus a small per-lane byte offset.
-        k_region = reinterpret_cast<const char *>(cache) + ww.pair * shp.t_capacity * (P::GRANULES * 16);
-        v_pair = reinterpret_cast<const char *>(v) + ww.pair * shp.t_capacity * ROWB;
+        if constexpr (PAGED) {
+            k_region = reinterpret_cast<const char *>(cache);
+            v_pair = reinterpret_cast<const char *>(v);
+        } else {
+            k_region = reinterpret_cast<const char *>(cache) + ww.pair * shp.t_capacity * (P::GRANULES * 16);
+            v_pair = reinterpret_cast<const char *>(v) + ww.pair * shp.t_capacity * ROWB;
+        }
 #pragma unroll
         for (int r = 0; r < RG; ++r) { m_run[r] = -INFINITY; l_lane[r] = 0.0f; }
 #pragma unroll
         for (int c = 0; c < CPL; ++c) acc[c] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
 
         if (ww.step_begin < ww.step_end) {
-            load_records(ww.step_begin, w_a);
+            if constexpr (PAGED) {
+                int page_first[KPL];
+                page_ids(ww.step_begin, page_first);
+                page_ids(min(ww.step_begin + ww.step_stride, ww.step_last), page_nxt);
+                page_slots(page_first, slot_cur);
+                load_records_at(slot_cur, w_a);
+            } else {
+                load_records(ww.step_begin, w_a);
+            }
             if constexpr (QJL) load_sidecar(ww.step_begin, sc_a);
             if constexpr (AHEAD) {
-                const __amdgpu_buffer_rsrc_t v_first = values_of(ww.step_begin, true);
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) load_values(v_first, ks, vr[ks]);
+                for (int ks = 0; ks < KS; ++ks) {
+                    const __amdgpu_buffer_rsrc_t v_first =
+                        PAGED ? values_at(ww.step_begin, ks / 2, slot_cur[ks / 2], true) : values_of(ww.step_begin, true);
+                    load_values(v_first, ks, vr[ks]);
+                }
             }
         }
         if (!tables_built) {   // workgroup-uniform
@@ -1188,8 +1263,38 @@ int launch_decode_mfma_rg(const octopus_codebooks_t &cb, const DecodeShape &s, c
     // one workgroup per compute unit; they share the items of the plan
     hipLaunchKernelGGL((decode_kernel_mfma<P, RG, SCORES, false>), dim3(kDecodeWorkgroups), dim3(kDecodeWaves * kWave),
                        0, stream, books, s, q_rot, static_cast<const uint4 *>(cache), static_cast<const uint32_t *>(v),
-                       seq_lens, part_ml, part_acc, scores_out, plan, nullptr, nullptr);
+                       seq_lens, part_ml, part_acc, scores_out, plan, nullptr, nullptr, nullptr, 0, 0);
     return static_cast<int>(hipGetLastError());
+}
+
+// Paged pools (bf16 values, row groups of at most 8 rows).
+template <class P, int RG>
+int launch_decode_paged_rg(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *k_pool,
+                           const void *v_pool, const PageTable &pt, const int32_t *seq_lens, float *part_ml,
+                           float *part_acc, int32_t *plan, hipStream_t stream) {
+    DeviceBooks books;
+    for (int c = 0; c < 2; ++c) {
+        for (int k = 0; k < 32; ++k) books.c_xi[c][k] = cb.c_xi[c][k];
+        for (int k = 0; k < 8; ++k) books.c_rho[c][k] = cb.c_rho[c][k];
+    }
+    hipLaunchKernelGGL((decode_kernel_mfma<P, RG, false, false, true>), dim3(kDecodeWorkgroups),
+                       dim3(kDecodeWaves * kWave), 0, stream, books, s, q_rot, static_cast<const uint4 *>(k_pool),
+                       static_cast<const uint32_t *>(v_pool), seq_lens, part_ml, part_acc, nullptr, plan, nullptr,
+                       nullptr, pt.table, pt.stride, pt.n_pages);
+    return static_cast<int>(hipGetLastError());
+}
+
+template <class P>
+int launch_decode_paged_plan(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot,
+                             const void *k_pool, const void *v_pool, const PageTable &pt, const int32_t *seq_lens,
+                             float *part_ml, float *part_acc, int32_t *plan, hipStream_t stream) {
+    switch (s.rows_per_pass) {
+        case 1: return launch_decode_paged_rg<P, 1>(cb, s, q_rot, k_pool, v_pool, pt, seq_lens, part_ml, part_acc, plan, stream);
+        case 2: return launch_decode_paged_rg<P, 2>(cb, s, q_rot, k_pool, v_pool, pt, seq_lens, part_ml, part_acc, plan, stream);
+        case 4: return launch_decode_paged_rg<P, 4>(cb, s, q_rot, k_pool, v_pool, pt, seq_lens, part_ml, part_acc, plan, stream);
+        case 8: return launch_decode_paged_rg<P, 8>(cb, s, q_rot, k_pool, v_pool, pt, seq_lens, part_ml, part_acc, plan, stream);
+        default: return static_cast<int>(hipErrorInvalidValue);
+    }
 }
 
 template <class P, bool SCORES>
@@ -1292,7 +1397,7 @@ int launch_decode_qjl_rg(const octopus_codebooks_t &cb, const DecodeShape &s, co
         hipLaunchKernelGGL((decode_kernel_mfma<P, RG, true, true>), dim3(kDecodeWorkgroups),
                            dim3(kDecodeWaves * kWave), 0, stream, books, s, q_rot, static_cast<const uint4 *>(cache),
                            static_cast<const uint32_t *>(v), seq_lens, part_ml, part_acc, scores_out, plan,
-                           static_cast<const unsigned char *>(qjl), q2);
+                           static_cast<const unsigned char *>(qjl), q2, nullptr, 0, 0);
         return static_cast<int>(hipGetLastError());
     } else {
         return static_cast<int>(hipErrorInvalidValue);

@@ -220,7 +220,7 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
                                                       uint4 *__restrict__ cache, int64_t t_capacity,
                                                       const int32_t *__restrict__ start_pos, int32_t n_kv_heads,
                                                       const uint8_t *__restrict__ signs2,
-                                                      unsigned char *__restrict__ qjl, int32_t mode) {
+                                                      unsigned char *__restrict__ qjl, int32_t mode, PageTable pt) {
     constexpr int D = P::D;
     constexpr int LPR = D / 8;        // threads per key row in the load phase
     constexpr int RPP = 256 / LPR;    // key rows per load pass
@@ -392,7 +392,13 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
         __syncthreads();
 
         // E8: store the tile, 16 bytes per (granule, key), coalesced over keys
+        // pt.table (or NULL): `cache` is a pool of [page][KV head] tiles, logical tile j of sequence s is in page
+        // pt.table[s * pt.stride + j] (clamped to the pool)
         uint4 *dst = region + tile * (P::GRANULES * kWave);
+        if (pt.table != nullptr) {
+            const int page = pt.table[static_cast<int64_t>(seq) * pt.stride + tile];
+            dst = cache + (static_cast<int64_t>(min(max(page, 0), pt.n_pages - 1)) * n_kv_heads + kvh) * (P::GRANULES * kWave);
+        }
         for (int e = tid; e < P::GRANULES * kWave; e += 256) {
             const int g = e / kWave, key = e % kWave;
             const int64_t tok = tile * kWave + key;
@@ -448,7 +454,7 @@ template <class P>
 int launch_encode_plan(const octopus_codebooks_t &cb, const void *keys, int key_dtype, int64_t stride_seq,
                        int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
                        const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos,
-                       const uint8_t *signs2, void *qjl, hipStream_t stream) {
+                       const uint8_t *signs2, void *qjl, hipStream_t stream, PageTable pt = PageTable{nullptr, 0, 0}) {
     DeviceBooks books;
     for (int c = 0; c < 2; ++c) {
         for (int k = 0; k < 32; ++k) books.c_xi[c][k] = cb.c_xi[c][k];
@@ -461,7 +467,7 @@ int launch_encode_plan(const octopus_codebooks_t &cb, const void *keys, int key_
     auto go = [&](auto kernel) {
         hipLaunchKernelGGL(kernel, grid, dim3(256), 0, stream, books, keys, stride_seq, stride_tok, stride_head, n_new,
                            signs, static_cast<uint4 *>(cache), t_capacity, start_pos, n_kv_heads, signs2,
-                           static_cast<unsigned char *>(qjl), 1);
+                           static_cast<unsigned char *>(qjl), 1, pt);
     };
     if (qjl != nullptr) {
         if (bf16) go(encode_kernel<P, true, true>); else go(encode_kernel<P, false, true>);
@@ -486,7 +492,8 @@ int launch_encode_rounding_plan(const octopus_codebooks_t &cb, const void *keys,
     const dim3 grid((tiles + kEncodeTilesPerGroup - 1) / kEncodeTilesPerGroup, n_kv_heads, n_seq);
     auto go = [&](auto kernel) {
         hipLaunchKernelGGL(kernel, grid, dim3(256), 0, stream, books, keys, stride_seq, stride_tok, stride_head, n_new,
-                           signs, static_cast<uint4 *>(cache), t_capacity, start_pos, n_kv_heads, nullptr, nullptr, mode);
+                           signs, static_cast<uint4 *>(cache), t_capacity, start_pos, n_kv_heads, nullptr, nullptr, mode,
+                           PageTable{nullptr, 0, 0});
     };
     if (key_dtype == OCTOPUS_DTYPE_BF16) go(encode_kernel<P, true, false, true>);
     else go(encode_kernel<P, false, false, true>);

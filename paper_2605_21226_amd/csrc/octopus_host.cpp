@@ -641,6 +641,74 @@ int octopus_attn_decode_vq(const octopus_codebooks_t *cb, const void *q, int32_t
                        false, nullptr, nullptr, v_bits, v_group);
 }
 
+size_t octopus_paged_pool_bytes(const octopus_codebooks_t *cb, int32_t n_pages, int32_t n_kv_heads) {
+    if (cb == nullptr || n_pages < 1 || n_kv_heads < 1 || !plan_consistent(cb->plan)) return 0;
+    return static_cast<size_t>(n_pages) * n_kv_heads * OCTOPUS_TILE * cb->plan.granules * 16;
+}
+
+static bool page_table_ok(const void *pool, int32_t n_pages, const int32_t *block_table, int32_t max_pages_per_seq) {
+    return pool != nullptr && block_table != nullptr && n_pages >= 1 && max_pages_per_seq >= 1 &&
+           max_pages_per_seq <= (INT32_MAX / OCTOPUS_TILE) && aligned(pool, 16) && aligned(block_table, 4);
+}
+
+int octopus_encode_paged(const octopus_codebooks_t *cb, const void *keys, int32_t key_dtype, int64_t stride_seq,
+                         int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
+                         const uint8_t *signs, void *k_pool, int32_t n_pages, const int32_t *block_table,
+                         int32_t max_pages_per_seq, const int32_t *start_pos, void *stream) {
+    if (cb == nullptr || keys == nullptr || signs == nullptr) return OCTOPUS_EINVAL;
+    if (!page_table_ok(k_pool, n_pages, block_table, max_pages_per_seq)) return OCTOPUS_EINVAL;
+    if (n_seq < 1 || n_kv_heads < 1 || n_new < 0) return OCTOPUS_EINVAL;
+    if (n_seq > 65535 || n_kv_heads > 65535) return OCTOPUS_EINVAL;   // they are grid dimensions of the launch
+    if (!plan_consistent(cb->plan)) return OCTOPUS_EINVAL;
+    if (key_dtype != OCTOPUS_DTYPE_F32 && key_dtype != OCTOPUS_DTYPE_BF16) return OCTOPUS_EUNSUPPORTED;
+    if (!plan_supported(cb->plan) || !seed_grid_ok(*cb)) return OCTOPUS_EUNSUPPORTED;
+    if (stride_seq < 0 || stride_tok < 0 || stride_head < 0) return OCTOPUS_EINVAL;
+    if (stride_seq % 8 != 0 || stride_tok % 8 != 0 || stride_head % 8 != 0) return OCTOPUS_EINVAL;
+    if (!aligned(keys, 16)) return OCTOPUS_EINVAL;
+    const int64_t reach = static_cast<int64_t>(max_pages_per_seq) * OCTOPUS_TILE;   // tokens the table can address
+    if (start_pos == nullptr && n_new > reach) return OCTOPUS_EINVAL;
+    if (n_new == 0) return OCTOPUS_OK;
+    const PageTable pt{block_table, max_pages_per_seq, n_pages};
+    const int err = launch_encode_paged(*cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads,
+                                        n_new, signs, k_pool, pt, start_pos, stream);
+    return err == 0 ? OCTOPUS_OK : OCTOPUS_EHIP;
+}
+
+int octopus_attn_decode_paged(const octopus_codebooks_t *cb, const void *q, int32_t q_dtype, int32_t n_seq,
+                              int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q, const uint8_t *signs,
+                              const void *k_pool, const void *v_pool, int32_t n_pages, const int32_t *block_table,
+                              int32_t max_pages_per_seq, const int32_t *seq_lens, int64_t max_len, float scale,
+                              float *out, void *workspace, size_t workspace_bytes, void *stream) {
+    const int ok = decode_args_ok(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len);
+    if (ok != OCTOPUS_OK) return ok;
+    if (q == nullptr || signs == nullptr || seq_lens == nullptr || out == nullptr) return OCTOPUS_EINVAL;
+    if (!page_table_ok(k_pool, n_pages, block_table, max_pages_per_seq) || v_pool == nullptr || !aligned(v_pool, 16))
+        return OCTOPUS_EINVAL;
+    const int64_t reach = static_cast<int64_t>(max_pages_per_seq) * OCTOPUS_TILE;
+    if (max_len > reach) return OCTOPUS_EINVAL;
+    if (q_dtype != OCTOPUS_DTYPE_F32 && q_dtype != OCTOPUS_DTYPE_BF16) return OCTOPUS_EUNSUPPORTED;
+    if (!aligned(q, 4) || !aligned(out, 4) || !std::isfinite(scale)) return OCTOPUS_EINVAL;
+    const DecodeShape s = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, reach, false);
+    const Workspace w = make_workspace(cb->plan, s);
+    if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < w.total) return OCTOPUS_EWORKSPACE;
+    char *base = static_cast<char *>(workspace);
+    float *q_rot = reinterpret_cast<float *>(base + w.q_rot_off);
+    float *part_ml = reinterpret_cast<float *>(base + w.part_ml_off);
+    float *part_acc = reinterpret_cast<float *>(base + w.part_acc_off);
+    int32_t *work_plan = reinterpret_cast<int32_t *>(base + w.plan_off);
+    const PageTable pt{block_table, max_pages_per_seq, n_pages};
+    int err = launch_rotate_queries(cb->plan, q, q_dtype, signs, s, scale, q_rot, seq_lens, work_plan, nullptr, nullptr,
+                                    stream);
+    void *ev_before = g_event_before, *ev_after = g_event_after;
+    g_event_before = g_event_after = nullptr;
+    if (err == 0 && ev_before != nullptr) err = record_event(ev_before, stream);
+    if (err == 0)
+        err = launch_decode_paged(*cb, s, q_rot, k_pool, v_pool, pt, seq_lens, part_ml, part_acc, work_plan, stream);
+    if (err == 0 && ev_after != nullptr) err = record_event(ev_after, stream);
+    if (err == 0) err = launch_merge(cb->plan, s, part_ml, part_acc, work_plan, out, nullptr, nullptr, stream);
+    return err == 0 ? OCTOPUS_OK : OCTOPUS_EHIP;
+}
+
 const char *octopus_strerror(int code) {
     switch (code) {
         case OCTOPUS_OK: return "ok";

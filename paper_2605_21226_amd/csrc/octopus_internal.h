@@ -31,6 +31,14 @@ struct DecodeShape {
     int64_t t_capacity;
 };
 
+// Paged cache: logical 64-token tile j of sequence s lives in page table[s * stride + j] of a pool of n_pages
+// pages; table NULL: the contiguous cache.
+struct PageTable {
+    const int32_t *table;
+    int32_t stride;
+    int32_t n_pages;
+};
+
 // Workspace carve-up (all offsets multiples of 256 bytes).
 struct Workspace {
     size_t q_rot_off, part_ml_off, part_acc_off, plan_off, q2_off, win_ml_off, win_acc_off, total;
@@ -70,6 +78,16 @@ int launch_encode(const octopus_codebooks_t &cb, const void *keys, int key_dtype
                   int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
                   const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos,
                   const uint8_t *signs2, void *qjl, void *stream);   // qjl NULL: no side-car
+
+// Paged pools: the encoder writes each tile into its page of `k_pool` ([page][KV head] key tiles); the decode
+// kernel reads key tiles from `k_pool` and bf16 value tiles ([page][KV head][64][head_dim]) from `v_pool`.
+int launch_encode_paged(const octopus_codebooks_t &cb, const void *keys, int key_dtype, int64_t stride_seq,
+                        int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
+                        const uint8_t *signs, void *k_pool, const PageTable &pt, const int32_t *start_pos,
+                        void *stream);
+int launch_decode_paged(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *k_pool,
+                        const void *v_pool, const PageTable &pt, const int32_t *seq_lens, float *part_ml,
+                        float *part_acc, int32_t *work_plan, void *stream);
 
 // The encoder with one of the rounding modes of App. E (OCTOPUS_ROUND_*), no side-car.
 int launch_encode_rounding(const octopus_codebooks_t &cb, const void *keys, int key_dtype, int64_t stride_seq,

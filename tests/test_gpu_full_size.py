@@ -41,7 +41,8 @@ def check_pair_codes(plan, k, signs_h, got, tag):
 
 def run_full_size(name, bits, pairs, q_rows, seed=0, chunked_encode=False, variant=None):
     """pairs: (sequence, KV head) pairs to check; q_rows: query positions (of n_q) to check;
-    variant: None, "qjl", ("vq", bits, group) or ("window", tokens)"""
+    variant: None, "qjl", ("vq", bits, group), ("window", tokens) or "paged" (the cache scattered over pages in a
+    random order, encoded once more straight into the pages, attention from the pages)"""
     base = synth.WORKLOADS[name]
     wl = synth.Workload(**{**base.__dict__, "bits": bits})
     cb = binding.octopus_build_codebooks(wl.head_dim, bits)
@@ -116,12 +117,33 @@ def run_full_size(name, bits, pairs, q_rows, seed=0, chunked_encode=False, varia
             side[(s * n_kv + h) * img.size:(s * n_kv + h + 1) * img.size] = torch.from_numpy(img).to(DEV)
     print(f"[full] {name} b={bits} {variant or ''}: decode attention", flush=True)
     lens_dev = torch.from_numpy(lens).to(DEV)
+    if kind == "paged":
+        tiles = cap // 64
+        n_pages = wl.n_seq * tiles + 7
+        gen = torch.Generator(device="cpu").manual_seed(seed + 5)
+        table = torch.randperm(n_pages, generator=gen)[:wl.n_seq * tiles].to(torch.int32).reshape(wl.n_seq, tiles).to(DEV)
+        tb = cb.plan.granules * 64 * 16
+        flat = table.reshape(-1).long()
+        k_pool = torch.full((n_pages, n_kv, tb), 0xAB, dtype=torch.uint8, device=DEV)
+        k_pool[flat] = cache.reshape(wl.n_seq, n_kv, tiles, tb).permute(0, 2, 1, 3).reshape(-1, n_kv, tb)
+        v_pool = torch.full((n_pages, n_kv, 64, d), 1e4, dtype=vals.dtype, device=DEV)
+        v_pool[flat] = vals.reshape(wl.n_seq, n_kv, tiles, 64, d).permute(0, 2, 1, 3, 4).reshape(-1, n_kv, 64, d)
+        # the encoder writes the same pages (sampled pairs hold the oracle's codes in k_pool: skip those)
+        k_pool2 = torch.full((n_pages, n_kv, tb), 0xAB, dtype=torch.uint8, device=DEV)
+        binding.octopus_encode_paged(cb, keys, sbits, k_pool2, n_pages, table)
+        same = (k_pool2 == k_pool).reshape(n_pages, n_kv, -1).all(dim=2)
+        for (s, h) in pairs:
+            same[table[s].long(), h] = True
+        assert bool(same.all()), "octopus_encode_paged and octopus_encode wrote different tiles"
+        del k_pool2, same
     if kind == "qjl":
         binding.octopus_attn_decode_qjl(cb, q, sbits, s2bits, cache, side, cap, vals, lens_dev, max_len, scale, out, ws)
     elif kind == "vq":
         binding.octopus_attn_decode_vq(cb, q, sbits, cache, cap, vq, v_bits, v_group, n_kv, lens_dev, max_len, scale, out, ws)
     elif kind == "window":
         binding.octopus_attn_decode_hybrid(cb, q, sbits, cache, cap, vals, lens_dev, max_len, k_win, win_dev, scale, out, ws)
+    elif kind == "paged":
+        binding.octopus_attn_decode_paged(cb, q, sbits, k_pool, v_pool, table, lens_dev, max_len, scale, out, ws)
     else:
         binding.octopus_attn_decode(cb, q, sbits, cache, cap, vals, lens_dev, max_len, scale, out, ws)
     torch.cuda.synchronize()
@@ -193,3 +215,7 @@ def test_full_llama3_8b_decode_quantised_values():
 
 def test_full_llama3_8b_decode_window():
     run_full_size("llama3_8b_decode", 3.0, [(1, 4), (14, 3)], [0], variant=("window", 32))
+
+
+def test_full_llama3_8b_decode_paged():
+    run_full_size("llama3_8b_decode", 3.0, [(3, 5), (15, 7)], [0], variant="paged")

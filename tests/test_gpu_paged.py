@@ -1,0 +1,193 @@
+"""GPU parity of the paged cache: the codes octopus_encode_paged writes into pages and the attention
+octopus_attn_decode_paged computes from pages, against the oracle (which knows only logical token order).
+Pages are handed out in a random order from pools larger than needed; unused pages hold garbage, so a read
+of a wrong page shows."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2605_21226_amd import binding, layout, synth
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+if not torch.cuda.is_available():
+    pytest.skip("no GPU", allow_module_level=True)
+
+from gpu_util import DEV, check_out, sign_bits_dev, to_dev  # noqa: E402
+from test_gpu_parity import compare_records, make_inputs, oracle_attention_all  # noqa: E402
+
+
+def random_table(rng, n_seq, max_pages, n_pages):
+    """distinct pages for every (sequence, logical tile)"""
+    ids = rng.permutation(n_pages)[:n_seq * max_pages]
+    return ids.reshape(n_seq, max_pages).astype(np.int32)
+
+
+def pools_from_logical(cb, records, v, table, n_pages, cap):
+    """records [n_seq, n_kv, T, rb], v [n_seq, n_kv, cap, d] -> (k_pool bytes, v_pool [n_pages, n_kv, 64, d])"""
+    n_seq, n_kv = records.shape[:2]
+    d = v.shape[-1]
+    tb = cb.plan.granules * 64 * 16
+    img = layout.records_to_cache(records, cb.plan.granules, cap).reshape(n_seq, n_kv, cap // 64, tb)
+    k_pool = np.full((n_pages, n_kv, tb), 0xAB, dtype=np.uint8)
+    v_pool = np.full((n_pages, n_kv, 64, d), 1e4, dtype=np.float32)      # garbage that would dominate an output
+    for s in range(n_seq):
+        for j in range(cap // 64):
+            k_pool[table[s, j]] = img[s, :, j]
+            v_pool[table[s, j]] = v[s, :, 64 * j:64 * j + 64]
+    return k_pool, v_pool
+
+
+def run_paged_decode_case(d, bits, n_seq, n_qh, n_kv, n_q, lens, seed, q_dtype="bf16", spare_pages=5):
+    cb = binding.octopus_build_codebooks(d, bits)
+    plan = oracle.make_plan(d, bits)
+    rng = np.random.default_rng(seed)
+    T = max(int(max(lens)), 1)
+    cap = -(-T // 64) * 64
+    max_pages = cap // 64
+    n_pages = n_seq * max_pages + spare_pages
+    keys, vals, signs = make_inputs(seed, n_seq, n_kv, T, d, "bf16")
+    records = np.stack([np.stack([oracle.encode(plan, keys[s, :, h].astype(np.float64), signs[h]) for h in range(n_kv)])
+                        for s in range(n_seq)])
+    q = synth.queries(seed, synth.Workload("t", n_seq, n_qh, n_kv, d, T, bits, q_dtype, n_q=n_q))
+    v = np.zeros((n_seq, n_kv, cap, d), dtype=np.float32)
+    v[:, :, :T] = vals
+    table = random_table(rng, n_seq, max_pages, n_pages)
+    k_pool, v_pool = pools_from_logical(cb, records, v, table, n_pages, cap)
+    scale = 1.0 / np.sqrt(d)
+    ws = torch.empty(binding.octopus_attn_decode_workspace(cb, n_seq, n_qh, n_kv, n_q, T), dtype=torch.uint8, device=DEV)
+    out = torch.full((n_seq, n_q, n_qh, d), float("nan"), dtype=torch.float32, device=DEV)
+    binding.octopus_attn_decode_paged(cb, to_dev(q, q_dtype), sign_bits_dev(signs), torch.from_numpy(k_pool).to(DEV),
+                                      to_dev(v_pool, "bf16"), torch.from_numpy(table).to(DEV),
+                                      torch.tensor(np.asarray(lens), dtype=torch.int32, device=DEV), T, scale, out, ws)
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    ref_out, _ = oracle_attention_all(plan, records, signs, q, v, lens, scale)
+    worst = 0.0
+    for s in range(n_seq):
+        for h in range(n_qh):
+            for qi in range(n_q):
+                if int(lens[s]) == 0:
+                    assert np.all(out[s, qi, h] == 0.0)
+                else:
+                    worst = max(worst, check_out(out[s, qi, h], ref_out[s, qi, h]))
+    print(f"[paged attn] d={d} b={bits} lens={list(lens)}: worst out err {worst:.3g}")
+
+
+@pytest.mark.parametrize("bits", [1, 1.5, 2, 2.5, 3, 4])
+def test_paged_decode_gqa_ragged_d128(bits):
+    run_paged_decode_case(128, bits, 3, 8, 2, 1, [0, 77, 1000], seed=int(700 + 10 * bits))
+
+
+@pytest.mark.parametrize("d,bits", [(64, 2), (64, 4), (256, 2.5), (256, 3)])
+def test_paged_decode_other_head_dims(d, bits):
+    run_paged_decode_case(d, bits, 2, 4, 2, 3, [513, 64], seed=int(800 + d + 10 * bits))
+
+
+def test_paged_decode_long_sequence_many_sequences_and_fp32_queries():
+    run_paged_decode_case(128, 3, 1, 4, 1, 1, [9000], seed=901)                       # 141 pages, several splits
+    rng = np.random.default_rng(902)
+    run_paged_decode_case(64, 3, 70, 2, 1, 1, [int(x) for x in rng.integers(0, 300, size=70)], seed=902)
+    run_paged_decode_case(128, 2, 2, 6, 2, 11, [300, 129], seed=903, q_dtype="fp32")  # 33 rows: groups of 8
+
+
+def test_paged_decode_shared_prefix_pages():
+    """two sequences whose first pages are the same physical pages (a common prefix)"""
+    d, bits, n_kv, n_qh = 128, 3, 2, 8
+    cb = binding.octopus_build_codebooks(d, bits)
+    plan = oracle.make_plan(d, bits)
+    keys, vals, signs = make_inputs(950, 2, n_kv, 320, d, "bf16")
+    keys[1, :128] = keys[0, :128]                      # 2 pages of common prefix
+    vals[1, :, :128] = vals[0, :, :128]
+    records = np.stack([np.stack([oracle.encode(plan, keys[s, :, h].astype(np.float64), signs[h]) for h in range(n_kv)])
+                        for s in range(2)])
+    table = np.array([[7, 3, 0, 9, 5], [7, 3, 1, 8, 2]], dtype=np.int32)
+    k_pool, v_pool = pools_from_logical(cb, records, vals, table, 10, 320)
+    lens = [320, 290]
+    q = synth.queries(950, synth.Workload("t", 2, n_qh, n_kv, d, 320, bits, "bf16"))
+    ws = torch.empty(binding.octopus_attn_decode_workspace(cb, 2, n_qh, n_kv, 1, 320), dtype=torch.uint8, device=DEV)
+    out = torch.zeros((2, 1, n_qh, d), dtype=torch.float32, device=DEV)
+    scale = 1 / np.sqrt(d)
+    binding.octopus_attn_decode_paged(cb, to_dev(q, "bf16"), sign_bits_dev(signs), torch.from_numpy(k_pool).to(DEV),
+                                      to_dev(v_pool, "bf16"), torch.from_numpy(table).to(DEV),
+                                      torch.tensor(lens, dtype=torch.int32, device=DEV), 320, scale, out, ws)
+    torch.cuda.synchronize()
+    ref_out, _ = oracle_attention_all(plan, records, signs, q, vals, lens, scale)
+    for s in range(2):
+        for h in range(n_qh):
+            check_out(out.cpu().numpy()[s, 0, h], ref_out[s, 0, h])
+
+
+def gather_records(cb, k_pool, table, n_seq, n_kv, cap):
+    tb = cb.plan.granules * 64 * 16
+    pool = k_pool.reshape(-1, n_kv, tb)
+    img = np.zeros((n_seq, n_kv, cap // 64, tb), dtype=np.uint8)
+    for s in range(n_seq):
+        for j in range(cap // 64):
+            img[s, :, j] = pool[table[s, j]]
+    return layout.cache_to_records(img.reshape(-1), n_seq, n_kv, cap, cb.plan.granules, cb.plan.record_bytes)
+
+
+@pytest.mark.parametrize("d,bits,dtype", [(128, 3, "bf16"), (64, 2.5, "fp32"), (256, 4, "bf16")])
+def test_paged_encode_matches_the_oracle_and_leaves_other_pages_alone(d, bits, dtype):
+    cb = binding.octopus_build_codebooks(d, bits)
+    plan = oracle.make_plan(d, bits)
+    n_seq, n_kv, n_tok, max_pages = 3, 2, 200, 5
+    n_pages = n_seq * max_pages + 4
+    rng = np.random.default_rng(int(d + 10 * bits))
+    keys, _, signs = make_inputs(int(d + 10 * bits), n_seq, n_kv, n_tok, d, dtype)
+    table = random_table(rng, n_seq, max_pages, n_pages)
+    k_pool = torch.full((binding.octopus_paged_pool_bytes(cb, n_pages, n_kv),), 0xAB, dtype=torch.uint8, device=DEV)
+    binding.octopus_encode_paged(cb, to_dev(keys, dtype), sign_bits_dev(signs), k_pool, n_pages,
+                                 torch.from_numpy(table).to(DEV))
+    torch.cuda.synchronize()
+    pool = k_pool.cpu().numpy()
+    rec, _ = gather_records(cb, pool, table, n_seq, n_kv, max_pages * 64)
+    compare_records(plan, keys, signs, rec, f"paged encode d={d} b={bits}")
+    tb = cb.plan.granules * 64 * 16
+    used = set(table[:, :4].reshape(-1).tolist())                      # 200 tokens: tiles 0..3
+    for page in range(n_pages):
+        if page not in used:
+            assert np.all(pool.reshape(n_pages, n_kv, tb)[page] == 0xAB)
+    # the contiguous encoder writes the same bytes
+    cache = torch.zeros(binding.octopus_cache_bytes(cb, n_seq, n_kv, 256), dtype=torch.uint8, device=DEV)
+    binding.octopus_encode(cb, to_dev(keys, dtype), sign_bits_dev(signs), cache, 256)
+    ref, _ = layout.cache_to_records(cache.cpu().numpy(), n_seq, n_kv, 256, cb.plan.granules, cb.plan.record_bytes)
+    assert np.array_equal(rec[:, :, :n_tok], ref[:, :, :n_tok])
+
+
+def test_paged_encode_append_then_decode_end_to_end():
+    """tokens appended in three calls at unaligned positions into pages, then attention from the pages"""
+    d, bits, n_seq, n_kv, n_qh, T, max_pages = 128, 3, 2, 2, 8, 300, 5
+    cb = binding.octopus_build_codebooks(d, bits)
+    plan = oracle.make_plan(d, bits)
+    rng = np.random.default_rng(77)
+    n_pages = 16
+    keys, vals, signs = make_inputs(77, n_seq, n_kv, T, d, "bf16")
+    table = random_table(rng, n_seq, max_pages, n_pages)
+    tab_dev = torch.from_numpy(table).to(DEV)
+    k_pool = torch.zeros(binding.octopus_paged_pool_bytes(cb, n_pages, n_kv), dtype=torch.uint8, device=DEV)
+    for lo, hi in ((0, 100), (100, 101), (101, 300)):
+        binding.octopus_encode_paged(cb, to_dev(keys[:, lo:hi], "bf16"), sign_bits_dev(signs), k_pool, n_pages, tab_dev,
+                                     torch.full((n_seq,), lo, dtype=torch.int32, device=DEV))
+    v = np.zeros((n_seq, n_kv, max_pages * 64, d), dtype=np.float32)
+    v[:, :, :T] = vals
+    v_pool = np.zeros((n_pages, n_kv, 64, d), dtype=np.float32)
+    for s in range(n_seq):
+        for j in range(max_pages):
+            v_pool[table[s, j]] = v[s, :, 64 * j:64 * j + 64]
+    lens = [300, 170]
+    q = synth.queries(77, synth.Workload("t", n_seq, n_qh, n_kv, d, T, bits, "bf16"))
+    ws = torch.empty(binding.octopus_attn_decode_workspace(cb, n_seq, n_qh, n_kv, 1, T), dtype=torch.uint8, device=DEV)
+    out = torch.zeros((n_seq, 1, n_qh, d), dtype=torch.float32, device=DEV)
+    scale = 1 / np.sqrt(d)
+    binding.octopus_attn_decode_paged(cb, to_dev(q, "bf16"), sign_bits_dev(signs), k_pool, to_dev(v_pool, "bf16"), tab_dev,
+                                      torch.tensor(lens, dtype=torch.int32, device=DEV), T, scale, out, ws)
+    torch.cuda.synchronize()
+    records = np.stack([np.stack([oracle.encode(plan, keys[s, :, h].astype(np.float64), signs[h]) for h in range(n_kv)])
+                        for s in range(n_seq)])
+    ref_out, _ = oracle_attention_all(plan, records, signs, q, v, lens, scale)
+    for s in range(n_seq):
+        for h in range(n_qh):
+            check_out(out.cpu().numpy()[s, 0, h], ref_out[s, 0, h])

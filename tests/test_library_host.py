@@ -214,3 +214,33 @@ def test_hybrid_decode_argument_checks(lib):
     assert dec(*args(w_capacity=0)) == binding.EINVAL
     assert dec(*args(k_dtype=5)) == binding.EUNSUPPORTED
     assert dec(*args(ws_bytes=ws - 1)) == binding.EWORKSPACE
+
+
+def test_paged_cache_sizes_and_argument_checks(lib):
+    cb = binding.octopus_build_codebooks(128, 3)
+    assert binding.octopus_paged_pool_bytes(cb, 10, 8) == 10 * 8 * 64 * cb.plan.granules * 16
+    assert binding.octopus_paged_pool_bytes(cb, 0, 8) == 0
+    ws = binding.octopus_attn_decode_workspace(cb, 2, 32, 8, 1, 4096)
+    fake, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+    dec = lib.octopus_attn_decode_paged
+    dargs = lambda **k: [ctypes.byref(cb), fake, 1, 2, 32, 8, 1, fake, k.get("k_pool", fake), k.get("v_pool", fake),
+                         k.get("n_pages", 128), k.get("table", fake), k.get("max_pages", 64), fake,
+                         k.get("max_len", 4096), ctypes.c_float(0.1), fake, ctypes.c_void_p(0x10000),
+                         k.get("ws_bytes", ws), null]
+    assert dec(*dargs(k_pool=null)) == binding.EINVAL
+    assert dec(*dargs(v_pool=null)) == binding.EINVAL
+    assert dec(*dargs(table=null)) == binding.EINVAL
+    assert dec(*dargs(n_pages=0)) == binding.EINVAL
+    assert dec(*dargs(max_pages=0)) == binding.EINVAL
+    assert dec(*dargs(max_len=4097)) == binding.EINVAL            # beyond what 64 pages of 64 tokens hold
+    assert dec(*dargs(k_pool=ctypes.c_void_p(0x1004))) == binding.EINVAL
+    assert dec(*dargs(ws_bytes=ws - 1)) == binding.EWORKSPACE
+    enc = lib.octopus_encode_paged
+    eargs = lambda **k: [ctypes.byref(cb), fake, 1, 8 * 1024, 1024, 128, 2, 8, k.get("n_new", 64), fake,
+                         k.get("k_pool", fake), k.get("n_pages", 128), k.get("table", fake), k.get("max_pages", 4),
+                         k.get("start", null), null]
+    assert enc(*eargs(k_pool=null)) == binding.EINVAL
+    assert enc(*eargs(table=null)) == binding.EINVAL
+    assert enc(*eargs(n_pages=0)) == binding.EINVAL
+    assert enc(*eargs(n_new=257)) == binding.EINVAL               # more tokens than 4 pages hold, no start positions
+    assert enc(*eargs(n_new=0)) == binding.OK                     # nothing to do, nothing launched
