@@ -15,6 +15,7 @@ if not torch.cuda.is_available():
     pytest.skip("no GPU", allow_module_level=True)
 
 import test_gpu_hybrid as hybrid  # noqa: E402
+import test_gpu_paged as paged  # noqa: E402
 import test_gpu_parity as parity  # noqa: E402
 import test_gpu_qjl as qjl  # noqa: E402
 import test_gpu_values as values  # noqa: E402
@@ -61,12 +62,12 @@ def test_decode_random_shapes(seed):
 @pytest.mark.parametrize("seed", range(4))
 def test_variant_entry_points_random_shapes(seed):
     rng = np.random.default_rng(9500 + seed)
-    for i in range(12):
+    for i in range(15):
         d, bits, n_kv, g, n_q, lens = draw_shape(rng)
         n_seq = len(lens)
         want_scores = bool(rng.random() < 0.4) and n_q * g <= 16
         case_seed = 9600 + 100 * seed + i
-        variant = ("qjl", "vq", "hybrid", "encode")[i % 4]
+        variant = ("qjl", "vq", "hybrid", "encode", "paged")[i % 5]
         head = f"{variant} seed={seed} case={i}: d={d} bits={bits} n_kv={n_kv} g={g} n_q={n_q} scores={want_scores}"
         if variant == "qjl":
             print(f"{head} lens={lens}", flush=True)
@@ -76,6 +77,10 @@ def test_variant_entry_points_random_shapes(seed):
             print(f"{head} v_bits={v_bits} group={group} lens={lens}", flush=True)
             values.run_decode_vq_case(d, bits, v_bits, group, n_seq, n_kv * g, n_kv, n_q, lens, case_seed,
                                       want_scores=want_scores)
+        elif variant == "paged":
+            print(f"{head} lens={lens}", flush=True)
+            paged.run_paged_decode_case(d, bits, n_seq, n_kv * g, n_kv, n_q, lens, case_seed,
+                                        q_dtype="bf16" if rng.random() < 0.7 else "fp32")
         elif variant == "hybrid":
             w_cap = int(rng.choice([1, 32, 64, 100]))
             win = [int(x) for x in rng.integers(0, w_cap + 1, size=n_seq)]
