@@ -141,7 +141,9 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one process, no collectives); --gpus must be 1. "
-              "How the path would shard over several GPUs is described in DESIGN.md.", file=sys.stderr)
+              "Over several GPUs the path would shard by sequence or KV head without any exchange; one long "
+              "sequence splits by tokens, with one all-gather of the (m, l, acc) partials before the merge.",
+              file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
