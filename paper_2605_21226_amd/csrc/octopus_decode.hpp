@@ -675,17 +675,25 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
     // PAGED: the page ids of the tiles of a step (the last tile's for tiles past it) are read as they are, one
     // step ahead; the position in the pools (in tiles) is computed from them when the step's loads are issued,
     // so that nothing waits for the table right after asking it.
+    // The ids come through the vector memory path (every lane reads the same entry), asked for before the
+    // step's other loads: the wait for them one step later then covers only loads that are long complete.  As
+    // scalar loads they shared a counter with the query chunks, whose first wait of a step also waited for a
+    // table entry that had missed the scalar cache.
+    int lane_zero = 0;
+    if constexpr (PAGED) asm volatile("" : "+v"(lane_zero));
     auto page_ids = [&](int step, int (&page)[KPL]) {
 #pragma unroll
         for (int k = 0; k < KPL; ++k) {
             const int tile = max(min(step * KPL + k, ww.n_tiles - 1), 0);
-            page[k] = pt_table[static_cast<int64_t>(ww.seq) * pt_stride + tile];
+            page[k] = pt_table[static_cast<int64_t>(ww.seq) * pt_stride + tile + lane_zero];
         }
     };
     auto page_slots = [&](const int (&page)[KPL], int64_t (&slot)[KPL]) {
 #pragma unroll
-        for (int k = 0; k < KPL; ++k)
-            slot[k] = static_cast<int64_t>(min(max(page[k], 0), pt_pages - 1)) * shp.n_kv_heads + ww.kvh;
+        for (int k = 0; k < KPL; ++k) {
+            const int id = __builtin_amdgcn_readfirstlane(page[k]);
+            slot[k] = static_cast<int64_t>(min(max(id, 0), pt_pages - 1)) * shp.n_kv_heads + ww.kvh;
+        }
     };
     auto load_records_at = [&](const int64_t (&slot)[KPL], uint32_t (&w)[KPL][P::NWORDS]) {
 #pragma unroll
@@ -796,7 +804,10 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
         const int step_nx = min(step + ww.step_stride, ww.step_last);
         __amdgpu_buffer_rsrc_t v_next[KPL];   // per tile of the step (all the same unless PAGED)
         int64_t slot_nxt[KPL];
-        if constexpr (PAGED) page_slots(page_nxt, slot_nxt);
+        if constexpr (PAGED) {
+            page_slots(page_nxt, slot_nxt);
+            page_ids(min(step_nx + ww.step_stride, ww.step_last), page_nxt);   // used one step from here
+        }
 #pragma unroll
         for (int k = 0; k < KPL; ++k) {
             if constexpr (PAGED)
@@ -812,7 +823,6 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
             load_records_at(slot_nxt, w_next);
 #pragma unroll
             for (int k = 0; k < KPL; ++k) slot_cur[k] = slot_nxt[k];
-            page_ids(min(step_nx + ww.step_stride, ww.step_last), page_nxt);   // used one step from here
         } else {
             load_records(step_nx, w_next);
         }
