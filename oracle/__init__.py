@@ -78,6 +78,8 @@ def _load():
                                          ctypes.c_double, vp, vp, vp]
         lib.oracle_classify.argtypes = [P, vp, ctypes.c_int64, vp, vp, ctypes.c_double, vp]
         lib.oracle_classify_mode.argtypes = [P, vp, ctypes.c_int64, vp, ctypes.c_int, vp, ctypes.c_double, vp]
+        lib.oracle_classify_both.argtypes = [P, vp, ctypes.c_int64, vp, ctypes.c_int, vp, ctypes.c_double, vp]
+        lib.oracle_classify_both.restype = None
         lib.oracle_vq_row_bytes.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int]
         lib.oracle_vq_row_bytes.restype = ctypes.c_int
         lib.oracle_vq_encode.argtypes = [vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp]
@@ -314,6 +316,20 @@ def classify(plan, keys, signs, foreign_records, tol=1e-6, mode=MODE_LOCAL_3X3):
     _load().oracle_classify_mode(plan.cptr, _ptr(keys), keys.shape[0], _ptr(s), int(mode), _ptr(fr), float(tol),
                                  _ptr(counts))
     return int(counts[0]), int(counts[1]), int(counts[2])
+
+
+def classify_both(plan, keys, signs, foreign_records, tol=1e-6, mode=MODE_LOCAL_3X3):
+    """The same comparison under both readings of "within tol": returns (n_equal, n_tie_literal, n_tie_scaled_only,
+    n_hard).  Literal: tol on every compared quantity (xi, eta and p_z included).  Scaled: the tolerance on the
+    octahedral coordinates is tol / min(l1, 1), a triplet with l1 < tol admits any direction (what classify()
+    applies).  n_tie_scaled_only counts the triplets only the scaled reading admits."""
+    keys, s = _f64(keys), signs_pm1(signs)
+    fr = np.ascontiguousarray(foreign_records, dtype=np.uint8)
+    assert fr.shape == (keys.shape[0], plan.record_bytes)
+    counts = np.zeros(4, dtype=np.int64)
+    _load().oracle_classify_both(plan.cptr, _ptr(keys), keys.shape[0], _ptr(s), int(mode), _ptr(fr), float(tol),
+                                 _ptr(counts))
+    return tuple(int(c) for c in counts)
 
 
 # ---- optional 1-bit QJL residual (Sec. 3.6) -------------------------------------------------------

@@ -588,8 +588,11 @@ static int window_admits(const oracle_plan *p, int c, const double t[3], double 
     return 0;
 }
 
-void oracle_classify_key_mode(const oracle_plan *p, const double *k, const int8_t *s, int mode,
-                              const uint8_t *foreign, double tol, int64_t counts[3])
+/* literal != 0: the plain reading of "within tol" -- the same tol on every compared quantity, the octahedral
+ * coordinates included (tol_p = tol), and no exemption for a numerically zero triplet.  literal == 0: tol_p
+ * scaled by 1 / l1 as described above.  Every tie under the literal rule is one under the scaled rule. */
+static void classify_key(const oracle_plan *p, const double *k, const int8_t *s, int mode, int literal,
+                         const uint8_t *foreign, double tol, int64_t counts[3])
 {
     int nt = p->n_tri;
     int32_t *idx = (int32_t *)malloc(sizeof(int32_t) * 6 * nt);
@@ -612,7 +615,7 @@ void oracle_classify_key_mode(const oracle_plan *p, const double *k, const int8_
             double l1 = fabs(t[0]) + fabs(t[1]) + fabs(t[2]);
             double den = (l1 > OCT_EPS) ? l1 : OCT_EPS;
             double px = t[0] / den, py = t[1] / den, pz = t[2] / den;
-            double tol_p = (l1 > tol) ? tol / (l1 < 1.0 ? l1 : 1.0) : 4.0;
+            double tol_p = literal ? tol : ((l1 > tol) ? tol / (l1 < 1.0 ? l1 : 1.0) : 4.0);
             if (pz >= -tol_p) ok = window_admits(p, c, t, px, py, fx, fy, fn, tol, tol_p, mode); /* unfolded branch */
             if (!ok && pz < tol_p)                                                     /* folded branch */
                 for (int vx = 0; vx < 2 && !ok; ++vx)
@@ -628,6 +631,29 @@ void oracle_classify_key_mode(const oracle_plan *p, const double *k, const int8_
     }
     free(idx);
     free(u);
+}
+
+void oracle_classify_key_mode(const oracle_plan *p, const double *k, const int8_t *s, int mode,
+                              const uint8_t *foreign, double tol, int64_t counts[3])
+{
+    classify_key(p, k, s, mode, 0, foreign, tol, counts);
+}
+
+/* Both rules at once: counts4 = { equal, ties under the literal rule, ties only the scaled rule admits, hard }. */
+void oracle_classify_both(const oracle_plan *p, const double *keys, int64_t n_keys, const int8_t *s, int mode,
+                          const uint8_t *foreign_records, double tol, int64_t counts4[4])
+{
+    int rb = oracle_record_bytes(p);
+    int64_t c0 = 0, c1 = 0, c2 = 0, c3 = 0;
+#pragma omp parallel for schedule(static) reduction(+ : c0, c1, c2, c3)
+    for (int64_t t = 0; t < n_keys; ++t) {
+        int64_t lit[3] = { 0, 0, 0 }, sca[3] = { 0, 0, 0 };
+        classify_key(p, keys + t * p->d, s, mode, 1, foreign_records + t * rb, tol, lit);
+        if (lit[1] + lit[2] == 0) { c0 += lit[0]; continue; }
+        classify_key(p, keys + t * p->d, s, mode, 0, foreign_records + t * rb, tol, sca);
+        c0 += lit[0]; c1 += lit[1]; c2 += sca[1] - lit[1]; c3 += sca[2];
+    }
+    counts4[0] += c0; counts4[1] += c1; counts4[2] += c2; counts4[3] += c3;
 }
 
 void oracle_classify_key(const oracle_plan *p, const double *k, const int8_t *s,

@@ -29,10 +29,18 @@ def make_inputs(seed, n_seq, n_kv, n_tok, d, dtype, sigma_ln=0.5, n_outlier=4):
     return keys, vals, signs
 
 
-def compare_records(plan, keys, signs, rec, tag, max_tie_rate=2e-4, mode=oracle.MODE_LOCAL_3X3):
-    """keys [n_seq, n_tok, n_kv, d]; rec [n_seq, n_kv, >= n_tok, rb] from the GPU; mode: the oracle's rounding mode"""
+# Caps on the boundary ties per triplet compared: a few times what a healthy encoder shows (about 1e-5 at full
+# size; small cases may show a handful)
+MAX_TIE_RATE = 5e-5
+MAX_SCALED_ONLY_RATE = 2e-5
+
+
+def compare_records(plan, keys, signs, rec, tag, max_ties=None, mode=oracle.MODE_LOCAL_3X3):
+    """keys [n_seq, n_tok, n_kv, d]; rec [n_seq, n_kv, >= n_tok, rb] from the GPU; mode: the oracle's rounding mode.
+    Returns (equal, ties under a plain 1e-6 on every compared quantity, ties only the l1-scaled reading admits,
+    hard); max_ties: an explicit cap on all ties instead of the rate."""
     n_seq, n_tok, n_kv, d = keys.shape
-    total = np.zeros(3, dtype=np.int64)
+    total = np.zeros(4, dtype=np.int64)
     for s in range(n_seq):
         for h in range(n_kv):
             k = keys[s, :, h, :].astype(np.float64)
@@ -44,10 +52,16 @@ def compare_records(plan, keys, signs, rec, tag, max_tie_rate=2e-4, mode=oracle.
             if np.array_equal(got[:, 4:], ref[:, 4:]):
                 total[0] += n_tok * plan.n_tri
             else:
-                total += np.array(oracle.classify(plan, k, signs[h], got, tol=1e-6, mode=mode))
-    print(f"[codes] {tag}: triplets equal={total[0]} boundary_ties={total[1]} hard={total[2]}")
-    assert total[2] == 0, f"{tag}: {total[2]} code mismatches away from any decision boundary"
-    assert total[1] <= max(2, max_tie_rate * total.sum()), f"{tag}: too many boundary ties ({total[1]})"
+                total += np.array(oracle.classify_both(plan, k, signs[h], got, tol=1e-6, mode=mode))
+    print(f"[codes] {tag}: triplets equal={total[0]} ties_literal_1e-6={total[1]} ties_scaled_only={total[2]} "
+          f"hard={total[3]}")
+    assert total[3] == 0, f"{tag}: {total[3]} code mismatches away from any decision boundary"
+    ties = total[1] + total[2]
+    if max_ties is not None:
+        assert ties <= max_ties, f"{tag}: too many boundary ties ({ties})"
+    else:
+        assert ties <= max(3, MAX_TIE_RATE * total.sum()), f"{tag}: too many boundary ties ({ties})"
+        assert total[2] <= max(2, MAX_SCALED_ONLY_RATE * total.sum()), f"{tag}: too many scaled-only ties ({total[2]})"
     return total
 
 
@@ -101,7 +115,11 @@ def test_encode_append_at_unaligned_positions_leaves_other_slots_alone():
 
 
 def test_encode_degenerate_keys():
-    """all-zero key, one-hot keys, tiny and huge magnitudes, strided input"""
+    """all-zero key, one-hot keys, a constant key, tiny and huge magnitudes.  Per key: the zero key's record is
+    the oracle's placeholder byte for byte; scaling a key by a power of two changes gamma only, so those keys
+    behave like any other; a one-hot or constant key rotates to coordinates of equal magnitude, where EVERY
+    decision of Alg. 1 sits exactly on a boundary (p = (+-1/3, +-1/3, +-1/3), nine candidates with equal
+    scores): any of its triplets may tie, none may be a hard mismatch."""
     d = 128
     cb = binding.octopus_build_codebooks(d, 3)
     plan = oracle.make_plan(d, 3)
@@ -117,7 +135,11 @@ def test_encode_degenerate_keys():
     rec, _, _ = gpu_encode(cb, keys, "bf16", signs, 64)
     ref0 = oracle.encode(plan, np.zeros((1, d)), signs[0])[0]
     assert np.array_equal(rec[0, 0, 0], ref0)                                 # the zero key's placeholder
-    compare_records(plan, keys, signs, rec, "degenerate keys", max_tie_rate=0.2)
+    symmetric = [1, 2, 5]                                                      # every decision on a boundary
+    ordinary = [t for t in range(64) if t not in symmetric]
+    for t in symmetric:
+        compare_records(plan, keys[:, t:t + 1], signs, rec[:, :, t:t + 1], f"degenerate key {t}", max_ties=plan.n_tri)
+    compare_records(plan, keys[:, ordinary], signs, rec[:, :, ordinary], "degenerate keys: the ordinary ones", max_ties=1)
 
 
 # ---- decode attention ------------------------------------------------------------------------------

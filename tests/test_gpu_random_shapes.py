@@ -98,4 +98,4 @@ def test_variant_entry_points_random_shapes(seed):
             keys, _, signs = parity.make_inputs(case_seed, ns, n_kv, n_tok, d, dtype)
             rec, pad, _ = gpu_encode(cb, keys, dtype, signs, cap)
             assert not pad.any() and not rec[:, :, n_tok:].any()
-            parity.compare_records(plan, keys, signs, rec, head, max_tie_rate=5e-4)
+            parity.compare_records(plan, keys, signs, rec, head)

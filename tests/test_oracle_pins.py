@@ -485,6 +485,64 @@ def test_classifier_scales_the_octahedral_tolerance_with_the_triplet_l1_norm():
     assert oracle.classify(plan, k[None, :], s, rec, tol=1e-8) == (plan.n_tri - 1, 0, 1)
 
 
+def test_classifier_reports_literal_and_scaled_ties_separately():
+    """classify_both() = (equal, ties under a plain 1e-6 on every compared quantity, ties only the l1-scaled
+    reading admits, hard).  The small-l1 cases above are ties of the second kind only; a norm code at a rho
+    boundary (a comparison in the units of u) is a tie under both readings."""
+    d = 64
+    plan = oracle.make_plan(d, 4)
+    s = synth.sign_vectors(9, 1, d)[0]
+    u = synth.gaussian_keys(10, 1, d)[0]
+    u[d - 1] = 0.0
+    u /= np.linalg.norm(u)
+    u[d - 1] = 1e-5
+    k = oracle.rotate_inverse(u, s)
+    e = oracle.encode_key(plan, k, s)
+    i = plan.n_tri - 1
+    n = plan.n_tri
+    own = oracle.pack_record(plan, e["gamma"], e["idx_dir"], e["idx_nrm"])[None, :]
+    assert oracle.classify_both(plan, k[None, :], s, own) == (n, 0, 0, 0)
+    # xi code 29 instead of 31 at l1 = 1e-5: outside the oracle's own window, admitted only because 1e-6 in u
+    # is 0.1 in xi there -> scaled-only.  Code 30 lies inside the oracle's window (scores equal to 1e-15): a
+    # tie under both readings.
+    for code, want in ((29, (n - 1, 0, 1, 0)), (30, (n - 1, 1, 0, 0)), (20, (n - 1, 0, 0, 1))):
+        dirs = e["idx_dir"].copy()
+        dirs[2 * i] = code
+        rec = oracle.pack_record(plan, e["gamma"], dirs, e["idx_nrm"])[None, :]
+        assert oracle.classify_both(plan, k[None, :], s, rec) == want, code
+        # consistent with classify(): ties = literal + scaled-only
+        eq, tie, hard = oracle.classify(plan, k[None, :], s, rec)
+        assert (eq, tie, hard) == (want[0], want[1] + want[2], want[3])
+    # a numerically zero triplet: any direction code is a scaled-only tie
+    u2 = synth.gaussian_keys(9, 1, d)[0]
+    u2[d - 1] = 0.0
+    k2 = 3.0 * oracle.rotate_inverse(u2 / np.linalg.norm(u2), s)
+    e2 = oracle.encode_key(plan, k2, s)
+    dirs = e2["idx_dir"].copy()
+    dirs[2 * i], dirs[2 * i + 1] = 3, 20
+    rec = oracle.pack_record(plan, e2["gamma"], dirs, e2["idx_nrm"])[None, :]
+    got = oracle.classify_both(plan, k2[None, :], s, rec)
+    assert got[0] == n - 1 and got[3] == 0 and got[1] + got[2] == 1
+    # a norm code across the nearest rho boundary: tie under both readings when tol exceeds the gap
+    plan3 = oracle.make_plan(128, 3)
+    s3 = _signs(2, 128)
+    keys = synth.gaussian_keys(5, 64, 128)
+    b_rho = plan3.b_rho[0].astype(np.float64)
+    best = None
+    for t, kk in enumerate(keys):
+        ee = oracle.encode_key(plan3, kk, s3)
+        gaps = np.abs(np.clip(ee["s_star"], 0, 1)[:, None] - b_rho[None, :])
+        a, b = np.unravel_index(np.argmin(gaps), gaps.shape)
+        if best is None or gaps[a, b] < best[0]:
+            best = (gaps[a, b], t, a, b, ee)
+    gap, t, a, b, ee = best
+    other = ee["idx_nrm"].copy()
+    other[a] = b + 1 if ee["idx_nrm"][a] == b else b
+    one = oracle.pack_record(plan3, ee["gamma"], ee["idx_dir"], other)[None, :]
+    assert oracle.classify_both(plan3, keys[t:t + 1], s3, one, tol=gap * 1.01) == (plan3.n_tri - 1, 1, 0, 0)
+    assert oracle.classify_both(plan3, keys[t:t + 1], s3, one, tol=gap * 0.99) == (plan3.n_tri - 1, 0, 0, 1)
+
+
 def test_classifier_follows_the_rounding_mode():
     """Each mode's own records are all 'equal' under that mode; records of a weaker window are hard
     mismatches under a wider one wherever the codes differ (the windows really differ), and a record of
