@@ -409,11 +409,25 @@ __global__ __launch_bounds__(kWave) void rotate_queries_kernel(const void *__res
 template <int REP>
 __device__ __forceinline__ uint32_t lane_part(int lane) { return (static_cast<uint32_t>(lane) & (REP - 1)) << 4; }
 
-template <class P, int RG, int KPL>
+// Chunks of the score pass: 8 / RG triplets each.
+template <class P, int RG>
+constexpr int score_chunks() { return (P::NTRI + 8 / RG - 1) / (8 / RG); }
+
+struct NoChunkHook {
+    template <class C>
+    __device__ __forceinline__ void operator()(C) const {}
+};
+
+// `hook(integral_constant<chunk>)` is called once per chunk, after the requests of the next chunk and before
+// the arithmetic of this one: the caller's slot for work that is to be spread evenly over the pass (the
+// matrix-core kernel runs the previous step's P.V and requests this step's values there).  LDS reads the
+// hook issues are complete at the top of the next chunk.
+template <class P, int RG, int KPL, class Hook = NoChunkHook>
 __device__ __forceinline__ void tile_scores(const uint32_t (&w)[KPL][P::NWORDS], const float *__restrict__ qg,
-                                            const DecodeTables<P> &tb, int lane, float (&s)[KPL][RG]) {
+                                            const DecodeTables<P> &tb, int lane, float (&s)[KPL][RG],
+                                            const Hook &hook = Hook{}) {
     constexpr int CT = 8 / RG;                       // triplets per chunk
-    constexpr int NCHUNK = (P::NTRI + CT - 1) / CT;
+    constexpr int NCHUNK = score_chunks<P, RG>();
     constexpr int QC = CT * 3 * RG;                  // query floats per chunk
 #pragma unroll
     for (int k = 0; k < KPL; ++k)
@@ -496,6 +510,7 @@ __device__ __forceinline__ void tile_scores(const uint32_t (&w)[KPL][P::NWORDS],
         __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0): the inputs of this chunk have arrived
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (ci + 1 < NCHUNK) request(std::integral_constant<int, ci + 1>{});
+        hook(cc);
         static_for<0, cn>([&](auto tt) {
             constexpr int t = decltype(tt)::value;
             static_for<0, KPL>([&](auto kk) {
@@ -600,7 +615,7 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
     // clobbered by the kernel's stores and become scalar loads)
     constexpr int D = P::D;
     constexpr int KPL = decode_keys_per_lane<D>();
-    constexpr bool AHEAD = D <= 128;       // request a step's values during the previous step's P.V
+    constexpr bool AHEAD = D <= 128;       // P.V runs one step behind the scores, inside the next score pass
     constexpr int KS = 2 * KPL;            // k-steps of 32 keys per step
     constexpr int CPL = D / 16;            // channels per lane chunk = N-blocks
     constexpr int CW = CPL / 2;            // 32-bit words per chunk
@@ -651,17 +666,24 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
             const char *gp = src + g * (kWave * 16) + k_lane;
             constexpr int kFull = 4;
             const int n = (USED - 4 * g) < kFull ? (USED - 4 * g) : kFull;
+            // (global address space said explicitly: the laundered base pointer below would otherwise make these
+            // flat loads, which count against the LDS / scalar wait counter as well)
+            typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+            typedef const u32x4_t __attribute__((address_space(1))) *g4_t;
+            typedef const u32x3_t __attribute__((address_space(1))) *g3_t;
+            typedef const u32x2_t __attribute__((address_space(1))) *g2_t;
+            typedef const uint32_t __attribute__((address_space(1))) *g1_t;
             if (n == 4) {
-                const uint4 x = *reinterpret_cast<const uint4 *>(gp);
+                const u32x4_t x = *(g4_t)(gp);
                 w[4 * g] = x.x; w[4 * g + 1] = x.y; w[4 * g + 2] = x.z; w[4 * g + 3] = x.w;
             } else if (n == 3) {
-                const u32x3_t x = *reinterpret_cast<const u32x3_t *>(gp);
+                const u32x3_t x = *(g3_t)(gp);
                 w[4 * g] = x.x; w[4 * g + 1] = x.y; w[4 * g + 2] = x.z; w[4 * g + 3] = 0u;
             } else if (n == 2) {
-                const u32x2_t x = *reinterpret_cast<const u32x2_t *>(gp);
+                const u32x2_t x = *(g2_t)(gp);
                 w[4 * g] = x.x; w[4 * g + 1] = x.y; w[4 * g + 2] = 0u; w[4 * g + 3] = 0u;
             } else {
-                w[4 * g] = *reinterpret_cast<const uint32_t *>(gp);
+                w[4 * g] = *(g1_t)(gp);
                 w[4 * g + 1] = 0u; w[4 * g + 2] = 0u; w[4 * g + 3] = 0u;
             }
         }
@@ -785,11 +807,38 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
             }
         }
     };
-    uint32_t vr[KS][8][CW];  // the values of the step being worked on, then of the wave's next step
-    // One step.  Up to d = 128 its values were requested during the previous step's P.V, k-step by k-step
-    // as the registers became free, so that they are in flight during the whole score phase and the
-    // wavefront has loads outstanding at all times (at d = 256 they are requested at the top of the
-    // step: holding them longer costs register spills there); the records of the wave's next step are requested first thing
+    uint32_t vr[KS][8][CW];  // values: of the previous step until its P.V piece has run, then of the current step
+    // P.V of one step is cut into KS * CW pieces: piece (ks, q) multiplies the probabilities of k-step ks with
+    // the two channel blocks 2 q and 2 q + 1, whose B operands are byte permutes of word q of the k-step's
+    // eight value registers.  A piece's A operand (16 bytes of the probability rows in LDS) is read one
+    // piece ahead.
+    constexpr int NPIECE = KS * CW;
+    auto pv_operand = [&](int ks) {
+        return *reinterpret_cast<const uint4 *>(&sm.pbuf[wave][n16][32 * ks + 8 * g4]);
+    };
+    auto pv_piece = [&](auto pp, const uint4 &pa_bits) __attribute__((always_inline)) {
+        constexpr int ks = decltype(pp)::value / CW, q = decltype(pp)::value % CW;
+        union { uint4 u; bf16x8_t b; } pa;
+        pa.u = pa_bits;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            union { uint32_t u[4]; bf16x8_t b; } vb;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj)
+                vb.u[jj] = __builtin_amdgcn_perm(vr[ks][2 * jj + 1][q], vr[ks][2 * jj][q], h ? 0x07060302u : 0x05040100u);
+            acc[2 * q + h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa.b, vb.b, acc[2 * q + h], 0, 0, 0);
+        }
+    };
+    // One step.  Up to d = 128 the step is software pipelined with P.V one step behind the scores: the score
+    // pass of step n carries, spread over its chunks, the P.V pieces of step n - 1 (whose probabilities sit in
+    // LDS since the end of that step) and, as soon as the last piece of a k-step has read its value registers,
+    // the loads of step n's own values into them.  Matrix-core work thus overlaps the vector arithmetic of the
+    // scores, and -- what matters more with a single in-order wavefront per SIMD -- the value loads enter the
+    // compute unit's memory pipeline a k-step at a time at the pace of the arithmetic, not in one burst per step
+    // whose issue stalls the wavefront.  The first step of an item multiplies zeros (the value registers are
+    // cleared at the item's start), the last step's P.V runs after the loop.  At d = 256 (registers: holding a
+    // step's values across the score pass spills there) the values are requested at the top of the step and
+    // P.V follows the softmax.  The records of the wave's next step are requested first thing
     // and are used one call later.  The step loop below is unrolled by two with the two record buffers
     // swapping roles, so that no register copies (and no full memory wait in front of them) carry the
     // prefetched records over.
@@ -798,11 +847,10 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
                             __attribute__((always_inline)) {
         const int t0 = step * (KPL * kWave);
         const int n_valid = min(KPL * kWave, ww.len - t0);
-        // always issued (the wave's last step re-reads its own records, and requests values through an
-        // empty descriptor): a branch here would make the compiler wait for every outstanding load first
-        const bool has_next = step + ww.step_stride < ww.step_end;
+        // always issued (the wave's last step re-reads its own records): a branch here would make the compiler
+        // wait for every outstanding load first
         const int step_nx = min(step + ww.step_stride, ww.step_last);
-        __amdgpu_buffer_rsrc_t v_next[KPL];   // per tile of the step (all the same unless PAGED)
+        __amdgpu_buffer_rsrc_t v_cur[KPL];   // this step's values, per tile of the step (all the same unless PAGED)
         int64_t slot_nxt[KPL];
         if constexpr (PAGED) {
             page_slots(page_nxt, slot_nxt);
@@ -810,14 +858,12 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
         }
 #pragma unroll
         for (int k = 0; k < KPL; ++k) {
-            if constexpr (PAGED)
-                v_next[k] = AHEAD ? values_at(step_nx, k, slot_nxt[k], has_next) : values_at(step, k, slot_cur[k], true);
-            else
-                v_next[k] = AHEAD ? values_of(has_next ? step + ww.step_stride : step, has_next) : values_of(step, true);
+            if constexpr (PAGED) v_cur[k] = values_at(step, k, slot_cur[k], true);
+            else v_cur[k] = values_of(step, true);
         }
         if constexpr (!AHEAD) {   // d = 256: the registers hold one step's values only while it is worked on
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) load_values(v_next[ks / 2], ks, vr[ks]);
+            for (int ks = 0; ks < KS; ++ks) load_values(v_cur[ks / 2], ks, vr[ks]);
         }
         if constexpr (PAGED) {
             load_records_at(slot_nxt, w_next);
@@ -827,13 +873,39 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
             load_records(step_nx, w_next);
         }
         if constexpr (QJL) load_sidecar(min(step + ww.step_stride, ww.step_last), sc_next);
+        // The loads above feed the NEXT step, which sits behind a branch in the unrolled loop; without this
+        // barrier the compiler sinks them into that branch, i.e. to the top of the step that uses them, and
+        // every second step waits for a full memory round trip.
+        asm volatile("" ::: "memory");
         // D2-D4: scores (queries carry the softmax scale already).  The query offset (always 0) is
         // laundered per step: otherwise the loop-invariant scalar loads of the whole query are hoisted
         // out of the step loop and hundreds of scalar registers spill.
         float s[KPL][RG];
         int q_off = 0;
         asm volatile("" : "+s"(q_off));
-        tile_scores<P, RG, KPL>(w, qg + q_off, sm.tb, lane, s);
+        if constexpr (AHEAD) {
+            // chunk c runs pieces [c NPIECE / NCH, (c + 1) NPIECE / NCH) and reads the A operands of chunk c + 1's
+            constexpr int NCH = score_chunks<P, RG>();
+            uint4 pa_bits[NPIECE];
+            static_for<0, NPIECE / NCH>([&](auto pp) { pa_bits[decltype(pp)::value] = pv_operand(decltype(pp)::value / CW); });
+            auto pv_in_chunk = [&](auto cc) __attribute__((always_inline)) {
+                constexpr int ci = decltype(cc)::value;
+                constexpr int lo = ci * NPIECE / NCH, hi = (ci + 1) * NPIECE / NCH;
+                constexpr int hi_next = ci + 1 < NCH ? (ci + 2) * NPIECE / NCH : hi;
+                static_for<hi, hi_next>([&](auto pp) { pa_bits[decltype(pp)::value] = pv_operand(decltype(pp)::value / CW); });
+                static_for<lo, hi>([&](auto pp) {
+                    constexpr int pi = decltype(pp)::value;
+                    pv_piece(pp, pa_bits[pi]);
+                    if constexpr (pi % CW == CW - 1) load_values(v_cur[(pi / CW) / 2], pi / CW, vr[pi / CW]);
+                });
+            };
+            tile_scores<P, RG, KPL>(w, qg + q_off, sm.tb, lane, s, pv_in_chunk);
+            // the probabilities of the previous step have been read: the new ones may overwrite them
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        } else {
+            tile_scores<P, RG, KPL>(w, qg + q_off, sm.tb, lane, s);
+        }
 #pragma unroll
         for (int k = 0; k < KPL; ++k) {
             const float gamma = __uint_as_float(w[k][0]);
@@ -890,26 +962,12 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        // D6: P.V.  Per k-step: build the B operands, request the same k-step of the next step's values
-        // into the registers just read, multiply.
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            union { uint4 u; bf16x8_t b; } pa;
-            pa.u = *reinterpret_cast<const uint4 *>(&sm.pbuf[wave][n16][32 * ks + 8 * g4]);
-            union { uint32_t u[4]; bf16x8_t b; } vb[CPL];
-#pragma unroll
-            for (int c = 0; c < CPL; ++c)
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj)
-                    vb[c].u[jj] = __builtin_amdgcn_perm(vr[ks][2 * jj + 1][c / 2], vr[ks][2 * jj][c / 2],
-                                                        (c & 1) ? 0x07060302u : 0x05040100u);
-            if constexpr (AHEAD) load_values(v_next[ks / 2], ks, vr[ks]);
-#pragma unroll
-            for (int c = 0; c < CPL; ++c)
-                acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa.b, vb[c].b, acc[c], 0, 0, 0);
+        if constexpr (!AHEAD) {
+            // D6: P.V of this step
+            static_for<0, NPIECE>([&](auto pp) { pv_piece(pp, pv_operand(decltype(pp)::value / CW)); });
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
         }
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
     };
     uint32_t w_a[KPL][P::NWORDS], w_b[KPL][P::NWORDS];
     uint32_t sc_a[KPL][QW + 1], sc_b[KPL][QW + 1];
@@ -944,6 +1002,17 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
             k_region = reinterpret_cast<const char *>(cache) + ww.pair * shp.t_capacity * (P::GRANULES * 16);
             v_pair = reinterpret_cast<const char *>(v) + ww.pair * shp.t_capacity * ROWB;
         }
+        // The record pointer loses its "read-only, never aliased" provenance here: loads known to be invariant
+        // may be moved across any barrier, and the compiler then sinks the prefetch of the next step's records
+        // into the (conditional) step that uses them.
+        // (not at d = 256: holding the next step's records through a whole step spills registers there)
+        if constexpr (AHEAD) {
+            const uint64_t bits = reinterpret_cast<uint64_t>(k_region);
+            uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(bits));
+            uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(bits >> 32));
+            asm volatile("" : "+s"(lo), "+s"(hi));
+            k_region = reinterpret_cast<const char *>((static_cast<uint64_t>(hi) << 32) | lo);
+        }
 #pragma unroll
         for (int r = 0; r < RG; ++r) { m_run[r] = -INFINITY; l_lane[r] = 0.0f; }
 #pragma unroll
@@ -960,14 +1029,16 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
                 load_records(ww.step_begin, w_a);
             }
             if constexpr (QJL) load_sidecar(ww.step_begin, sc_a);
-            if constexpr (AHEAD) {
+        }
+        if constexpr (AHEAD) {
+            // The first step's P.V pieces multiply zeros (by whatever probabilities the previous item left in
+            // LDS).  The zeros come from loads through an empty descriptor, which move nothing: the wavefront
+            // then enters the step loop with the same sequence of outstanding loads as a later iteration has,
+            // and the wait counts the compiler derives for the loop are those of the steady state (it takes the
+            // stricter of the two ways into the loop).
+            const __amdgpu_buffer_rsrc_t v_none = values_of(0, false);
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    const __amdgpu_buffer_rsrc_t v_first =
-                        PAGED ? values_at(ww.step_begin, ks / 2, slot_cur[ks / 2], true) : values_of(ww.step_begin, true);
-                    load_values(v_first, ks, vr[ks]);
-                }
-            }
+            for (int ks = 0; ks < KS; ++ks) load_values(v_none, ks, vr[ks]);
         }
         if (!tables_built) {   // workgroup-uniform
             build_tables<P>(sm.tb, books, tid, kDecodeWaves * kWave);
@@ -976,6 +1047,11 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
         for (int step = ww.step_begin; step < ww.step_end; step += 2 * ww.step_stride) {
             process_step(step, w_a, w_b, sc_a, sc_b);
             if (step + ww.step_stride < ww.step_end) process_step(step + ww.step_stride, w_b, w_a, sc_b, sc_a);
+        }
+        if constexpr (AHEAD) {   // D6 of the wave's last step
+            static_for<0, NPIECE>([&](auto pp) { pv_piece(pp, pv_operand(decltype(pp)::value / CW)); });
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
         }
 
         // D7: add the hi and lo partial results (lane groups RP/4 apart) and emit the wave's partial of
