@@ -56,6 +56,7 @@ extern "C" {
 #define OCTOPUS_EUNSUPPORTED (-2) /* head_dim / bit width / dtype / head ratio not built in    */
 #define OCTOPUS_EWORKSPACE   (-3) /* workspace missing, misaligned or too small                */
 #define OCTOPUS_EHIP         (-4) /* the HIP runtime refused a launch                          */
+#define OCTOPUS_ESCRATCH     (-5) /* shapes exceed the static scratch of octopus_attn_decode_static */
 
 #define OCTOPUS_DTYPE_F32  0
 #define OCTOPUS_DTYPE_BF16 1
@@ -225,6 +226,29 @@ int octopus_attn_decode(const octopus_codebooks_t *cb,
                         float *out, float *scores_out,
                         void *workspace, size_t workspace_bytes,
                         void *stream);
+
+/* For callers that cannot allocate device memory -- code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc: octopus_attn_decode without the workspace arguments.  The rotated queries,
+ * the split-K partials and the work plan live in a static device array inside the library,
+ * OCTOPUS_STATIC_SCRATCH_BYTES bytes on every GPU the library runs on, held until the process ends.  The
+ * call allocates and frees nothing (the array's device address is looked up on the first call on a device).
+ *   Limit: shapes whose octopus_attn_decode_workspace(...) exceeds OCTOPUS_STATIC_SCRATCH_BYTES are refused
+ *   with OCTOPUS_ESCRATCH and nothing is launched (the Llama-shaped decode batch, 16 x 32 heads over 32768
+ *   tokens, needs about 19 MiB; a chunk of thousands of query rows does not fit: use octopus_attn_decode).
+ *   All calls on one GPU share the one array, which keeps the previous call's contents: calls that overlap
+ *   on a GPU (different streams, different threads) race; calls on one stream are ordered and safe.
+ * Arguments, results and the other errors are those of octopus_attn_decode, bit for bit. */
+#define OCTOPUS_STATIC_SCRATCH_BYTES (32 * 1024 * 1024)
+int octopus_attn_decode_static(const octopus_codebooks_t *cb,
+                               const void *q, int32_t q_dtype,
+                               int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q,
+                               const uint8_t *signs,
+                               const void *cache, int64_t t_capacity,
+                               const void *v, int32_t v_dtype,
+                               const int32_t *seq_lens, int64_t max_len,
+                               float scale,
+                               float *out, float *scores_out,
+                               void *stream);
 
 /* octopus_attn_decode with the QJL-corrected score of Sec. 3.6:
  *   score_t = scale * (q . k^_t + gamma_t * sqrt(pi / (2 d)) * gamma_r,t * (H diag(s') q_rot) . sigma_t),

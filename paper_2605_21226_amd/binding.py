@@ -12,7 +12,8 @@ import os
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "liboctopus.so")
 
-OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP, ESCRATCH = 0, -1, -2, -3, -4, -5
+STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
 DTYPE_F32, DTYPE_BF16 = 0, 1
 MAX_LEVELS = 64
 TILE = 64
@@ -22,7 +23,8 @@ EXPORTS = ("octopus_build_codebooks", "octopus_build_codebooks_pair", "octopus_c
            "octopus_qjl_bytes", "octopus_encode_qjl", "octopus_attn_decode_qjl",
            "octopus_encode_rounding", "octopus_vq_row_bytes", "octopus_vq_bytes", "octopus_encode_values",
            "octopus_attn_decode_vq", "octopus_attn_decode_hybrid",
-           "octopus_paged_pool_bytes", "octopus_encode_paged", "octopus_attn_decode_paged")
+           "octopus_paged_pool_bytes", "octopus_encode_paged", "octopus_attn_decode_paged",
+           "octopus_attn_decode_static")
 
 
 class Plan(ctypes.Structure):
@@ -102,6 +104,9 @@ def load():
     lib.octopus_attn_decode.argtypes = [CB, vp, i32, i32, i32, i32, i32, vp, vp, i64, vp, i32, vp, i64, f32, vp, vp,
                                         vp, ctypes.c_size_t, vp]
     lib.octopus_attn_decode.restype = ctypes.c_int
+    lib.octopus_attn_decode_static.argtypes = [CB, vp, i32, i32, i32, i32, i32, vp, vp, i64, vp, i32, vp, i64, f32, vp, vp,
+                                               vp]
+    lib.octopus_attn_decode_static.restype = ctypes.c_int
     lib.octopus_attn_decode_qjl.argtypes = [CB, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, i64, vp, i32, vp, i64, f32,
                                             vp, vp, vp, ctypes.c_size_t, vp]
     lib.octopus_attn_decode_qjl.restype = ctypes.c_int
@@ -226,6 +231,19 @@ def octopus_attn_decode(cb, q, signs, cache, t_capacity, v, seq_lens, max_len, s
                                       int(max_len), float(scale), _ptr(out), _ptr(scores_out), _ptr(workspace),
                                       int(workspace.numel() * workspace.element_size()), _stream_ptr(stream))
     _check(code, "octopus_attn_decode")
+
+
+def octopus_attn_decode_static(cb, q, signs, cache, t_capacity, v, seq_lens, max_len, scale, out, scores_out=None,
+                               stream=None):
+    """octopus_attn_decode without a workspace: the library's static scratch array serves (no allocation)."""
+    assert q.is_contiguous() and v.is_contiguous() and out.is_contiguous()
+    n_seq, n_q, n_qh, _ = q.shape
+    n_kv = v.shape[1]
+    code = load().octopus_attn_decode_static(ctypes.byref(cb), _ptr(q), _dtype_code(q), n_seq, n_qh, n_kv, n_q,
+                                             _ptr(signs), _ptr(cache), int(t_capacity), _ptr(v), _dtype_code(v),
+                                             _ptr(seq_lens), int(max_len), float(scale), _ptr(out), _ptr(scores_out),
+                                             _stream_ptr(stream))
+    _check(code, "octopus_attn_decode_static")
 
 
 def octopus_attn_decode_qjl(cb, q, signs, signs2, cache, qjl, t_capacity, v, seq_lens, max_len, scale, out, workspace,

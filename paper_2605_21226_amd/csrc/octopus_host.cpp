@@ -7,6 +7,8 @@
 #include <mutex>
 #include <vector>
 
+#include <hip/hip_runtime.h>
+
 #include "octopus_internal.h"
 
 namespace octopus {
@@ -571,6 +573,60 @@ int octopus_attn_decode(const octopus_codebooks_t *cb, const void *q, int32_t q_
                        nullptr);
 }
 
+// ---- the entry point that allocates nothing ---------------------------------------------------------
+// Scratch memory of octopus_attn_decode_static: a static device array, one copy per GPU for the life of the
+// process.  Its name is only a host-side handle here: the device address is asked for once per device
+// (hipGetSymbolAddress with that device current) and kept; kernels and everything else use that address.
+static __device__ __align__(256) unsigned char scratch[OCTOPUS_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device, or NULL (with *err set) if the runtime refuses.
+void *static_scratch(int *err) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        *err = OCTOPUS_EHIP;
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || ptr == nullptr) {
+            *err = OCTOPUS_EHIP;
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
+int octopus_attn_decode_static(const octopus_codebooks_t *cb, const void *q, int32_t q_dtype, int32_t n_seq,
+                               int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q, const uint8_t *signs,
+                               const void *cache, int64_t t_capacity, const void *v, int32_t v_dtype,
+                               const int32_t *seq_lens, int64_t max_len, float scale, float *out, float *scores_out,
+                               void *stream) {
+    const int ok = decode_args_ok(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len);
+    if (ok != OCTOPUS_OK) return ok;
+    // the shapes must fit the static array: refused here, before anything is looked up or launched
+    const size_t need = octopus_attn_decode_workspace(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len);
+    if (need == 0) return OCTOPUS_EINVAL;
+    if (need > static_cast<size_t>(OCTOPUS_STATIC_SCRATCH_BYTES)) return OCTOPUS_ESCRATCH;
+    int err = OCTOPUS_OK;
+    void *ws = static_scratch(&err);
+    if (ws == nullptr) return err;
+    // nothing in the scratch has to start at zero: the first kernel of the call writes the work plan and its
+    // counter, and every partial result that the merge reads is written by the call's own main kernel
+    return attn_decode(cb, q, q_dtype, n_seq, n_q_heads, n_kv_heads, n_q, signs, cache, t_capacity, v, v_dtype,
+                       seq_lens, max_len, scale, out, scores_out, ws, OCTOPUS_STATIC_SCRATCH_BYTES, stream, false,
+                       nullptr, nullptr);
+}
+
 int octopus_attn_decode_hybrid(const octopus_codebooks_t *cb, const void *q, int32_t q_dtype, int32_t n_seq,
                                int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q, const uint8_t *signs,
                                const void *cache, int64_t t_capacity, const void *v, int32_t v_dtype,
@@ -716,6 +772,8 @@ const char *octopus_strerror(int code) {
         case OCTOPUS_EUNSUPPORTED: return "unsupported head_dim, bit width, dtype or head ratio";
         case OCTOPUS_EWORKSPACE: return "workspace missing, misaligned or too small";
         case OCTOPUS_EHIP: return "HIP launch failed";
+        case OCTOPUS_ESCRATCH:
+            return "shapes need more scratch memory than the library's static array holds (OCTOPUS_STATIC_SCRATCH_BYTES)";
         default: return "unknown error";
     }
 }
