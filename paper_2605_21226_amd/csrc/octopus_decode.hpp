@@ -112,6 +112,39 @@ __device__ __forceinline__ void build_joint_table(float4 *table, const float *c_
     }
 }
 
+// ---- operands of the matrix-core score pass --------------------------------------------------------
+// fp32 -> two bf16 numbers whose sum represents it to about 2^-17 (round to nearest even both times; the
+// difference x - hi is exact in fp32).
+__device__ __forceinline__ uint32_t bf16_rne(float x) {
+    const uint32_t u = __float_as_uint(x);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+// (x, y, z) -> 16 bytes: bf16 hi of (x, y, z, 0), then bf16 lo of (x, y, z, 0): the k = 4 operand of
+// v_mfma_f32_4x4x4_16b_bf16, once for the leading parts and once for the remainders.
+__device__ __forceinline__ uint4 split_triplet(float x, float y, float z) {
+    const uint32_t hx = bf16_rne(x), hy = bf16_rne(y), hz = bf16_rne(z);
+    const uint32_t lx = bf16_rne(x - __uint_as_float(hx << 16)), ly = bf16_rne(y - __uint_as_float(hy << 16)),
+                   lz = bf16_rne(z - __uint_as_float(hz << 16));
+    return make_uint4(hx | (hy << 16), hz, lx | (ly << 16), lz);
+}
+
+// The joint table of a class with its entries in that form (same size and addressing as the fp32 table).
+template <int BD, int BN>
+__device__ __forceinline__ void build_joint_table_mx(float4 *table, const float *c_xi, const float *c_rho, int tid,
+                                                     int nthreads) {
+    using T = JointTable<BD, BN>;
+    constexpr int K = 1 << BD;
+    uint4 *out = reinterpret_cast<uint4 *>(table);
+    for (int e = tid; e < T::ENTRIES; e += nthreads) {
+        const int dir = e >> BN, nrm = e & ((1 << BN) - 1);
+        const float4 n = oct_decode(c_xi[dir & (K - 1)], c_xi[dir >> BD]);
+        const float rho = c_rho[nrm];
+        const uint4 val = split_triplet(rho * n.x, rho * n.y, rho * n.z);
+#pragma unroll
+        for (int r = 0; r < T::REP; ++r) out[e * T::REP + r] = val;
+    }
+}
+
 template <int BD, int BN>
 constexpr int dir_table_float4s() {
     return joint_codes(BD, BN) ? JointTable<BD, BN>::FLOAT4S : DirTable<BD>::FLOAT4S;
@@ -129,10 +162,22 @@ struct DecodeTables {
     float c_rho[2][8];
 };
 
+// Plans whose every class has a joint table (all up to 3 bits per coordinate) can score on the matrix cores.
 template <class P>
+constexpr bool mx_scores() { return DecodeTables<P>::J0 && (P::NCLASS == 1 || DecodeTables<P>::J1); }
+
+// MX: joint tables hold bf16 hi / lo operands (the matrix-core score pass) instead of fp32 vectors.
+template <class P, bool MX = false>
 __device__ __forceinline__ void build_tables(DecodeTables<P> &tb, const DeviceBooks &books, int tid, int nthreads) {
     if (tid < kWave) copy_books(books, tb.c_xi, tb.c_rho);
     __syncthreads();
+    if constexpr (MX) {
+        static_assert(mx_scores<P>(), "matrix-core scores need joint tables");
+        build_joint_table_mx<P::BD0, P::BN0>(tb.dir0, tb.c_xi[0], tb.c_rho[0], tid, nthreads);
+        if constexpr (P::NCLASS == 2) build_joint_table_mx<P::BD1, P::BN1>(tb.dir1, tb.c_xi[1], tb.c_rho[1], tid, nthreads);
+        __syncthreads();
+        return;
+    }
     if constexpr (DecodeTables<P>::J0) {
         build_joint_table<P::BD0, P::BN0>(tb.dir0, tb.c_xi[0], tb.c_rho[0], tid, nthreads);
     } else {
@@ -540,6 +585,108 @@ __device__ __forceinline__ void tile_scores(const uint32_t (&w)[KPL][P::NWORDS],
     });
 }
 
+// Byte offset, in the joint table of its class, of the entry of triplet I of the record `w` for this lane.
+template <class P, int I>
+__device__ __forceinline__ uint32_t joint_offset(const uint32_t (&w)[P::NWORDS], int lane) {
+    constexpr int bn = P::bnrm(I), bd = P::bdir(I);
+    using JT = JointTable<bd, bn>;
+    constexpr int nb = P::nrm_bit(I), db = P::dir_bit(I);
+    if constexpr (JT::BYTE_CODES && (nb & 31) + bn <= 32) {
+        const uint32_t dl = __builtin_amdgcn_perm(w[db >> 5], lane_part<JT::REP>(lane),
+                                                  0x0c0c0000u | ((4u + ((db & 31) >> 3)) << 8));
+        uint32_t nrm, off;
+        asm("v_bfe_u32 %0, %1, %2, %3" : "=v"(nrm) : "v"(w[nb >> 5]), "n"(nb & 31), "n"(bn));
+        asm("v_lshl_or_b32 %0, %1, %2, %3" : "=v"(off) : "v"(nrm), "n"(JT::NS), "v"(dl));
+        return off;
+    } else {
+        return (field<db, 2 * bd>(w) << JT::CS) | (field<nb, bn>(w) << JT::NS) | lane_part<JT::REP>(lane);
+    }
+}
+
+// ---- D2-D4 on the matrix cores ------------------------------------------------------------------------
+// Once the table entry of a triplet is in hand, its contribution to the scores of RG query rows is a dense
+// 4 x 4 x 4 product per group of four keys: rows x (x, y, z, 0) times (x, y, z, 0) x keys.
+// v_mfma_f32_4x4x4_16b_bf16 multiplies 16 such blocks at once: lane l supplies row l % 4 of A and column
+// l % 4 of B of block l / 4 (four bf16 each) and receives column l % 4 of D, register v = row v.  With
+// A = the rotated queries (row l % 4; the same in every block) and B = the table entry of lane l's own key,
+// lane l ends up with the scores of ITS key for four query rows: the layout the softmax below expects, with
+// no cross-lane traffic.  fp32 accuracy comes from bf16 pairs: q = q_hi + q_lo, entry = e_hi + e_lo, and
+// three products per triplet (hi hi, lo hi, hi lo; the dropped lo lo term is below 2^-16 of the product),
+// accumulated in fp32 by the instruction.
+//
+// Query operands of a work item, staged in LDS by the workgroup: entry (triplet i, row r) = split_triplet of
+// (q_rot[r][3 i], q_rot[r][3 i + 1], q_rot[r][3 i + 2]); rows are padded to a multiple of four with zeros.
+template <class P, int RG>
+struct QueryOperands {
+    static constexpr int ROWS = RG <= 4 ? 4 : 8;
+    uint4 e[P::NTRI][ROWS];
+};
+
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef float mx_f32x4_t __attribute__((ext_vector_type(4)));
+
+// All operands come from LDS (no scalar loads in the pass), so the hardware counter of outstanding LDS reads
+// is exact and the reads of a triplet can be issued LA triplets before its products.  `hook` as in
+// tile_scores, called every 8 / RG triplets.
+template <class P, int RG, int KPL, class Hook = NoChunkHook>
+__device__ __forceinline__ void tile_scores_mx(const uint32_t (&w)[KPL][P::NWORDS], const QueryOperands<P, RG> &qop,
+                                               const DecodeTables<P> &tb, int lane, float (&s)[KPL][RG],
+                                               const Hook &hook = Hook{}) {
+    constexpr int CT = 8 / RG;
+    constexpr int NSET = QueryOperands<P, RG>::ROWS / 4;
+    constexpr int LA = P::NTRI < 4 ? P::NTRI : 4;   // triplets requested ahead
+    constexpr int NB = LA + 1;
+    uint4 ev[NB][KPL], qv[NB][NSET];
+    mx_f32x4_t d_main[KPL][NSET], d_cross[KPL][NSET];
+#pragma unroll
+    for (int k = 0; k < KPL; ++k)
+#pragma unroll
+        for (int h = 0; h < NSET; ++h) {
+            d_main[k][h] = mx_f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+            d_cross[k][h] = mx_f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+        }
+    const char *q_lane = reinterpret_cast<const char *>(&qop.e[0][0]) + (lane & 3) * 16;
+    auto request = [&](auto ii) __attribute__((always_inline)) {
+        constexpr int i = decltype(ii)::value;
+        constexpr int slot = i % NB;
+        constexpr int c = P::cls(i);
+#pragma unroll
+        for (int k = 0; k < KPL; ++k)
+            ev[slot][k] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(c ? tb.dir1 : tb.dir0) +
+                                                           joint_offset<P, i>(w[k], lane));
+#pragma unroll
+        for (int h = 0; h < NSET; ++h)
+            qv[slot][h] = *reinterpret_cast<const uint4 *>(q_lane + (i * QueryOperands<P, RG>::ROWS + 4 * h) * 16);
+    };
+    static_for<0, LA>(request);
+    static_for<0, P::NTRI>([&](auto ii) {
+        constexpr int i = decltype(ii)::value;
+        constexpr int slot = i % NB;
+        if constexpr (i + LA < P::NTRI) request(std::integral_constant<int, i + LA>{});
+        if constexpr (i % CT == 0) hook(std::integral_constant<int, i / CT>{});
+#pragma unroll
+        for (int h = 0; h < NSET; ++h) {
+            union { uint32_t u[2]; s16x4_t v; } q_hi, q_lo;
+            q_hi.u[0] = qv[slot][h].x; q_hi.u[1] = qv[slot][h].y;
+            q_lo.u[0] = qv[slot][h].z; q_lo.u[1] = qv[slot][h].w;
+#pragma unroll
+            for (int k = 0; k < KPL; ++k) {
+                union { uint32_t u[2]; s16x4_t v; } e_hi, e_lo;
+                e_hi.u[0] = ev[slot][k].x; e_hi.u[1] = ev[slot][k].y;
+                e_lo.u[0] = ev[slot][k].z; e_lo.u[1] = ev[slot][k].w;
+                d_main[k][h] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(q_hi.v, e_hi.v, d_main[k][h], 0, 0, 0);
+                d_cross[k][h] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(q_lo.v, e_hi.v, d_cross[k][h], 0, 0, 0);
+                d_cross[k][h] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(q_hi.v, e_lo.v, d_cross[k][h], 0, 0, 0);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    });
+#pragma unroll
+    for (int k = 0; k < KPL; ++k)
+#pragma unroll
+        for (int r = 0; r < RG; ++r) s[k][r] = d_main[k][r / 4][r % 4] + d_cross[k][r / 4][r % 4];
+}
+
 template <int RG>
 __device__ __forceinline__ void store_scores(const DecodeShape &shp, const WaveWork &ww, float *scores_out, int tok,
                                              const float (&s)[RG]) {
@@ -593,7 +740,8 @@ template <class P, int RG>
 constexpr int qjl_table_floats() { return (P::D / 8) * 256 * RG; }
 template <class P, int RG>
 constexpr bool qjl_fits() {
-    return sizeof(DecodeSmemMfma<P, decode_keys_per_lane<P::D>()>) + qjl_table_floats<P, RG>() * 4 + 64 <= 160 * 1024;
+    return sizeof(DecodeSmemMfma<P, decode_keys_per_lane<P::D>()>) + qjl_table_floats<P, RG>() * 4 +
+               sizeof(QueryOperands<P, RG>) + 64 <= 160 * 1024;
 }
 
 // SCORES: also store the scaled scores (a second instantiation, so that the usual one carries none of
@@ -626,8 +774,11 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
     constexpr int QW = D / 32;             // sign words per key of the QJL side-car
     constexpr int TQ = kWave * (D / 8 + 2);  // side-car bytes per tile
     // static, so that table addresses are compile-time constants that fold into the LDS instructions
+    constexpr bool MX = mx_scores<P>();    // scores on the matrix cores (every plan up to 3 bits per coordinate)
     __shared__ DecodeSmemMfma<P, KPL> sm;
     __shared__ __attribute__((aligned(16))) float qtab[QJL ? qjl_table_floats<P, RG>() : 4];
+    __shared__ __attribute__((aligned(16))) uint4 qop_store[MX ? P::NTRI * QueryOperands<P, RG>::ROWS : 1];
+    const QueryOperands<P, RG> &qop = *reinterpret_cast<const QueryOperands<P, RG> *>(&qop_store[0]);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
@@ -899,12 +1050,14 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
                     if constexpr (pi % CW == CW - 1) load_values(v_cur[(pi / CW) / 2], pi / CW, vr[pi / CW]);
                 });
             };
-            tile_scores<P, RG, KPL>(w, qg + q_off, sm.tb, lane, s, pv_in_chunk);
+            if constexpr (MX) tile_scores_mx<P, RG, KPL>(w, qop, sm.tb, lane, s, pv_in_chunk);
+            else tile_scores<P, RG, KPL>(w, qg + q_off, sm.tb, lane, s, pv_in_chunk);
             // the probabilities of the previous step have been read: the new ones may overwrite them
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             __builtin_amdgcn_wave_barrier();
         } else {
-            tile_scores<P, RG, KPL>(w, qg + q_off, sm.tb, lane, s);
+            if constexpr (MX) tile_scores_mx<P, RG, KPL>(w, qop, sm.tb, lane, s);
+            else tile_scores<P, RG, KPL>(w, qg + q_off, sm.tb, lane, s);
         }
 #pragma unroll
         for (int k = 0; k < KPL; ++k) {
@@ -1041,8 +1194,25 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
             for (int ks = 0; ks < KS; ++ks) load_values(v_none, ks, vr[ks]);
         }
         if (!tables_built) {   // workgroup-uniform
-            build_tables<P>(sm.tb, books, tid, kDecodeWaves * kWave);
+            build_tables<P, MX>(sm.tb, books, tid, kDecodeWaves * kWave);
             tables_built = true;
+        }
+        if constexpr (MX) {
+            // The item's rotated queries as matrix-core operands.  Every wavefront is past the previous item
+            // here (next_item's barriers, or this is the workgroup's only item).
+            constexpr int ROWS = QueryOperands<P, RG>::ROWS;
+            uint4 *dst = reinterpret_cast<uint4 *>(&qop_store[0]);
+            for (int e = tid; e < P::NTRI * ROWS; e += kDecodeWaves * kWave) {
+                const int i = e / ROWS, r = e % ROWS;
+                float x = 0.0f, y = 0.0f, z = 0.0f;
+                if (r < RG) {   // (the rotated queries are stored [coordinate][row], zero past d)
+                    x = qg[(3 * i) * RG + r];
+                    y = qg[(3 * i + 1) * RG + r];
+                    z = qg[(3 * i + 2) * RG + r];
+                }
+                dst[e] = split_triplet(x, y, z);
+            }
+            __syncthreads();
         }
         for (int step = ww.step_begin; step < ww.step_end; step += 2 * ww.step_stride) {
             process_step(step, w_a, w_b, sc_a, sc_b);
