@@ -5,16 +5,21 @@ One step = one pass of the whole hot path over one batch of synthetic input resi
 prefill-time encode of every cached token (octopus_encode) followed by one decode-attention step
 over the compressed cache (octopus_attn_decode: query rotation, fused split-K kernel, merge).
 
-Workload: the Llama-3-8B-shaped GQA decode configuration (batch 16, 32 query heads over 8 KV heads,
-head_dim 128, 32768 cached tokens per sequence, bf16 keys / values / queries, 3 bits per coordinate).
+Headline workload: the Llama-3-8B-shaped GQA decode configuration (batch 16, 32 query heads over 8 KV
+heads, head_dim 128, 32768 cached tokens per sequence, bf16 keys / values / queries, 3 bits per
+coordinate).
 
 Prints ONE JSON line.  `value` is the effective HBM rate of the decode-attention call: algorithmic
 bytes (per key: the 58-byte canonical record + the 256-byte bf16 value row; plus queries and outputs)
-divided by the call's average duration, measured with events on the launch stream.  `roofline`
-is the same byte count over the fused kernel's own duration (events recorded by the library around
-its launch), against the published 8 TB/s.
+divided by the call's average duration over the timed steps, measured with events on the launch stream.
+`roofline` is the same byte count over the fused kernel's own duration (events recorded by the library
+around its launch), against the published 8 TB/s.  `workloads` holds the other named configurations
+(30 warm-up + 50 timed calls, median: the protocol of the paper's kernel table), `encode_roofline` the
+encoder against the fp32 vector issue rate, `cpu_baseline` the oracle on the host cores.
 """
 import argparse
+import ctypes
+import hashlib
 import json
 import os
 import sys
@@ -26,8 +31,12 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 KERNEL_EVENT_STRIDE = 4        # every 4th timed step carries the event pair around the dominant kernel
-FP32_VALU_PEAK_TFLOPS = 157.3  # MI355X published fp32 vector peak
+FP32_VALU_PEAK_TFLOPS = 157.3  # MI355X published fp32 vector peak (packed fp32; 2 flops per lane-op)
+# fp32 lane-operations per second without packed math (this library builds with packed fp32 off):
+# 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz = a quarter of the published flop rate
+FP32_LANE_OPS_PER_S = FP32_VALU_PEAK_TFLOPS * 1e12 / 4.0
 BF16_MFMA_PEAK_TFLOPS = 2500.0 # MI355X published dense bf16 matrix peak
+PROTOCOL_WARMUP, PROTOCOL_TIMED = 30, 50   # App. G: 30 warm-up + 50 timed iterations, median
 
 
 def parse():
@@ -36,7 +45,11 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama3_8b_decode")
+    ap.add_argument("--bits", type=float, default=None,
+                    help="bits per coordinate (1, 1.5, 2, 2.5, 3, 4) instead of the workload's own")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the `workloads` block (the other named configurations)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--rounding", type=int, default=1,
                     help="encoder rounding mode (App. E): 0 seed only, 1 local 3x3 (default), 2 full grid, "
@@ -59,10 +72,27 @@ def parse():
     return ap.parse_args()
 
 
+def encode_lane_ops_per_key(head_dim):
+    """Algorithmic fp32 lane-operations of Alg. 1 per key: the Walsh-Hadamard butterflies (d log2 d add / sub), norm,
+    scale and sign flip (3 d), and per triplet the octahedral map with the two seed searches (14), nine candidate
+    evaluations of 3 multiply-adds + compare + select + index (9 x 6) and the norm index + packing (8)."""
+    n_tri = (head_dim + 2) // 3
+    return head_dim * (head_dim.bit_length() - 1) + 3 * head_dim + n_tri * (14 + 9 * 6 + 8)
+
+
+def set_omp_threads(n):
+    try:
+        ctypes.CDLL("libgomp.so.1").omp_set_num_threads(int(n))
+        return True
+    except OSError:
+        return False
+
+
 def cpu_baseline(wl, keys, vals, q, signs, scale, record_bytes, budget_s=12.0, signs2=None, mode=1, vq=None):
     """The oracle as it stands, timed on this machine's host cores on a bounded sample of the workload:
     whole sequences (all KV heads, all cached tokens; encode, then attention of each KV head's group of
-    query heads over its tokens), one sequence after another until about `budget_s` seconds are spent."""
+    query heads over its tokens), one sequence after another until about `budget_s` seconds are spent;
+    then one (sequence, KV head) pair once more on a single thread."""
     import numpy as np
 
     import oracle
@@ -103,9 +133,10 @@ def cpu_baseline(wl, keys, vals, q, signs, scale, record_bytes, budget_s=12.0, s
     n_keys = n_seq_done * n_tok * wl.n_kv_heads
     elt = 2 if wl.dtype == "bf16" else 4
     v_bytes = oracle.vq_row_bytes(wl.head_dim, vq[0], vq[1]) if vq is not None else wl.head_dim * elt
-    dec_bytes = n_keys * (record_bytes + v_bytes + (wl.head_dim // 8 + 2 if signs2 is not None else 0))
+    key_bytes = record_bytes + v_bytes + (wl.head_dim // 8 + 2 if signs2 is not None else 0)
+    dec_bytes = n_keys * key_bytes
     threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-    return {
+    result = {
         "value": round(dec_bytes / dec_s / 1e9, 4),
         "unit": "GB/s",
         "cores": min(threads, os.cpu_count() or threads),
@@ -118,13 +149,42 @@ def cpu_baseline(wl, keys, vals, q, signs, scale, record_bytes, budget_s=12.0, s
         "encode_seconds": round(enc_s, 3),
         "encode_mtokens_per_s": round(n_seq_done * n_tok / enc_s / 1e6, 4),
     }
+    # the same code on ONE thread, on one (sequence, KV head) pair of the sample (plain variant)
+    if signs2 is None and vq is None and set_omp_threads(1):
+        n1 = min(n_tok, 32768)
+        t0 = time.perf_counter()
+        rec1 = oracle.encode(plan, k_heads[0][:n1], signs[0], mode=mode)
+        t1 = time.perf_counter()
+        oracle.attention(plan, rec1, signs[0], q_host[:, :g].reshape(-1, wl.head_dim), v_host[0][:n1], scale)
+        t2 = time.perf_counter()
+        set_omp_threads(threads)
+        result["one_thread"] = {
+            "sample": f"one (sequence, KV head) pair, {n1} keys, {g} query heads" + (f" x {nq_s} queries" if wl.n_q > 1 else ""),
+            "encode_seconds": round(t1 - t0, 3), "decode_seconds": round(t2 - t1, 3),
+            "decode_gb_per_s": round(n1 * key_bytes / (t2 - t1) / 1e9, 4),
+            "encode_mkeys_per_s": round(n1 / (t1 - t0) / 1e6, 4),
+            # the whole workload on one thread at this rate (keys scale linearly)
+            "whole_workload_seconds_extrapolated": round((t2 - t0) * (wl.n_seq * wl.n_kv_heads * n_tok / n1), 1),
+        }
+    return result
 
 
-def measured_traffic(workload, kernel="decode_kernel_mfma"):
+def kernel_source_digest():
+    """First 16 hex digits of the SHA-256 of the decode kernels' sources: what a traffic summary under profiles/
+    records, so that a summary measured on other code is not reported as this build's."""
+    h = hashlib.sha256()
+    for name in ("octopus_decode.hpp", "octopus_decode_mq.hpp", "octopus_device.hpp"):
+        with open(os.path.join(ROOT, "paper_2605_21226_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload, kernel="decode_kernel_mfma", profiles_dir=None):
     """HBM bytes per launch of the dominant decode kernel as measured with rocprofv3 --pmc FETCH_SIZE /
     WRITE_SIZE (scaled by a plain copy of known size); read from the committed profile summary of this
-    kernel and workload, None if there is none."""
-    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_traffic.txt")
+    kernel and workload.  -> (bytes or None, note).  None when there is no summary or when it was taken on
+    other kernel sources than the ones in this tree (KERNEL_SOURCE_SHA in the summary)."""
+    path = os.path.join(profiles_dir or os.path.join(ROOT, "profiles"), f"{kernel}_{workload}_traffic.txt")
     try:
         vals = {}
         with open(path) as f:
@@ -132,9 +192,273 @@ def measured_traffic(workload, kernel="decode_kernel_mfma"):
                 if "=" in line and not line.startswith("#"):
                     k, v = line.split("=", 1)
                     vals[k.strip()] = v.strip()
-        return int(float(vals["FETCH_BYTES_PER_LAUNCH"]) + float(vals["WRITE_BYTES_PER_LAUNCH"]))
+        total = int(float(vals["FETCH_BYTES_PER_LAUNCH"]) + float(vals["WRITE_BYTES_PER_LAUNCH"]))
     except (OSError, KeyError, ValueError):
-        return None
+        return None, "no traffic summary under profiles/ for this kernel and workload"
+    sha, commit = vals.get("KERNEL_SOURCE_SHA"), vals.get("MEASURED_AT_COMMIT", "unknown")
+    if sha != kernel_source_digest():
+        return None, f"the traffic summary (commit {commit}) was taken on other kernel sources than this tree's"
+    return total, f"rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, measured at commit {commit} on these kernel sources"
+
+
+class Run:
+    """One workload resident in device memory, with closures for its encode and decode calls."""
+
+    def __init__(self, wl, args, dev, variants=True):
+        import numpy as np
+        import torch
+
+        from paper_2605_21226_amd import binding, synth
+        from paper_2605_21226_amd.synth_device import device_inputs
+
+        self.wl, self.args, self.dev = wl, args, dev
+        self.qjl = bool(args.qjl) and variants
+        self.paged = bool(args.paged) and variants
+        self.window = args.window if variants else 0
+        self.rounding = args.rounding if variants else 1
+        self.v_bits, self.v_group = ((int(x) for x in args.vq.split(":")) if (args.vq and variants) else (0, 0))
+        self.many_rows = wl.n_q > 1
+        self.cb = cb = binding.octopus_build_codebooks(wl.head_dim, wl.bits)
+        self.keys, self.vals, self.q, self.signs, lens = device_inputs(wl, args.seed, dev)
+        self.cap = cap = -(-wl.n_tokens // 64) * 64
+        if cap != wl.n_tokens:                      # the values need t_capacity rows
+            padded = torch.zeros((wl.n_seq, wl.n_kv_heads, cap, wl.head_dim), dtype=self.vals.dtype, device=dev)
+            padded[:, :, :wl.n_tokens] = self.vals
+            self.vals = padded
+        self.sbits = torch.from_numpy(synth.sign_bits(self.signs)).to(dev)
+        self.cache = torch.zeros(binding.octopus_cache_bytes(cb, wl.n_seq, wl.n_kv_heads, cap), dtype=torch.uint8,
+                                 device=dev)
+        self.k_win = self.win_dev = None
+        if self.window:
+            # the last `window` tokens of every sequence stay uncompressed; the compressed part shrinks by as much
+            win = np.minimum(lens, self.window).astype(np.int32)
+            self.k_win = torch.zeros((wl.n_seq, wl.n_kv_heads, self.window, wl.head_dim), dtype=self.keys.dtype,
+                                     device=dev)
+            for s_i in range(wl.n_seq):
+                a, b = int(lens[s_i] - win[s_i]), int(lens[s_i])
+                self.k_win[s_i, :, :b - a] = self.keys[s_i, a:b].permute(1, 0, 2)
+            lens = (lens - win).astype(np.int32)
+            self.win_dev = torch.from_numpy(win).to(dev)
+        self.lens = lens
+        self.max_len = int(lens.max())
+        self.ws = torch.empty(binding.octopus_attn_decode_workspace(cb, wl.n_seq, wl.n_q_heads, wl.n_kv_heads, wl.n_q,
+                                                                    self.max_len), dtype=torch.uint8, device=dev)
+        self.out = torch.zeros((wl.n_seq, wl.n_q, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device=dev)
+        self.lens_dev = torch.from_numpy(lens).to(dev)
+        self.scale = 1.0 / float(np.sqrt(wl.head_dim))
+        # single-query workloads: prefill-time encode of the whole cache; a chunk workload: the cache is
+        # filled up to the chunk once, and a step encodes the chunk's tokens at their position
+        self.n_new = wl.n_new if self.many_rows else wl.n_tokens
+        self.first = wl.n_tokens - self.n_new
+        self.start_dev = None
+        if self.first > 0:
+            binding.octopus_encode(cb, self.keys[:, :self.first], self.sbits, self.cache, cap)
+            self.start_dev = torch.full((wl.n_seq,), self.first, dtype=torch.int32, device=dev)
+        self.signs2 = self.s2bits = self.side = None
+        if self.qjl:
+            self.signs2 = synth.sign_vectors(args.seed + 1, wl.n_kv_heads, wl.head_dim)
+            self.s2bits = torch.from_numpy(synth.sign_bits(self.signs2)).to(dev)
+            self.side = torch.zeros(binding.octopus_qjl_bytes(cb, wl.n_seq, wl.n_kv_heads, cap), dtype=torch.uint8,
+                                    device=dev)
+        self.vq = self.vals_tok = None
+        if self.v_bits:
+            self.vq = torch.zeros(binding.octopus_vq_bytes(wl.head_dim, self.v_bits, self.v_group, wl.n_seq,
+                                                           wl.n_kv_heads, cap), dtype=torch.uint8, device=dev)
+            self.vals_tok = self.vals.permute(0, 2, 1, 3)[:, :wl.n_tokens]      # [n_seq, n_tokens, n_kv_heads, d] view
+        self.table = self.k_pool = self.v_pool = None
+        if self.paged:
+            tiles = cap // 64
+            self.n_pages = n_pages = wl.n_seq * tiles + 7
+            gen = torch.Generator(device="cpu").manual_seed(args.seed + 5)
+            self.table = (torch.randperm(n_pages, generator=gen)[:wl.n_seq * tiles].to(torch.int32)
+                          .reshape(wl.n_seq, tiles).to(dev))
+            self.k_pool = torch.zeros(binding.octopus_paged_pool_bytes(cb, n_pages, wl.n_kv_heads), dtype=torch.uint8,
+                                      device=dev)
+            self.v_pool = torch.zeros((n_pages, wl.n_kv_heads, 64, wl.head_dim), dtype=self.vals.dtype, device=dev)
+            self.v_pool[self.table.reshape(-1).long()] = (
+                self.vals.reshape(wl.n_seq, wl.n_kv_heads, tiles, 64, wl.head_dim).permute(0, 2, 1, 3, 4)
+                .reshape(-1, wl.n_kv_heads, 64, wl.head_dim))
+
+    def encode(self):
+        from paper_2605_21226_amd import binding
+        cb, cap = self.cb, self.cap
+        if self.v_bits:
+            binding.octopus_encode_values(self.vals_tok, self.v_bits, self.v_group, self.vq, cap)
+        if self.qjl:
+            binding.octopus_encode_qjl(cb, self.keys[:, self.first:], self.sbits, self.s2bits, self.cache, self.side, cap,
+                                       self.start_dev)
+        elif self.paged:
+            binding.octopus_encode_paged(cb, self.keys, self.sbits, self.k_pool, self.n_pages, self.table)
+        elif self.rounding != 1:
+            binding.octopus_encode_rounding(cb, self.keys[:, self.first:], self.sbits, self.cache, cap, self.rounding,
+                                            self.start_dev)
+        else:
+            binding.octopus_encode(cb, self.keys[:, self.first:], self.sbits, self.cache, cap, self.start_dev)
+
+    def decode(self):
+        from paper_2605_21226_amd import binding
+        cb, cap, wl = self.cb, self.cap, self.wl
+        if self.qjl:
+            binding.octopus_attn_decode_qjl(cb, self.q, self.sbits, self.s2bits, self.cache, self.side, cap, self.vals,
+                                            self.lens_dev, self.max_len, self.scale, self.out, self.ws)
+        elif self.window:
+            binding.octopus_attn_decode_hybrid(cb, self.q, self.sbits, self.cache, cap, self.vals, self.lens_dev,
+                                               self.max_len, self.k_win, self.win_dev, self.scale, self.out, self.ws)
+        elif self.v_bits:
+            binding.octopus_attn_decode_vq(cb, self.q, self.sbits, self.cache, cap, self.vq, self.v_bits, self.v_group,
+                                           wl.n_kv_heads, self.lens_dev, self.max_len, self.scale, self.out, self.ws)
+        elif self.paged:
+            binding.octopus_attn_decode_paged(cb, self.q, self.sbits, self.k_pool, self.v_pool, self.table, self.lens_dev,
+                                              self.max_len, self.scale, self.out, self.ws)
+        else:
+            binding.octopus_attn_decode(cb, self.q, self.sbits, self.cache, cap, self.vals, self.lens_dev, self.max_len,
+                                        self.scale, self.out, self.ws)
+
+    # ---- byte and flop counts -----------------------------------------------------------------------
+    def decode_bytes(self):
+        from paper_2605_21226_amd import binding
+        import numpy as np
+        wl = self.wl
+        elt = 2 if wl.dtype == "bf16" else 4
+        n_keys = int(self.lens.astype(np.int64).sum()) * wl.n_kv_heads
+        q_out = wl.n_seq * wl.n_q * wl.n_q_heads * wl.head_dim * (elt + 4)
+        side = wl.head_dim // 8 + 2 if self.qjl else 0     # sign bits + fp16 residual norm per key
+        v_row = binding.octopus_vq_row_bytes(wl.head_dim, self.v_bits, self.v_group) if self.v_bits else wl.head_dim * elt
+        total = n_keys * (self.cb.plan.record_bytes + side + v_row) + q_out
+        if self.window:       # window tokens: native key and value rows
+            total += int(self.win_dev.sum().item()) * wl.n_kv_heads * 2 * wl.head_dim * elt
+        return total, n_keys, side, v_row
+
+    def uses_mq(self):
+        wl = self.wl
+        return (self.many_rows and wl.head_dim <= 128 and wl.n_q * (wl.n_q_heads // wl.n_kv_heads) >= 32 and
+                wl.dtype == "bf16")
+
+    def dominant_kernel(self):
+        return "decode_kernel_valu" if self.v_bits else ("decode_kernel_mq" if self.uses_mq() else "decode_kernel_mfma")
+
+    def dense_flops(self):
+        import numpy as np
+        wl = self.wl
+        return 4.0 * wl.head_dim * wl.n_q * wl.n_q_heads * float(self.lens.astype(np.int64).sum())
+
+
+def timed_calls(fn, warmup, timed):
+    """ms per call of `fn` (device time between events on the launch stream), after `warmup` untimed calls."""
+    import numpy as np
+    import torch
+    for _ in range(warmup):
+        fn()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(timed)]
+    for a, b in ev:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    return np.array([a.elapsed_time(b) for a, b in ev])
+
+
+def kernel_times(run, calls):
+    """ms of the fused kernel alone inside `calls` decode calls (events recorded by the library around its launch)."""
+    import numpy as np
+    import torch
+    from paper_2605_21226_amd import binding
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(calls)]
+    for a, b in ev:          # a first record creates the HIP handles the library records into
+        a.record()
+        b.record()
+    torch.cuda.synchronize()
+    for a, b in ev:
+        binding.octopus_profile_events(a, b)
+        run.decode()
+    torch.cuda.synchronize()
+    return np.array([a.elapsed_time(b) for a, b in ev])
+
+
+def roofline_of(run, ker_s, dec_bytes):
+    """The roofline entry of the run's dominant decode kernel for a kernel time of ker_s seconds."""
+    wl = run.wl
+    kernel = run.dominant_kernel()
+    if run.uses_mq():
+        # hundreds of query rows per key: a dense contraction on the matrix cores, 4 d flops per (query row, key)
+        flops = run.dense_flops()
+        tf = flops / ker_s / 1e12
+        return {"kernel": kernel, "bound": "mfma", "achieved": round(tf, 2), "peak": BF16_MFMA_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(tf / BF16_MFMA_PEAK_TFLOPS, 4), "dense_flops_per_launch": flops,
+                "note": "achieved counts the flops of dense attention on the reconstructed keys (2 d for q.k and 2 d "
+                        "for p.v per query row and key); the kernel issues 2.5 times as many bf16 matrix flops, because "
+                        "scores and probabilities go through the bf16 units as hi + lo pairs to keep fp32 accuracy"}
+    gbs = dec_bytes / ker_s / 1e9
+    return {"kernel": kernel, "bound": "hbm", "achieved": round(gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(gbs / HBM_PEAK_GBS, 4)}
+
+
+def measure_extra(run, encode_calls=8):
+    """One of the other named workloads under the 30 + 50 median protocol: back-to-back decode calls on a cache
+    encoded once, the fused kernel alone, and the encode call."""
+    import numpy as np
+    import torch
+    wl = run.wl
+    enc_ms = timed_calls(run.encode, 2, encode_calls)
+    dec_ms = timed_calls(run.decode, PROTOCOL_WARMUP, PROTOCOL_TIMED)
+    ker_ms = kernel_times(run, 20)
+    assert bool(torch.isfinite(run.out).all())
+    dec_bytes, n_keys, _, _ = run.decode_bytes()
+    med, ker = float(np.median(dec_ms)), float(np.median(ker_ms))
+    res = {
+        "bits": wl.bits, "record_bytes": run.cb.plan.record_bytes, "keys": n_keys,
+        "decode_ms": round(med, 4), "decode_ms_min": round(float(dec_ms.min()), 4),
+        "effective_gb_per_s": round(dec_bytes / (med * 1e-3) / 1e9, 1),
+        "pct_of_hbm_peak": round(100.0 * dec_bytes / (med * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
+        "kernel_ms": round(ker, 4),
+        "roofline": roofline_of(run, ker * 1e-3, dec_bytes),
+        "encode_ms": round(float(np.median(enc_ms)), 4),
+        "encode_tokens": wl.n_seq * run.n_new,
+        "encode_mtokens_per_s": round(wl.n_seq * run.n_new / (float(np.median(enc_ms)) * 1e-3) / 1e6, 3),
+    }
+    return res
+
+
+def streaming_append(run):
+    """Config 3's encode side: ONE new token per sequence per call, appended at the end of a full cache (the cache
+    holds n_tokens - 1 tokens; the call writes the last slot of every sequence).  us per call, 30 + 50 median."""
+    import numpy as np
+    import torch
+    from paper_2605_21226_amd import binding
+    wl = run.wl
+    pos = torch.full((wl.n_seq,), wl.n_tokens - 1, dtype=torch.int32, device=run.dev)
+    last = run.keys[:, wl.n_tokens - 1:wl.n_tokens]
+    ms = timed_calls(lambda: binding.octopus_encode(run.cb, last, run.sbits, run.cache, run.cap, pos), PROTOCOL_WARMUP,
+                     PROTOCOL_TIMED)
+    return {"tokens_per_call": wl.n_seq, "keys_per_call": wl.n_seq * wl.n_kv_heads,
+            "us_per_call": round(float(np.median(ms)) * 1e3, 2), "us_per_call_min": round(float(ms.min()) * 1e3, 2)}
+
+
+def extras(args, dev):
+    """The other configurations of the contract, each generated, measured and released in turn."""
+    import dataclasses
+    import torch
+    from paper_2605_21226_amd import synth
+    out = {}
+    plan = [("tiny", None), ("long_context_2bit", None), ("causal_video", None)] + \
+           [("ragged_d256", b) for b in (1.5, 2.0, 2.5, 3.0, 4.0)]
+    for name, bits in plan:
+        wl = synth.WORKLOADS[name]
+        if bits is not None:
+            wl = dataclasses.replace(wl, bits=bits)
+        try:
+            run = Run(wl, args, dev, variants=False)
+            res = measure_extra(run, encode_calls=4 if name == "ragged_d256" else 8)
+            if name == "tiny":
+                res["note"] = "2.3 MB working set, resident in cache: a latency figure, not a bandwidth one"
+            if name == "long_context_2bit":
+                res["streaming_append"] = streaming_append(run)
+            out[name if bits is None else f"{name}@{bits:g}"] = res
+        except Exception as exc:    # a failing extra must not take the headline line with it
+            out[name if bits is None else f"{name}@{bits:g}"] = {"error": f"{type(exc).__name__}: {exc}"}
+        run = None
+        torch.cuda.empty_cache()
+    return out
 
 
 def main():
@@ -146,11 +470,12 @@ def main():
               file=sys.stderr)
         sys.exit(2)
 
+    import dataclasses
+
     import numpy as np
     import torch
 
     from paper_2605_21226_amd import binding, synth
-    from paper_2605_21226_amd.synth_device import device_inputs
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -158,8 +483,9 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     wl = synth.WORKLOADS[args.workload]
+    if args.bits is not None:
+        wl = dataclasses.replace(wl, bits=float(args.bits))
     many_rows = wl.n_q > 1
-    v_bits, v_group = (int(x) for x in args.vq.split(":")) if args.vq else (0, 0)
     if args.vq and (many_rows or args.qjl):
         print("bench.py: --vq times single-query workloads without --qjl", file=sys.stderr)
         sys.exit(2)
@@ -175,93 +501,20 @@ def main():
     if args.qjl and many_rows:
         print("bench.py: --qjl times single-query workloads only", file=sys.stderr)
         sys.exit(2)
+    variant = bool(args.qjl or args.vq or args.window or args.paged or args.rounding != 1)
 
-    cb = binding.octopus_build_codebooks(wl.head_dim, wl.bits)
-    keys, vals, q, signs, lens = device_inputs(wl, args.seed, dev)
-    cap = -(-wl.n_tokens // 64) * 64
-    if cap != wl.n_tokens:                      # the values need t_capacity rows
-        padded = torch.zeros((wl.n_seq, wl.n_kv_heads, cap, wl.head_dim), dtype=vals.dtype, device=dev)
-        padded[:, :, :wl.n_tokens] = vals
-        vals = padded
-    sbits = torch.from_numpy(synth.sign_bits(signs)).to(dev)
-    cache = torch.zeros(binding.octopus_cache_bytes(cb, wl.n_seq, wl.n_kv_heads, cap), dtype=torch.uint8, device=dev)
-    k_win = win_dev = None
-    if args.window:
-        # the last `window` tokens of every sequence stay uncompressed; the compressed part shrinks by as much
-        win = np.minimum(lens, args.window).astype(np.int32)
-        k_win = torch.zeros((wl.n_seq, wl.n_kv_heads, args.window, wl.head_dim), dtype=keys.dtype, device=dev)
-        for s_i in range(wl.n_seq):
-            a, b = int(lens[s_i] - win[s_i]), int(lens[s_i])
-            k_win[s_i, :, :b - a] = keys[s_i, a:b].permute(1, 0, 2)
-        lens = (lens - win).astype(np.int32)
-        win_dev = torch.from_numpy(win).to(dev)
-    max_len = int(lens.max())
-    ws = torch.empty(binding.octopus_attn_decode_workspace(cb, wl.n_seq, wl.n_q_heads, wl.n_kv_heads, wl.n_q, max_len),
-                     dtype=torch.uint8, device=dev)
-    out = torch.zeros((wl.n_seq, wl.n_q, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device=dev)
-    lens_dev = torch.from_numpy(lens).to(dev)
-    scale = 1.0 / float(np.sqrt(wl.head_dim))
-    # single-query workloads: prefill-time encode of the whole cache; a chunk workload: the cache is
-    # filled up to the chunk once, and a step encodes the chunk's tokens at their position
-    n_new = wl.n_new if many_rows else wl.n_tokens
-    first = wl.n_tokens - n_new
-    start_dev = None
-    if first > 0:
-        binding.octopus_encode(cb, keys[:, :first], sbits, cache, cap)
-        start_dev = torch.full((wl.n_seq,), first, dtype=torch.int32, device=dev)
-
-    signs2 = s2bits = side = None
-    if args.qjl:
-        signs2 = synth.sign_vectors(args.seed + 1, wl.n_kv_heads, wl.head_dim)
-        s2bits = torch.from_numpy(synth.sign_bits(signs2)).to(dev)
-        side = torch.zeros(binding.octopus_qjl_bytes(cb, wl.n_seq, wl.n_kv_heads, cap), dtype=torch.uint8, device=dev)
-
-    vq = vals_tok = None
-    if args.vq:
-        vq = torch.zeros(binding.octopus_vq_bytes(wl.head_dim, v_bits, v_group, wl.n_seq, wl.n_kv_heads, cap),
-                         dtype=torch.uint8, device=dev)
-        vals_tok = vals.permute(0, 2, 1, 3)[:, :wl.n_tokens]      # [n_seq, n_tokens, n_kv_heads, d] view
-
-    table = k_pool = v_pool = None
-    if args.paged:
-        tiles = cap // 64
-        n_pages = wl.n_seq * tiles + 7
-        gen = torch.Generator(device="cpu").manual_seed(args.seed + 5)
-        table = torch.randperm(n_pages, generator=gen)[:wl.n_seq * tiles].to(torch.int32).reshape(wl.n_seq, tiles).to(dev)
-        k_pool = torch.zeros(binding.octopus_paged_pool_bytes(cb, n_pages, wl.n_kv_heads), dtype=torch.uint8, device=dev)
-        v_pool = torch.zeros((n_pages, wl.n_kv_heads, 64, wl.head_dim), dtype=vals.dtype, device=dev)
-        v_pool[table.reshape(-1).long()] = (vals.reshape(wl.n_seq, wl.n_kv_heads, tiles, 64, wl.head_dim)
-                                            .permute(0, 2, 1, 3, 4).reshape(-1, wl.n_kv_heads, 64, wl.head_dim))
+    run = Run(wl, args, dev)
+    cb = run.cb
 
     def step(ev=None, kernel_events=False):
         if ev:
             ev[0].record()
-        if args.vq:
-            binding.octopus_encode_values(vals_tok, v_bits, v_group, vq, cap)
-        if args.qjl:
-            binding.octopus_encode_qjl(cb, keys[:, first:], sbits, s2bits, cache, side, cap, start_dev)
-        elif args.paged:
-            binding.octopus_encode_paged(cb, keys, sbits, k_pool, n_pages, table)
-        elif args.rounding != 1:
-            binding.octopus_encode_rounding(cb, keys[:, first:], sbits, cache, cap, args.rounding, start_dev)
-        else:
-            binding.octopus_encode(cb, keys[:, first:], sbits, cache, cap, start_dev)
+        run.encode()
         if ev:
             ev[1].record()
             if kernel_events:
                 binding.octopus_profile_events(ev[3], ev[4])  # around the fused kernel inside the next call
-        if args.qjl:
-            binding.octopus_attn_decode_qjl(cb, q, sbits, s2bits, cache, side, cap, vals, lens_dev, max_len, scale, out, ws)
-        elif args.window:
-            binding.octopus_attn_decode_hybrid(cb, q, sbits, cache, cap, vals, lens_dev, max_len, k_win, win_dev, scale,
-                                               out, ws)
-        elif args.vq:
-            binding.octopus_attn_decode_vq(cb, q, sbits, cache, cap, vq, v_bits, v_group, wl.n_kv_heads, lens_dev, max_len,
-                                           scale, out, ws)
-        elif args.paged:
-            binding.octopus_attn_decode_paged(cb, q, sbits, k_pool, v_pool, table, lens_dev, max_len, scale, out, ws)
-        else:
-            binding.octopus_attn_decode(cb, q, sbits, cache, cap, vals, lens_dev, max_len, scale, out, ws)
+        run.decode()
         if ev:
             ev[2].record()
 
@@ -287,23 +540,21 @@ def main():
     dec_ms_all = np.array([e[1].elapsed_time(e[2]) for e in events])
     dec_ms = dec_ms_all[~with_kernel_events] if (~with_kernel_events).any() else dec_ms_all
     ker_ms = np.array([e[3].elapsed_time(e[4]) for e, k in zip(events, with_kernel_events) if k])
-    assert bool(torch.isfinite(out).all())
+    assert bool(torch.isfinite(run.out).all())
 
-    elt = 2 if wl.dtype == "bf16" else 4
-    n_keys_dec = int(lens.astype(np.int64).sum()) * wl.n_kv_heads
+    dec_bytes, n_keys_dec, side_bytes, v_row_bytes = run.decode_bytes()
+    n_new = run.n_new
     n_keys_enc = wl.n_seq * n_new * wl.n_kv_heads
     rec_bytes = cb.plan.record_bytes
-    q_out_bytes = wl.n_seq * wl.n_q * wl.n_q_heads * wl.head_dim * (elt + 4)
-    side_bytes = wl.head_dim // 8 + 2 if args.qjl else 0     # sign bits + fp16 residual norm per key
-    v_row_bytes = binding.octopus_vq_row_bytes(wl.head_dim, v_bits, v_group) if args.vq else wl.head_dim * elt
-    dec_bytes = n_keys_dec * (rec_bytes + side_bytes + v_row_bytes) + q_out_bytes
-    n_keys_win = int(win_dev.sum().item()) * wl.n_kv_heads if args.window else 0
-    dec_bytes += n_keys_win * 2 * wl.head_dim * elt          # window tokens: native key and value rows
     dec_s = float(dec_ms.mean()) * 1e-3
     enc_s = float(enc_ms.mean()) * 1e-3
     gbs = dec_bytes / dec_s / 1e9
     ker_s = float(ker_ms.mean()) * 1e-3
-    ker_gbs = dec_bytes / ker_s / 1e9
+
+    # after the timed region: the same decode call back to back on the cache as it stands (no re-encode between
+    # calls), under the 30 + 50 median protocol, and the fused kernel alone in that setting
+    b2b_ms = timed_calls(run.decode, PROTOCOL_WARMUP, PROTOCOL_TIMED)
+    b2b_ker_ms = kernel_times(run, 20)
 
     result = {
         "metric": "fused decode-attn effective HBM GB/s (% of peak); encode Mtokens/s",
@@ -316,11 +567,11 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "bf16",
         "data": "synthetic",
         "config": {
             "workload": f"{wl.name}{' + QJL residual' if args.qjl else ''}"
-                        f"{f' + values quantised to {v_bits} bits in groups of {v_group}' if args.vq else ''}"
+                        f"{f' + values quantised to {run.v_bits} bits in groups of {run.v_group}' if args.vq else ''}"
                         f"{' + paged cache (64-token pages in random order)' if args.paged else ''}: batch {wl.n_seq}, {wl.n_q_heads} query / {wl.n_kv_heads} KV heads, head_dim "
                         f"{wl.head_dim}, {wl.n_tokens} cached tokens, {wl.dtype} K/V/Q, {wl.bits:g} bits/coordinate "
                         f"(b_dir {cb.plan.b_dir[0]}, b_nrm {cb.plan.b_nrm[0]}); step = encode of "
@@ -333,57 +584,70 @@ def main():
             "window_tokens": args.window,
             "encode_phase_includes_value_quantisation": bool(args.vq),
             "keys": n_keys_dec,
+            "arithmetic": "inputs bf16 (fp32 for the tiny workload); scores and P.V on the bf16 matrix cores with hi + lo "
+                          "operand pairs and fp32 accumulation (relative error below 2^-16), softmax in fp32",
         },
         "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
         "decode_ms": round(dec_s * 1e3, 4),
         "decode_ms_median": round(float(np.median(dec_ms)), 4),
         "decode_ms_steps_with_kernel_events": round(float(dec_ms_all[with_kernel_events].mean()), 4),
         "kernel_event_steps": int(with_kernel_events.sum()),
+        "decode_back_to_back": {
+            "what": f"{PROTOCOL_TIMED} decode calls in a row after {PROTOCOL_WARMUP} warm-up calls, no encode between them "
+                    "(the timed steps above re-encode the whole cache before every decode call)",
+            "decode_ms_median": round(float(np.median(b2b_ms)), 4),
+            "decode_ms_min": round(float(b2b_ms.min()), 4),
+            "kernel_ms_median": round(float(np.median(b2b_ker_ms)), 4),
+            "pct_of_hbm_peak_call": round(100.0 * dec_bytes / (float(np.median(b2b_ms)) * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
+            "frac_kernel": round(dec_bytes / (float(np.median(b2b_ker_ms)) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        },
         "encode_ms": round(enc_s * 1e3, 4),
         "encode_mtokens_per_s": round(wl.n_seq * n_new / enc_s / 1e6, 3),
         "encode_mkeys_per_s": round(n_keys_enc / enc_s / 1e6, 3),
-        "roofline": {
-            "kernel": "decode_kernel_mfma (the fused split-K decode kernel inside octopus_attn_decode), timed "
-                      "with HIP events recorded by the library around its launch on the launch stream, on every "
-                      f"{KERNEL_EVENT_STRIDE}th step of the timed region",
-            "bound": "hbm",
-            "achieved": round(ker_gbs, 2),
-            "peak": HBM_PEAK_GBS,
-            "unit": "GB/s",
-            "frac": round(ker_gbs / HBM_PEAK_GBS, 4),
-            "traffic": None,
-            "algorithmic_bytes_per_launch": dec_bytes,
-            "kernel_ms": round(ker_s * 1e3, 4),
-        },
     }
-    uses_mq = (many_rows and wl.head_dim <= 128 and wl.n_q * (wl.n_q_heads // wl.n_kv_heads) >= 32 and
-               wl.dtype == "bf16")
-    dominant = "decode_kernel_valu" if args.vq else ("decode_kernel_mq" if uses_mq else "decode_kernel_mfma")
-    result["roofline"]["traffic"] = None if (args.window or args.paged) else measured_traffic(
-        wl.name + ("_qjl" if args.qjl else "") + (f"_vq{v_bits}g{v_group}" if args.vq else ""), dominant)
-    if args.vq:
-        result["roofline"]["kernel"] = result["roofline"]["kernel"].replace("decode_kernel_mfma", "decode_kernel_valu")
-    if uses_mq:
-        # hundreds of query rows per key: a dense contraction on the matrix cores, 4 d flops per (query row, key)
-        flops = 4.0 * wl.head_dim * wl.n_q * wl.n_q_heads * float(lens.astype(np.int64).sum())
-        tf = flops / ker_s / 1e12
-        result["roofline"].update({
-            "kernel": "decode_kernel_mq (decode attention for many query rows on the matrix cores), timed with HIP "
-                      "events recorded by the library around its launch on the launch stream",
-            "bound": "mfma", "achieved": round(tf, 2), "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": round(tf / BF16_MFMA_PEAK_TFLOPS, 4), "dense_flops_per_launch": flops,
-            "note": "achieved counts the flops of dense attention on the reconstructed keys (2 d for q.k and 2 d for "
-                    "p.v per query row and key); the kernel issues 2.5 times as many bf16 matrix flops, because "
-                    "scores and probabilities go through the bf16 units as hi + lo pairs to keep fp32 accuracy"})
+    roof = roofline_of(run, ker_s, dec_bytes)
+    roof["kernel"] = (f"{roof['kernel']} (the fused decode kernel inside the decode call), timed with HIP events recorded by "
+                      f"the library around its launch on the launch stream, on every {KERNEL_EVENT_STRIDE}th step of the "
+                      "timed region")
+    roof["algorithmic_bytes_per_launch"] = dec_bytes
+    roof["kernel_ms"] = round(ker_s * 1e3, 4)
+    if args.window or args.paged:
+        roof["traffic"], roof["traffic_source"] = None, "not measured for this variant"
+    else:
+        roof["traffic"], roof["traffic_source"] = measured_traffic(
+            wl.name + ("_qjl" if args.qjl else "") + (f"_vq{run.v_bits}g{run.v_group}" if args.vq else ""),
+            run.dominant_kernel())
+    result["roofline"] = roof
+    # the encoder against the fp32 vector units (its bound: plain ALU work, not HBM, not the matrix cores)
+    ops = encode_lane_ops_per_key(wl.head_dim)
+    result["encode_roofline"] = {
+        "kernel": "encode_kernel", "bound": "alu",
+        "achieved": round(ops * n_keys_enc / enc_s / 1e12, 3), "peak": round(FP32_LANE_OPS_PER_S / 1e12, 3),
+        "unit": "T lane-ops/s", "frac": round(ops * n_keys_enc / enc_s / FP32_LANE_OPS_PER_S, 4),
+        "algorithmic_lane_ops_per_key": ops,
+        "note": "peak = fp32 lane-operations per second without packed math (256 CUs x 64 lanes x 2.4 GHz = the "
+                "published 157.3 TFLOP/s / 4); algorithmic operations per key as counted in "
+                "bench.encode_lane_ops_per_key",
+        "hbm_frac": round((n_keys_enc * (wl.head_dim * (2 if wl.dtype == "bf16" else 4) + cb.plan.granules * 16)) /
+                          enc_s / 1e9 / HBM_PEAK_GBS, 4),
+    }
     if args.calibration_copy:
         src = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
+        del src, dst
     if not args.no_cpu_baseline and not args.window:      # (the baseline leg times the plain variants)
-        result["cpu_baseline"] = cpu_baseline(wl, keys, vals, q, signs, scale, rec_bytes, signs2=signs2, mode=args.rounding,
-                                              vq=(v_bits, v_group) if args.vq else None)
+        result["cpu_baseline"] = cpu_baseline(wl, run.keys, run.vals, run.q, run.signs, run.scale, rec_bytes,
+                                              signs2=run.signs2, mode=args.rounding,
+                                              vq=(run.v_bits, run.v_group) if args.vq else None)
+    if not args.no_extras and not variant and args.workload == "llama3_8b_decode" and args.bits is None:
+        run = None
+        torch.cuda.empty_cache()
+        result["protocol_of_workloads"] = (f"{PROTOCOL_WARMUP} warm-up + {PROTOCOL_TIMED} timed decode calls back to back on a "
+                                           "cache encoded once, median; kernel_ms: the fused kernel alone, median of 20")
+        result["workloads"] = extras(args, dev)
     print(json.dumps(result))
 
 
