@@ -66,6 +66,10 @@ def parse():
     ap.add_argument("--paged", action="store_true",
                     help="paged cache: 64-token pages handed out in a random order from pools (octopus_encode_paged + "
                          "octopus_attn_decode_paged); single-query bf16 workloads, plain variant only")
+    ap.add_argument("--read-probe", action="store_true",
+                    help="instead of the benchmark: time a plain streaming read of 1.25 GiB (octopus_probe_read), with and "
+                         "without the non-temporal hint, and print the rates: the read rate this machine reaches with "
+                         "nothing else to do, to set beside the published peak")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy (torch) three times, so that a rocprofv3 "
                          "--pmc run of this command can scale FETCH_SIZE / WRITE_SIZE by a kernel of known size")
@@ -434,6 +438,24 @@ def streaming_append(run):
             "us_per_call": round(float(np.median(ms)) * 1e3, 2), "us_per_call_min": round(float(ms.min()) * 1e3, 2)}
 
 
+def read_probe(dev):
+    """Plain streaming reads of 1.25 GiB (about the bytes of one decode call of the headline workload)."""
+    import numpy as np
+    import torch
+    from paper_2605_21226_amd import binding
+    data = torch.zeros(1342177280, dtype=torch.uint8, device=dev)
+    sink = torch.zeros(4, dtype=torch.uint8, device=dev)
+    rows = []
+    for nt in (0, 1):
+        for n_wg in (1024, 2048, 4096, 8192):
+            ms = timed_calls(lambda: binding.octopus_probe_read(data, nt, n_wg, sink), 5, 30)
+            rows.append({"nontemporal": bool(nt), "workgroups": n_wg, "ms_median": round(float(np.median(ms)), 4),
+                         "gb_per_s": round(data.numel() / (float(np.median(ms)) * 1e-3) / 1e9, 1),
+                         "frac_of_8_tb_per_s": round(data.numel() / (float(np.median(ms)) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)})
+    return {"probe": "plain streaming read, 16 bytes per lane, 256 threads per workgroup", "bytes": data.numel(),
+            "protocol": "5 warm-up + 30 timed launches, median", "results": rows}
+
+
 def extras(args, dev):
     """The other configurations of the contract, each generated, measured and released in turn."""
     import dataclasses
@@ -482,6 +504,9 @@ def main():
         sys.exit(1)
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.read_probe:
+        print(json.dumps(read_probe(dev)))
+        return
     wl = synth.WORKLOADS[args.workload]
     if args.bits is not None:
         wl = dataclasses.replace(wl, bits=float(args.bits))

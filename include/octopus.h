@@ -121,8 +121,9 @@ size_t octopus_cache_bytes(const octopus_codebooks_t *cb, int32_t n_seq, int32_t
  *               s_j = -1 (Eq. (rotation): one sign vector per head).
  *   cache       device, 16-byte aligned, layout above; token t of sequence s is
  *               written to slot start_pos[s] + t.  Other slots are untouched.
- *   start_pos   device [n_seq] int32, or NULL for all zeros.  Slots beyond
- *               t_capacity are not written (the caller must size the cache).
+ *   start_pos   device [n_seq] int32 >= 0 (a negative entry is read as 0), or NULL
+ *               for all zeros.  Slots beyond t_capacity are not written (the
+ *               caller must size the cache).
  * Errors: EINVAL (also n_seq or n_kv_heads above 65535), EUNSUPPORTED (plan /
  * dtype without a kernel; centroids not ascending, or two boundaries of C_xi closer than 1 / (4 * 2^b_dir), which the
  * kernel's seed search does not resolve -- never the case for the codebooks
@@ -350,15 +351,6 @@ int octopus_attn_decode_vq(const octopus_codebooks_t *cb,
                            void *workspace, size_t workspace_bytes,
                            void *stream);
 
-/* Measurement aid (not part of the method): the next octopus_attn_decode call made by this thread
- * records the HIP events `before` and `after` (hipEvent_t passed as void*, caller-owned, created
- * with timing enabled) on the call's stream immediately before and after the launch of the fused
- * split-K decode kernel, i.e. around Alg. 2 proper without the query rotation and the split merge.
- * The handles are forgotten after that call; NULL, NULL cancels.  Returns OCTOPUS_OK, or
- * OCTOPUS_EINVAL if only one of the two is NULL. */
-int octopus_profile_events(void *before, void *after);
-
-/* Static, human-readable name of an error code. */
 /* ---- paged cache (an integration layout; the paper's Sec. 4 recipe leaves the cache's storage open) ----
  * The cache of a sequence need not be contiguous: tokens live in pages of 64 (one tile of the layout
  * above), handed out from pools shared by all sequences, and a block table maps a sequence's logical
@@ -375,8 +367,9 @@ int octopus_profile_events(void *before, void *after);
  * octopus_encode_paged: arguments as octopus_encode with (cache, t_capacity) replaced by the pool and
  * the table; a sequence can hold max_pages_per_seq * 64 tokens, tokens past that are dropped.
  * octopus_attn_decode_paged: arguments as octopus_attn_decode (bf16 values only, no scores_out);
- * max_len <= max_pages_per_seq * 64; query rows are served in groups of at most 8 per KV head (the
- * many-row kernel is not built for pages).  Workspace: octopus_attn_decode_workspace of the same
+ * max_len <= max_pages_per_seq * 64; query rows are served in groups of at most 8 per KV head; 32 or more
+ * query rows per KV head (n_q * n_q_heads / n_kv_heads) are refused with EUNSUPPORTED, because the many-row
+ * kernel is not built for pages.  Workspace: octopus_attn_decode_workspace of the same
  * shapes.  Errors: EINVAL for NULL / misaligned pointers, n_pages < 1, max_pages_per_seq < 1 and the
  * conditions of the contiguous calls; EUNSUPPORTED / EWORKSPACE / EHIP as there. */
 size_t octopus_paged_pool_bytes(const octopus_codebooks_t *cb, int32_t n_pages, int32_t n_kv_heads);
@@ -403,7 +396,24 @@ int octopus_attn_decode_paged(const octopus_codebooks_t *cb,
                               void *workspace, size_t workspace_bytes,
                               void *stream);
 
+/* Static, human-readable name of an error code. */
 const char *octopus_strerror(int code);
+
+/* ---- measurement aids (not part of the method; nothing above depends on them) ----
+ * octopus_profile_events: the next decode-attention call made by this thread (octopus_attn_decode, its _static,
+ * _qjl, _vq and _hybrid forms, octopus_attn_decode_paged) records the HIP events `before` and `after` (hipEvent_t
+ * passed as void*, caller-owned, created with timing enabled) on the call's stream immediately before and after
+ * the launch of its fused decode kernel, i.e. around Alg. 2 proper without the query rotation and the split
+ * merge.  The handles are per thread and are forgotten by that call whether it succeeds or not; NULL, NULL
+ * cancels.  Returns OCTOPUS_OK, or OCTOPUS_EINVAL if only one of the two is NULL. */
+int octopus_profile_events(void *before, void *after);
+
+/* octopus_probe_read: a plain streaming read of `bytes` bytes of device memory at `data` (16-byte aligned) by
+ * n_workgroups workgroups of 256 threads, each walking its contiguous share with 16-byte loads, non-temporal or
+ * not: the reference that says what read rate the machine reaches with nothing else to do.  `sink`: 4 bytes of
+ * device memory (practically never written).  Errors: EINVAL, EHIP. */
+int octopus_probe_read(const void *data, size_t bytes, int32_t nontemporal, int32_t n_workgroups, void *sink,
+                       void *stream);
 
 #ifdef __cplusplus
 }

@@ -39,6 +39,38 @@ OCTOPUS_DECL(128)
 OCTOPUS_DECL(256)
 #undef OCTOPUS_DECL
 
+// Measurement aid: a plain streaming read of `bytes` bytes (16 bytes per lane, every workgroup walks its own
+// contiguous share front to back, 8 loads in flight per lane), with or without the non-temporal hint.
+template <bool NT>
+__global__ __launch_bounds__(256) void probe_read_kernel(const uint32_t *__restrict__ p, int64_t units_per_block,
+                                                         uint32_t *__restrict__ sink) {
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+    const u32x4_t *base = reinterpret_cast<const u32x4_t *>(p) + static_cast<int64_t>(blockIdx.x) * units_per_block;
+    uint32_t acc = 0;
+    for (int64_t i = threadIdx.x; i < units_per_block; i += 256 * 8) {
+        u32x4_t x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int64_t j = min(i + u * 256, units_per_block - 1);
+            x[u] = NT ? __builtin_nontemporal_load(base + j) : base[j];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += x[u].x ^ x[u].y ^ x[u].z ^ x[u].w;
+    }
+    if (acc == 0x9e3779b9u) sink[0] = acc;   // (keeps the loads alive; practically never taken)
+}
+
+int launch_probe_read(const void *data, int64_t bytes, int nontemporal, int n_blocks, void *sink, void *stream) {
+    const int64_t units = bytes / 16 / n_blocks;
+    if (nontemporal)
+        hipLaunchKernelGGL(probe_read_kernel<true>, dim3(n_blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                           static_cast<const uint32_t *>(data), units, static_cast<uint32_t *>(sink));
+    else
+        hipLaunchKernelGGL(probe_read_kernel<false>, dim3(n_blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                           static_cast<const uint32_t *>(data), units, static_cast<uint32_t *>(sink));
+    return static_cast<int>(hipGetLastError());
+}
+
 int record_event(void *event, void *stream) {
     return static_cast<int>(hipEventRecord(static_cast<hipEvent_t>(event), static_cast<hipStream_t>(stream)));
 }

@@ -1315,7 +1315,8 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) void decode_kernel_valu(
         const uint4 *src = region + static_cast<int64_t>(tile) * (P::GRANULES * kWave) + lane;
 #pragma unroll
         for (int g = 0; g < P::GRANULES; ++g) {
-            const uint4 x = src[g * kWave];
+            typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+            const u32x4_t x = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(src + g * kWave));   // streamed
             w[4 * g] = x.x; w[4 * g + 1] = x.y; w[4 * g + 2] = x.z; w[4 * g + 3] = x.w;
         }
         // VQ: the tile's quantised value words are requested here, so that they arrive during the scores.

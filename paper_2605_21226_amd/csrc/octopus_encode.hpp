@@ -230,7 +230,7 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int kvh = blockIdx.y, seq = blockIdx.z;
-    const int64_t start = start_pos ? start_pos[seq] : 0;
+    const int64_t start = start_pos ? max(start_pos[seq], 0) : 0;   // (a negative position would write before the cache)
     const int64_t tok_end = min(start + n_new, t_capacity);
     const int64_t first_tile = start / kWave + static_cast<int64_t>(blockIdx.x) * kEncodeTilesPerGroup;
     if (max(first_tile * kWave, start) >= tok_end) return;
@@ -271,7 +271,11 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
             if (valid) {
                 const int64_t off = head_base + (tok - start) * stride_tok + col;
                 if constexpr (BF16) {
-                    raw[pass][0] = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(keys) + off);
+                    // 16 threads read one whole 256- or 512-byte row: streamed, read once (non-temporal)
+                    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+                    const u32x4_t x = __builtin_nontemporal_load(
+                        reinterpret_cast<const u32x4_t *>(static_cast<const uint16_t *>(keys) + off));
+                    raw[pass][0] = make_uint4(x.x, x.y, x.z, x.w);
                 } else {
                     raw[pass][0] = *reinterpret_cast<const uint4 *>(static_cast<const float *>(keys) + off);
                     raw[pass][BF16 ? 0 : 1] = *reinterpret_cast<const uint4 *>(static_cast<const float *>(keys) + off + 4);

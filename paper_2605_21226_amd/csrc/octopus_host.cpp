@@ -325,6 +325,15 @@ int octopus_profile_events(void *before, void *after) {
     return OCTOPUS_OK;
 }
 
+int octopus_probe_read(const void *data, size_t bytes, int32_t nontemporal, int32_t n_workgroups, void *sink,
+                       void *stream) {
+    if (data == nullptr || sink == nullptr || !aligned(data, 16) || !aligned(sink, 4)) return OCTOPUS_EINVAL;
+    if (n_workgroups < 1 || n_workgroups > (1 << 20) || bytes / 16 / static_cast<size_t>(n_workgroups) < 1)
+        return OCTOPUS_EINVAL;
+    const int err = launch_probe_read(data, static_cast<int64_t>(bytes), nontemporal != 0, n_workgroups, sink, stream);
+    return err == 0 ? OCTOPUS_OK : OCTOPUS_EHIP;
+}
+
 int octopus_build_codebooks(int32_t head_dim, float bits, octopus_codebooks_t *out) {
     if (out == nullptr) return OCTOPUS_EINVAL;
     if (!head_dim_ok(head_dim)) return OCTOPUS_EUNSUPPORTED;
@@ -499,6 +508,9 @@ static int attn_decode(const octopus_codebooks_t *cb, const void *q, int32_t q_d
                        void *stream, bool with_qjl, const uint8_t *signs2, const void *qjl, int v_bits = 0,
                        int v_group = 0, const WindowArgs *win = nullptr) {
     const bool with_vq = v_bits != 0;    // v: group-quantised rows (v_dtype is not looked at)
+    // the measurement events belong to THIS call whatever becomes of it: a call that fails leaves none armed
+    void *ev_before = g_event_before, *ev_after = g_event_after;
+    g_event_before = g_event_after = nullptr;
     const int ok = decode_args_ok(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len);
     if (ok != OCTOPUS_OK) return ok;
     if (with_vq) {
@@ -537,8 +549,6 @@ static int attn_decode(const octopus_codebooks_t *cb, const void *q, int32_t q_d
     int32_t *work_plan = many_rows ? nullptr : reinterpret_cast<int32_t *>(base + w.plan_off);
     int err = launch_rotate_queries(cb->plan, q, q_dtype, signs, s, scale, q_rot, seq_lens, work_plan, signs2, q2,
                                     stream);
-    void *ev_before = g_event_before, *ev_after = g_event_after;
-    g_event_before = g_event_after = nullptr;
     if (err == 0 && ev_before != nullptr) err = record_event(ev_before, stream);
     if (err == 0) {
         if (with_qjl)
@@ -735,9 +745,14 @@ int octopus_attn_decode_paged(const octopus_codebooks_t *cb, const void *q, int3
                               const void *k_pool, const void *v_pool, int32_t n_pages, const int32_t *block_table,
                               int32_t max_pages_per_seq, const int32_t *seq_lens, int64_t max_len, float scale,
                               float *out, void *workspace, size_t workspace_bytes, void *stream) {
+    void *ev_before = g_event_before, *ev_after = g_event_after;
+    g_event_before = g_event_after = nullptr;
     const int ok = decode_args_ok(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len);
     if (ok != OCTOPUS_OK) return ok;
     if (q == nullptr || signs == nullptr || seq_lens == nullptr || out == nullptr) return OCTOPUS_EINVAL;
+    // A chunk of many query rows per KV head belongs to the many-row kernel, which is not built for pages: refused
+    // rather than run as hundreds of row groups that each read the keys again.
+    if (static_cast<int64_t>(n_q) * (n_q_heads / n_kv_heads) >= 32) return OCTOPUS_EUNSUPPORTED;
     if (!page_table_ok(k_pool, n_pages, block_table, max_pages_per_seq) || v_pool == nullptr || !aligned(v_pool, 16))
         return OCTOPUS_EINVAL;
     const int64_t reach = static_cast<int64_t>(max_pages_per_seq) * OCTOPUS_TILE;
@@ -755,8 +770,6 @@ int octopus_attn_decode_paged(const octopus_codebooks_t *cb, const void *q, int3
     const PageTable pt{block_table, max_pages_per_seq, n_pages};
     int err = launch_rotate_queries(cb->plan, q, q_dtype, signs, s, scale, q_rot, seq_lens, work_plan, nullptr, nullptr,
                                     stream);
-    void *ev_before = g_event_before, *ev_after = g_event_after;
-    g_event_before = g_event_after = nullptr;
     if (err == 0 && ev_before != nullptr) err = record_event(ev_before, stream);
     if (err == 0)
         err = launch_decode_paged(*cb, s, q_rot, k_pool, v_pool, pt, seq_lens, part_ml, part_acc, work_plan, stream);

@@ -103,6 +103,9 @@ int launch_decode_vq(const octopus_codebooks_t &cb, const DecodeShape &s, const 
                      const void *vq, int v_bits, int v_group, const int32_t *seq_lens, float *part_ml,
                      float *part_acc, float *scores_out, int32_t *work_plan, void *stream);
 
+// Measurement aid: plain streaming read of `bytes` bytes by n_blocks workgroups (non-temporal loads or not).
+int launch_probe_read(const void *data, int64_t bytes, int nontemporal, int n_blocks, void *sink, void *stream);
+
 // hipEventRecord(event, stream); returns a hipError_t cast to int.
 int record_event(void *event, void *stream);
 

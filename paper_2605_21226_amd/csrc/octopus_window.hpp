@@ -36,7 +36,7 @@ __global__ __launch_bounds__(kWave) void window_kernel(DecodeShape shp, const vo
     for (int c = 0; c < CPT; ++c) qs[c * kWave + lane] = load(q, q_is_bf16, orow * D + c * kWave + lane) * scale;
     __syncthreads();
 
-    const int64_t len = seq_lens[seq];
+    const int64_t len = min(max(seq_lens[seq], 0), shp.max_len);   // clamped like every other kernel's
     // the window's tokens must fit behind the compressed ones in the value buffer
     const int64_t n_win = max(int64_t{0}, min(min(static_cast<int64_t>(win_lens[seq]), w_capacity), shp.t_capacity - len));
     const int64_t pair = static_cast<int64_t>(seq) * shp.n_kv_heads + kvh;

@@ -39,6 +39,22 @@ def pools_from_logical(cb, records, v, table, n_pages, cap):
     return k_pool, v_pool
 
 
+def test_paged_decode_refuses_chunks_of_many_query_rows():
+    """32 or more query rows per KV head are the many-row kernel's, which is not built for pages."""
+    cb = binding.octopus_build_codebooks(128, 3)
+    q = torch.zeros((1, 11, 6, 128), dtype=torch.bfloat16, device=DEV)           # 11 queries x 3 heads per KV head
+    pool = torch.zeros(binding.octopus_paged_pool_bytes(cb, 4, 2), dtype=torch.uint8, device=DEV)
+    v_pool = torch.zeros((4, 2, 64, 128), dtype=torch.bfloat16, device=DEV)
+    table = torch.zeros((1, 4), dtype=torch.int32, device=DEV)
+    lens = torch.tensor([200], dtype=torch.int32, device=DEV)
+    ws = torch.empty(binding.octopus_attn_decode_workspace(cb, 1, 6, 2, 11, 200), dtype=torch.uint8, device=DEV)
+    out = torch.zeros((1, 11, 6, 128), dtype=torch.float32, device=DEV)
+    signs = torch.zeros(2 * 16, dtype=torch.uint8, device=DEV)
+    with pytest.raises(binding.OctopusError) as err:
+        binding.octopus_attn_decode_paged(cb, q, signs, pool, v_pool, table, lens, 200, 0.1, out, ws)
+    assert err.value.code == binding.EUNSUPPORTED
+
+
 def run_paged_decode_case(d, bits, n_seq, n_qh, n_kv, n_q, lens, seed, q_dtype="bf16", spare_pages=5):
     cb = binding.octopus_build_codebooks(d, bits)
     plan = oracle.make_plan(d, bits)
@@ -89,7 +105,7 @@ def test_paged_decode_long_sequence_many_sequences_and_fp32_queries():
     run_paged_decode_case(128, 3, 1, 4, 1, 1, [9000], seed=901)                       # 141 pages, several splits
     rng = np.random.default_rng(902)
     run_paged_decode_case(64, 3, 70, 2, 1, 1, [int(x) for x in rng.integers(0, 300, size=70)], seed=902)
-    run_paged_decode_case(128, 2, 2, 6, 2, 11, [300, 129], seed=903, q_dtype="fp32")  # 33 rows: groups of 8
+    run_paged_decode_case(128, 2, 2, 6, 2, 10, [300, 129], seed=903, q_dtype="fp32")  # 30 rows: groups of 8
 
 
 def test_paged_decode_shared_prefix_pages():
