@@ -47,6 +47,9 @@ def parse():
     ap.add_argument("--workload", default="llama3_8b_decode")
     ap.add_argument("--bits", type=float, default=None,
                     help="bits per coordinate (1, 1.5, 2, 2.5, 3, 4) instead of the workload's own")
+    ap.add_argument("--pair", default="",
+                    help="BD:BN - an explicit (b_dir, b_nrm) pair of the bit-allocation sweep of App. D instead of a nominal "
+                         "bit width (octopus_build_codebooks_pair); workloads of head_dim 128, plain variant")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the `workloads` block (the other named configurations)")
@@ -92,7 +95,7 @@ def set_omp_threads(n):
         return False
 
 
-def cpu_baseline(wl, keys, vals, q, signs, scale, record_bytes, budget_s=12.0, signs2=None, mode=1, vq=None):
+def cpu_baseline(wl, keys, vals, q, signs, scale, record_bytes, budget_s=12.0, signs2=None, mode=1, vq=None, pair=None):
     """The oracle as it stands, timed on this machine's host cores on a bounded sample of the workload:
     whole sequences (all KV heads, all cached tokens; encode, then attention of each KV head's group of
     query heads over its tokens), one sequence after another until about `budget_s` seconds are spent;
@@ -101,7 +104,7 @@ def cpu_baseline(wl, keys, vals, q, signs, scale, record_bytes, budget_s=12.0, s
 
     import oracle
 
-    plan = oracle.make_plan(wl.head_dim, wl.bits)
+    plan = oracle.make_plan_pair(wl.head_dim, *pair) if pair else oracle.make_plan(wl.head_dim, wl.bits)
     g = wl.n_q_heads // wl.n_kv_heads
     n_tok = wl.n_tokens
     oracle.encode(plan, np.zeros((64, wl.head_dim)), signs[0])               # load the library
@@ -222,7 +225,9 @@ class Run:
         self.rounding = args.rounding if variants else 1
         self.v_bits, self.v_group = ((int(x) for x in args.vq.split(":")) if (args.vq and variants) else (0, 0))
         self.many_rows = wl.n_q > 1
-        self.cb = cb = binding.octopus_build_codebooks(wl.head_dim, wl.bits)
+        self.pair = tuple(int(x) for x in args.pair.split(":")) if (args.pair and variants) else None
+        self.cb = cb = (binding.octopus_build_codebooks_pair(wl.head_dim, *self.pair) if self.pair
+                        else binding.octopus_build_codebooks(wl.head_dim, wl.bits))
         self.keys, self.vals, self.q, self.signs, lens = device_inputs(wl, args.seed, dev)
         self.cap = cap = -(-wl.n_tokens // 64) * 64
         if cap != wl.n_tokens:                      # the values need t_capacity rows
@@ -526,7 +531,10 @@ def main():
     if args.qjl and many_rows:
         print("bench.py: --qjl times single-query workloads only", file=sys.stderr)
         sys.exit(2)
-    variant = bool(args.qjl or args.vq or args.window or args.paged or args.rounding != 1)
+    if args.pair and (args.qjl or args.vq or args.paged or args.rounding != 1 or args.bits is not None or wl.head_dim != 128):
+        print("bench.py: --pair goes with the plain variant of a head_dim 128 workload, without --bits", file=sys.stderr)
+        sys.exit(2)
+    variant = bool(args.qjl or args.vq or args.window or args.paged or args.rounding != 1 or args.pair)
 
     run = Run(wl, args, dev)
     cb = run.cb
@@ -598,7 +606,8 @@ def main():
             "workload": f"{wl.name}{' + QJL residual' if args.qjl else ''}"
                         f"{f' + values quantised to {run.v_bits} bits in groups of {run.v_group}' if args.vq else ''}"
                         f"{' + paged cache (64-token pages in random order)' if args.paged else ''}: batch {wl.n_seq}, {wl.n_q_heads} query / {wl.n_kv_heads} KV heads, head_dim "
-                        f"{wl.head_dim}, {wl.n_tokens} cached tokens, {wl.dtype} K/V/Q, {wl.bits:g} bits/coordinate "
+                        f"{wl.head_dim}, {wl.n_tokens} cached tokens, {wl.dtype} K/V/Q, "
+                        f"{'an explicit pair of the App. D sweep' if args.pair else f'{wl.bits:g} bits/coordinate'} "
                         f"(b_dir {cb.plan.b_dir[0]}, b_nrm {cb.plan.b_nrm[0]}); step = encode of "
                         f"{wl.n_seq * n_new} tokens + one decode-attention call"
                         + (f" of {wl.n_q} queries per sequence" if many_rows else ""),
@@ -666,7 +675,7 @@ def main():
     if not args.no_cpu_baseline and not args.window:      # (the baseline leg times the plain variants)
         result["cpu_baseline"] = cpu_baseline(wl, run.keys, run.vals, run.q, run.signs, run.scale, rec_bytes,
                                               signs2=run.signs2, mode=args.rounding,
-                                              vq=(run.v_bits, run.v_group) if args.vq else None)
+                                              vq=(run.v_bits, run.v_group) if args.vq else None, pair=run.pair)
     if not args.no_extras and not variant and args.workload == "llama3_8b_decode" and args.bits is None:
         run = None
         torch.cuda.empty_cache()

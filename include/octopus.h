@@ -99,8 +99,14 @@ typedef struct octopus_codebooks {
  * Errors: EINVAL (out NULL), EUNSUPPORTED (head_dim or bits not listed). */
 int octopus_build_codebooks(int32_t head_dim, float bits, octopus_codebooks_t *out);
 
-/* Same with an explicit single-class (b_dir, b_nrm), 1 <= b_dir <= 5,
- * 1 <= b_nrm <= 3 (the pairs swept in App. D that the kernels are built for). */
+/* Same with an explicit single-class (b_dir, b_nrm), 1 <= b_dir, b_nrm <= 6: the
+ * bit-allocation sweep of App. D.  Codebooks are built for every such pair.  Kernels:
+ * the pairs that are a built bit width ((1,1), (3,1), (4,2), (5,3)) have every kernel;
+ * at head_dim 128 the other pairs of the App. D table -- (1,3), (2,2), (1,5), (2,4),
+ * (3,3), (5,1), (2,6), (3,5), (4,4), (6,2) -- have octopus_encode and octopus_attn_decode
+ * (and its _static / _hybrid forms) over bf16 values without score output and with fewer
+ * than 32 query rows per KV head; every other call with them, and every other pair,
+ * answers EUNSUPPORTED. */
 int octopus_build_codebooks_pair(int32_t head_dim, int32_t b_dir, int32_t b_nrm, octopus_codebooks_t *out);
 
 /* Bytes of a compressed cache of n_seq x n_kv_heads regions of t_capacity

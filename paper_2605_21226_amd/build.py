@@ -18,7 +18,8 @@ SOURCES = []
 for _d in ("256", "128", "64"):
     SOURCES += [_family + _d + ".hip" for _family in ("octopus_d", "octopus_paged_d", "octopus_scores_d", "octopus_vq_d", "octopus_valu_d",
                                                       "octopus_qjl_d", "octopus_enc_d", "octopus_round_d")]
-SOURCES += ["octopus_common.hip", "octopus_values.hip", "octopus_host.cpp"]
+SOURCES += ["octopus_sweep_dec_d128.hip", "octopus_sweep_enc_d128.hip", "octopus_common.hip", "octopus_values.hip",
+            "octopus_host.cpp"]
 # -packed-fp32-ops is switched off on purpose: hipcc must not form packed fp32 instructions here.
 FLAGS = (["-D" + d for d in os.environ.get("OCTOPUS_DEFS", "").split(",") if d]) + ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]

@@ -71,9 +71,18 @@ int launch_probe_read(const void *data, int64_t bytes, int nontemporal, int n_bl
     return static_cast<int>(hipGetLastError());
 }
 
+// the pairs of the App. D sweep (head dimension 128 only): plain encoder and bf16-value split-K decode
+bool plan_supported_sweep_d128(const octopus_plan_t &);
+int launch_decode_sweep_d128(const octopus_codebooks_t &, const DecodeShape &, const float *, const void *, const void *,
+                             const int32_t *, float *, float *, int32_t *, void *);
+int launch_encode_sweep_d128(const octopus_codebooks_t &, const void *, int, int64_t, int64_t, int64_t, int32_t, int32_t,
+                             int32_t, const uint8_t *, void *, int64_t, const int32_t *, void *);
+
 int record_event(void *event, void *stream) {
     return static_cast<int>(hipEventRecord(static_cast<hipEvent_t>(event), static_cast<hipStream_t>(stream)));
 }
+
+bool plan_sweep_only(const octopus_plan_t &plan) { return plan.head_dim == 128 && plan_supported_sweep_d128(plan); }
 
 bool plan_supported(const octopus_plan_t &plan) {
     switch (plan.head_dim) {
@@ -87,6 +96,10 @@ bool plan_supported(const octopus_plan_t &plan) {
 int launch_decode(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
                   const void *v, int v_dtype, const int32_t *seq_lens, float *part_ml, float *part_acc,
                   float *scores_out, int32_t *work_plan, void *stream) {
+    if (plan_sweep_only(cb.plan)) {
+        if (v_dtype != OCTOPUS_DTYPE_BF16 || scores_out != nullptr) return static_cast<int>(hipErrorInvalidValue);
+        return launch_decode_sweep_d128(cb, s, q_rot, cache, v, seq_lens, part_ml, part_acc, work_plan, stream);
+    }
     // kernel family: 0 matrix cores, 1 matrix cores with score output, 2 vector units (fp32 values)
     const int family = v_dtype == OCTOPUS_DTYPE_BF16 ? (scores_out != nullptr ? 1 : 0) : 2;
 #define OCTOPUS_GO(D)                                                                                                   \
@@ -141,6 +154,11 @@ int launch_encode(const octopus_codebooks_t &cb, const void *keys, int key_dtype
                   int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
                   const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos,
                   const uint8_t *signs2, void *qjl, void *stream) {
+    if (plan_sweep_only(cb.plan)) {
+        if (qjl != nullptr) return static_cast<int>(hipErrorInvalidValue);
+        return launch_encode_sweep_d128(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new,
+                                        signs, cache, t_capacity, start_pos, stream);
+    }
     switch (cb.plan.head_dim) {
         case 64: return launch_encode_d64(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs, cache, t_capacity, start_pos, signs2, qjl, stream);
         case 128: return launch_encode_d128(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs, cache, t_capacity, start_pos, signs2, qjl, stream);

@@ -59,10 +59,10 @@ __device__ __forceinline__ void build_dir_table(float4 *table, const float *c_xi
 // the entry holds their NTG centroids (4 one-bit codes, or 2 two- or three-bit codes, per lookup).
 template <int BN>
 struct RhoTable {
-    static constexpr int NTG = BN == 1 ? 4 : 2;
+    static constexpr int NTG = BN == 1 ? 4 : (BN <= 3 ? 2 : 1);   // (4 bits and more: one code per lookup)
     static constexpr int BITS = BN * NTG;
     static constexpr int ENTRIES = 1 << BITS;
-    static constexpr int REP = NTG == 4 ? 8 : 16;   // 8 x 16 bytes or 16 x 8 bytes = all 32 banks
+    static constexpr int REP = 32 / NTG;   // 8 x 16 bytes, 16 x 8 bytes or 32 x 4 bytes = all 32 banks
     static constexpr int FLOATS = ENTRIES * REP * NTG;
 };
 
@@ -159,8 +159,8 @@ struct DecodeTables {
     float4 dir1[P::NCLASS == 2 ? dir_table_float4s<(P::BD1 > 0 ? P::BD1 : 1), (P::BN1 > 0 ? P::BN1 : 1)>() : 1];
     __attribute__((aligned(16))) float rho0[J0 ? 4 : RhoTable<P::BN0>::FLOATS];
     __attribute__((aligned(16))) float rho1[P::NCLASS == 2 && !J1 ? RhoTable<(P::BN1 > 0 ? P::BN1 : 1)>::FLOATS : 4];
-    float c_xi[2][32];
-    float c_rho[2][8];
+    float c_xi[2][kMaxLevels];
+    float c_rho[2][kMaxLevels];
 };
 
 // Plans whose every class has a joint table (all up to 3 bits per coordinate) can score on the matrix cores.
@@ -535,6 +535,8 @@ __device__ __forceinline__ void tile_scores(const uint32_t (&w)[KPL][P::NWORDS],
                         if constexpr (RT::NTG == 4) {
                             const float4 e = *reinterpret_cast<const float4 *>(entry);
                             rgv[k][0] = e.x; rgv[k][1] = e.y; rgv[k][2] = e.z; rgv[k][3] = e.w;
+                        } else if constexpr (RT::NTG == 1) {
+                            rgv[k][0] = entry[0];
                         } else {
                             const float2 e = *reinterpret_cast<const float2 *>(entry);
                             rgv[k][0] = e.x; rgv[k][1] = e.y;
@@ -1523,11 +1525,7 @@ template <class P, int RG, bool SCORES>
 int launch_decode_mfma_rg(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
                           const void *v, const int32_t *seq_lens, float *part_ml, float *part_acc, float *scores_out,
                           int32_t *plan, hipStream_t stream) {
-    DeviceBooks books;
-    for (int c = 0; c < 2; ++c) {
-        for (int k = 0; k < 32; ++k) books.c_xi[c][k] = cb.c_xi[c][k];
-        for (int k = 0; k < 8; ++k) books.c_rho[c][k] = cb.c_rho[c][k];
-    }
+    const DeviceBooks books = device_books(cb);
     // one workgroup per compute unit; they share the items of the plan
     hipLaunchKernelGGL((decode_kernel_mfma<P, RG, SCORES, false>), dim3(kDecodeWorkgroups), dim3(kDecodeWaves * kWave),
                        0, stream, books, s, q_rot, static_cast<const uint4 *>(cache), static_cast<const uint32_t *>(v),
@@ -1540,11 +1538,7 @@ template <class P, int RG>
 int launch_decode_paged_rg(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *k_pool,
                            const void *v_pool, const PageTable &pt, const int32_t *seq_lens, float *part_ml,
                            float *part_acc, int32_t *plan, hipStream_t stream) {
-    DeviceBooks books;
-    for (int c = 0; c < 2; ++c) {
-        for (int k = 0; k < 32; ++k) books.c_xi[c][k] = cb.c_xi[c][k];
-        for (int k = 0; k < 8; ++k) books.c_rho[c][k] = cb.c_rho[c][k];
-    }
+    const DeviceBooks books = device_books(cb);
     hipLaunchKernelGGL((decode_kernel_mfma<P, RG, false, false, true>), dim3(kDecodeWorkgroups),
                        dim3(kDecodeWaves * kWave), 0, stream, books, s, q_rot, static_cast<const uint4 *>(k_pool),
                        static_cast<const uint32_t *>(v_pool), seq_lens, part_ml, part_acc, nullptr, plan, nullptr,
@@ -1589,11 +1583,7 @@ template <class P, int RG>
 int launch_decode_valu_rg(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
                           const void *v, const int32_t *seq_lens, float *part_ml, float *part_acc, float *scores_out,
                           int32_t *plan, hipStream_t stream) {
-    DeviceBooks books;
-    for (int c = 0; c < 2; ++c) {
-        for (int k = 0; k < 32; ++k) books.c_xi[c][k] = cb.c_xi[c][k];
-        for (int k = 0; k < 8; ++k) books.c_rho[c][k] = cb.c_rho[c][k];
-    }
+    const DeviceBooks books = device_books(cb);
     const size_t smem = sizeof(DecodeSmemValu<P, RG>);
     const hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel_valu<P, RG>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem));
@@ -1622,11 +1612,7 @@ template <class P, int RG>
 int launch_decode_vq_rg(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
                         const void *vq, int v_bits, int v_group, const int32_t *seq_lens, float *part_ml,
                         float *part_acc, float *scores_out, int32_t *plan, hipStream_t stream) {
-    DeviceBooks books;
-    for (int c = 0; c < 2; ++c) {
-        for (int k = 0; k < 32; ++k) books.c_xi[c][k] = cb.c_xi[c][k];
-        for (int k = 0; k < 8; ++k) books.c_rho[c][k] = cb.c_rho[c][k];
-    }
+    const DeviceBooks books = device_books(cb);
     const size_t smem = sizeof(DecodeSmemValu<P, RG>);
     hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel_valu<P, RG, true>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem));
@@ -1657,11 +1643,7 @@ int launch_decode_qjl_rg(const octopus_codebooks_t &cb, const DecodeShape &s, co
                          const void *qjl, const float *q2, const void *v, const int32_t *seq_lens, float *part_ml,
                          float *part_acc, float *scores_out, int32_t *plan, hipStream_t stream) {
     if constexpr (qjl_fits<P, RG>()) {
-        DeviceBooks books;
-        for (int c = 0; c < 2; ++c) {
-            for (int k = 0; k < 32; ++k) books.c_xi[c][k] = cb.c_xi[c][k];
-            for (int k = 0; k < 8; ++k) books.c_rho[c][k] = cb.c_rho[c][k];
-        }
+        const DeviceBooks books = device_books(cb);
         hipLaunchKernelGGL((decode_kernel_mfma<P, RG, true, true>), dim3(kDecodeWorkgroups),
                            dim3(kDecodeWaves * kWave), 0, stream, books, s, q_rot, static_cast<const uint4 *>(cache),
                            static_cast<const uint32_t *>(v), seq_lens, part_ml, part_acc, scores_out, plan,

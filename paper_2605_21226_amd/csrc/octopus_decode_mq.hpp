@@ -38,8 +38,8 @@ struct MqSmem {
     static constexpr int VST = kWave + 4;   // bf16 per row of the transposed value tile (8-byte aligned rows)
     float4 dir0[1 << (2 * P::BD0)];
     float4 dir1[P::NCLASS == 2 ? 1 << (2 * P::BD1) : 1];
-    float c_xi[2][32];
-    float c_rho[2][8];
+    float c_xi[2][kMaxLevels];
+    float c_rho[2][kMaxLevels];
     uint16_t kh[2][kWave][KST];
     uint16_t kl[2][kWave][KST];
     uint16_t vt[2][D][VST];
@@ -327,11 +327,7 @@ __global__ __launch_bounds__(kWave *NW) __attribute__((amdgpu_waves_per_eu(P::D 
 template <class P>
 int launch_decode_mq(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
                      const void *v, const int32_t *seq_lens, float *part_ml, float *part_acc, hipStream_t stream) {
-    DeviceBooks books;
-    for (int c = 0; c < 2; ++c) {
-        for (int k = 0; k < 32; ++k) books.c_xi[c][k] = cb.c_xi[c][k];
-        for (int k = 0; k < 8; ++k) books.c_rho[c][k] = cb.c_rho[c][k];
-    }
+    const DeviceBooks books = device_books(cb);
     const int64_t wgs = static_cast<int64_t>(s.n_seq) * s.n_kv_heads * s.n_row_groups * s.n_splits;
     auto go = [&](auto kernel, int waves) {
         hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(wgs)), dim3(kWave * waves), 0, stream, books, s, q_rot,

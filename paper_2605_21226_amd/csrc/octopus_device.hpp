@@ -113,13 +113,13 @@ __device__ __forceinline__ void build_dir_lut(float4 *lut, const float *c_xi, in
 }
 
 // Kernel-argument centroids to LDS with compile-time indices (every lane stores the same values).
-__device__ __forceinline__ void copy_books(const DeviceBooks &books, float (*c_xi)[32], float (*c_rho)[8]) {
+__device__ __forceinline__ void copy_books(const DeviceBooks &books, float (*c_xi)[kMaxLevels], float (*c_rho)[kMaxLevels]) {
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
 #pragma unroll
-        for (int k = 0; k < 32; ++k) c_xi[c][k] = books.c_xi[c][k];
+        for (int k = 0; k < kMaxLevels; ++k) c_xi[c][k] = books.c_xi[c][k];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) c_rho[c][k] = books.c_rho[c][k];
+        for (int k = 0; k < kMaxLevels; ++k) c_rho[c][k] = books.c_rho[c][k];
     }
 }
 

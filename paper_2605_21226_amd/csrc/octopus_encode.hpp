@@ -32,22 +32,22 @@ struct SeedGrid {
 // The direction table and the seed grid are kept in two copies up to d = 128 (entry e of copy r at index
 // e * REP + r, lane l reads copy l % REP), which halves the LDS bank conflicts of the lookups; more
 // copies, or any at d = 256, would cost a resident workgroup per compute unit (measured slower).
-template <int D>
-constexpr int encode_table_rep() { return D <= 128 ? 2 : 1; }
+template <int D, int BD = 1>
+constexpr int encode_table_rep() { return (D <= 128 && BD <= 5) ? 2 : 1; }
 
 template <class P>
 struct EncodeSmem {
     float u[3 * P::NTRI][kURow];           // rotated coordinates [coordinate][key]
     uint32_t rec[P::NWORDS][kWave];        // packed records [word][key]
-    static constexpr int REP = encode_table_rep<P::D>();
+    static constexpr int REP = encode_table_rep<P::D, (P::BD0 > P::BD1 ? P::BD0 : P::BD1)>();
     float4 lut0[(1 << (2 * P::BD0)) * REP];
     float4 lut1[P::NCLASS == 2 ? (1 << (2 * P::BD1)) * REP : 1];
     float2 cell0[SeedGrid<P::BD0>::NCELL * REP];
     float2 cell1[P::NCLASS == 2 ? SeedGrid<(P::BD1 > 0 ? P::BD1 : 1)>::NCELL * REP : 1];
-    float c_xi[2][32];
-    float c_rho[2][8];
-    float bnd_xi[2][33];                   // boundaries, +inf padded
-    float bnd_rho[2][8];
+    float c_xi[2][kMaxLevels];
+    float c_rho[2][kMaxLevels];
+    float bnd_xi[2][kMaxLevels + 1];       // boundaries, +inf padded
+    float bnd_rho[2][kMaxLevels];
     float inv_norm[kWave];
     float res_sq[4][kWave];                // QJL side-car: squared residual norm, partial per wavefront
 };
@@ -65,7 +65,7 @@ __device__ __forceinline__ void build_encode_lut(float4 *lut, const float *c_xi,
 template <int BD, int REP>
 __device__ __forceinline__ void build_seed_grid(float2 *cell, float *bnd, const float *c_xi, int tid, int nthreads) {
     using G = SeedGrid<BD>;
-    for (int k = tid; k < 33; k += nthreads)
+    for (int k = tid; k <= kMaxLevels; k += nthreads)
         bnd[k] = (k < G::K - 1) ? 0.5f * (c_xi[k] + c_xi[k + 1]) : INFINITY;
     for (int c = tid; c < G::NCELL; c += nthreads) {
         int below = 0;
@@ -224,7 +224,7 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
     constexpr int D = P::D;
     constexpr int LPR = D / 8;        // threads per key row in the load phase
     constexpr int RPP = 256 / LPR;    // key rows per load pass
-    constexpr int REP = encode_table_rep<D>();
+    constexpr int REP = EncodeSmem<P>::REP;
     // static, so that table addresses are compile-time constants that fold into the LDS instructions
     __shared__ EncodeSmem<P> sm;
 
@@ -244,9 +244,10 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
         build_encode_lut<P::BD1, REP>(sm.lut1, sm.c_xi[1], tid, 256);
         build_seed_grid<P::BD1, REP>(sm.cell1, sm.bnd_xi[1], sm.c_xi[1], tid, 256);
     }
-    if (tid < 16) {
-        const int c = tid >> 3, k = tid & 7;
-        sm.bnd_rho[c][k] = (k < 7) ? 0.5f * (sm.c_rho[c][k] + sm.c_rho[c][k + 1]) : INFINITY;
+    if (tid < 2 * kMaxLevels) {
+        const int c = tid / kMaxLevels, k = tid % kMaxLevels;
+        const int levels = 1 << (c ? (P::BN1 > 0 ? P::BN1 : 1) : P::BN0);
+        sm.bnd_rho[c][k] = (k < levels - 1) ? 0.5f * (sm.c_rho[c][k] + sm.c_rho[c][k + 1]) : INFINITY;
     }
     for (int e = tid; e < (3 * P::NTRI - D) * kWave; e += 256) sm.u[D + e / kWave][e % kWave] = 0.0f;
 
@@ -459,11 +460,7 @@ int launch_encode_plan(const octopus_codebooks_t &cb, const void *keys, int key_
                        int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
                        const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos,
                        const uint8_t *signs2, void *qjl, hipStream_t stream, PageTable pt = PageTable{nullptr, 0, 0}) {
-    DeviceBooks books;
-    for (int c = 0; c < 2; ++c) {
-        for (int k = 0; k < 32; ++k) books.c_xi[c][k] = cb.c_xi[c][k];
-        for (int k = 0; k < 8; ++k) books.c_rho[c][k] = cb.c_rho[c][k];
-    }
+    const DeviceBooks books = device_books(cb);
     // a start that is not a multiple of 64 makes the new tokens straddle one more tile
     const int tiles = (n_new + kWave - 1) / kWave + (start_pos ? 1 : 0);
     const dim3 grid((tiles + kEncodeTilesPerGroup - 1) / kEncodeTilesPerGroup, n_kv_heads, n_seq);
@@ -481,17 +478,32 @@ int launch_encode_plan(const octopus_codebooks_t &cb, const void *keys, int key_
     return static_cast<int>(hipGetLastError());
 }
 
+// The default encoder alone (local 3x3, no side-car, no pages): what the pairs of the App. D sweep are built with.
+template <class P>
+int launch_encode_basic_plan(const octopus_codebooks_t &cb, const void *keys, int key_dtype, int64_t stride_seq,
+                             int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
+                             const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos,
+                             hipStream_t stream) {
+    const DeviceBooks books = device_books(cb);
+    const int tiles = (n_new + kWave - 1) / kWave + (start_pos ? 1 : 0);
+    const dim3 grid((tiles + kEncodeTilesPerGroup - 1) / kEncodeTilesPerGroup, n_kv_heads, n_seq);
+    auto go = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, grid, dim3(256), 0, stream, books, keys, stride_seq, stride_tok, stride_head, n_new,
+                           signs, static_cast<uint4 *>(cache), t_capacity, start_pos, n_kv_heads, nullptr, nullptr, 1,
+                           PageTable{nullptr, 0, 0});
+    };
+    if (key_dtype == OCTOPUS_DTYPE_BF16) go(encode_kernel<P, true, false>);
+    else go(encode_kernel<P, false, false>);
+    return static_cast<int>(hipGetLastError());
+}
+
 // The encoder with the rounding mode chosen at run time (no side-car).
 template <class P>
 int launch_encode_rounding_plan(const octopus_codebooks_t &cb, const void *keys, int key_dtype, int64_t stride_seq,
                                 int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads,
                                 int32_t n_new, const uint8_t *signs, void *cache, int64_t t_capacity,
                                 const int32_t *start_pos, int32_t mode, hipStream_t stream) {
-    DeviceBooks books;
-    for (int c = 0; c < 2; ++c) {
-        for (int k = 0; k < 32; ++k) books.c_xi[c][k] = cb.c_xi[c][k];
-        for (int k = 0; k < 8; ++k) books.c_rho[c][k] = cb.c_rho[c][k];
-    }
+    const DeviceBooks books = device_books(cb);
     const int tiles = (n_new + kWave - 1) / kWave + (start_pos ? 1 : 0);
     const dim3 grid((tiles + kEncodeTilesPerGroup - 1) / kEncodeTilesPerGroup, n_kv_heads, n_seq);
     auto go = [&](auto kernel) {

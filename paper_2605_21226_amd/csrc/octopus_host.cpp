@@ -206,7 +206,7 @@ bool plan_consistent(const octopus_plan_t &p) {
     if (p.n_class < 1 || p.n_class > 2) return false;
     int total = 0;
     for (int c = 0; c < p.n_class; ++c) {
-        if (p.class_ntri[c] < 1 || p.b_dir[c] < 1 || p.b_dir[c] > 5 || p.b_nrm[c] < 1 || p.b_nrm[c] > 3) return false;
+        if (p.class_ntri[c] < 1 || p.b_dir[c] < 1 || p.b_dir[c] > 6 || p.b_nrm[c] < 1 || p.b_nrm[c] > 6) return false;
         total += p.class_ntri[c];
     }
     if (total != p.n_tri) return false;
@@ -363,7 +363,7 @@ int octopus_build_codebooks(int32_t head_dim, float bits, octopus_codebooks_t *o
 
 int octopus_build_codebooks_pair(int32_t head_dim, int32_t b_dir, int32_t b_nrm, octopus_codebooks_t *out) {
     if (out == nullptr) return OCTOPUS_EINVAL;
-    if (!head_dim_ok(head_dim) || b_dir < 1 || b_dir > 5 || b_nrm < 1 || b_nrm > 3) return OCTOPUS_EUNSUPPORTED;
+    if (!head_dim_ok(head_dim) || b_dir < 1 || b_dir > 6 || b_nrm < 1 || b_nrm > 6) return OCTOPUS_EUNSUPPORTED;
     std::memset(out, 0, sizeof(*out));
     octopus_plan_t &p = out->plan;
     p.head_dim = head_dim;
@@ -415,7 +415,10 @@ static int encode_checked(const octopus_codebooks_t *cb, const void *keys, int32
     if (t_capacity < OCTOPUS_TILE || t_capacity % OCTOPUS_TILE != 0) return OCTOPUS_EINVAL;
     if (!plan_consistent(cb->plan)) return OCTOPUS_EINVAL;
     if (key_dtype != OCTOPUS_DTYPE_F32 && key_dtype != OCTOPUS_DTYPE_BF16) return OCTOPUS_EUNSUPPORTED;
-    if (!plan_supported(cb->plan) || !seed_grid_ok(*cb)) return OCTOPUS_EUNSUPPORTED;
+    // a pair of the App. D sweep has the plain encoder only (local 3x3, no side-car)
+    const bool sweep = !plan_supported(cb->plan) && plan_sweep_only(cb->plan);
+    if (sweep && (rounding != OCTOPUS_ROUND_LOCAL_3X3 || qjl != nullptr)) return OCTOPUS_EUNSUPPORTED;
+    if ((!plan_supported(cb->plan) && !sweep) || !seed_grid_ok(*cb)) return OCTOPUS_EUNSUPPORTED;
     if (stride_seq < 0 || stride_tok < 0 || stride_head < 0) return OCTOPUS_EINVAL;
     if (stride_seq % 8 != 0 || stride_tok % 8 != 0 || stride_head % 8 != 0) return OCTOPUS_EINVAL;
     if (!aligned(keys, 16) || !aligned(cache, 16)) return OCTOPUS_EINVAL;
@@ -469,7 +472,7 @@ static int decode_args_ok(const octopus_codebooks_t *cb, int32_t n_seq, int32_t 
         return OCTOPUS_EINVAL;
     if (n_q_heads % n_kv_heads != 0) return OCTOPUS_EINVAL;
     if (!plan_consistent(cb->plan)) return OCTOPUS_EINVAL;
-    if (!plan_supported(cb->plan)) return OCTOPUS_EUNSUPPORTED;
+    if (!plan_supported(cb->plan) && !plan_sweep_only(cb->plan)) return OCTOPUS_EUNSUPPORTED;
     return OCTOPUS_OK;
 }
 
@@ -520,6 +523,11 @@ static int attn_decode(const octopus_codebooks_t *cb, const void *q, int32_t q_d
     if (q == nullptr || signs == nullptr || cache == nullptr || v == nullptr || seq_lens == nullptr || out == nullptr)
         return OCTOPUS_EINVAL;
     if (with_qjl && (signs2 == nullptr || qjl == nullptr)) return OCTOPUS_EINVAL;
+    // a pair of the App. D sweep has the split-K kernel over bf16 values only
+    const bool sweep = !plan_supported(cb->plan);
+    if (sweep && (with_qjl || with_vq || v_dtype != OCTOPUS_DTYPE_BF16 || scores_out != nullptr ||
+                  many_rows_shape(cb->plan, n_q_heads, n_kv_heads, n_q)))
+        return OCTOPUS_EUNSUPPORTED;
     if (t_capacity < OCTOPUS_TILE || t_capacity % OCTOPUS_TILE != 0 || max_len > t_capacity) return OCTOPUS_EINVAL;
     if ((q_dtype != OCTOPUS_DTYPE_F32 && q_dtype != OCTOPUS_DTYPE_BF16) ||
         (v_dtype != OCTOPUS_DTYPE_F32 && v_dtype != OCTOPUS_DTYPE_BF16))
@@ -753,6 +761,7 @@ int octopus_attn_decode_paged(const octopus_codebooks_t *cb, const void *q, int3
     // A chunk of many query rows per KV head belongs to the many-row kernel, which is not built for pages: refused
     // rather than run as hundreds of row groups that each read the keys again.
     if (static_cast<int64_t>(n_q) * (n_q_heads / n_kv_heads) >= 32) return OCTOPUS_EUNSUPPORTED;
+    if (!plan_supported(cb->plan)) return OCTOPUS_EUNSUPPORTED;   // (a pair of the App. D sweep: no paged kernels)
     if (!page_table_ok(k_pool, n_pages, block_table, max_pages_per_seq) || v_pool == nullptr || !aligned(v_pool, 16))
         return OCTOPUS_EINVAL;
     const int64_t reach = static_cast<int64_t>(max_pages_per_seq) * OCTOPUS_TILE;

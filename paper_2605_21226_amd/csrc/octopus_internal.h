@@ -11,10 +11,21 @@ namespace octopus {
 
 // Centroids handed to kernels by value (kernel argument space); boundaries are
 // recomputed on the device as midpoints, exactly as the host computes them.
+constexpr int kMaxLevels = OCTOPUS_MAX_LEVELS;   // 64: up to 6 bits per index (the pairs swept in App. D)
 struct DeviceBooks {
-    float c_xi[2][32];
-    float c_rho[2][8];
+    float c_xi[2][kMaxLevels];
+    float c_rho[2][kMaxLevels];
 };
+
+inline DeviceBooks device_books(const octopus_codebooks_t &cb) {
+    DeviceBooks books;
+    for (int c = 0; c < 2; ++c)
+        for (int k = 0; k < kMaxLevels; ++k) {
+            books.c_xi[c][k] = cb.c_xi[c][k];
+            books.c_rho[c][k] = cb.c_rho[c][k];
+        }
+    return books;
+}
 
 // Floats per rotated query row in the workspace: 3 * n_tri rounded up to 4.
 inline int q_row_stride(int n_tri) { return (3 * n_tri + 3) & ~3; }
@@ -109,8 +120,11 @@ int launch_probe_read(const void *data, int64_t bytes, int nontemporal, int n_bl
 // hipEventRecord(event, stream); returns a hipError_t cast to int.
 int record_event(void *event, void *stream);
 
-// True when the kernels are instantiated for this plan.
+// True when every kernel family is instantiated for this plan (the six built bit widths of each head dimension).
 bool plan_supported(const octopus_plan_t &plan);
+// True for the extra (b_dir, b_nrm) pairs of the App. D sweep: plain encoder (local 3x3) and split-K decode over
+// bf16 values only -- no score output, no QJL side-car, no quantised values, no pages, no many-row kernel.
+bool plan_sweep_only(const octopus_plan_t &plan);
 
 }  // namespace octopus
 

@@ -33,7 +33,9 @@ int launch_encode_values(const void *, int, int64_t, int64_t, int64_t, int32_t, 
 int launch_decode_vq(const octopus_codebooks_t &, const DecodeShape &, const float *, const void *, const void *, int,
                      int, const int32_t *, float *, float *, float *, int32_t *, void *) { ++g_launches; return 0; }
 int record_event(void *, void *) { return 0; }
+int launch_probe_read(const void *, int64_t, int, int, void *, void *) { ++g_launches; return 0; }
 bool plan_supported(const octopus_plan_t &p) { return p.b_dir[0] <= 5 && p.b_nrm[0] <= 3; }
+bool plan_sweep_only(const octopus_plan_t &p) { return p.head_dim == 128 && !plan_supported(p); }
 }  // namespace octopus
 
 static int failures = 0;
@@ -107,9 +109,13 @@ int main() {
     EXPECT(octopus_build_codebooks(128, 3.0f, nullptr) == OCTOPUS_EINVAL);
     EXPECT(octopus_build_codebooks_pair(128, 3, 3, &cb) == OCTOPUS_OK);
     EXPECT(octopus_build_codebooks_pair(128, 0, 3, &cb) == OCTOPUS_EUNSUPPORTED);
+    EXPECT(octopus_build_codebooks_pair(128, 6, 6, &cb) == OCTOPUS_OK && cb.plan.record_bytes == 4 + 66 + 33);
+    EXPECT(octopus_build_codebooks_pair(128, 7, 2, &cb) == OCTOPUS_EUNSUPPORTED);
     EXPECT(octopus_vq_row_bytes(128, 3, 32) == 80 && octopus_vq_row_bytes(128, 5, 32) == 0);
     EXPECT(octopus_encode_values(fake, OCTOPUS_DTYPE_BF16, 1024, 128, 128, 1, 1, 4, 128, 3, 32, fake, 64, nullptr, nullptr) == OCTOPUS_OK);
     EXPECT(octopus_profile_events(fake, nullptr) == OCTOPUS_EINVAL);
+    EXPECT(octopus_probe_read(fake, 4096, 1, 4, fake, nullptr) == OCTOPUS_OK);
+    EXPECT(octopus_probe_read(fake, 16, 1, 4, fake, nullptr) == OCTOPUS_EINVAL);
     for (int code = 1; code >= -6; --code) EXPECT(std::strlen(octopus_strerror(code)) > 0);
     // a video-chunk shape needs more scratch than the static array holds
     EXPECT(octopus_build_codebooks(64, 4.0f, &cb) == OCTOPUS_OK);

@@ -60,7 +60,11 @@ def compare_records(plan, keys, signs, rec, tag, max_ties=None, mode=oracle.MODE
     if max_ties is not None:
         assert ties <= max_ties, f"{tag}: too many boundary ties ({ties})"
     else:
-        assert ties <= max(3, MAX_TIE_RATE * total.sum()), f"{tag}: too many boundary ties ({ties})"
+        # a tie needs a decision boundary within the rounding error of the fp32 path: their number grows with the
+        # number of levels per octahedral coordinate (the rates above are those of up to 32 levels)
+        levels = max(1 << bd for _, bd, _ in plan.classes)
+        rate = MAX_TIE_RATE * max(1, levels // 32)
+        assert ties <= max(3, rate * total.sum()), f"{tag}: too many boundary ties ({ties})"
         assert total[2] <= max(2, MAX_SCALED_ONLY_RATE * total.sum()), f"{tag}: too many scaled-only ties ({total[2]})"
     return total
 

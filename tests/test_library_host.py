@@ -57,12 +57,25 @@ def test_plan_and_codebooks_match_the_oracle(lib, d, bits):
         assert np.all(np.diff(cx) > 0) and np.array_equal(cx, -cx[::-1])
 
 
+def test_pair_codebooks_of_the_bit_allocation_sweep_match_the_oracle(lib, golden):
+    """All 13 (b_dir, b_nrm) pairs of App. D's table at d = 128, up to 6 bits per index."""
+    for b_dir, b_nrm, _, _ in golden("bit_split_diagonal.txt"):
+        bd, bn = int(b_dir), int(b_nrm)
+        cb = binding.octopus_build_codebooks_pair(128, bd, bn)
+        ref = oracle.make_plan_pair(128, bd, bn)
+        assert (cb.plan.dir_bytes, cb.plan.nrm_bytes, cb.plan.record_bytes) == (ref.dir_bytes, ref.nrm_bytes, ref.record_bytes)
+        assert np.max(np.abs(np.array(cb.c_xi[0][:1 << bd]) - ref.c_xi[0])) <= 1e-6, (bd, bn)
+        assert np.max(np.abs(np.array(cb.c_rho[0][:1 << bn]) - ref.c_rho[0])) <= 1e-6, (bd, bn)
+
+
 def test_build_codebooks_errors(lib):
     cb = binding.Codebooks()
     assert lib.octopus_build_codebooks(128, 3.0, None) == binding.EINVAL
     for d, bits in [(96, 3.0), (512, 3.0), (128, 0.5), (128, 3.5), (128, 5.0), (128, 2.25)]:
         assert lib.octopus_build_codebooks(d, bits, ctypes.byref(cb)) == binding.EUNSUPPORTED
-    assert lib.octopus_build_codebooks_pair(128, 6, 2, ctypes.byref(cb)) == binding.EUNSUPPORTED
+    assert lib.octopus_build_codebooks_pair(128, 7, 2, ctypes.byref(cb)) == binding.EUNSUPPORTED
+    assert lib.octopus_build_codebooks_pair(128, 2, 7, ctypes.byref(cb)) == binding.EUNSUPPORTED
+    assert lib.octopus_build_codebooks_pair(128, 6, 2, ctypes.byref(cb)) == binding.OK
     assert lib.octopus_build_codebooks_pair(128, 3, 3, ctypes.byref(cb)) == binding.OK
     assert cb.plan.record_bytes == 4 + oracle.stream_bytes(86, 3) + oracle.stream_bytes(43, 3)
     with pytest.raises(binding.OctopusError):
@@ -90,7 +103,7 @@ def test_encode_and_decode_reject_bad_arguments_before_launching(lib):
     assert enc(P, ctypes.c_void_p(0x1004), 1, 1024, 1024, 128, 1, 8, 64, fake, fake, 64, null, null) == binding.EINVAL
     assert enc(P, fake, 1, 1024, 1024, 128, 1, 8, 0, fake, fake, 64, null, null) == binding.OK             # nothing to do
     assert enc(P, fake, 1, 1024, 1024, 128, 65536, 8, 64, fake, fake, 64, null, null) == binding.EINVAL   # grid limit
-    pair = binding.octopus_build_codebooks_pair(128, 3, 3)   # no kernel is built for this pair
+    pair = binding.octopus_build_codebooks_pair(64, 3, 3)    # no kernel is built for this pair (the sweep's are d = 128)
     assert enc(ctypes.byref(pair), fake, 1, 1024, 1024, 128, 1, 8, 64, fake, fake, 64, null, null) == binding.EUNSUPPORTED
     broken = binding.octopus_build_codebooks(128, 3)
     broken.plan.record_bytes = 57
