@@ -110,7 +110,11 @@ __device__ __forceinline__ void encode_triplet(float x, float y, float z, const 
     constexpr int K = 1 << BD, M = 1 << BN;
     // Eq. (oct-encode)
     const float l1 = fabsf(x) + fabsf(y) + fabsf(z);
-    const float inv = __builtin_amdgcn_rcpf(fmaxf(l1, kEps));
+    // 1 / l1: the hardware reciprocal (1 ulp) refined by one Newton step, so that xi and eta carry the rounding of
+    // a division rather than of an approximation (they are compared with the codebook boundaries below)
+    const float l1c = fmaxf(l1, kEps);
+    float inv = __builtin_amdgcn_rcpf(l1c);
+    inv = fmaf(fmaf(-l1c, inv, 1.0f), inv, inv);
     const float px = x * inv, py = y * inv;
     float xi = px, eta = py;
     if (z < 0.0f) {
@@ -160,7 +164,11 @@ __device__ __forceinline__ void encode_triplet_any(float x, float y, float z, co
                                                    uint32_t *dir_field, uint32_t *nrm_index) {
     constexpr int K = 1 << BD, M = 1 << BN;
     const float l1 = fabsf(x) + fabsf(y) + fabsf(z);
-    const float inv = __builtin_amdgcn_rcpf(fmaxf(l1, kEps));
+    // 1 / l1: the hardware reciprocal (1 ulp) refined by one Newton step, so that xi and eta carry the rounding of
+    // a division rather than of an approximation (they are compared with the codebook boundaries below)
+    const float l1c = fmaxf(l1, kEps);
+    float inv = __builtin_amdgcn_rcpf(l1c);
+    inv = fmaf(fmaf(-l1c, inv, 1.0f), inv, inv);
     const float px = x * inv, py = y * inv;
     float xi = px, eta = py;
     if (z < 0.0f) {
