@@ -176,11 +176,14 @@ def cpu_baseline(wl, keys, vals, q, signs, scale, record_bytes, budget_s=12.0, s
     return result
 
 
-def kernel_source_digest():
-    """First 16 hex digits of the SHA-256 of the decode kernels' sources: what a traffic summary under profiles/
-    records, so that a summary measured on other code is not reported as this build's."""
+def kernel_source_digest(kernel="decode_kernel_mfma"):
+    """First 16 hex digits of the SHA-256 of the sources of a decode kernel: what a traffic summary under
+    profiles/ records, so that a summary measured on other code is not reported as this build's."""
+    names = ["octopus_decode.hpp", "octopus_decode_mq.hpp", "octopus_device.hpp"]
+    if kernel == "decode_kernel_vq_mfma":
+        names.append("octopus_decode_vq.hpp")
     h = hashlib.sha256()
-    for name in ("octopus_decode.hpp", "octopus_decode_mq.hpp", "octopus_device.hpp"):
+    for name in names:
         with open(os.path.join(ROOT, "paper_2605_21226_amd", "csrc", name), "rb") as f:
             h.update(f.read())
     return h.hexdigest()[:16]
@@ -203,7 +206,7 @@ def measured_traffic(workload, kernel="decode_kernel_mfma", profiles_dir=None):
     except (OSError, KeyError, ValueError):
         return None, "no traffic summary under profiles/ for this kernel and workload"
     sha, commit = vals.get("KERNEL_SOURCE_SHA"), vals.get("MEASURED_AT_COMMIT", "unknown")
-    if sha != kernel_source_digest():
+    if sha != kernel_source_digest(kernel):
         return None, f"the traffic summary (commit {commit}) was taken on other kernel sources than this tree's"
     return total, f"rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, measured at commit {commit} on these kernel sources"
 
@@ -344,7 +347,8 @@ class Run:
                 wl.dtype == "bf16")
 
     def dominant_kernel(self):
-        return "decode_kernel_valu" if self.v_bits else ("decode_kernel_mq" if self.uses_mq() else "decode_kernel_mfma")
+        # (quantised values of a single-query batch: row groups of 4 or 8, served by the matrix-core kernel)
+        return "decode_kernel_vq_mfma" if self.v_bits else ("decode_kernel_mq" if self.uses_mq() else "decode_kernel_mfma")
 
     def dense_flops(self):
         import numpy as np

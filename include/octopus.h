@@ -344,7 +344,10 @@ int octopus_encode_values(const void *v, int32_t v_dtype,
  * rows vq dequantised on the fly (the "value dequantization" of Alg. 2).
  *   vq, v_bits, v_group   as written by octopus_encode_values for the same head_dim.
  * Workspace: octopus_attn_decode_workspace(...) of the same shapes.  Other arguments and errors
- * as octopus_attn_decode; EUNSUPPORTED for v_bits outside 2..4 or v_group not 16/32. */
+ * as octopus_attn_decode; EUNSUPPORTED for v_bits outside 2..4 or v_group not 16/32.
+ * Without score output (scores_out NULL) the products P.V run on the matrix cores over the codes
+ * themselves (output error up to about 1e-4 of a row's largest magnitude); with it, on the vector
+ * units over dequantised values (about 1e-5). */
 int octopus_attn_decode_vq(const octopus_codebooks_t *cb,
                            const void *q, int32_t q_dtype,
                            int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q,

@@ -18,6 +18,7 @@ SOURCES = []
 for _d in ("256", "128", "64"):
     SOURCES += [_family + _d + ".hip" for _family in ("octopus_d", "octopus_paged_d", "octopus_scores_d", "octopus_vq_d", "octopus_valu_d",
                                                       "octopus_qjl_d", "octopus_enc_d", "octopus_round_d")]
+    SOURCES += ["octopus_vqm_d" + _d + "_b" + _b + ".hip" for _b in ("4", "3", "2")]
 SOURCES += ["octopus_sweep_dec_d128.hip", "octopus_sweep_enc_d128.hip", "octopus_common.hip", "octopus_values.hip",
             "octopus_host.cpp"]
 # -packed-fp32-ops is switched off on purpose: hipcc must not form packed fp32 instructions here.

@@ -221,7 +221,8 @@ bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 }  // namespace
 
 DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads,
-                              int32_t n_q, int64_t max_len, int64_t t_capacity, bool many_rows, int32_t rows_cap) {
+                              int32_t n_q, int64_t max_len, int64_t t_capacity, bool many_rows, int32_t rows_cap,
+                              int32_t rows_floor) {
     DecodeShape s{};
     s.n_seq = n_seq;
     s.n_q_heads = n_q_heads;
@@ -255,8 +256,8 @@ DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t
     }
     // Query rows scored per key by one workgroup: the power of two covering rows_per_kv, at most 8
     // (fewer with the QJL residual).  Rows beyond rows_per_kv in the last group are zero queries whose
-    // results are not stored.
-    s.rows_per_pass = 1;
+    // results are not stored.  rows_floor: the smallest group the kernel that will serve the call is built for.
+    s.rows_per_pass = std::max(1, rows_floor);
     while (s.rows_per_pass < s.rows_per_kv && s.rows_per_pass < rows_cap) s.rows_per_pass *= 2;
     s.n_row_groups = (s.rows_per_kv + s.rows_per_pass - 1) / s.rows_per_pass;
     // Split-K sizing: one wavefront per split.  The decode kernel runs one wavefront per SIMD, 256
@@ -491,6 +492,10 @@ size_t octopus_attn_decode_workspace(const octopus_codebooks_t *cb, int32_t n_se
         const DecodeShape j = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, 0, false, cap);
         total = std::max(total, make_workspace(cb->plan, j).total);
     }
+    // ... and of the matrix-core kernel over quantised values, whose row groups have at least four rows
+    const DecodeShape vqs = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, 0, false, 8,
+                                              kVqRowsFloor);
+    total = std::max(total, make_workspace(cb->plan, vqs).total);
     return total;
 }
 
@@ -545,8 +550,10 @@ static int attn_decode(const octopus_codebooks_t *cb, const void *q, int32_t q_d
                            v_dtype == OCTOPUS_DTYPE_BF16 && scores_out == nullptr;
     const int rows_cap = with_qjl ? qjl_rows_cap(cb->plan) : 8;
     if (rows_cap <= 0) return OCTOPUS_EUNSUPPORTED;
+    // quantised values without score output: the matrix-core kernel (row groups of 4 or 8)
+    const int rows_floor = with_vq && scores_out == nullptr ? kVqRowsFloor : 1;
     const DecodeShape s = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, t_capacity, many_rows,
-                                            rows_cap);
+                                            rows_cap, rows_floor);
     const Workspace w = make_workspace(cb->plan, s);
     if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < w.total) return OCTOPUS_EWORKSPACE;
     char *base = static_cast<char *>(workspace);

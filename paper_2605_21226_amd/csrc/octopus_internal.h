@@ -56,7 +56,9 @@ struct Workspace {
 };
 
 DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads,
-                              int32_t n_q, int64_t max_len, int64_t t_capacity, bool many_rows, int32_t rows_cap = 8);
+                              int32_t n_q, int64_t max_len, int64_t t_capacity, bool many_rows, int32_t rows_cap = 8,
+                              int32_t rows_floor = 1);
+constexpr int32_t kVqRowsFloor = 4;   // smallest row group of the matrix-core kernel over quantised values
 Workspace make_workspace(const octopus_plan_t &plan, const DecodeShape &s);
 
 // Kernel launchers (defined in the .hip files).  Each returns a hipError_t cast to int.

@@ -1,0 +1,3 @@
+#define OCTOPUS_D 128
+#define OCTOPUS_VB 2
+#include "octopus_plans_vqm.inc"

@@ -109,16 +109,33 @@ def run_decode_vq_case(d, bits, v_bits, group, n_seq, n_qh, n_kv, n_q, lens, see
           f"worst out err {worst_o:.3g}")
 
 
+# Without score output the call is served by the matrix-core kernel (where one is built for the shape), with
+# it by the kernel that multiplies on the vector units: both are held to the same bar.
+@pytest.mark.parametrize("want_scores", [True, False])
 @pytest.mark.parametrize("v_bits", [2, 3, 4])
 @pytest.mark.parametrize("group", [16, 32])
-def test_decode_vq_gqa_ragged_d128(v_bits, group):
-    run_decode_vq_case(128, 3, v_bits, group, 3, 8, 2, 1, [0, 77, 1000], seed=1100 + 10 * v_bits + group)
+def test_decode_vq_gqa_ragged_d128(v_bits, group, want_scores):
+    run_decode_vq_case(128, 3, v_bits, group, 3, 8, 2, 1, [0, 77, 1000], seed=1100 + 10 * v_bits + group,
+                       want_scores=want_scores)
 
 
 @pytest.mark.parametrize("d,bits,v_bits,group", [(64, 4, 4, 16), (64, 2, 2, 32), (256, 2.5, 3, 32), (256, 3, 3, 16),
                                                  (128, 1.5, 2, 16)])
-def test_decode_vq_other_shapes(d, bits, v_bits, group):
-    run_decode_vq_case(d, bits, v_bits, group, 2, 4, 2, 3, [513, 64], seed=int(1200 + d + 10 * bits))
+@pytest.mark.parametrize("want_scores", [True, False])
+def test_decode_vq_other_shapes(d, bits, v_bits, group, want_scores):
+    run_decode_vq_case(d, bits, v_bits, group, 2, 4, 2, 3, [513, 64], seed=int(1200 + d + 10 * bits),
+                       want_scores=want_scores)
+
+
+# Row groups of the matrix-core kernel: 1, 2 and 3 query rows per KV head ride in a group of four, 5 to 8 in a
+# group of eight, more in several groups; every head dimension, code width and group size it is built for.
+@pytest.mark.parametrize("d,bits,v_bits,group,n_qh,n_kv,n_q", [
+    (128, 3, 3, 32, 2, 2, 1), (128, 2, 2, 32, 4, 2, 1), (128, 4, 4, 16, 3, 1, 1), (128, 2.5, 3, 16, 8, 1, 1),
+    (128, 1, 4, 32, 4, 1, 3), (64, 3, 3, 32, 4, 1, 1), (64, 1.5, 2, 16, 8, 1, 2), (64, 4, 4, 32, 2, 2, 1),
+    (256, 3, 3, 32, 4, 1, 1), (256, 2, 4, 32, 8, 2, 1), (256, 4, 2, 16, 4, 1, 1), (256, 1.5, 2, 32, 8, 1, 1)])
+def test_decode_vq_matrix_core_row_groups(d, bits, v_bits, group, n_qh, n_kv, n_q):
+    run_decode_vq_case(d, bits, v_bits, group, 2, n_qh, n_kv, n_q, [300, 129], seed=int(1400 + d + 10 * bits + v_bits),
+                       want_scores=False)
 
 
 def test_decode_vq_long_sequence_many_items_and_errors():
