@@ -322,7 +322,7 @@ __device__ __forceinline__ void item_work(const DecodeShape &shp, const int32_t 
     const int wb = chunk * base + min(chunk, rem);
     ww->step_end = wb + base + (chunk < rem ? 1 : 0);
     ww->step_begin = wb + wave;
-    ww->step_stride = kDecodeWaves;
+    ww->step_stride = shp.item_waves;
     ww->step_last = ww->step_begin + (ww->step_begin < ww->step_end
                                           ? (ww->step_end - 1 - ww->step_begin) / ww->step_stride
                                           : 0) * ww->step_stride;
@@ -345,7 +345,8 @@ __device__ __forceinline__ bool next_item(int32_t *plan, int *slot, int tid, int
     return *it < n_items;
 }
 
-// Tiles per step of the split-K kernels: up to d = 128 a lane carries two keys (see the kernel).
+// Tiles per step of the split-K kernels: up to d = 128 a lane carries two keys (see the kernel).  The host's
+// DecodeShape carries the same number (tiles_per_step) for the kernel that cuts the items.
 template <int D>
 constexpr int decode_keys_per_lane() { return D <= 128 ? 2 : 1; }
 
@@ -364,7 +365,7 @@ __global__ __launch_bounds__(kWave) void rotate_queries_kernel(const void *__res
     constexpr int EPL = D / kWave;  // elements per lane (1, 2, 4)
     const int lane = threadIdx.x;
     // block 0 also cuts the work items of the split-K kernel that follows (not used by the many-row kernel)
-    if (blockIdx.x == 0 && plan != nullptr) build_plan(s, seq_lens, decode_keys_per_lane<D>(), plan, lane);
+    if (blockIdx.x == 0 && plan != nullptr) build_plan(s, seq_lens, s.tiles_per_step, plan, lane);
     const int rg = s.rows_per_pass;
     const int padded_rows = s.n_row_groups * rg;
     const int64_t gid = blockIdx.x;  // (seq, kvh, padded row)
@@ -631,13 +632,15 @@ typedef float mx_f32x4_t __attribute__((ext_vector_type(4)));
 // All operands come from LDS (no scalar loads in the pass), so the hardware counter of outstanding LDS reads
 // is exact and the reads of a triplet can be issued LA triplets before its products.  `hook` as in
 // tile_scores, called every 8 / RG triplets.
-template <class P, int RG, int KPL, class Hook = NoChunkHook>
+// LOOKAHEAD: triplets requested ahead of their products (4 hides the LDS latency for a wavefront that has its
+// SIMD to itself; a kernel with two wavefronts per SIMD and registers to spare for neither asks for less).
+template <class P, int RG, int KPL, class Hook = NoChunkHook, int LOOKAHEAD = 4>
 __device__ __forceinline__ void tile_scores_mx(const uint32_t (&w)[KPL][P::NWORDS], const QueryOperands<P, RG> &qop,
                                                const DecodeTables<P> &tb, int lane, float (&s)[KPL][RG],
                                                const Hook &hook = Hook{}) {
     constexpr int CT = 8 / RG;
     constexpr int NSET = QueryOperands<P, RG>::ROWS / 4;
-    constexpr int LA = P::NTRI < 4 ? P::NTRI : 4;   // triplets requested ahead
+    constexpr int LA = P::NTRI < LOOKAHEAD ? P::NTRI : LOOKAHEAD;   // triplets requested ahead
     constexpr int NB = LA + 1;
     uint4 ev[NB][KPL], qv[NB][NSET];
     mx_f32x4_t d_main[KPL][NSET], d_cross[KPL][NSET];
@@ -1462,8 +1465,8 @@ __global__ __launch_bounds__(kWave) void merge_kernel(DecodeShape shp, const flo
         const int before = plan[kPlanHeader + seq];
         const int c_s = (plan[kPlanHeader + seq + 1] - before) / G;
         const int64_t first = before + static_cast<int64_t>(kvh * shp.n_row_groups + grp) * c_s;
-        prow0 = first * kDecodeWaves * shp.rows_per_pass + r;
-        n_part = c_s * kDecodeWaves;
+        prow0 = first * shp.item_waves * shp.rows_per_pass + r;
+        n_part = c_s * shp.item_waves;
         pstride = shp.rows_per_pass;
     }
     float m = -INFINITY;

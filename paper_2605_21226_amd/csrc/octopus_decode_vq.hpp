@@ -32,10 +32,16 @@ namespace octopus {
 //     leading parts in rows r, remainders in rows RP + r of the group's share; a column reads the rows of ITS
 //     group from the result and ignores the others, so an N-block costs NA = (64 / v_group) / GPA MFMAs per
 //     k-step: one for groups of 32 channels and four query rows, the same as over bf16 values.
+// Wavefronts per workgroup: two per SIMD up to d = 128 (each within 256 registers), whose different phases --
+// vector work, matrix-core work, LDS traffic -- the hardware overlaps; one per SIMD at d = 256.
+template <class P>
+constexpr int vq_waves() { return P::D <= 128 ? 8 : 4; }
+
 template <class P, int RG, int VB, int VG>
 struct VqGeometry {
     static constexpr int D = P::D;
-    static constexpr int KPL = decode_keys_per_lane<D>();
+    static constexpr int KPL = 1;                           // tiles per step: one key per lane
+    static constexpr int NWV = vq_waves<P>();
     static constexpr int CB = VB * D / 8;                   // code bytes per row
     static constexpr int G = D / VG;                        // groups per row
     static constexpr int RB = CB + 8 * G;                   // bytes per row
@@ -58,9 +64,9 @@ struct DecodeSmemVq {
     DecodeTables<P> tb;
     // scaled probabilities of XT 64-key tiles as bf16: [tile][group][leading part, remainder][row][key slot];
     // a row is padded by 16 bytes, so that the 16 rows the lanes of an A operand read lie in different banks
-    __attribute__((aligned(16))) uint16_t xs[kDecodeWaves][XT][Gm::G][2][RG][kVqRow];
-    float zbuf[kDecodeWaves][Gm::ZP];
-    __attribute__((aligned(16))) unsigned char stage[kDecodeWaves][Gm::STEP_BYTES];
+    __attribute__((aligned(16))) uint16_t xs[Gm::NWV][XT][Gm::G][2][RG][kVqRow];
+    float zbuf[Gm::NWV][Gm::ZP];
+    __attribute__((aligned(16))) unsigned char stage[Gm::NWV][Gm::STEP_BYTES];
 };
 
 // Shapes the kernel is built for: row groups of 4 or 8, at most 64 (row, group) pairs, at most 32
@@ -69,11 +75,9 @@ template <class P, int RG, int VB, int VG, int XT>
 constexpr bool vq_lds_fits() {
     return sizeof(DecodeSmemVq<P, RG, VB, VG, XT>) + (mx_scores<P>() ? sizeof(QueryOperands<P, RG>) : 16) + 64 <= 160 * 1024;
 }
-// Tiles whose scaled probabilities are in LDS at once: a whole step's if there is room, else one.
+// Tiles whose scaled probabilities are in LDS at once (a step is one tile).
 template <class P, int RG, int VB, int VG>
-constexpr int vq_xs_tiles() {
-    return vq_lds_fits<P, RG, VB, VG, decode_keys_per_lane<P::D>()>() ? decode_keys_per_lane<P::D>() : 1;
-}
+constexpr int vq_xs_tiles() { return 1; }
 template <class P, int RG, int VB, int VG>
 constexpr bool vq_mfma_fits() {
     using Gm = VqGeometry<P, RG, VB, VG>;
@@ -81,14 +85,15 @@ constexpr bool vq_mfma_fits() {
 }
 
 template <class P, int RG, int VB, int VG>
-__global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) void decode_kernel_vq_mfma(
+__global__ __launch_bounds__(vq_waves<P>() * kWave)
+    __attribute__((amdgpu_waves_per_eu(vq_waves<P>() / 4, vq_waves<P>() / 4))) void decode_kernel_vq_mfma(
     DeviceBooks books, DecodeShape shp, const float *__restrict__ q_rot, const uint4 *__restrict__ cache,
     const unsigned char *__restrict__ vq, const int32_t *__restrict__ seq_lens, float *__restrict__ part_ml,
     float *__restrict__ part_acc, int32_t *__restrict__ plan) {
     using Gm = VqGeometry<P, RG, VB, VG>;
     static_assert(RG == 4 || RG == 8, "row groups of 4 or 8");
     constexpr int D = P::D, KPL = Gm::KPL, CPL = Gm::CPL, RP = Gm::RP, RB = Gm::RB, CB = Gm::CB;
-    constexpr int PCS = Gm::PCS, NA = Gm::NA, GPA = Gm::GPA, GPB = Gm::GPB, G = Gm::G, NLS = Gm::NLS;
+    constexpr int PCS = Gm::PCS, NA = Gm::NA, GPA = Gm::GPA, GPB = Gm::GPB, G = Gm::G, NLS = Gm::NLS, NWV = Gm::NWV;
     constexpr int STEP_BYTES = Gm::STEP_BYTES;
     constexpr int TILEB = P::GRANULES * kWave * 16;  // bytes per cache tile
     constexpr bool MX = mx_scores<P>();
@@ -209,19 +214,19 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
             }
         }
     };
-    // The B operands of a step are built during its score pass, a piece = (k-step, 64-channel piece of the
-    // rows) at a time, from the staged rows alone (the pass keeps the matrix cores and LDS busy and leaves the
+    // The B operands of a step are built during its score pass, half a piece = (k-step, 64-channel piece of the
+    // rows, 4 of the lane's 8 keys) at a time, from the staged rows alone (the pass keeps the matrix cores and LDS busy and leaves the
     // vector units idle; building the operands is vector work).  The words around the code fields of a piece
     // are requested one slot before they are used.
-    constexpr int NPB = KS * PCS;
-    struct RawPiece { uint32_t lo[8], hi[8]; };
+    constexpr int NPB = 2 * KS * PCS;   // half pieces: 4 keys (2 words of each of the piece's 4 B operands) each
+    struct RawPiece { uint32_t lo[4], hi[4]; };
     RawPiece raw[NPB];
     uint32_t vbw[KS][PCS][4][4];   // [k-step][piece][N-block of the piece][word]
     auto raw_request = [&](auto pp) __attribute__((always_inline)) {
-        constexpr int pi = decltype(pp)::value, ks = pi / PCS, pc = pi % PCS;
+        constexpr int pi = decltype(pp)::value, ks = pi / (2 * PCS), pc = (pi / 2) % PCS, half = pi % 2;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const unsigned char *src = code_lane + (32 * ks + 4 * j) * RB + pc * PIECE_BYTES;
+        for (int j = 0; j < 4; ++j) {
+            const unsigned char *src = code_lane + (32 * ks + 4 * (4 * half + j)) * RB + pc * PIECE_BYTES;
             if constexpr (VB == 3) {
                 const uint32_t *wp = reinterpret_cast<const uint32_t *>(src);
                 raw[pi].lo[j] = wp[0];
@@ -234,14 +239,14 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
         }
     };
     auto b_build = [&](auto pp) __attribute__((always_inline)) {
-        constexpr int pi = decltype(pp)::value, ks = pi / PCS, pc = pi % PCS;
+        constexpr int pi = decltype(pp)::value, ks = pi / (2 * PCS), pc = (pi / 2) % PCS, half = pi % 2;
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
+        for (int jh = 0; jh < 2; ++jh) {
             uint32_t t[2];
 #pragma unroll
             for (int o = 0; o < 2; ++o) {
-                if constexpr (VB == 3) t[o] = __builtin_amdgcn_alignbit(raw[pi].hi[2 * jj + o], raw[pi].lo[2 * jj + o], code_sh);
-                else t[o] = raw[pi].lo[2 * jj + o];
+                if constexpr (VB == 3) t[o] = __builtin_amdgcn_alignbit(raw[pi].hi[2 * jh + o], raw[pi].lo[2 * jh + o], code_sh);
+                else t[o] = raw[pi].lo[2 * jh + o];
             }
             const uint32_t cu = __builtin_amdgcn_perm(t[1], t[0], 0x05040100u);   // two keys' fields side by side
 #pragma unroll
@@ -251,7 +256,7 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
                 // (written out: the compiler's own choice is an and and an or)
                 uint32_t word;
                 asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(word) : "v"(moved), "s"(CODE_MASK), "v"(CODE_BASE));
-                vbw[ks][pc][e][jj] = word;
+                vbw[ks][pc][e][2 * half + jh] = word;
             }
         }
     };
@@ -286,8 +291,8 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
     };
 
     uint4 rows[NLS];   // the value rows of the wave's next step, in flight; staged at the top of that step
-    auto process_step = [&](int step, const uint32_t (&w)[KPL][P::NWORDS], uint32_t (&w_next)[KPL][P::NWORDS])
-                            __attribute__((always_inline)) {
+    uint32_t w[KPL][P::NWORDS];   // the records of the wave's next step, in flight; replaced after the score pass
+    auto process_step = [&](int step) __attribute__((always_inline)) {
         const int t0 = step * (KPL * kWave);
         const int n_valid = min(KPL * kWave, ww.len - t0);
         // this step's rows, asked for one step ago, into LDS as they lie in memory ...
@@ -296,17 +301,13 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
             const int off = (i * kWave + lane) * 16;
             if ((i + 1) * 1024 <= STEP_BYTES || off < STEP_BYTES) *reinterpret_cast<uint4 *>(stage_w + off) = rows[i];
         }
-        // ... and the next step's rows and records on their way (the wave's last step re-reads its own records;
-        // its row loads go through an empty descriptor)
+        // ... and the next step's rows on their way (the row loads of a step that does not exist go through an
+        // empty descriptor)
         const int step_nx = min(step + ww.step_stride, ww.step_last);
         load_rows(step_nx, step + ww.step_stride < ww.step_end, rows);
-        load_records(step_nx, w_next);
         asm volatile("" ::: "memory");
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        // scales and zero points of this lane's keys (used after the softmax)
-        float2 sz[KPL][G];
-        load_meta(sz);
         float s[KPL][RG];
         int q_off = 0;
         asm volatile("" : "+s"(q_off));
@@ -326,7 +327,7 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
                 if constexpr (pi * (NCH - 1) / NPB == ci) raw_request(pp);
             });
         };
-        if constexpr (MX) tile_scores_mx<P, RG, KPL>(w, qop, sm.tb, lane, s, build_in_chunk);
+        if constexpr (MX) tile_scores_mx<P, RG, KPL, decltype(build_in_chunk), (NWV > 4 ? 2 : 4)>(w, qop, sm.tb, lane, s, build_in_chunk);
         else tile_scores<P, RG, KPL>(w, qg + q_off, sm.tb, lane, s, build_in_chunk);
 #pragma unroll
         for (int k = 0; k < KPL; ++k) {
@@ -335,6 +336,11 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
 #pragma unroll
             for (int r = 0; r < RG; ++r) s[k][r] = valid ? s[k][r] * gamma : -INFINITY;
         }
+        // the records are used up: the next step's take their place (the wave's last step re-reads its own);
+        // scales and zero points of this lane's keys for the products below
+        load_records(step_nx, w);
+        float2 sz[KPL][G];
+        load_meta(sz);
         // D5: online softmax, one running maximum per row for the whole wave; s becomes the probabilities
         float alpha[RG];
 #pragma unroll
@@ -386,7 +392,6 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
         });
     };
 
-    uint32_t w_a[KPL][P::NWORDS], w_b[KPL][P::NWORDS];
     int it, taken = 0;
     while (next_item(plan, &item_slot, tid, &taken, &it)) {
         item_work(shp, plan, seq_lens, it, wave, KPL, &ww);
@@ -413,10 +418,10 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
             for (int hh = 0; hh < NA; ++hh) acc[c][hh] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
 
         const bool any = ww.step_begin < ww.step_end;
-        if (any) load_records(ww.step_begin, w_a);
+        if (any) load_records(ww.step_begin, w);
         load_rows(ww.step_begin, any, rows);
         if (!tables_built) {   // workgroup-uniform
-            build_tables<P, MX>(sm.tb, books, tid, kDecodeWaves * kWave);
+            build_tables<P, MX>(sm.tb, books, tid, NWV * kWave);
             tables_built = true;
         }
         if constexpr (MX) {
@@ -424,7 +429,7 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
             // here (next_item's barriers, or this is the workgroup's only item).
             constexpr int ROWS = QueryOperands<P, RG>::ROWS;
             uint4 *dst = reinterpret_cast<uint4 *>(&qop_store[0]);
-            for (int e = tid; e < P::NTRI * ROWS; e += kDecodeWaves * kWave) {
+            for (int e = tid; e < P::NTRI * ROWS; e += NWV * kWave) {
                 const int i = e / ROWS, r = e % ROWS;
                 float x = 0.0f, y = 0.0f, z = 0.0f;
                 if (r < RG) {
@@ -436,10 +441,7 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
             }
             __syncthreads();
         }
-        for (int step = ww.step_begin; step < ww.step_end; step += 2 * ww.step_stride) {
-            process_step(step, w_a, w_b);
-            if (step + ww.step_stride < ww.step_end) process_step(step + ww.step_stride, w_b, w_a);
-        }
+        for (int step = ww.step_begin; step < ww.step_end; step += ww.step_stride) process_step(step);
 
         // D7: the zero-point sums of the lanes are added up and handed to the lanes that hold the channels ...
 #pragma unroll
@@ -453,7 +455,7 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
         __builtin_amdgcn_wave_barrier();
         // ... which add the leading-part and remainder rows of their group (lane groups 16 or 32 lanes apart)
         // and emit the wave's partial of this item
-        const int64_t pbase = (static_cast<int64_t>(it) * kDecodeWaves + wave) * RG;
+        const int64_t pbase = (static_cast<int64_t>(it) * NWV + wave) * RG;
         const int lgrp = (4 * n16) / VG;                 // group of this lane's columns within a piece
         const int a_sel = lgrp / GPA, member = lgrp % GPA;
         const bool holder = RP == 4 ? g4 == 2 * member : g4 < 2;
@@ -494,7 +496,9 @@ int launch_decode_vq_mfma_one(const octopus_codebooks_t &cb, const DecodeShape &
                               hipStream_t stream) {
     if constexpr (vq_mfma_fits<P, RG, VB, VG>()) {
         const DeviceBooks books = device_books(cb);
-        hipLaunchKernelGGL((decode_kernel_vq_mfma<P, RG, VB, VG>), dim3(kDecodeWorkgroups), dim3(kDecodeWaves * kWave), 0,
+        constexpr int NWV = VqGeometry<P, RG, VB, VG>::NWV;
+        if (s.item_waves != NWV || s.tiles_per_step != 1) return static_cast<int>(hipErrorInvalidValue);
+        hipLaunchKernelGGL((decode_kernel_vq_mfma<P, RG, VB, VG>), dim3(kDecodeWorkgroups), dim3(NWV * kWave), 0,
                            stream, books, s, q_rot, static_cast<const uint4 *>(cache),
                            static_cast<const unsigned char *>(vq), seq_lens, part_ml, part_acc, plan);
         return static_cast<int>(hipGetLastError());

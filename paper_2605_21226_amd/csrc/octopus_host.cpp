@@ -222,7 +222,7 @@ bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 
 DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads,
                               int32_t n_q, int64_t max_len, int64_t t_capacity, bool many_rows, int32_t rows_cap,
-                              int32_t rows_floor) {
+                              bool vq_mfma) {
     DecodeShape s{};
     s.n_seq = n_seq;
     s.n_q_heads = n_q_heads;
@@ -232,6 +232,8 @@ DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t
     s.rows_per_kv = n_q * s.heads_per_kv;
     s.t_capacity = t_capacity;
     s.max_len = static_cast<int32_t>(max_len);
+    s.item_waves = 4;
+    s.tiles_per_step = plan.head_dim <= 128 ? 2 : 1;
     const int64_t len = std::max<int64_t>(max_len, 1);
     if (many_rows) {
         // Matrix-core kernel for many query rows: blocks of 128 rows (4 wavefronts), or of 256 rows (8
@@ -256,16 +258,23 @@ DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t
     }
     // Query rows scored per key by one workgroup: the power of two covering rows_per_kv, at most 8
     // (fewer with the QJL residual).  Rows beyond rows_per_kv in the last group are zero queries whose
-    // results are not stored.  rows_floor: the smallest group the kernel that will serve the call is built for.
-    s.rows_per_pass = std::max(1, rows_floor);
+    // results are not stored.
+    s.rows_per_pass = 1;
     while (s.rows_per_pass < s.rows_per_kv && s.rows_per_pass < rows_cap) s.rows_per_pass *= 2;
+    if (vq_mfma) {
+        // The matrix-core kernel over quantised values: row groups of 4 or 8; up to d = 128 two wavefronts per
+        // SIMD (8 per workgroup), each taking one tile per step.
+        s.rows_per_pass = vq_mfma_rows(s.rows_per_kv);
+        s.tiles_per_step = 1;
+        s.item_waves = plan.head_dim <= 128 ? 8 : 4;
+    }
     s.n_row_groups = (s.rows_per_kv + s.rows_per_pass - 1) / s.rows_per_pass;
     // Split-K sizing: one wavefront per split.  The decode kernel runs one wavefront per SIMD, 256
     // compute units x 4 at once; the steps (128 keys up to d = 128, 64 keys at d = 256) of each
     // (sequence, KV head, row group) are divided over as many splits as fill those slots once, so that
     // all wavefronts start together and end together.
     const int64_t groups = static_cast<int64_t>(n_seq) * n_kv_heads * s.n_row_groups;
-    const int64_t step_keys = OCTOPUS_TILE * (plan.head_dim <= 128 ? 2 : 1);
+    const int64_t step_keys = OCTOPUS_TILE * s.tiles_per_step;
     const int64_t max_steps = (len + step_keys - 1) / step_keys;
     const int64_t slots = 256 * 4;
     // workgroups of 4 wavefronts: splits come in fours
@@ -290,7 +299,7 @@ Workspace make_workspace(const octopus_plan_t &plan, const DecodeShape &s) {
     // partial results: one per (row, split) with blocks of 128 or 256 rows, else one per (item, wavefront, row of
     // the group)
     const size_t partials = s.rows_per_pass >= 128 ? rows * s.n_splits
-                                                   : static_cast<size_t>(s.max_items) * 4 * s.rows_per_pass;
+                                                   : static_cast<size_t>(s.max_items) * s.item_waves * s.rows_per_pass;
     w.q_rot_off = 0;
     const size_t q_bytes = up(rows * q_row_stride(plan.n_tri) * sizeof(float));
     w.part_ml_off = q_bytes;
@@ -477,9 +486,9 @@ static int decode_args_ok(const octopus_codebooks_t *cb, int32_t n_seq, int32_t 
     return OCTOPUS_OK;
 }
 
-size_t octopus_attn_decode_workspace(const octopus_codebooks_t *cb, int32_t n_seq, int32_t n_q_heads,
+// Workspace of a decode call without quantised values (what octopus_attn_decode_static has to fit).
+static size_t plain_decode_workspace(const octopus_codebooks_t *cb, int32_t n_seq, int32_t n_q_heads,
                                      int32_t n_kv_heads, int32_t n_q, int64_t max_len) {
-    if (decode_args_ok(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len) != OCTOPUS_OK) return 0;
     const DecodeShape s = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, 0, false);
     size_t total = make_workspace(cb->plan, s).total;
     if (many_rows_shape(cb->plan, n_q_heads, n_kv_heads, n_q)) {   // the larger of the two kernels' needs
@@ -492,9 +501,15 @@ size_t octopus_attn_decode_workspace(const octopus_codebooks_t *cb, int32_t n_se
         const DecodeShape j = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, 0, false, cap);
         total = std::max(total, make_workspace(cb->plan, j).total);
     }
-    // ... and of the matrix-core kernel over quantised values, whose row groups have at least four rows
-    const DecodeShape vqs = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, 0, false, 8,
-                                              kVqRowsFloor);
+    return total;
+}
+
+size_t octopus_attn_decode_workspace(const octopus_codebooks_t *cb, int32_t n_seq, int32_t n_q_heads,
+                                     int32_t n_kv_heads, int32_t n_q, int64_t max_len) {
+    if (decode_args_ok(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len) != OCTOPUS_OK) return 0;
+    size_t total = plain_decode_workspace(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len);
+    // ... and of the matrix-core kernel over quantised values (row groups of 4 or 8, up to 8 wavefronts an item)
+    const DecodeShape vqs = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, 0, false, 8, true);
     total = std::max(total, make_workspace(cb->plan, vqs).total);
     return total;
 }
@@ -514,7 +529,7 @@ static int attn_decode(const octopus_codebooks_t *cb, const void *q, int32_t q_d
                        int64_t t_capacity, const void *v, int32_t v_dtype, const int32_t *seq_lens, int64_t max_len,
                        float scale, float *out, float *scores_out, void *workspace, size_t workspace_bytes,
                        void *stream, bool with_qjl, const uint8_t *signs2, const void *qjl, int v_bits = 0,
-                       int v_group = 0, const WindowArgs *win = nullptr) {
+                       int v_group = 0, const WindowArgs *win = nullptr, bool static_scratch_call = false) {
     const bool with_vq = v_bits != 0;    // v: group-quantised rows (v_dtype is not looked at)
     // the measurement events belong to THIS call whatever becomes of it: a call that fails leaves none armed
     void *ev_before = g_event_before, *ev_after = g_event_after;
@@ -550,12 +565,18 @@ static int attn_decode(const octopus_codebooks_t *cb, const void *q, int32_t q_d
                            v_dtype == OCTOPUS_DTYPE_BF16 && scores_out == nullptr;
     const int rows_cap = with_qjl ? qjl_rows_cap(cb->plan) : 8;
     if (rows_cap <= 0) return OCTOPUS_EUNSUPPORTED;
-    // quantised values without score output: the matrix-core kernel (row groups of 4 or 8)
-    const int rows_floor = with_vq && scores_out == nullptr ? kVqRowsFloor : 1;
+    // quantised values without score output: the matrix-core kernel where one is built for the shape
+    const bool vq_mfma = with_vq && scores_out == nullptr &&
+                         vq_mfma_available(cb->plan, vq_mfma_rows(n_q * (n_q_heads / n_kv_heads)), v_bits, v_group);
     const DecodeShape s = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, t_capacity, many_rows,
-                                            rows_cap, rows_floor);
+                                            rows_cap, vq_mfma);
     const Workspace w = make_workspace(cb->plan, s);
-    if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < w.total) return OCTOPUS_EWORKSPACE;
+    // every entry point asks for the one documented size, whatever its own kernel needs (the static scratch
+    // has been checked against the need of the kernels it serves)
+    const size_t required = static_scratch_call ? w.total
+                                                : std::max(w.total, octopus_attn_decode_workspace(cb, n_seq, n_q_heads, n_kv_heads,
+                                                                                                  n_q, max_len));
+    if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < required) return OCTOPUS_EWORKSPACE;
     char *base = static_cast<char *>(workspace);
     float *q_rot = reinterpret_cast<float *>(base + w.q_rot_off);
     float *part_ml = reinterpret_cast<float *>(base + w.part_ml_off);
@@ -639,8 +660,8 @@ int octopus_attn_decode_static(const octopus_codebooks_t *cb, const void *q, int
     const int ok = decode_args_ok(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len);
     if (ok != OCTOPUS_OK) return ok;
     // the shapes must fit the static array: refused here, before anything is looked up or launched
-    const size_t need = octopus_attn_decode_workspace(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len);
-    if (need == 0) return OCTOPUS_EINVAL;
+    if (decode_args_ok(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len) != OCTOPUS_OK) return OCTOPUS_EINVAL;
+    const size_t need = plain_decode_workspace(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len);
     if (need > static_cast<size_t>(OCTOPUS_STATIC_SCRATCH_BYTES)) return OCTOPUS_ESCRATCH;
     int err = OCTOPUS_OK;
     void *ws = static_scratch(&err);
@@ -649,7 +670,7 @@ int octopus_attn_decode_static(const octopus_codebooks_t *cb, const void *q, int
     // counter, and every partial result that the merge reads is written by the call's own main kernel
     return attn_decode(cb, q, q_dtype, n_seq, n_q_heads, n_kv_heads, n_q, signs, cache, t_capacity, v, v_dtype,
                        seq_lens, max_len, scale, out, scores_out, ws, OCTOPUS_STATIC_SCRATCH_BYTES, stream, false,
-                       nullptr, nullptr);
+                       nullptr, nullptr, 0, 0, nullptr, true);
 }
 
 int octopus_attn_decode_hybrid(const octopus_codebooks_t *cb, const void *q, int32_t q_dtype, int32_t n_seq,
@@ -777,7 +798,8 @@ int octopus_attn_decode_paged(const octopus_codebooks_t *cb, const void *q, int3
     if (!aligned(q, 4) || !aligned(out, 4) || !std::isfinite(scale)) return OCTOPUS_EINVAL;
     const DecodeShape s = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, reach, false);
     const Workspace w = make_workspace(cb->plan, s);
-    if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < w.total) return OCTOPUS_EWORKSPACE;
+    const size_t required = std::max(w.total, octopus_attn_decode_workspace(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len));
+    if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < required) return OCTOPUS_EWORKSPACE;
     char *base = static_cast<char *>(workspace);
     float *q_rot = reinterpret_cast<float *>(base + w.q_rot_off);
     float *part_ml = reinterpret_cast<float *>(base + w.part_ml_off);
