@@ -244,15 +244,19 @@ DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t
         const int64_t groups = static_cast<int64_t>(n_seq) * n_kv_heads * s.n_row_groups;
         const int64_t max_tiles = (len + OCTOPUS_TILE - 1) / OCTOPUS_TILE;
         const int64_t slots = (plan.head_dim <= 64 && s.rows_per_pass == 128) ? 512 : 256;
-        // The workgroups run in rounds of `slots`; pick the split count (each split keeping at least 16
-        // tiles) whose last round is fullest, the smallest such count on ties.
-        int64_t best = 1;
-        double best_eff = 0.0;
-        for (int64_t n = 1; n <= 32 && (n == 1 || max_tiles / n >= 16); ++n) {
+        // The workgroups run in rounds of `slots`.  Among the split counts (each split keeping at least 16 tiles)
+        // the fullest last round wins, but every split writes a partial result per query row that the merge reads
+        // again: the smallest count within 3 % of the best fill is taken (the Lumiere-shaped batch: 7 splits
+        // at 98.4 % instead of 32 at 100 %, a fifth of the partial traffic).
+        auto fill = [&](int64_t n) {
             const int64_t wgs = groups * n, rounds = (wgs + slots - 1) / slots;
-            const double eff = static_cast<double>(wgs) / static_cast<double>(rounds * slots);
-            if (eff > best_eff + 1e-9) { best_eff = eff; best = n; }
-        }
+            return static_cast<double>(wgs) / static_cast<double>(rounds * slots);
+        };
+        double best_eff = 0.0;
+        for (int64_t n = 1; n <= 32 && (n == 1 || max_tiles / n >= 16); ++n) best_eff = std::max(best_eff, fill(n));
+        int64_t best = 1;
+        for (int64_t n = 1; n <= 32 && (n == 1 || max_tiles / n >= 16); ++n)
+            if (fill(n) >= best_eff - 0.03) { best = n; break; }
         s.n_splits = static_cast<int32_t>(best);
         return s;
     }
