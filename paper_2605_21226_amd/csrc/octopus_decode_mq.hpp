@@ -30,6 +30,7 @@ namespace octopus {
 // workgroup, so more rows mean less decoding; the host picks 256 when there are rows enough to fill them.
 
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+constexpr int kXcds = 8;   // accelerator dies of the chip; consecutive workgroups go to consecutive dies
 
 template <class P>
 struct MqSmem {
@@ -72,11 +73,18 @@ __global__ __launch_bounds__(kWave *NW) __attribute__((amdgpu_waves_per_eu(P::D 
     build_dir_lut<P::BD0>(sm.dir0, sm.c_xi[0], tid, kWave * NW);
     if constexpr (P::NCLASS == 2) build_dir_lut<P::BD1>(sm.dir1, sm.c_xi[1], tid, kWave * NW);
 
-    // work: (sequence, KV head, block of ROWS rows, split) and the split's tiles
-    const int64_t wg = blockIdx.x;
-    const int split = static_cast<int>(wg % shp.n_splits);
-    const int64_t group_id = wg / shp.n_splits;
-    const int64_t pair = group_id / shp.n_row_groups;
+    // work: (sequence, KV head, block of ROWS rows, split) and the split's tiles.  The blocks of rows of one
+    // (sequence, KV head, split) read the same keys and values: they are given to ONE accelerator die (workgroup
+    // b runs on die b % 8, each with its own L2), next to each other in that die's sequence of workgroups, so
+    // that the tiles are fetched from memory once and not once per die.  Unit u = (pair, split) goes to die
+    // u % 8; the grid is padded to whole rounds of 8 units (the workgroups of units that do not exist leave).
+    const int64_t slot = blockIdx.x / kXcds;
+    const int64_t unit = (slot / shp.n_row_groups) * kXcds + blockIdx.x % kXcds;
+    const int64_t n_units = static_cast<int64_t>(shp.n_seq) * shp.n_kv_heads * shp.n_splits;
+    if (unit >= n_units) return;   // (whole workgroup, before any barrier)
+    const int split = static_cast<int>(unit % shp.n_splits);
+    const int64_t pair = unit / shp.n_splits;
+    const int64_t group_id = pair * shp.n_row_groups + slot % shp.n_row_groups;
     const int seq = static_cast<int>(pair / shp.n_kv_heads);
     const int len = min(max(seq_lens[seq], 0), shp.max_len);
     const int n_tiles = (len + kWave - 1) / kWave;
@@ -328,7 +336,8 @@ template <class P>
 int launch_decode_mq(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
                      const void *v, const int32_t *seq_lens, float *part_ml, float *part_acc, hipStream_t stream) {
     const DeviceBooks books = device_books(cb);
-    const int64_t wgs = static_cast<int64_t>(s.n_seq) * s.n_kv_heads * s.n_row_groups * s.n_splits;
+    const int64_t units = static_cast<int64_t>(s.n_seq) * s.n_kv_heads * s.n_splits;
+    const int64_t wgs = (units + kXcds - 1) / kXcds * kXcds * s.n_row_groups;   // see the kernel's work mapping
     auto go = [&](auto kernel, int waves) {
         hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(wgs)), dim3(kWave * waves), 0, stream, books, s, q_rot,
                            static_cast<const uint4 *>(cache), static_cast<const uint16_t *>(v), seq_lens, part_ml, part_acc);
