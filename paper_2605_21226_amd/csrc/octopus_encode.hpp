@@ -29,21 +29,37 @@ struct SeedGrid {
     }
 };
 
-// The direction table and the seed grid are kept in two copies up to d = 128 (entry e of copy r at index
-// e * REP + r, lane l reads copy l % REP), which halves the LDS bank conflicts of the lookups; more
-// copies, or any at d = 256, would cost a resident workgroup per compute unit (measured slower).
+// The direction table holds ONE QUADRANT of the code grid: a Lloyd-Max codebook of the symmetric marginal is
+// antisymmetric (C_xi[K - 1 - j] = -C_xi[j], checked on the host), and Oct^-1(-xi, eta) is Oct^-1(xi, eta) with
+// its first component negated, bit for bit (likewise eta and the second component).  Entry (fx, fy), fx, fy <
+// K / 2, is Oct^-1(C_xi[fx], C_xi[fy]); a code (jx, jy) reads entry (min(jx, K-1-jx), min(jy, K-1-jy)) and negates
+// the key's x (y) coordinate instead of the entry's when jx (jy) lies in the upper half -- the products, and so
+// the scores, are the same numbers.  A quarter of the entries pays for four times the copies: copy r of entry
+// e sits at index e * REP + r and lane l reads copy l % REP, so with 8 copies of 16 bytes any 8 neighbouring lanes
+// read 8 different groups of banks whatever their codes (two copies of the full table left the candidate reads
+// with about one conflict cycle per useful cycle).  At d = 256 and for 6-bit direction codes four copies fit the
+// budget (more LDS would cost a resident workgroup per compute unit).  The seed grid keeps two copies up to
+// d = 128.
 template <int D, int BD = 1>
-constexpr int encode_table_rep() { return (D <= 128 && BD <= 5) ? 2 : 1; }
+constexpr int encode_table_rep() { return (D <= 128 && BD <= 5) ? 8 : 4; }
+template <int D>
+constexpr int encode_cell_rep() { return D <= 128 ? 2 : 1; }
+constexpr int quadrant_entries(int bd) { return bd <= 1 ? 1 : (1 << (2 * (bd - 1))); }
 
 template <class P>
 struct EncodeSmem {
     float u[3 * P::NTRI][kURow];           // rotated coordinates [coordinate][key]
     uint32_t rec[P::NWORDS][kWave];        // packed records [word][key]
     static constexpr int REP = encode_table_rep<P::D, (P::BD0 > P::BD1 ? P::BD0 : P::BD1)>();
-    float4 lut0[(1 << (2 * P::BD0)) * REP];
-    float4 lut1[P::NCLASS == 2 ? (1 << (2 * P::BD1)) * REP : 1];
-    float2 cell0[SeedGrid<P::BD0>::NCELL * REP];
-    float2 cell1[P::NCLASS == 2 ? SeedGrid<(P::BD1 > 0 ? P::BD1 : 1)>::NCELL * REP : 1];
+    static constexpr int CREP = encode_cell_rep<P::D>();
+    float4 lut0[quadrant_entries(P::BD0) * REP];
+    float4 lut1[P::NCLASS == 2 ? quadrant_entries(P::BD1) * REP : 1];
+    float2 cell0[SeedGrid<P::BD0>::NCELL * CREP];
+    float2 cell1[P::NCLASS == 2 ? SeedGrid<(P::BD1 > 0 ? P::BD1 : 1)>::NCELL * CREP : 1];
+    // neighbours of a seed index j on the x and on the y axis, [j][dx + 1]: {+-1 (the sign the key's coordinate
+    // takes), byte offset of the candidate's row / column in the quadrant table}
+    float2 nbx0[(1 << P::BD0) * 3], nby0[(1 << P::BD0) * 3];
+    float2 nbx1[P::NCLASS == 2 ? (1 << P::BD1) * 3 : 1], nby1[P::NCLASS == 2 ? (1 << P::BD1) * 3 : 1];
     float c_xi[2][kMaxLevels];
     float c_rho[2][kMaxLevels];
     float bnd_xi[2][kMaxLevels + 1];       // boundaries, +inf padded
@@ -53,13 +69,31 @@ struct EncodeSmem {
 };
 
 template <int BD, int REP>
-__device__ __forceinline__ void build_encode_lut(float4 *lut, const float *c_xi, int tid, int nthreads) {
-    constexpr int K = 1 << BD;
-    for (int e = tid; e < K * K; e += nthreads) {
-        const float4 n = oct_decode(c_xi[e & (K - 1)], c_xi[e >> BD]);
-#pragma unroll
-        for (int r = 0; r < REP; ++r) lut[e * REP + r] = n;
+__device__ __forceinline__ void build_encode_lut(float4 *lut, float2 *nbx, float2 *nby, const float *c_xi, int tid,
+                                                 int nthreads) {
+    constexpr int K = 1 << BD, H = BD <= 1 ? 1 : K / 2;
+    // (one table slot per thread and round: every copy computes its own entry, which is quicker than a quarter of
+    // the threads writing eight copies each)
+    for (int e = tid; e < H * H * REP; e += nthreads) lut[e] = oct_decode(c_xi[(e / REP) % H], c_xi[(e / REP) / H]);
+    for (int e = tid; e < 3 * K; e += nthreads) {
+        const int j = min(max(e / 3 + e % 3 - 1, 0), K - 1);   // the clamped neighbour (Alg. 1's window at the rim)
+        const int f = min(j, K - 1 - j);
+        const float sign = j >= H && K > 1 ? -1.0f : 1.0f;
+        nbx[e] = make_float2(sign, __uint_as_float(static_cast<uint32_t>(f * REP * 16)));
+        nby[e] = make_float2(sign, __uint_as_float(static_cast<uint32_t>(f * H * REP * 16)));
     }
+}
+
+// Oct^-1 of the centroids of a direction code, from the quadrant table.
+template <int BD, int REP>
+__device__ __forceinline__ float4 dir_lookup(const float4 *lut, uint32_t code, int lane) {
+    constexpr int K = 1 << BD, H = BD <= 1 ? 1 : K / 2;
+    const int jx = static_cast<int>(code & (K - 1)), jy = static_cast<int>(code >> BD);
+    const int fx = min(jx, K - 1 - jx), fy = min(jy, K - 1 - jy);
+    float4 n = lut[(fx + fy * H) * REP + (lane & (REP - 1))];
+    if (jx >= H) n.x = -n.x;
+    if (jy >= H) n.y = -n.y;
+    return n;
 }
 
 template <int BD, int REP>
@@ -103,10 +137,11 @@ __device__ __forceinline__ void butterflies(float (&x)[R]) {
 }
 
 // One triplet of one key: E4-E7 of the hot path.  Returns the packed direction field and norm index.
-template <int BD, int BN, int REP>
+template <int BD, int BN, int REP, int CREP>
 __device__ __forceinline__ void encode_triplet(float x, float y, float z, const float4 *lut, const float2 *cell,
-                                               const float *bnd_xi, const float *bnd_rho, int lane,
-                                               uint32_t *dir_field, uint32_t *nrm_index) {
+                                               const float2 *nbx, const float2 *nby, const float *bnd_xi,
+                                               const float *bnd_rho, int lane, uint32_t *dir_field,
+                                               uint32_t *nrm_index) {
     constexpr int K = 1 << BD, M = 1 << BN;
     // Eq. (oct-encode)
     const float l1 = fabsf(x) + fabsf(y) + fabsf(z);
@@ -123,11 +158,23 @@ __device__ __forceinline__ void encode_triplet(float x, float y, float z, const 
         eta = (py >= 0.0f) ? fy : -fy;
     }
     // scalar seed
-    const int jx = seed_index<BD, REP>(cell, bnd_xi, xi, lane);
-    const int jy = seed_index<BD, REP>(cell, bnd_xi, eta, lane);
+    const int jx = seed_index<BD, CREP>(cell, bnd_xi, xi, lane);
+    const int jy = seed_index<BD, CREP>(cell, bnd_xi, eta, lane);
     // local 3x3 joint rounding: dx outer, dy inner, strict '>' keeps the first maximum
     int ax[3] = {max(jx - 1, 0), jx, min(jx + 1, K - 1)};
     int ay[3] = {max(jy - 1, 0) << BD, jy << BD, min(jy + 1, K - 1) << BD};
+    // the candidates' places in the quadrant table and the signs the key's coordinates take for them
+    float xa[3], yb[3];
+    uint32_t ox[3], oy[3];
+#pragma unroll
+    for (int a = 0; a < 3; ++a) {
+        const float2 ex = nbx[jx * 3 + a], ey = nby[jy * 3 + a];
+        xa[a] = x * ex.x;
+        ox[a] = __float_as_uint(ex.y);
+        yb[a] = y * ey.x;
+        oy[a] = __float_as_uint(ey.y);
+    }
+    const char *base = reinterpret_cast<const char *>(lut) + (lane & (REP - 1)) * 16;
     // all nine scores, their maximum, then the first candidate that attains it
     float sc[9];
     uint32_t cd[9];
@@ -135,10 +182,9 @@ __device__ __forceinline__ void encode_triplet(float x, float y, float z, const 
     for (int a = 0; a < 3; ++a) {
 #pragma unroll
         for (int b = 0; b < 3; ++b) {
-            const uint32_t code = static_cast<uint32_t>(ax[a] | ay[b]);
-            const float4 n = lut[code * REP + (lane & (REP - 1))];
-            sc[3 * a + b] = fmaf(z, n.z, fmaf(y, n.y, x * n.x));
-            cd[3 * a + b] = code;
+            const float4 n = *reinterpret_cast<const float4 *>(base + ox[a] + oy[b]);
+            sc[3 * a + b] = fmaf(z, n.z, fmaf(yb[b], n.y, xa[a] * n.x));
+            cd[3 * a + b] = static_cast<uint32_t>(ax[a] | ay[b]);
         }
     }
     const float best = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])),
@@ -158,7 +204,7 @@ __device__ __forceinline__ void encode_triplet(float x, float y, float z, const 
 // 0 seed only (Alg. 1 with the window {(0,0)}), 1 local 3x3, 2 full K x K grid, 3 three independent
 // nearest-centroid rounds (the norm code from rho_i itself), 4 local 2x2 (the seed and its upper neighbour).
 // Candidates are visited dx outer, dy inner (full grid: x index outer); the first maximum wins.
-template <int BD, int BN, int REP>
+template <int BD, int BN, int REP, int CREP>
 __device__ __forceinline__ void encode_triplet_any(float x, float y, float z, const float4 *lut, const float2 *cell,
                                                    const float *bnd_xi, const float *bnd_rho, int lane, int mode,
                                                    uint32_t *dir_field, uint32_t *nrm_index) {
@@ -176,13 +222,13 @@ __device__ __forceinline__ void encode_triplet_any(float x, float y, float z, co
         xi = (px >= 0.0f) ? fx : -fx;
         eta = (py >= 0.0f) ? fy : -fy;
     }
-    const int jx = seed_index<BD, REP>(cell, bnd_xi, xi, lane);
-    const int jy = seed_index<BD, REP>(cell, bnd_xi, eta, lane);
+    const int jx = seed_index<BD, CREP>(cell, bnd_xi, xi, lane);
+    const int jy = seed_index<BD, CREP>(cell, bnd_xi, eta, lane);
     float best = -INFINITY;
     uint32_t best_code = 0u;
     auto consider = [&](int ax, int ay) {
         const uint32_t code = static_cast<uint32_t>(ax | (ay << BD));
-        const float4 n = lut[code * REP + (lane & (REP - 1))];
+        const float4 n = dir_lookup<BD, REP>(lut, code, lane);
         const float sc = fmaf(z, n.z, fmaf(y, n.y, x * n.x));
         if (sc > best) { best = sc; best_code = code; }
     };
@@ -232,7 +278,7 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
     constexpr int D = P::D;
     constexpr int LPR = D / 8;        // threads per key row in the load phase
     constexpr int RPP = 256 / LPR;    // key rows per load pass
-    constexpr int REP = EncodeSmem<P>::REP;
+    constexpr int REP = EncodeSmem<P>::REP, CREP = EncodeSmem<P>::CREP;
     // static, so that table addresses are compile-time constants that fold into the LDS instructions
     __shared__ EncodeSmem<P> sm;
 
@@ -246,11 +292,11 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
     // tables
     if (wave == 0) copy_books(books, sm.c_xi, sm.c_rho);
     __syncthreads();
-    build_encode_lut<P::BD0, REP>(sm.lut0, sm.c_xi[0], tid, 256);
-    build_seed_grid<P::BD0, REP>(sm.cell0, sm.bnd_xi[0], sm.c_xi[0], tid, 256);
+    build_encode_lut<P::BD0, REP>(sm.lut0, sm.nbx0, sm.nby0, sm.c_xi[0], tid, 256);
+    build_seed_grid<P::BD0, CREP>(sm.cell0, sm.bnd_xi[0], sm.c_xi[0], tid, 256);
     if constexpr (P::NCLASS == 2) {
-        build_encode_lut<P::BD1, REP>(sm.lut1, sm.c_xi[1], tid, 256);
-        build_seed_grid<P::BD1, REP>(sm.cell1, sm.bnd_xi[1], sm.c_xi[1], tid, 256);
+        build_encode_lut<P::BD1, REP>(sm.lut1, sm.nbx1, sm.nby1, sm.c_xi[1], tid, 256);
+        build_seed_grid<P::BD1, CREP>(sm.cell1, sm.bnd_xi[1], sm.c_xi[1], tid, 256);
     }
     if (tid < 2 * kMaxLevels) {
         const int c = tid / kMaxLevels, k = tid % kMaxLevels;
@@ -370,25 +416,25 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
                 float rho;
                 if (P::NCLASS == 1 || i < P::NT0) {
                     if constexpr (ANY)
-                        encode_triplet_any<P::BD0, P::BN0, REP>(x, y, z, sm.lut0, sm.cell0, sm.bnd_xi[0], sm.bnd_rho[0],
-                                                                lane, mode, &dir_field, &nrm_index);
+                        encode_triplet_any<P::BD0, P::BN0, REP, CREP>(x, y, z, sm.lut0, sm.cell0, sm.bnd_xi[0],
+                                                                      sm.bnd_rho[0], lane, mode, &dir_field, &nrm_index);
                     else
-                        encode_triplet<P::BD0, P::BN0, REP>(x, y, z, sm.lut0, sm.cell0, sm.bnd_xi[0], sm.bnd_rho[0],
-                                                            lane, &dir_field, &nrm_index);
+                        encode_triplet<P::BD0, P::BN0, REP, CREP>(x, y, z, sm.lut0, sm.cell0, sm.nbx0, sm.nby0,
+                                                                  sm.bnd_xi[0], sm.bnd_rho[0], lane, &dir_field, &nrm_index);
                     or_bits(sm.rec, lane, P::DIR0_BIT + i * 2 * P::BD0, 2 * P::BD0, dir_field);
                     or_bits(sm.rec, lane, P::NRM0_BIT + i * P::BN0, P::BN0, nrm_index);
-                    if constexpr (QJL) { nhat = sm.lut0[dir_field * REP + (lane & (REP - 1))]; rho = sm.c_rho[0][nrm_index]; }
+                    if constexpr (QJL) { nhat = dir_lookup<P::BD0, REP>(sm.lut0, dir_field, lane); rho = sm.c_rho[0][nrm_index]; }
                 } else {
                     if constexpr (P::NCLASS == 2) {
                         if constexpr (ANY)
-                            encode_triplet_any<P::BD1, P::BN1, REP>(x, y, z, sm.lut1, sm.cell1, sm.bnd_xi[1],
-                                                                    sm.bnd_rho[1], lane, mode, &dir_field, &nrm_index);
+                            encode_triplet_any<P::BD1, P::BN1, REP, CREP>(x, y, z, sm.lut1, sm.cell1, sm.bnd_xi[1],
+                                                                          sm.bnd_rho[1], lane, mode, &dir_field, &nrm_index);
                         else
-                            encode_triplet<P::BD1, P::BN1, REP>(x, y, z, sm.lut1, sm.cell1, sm.bnd_xi[1],
-                                                                sm.bnd_rho[1], lane, &dir_field, &nrm_index);
+                            encode_triplet<P::BD1, P::BN1, REP, CREP>(x, y, z, sm.lut1, sm.cell1, sm.nbx1, sm.nby1,
+                                                                      sm.bnd_xi[1], sm.bnd_rho[1], lane, &dir_field, &nrm_index);
                         or_bits(sm.rec, lane, P::DIR1_BIT + (i - P::NT0) * 2 * P::BD1, 2 * P::BD1, dir_field);
                         or_bits(sm.rec, lane, P::NRM1_BIT + (i - P::NT0) * P::BN1, P::BN1, nrm_index);
-                        if constexpr (QJL) { nhat = sm.lut1[dir_field * REP + (lane & (REP - 1))]; rho = sm.c_rho[1][nrm_index]; }
+                        if constexpr (QJL) { nhat = dir_lookup<P::BD1, REP>(sm.lut1, dir_field, lane); rho = sm.c_rho[1][nrm_index]; }
                     }
                 }
                 if constexpr (QJL) {

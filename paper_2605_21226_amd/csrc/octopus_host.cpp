@@ -401,9 +401,14 @@ size_t octopus_cache_bytes(const octopus_codebooks_t *cb, int32_t n_seq, int32_t
 // The encoder finds the scalar seed through a grid of 8 * 2^b_dir cells over [-1, 1] and one compare; that
 // is exact when no cell holds two boundaries of C_xi (true of every Lloyd-Max codebook this library builds;
 // a caller-edited codebook may violate it).  Same fp32 arithmetic as the kernel.
+// The encoder's direction table covers one quadrant of the code grid and relies on C_xi being antisymmetric,
+// C_xi[K - 1 - k] == -C_xi[k] bit for bit, as the Lloyd-Max codebook of a symmetric marginal is (and every
+// codebook this library builds).
 static bool seed_grid_ok(const octopus_codebooks_t &cb) {
     for (int c = 0; c < cb.plan.n_class; ++c) {
         const int K = 1 << cb.plan.b_dir[c];
+        for (int k = 0; k < K; ++k)
+            if (!(cb.c_xi[c][K - 1 - k] == -cb.c_xi[c][k])) return false;
         const int ncell = 8 * K;
         int last = -1;
         for (int k = 0; k + 1 < K; ++k) {
