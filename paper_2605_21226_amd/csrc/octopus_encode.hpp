@@ -37,16 +37,16 @@ struct SeedGrid {
 // the scores, are the same numbers.  A quarter of the entries pays for four times the copies: copy r of entry
 // e sits at index e * REP + r and lane l reads copy l % REP, so with 8 copies of 16 bytes any 8 neighbouring lanes
 // read 8 different groups of banks whatever their codes (two copies of the full table left the candidate reads
-// with about one conflict cycle per useful cycle).  At d = 256 and for 6-bit direction codes four copies fit the
-// budget (more LDS would cost a resident workgroup per compute unit).  The seed grid keeps two copies up to
-// d = 128.
+// with about one conflict cycle per useful cycle).  For 6-bit direction codes four copies fit the budget; at
+// d = 256, where the rotated tile alone takes 67 KB, four copies up to 3-bit codes and two above, so that two
+// workgroups still fit a compute unit at 3 bits per coordinate.  The seed grid keeps two copies up to d = 128.
 template <int D, int BD = 1>
-constexpr int encode_table_rep() { return (D <= 128 && BD <= 5) ? 8 : 4; }
+constexpr int encode_table_rep() { return (D <= 128 && BD <= 5) ? 8 : (D <= 128 || BD <= 3 ? 4 : 2); }
 template <int D>
 constexpr int encode_cell_rep() { return D <= 128 ? 2 : 1; }
 constexpr int quadrant_entries(int bd) { return bd <= 1 ? 1 : (1 << (2 * (bd - 1))); }
 
-template <class P>
+template <class P, bool QJL = false>
 struct EncodeSmem {
     float u[3 * P::NTRI][kURow];           // rotated coordinates [coordinate][key]
     uint32_t rec[P::NWORDS][kWave];        // packed records [word][key]
@@ -65,16 +65,27 @@ struct EncodeSmem {
     float bnd_xi[2][kMaxLevels + 1];       // boundaries, +inf padded
     float bnd_rho[2][kMaxLevels];
     float inv_norm[kWave];
-    float res_sq[4][kWave];                // QJL side-car: squared residual norm, partial per wavefront
+    float res_sq[QJL ? 4 : 1][QJL ? kWave : 1];   // QJL side-car: squared residual norm, partial per wavefront
 };
 
 template <int BD, int REP>
 __device__ __forceinline__ void build_encode_lut(float4 *lut, float2 *nbx, float2 *nby, const float *c_xi, int tid,
                                                  int nthreads) {
     constexpr int K = 1 << BD, H = BD <= 1 ? 1 : K / 2;
-    // (one table slot per thread and round: every copy computes its own entry, which is quicker than a quarter of
-    // the threads writing eight copies each)
-    for (int e = tid; e < H * H * REP; e += nthreads) lut[e] = oct_decode(c_xi[(e / REP) % H], c_xi[(e / REP) / H]);
+    // (with fewer entries than threads, nthreads / (H * H) threads share an entry: each computes it once and
+    // writes its share of the copies)
+    constexpr int Q = H * H;
+    if (Q >= nthreads) {
+        for (int e = tid; e < Q; e += nthreads) {
+            const float4 n = oct_decode(c_xi[e % H], c_xi[e / H]);
+#pragma unroll
+            for (int r = 0; r < REP; ++r) lut[e * REP + r] = n;
+        }
+    } else {
+        const int per_entry = nthreads / Q, e = tid % Q;
+        const float4 n = oct_decode(c_xi[e % H], c_xi[e / H]);
+        for (int r = tid / Q; r < REP; r += per_entry) lut[e * REP + r] = n;
+    }
     for (int e = tid; e < 3 * K; e += nthreads) {
         const int j = min(max(e / 3 + e % 3 - 1, 0), K - 1);   // the clamped neighbour (Alg. 1's window at the rim)
         const int f = min(j, K - 1 - j);
@@ -278,9 +289,9 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
     constexpr int D = P::D;
     constexpr int LPR = D / 8;        // threads per key row in the load phase
     constexpr int RPP = 256 / LPR;    // key rows per load pass
-    constexpr int REP = EncodeSmem<P>::REP, CREP = EncodeSmem<P>::CREP;
+    constexpr int REP = EncodeSmem<P, QJL>::REP, CREP = EncodeSmem<P, QJL>::CREP;
     // static, so that table addresses are compile-time constants that fold into the LDS instructions
-    __shared__ EncodeSmem<P> sm;
+    __shared__ EncodeSmem<P, QJL> sm;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int kvh = blockIdx.y, seq = blockIdx.z;
