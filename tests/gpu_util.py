@@ -60,13 +60,28 @@ def gpu_decode(cb, q, q_dtype, signs_pm1, cache, t_capacity, v, v_dtype, seq_len
     return out.cpu().numpy(), (scores.cpu().numpy() if want_scores else None)
 
 
-def check_scores(got, ref):
-    """|s - s_ref| <= 1e-3 * max(|s_ref|, rms(s_ref)) per score row"""
+def score_floor(q_vec, gamma, scale):
+    """The size a score of this query has against a key of norm gamma whatever their relative direction:
+    s_t = scale * gamma_t * (q_rot . u_t) with u_t a unit vector (Eq. (score-exact)), and q_rot . u has root mean
+    square ||q|| / sqrt(d) over directions.  The yardstick of a row too short for its own rms to be one."""
+    q_vec = np.asarray(q_vec, dtype=np.float64)
+    return scale * np.linalg.norm(q_vec) * np.asarray(gamma, dtype=np.float64) / np.sqrt(q_vec.size)
+
+
+def check_scores(got, ref, floor=None):
+    """|s - s_ref| <= 1e-3 * max(|s_ref|, rms(s_ref), floor) per score row; `floor` (score_floor) or None"""
     rms = np.sqrt(np.mean(ref ** 2))
     bound = 1e-3 * np.maximum(np.abs(ref), rms)
+    if floor is not None:
+        bound = np.maximum(bound, 1e-3 * np.asarray(floor))
     err = np.abs(got - ref)
     assert np.all(err <= bound), f"score error {np.max(err / bound):.3g} x tolerance"
     return float(np.max(err / bound))
+
+
+def record_gammas(records):
+    """gamma (fp32, the first four bytes) of records [..., record_bytes] -> float64 [...]"""
+    return np.ascontiguousarray(records[..., :4]).view(np.float32)[..., 0].astype(np.float64)
 
 
 def check_out(got, ref):

@@ -14,7 +14,8 @@ torch = pytest.importorskip("torch")
 if not torch.cuda.is_available():
     pytest.skip("no GPU", allow_module_level=True)
 
-from gpu_util import (cache_from_records, check_out, check_scores, gpu_decode, gpu_encode, new_cache)  # noqa: E402
+from gpu_util import (cache_from_records, check_out, check_scores, gpu_decode, gpu_encode, new_cache,  # noqa: E402
+                      record_gammas, score_floor)
 
 ALL_BITS = (1, 1.5, 2, 2.5, 3, 4)
 
@@ -192,7 +193,8 @@ def run_decode_case(d, bits, n_seq, n_qh, n_kv, n_q, lens, dtype, seed, t_capaci
                     assert np.all(out[s, qi, h] == 0.0)
                     continue
                 if want_scores:
-                    worst_s = max(worst_s, check_scores(scores[s, qi, h, :L], ref_scores[(s, h // g)][qi, h % g]))
+                    floor = score_floor(q[s, qi, h], record_gammas(records[s, h // g, :L]), scale)
+                    worst_s = max(worst_s, check_scores(scores[s, qi, h, :L], ref_scores[(s, h // g)][qi, h % g], floor))
                 worst_o = max(worst_o, check_out(out[s, qi, h], ref_out[s, qi, h]))
         if want_scores:
             assert np.all(np.isnan(scores[s, :, :, L:]))      # scores past len are not written

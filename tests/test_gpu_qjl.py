@@ -20,7 +20,8 @@ torch = pytest.importorskip("torch")
 if not torch.cuda.is_available():
     pytest.skip("no GPU", allow_module_level=True)
 
-from gpu_util import DEV, cache_from_records, check_out, check_scores, new_cache, sign_bits_dev, to_dev  # noqa: E402
+from gpu_util import (DEV, cache_from_records, check_out, check_scores, new_cache, record_gammas, score_floor,  # noqa: E402
+                      sign_bits_dev, to_dev)
 from test_gpu_parity import make_inputs  # noqa: E402
 
 
@@ -150,7 +151,8 @@ def run_decode_qjl_case(d, bits, n_seq, n_qh, n_kv, n_q, lens, seed, t_capacity=
             for qi in range(n_q):
                 for j in range(g):
                     if want_scores:
-                        worst_s = max(worst_s, check_scores(scores[s, qi, h * g + j, :L], ref_s[qi, j]))
+                        floor = score_floor(q[s, qi, h * g + j], record_gammas(records[s, h, :L]), scale)
+                        worst_s = max(worst_s, check_scores(scores[s, qi, h * g + j, :L], ref_s[qi, j], floor))
                     worst_o = max(worst_o, check_out(out[s, qi, h * g + j], ref_o[qi, j]))
         if want_scores:
             assert np.all(np.isnan(scores[s, :, :, L:]))
