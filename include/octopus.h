@@ -131,9 +131,10 @@ size_t octopus_cache_bytes(const octopus_codebooks_t *cb, int32_t n_seq, int32_t
  *               for all zeros.  Slots beyond t_capacity are not written (the
  *               caller must size the cache).
  * Errors: EINVAL (also n_seq or n_kv_heads above 65535), EUNSUPPORTED (plan /
- * dtype without a kernel; centroids not ascending, or two boundaries of C_xi closer than 1 / (4 * 2^b_dir), which the
- * kernel's seed search does not resolve -- never the case for the codebooks
- * octopus_build_codebooks returns), EHIP. */
+ * dtype without a kernel; centroids not ascending, two boundaries of C_xi closer than 1 / (4 * 2^b_dir), which the
+ * kernel's seed search does not resolve, or C_xi not antisymmetric (c_xi[K - 1 - k] == -c_xi[k] exactly, as the
+ * Lloyd-Max codebook of the symmetric marginal is: the kernel keeps one quadrant of the direction table) --
+ * never the case for the codebooks octopus_build_codebooks returns), EHIP. */
 int octopus_encode(const octopus_codebooks_t *cb,
                    const void *keys, int32_t key_dtype,
                    int64_t stride_seq, int64_t stride_tok, int64_t stride_head,

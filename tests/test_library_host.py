@@ -182,6 +182,26 @@ def test_encode_refuses_a_codebook_too_fine_for_the_seed_grid():
     bad2 = binding.Codebooks.from_buffer_copy(cb)
     bad2.c_xi[0][3], bad2.c_xi[0][4] = bad2.c_xi[0][4], bad2.c_xi[0][3]   # not ascending
     assert lib.octopus_encode(ctypes.byref(bad2), *args) == binding.EUNSUPPORTED
+    # the encoder keeps one quadrant of the direction table: C_xi must be antisymmetric to the bit
+    bad3 = binding.Codebooks.from_buffer_copy(cb)
+    bad3.c_xi[0][15] = float(np.nextafter(np.float32(bad3.c_xi[0][15]), np.float32(2.0)))
+    assert bad3.c_xi[0][15] != -bad3.c_xi[0][0]
+    assert lib.octopus_encode(ctypes.byref(bad3), *args) == binding.EUNSUPPORTED
+
+
+def test_every_built_codebook_is_antisymmetric():
+    """What the encoder's quadrant table relies on: c_xi[K - 1 - k] == -c_xi[k] exactly, for every bit width
+    and every pair of the App. D sweep."""
+    books = [binding.octopus_build_codebooks(d, b) for d in (64, 128, 256) for b in (1, 1.5, 2, 2.5, 3, 4)]
+    books += [binding.octopus_build_codebooks_pair(128, bd, bn) for bd in range(1, 7) for bn in range(1, 7)
+              if 2 * bd + bn in (5, 6, 7, 8, 9, 10, 11, 12, 13, 14) and bd <= 6 and bn <= 6 and (bd, bn) in
+              ((1, 3), (2, 2), (3, 1), (1, 5), (2, 4), (3, 3), (4, 2), (5, 1), (2, 6), (3, 5), (4, 4), (5, 3), (6, 2))]
+    assert len(books) == 18 + 13
+    for cb in books:
+        for c in range(cb.plan.n_class):
+            K = 1 << cb.plan.b_dir[c]
+            xi = np.array([cb.c_xi[c][k] for k in range(K)], dtype=np.float32)
+            assert np.array_equal(xi[::-1], -xi), (cb.plan.head_dim, c, K)
 
 
 def test_value_codec_sizes_and_argument_checks(lib):
