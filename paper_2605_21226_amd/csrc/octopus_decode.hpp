@@ -223,21 +223,23 @@ __device__ __forceinline__ int steps_of(int len, int max_len, int tiles_per_step
 __device__ __forceinline__ void build_plan(const DecodeShape &shp, const int32_t *seq_lens, int tiles_per_step,
                                            int32_t *plan, int lane) {
     const int G = shp.n_kv_heads * shp.n_row_groups;
-    long long total = 0;
-    for (int s0 = 0; s0 < shp.n_seq; s0 += kWave) {
+    // With at most 64 sequences every lane reads its sequence's length once (the three passes below would
+    // otherwise each wait for memory again: this kernel is on the critical path of a decode call).
+    const bool one_round = shp.n_seq <= kWave;
+    const int own_steps = one_round && lane < shp.n_seq ? steps_of(seq_lens[lane], shp.max_len, tiles_per_step) : 0;
+    auto steps_at = [&](int s0) {
+        if (one_round) return own_steps;
         const int s = s0 + lane;
-        total += s < shp.n_seq ? steps_of(seq_lens[s], shp.max_len, tiles_per_step) : 0;
-    }
+        return s < shp.n_seq ? steps_of(seq_lens[s], shp.max_len, tiles_per_step) : 0;
+    };
+    long long total = 0;
+    for (int s0 = 0; s0 < shp.n_seq; s0 += kWave) total += steps_at(s0);
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) total += __shfl_xor(total, o, kWave);
     total *= G;
     auto count_items = [&](int item) {
         long long cnt = 0;
-        for (int s0 = 0; s0 < shp.n_seq; s0 += kWave) {
-            const int s = s0 + lane;
-            const int st = s < shp.n_seq ? steps_of(seq_lens[s], shp.max_len, tiles_per_step) : 0;
-            cnt += static_cast<long long>((st + item - 1) / item) * G;
-        }
+        for (int s0 = 0; s0 < shp.n_seq; s0 += kWave) cnt += static_cast<long long>((steps_at(s0) + item - 1) / item) * G;
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, kWave);
         return cnt;
@@ -249,7 +251,7 @@ __device__ __forceinline__ void build_plan(const DecodeShape &shp, const int32_t
     int running = 0;
     for (int s0 = 0; s0 < shp.n_seq; s0 += kWave) {
         const int s = s0 + lane;
-        const int st = s < shp.n_seq ? steps_of(seq_lens[s], shp.max_len, tiles_per_step) : 0;
+        const int st = steps_at(s0);
         const int mine = ((st + item - 1) / item) * G;
         int incl = mine;
 #pragma unroll
@@ -1469,6 +1471,16 @@ __global__ __launch_bounds__(kWave) void merge_kernel(DecodeShape shp, const flo
         n_part = c_s * shp.item_waves;
         pstride = shp.rows_per_pass;
     }
+    // The first UN accumulator rows are requested before anything waits for the (m, l) pairs: their addresses do
+    // not depend on them, and with the usual handful of partials per row this is all there is to read.
+    float x_first[UN][CPT];
+#pragma unroll
+    for (int u = 0; u < UN; ++u)
+#pragma unroll
+        for (int c = 0; c < CPT; ++c)
+            x_first[u][c] = n_part > 0 ? part_acc[(prow0 + static_cast<int64_t>(min(u, n_part - 1)) * pstride) * D +
+                                                  c * kWave + lane]
+                                       : 0.0f;   // (an empty sequence has no partial)
     float m = -INFINITY;
     for (int j = lane; j < n_part; j += kWave) m = fmaxf(m, part_ml[(prow0 + static_cast<int64_t>(j) * pstride) * 2]);
     m = wave_max(m);
@@ -1498,12 +1510,19 @@ __global__ __launch_bounds__(kWave) void merge_kernel(DecodeShape shp, const flo
         const int nj = min(kWave, n_part - j0);
         for (int jj = 0; jj < nj; jj += UN) {
             float x[UN][CPT];
+            if (j0 == 0 && jj == 0) {
 #pragma unroll
-            for (int u = 0; u < UN; ++u)
+                for (int u = 0; u < UN; ++u)
 #pragma unroll
-                for (int c = 0; c < CPT; ++c)
-                    x[u][c] = part_acc[(prow0 + static_cast<int64_t>(j0 + min(jj + u, nj - 1)) * pstride) * D +
-                                       c * kWave + lane];
+                    for (int c = 0; c < CPT; ++c) x[u][c] = x_first[u][c];
+            } else {
+#pragma unroll
+                for (int u = 0; u < UN; ++u)
+#pragma unroll
+                    for (int c = 0; c < CPT; ++c)
+                        x[u][c] = part_acc[(prow0 + static_cast<int64_t>(j0 + min(jj + u, nj - 1)) * pstride) * D +
+                                           c * kWave + lane];
+            }
 #pragma unroll
             for (int u = 0; u < UN; ++u) {
                 const float fj = (jj + u < nj) ? wgt[jj + u] : 0.0f;
