@@ -472,9 +472,14 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
         for (int e = tid; e < P::GRANULES * kWave; e += 256) {
             const int g = e / kWave, key = e % kWave;
             const int64_t tok = tile * kWave + key;
-            if (tok >= tok_lo && tok < tok_hi)
-                dst[e] = make_uint4(sm.rec[4 * g][key], sm.rec[4 * g + 1][key], sm.rec[4 * g + 2][key],
-                                    sm.rec[4 * g + 3][key]);
+            if (tok >= tok_lo && tok < tok_hi) {
+                // non-temporal: the records are not read again by this kernel, and lines left behind in the caches
+                // (dirty, a whole prefill's worth) slow down whatever streams through memory next
+                typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+                const u32x4_t rec4 = {sm.rec[4 * g][key], sm.rec[4 * g + 1][key], sm.rec[4 * g + 2][key],
+                                      sm.rec[4 * g + 3][key]};
+                __builtin_nontemporal_store(rec4, reinterpret_cast<u32x4_t *>(dst + e));
+            }
         }
 
         if constexpr (QJL) {
