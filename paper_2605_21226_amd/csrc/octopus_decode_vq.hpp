@@ -58,30 +58,27 @@ struct VqGeometry {
 
 constexpr int kVqRow = kWave + 8;   // uint16 per row of scaled probabilities in LDS
 
-template <class P, int RG, int VB, int VG, int XT>
+template <class P, int RG, int VB, int VG>
 struct DecodeSmemVq {
     using Gm = VqGeometry<P, RG, VB, VG>;
     DecodeTables<P> tb;
-    // scaled probabilities of XT 64-key tiles as bf16: [tile][group][leading part, remainder][row][key slot];
+    // scaled probabilities of a 64-key tile as bf16: [group][leading part, remainder][row][key slot];
     // a row is padded by 16 bytes, so that the 16 rows the lanes of an A operand read lie in different banks
-    __attribute__((aligned(16))) uint16_t xs[Gm::NWV][XT][Gm::G][2][RG][kVqRow];
+    __attribute__((aligned(16))) uint16_t xs[Gm::NWV][Gm::G][2][RG][kVqRow];
     float zbuf[Gm::NWV][Gm::ZP];
     __attribute__((aligned(16))) unsigned char stage[Gm::NWV][Gm::STEP_BYTES];
 };
 
 // Shapes the kernel is built for: row groups of 4 or 8, at most 64 (row, group) pairs, at most 32
 // accumulator tiles, everything within the 160 KB of LDS.
-template <class P, int RG, int VB, int VG, int XT>
-constexpr bool vq_lds_fits() {
-    return sizeof(DecodeSmemVq<P, RG, VB, VG, XT>) + (mx_scores<P>() ? sizeof(QueryOperands<P, RG>) : 16) + 64 <= 160 * 1024;
-}
-// Tiles whose scaled probabilities are in LDS at once (a step is one tile).
 template <class P, int RG, int VB, int VG>
-constexpr int vq_xs_tiles() { return 1; }
+constexpr bool vq_lds_fits() {
+    return sizeof(DecodeSmemVq<P, RG, VB, VG>) + (mx_scores<P>() ? sizeof(QueryOperands<P, RG>) : 16) + 64 <= 160 * 1024;
+}
 template <class P, int RG, int VB, int VG>
 constexpr bool vq_mfma_fits() {
     using Gm = VqGeometry<P, RG, VB, VG>;
-    return (RG == 4 || RG == 8) && Gm::ZP <= 64 && Gm::CPL * Gm::NA <= 32 && vq_lds_fits<P, RG, VB, VG, 1>();
+    return (RG == 4 || RG == 8) && Gm::ZP <= 64 && Gm::CPL * Gm::NA <= 32 && vq_lds_fits<P, RG, VB, VG>();
 }
 
 template <class P, int RG, int VB, int VG>
@@ -102,9 +99,8 @@ __global__ __launch_bounds__(vq_waves<P>() * kWave)
     constexpr int CODE_POS = 7 - VB;
     constexpr uint32_t CODE_MASK = (((1u << VB) - 1u) << CODE_POS) * 0x00010001u;
     constexpr uint32_t CODE_BASE = (static_cast<uint32_t>(127 + VB) << 7) * 0x00010001u;
-    constexpr int XT = vq_xs_tiles<P, RG, VB, VG>();
     constexpr int KS = 2 * KPL;
-    __shared__ DecodeSmemVq<P, RG, VB, VG, XT> sm;
+    __shared__ DecodeSmemVq<P, RG, VB, VG> sm;
     __shared__ __attribute__((aligned(16))) uint4 qop_store[MX ? P::NTRI * QueryOperands<P, RG>::ROWS : 1];
     const QueryOperands<P, RG> &qop = *reinterpret_cast<const QueryOperands<P, RG> *>(&qop_store[0]);
 
@@ -127,7 +123,7 @@ __global__ __launch_bounds__(vq_waves<P>() * kWave)
     const int a_r = n16 & (RP - 1);
     const int a_part = RP == 4 ? (n16 >> 2) & 1 : n16 >> 3;
     const int a_member = RP == 4 ? (n16 >> 3) : 0;
-    const uint16_t *xs_lane = &sm.xs[wave][0][a_member][a_part][a_r][8 * g4];
+    const uint16_t *xs_lane = &sm.xs[wave][a_member][a_part][a_r][8 * g4];
     // the four channels 4 n16 .. + 3 of a piece: 4 VB bits at bit 4 VB n16 of the piece's 8 VB bytes
     constexpr int PIECE_BYTES = 8 * VB;
     const int code_bit = 4 * VB * n16;
@@ -135,8 +131,7 @@ __global__ __launch_bounds__(vq_waves<P>() * kWave)
     const uint32_t code_sh = static_cast<uint32_t>(code_bit & 31);
     // producer side: lane = key of a tile
     const unsigned char *meta_lane = stage_w + lane * RB + CB;
-    uint16_t *xs_key = &sm.xs[wave][0][0][0][0][ppos];
-    constexpr int XS_TILE = G * 2 * RG * kVqRow;   // uint16 per tile
+    uint16_t *xs_key = &sm.xs[wave][0][0][0][ppos];
 
     auto load_record = [&](int64_t tile, uint32_t (&w)[P::NWORDS]) {
         typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
@@ -199,7 +194,7 @@ __global__ __launch_bounds__(vq_waves<P>() * kWave)
     };
     auto produce = [&](auto kk, const float (&p)[KPL][RG], const float2 (&sz)[KPL][G]) __attribute__((always_inline)) {
         constexpr int k = decltype(kk)::value;
-        uint16_t *dst = xs_key + (k % XT) * XS_TILE;
+        uint16_t *dst = xs_key;
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const float zero_b = fmaf(-BIAS, sz[k][g].x, sz[k][g].y);
@@ -260,31 +255,30 @@ __global__ __launch_bounds__(vq_waves<P>() * kWave)
             }
         }
     };
-    // D6 of tiles [k0, k0 + XT): all A operands are requested, then the products run
-    auto pv_tiles = [&](auto kk0) __attribute__((always_inline)) {
-        constexpr int k0 = decltype(kk0)::value;
-        uint4 aop[2 * XT][PCS][NA];
+    // D6 of the step's tile: all A operands are requested, then the products run
+    auto pv_tile = [&]() __attribute__((always_inline)) {
+        uint4 aop[KS][PCS][NA];
 #pragma unroll
-        for (int hs = 0; hs < 2 * XT; ++hs)
+        for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
             for (int pc = 0; pc < PCS; ++pc)
 #pragma unroll
                 for (int a = 0; a < NA; ++a)
-                    aop[hs][pc][a] = *reinterpret_cast<const uint4 *>(xs_lane + ((k0 + hs / 2) % XT) * XS_TILE +
-                                                                      ((pc * GPB + a * GPA) * 2 * RG) * kVqRow + 32 * (hs & 1));
+                    aop[ks][pc][a] = *reinterpret_cast<const uint4 *>(xs_lane + ((pc * GPB + a * GPA) * 2 * RG) * kVqRow +
+                                                                      32 * ks);
 #pragma unroll
-        for (int hs = 0; hs < 2 * XT; ++hs)
+        for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
             for (int pc = 0; pc < PCS; ++pc)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     union { uint32_t u[4]; bf16x8_t b; } vb;
 #pragma unroll
-                    for (int jj = 0; jj < 4; ++jj) vb.u[jj] = vbw[2 * k0 + hs][pc][e][jj];
+                    for (int jj = 0; jj < 4; ++jj) vb.u[jj] = vbw[ks][pc][e][jj];
 #pragma unroll
                     for (int a = 0; a < NA; ++a) {
                         union { uint4 q; bf16x8_t b; } pa;
-                        pa.q = aop[hs][pc][a];
+                        pa.q = aop[ks][pc][a];
                         acc[4 * pc + e][a] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa.b, vb.b, acc[4 * pc + e][a], 0, 0, 0);
                     }
                 }
@@ -380,16 +374,14 @@ __global__ __launch_bounds__(vq_waves<P>() * kWave)
                     for (int hh = 0; hh < NA; ++hh) acc[c][hh][i] *= a;
             }
         }
-        // D6, XT tiles at a time: their scaled probabilities go to LDS, then their k-steps run
-        static_for<0, KPL / XT>([&](auto tt) {
-            constexpr int k0 = decltype(tt)::value * XT;
-            static_for<k0, k0 + XT>([&](auto kk) { produce(kk, s, sz); });
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            pv_tiles(std::integral_constant<int, k0>{});
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-        });
+        // D6: the tile's scaled probabilities go to LDS, then its two k-steps run
+        static_assert(KPL == 1, "one tile per step");
+        produce(std::integral_constant<int, 0>{}, s, sz);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        pv_tile();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
     };
 
     int it, taken = 0;
