@@ -347,8 +347,12 @@ class Run:
                 wl.dtype == "bf16")
 
     def dominant_kernel(self):
-        # (quantised values of a single-query batch: row groups of 4 or 8, served by the matrix-core kernel)
-        return "decode_kernel_vq_mfma" if self.v_bits else ("decode_kernel_mq" if self.uses_mq() else "decode_kernel_mfma")
+        if self.v_bits:     # quantised values: the matrix-core kernel where one is built for the shape
+            from paper_2605_21226_amd import binding
+            wl = self.wl
+            on_mfma = binding.octopus_vq_on_matrix_cores(self.cb, wl.n_q_heads, wl.n_kv_heads, wl.n_q, self.v_bits, self.v_group)
+            return "decode_kernel_vq_mfma" if on_mfma else "decode_kernel_valu"
+        return "decode_kernel_mq" if self.uses_mq() else "decode_kernel_mfma"
 
     def dense_flops(self):
         import numpy as np

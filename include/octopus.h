@@ -418,6 +418,12 @@ const char *octopus_strerror(int code);
  * cancels.  Returns OCTOPUS_OK, or OCTOPUS_EINVAL if only one of the two is NULL. */
 int octopus_profile_events(void *before, void *after);
 
+/* octopus_vq_on_matrix_cores: 1 if octopus_attn_decode_vq without score output serves this shape and value
+ * format with the kernel that multiplies P.V on the matrix cores, 0 if with the vector-unit kernel (or if the
+ * arguments are not ones the call accepts).  Host-side; says which kernel a measurement is of. */
+int octopus_vq_on_matrix_cores(const octopus_codebooks_t *cb, int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q,
+                               int32_t v_bits, int32_t v_group);
+
 /* octopus_probe_read: a plain streaming read of `bytes` bytes of device memory at `data` (16-byte aligned) by
  * n_workgroups workgroups of 256 threads, each walking its contiguous share with 16-byte loads, non-temporal or
  * not: the reference that says what read rate the machine reaches with nothing else to do.  `sink`: 4 bytes of

@@ -24,7 +24,7 @@ EXPORTS = ("octopus_build_codebooks", "octopus_build_codebooks_pair", "octopus_c
            "octopus_encode_rounding", "octopus_vq_row_bytes", "octopus_vq_bytes", "octopus_encode_values",
            "octopus_attn_decode_vq", "octopus_attn_decode_hybrid",
            "octopus_paged_pool_bytes", "octopus_encode_paged", "octopus_attn_decode_paged",
-           "octopus_attn_decode_static", "octopus_probe_read")
+           "octopus_attn_decode_static", "octopus_probe_read", "octopus_vq_on_matrix_cores")
 
 
 class Plan(ctypes.Structure):
@@ -120,6 +120,8 @@ def load():
     lib.octopus_attn_decode_paged.argtypes = [CB, vp, i32, i32, i32, i32, i32, vp, vp, vp, i32, vp, i32, vp, i64, f32,
                                               vp, vp, ctypes.c_size_t, vp]
     lib.octopus_attn_decode_paged.restype = ctypes.c_int
+    lib.octopus_vq_on_matrix_cores.argtypes = [ctypes.POINTER(Codebooks), i32, i32, i32, i32, i32]
+    lib.octopus_vq_on_matrix_cores.restype = ctypes.c_int
     lib.octopus_probe_read.argtypes = [vp, ctypes.c_size_t, i32, i32, vp, vp]
     lib.octopus_probe_read.restype = ctypes.c_int
     lib.octopus_profile_events.argtypes = [vp, vp]
@@ -310,6 +312,11 @@ def octopus_attn_decode_hybrid(cb, q, signs, cache, t_capacity, v, seq_lens, max
                                              _ptr(scores_out), _ptr(workspace),
                                              int(workspace.numel() * workspace.element_size()), _stream_ptr(stream))
     _check(code, "octopus_attn_decode_hybrid")
+
+
+def octopus_vq_on_matrix_cores(cb, n_q_heads, n_kv_heads, n_q, v_bits, v_group):
+    return bool(load().octopus_vq_on_matrix_cores(ctypes.byref(cb), int(n_q_heads), int(n_kv_heads), int(n_q),
+                                                  int(v_bits), int(v_group)))
 
 
 def octopus_probe_read(data, nontemporal, n_workgroups, sink, stream=None):

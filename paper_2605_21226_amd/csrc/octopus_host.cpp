@@ -495,6 +495,13 @@ static int decode_args_ok(const octopus_codebooks_t *cb, int32_t n_seq, int32_t 
     return OCTOPUS_OK;
 }
 
+int octopus_vq_on_matrix_cores(const octopus_codebooks_t *cb, int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q,
+                               int32_t v_bits, int32_t v_group) {
+    if (decode_args_ok(cb, 1, n_q_heads, n_kv_heads, n_q, 1) != OCTOPUS_OK) return 0;
+    if (v_bits < 2 || v_bits > 4 || (v_group != 16 && v_group != 32)) return 0;
+    return vq_mfma_available(cb->plan, vq_mfma_rows(n_q * (n_q_heads / n_kv_heads)), v_bits, v_group) ? 1 : 0;
+}
+
 // Workspace of a decode call without quantised values (what octopus_attn_decode_static has to fit).
 static size_t plain_decode_workspace(const octopus_codebooks_t *cb, int32_t n_seq, int32_t n_q_heads,
                                      int32_t n_kv_heads, int32_t n_q, int64_t max_len) {

@@ -189,6 +189,16 @@ def test_encode_refuses_a_codebook_too_fine_for_the_seed_grid():
     assert lib.octopus_encode(ctypes.byref(bad3), *args) == binding.EUNSUPPORTED
 
 
+def test_which_kernel_serves_quantised_values():
+    """Host-side query used by bench.py to name the kernel it measured."""
+    cb = binding.octopus_build_codebooks(128, 3)
+    assert binding.octopus_vq_on_matrix_cores(cb, 32, 8, 1, 3, 32)          # GQA 4, groups of 32: matrix cores
+    assert not binding.octopus_vq_on_matrix_cores(cb, 32, 8, 1, 3, 16)      # groups of 16 do not fit LDS at d = 128
+    assert not binding.octopus_vq_on_matrix_cores(cb, 32, 8, 1, 5, 32)      # not a value format
+    assert not binding.octopus_vq_on_matrix_cores(cb, 30, 8, 1, 3, 32)      # heads not divisible
+    assert binding.octopus_vq_on_matrix_cores(binding.octopus_build_codebooks(64, 2), 8, 8, 1, 2, 16)
+
+
 def test_every_built_codebook_is_antisymmetric():
     """What the encoder's quadrant table relies on: c_xi[K - 1 - k] == -c_xi[k] exactly, for every bit width
     and every pair of the App. D sweep."""
