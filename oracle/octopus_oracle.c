@@ -162,75 +162,113 @@ static int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v
 
 /* ---- encoder: Alg. 1 ----------------------------------------------------- */
 
-/* mode: 0 = Alg. 1 with Delta = {(0,0)}, 1 = local 3x3 (default),
- *       2 = full K x K grid, 3 = three independent nearest-centroid rounds
- *       (Sec. 3.5, first paragraph: the radius code is the centroid nearest
- *       to rho_i itself, not to s*; this is what the "scalar" rows of the
- *       rounding ablation print), 4 = local 2x2 (App. E names it without
- *       defining it; read as the window of offsets {0, +1} per axis: the
- *       seed cell and its upper neighbour, clamped at the end.  This window
- *       reproduces the printed local 2x2 rows; the window of the two
- *       centroids that bracket the coordinate reproduces the 3x3 rows
- *       instead).
- * Outputs per key: gamma, idx_dir[2*n_tri] (order (i,0),(i,1)), idx_nrm[n_tri];
- * optional diagnostics (may be NULL): u[d], xi_eta[2*n_tri], s_star[n_tri]. */
+/* The encoder is put together from four parts, each of which can be read against the paper on its own:
+ *   unit_rotated      gamma = ||k||, u = H (s . k / gamma), zero-padded to whole triplets (Alg. 1, first steps);
+ *   the seed          per axis, the centroid cell the octahedral coordinate falls into (searchsorted on B_xi);
+ *   a candidate set   which cells around the seed compete: a list of (dx, dy) offsets per rounding mode, in
+ *                     the order they are tried (App. E; Sec. 3.5 for the default), or the whole K x K grid;
+ *   the choice        the candidate whose direction has the largest cosine with the triplet, the first one on
+ *                     ties; the norm code is then the cell of that cosine (of the triplet's own length for the
+ *                     independent rounds) in B_rho.
+ * Rounding modes: 0 = the seed alone, 1 = the seed's 3x3 neighbourhood (default), 2 = the full grid,
+ * 3 = three independent nearest-centroid rounds (Sec. 3.5, first paragraph: the radius code is the centroid
+ * nearest to rho_i itself; the "scalar" rows of the rounding ablation), 4 = local 2x2 (App. E names it without
+ * defining it; read as the seed cell and its upper neighbour per axis, clamped at the rim: this window
+ * reproduces the printed local 2x2 rows, whereas the two centroids that bracket the coordinate reproduce the
+ * 3x3 rows instead). */
+
+typedef struct { int8_t dx, dy; } cell_offset;
+
+static const cell_offset kSeedOnly[] = {{0, 0}};
+static const cell_offset kNeighbours3x3[] = {{-1, -1}, {-1, 0}, {-1, 1}, {0, -1}, {0, 0}, {0, 1}, {1, -1}, {1, 0}, {1, 1}};
+static const cell_offset kUpper2x2[] = {{0, 0}, {0, 1}, {1, 0}, {1, 1}};
+
+typedef struct {
+    int cell_x, cell_y;   /* centroid indices of the chosen direction */
+    double cosine;        /* t . n^ of the chosen direction (-inf: nothing tried yet) */
+} direction_choice;
+
+/* gamma and the rotated unit key, zero-padded to 3 * n_tri coordinates (u must hold that many). */
+static double unit_rotated(const oracle_plan *p, const double *key, const int8_t *signs, double *u)
+{
+    const int d = p->d;
+    double *scaled = (double *)malloc(sizeof(double) * (size_t)d);
+    double sq = 0.0;
+    for (int j = 0; j < d; ++j) sq += key[j] * key[j];
+    const double gamma = sqrt(sq);
+    const double divisor = (gamma > OCT_EPS) ? gamma : OCT_EPS;
+    for (int j = 0; j < d; ++j) scaled[j] = key[j] / divisor;
+    for (int j = d; j < 3 * p->n_tri; ++j) u[j] = 0.0;
+    oracle_rotate(scaled, signs, u, d);
+    free(scaled);
+    return gamma;
+}
+
+/* t . Oct^-1(C[ix], C[iy]) */
+static double cell_cosine(const double t[3], const double *centroids, int ix, int iy)
+{
+    double n[3];
+    oracle_oct_decode(centroids[ix], centroids[iy], n);
+    return t[0] * n[0] + t[1] * n[1] + t[2] * n[2];
+}
+
+/* Offers one cell to the running choice; a later cell wins only if strictly better. */
+static void offer_cell(direction_choice *best, const double t[3], const double *centroids, int ix, int iy)
+{
+    const double c = cell_cosine(t, centroids, ix, iy);
+    if (c > best->cosine) {
+        best->cosine = c;
+        best->cell_x = ix;
+        best->cell_y = iy;
+    }
+}
+
+static direction_choice choose_direction(const double t[3], const double *centroids, int n_levels, int seed_x,
+                                         int seed_y, int mode)
+{
+    direction_choice best = {seed_x, seed_y, -INFINITY};
+    if (mode == 2) {
+        for (int ix = 0; ix < n_levels; ++ix)
+            for (int iy = 0; iy < n_levels; ++iy) offer_cell(&best, t, centroids, ix, iy);
+        return best;
+    }
+    const cell_offset *window = kSeedOnly;
+    int n_cells = 1;
+    if (mode == 1) { window = kNeighbours3x3; n_cells = 9; }
+    if (mode == 4) { window = kUpper2x2; n_cells = 4; }
+    for (int c = 0; c < n_cells; ++c)
+        offer_cell(&best, t, centroids, clampi(seed_x + window[c].dx, 0, n_levels - 1),
+                   clampi(seed_y + window[c].dy, 0, n_levels - 1));
+    return best;
+}
+
+/* Outputs per key: gamma, idx_dir[2*n_tri] (order (i,0),(i,1)), idx_nrm[n_tri];
+ * optional diagnostics (may be NULL): u[d], xi_eta[2*n_tri], s_star[n_tri] (the chosen cosine). */
 void oracle_encode_key(const oracle_plan *p, const double *k, const int8_t *s, int mode,
                        double *gamma_out, int32_t *idx_dir, int32_t *idx_nrm,
                        double *u_out, double *xi_eta_out, double *s_star_out)
 {
-    int d = p->d;
-    double *ut = (double *)calloc((size_t)3 * p->n_tri + d, sizeof(double));
-    double *u = ut;               /* 3*n_tri entries, zero padded */
-    double *tmp = ut + 3 * p->n_tri;
-
-    double g2 = 0.0;
-    for (int j = 0; j < d; ++j) g2 += k[j] * k[j];
-    double gamma = sqrt(g2);
-    double den = (gamma > OCT_EPS) ? gamma : OCT_EPS;
-    for (int j = 0; j < d; ++j) tmp[j] = k[j] / den;
-    oracle_rotate(tmp, s, u, d);
-    *gamma_out = gamma;
-    if (u_out) memcpy(u_out, u, sizeof(double) * d);
+    double *u = (double *)malloc(sizeof(double) * (size_t)(3 * p->n_tri));
+    *gamma_out = unit_rotated(p, k, s, u);
+    if (u_out) memcpy(u_out, u, sizeof(double) * p->d);
 
     for (int i = 0; i < p->n_tri; ++i) {
-        int c = class_of(p, i);
-        int K = 1 << p->b_dir[c], M = 1 << p->b_nrm[c];
-        const double *cx = p->c_xi[c], *bx = p->b_xi[c];
+        const int cls = class_of(p, i);
+        const int n_dir = 1 << p->b_dir[cls], n_nrm = 1 << p->b_nrm[cls];
         const double *t = u + 3 * i;
         double xi, eta;
         oracle_oct_encode(t, &xi, &eta);
-        int jx = count_below(bx, K - 1, xi);
-        int jy = count_below(bx, K - 1, eta);
-        double s_star = -INFINITY;
-        int Jx = jx, Jy = jy;
-        if (mode == 2) {
-            for (int ax = 0; ax < K; ++ax)
-                for (int ay = 0; ay < K; ++ay) {
-                    double n[3];
-                    oracle_oct_decode(cx[ax], cx[ay], n);
-                    double sc = t[0] * n[0] + t[1] * n[1] + t[2] * n[2];
-                    if (sc > s_star) { s_star = sc; Jx = ax; Jy = ay; }
-                }
-        } else {
-            int r = (mode == 0 || mode == 3) ? 0 : 1;
-            for (int dx = -r; dx <= r; ++dx)
-                for (int dy = -r; dy <= r; ++dy) {
-                    if (mode == 4 && (dx < 0 || dy < 0)) continue;
-                    int ax = clampi(jx + dx, 0, K - 1), ay = clampi(jy + dy, 0, K - 1);
-                    double n[3];
-                    oracle_oct_decode(cx[ax], cx[ay], n);
-                    double sc = t[0] * n[0] + t[1] * n[1] + t[2] * n[2];
-                    if (sc > s_star) { s_star = sc; Jx = ax; Jy = ay; }
-                }
-        }
-        idx_dir[2 * i] = Jx;
-        idx_dir[2 * i + 1] = Jy;
-        double radial = (mode == 3) ? sqrt(t[0] * t[0] + t[1] * t[1] + t[2] * t[2]) : s_star;
-        idx_nrm[i] = count_below(p->b_rho[c], M - 1, clip01(radial));
+        const int seed_x = count_below(p->b_xi[cls], n_dir - 1, xi);
+        const int seed_y = count_below(p->b_xi[cls], n_dir - 1, eta);
+        const direction_choice best = choose_direction(t, p->c_xi[cls], n_dir, seed_x, seed_y, mode);
+        idx_dir[2 * i] = best.cell_x;
+        idx_dir[2 * i + 1] = best.cell_y;
+        const double radial = (mode == 3) ? sqrt(t[0] * t[0] + t[1] * t[1] + t[2] * t[2]) : best.cosine;
+        idx_nrm[i] = count_below(p->b_rho[cls], n_nrm - 1, clip01(radial));
         if (xi_eta_out) { xi_eta_out[2 * i] = xi; xi_eta_out[2 * i + 1] = eta; }
-        if (s_star_out) s_star_out[i] = s_star;
+        if (s_star_out) s_star_out[i] = best.cosine;
     }
-    free(ut);
+    free(u);
 }
 
 /* ---- bit streams --------------------------------------------------------- */
