@@ -170,7 +170,7 @@ constexpr bool mx_scores() { return DecodeTables<P>::J0 && (P::NCLASS == 1 || De
 // MX: joint tables hold bf16 hi / lo operands (the matrix-core score pass) instead of fp32 vectors.
 template <class P, bool MX = false>
 __device__ __forceinline__ void build_tables(DecodeTables<P> &tb, const DeviceBooks &books, int tid, int nthreads) {
-    if (tid < kWave) copy_books(books, tb.c_xi, tb.c_rho);
+    if (tid < kWave) copy_books<P>(books, tb.c_xi, tb.c_rho);
     __syncthreads();
     if constexpr (MX) {
         static_assert(mx_scores<P>(), "matrix-core scores need joint tables");

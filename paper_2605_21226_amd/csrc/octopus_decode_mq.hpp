@@ -68,7 +68,7 @@ __global__ __launch_bounds__(kWave *NW) __attribute__((amdgpu_waves_per_eu(P::D 
     const int n = lane & 31, h = lane >> 5;
 
     // tables (one copy: the lookups are a small part of this kernel)
-    if (tid < kWave) copy_books(books, sm.c_xi, sm.c_rho);
+    if (tid < kWave) copy_books<P>(books, sm.c_xi, sm.c_rho);
     __syncthreads();
     build_dir_lut<P::BD0>(sm.dir0, sm.c_xi[0], tid, kWave * NW);
     if constexpr (P::NCLASS == 2) build_dir_lut<P::BD1>(sm.dir1, sm.c_xi[1], tid, kWave * NW);

@@ -112,14 +112,21 @@ __device__ __forceinline__ void build_dir_lut(float4 *lut, const float *c_xi, in
     for (int e = tid; e < K * K; e += nthreads) lut[e] = oct_decode(c_xi[e & (K - 1)], c_xi[e >> BD]);
 }
 
-// Kernel-argument centroids to LDS with compile-time indices (every lane stores the same values).
+// Kernel-argument centroids to LDS with compile-time indices (every lane stores the same values).  Only the
+// levels that plan P has are copied: the arrays are sized for the largest plan, and each level costs the
+// copying wavefront a move and an LDS store while the rest of the workgroup waits.
+template <class P>
 __device__ __forceinline__ void copy_books(const DeviceBooks &books, float (*c_xi)[kMaxLevels], float (*c_rho)[kMaxLevels]) {
+    constexpr int two = P::NCLASS == 2 ? 1 : 0;
+    constexpr int n_xi[2] = {1 << P::BD0, two << (P::BD1 > 0 ? P::BD1 : 0)};
+    // (at least two norm levels, so that the first boundary of a class is a number whatever its bit width)
+    constexpr int n_rho[2] = {P::BN0 > 0 ? 1 << P::BN0 : 2, two * (P::BN1 > 0 ? 1 << P::BN1 : 2)};
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
 #pragma unroll
-        for (int k = 0; k < kMaxLevels; ++k) c_xi[c][k] = books.c_xi[c][k];
+        for (int k = 0; k < n_xi[c]; ++k) c_xi[c][k] = books.c_xi[c][k];
 #pragma unroll
-        for (int k = 0; k < kMaxLevels; ++k) c_rho[c][k] = books.c_rho[c][k];
+        for (int k = 0; k < n_rho[c]; ++k) c_rho[c][k] = books.c_rho[c][k];
     }
 }
 

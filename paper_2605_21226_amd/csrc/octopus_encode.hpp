@@ -24,7 +24,9 @@ struct SeedGrid {
     static constexpr int K = 1 << BD;
     static constexpr int NCELL = 8 * K;
     __device__ static __forceinline__ int cell_of(float x) {
-        const int c = static_cast<int>(floorf((x + 1.0f) * (0.5f * NCELL)));
+        // floor((x + 1) * NCELL / 2), clamped: the scaling by a power of two is exact, so one fused multiply-add
+        // rounds as the sum does, and the conversion's truncation is the floor wherever the clamp lets it through
+        const int c = static_cast<int>(fmaf(x, 0.5f * NCELL, 0.5f * NCELL));
         return min(max(c, 0), NCELL - 1);
     }
 };
@@ -64,7 +66,7 @@ struct EncodeSmem {
     float c_rho[2][kMaxLevels];
     float bnd_xi[2][kMaxLevels + 1];       // boundaries, +inf padded
     float bnd_rho[2][kMaxLevels];
-    float inv_norm[kWave];
+    float sumsq[kWave];                    // squared norm of each key of the tile
     float res_sq[QJL ? 4 : 1][QJL ? kWave : 1];   // QJL side-car: squared residual norm, partial per wavefront
 };
 
@@ -132,6 +134,26 @@ __device__ __forceinline__ int seed_index(const float2 *cell, const float *bnd, 
     return __float_as_int(e.x) + (e.y < x ? 1 : 0);
 }
 
+// Sum over the LPR (8, 16 or 32) neighbouring lanes that hold one key row, left in all of them: an exchange-and-add
+// butterfly over lane distances 1, 2, 4, 8 (and 16).  The first four go through the vector ALU's own lane permutes
+// instead of LDS: after the distances 1 and 2 the four lanes of a quad hold the same sum, so the mirror of 8 lanes
+// pairs each quad with its neighbour exactly as distance 4 does, and the mirror of 16 each half as distance 8 does
+// (the same two operands in every addition, so the same bits).
+template <int CTRL>
+__device__ __forceinline__ float lane_permute(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+template <int LPR>
+__device__ __forceinline__ float row_sum(float v) {
+    static_assert(LPR == 8 || LPR == 16 || LPR == 32, "lanes per key row");
+    v += lane_permute<0xB1>(v);    // quad permute [1, 0, 3, 2]
+    v += lane_permute<0x4E>(v);    // quad permute [2, 3, 0, 1]
+    v += lane_permute<0x141>(v);   // mirror within each 8 lanes
+    if constexpr (LPR >= 16) v += lane_permute<0x140>(v);   // mirror within each 16 lanes
+    if constexpr (LPR >= 32) v += __shfl_xor(v, 16, kWave);
+    return v;
+}
+
 template <int R>
 __device__ __forceinline__ void butterflies(float (&x)[R]) {
 #pragma unroll
@@ -171,15 +193,16 @@ __device__ __forceinline__ void encode_triplet(float x, float y, float z, const 
     // scalar seed
     const int jx = seed_index<BD, CREP>(cell, bnd_xi, xi, lane);
     const int jy = seed_index<BD, CREP>(cell, bnd_xi, eta, lane);
-    // local 3x3 joint rounding: dx outer, dy inner, strict '>' keeps the first maximum
-    int ax[3] = {max(jx - 1, 0), jx, min(jx + 1, K - 1)};
-    int ay[3] = {max(jy - 1, 0) << BD, jy << BD, min(jy + 1, K - 1) << BD};
+    // local 3x3 joint rounding: dx outer, dy inner, the first maximum wins
     // the candidates' places in the quadrant table and the signs the key's coordinates take for them
+    // (24-bit multiplies: full rate, unlike the 32-bit one)
+    const float2 *rowx = reinterpret_cast<const float2 *>(reinterpret_cast<const char *>(nbx) + __mul24(jx, 24));
+    const float2 *rowy = reinterpret_cast<const float2 *>(reinterpret_cast<const char *>(nby) + __mul24(jy, 24));
     float xa[3], yb[3];
     uint32_t ox[3], oy[3];
 #pragma unroll
     for (int a = 0; a < 3; ++a) {
-        const float2 ex = nbx[jx * 3 + a], ey = nby[jy * 3 + a];
+        const float2 ex = rowx[a], ey = rowy[a];
         xa[a] = x * ex.x;
         ox[a] = __float_as_uint(ex.y);
         yb[a] = y * ey.x;
@@ -188,21 +211,23 @@ __device__ __forceinline__ void encode_triplet(float x, float y, float z, const 
     const char *base = reinterpret_cast<const char *>(lut) + (lane & (REP - 1)) * 16;
     // all nine scores, their maximum, then the first candidate that attains it
     float sc[9];
-    uint32_t cd[9];
 #pragma unroll
     for (int a = 0; a < 3; ++a) {
 #pragma unroll
         for (int b = 0; b < 3; ++b) {
             const float4 n = *reinterpret_cast<const float4 *>(base + ox[a] + oy[b]);
             sc[3 * a + b] = fmaf(z, n.z, fmaf(yb[b], n.y, xa[a] * n.x));
-            cd[3 * a + b] = static_cast<uint32_t>(ax[a] | ay[b]);
         }
     }
     const float best = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])),
                              fmaxf(fmaxf(sc[4], sc[5]), fmaxf(fmaxf(sc[6], sc[7]), sc[8])));
-    uint32_t best_code = cd[8];
+    // the winner as (dx + 1) + 4 (dy + 1): small constants through the selects, the code built once afterwards
+    uint32_t pick = 2u + 4u * 2u;
 #pragma unroll
-    for (int i = 7; i >= 0; --i) best_code = (sc[i] == best) ? cd[i] : best_code;
+    for (int i = 7; i >= 0; --i) pick = (sc[i] == best) ? static_cast<uint32_t>(i / 3 + 4 * (i % 3)) : pick;
+    const int cx = min(max(jx + static_cast<int>(pick & 3u) - 1, 0), K - 1);
+    const int cy = min(max(jy + static_cast<int>(pick >> 2) - 1, 0), K - 1);
+    const uint32_t best_code = static_cast<uint32_t>(cx | (cy << BD));
     const float cs = fminf(fmaxf(best, 0.0f), 1.0f);
     int r = 0;
 #pragma unroll
@@ -293,28 +318,13 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
     // static, so that table addresses are compile-time constants that fold into the LDS instructions
     __shared__ EncodeSmem<P, QJL> sm;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
     const int kvh = blockIdx.y, seq = blockIdx.z;
     const int64_t start = start_pos ? max(start_pos[seq], 0) : 0;   // (a negative position would write before the cache)
     const int64_t tok_end = min(start + n_new, t_capacity);
     const int64_t first_tile = start / kWave + static_cast<int64_t>(blockIdx.x) * kEncodeTilesPerGroup;
     if (max(first_tile * kWave, start) >= tok_end) return;
-
-    // tables
-    if (wave == 0) copy_books(books, sm.c_xi, sm.c_rho);
-    __syncthreads();
-    build_encode_lut<P::BD0, REP>(sm.lut0, sm.nbx0, sm.nby0, sm.c_xi[0], tid, 256);
-    build_seed_grid<P::BD0, CREP>(sm.cell0, sm.bnd_xi[0], sm.c_xi[0], tid, 256);
-    if constexpr (P::NCLASS == 2) {
-        build_encode_lut<P::BD1, REP>(sm.lut1, sm.nbx1, sm.nby1, sm.c_xi[1], tid, 256);
-        build_seed_grid<P::BD1, CREP>(sm.cell1, sm.bnd_xi[1], sm.c_xi[1], tid, 256);
-    }
-    if (tid < 2 * kMaxLevels) {
-        const int c = tid / kMaxLevels, k = tid % kMaxLevels;
-        const int levels = 1 << (c ? (P::BN1 > 0 ? P::BN1 : 1) : P::BN0);
-        sm.bnd_rho[c][k] = (k < levels - 1) ? 0.5f * (sm.c_rho[c][k] + sm.c_rho[c][k + 1]) : INFINITY;
-    }
-    for (int e = tid; e < (3 * P::NTRI - D) * kWave; e += 256) sm.u[D + e / kWave][e % kWave] = 0.0f;
 
     const int64_t head_base = seq * stride_seq + kvh * stride_head;
     const int col = (tid % LPR) * 8;
@@ -349,7 +359,24 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
             }
         }
     };
+    // the first tile's rows are requested before the tables are built, so that they arrive meanwhile
     fetch_tile(first_tile);
+
+    // tables
+    if (wave == 0) copy_books<P>(books, sm.c_xi, sm.c_rho);
+    __syncthreads();
+    build_encode_lut<P::BD0, REP>(sm.lut0, sm.nbx0, sm.nby0, sm.c_xi[0], tid, 256);
+    build_seed_grid<P::BD0, CREP>(sm.cell0, sm.bnd_xi[0], sm.c_xi[0], tid, 256);
+    if constexpr (P::NCLASS == 2) {
+        build_encode_lut<P::BD1, REP>(sm.lut1, sm.nbx1, sm.nby1, sm.c_xi[1], tid, 256);
+        build_seed_grid<P::BD1, CREP>(sm.cell1, sm.bnd_xi[1], sm.c_xi[1], tid, 256);
+    }
+    if (tid < 2 * kMaxLevels) {
+        const int c = tid / kMaxLevels, k = tid % kMaxLevels;
+        const int levels = 1 << (c ? (P::BN1 > 0 ? P::BN1 : 1) : P::BN0);
+        sm.bnd_rho[c][k] = (k < levels - 1) ? 0.5f * (sm.c_rho[c][k] + sm.c_rho[c][k + 1]) : INFINITY;
+    }
+    for (int e = tid; e < (3 * P::NTRI - D) * kWave; e += 256) sm.u[D + e / kWave][e % kWave] = 0.0f;
 
     for (int tg = 0; tg < kEncodeTilesPerGroup; ++tg) {
         const int64_t tile = first_tile + tg;
@@ -357,7 +384,7 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
         const int64_t tok_hi = min((tile + 1) * kWave, tok_end);
         if (tok_lo >= tok_hi) break;   // uniform over the workgroup
         __syncthreads();               // the previous tile's records have been stored; tables are complete
-        // word 0 (gamma) is written whole by the load phase below; the code words are OR-ed into
+        // word 0 (gamma) is written whole by the transform phase below; the code words are OR-ed into
         for (int e = kWave + tid; e < P::NWORDS * kWave; e += 256) sm.rec[e / kWave][e % kWave] = 0u;
 
         // E1-E2: squared norm, sign flip
@@ -378,15 +405,10 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
             float ss = 0.0f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) ss = fmaf(x[e], x[e], ss);
-#pragma unroll
-            for (int o = 1; o < LPR; o <<= 1) ss += __shfl_xor(ss, o, kWave);
+            ss = row_sum<LPR>(ss);
 #pragma unroll
             for (int e = 0; e < 8; ++e) sm.u[col + e][key] = ((sbits >> e) & 1u) ? -x[e] : x[e];
-            if (tid % LPR == 0) {
-                const float gamma = sqrtf(ss);
-                sm.rec[0][key] = __float_as_uint(gamma);
-                sm.inv_norm[key] = (1.0f / fmaxf(gamma, kEps)) * inv_sqrt_dim<D>();
-            }
+            if (tid % LPR == 0) sm.sumsq[key] = ss;
         }
         if (tg + 1 < kEncodeTilesPerGroup) fetch_tile(tile + 1);
         __syncthreads();
@@ -394,6 +416,11 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
         // E3: Walsh-Hadamard transform, one key per lane, two radix passes through LDS
         {
             constexpr int R2 = D / 16;
+            // the norm of this lane's key, once per key and wavefront (the load phase has 4 to 32 lanes per key,
+            // and a square root and a division cost as much there for one active lane as for 64)
+            const float gamma = sqrtf(sm.sumsq[lane]);
+            const float norm = (1.0f / fmaxf(gamma, kEps)) * inv_sqrt_dim<D>();
+            if (wave == 0) sm.rec[0][lane] = __float_as_uint(gamma);
             for (int g = wave; g < D / 16; g += 4) {
                 float x[16];
 #pragma unroll
@@ -403,7 +430,6 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
                 for (int e = 0; e < 16; ++e) sm.u[g * 16 + e][lane] = x[e];
             }
             __syncthreads();
-            const float norm = sm.inv_norm[lane];
             for (int lo = wave; lo < 16; lo += 4) {
                 float x[R2];
 #pragma unroll
