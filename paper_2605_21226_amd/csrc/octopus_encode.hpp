@@ -1,5 +1,5 @@
-// Online key encoder (Alg. 1 with the local 3x3 candidate set), one workgroup of 4 wavefronts per
-// 64-token cache tile of one (sequence, KV head).
+// Online key encoder (Alg. 1 with the local 3x3 candidate set): a workgroup of 4 or 8 wavefronts takes four
+// consecutive 64-token cache tiles of one (sequence, KV head), one after the other.
 #ifndef OCTOPUS_ENCODE_HPP_
 #define OCTOPUS_ENCODE_HPP_
 
@@ -48,6 +48,16 @@ template <int D>
 constexpr int encode_cell_rep() { return D <= 128 ? 2 : 1; }
 constexpr int quadrant_entries(int bd) { return bd <= 1 ? 1 : (1 << (2 * (bd - 1))); }
 
+// Wavefronts per workgroup.  LDS (the rotated tile, above all) decides how many workgroups a compute unit holds:
+// three at d = 128 up to 3 bits per coordinate, two at 4 bits and at d = 256, one at d = 256 and 4 bits; with four
+// wavefronts each a SIMD then has three, two or one to choose from, and the kernel waits on LDS and barriers.  Eight
+// wavefronts share a tile from d = 128 on (measured, same records: d = 128 b = 3 -4 %, b = 4 -15 %; d = 256 b = 3
+// -8 %, b = 4 -28 %; at d = 64 four workgroups fit anyway and eight wavefronts gain nothing).
+template <class P>
+constexpr int encode_waves() { return P::D >= 128 ? 8 : 4; }
+template <class P>
+constexpr int encode_threads() { return encode_waves<P>() * kWave; }
+
 template <class P, bool QJL = false>
 struct EncodeSmem {
     float u[3 * P::NTRI][kURow];           // rotated coordinates [coordinate][key]
@@ -67,8 +77,17 @@ struct EncodeSmem {
     float bnd_xi[2][kMaxLevels + 1];       // boundaries, +inf padded
     float bnd_rho[2][kMaxLevels];
     float sumsq[kWave];                    // squared norm of each key of the tile
-    float res_sq[QJL ? 4 : 1][QJL ? kWave : 1];   // QJL side-car: squared residual norm, partial per wavefront
+    float res_sq[QJL ? encode_waves<P>() : 1][QJL ? kWave : 1];   // QJL side-car: squared residual norm, partial per wavefront
 };
+
+// Wavefronts per SIMD that the LDS footprint allows (160 KB per compute unit, 4 SIMDs): the register budget the
+// kernel is compiled for, so that registers never cost a workgroup that LDS has room for.
+template <class P, bool QJL>
+constexpr int encode_waves_per_simd() {
+    constexpr int groups = static_cast<int>((160 * 1024) / sizeof(EncodeSmem<P, QJL>));
+    constexpr int waves = (groups < 1 ? 1 : groups) * encode_waves<P>() / 4;
+    return waves > 6 ? 6 : waves;   // (the kernel does not fit the 64 registers of 8 wavefronts per SIMD)
+}
 
 template <int BD, int REP>
 __device__ __forceinline__ void build_encode_lut(float4 *lut, float2 *nbx, float2 *nby, const float *c_xi, int tid,
@@ -304,7 +323,9 @@ constexpr int kEncodeTilesPerGroup = 4;  // consecutive cache tiles per workgrou
 // key: per tile of 64 tokens [d/32 words][64 keys] uint32, then [64 keys] fp16.
 // ANY: the rounding mode is the run-time argument `mode` (the default encoder is built without it).
 template <class P, bool BF16, bool QJL, bool ANY = false>
-__global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const void *__restrict__ keys,
+__global__ __launch_bounds__(encode_threads<P>())
+__attribute__((amdgpu_waves_per_eu(encode_waves_per_simd<P, QJL>(), encode_waves_per_simd<P, QJL>())))
+void encode_kernel(DeviceBooks books, const void *__restrict__ keys,
                                                       int64_t stride_seq, int64_t stride_tok, int64_t stride_head,
                                                       int32_t n_new, const uint8_t *__restrict__ signs,
                                                       uint4 *__restrict__ cache, int64_t t_capacity,
@@ -313,7 +334,8 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
                                                       unsigned char *__restrict__ qjl, int32_t mode, PageTable pt) {
     constexpr int D = P::D;
     constexpr int LPR = D / 8;        // threads per key row in the load phase
-    constexpr int RPP = 256 / LPR;    // key rows per load pass
+    constexpr int NWV = encode_waves<P>(), NT = encode_threads<P>();
+    constexpr int RPP = NT / LPR;     // key rows per load pass
     constexpr int REP = EncodeSmem<P, QJL>::REP, CREP = EncodeSmem<P, QJL>::CREP;
     // static, so that table addresses are compile-time constants that fold into the LDS instructions
     __shared__ EncodeSmem<P, QJL> sm;
@@ -365,18 +387,18 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
     // tables
     if (wave == 0) copy_books<P>(books, sm.c_xi, sm.c_rho);
     __syncthreads();
-    build_encode_lut<P::BD0, REP>(sm.lut0, sm.nbx0, sm.nby0, sm.c_xi[0], tid, 256);
-    build_seed_grid<P::BD0, CREP>(sm.cell0, sm.bnd_xi[0], sm.c_xi[0], tid, 256);
+    build_encode_lut<P::BD0, REP>(sm.lut0, sm.nbx0, sm.nby0, sm.c_xi[0], tid, NT);
+    build_seed_grid<P::BD0, CREP>(sm.cell0, sm.bnd_xi[0], sm.c_xi[0], tid, NT);
     if constexpr (P::NCLASS == 2) {
-        build_encode_lut<P::BD1, REP>(sm.lut1, sm.nbx1, sm.nby1, sm.c_xi[1], tid, 256);
-        build_seed_grid<P::BD1, CREP>(sm.cell1, sm.bnd_xi[1], sm.c_xi[1], tid, 256);
+        build_encode_lut<P::BD1, REP>(sm.lut1, sm.nbx1, sm.nby1, sm.c_xi[1], tid, NT);
+        build_seed_grid<P::BD1, CREP>(sm.cell1, sm.bnd_xi[1], sm.c_xi[1], tid, NT);
     }
     if (tid < 2 * kMaxLevels) {
         const int c = tid / kMaxLevels, k = tid % kMaxLevels;
         const int levels = 1 << (c ? (P::BN1 > 0 ? P::BN1 : 1) : P::BN0);
         sm.bnd_rho[c][k] = (k < levels - 1) ? 0.5f * (sm.c_rho[c][k] + sm.c_rho[c][k + 1]) : INFINITY;
     }
-    for (int e = tid; e < (3 * P::NTRI - D) * kWave; e += 256) sm.u[D + e / kWave][e % kWave] = 0.0f;
+    for (int e = tid; e < (3 * P::NTRI - D) * kWave; e += NT) sm.u[D + e / kWave][e % kWave] = 0.0f;
 
     for (int tg = 0; tg < kEncodeTilesPerGroup; ++tg) {
         const int64_t tile = first_tile + tg;
@@ -385,7 +407,7 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
         if (tok_lo >= tok_hi) break;   // uniform over the workgroup
         __syncthreads();               // the previous tile's records have been stored; tables are complete
         // word 0 (gamma) is written whole by the transform phase below; the code words are OR-ed into
-        for (int e = kWave + tid; e < P::NWORDS * kWave; e += 256) sm.rec[e / kWave][e % kWave] = 0u;
+        for (int e = kWave + tid; e < P::NWORDS * kWave; e += NT) sm.rec[e / kWave][e % kWave] = 0u;
 
         // E1-E2: squared norm, sign flip
 #pragma unroll
@@ -421,7 +443,7 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
             const float gamma = sqrtf(sm.sumsq[lane]);
             const float norm = (1.0f / fmaxf(gamma, kEps)) * inv_sqrt_dim<D>();
             if (wave == 0) sm.rec[0][lane] = __float_as_uint(gamma);
-            for (int g = wave; g < D / 16; g += 4) {
+            for (int g = wave; g < D / 16; g += NWV) {
                 float x[16];
 #pragma unroll
                 for (int e = 0; e < 16; ++e) x[e] = sm.u[g * 16 + e][lane];
@@ -430,7 +452,7 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
                 for (int e = 0; e < 16; ++e) sm.u[g * 16 + e][lane] = x[e];
             }
             __syncthreads();
-            for (int lo = wave; lo < 16; lo += 4) {
+            for (int lo = wave; lo < 16; lo += NWV) {
                 float x[R2];
 #pragma unroll
                 for (int e = 0; e < R2; ++e) x[e] = sm.u[e * 16 + lo][lane];
@@ -441,9 +463,9 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
             __syncthreads();
         }
 
-        // E4-E8: triplets, a quarter of them per wavefront, one key per lane
+        // E4-E8: triplets, an equal share of them per wavefront, one key per lane
         {
-            constexpr int CHUNK = (P::NTRI + 3) / 4;
+            constexpr int CHUNK = (P::NTRI + NWV - 1) / NWV;
             const int i_end = min(P::NTRI, (wave + 1) * CHUNK);
             float rsq = 0.0f;
             for (int i = wave * CHUNK; i < i_end; ++i) {
@@ -495,7 +517,7 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
             const int page = pt.table[static_cast<int64_t>(seq) * pt.stride + tile];
             dst = cache + (static_cast<int64_t>(min(max(page, 0), pt.n_pages - 1)) * n_kv_heads + kvh) * (P::GRANULES * kWave);
         }
-        for (int e = tid; e < P::GRANULES * kWave; e += 256) {
+        for (int e = tid; e < P::GRANULES * kWave; e += NT) {
             const int g = e / kWave, key = e % kWave;
             const int64_t tok = tile * kWave + key;
             if (tok >= tok_lo && tok < tok_hi) {
@@ -511,7 +533,7 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
         if constexpr (QJL) {
             // sigma = sign(H diag(s2) r): the same two radix passes, signs applied on the way in, no scaling
             constexpr int R2 = D / 16;
-            for (int g = wave; g < D / 16; g += 4) {
+            for (int g = wave; g < D / 16; g += NWV) {
                 const uint32_t sb = signs2[kvh * (D / 8) + 2 * g] | (static_cast<uint32_t>(signs2[kvh * (D / 8) + 2 * g + 1]) << 8);
                 float x[16];
 #pragma unroll
@@ -524,7 +546,7 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
                 for (int e = 0; e < 16; ++e) sm.u[g * 16 + e][lane] = x[e];
             }
             __syncthreads();
-            for (int lo = wave; lo < 16; lo += 4) {
+            for (int lo = wave; lo < 16; lo += NWV) {
                 float x[R2];
 #pragma unroll
                 for (int e = 0; e < R2; ++e) x[e] = sm.u[e * 16 + lo][lane];
@@ -537,14 +559,17 @@ __global__ __launch_bounds__(256) void encode_kernel(DeviceBooks books, const vo
             unsigned char *qt = qjl + ((static_cast<int64_t>(seq) * n_kv_heads + kvh) * (t_capacity / kWave) + tile) * TQ;
             const int64_t tok = tile * kWave + lane;
             const bool valid = tok >= tok_lo && tok < tok_hi;
-            for (int wd = wave; wd < D / 32; wd += 4) {
+            for (int wd = wave; wd < D / 32; wd += NWV) {
                 uint32_t bits = 0u;
 #pragma unroll
                 for (int e = 0; e < 32; ++e) bits |= (sm.u[32 * wd + e][lane] < 0.0f ? 1u : 0u) << e;
                 if (valid) reinterpret_cast<uint32_t *>(qt)[wd * kWave + lane] = bits;
             }
             if (wave == 0 && valid) {
-                const float n2 = (sm.res_sq[0][lane] + sm.res_sq[1][lane]) + (sm.res_sq[2][lane] + sm.res_sq[3][lane]);
+                float n2 = 0.0f;
+#pragma unroll
+                for (int wv = 0; wv < NWV; wv += 4)
+                    n2 += (sm.res_sq[wv][lane] + sm.res_sq[wv + 1][lane]) + (sm.res_sq[wv + 2][lane] + sm.res_sq[wv + 3][lane]);
                 reinterpret_cast<__half *>(qt + (D / 8) * kWave)[lane] = __float2half_rn(sqrtf(n2));
             }
         }
@@ -562,7 +587,7 @@ int launch_encode_plan(const octopus_codebooks_t &cb, const void *keys, int key_
     const dim3 grid((tiles + kEncodeTilesPerGroup - 1) / kEncodeTilesPerGroup, n_kv_heads, n_seq);
     const bool bf16 = key_dtype == OCTOPUS_DTYPE_BF16;
     auto go = [&](auto kernel) {
-        hipLaunchKernelGGL(kernel, grid, dim3(256), 0, stream, books, keys, stride_seq, stride_tok, stride_head, n_new,
+        hipLaunchKernelGGL(kernel, grid, dim3(encode_threads<P>()), 0, stream, books, keys, stride_seq, stride_tok, stride_head, n_new,
                            signs, static_cast<uint4 *>(cache), t_capacity, start_pos, n_kv_heads, signs2,
                            static_cast<unsigned char *>(qjl), 1, pt);
     };
@@ -584,7 +609,7 @@ int launch_encode_basic_plan(const octopus_codebooks_t &cb, const void *keys, in
     const int tiles = (n_new + kWave - 1) / kWave + (start_pos ? 1 : 0);
     const dim3 grid((tiles + kEncodeTilesPerGroup - 1) / kEncodeTilesPerGroup, n_kv_heads, n_seq);
     auto go = [&](auto kernel) {
-        hipLaunchKernelGGL(kernel, grid, dim3(256), 0, stream, books, keys, stride_seq, stride_tok, stride_head, n_new,
+        hipLaunchKernelGGL(kernel, grid, dim3(encode_threads<P>()), 0, stream, books, keys, stride_seq, stride_tok, stride_head, n_new,
                            signs, static_cast<uint4 *>(cache), t_capacity, start_pos, n_kv_heads, nullptr, nullptr, 1,
                            PageTable{nullptr, 0, 0});
     };
@@ -603,7 +628,7 @@ int launch_encode_rounding_plan(const octopus_codebooks_t &cb, const void *keys,
     const int tiles = (n_new + kWave - 1) / kWave + (start_pos ? 1 : 0);
     const dim3 grid((tiles + kEncodeTilesPerGroup - 1) / kEncodeTilesPerGroup, n_kv_heads, n_seq);
     auto go = [&](auto kernel) {
-        hipLaunchKernelGGL(kernel, grid, dim3(256), 0, stream, books, keys, stride_seq, stride_tok, stride_head, n_new,
+        hipLaunchKernelGGL(kernel, grid, dim3(encode_threads<P>()), 0, stream, books, keys, stride_seq, stride_tok, stride_head, n_new,
                            signs, static_cast<uint4 *>(cache), t_capacity, start_pos, n_kv_heads, nullptr, nullptr, mode,
                            PageTable{nullptr, 0, 0});
     };
