@@ -332,7 +332,8 @@ size_t octopus_vq_bytes(int32_t head_dim, int32_t bits, int32_t group, int32_t n
  *               (element strides), v_dtype F32/BF16, 4-byte aligned.
  *   vq          device, 16-byte aligned, octopus_vq_bytes(...) bytes; other rows untouched.
  *   start_pos   device [n_seq] int32 or NULL (all zero); rows at or past t_capacity are dropped.
- * Errors: EINVAL, EUNSUPPORTED (dtype, head_dim, bits, group), EHIP. */
+ * Errors: EINVAL (also: more than 65535 sequences, or more than 4096 (KV head, group) pairs per token),
+ * EUNSUPPORTED (dtype, head_dim, bits, group), EHIP. */
 int octopus_encode_values(const void *v, int32_t v_dtype,
                           int64_t stride_seq, int64_t stride_tok, int64_t stride_head,
                           int32_t n_seq, int32_t n_kv_heads, int32_t n_new,

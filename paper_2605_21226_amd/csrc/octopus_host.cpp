@@ -742,6 +742,8 @@ int octopus_encode_values(const void *v, int32_t v_dtype, int64_t stride_seq, in
     if (!aligned(v, 4) || !aligned(vq, 16)) return OCTOPUS_EINVAL;
     if (start_pos == nullptr && n_new > t_capacity) return OCTOPUS_EINVAL;
     if (static_cast<int64_t>(n_seq) * n_new * n_kv_heads * (head_dim / group) > (int64_t{1} << 38)) return OCTOPUS_EINVAL;
+    // the launch: one sequence per grid z, a 32-bit index over the (token, KV head, group) triples of a slab of tokens
+    if (n_seq > 65535 || static_cast<int64_t>(n_kv_heads) * (head_dim / group) > 4096) return OCTOPUS_EINVAL;
     if (n_new == 0) return OCTOPUS_OK;
     const int err = launch_encode_values(v, v_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new,
                                          head_dim, bits, group, vq, t_capacity, start_pos, stream);

@@ -60,6 +60,68 @@ def test_encode_values_fp32_append_and_degenerate_groups():
         assert np.all(rows[s, 0, :st] == 0xEE) and np.all(rows[s, 0, st + 70:] == 0xEE)
 
 
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("group", [16, 32])
+def test_encode_values_quotients_at_half_integers_and_extreme_scales(bits, group):
+    """(v - min) / scale exactly on, and one fp32 step beside, every half-integer, for scales whose reciprocal is
+    not a power of two; then the same at scales near the ends of the fp32 range: the codes are the rounding (ties
+    to even) of the correctly rounded quotient, whatever shortcut the kernel takes to it."""
+    d, levels = 128, (1 << bits) - 1
+    rng = np.random.default_rng(100 * bits + group)
+    rows_in = []
+    for scale in (3.0, 0.7, 1.0 / 3.0, 5.0e-3, 11.0, 1.0e-36, 2.0e-38, 3.0e36, 1.0e-41):
+        sc = np.float32(scale)
+        for _ in range(6):
+            row = np.empty(d, dtype=np.float32)
+            for g0 in range(0, d, group):
+                k = rng.integers(0, levels, size=group).astype(np.float32) + np.float32(0.5)
+                vals = (k * sc).astype(np.float32)
+                step = rng.integers(-1, 2, size=group)                      # exactly on the tie, or one step off
+                vals = np.where(step < 0, np.nextafter(vals, np.float32(0)), np.where(step > 0, np.nextafter(vals, np.float32(np.inf)), vals))
+                vals[0], vals[1] = 0.0, np.float32(levels) * sc             # pins min and max of the group
+                row[g0:g0 + group] = vals.astype(np.float32)
+            rows_in.append(row)
+    vals = np.stack(rows_in)[None, None]                                     # [1, 1, n_tok, d]
+    n_tok = vals.shape[2]
+    rows, _ = gpu_encode_values(vals, "fp32", bits, group, 64 * ((n_tok + 63) // 64))
+    ref = oracle.vq_encode(vals[0, 0], bits, group)
+    assert np.array_equal(rows[0, 0, :n_tok], ref)
+    # the construction does hit ties: some group has quotients that are exact half-integers
+    q = vals[0, 0, :6, :group] / ((vals[0, 0, :6, :group].max(axis=1, keepdims=True)) / np.float32(levels))
+    assert np.any(np.abs(q - np.floor(q) - 0.5) == 0)
+
+
+def test_encode_values_first_extreme_decides_the_sign_of_a_zero():
+    """The stored minimum is the FIRST element that attains it (the scan of the codec's definition): with both
+    zeros in a group, which one comes first shows in the sign bit of the stored zero point."""
+    d, bits, group = 64, 3, 16
+    rng = np.random.default_rng(9)
+    rows_in = []
+    for first, second in ((-0.0, 0.0), (0.0, -0.0)):
+        for sign in (1.0, -1.0):                                  # zero is the minimum / the maximum of the group
+            for _ in range(4):
+                row = (np.abs(rng.standard_normal(d)) * sign).astype(np.float32)
+                for g0 in range(0, d, group):
+                    i, j = sorted(rng.choice(group, size=2, replace=False))
+                    row[g0 + i], row[g0 + j] = first, second
+                rows_in.append(row)
+    rows_in.append(np.full(d, -0.0, dtype=np.float32))
+    rows_in.append(np.zeros(d, dtype=np.float32))
+    mixed = np.zeros(d, dtype=np.float32); mixed[::3] = -0.0
+    rows_in.append(mixed)
+    vals = np.stack(rows_in)[None, None]
+    n_tok = vals.shape[2]
+    for dtype in ("fp32", "bf16"):
+        if dtype == "bf16":                                       # the same rows at the precision the kernel is handed
+            vals = torch.from_numpy(vals).to(torch.bfloat16).to(torch.float32).numpy()
+        rows, _ = gpu_encode_values(vals, dtype, bits, group, 64)
+        assert np.array_equal(rows[0, 0, :n_tok], oracle.vq_encode(vals[0, 0], bits, group)), dtype
+    # the fixture does what it says: stored minima of both signs occur
+    ref = oracle.vq_encode(vals[0, 0], bits, group)
+    zero_points = ref[:, bits * d // 8:].copy().view(np.float32)[:, 1::2]
+    assert np.any(np.signbit(zero_points) & (zero_points == 0)) and np.any(~np.signbit(zero_points) & (zero_points == 0))
+
+
 def run_decode_vq_case(d, bits, v_bits, group, n_seq, n_qh, n_kv, n_q, lens, seed, want_scores=True):
     cb = binding.octopus_build_codebooks(d, bits)
     plan = oracle.make_plan(d, bits)
