@@ -232,6 +232,10 @@ def test_value_codec_sizes_and_argument_checks(lib):
     assert enc(fake, 1, 1024, 1024, 128, 1, 8, 128, 128, 3, 32, fake, 64, null, null) == binding.EINVAL    # overflow
     assert enc(fake, 1, 1024, 1024, 128, 1, 8, 64, 128, 3, 32, ctypes.c_void_p(0x1008), 64, null, null) == binding.EINVAL
     assert enc(fake, 1, 1024, 1024, 128, 1, 8, 0, 128, 3, 32, fake, 64, null, null) == binding.OK          # nothing to do
+    # the launch's own limits: one sequence per grid z, at most 4096 (KV head, group) pairs per token
+    assert enc(fake, 1, 1024, 1024, 128, 65536, 8, 0, 128, 3, 32, fake, 64, null, null) == binding.EINVAL
+    assert enc(fake, 1, 1024, 1024, 128, 1, 513, 0, 128, 3, 16, fake, 64, null, null) == binding.EINVAL
+    assert enc(fake, 1, 1024, 1024, 128, 65535, 512, 0, 128, 3, 16, fake, 64, null, null) == binding.OK
     cb = binding.octopus_build_codebooks(128, 3)
     ws = binding.octopus_attn_decode_workspace(cb, 2, 32, 8, 1, 4096)
     dec = lib.octopus_attn_decode_vq
