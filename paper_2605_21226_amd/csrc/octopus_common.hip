@@ -22,7 +22,7 @@ bool plan_supported_d256(const octopus_plan_t &);
                                const void *, const float *, const void *, const int32_t *, float *, float *,       \
                                float *, int32_t *, void *);                                                        \
     int qjl_rows_cap_d##D(const octopus_plan_t &);                                                                 \
-    bool vq_mfma_available_d##D(const octopus_plan_t &, int, int, int);                                            \
+    int vq_mfma_available_d##D(const octopus_plan_t &, int, int, int);                                             \
     int launch_decode_vq_d##D(const octopus_codebooks_t &, const DecodeShape &, const float *, const void *,       \
                               const void *, int, int, const int32_t *, float *, float *, float *, int32_t *,       \
                               void *);                                                                             \
@@ -131,13 +131,13 @@ int launch_decode_vq(const octopus_codebooks_t &cb, const DecodeShape &s, const 
     }
 }
 
-bool vq_mfma_available(const octopus_plan_t &plan, int32_t rows_per_pass, int32_t v_bits, int32_t v_group) {
-    if (plan_sweep_only(plan)) return false;
+int vq_mfma_available(const octopus_plan_t &plan, int32_t rows_per_pass, int32_t v_bits, int32_t v_group) {
+    if (plan_sweep_only(plan)) return 0;
     switch (plan.head_dim) {
         case 64: return vq_mfma_available_d64(plan, rows_per_pass, v_bits, v_group);
         case 128: return vq_mfma_available_d128(plan, rows_per_pass, v_bits, v_group);
         case 256: return vq_mfma_available_d256(plan, rows_per_pass, v_bits, v_group);
-        default: return false;
+        default: return 0;
     }
 }
 

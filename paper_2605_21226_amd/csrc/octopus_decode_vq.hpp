@@ -32,16 +32,13 @@ namespace octopus {
 //     leading parts in rows r, remainders in rows RP + r of the group's share; a column reads the rows of ITS
 //     group from the result and ignores the others, so an N-block costs NA = (64 / v_group) / GPA MFMAs per
 //     k-step: one for groups of 32 channels and four query rows, the same as over bf16 values.
-// Wavefronts per workgroup: two per SIMD up to d = 128 (each within 256 registers), whose different phases --
-// vector work, matrix-core work, LDS traffic -- the hardware overlaps; one per SIMD at d = 256.
-template <class P>
-constexpr int vq_waves() { return P::D <= 128 ? 8 : 4; }
+constexpr int kVqRow = kWave + 8;   // uint16 per row of scaled probabilities in LDS
 
-template <class P, int RG, int VB, int VG>
-struct VqGeometry {
+template <class P, int RG, int VB, int VG, int NW>
+struct VqGeometryN {
     static constexpr int D = P::D;
     static constexpr int KPL = 1;                           // tiles per step: one key per lane
-    static constexpr int NWV = vq_waves<P>();
+    static constexpr int NWV = NW;                          // wavefronts per workgroup
     static constexpr int CB = VB * D / 8;                   // code bytes per row
     static constexpr int G = D / VG;                        // groups per row
     static constexpr int RB = CB + 8 * G;                   // bytes per row
@@ -56,11 +53,9 @@ struct VqGeometry {
     static constexpr int ZP = RG * G;                       // (row, group) pairs of the zero-point sums
 };
 
-constexpr int kVqRow = kWave + 8;   // uint16 per row of scaled probabilities in LDS
-
-template <class P, int RG, int VB, int VG>
-struct DecodeSmemVq {
-    using Gm = VqGeometry<P, RG, VB, VG>;
+template <class P, int RG, int VB, int VG, int NW>
+struct DecodeSmemVqN {
+    using Gm = VqGeometryN<P, RG, VB, VG, NW>;
     DecodeTables<P> tb;
     // scaled probabilities of a 64-key tile as bf16: [group][leading part, remainder][row][key slot];
     // a row is padded by 16 bytes, so that the 16 rows the lanes of an A operand read lie in different banks
@@ -69,21 +64,39 @@ struct DecodeSmemVq {
     __attribute__((aligned(16))) unsigned char stage[Gm::NWV][Gm::STEP_BYTES];
 };
 
+template <class P, int RG, int VB, int VG, int NW>
+constexpr bool vq_lds_fits_n() {
+    return sizeof(DecodeSmemVqN<P, RG, VB, VG, NW>) + (mx_scores<P>() ? sizeof(QueryOperands<P, RG>) : 16) + 64 <= 160 * 1024;
+}
+
+// Wavefronts per workgroup: two per SIMD up to d = 128 (each within 256 registers), whose different phases --
+// vector work, matrix-core work, LDS traffic -- the hardware overlaps, where the LDS of eight wavefronts fits (each
+// has its own staging buffer and probability rows); else, and at d = 256, one per SIMD.
+template <class P, int RG, int VB, int VG>
+constexpr int vq_waves() { return (P::D <= 128 && vq_lds_fits_n<P, RG, VB, VG, 8>()) ? 8 : 4; }
+
+template <class P, int RG, int VB, int VG>
+using VqGeometry = VqGeometryN<P, RG, VB, VG, vq_waves<P, RG, VB, VG>()>;
+template <class P, int RG, int VB, int VG>
+using DecodeSmemVq = DecodeSmemVqN<P, RG, VB, VG, vq_waves<P, RG, VB, VG>()>;
+
 // Shapes the kernel is built for: row groups of 4 or 8, at most 64 (row, group) pairs, at most 32
 // accumulator tiles, everything within the 160 KB of LDS.
 template <class P, int RG, int VB, int VG>
-constexpr bool vq_lds_fits() {
-    return sizeof(DecodeSmemVq<P, RG, VB, VG>) + (mx_scores<P>() ? sizeof(QueryOperands<P, RG>) : 16) + 64 <= 160 * 1024;
-}
+constexpr bool vq_lds_fits() { return vq_lds_fits_n<P, RG, VB, VG, vq_waves<P, RG, VB, VG>()>(); }
 template <class P, int RG, int VB, int VG>
 constexpr bool vq_mfma_fits() {
     using Gm = VqGeometry<P, RG, VB, VG>;
     return (RG == 4 || RG == 8) && Gm::ZP <= 64 && Gm::CPL * Gm::NA <= 32 && vq_lds_fits<P, RG, VB, VG>();
 }
 
+// wavefronts per workgroup of the kernel for a shape, 0 if none is built
 template <class P, int RG, int VB, int VG>
-__global__ __launch_bounds__(vq_waves<P>() * kWave)
-    __attribute__((amdgpu_waves_per_eu(vq_waves<P>() / 4, vq_waves<P>() / 4))) void decode_kernel_vq_mfma(
+constexpr int vq_mfma_wavefronts() { return vq_mfma_fits<P, RG, VB, VG>() ? vq_waves<P, RG, VB, VG>() : 0; }
+
+template <class P, int RG, int VB, int VG>
+__global__ __launch_bounds__((vq_waves<P, RG, VB, VG>() * kWave))
+    __attribute__((amdgpu_waves_per_eu(vq_waves<P, RG, VB, VG>() / 4, vq_waves<P, RG, VB, VG>() / 4))) void decode_kernel_vq_mfma(
     DeviceBooks books, DecodeShape shp, const float *__restrict__ q_rot, const uint4 *__restrict__ cache,
     const unsigned char *__restrict__ vq, const int32_t *__restrict__ seq_lens, float *__restrict__ part_ml,
     float *__restrict__ part_acc, int32_t *__restrict__ plan) {

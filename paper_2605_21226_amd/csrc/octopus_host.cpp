@@ -222,7 +222,7 @@ bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 
 DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads,
                               int32_t n_q, int64_t max_len, int64_t t_capacity, bool many_rows, int32_t rows_cap,
-                              bool vq_mfma) {
+                              int32_t vq_mfma_waves) {
     DecodeShape s{};
     s.n_seq = n_seq;
     s.n_q_heads = n_q_heads;
@@ -265,12 +265,12 @@ DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t
     // results are not stored.
     s.rows_per_pass = 1;
     while (s.rows_per_pass < s.rows_per_kv && s.rows_per_pass < rows_cap) s.rows_per_pass *= 2;
-    if (vq_mfma) {
+    if (vq_mfma_waves > 0) {
         // The matrix-core kernel over quantised values: row groups of 4 or 8; up to d = 128 two wavefronts per
-        // SIMD (8 per workgroup), each taking one tile per step.
+        // SIMD (8 per workgroup) where their LDS fits, each taking one tile per step.
         s.rows_per_pass = vq_mfma_rows(s.rows_per_kv);
         s.tiles_per_step = 1;
-        s.item_waves = plan.head_dim <= 128 ? 8 : 4;
+        s.item_waves = vq_mfma_waves;
     }
     s.n_row_groups = (s.rows_per_kv + s.rows_per_pass - 1) / s.rows_per_pass;
     // Split-K sizing: one wavefront per split.  The decode kernel runs one wavefront per SIMD, 256
@@ -499,7 +499,7 @@ int octopus_vq_on_matrix_cores(const octopus_codebooks_t *cb, int32_t n_q_heads,
                                int32_t v_bits, int32_t v_group) {
     if (decode_args_ok(cb, 1, n_q_heads, n_kv_heads, n_q, 1) != OCTOPUS_OK) return 0;
     if (v_bits < 2 || v_bits > 4 || (v_group != 16 && v_group != 32)) return 0;
-    return vq_mfma_available(cb->plan, vq_mfma_rows(n_q * (n_q_heads / n_kv_heads)), v_bits, v_group) ? 1 : 0;
+    return vq_mfma_available(cb->plan, vq_mfma_rows(n_q * (n_q_heads / n_kv_heads)), v_bits, v_group) > 0 ? 1 : 0;
 }
 
 // Workspace of a decode call without quantised values (what octopus_attn_decode_static has to fit).
@@ -525,7 +525,8 @@ size_t octopus_attn_decode_workspace(const octopus_codebooks_t *cb, int32_t n_se
     if (decode_args_ok(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len) != OCTOPUS_OK) return 0;
     size_t total = plain_decode_workspace(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len);
     // ... and of the matrix-core kernel over quantised values (row groups of 4 or 8, up to 8 wavefronts an item)
-    const DecodeShape vqs = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, 0, false, 8, true);
+    const DecodeShape vqs = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, 0, false, 8,
+                                              cb->plan.head_dim <= 128 ? 8 : 4);
     total = std::max(total, make_workspace(cb->plan, vqs).total);
     return total;
 }
@@ -582,8 +583,9 @@ static int attn_decode(const octopus_codebooks_t *cb, const void *q, int32_t q_d
     const int rows_cap = with_qjl ? qjl_rows_cap(cb->plan) : 8;
     if (rows_cap <= 0) return OCTOPUS_EUNSUPPORTED;
     // quantised values without score output: the matrix-core kernel where one is built for the shape
-    const bool vq_mfma = with_vq && scores_out == nullptr &&
-                         vq_mfma_available(cb->plan, vq_mfma_rows(n_q * (n_q_heads / n_kv_heads)), v_bits, v_group);
+    const int32_t vq_mfma = with_vq && scores_out == nullptr
+                                ? vq_mfma_available(cb->plan, vq_mfma_rows(n_q * (n_q_heads / n_kv_heads)), v_bits, v_group)
+                                : 0;
     const DecodeShape s = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, t_capacity, many_rows,
                                             rows_cap, vq_mfma);
     const Workspace w = make_workspace(cb->plan, s);

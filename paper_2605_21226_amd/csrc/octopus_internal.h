@@ -39,7 +39,7 @@ struct DecodeShape {
     int32_t n_splits;       // wavefronts (workgroups of the many-row kernel) sharing the tiles of one (sequence, KV head, row group)
     int32_t max_items;      // bound of the work items the device cuts (row groups of at most 8)
     int32_t max_len;        // host-side bound of the sequence lengths
-    int32_t item_waves;     // wavefronts of the workgroup that share a work item (4; 8: matrix-core kernel over quantised values, d <= 128)
+    int32_t item_waves;     // wavefronts of the workgroup that share a work item (4; 8: matrix-core kernel over quantised values up to d = 128 where its LDS fits)
     int32_t tiles_per_step; // 64-token tiles a wavefront takes per step (2 up to d = 128, else 1; 1: that kernel)
     int64_t t_capacity;
 };
@@ -59,11 +59,12 @@ struct Workspace {
 
 DecodeShape make_decode_shape(const octopus_plan_t &plan, int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads,
                               int32_t n_q, int64_t max_len, int64_t t_capacity, bool many_rows, int32_t rows_cap = 8,
-                              bool vq_mfma = false);
+                              int32_t vq_mfma_waves = 0);
 // Row group the matrix-core kernel over quantised values would serve a call with (4 or 8 query rows), and
 // whether such a kernel is built for the plan and value format (octopus_common.hip).
 inline int32_t vq_mfma_rows(int32_t rows_per_kv) { return rows_per_kv <= 4 ? 4 : 8; }
-bool vq_mfma_available(const octopus_plan_t &plan, int32_t rows_per_pass, int32_t v_bits, int32_t v_group);
+// wavefronts per workgroup (4 or 8) of the matrix-core kernel over quantised values built for the shape, 0: none
+int vq_mfma_available(const octopus_plan_t &plan, int32_t rows_per_pass, int32_t v_bits, int32_t v_group);
 Workspace make_workspace(const octopus_plan_t &plan, const DecodeShape &s);
 
 // Kernel launchers (defined in the .hip files).  Each returns a hipError_t cast to int.

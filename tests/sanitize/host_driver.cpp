@@ -36,7 +36,7 @@ int record_event(void *, void *) { return 0; }
 int launch_probe_read(const void *, int64_t, int, int, void *, void *) { ++g_launches; return 0; }
 bool plan_supported(const octopus_plan_t &p) { return p.b_dir[0] <= 5 && p.b_nrm[0] <= 3; }
 bool plan_sweep_only(const octopus_plan_t &p) { return p.head_dim == 128 && !plan_supported(p); }
-bool vq_mfma_available(const octopus_plan_t &p, int32_t, int32_t v_bits, int32_t v_group) { return plan_supported(p) && v_bits == 3 && v_group == 32; }
+int vq_mfma_available(const octopus_plan_t &p, int32_t, int32_t v_bits, int32_t v_group) { return plan_supported(p) && v_bits == 3 && v_group == 32 ? (p.head_dim <= 128 ? 8 : 4) : 0; }
 }  // namespace octopus
 
 static int failures = 0;

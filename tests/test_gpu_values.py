@@ -196,7 +196,10 @@ def test_decode_vq_other_shapes(d, bits, v_bits, group, want_scores):
 @pytest.mark.parametrize("d,bits,v_bits,group,n_qh,n_kv,n_q", [
     (128, 3, 3, 32, 2, 2, 1), (128, 2, 2, 32, 4, 2, 1), (128, 4, 4, 16, 3, 1, 1), (128, 2.5, 3, 16, 8, 1, 1),
     (128, 1, 4, 32, 4, 1, 3), (64, 3, 3, 32, 4, 1, 1), (64, 1.5, 2, 16, 8, 1, 2), (64, 4, 4, 32, 2, 2, 1),
-    (256, 3, 3, 32, 4, 1, 1), (256, 2, 4, 32, 8, 2, 1), (256, 4, 2, 16, 4, 1, 1), (256, 1.5, 2, 32, 8, 1, 1)])
+    (256, 3, 3, 32, 4, 1, 1), (256, 2, 4, 32, 8, 2, 1), (256, 4, 2, 16, 4, 1, 1), (256, 1.5, 2, 32, 8, 1, 1),
+    # shapes whose LDS fits four wavefronts per workgroup but not eight at d = 128
+    (128, 3, 3, 16, 4, 1, 1), (128, 3, 3, 32, 8, 1, 1), (128, 4, 4, 16, 2, 2, 1), (128, 4, 2, 32, 8, 2, 1),
+    (128, 2.5, 3, 32, 16, 2, 1), (128, 3, 4, 16, 1, 1, 3)])
 def test_decode_vq_matrix_core_row_groups(d, bits, v_bits, group, n_qh, n_kv, n_q):
     run_decode_vq_case(d, bits, v_bits, group, 2, n_qh, n_kv, n_q, [300, 129], seed=int(1400 + d + 10 * bits + v_bits),
                        want_scores=False)

@@ -193,7 +193,9 @@ def test_which_kernel_serves_quantised_values():
     """Host-side query used by bench.py to name the kernel it measured."""
     cb = binding.octopus_build_codebooks(128, 3)
     assert binding.octopus_vq_on_matrix_cores(cb, 32, 8, 1, 3, 32)          # GQA 4, groups of 32: matrix cores
-    assert not binding.octopus_vq_on_matrix_cores(cb, 32, 8, 1, 3, 16)      # groups of 16 do not fit LDS at d = 128
+    assert binding.octopus_vq_on_matrix_cores(cb, 32, 8, 1, 3, 16)          # groups of 16: the four-wavefront build fits
+    assert binding.octopus_vq_on_matrix_cores(cb, 64, 8, 1, 3, 32)          # GQA 8 likewise
+    assert not binding.octopus_vq_on_matrix_cores(cb, 64, 8, 1, 3, 16)      # eight rows x groups of 16: no build fits LDS
     assert not binding.octopus_vq_on_matrix_cores(cb, 32, 8, 1, 5, 32)      # not a value format
     assert not binding.octopus_vq_on_matrix_cores(cb, 30, 8, 1, 3, 32)      # heads not divisible
     assert binding.octopus_vq_on_matrix_cores(binding.octopus_build_codebooks(64, 2), 8, 8, 1, 2, 16)
