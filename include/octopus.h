@@ -11,7 +11,8 @@
  *   octopus_encode_qjl, octopus_attn_decode_qjl    the 1-bit QJL residual (Sec. 3.6)
  *   octopus_encode_values, octopus_attn_decode_vq  group-quantised values (Sec. 4, Alg. 2)
  *   octopus_attn_decode_hybrid                     native-precision window (Sec. 4)
- *   octopus_encode_paged, octopus_attn_decode_paged  the same codec and attention over a paged cache
+ *   octopus_encode_paged, octopus_attn_decode_paged, octopus_attn_decode_paged_hybrid
+ *                                                  the same codec and attention over a paged cache
  *
  * Conventions
  *   - Plain C.  Every function returns 0 (OCTOPUS_OK) or a negative error
@@ -407,12 +408,34 @@ int octopus_attn_decode_paged(const octopus_codebooks_t *cb,
                               void *workspace, size_t workspace_bytes,
                               void *stream);
 
+/* octopus_attn_decode_paged plus the native-precision window of octopus_attn_decode_hybrid (Sec. 4,
+ * default recipe): sequence s holds seq_lens[s] compressed tokens in its key pages, followed by
+ * win_lens[s] window tokens whose keys are k_window[s][h][0 .. win_lens[s]-1]; the value rows of ALL
+ * its tokens lie in its value pages, the window's at positions seq_lens[s] + j (row (seq_lens[s] + j) % 64
+ * of page block_table[s][(seq_lens[s] + j) / 64]).  Window tokens at or past max_pages_per_seq * 64 are
+ * ignored.  k_window, k_dtype, w_capacity, win_lens as for octopus_attn_decode_hybrid; everything else,
+ * the limits and the errors as for octopus_attn_decode_paged; EINVAL if k_window or win_lens is NULL
+ * or w_capacity < 1. */
+int octopus_attn_decode_paged_hybrid(const octopus_codebooks_t *cb,
+                                     const void *q, int32_t q_dtype,
+                                     int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q,
+                                     const uint8_t *signs,
+                                     const void *k_pool, const void *v_pool, int32_t n_pages,
+                                     const int32_t *block_table, int32_t max_pages_per_seq,
+                                     const int32_t *seq_lens, int64_t max_len,
+                                     const void *k_window, int32_t k_dtype, int64_t w_capacity,
+                                     const int32_t *win_lens,
+                                     float scale,
+                                     float *out,
+                                     void *workspace, size_t workspace_bytes,
+                                     void *stream);
+
 /* Static, human-readable name of an error code. */
 const char *octopus_strerror(int code);
 
 /* ---- measurement aids (not part of the method; nothing above depends on them) ----
  * octopus_profile_events: the next decode-attention call made by this thread (octopus_attn_decode, its _static,
- * _qjl, _vq and _hybrid forms, octopus_attn_decode_paged) records the HIP events `before` and `after` (hipEvent_t
+ * _qjl, _vq and _hybrid forms, octopus_attn_decode_paged and its _hybrid form) records the HIP events `before` and `after` (hipEvent_t
  * passed as void*, caller-owned, created with timing enabled) on the call's stream immediately before and after
  * the launch of its fused decode kernel, i.e. around Alg. 2 proper without the query rotation and the split
  * merge.  The handles are per thread and are forgotten by that call whether it succeeds or not; NULL, NULL

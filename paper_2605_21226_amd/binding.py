@@ -24,6 +24,7 @@ EXPORTS = ("octopus_build_codebooks", "octopus_build_codebooks_pair", "octopus_c
            "octopus_encode_rounding", "octopus_vq_row_bytes", "octopus_vq_bytes", "octopus_encode_values",
            "octopus_attn_decode_vq", "octopus_attn_decode_hybrid",
            "octopus_paged_pool_bytes", "octopus_encode_paged", "octopus_attn_decode_paged",
+           "octopus_attn_decode_paged_hybrid",
            "octopus_attn_decode_static", "octopus_probe_read", "octopus_vq_on_matrix_cores")
 
 
@@ -120,6 +121,9 @@ def load():
     lib.octopus_attn_decode_paged.argtypes = [CB, vp, i32, i32, i32, i32, i32, vp, vp, vp, i32, vp, i32, vp, i64, f32,
                                               vp, vp, ctypes.c_size_t, vp]
     lib.octopus_attn_decode_paged.restype = ctypes.c_int
+    lib.octopus_attn_decode_paged_hybrid.argtypes = [CB, vp, i32, i32, i32, i32, i32, vp, vp, vp, i32, vp, i32, vp, i64,
+                                                     vp, i32, i64, vp, f32, vp, vp, ctypes.c_size_t, vp]
+    lib.octopus_attn_decode_paged_hybrid.restype = ctypes.c_int
     lib.octopus_vq_on_matrix_cores.argtypes = [ctypes.POINTER(Codebooks), i32, i32, i32, i32, i32]
     lib.octopus_vq_on_matrix_cores.restype = ctypes.c_int
     lib.octopus_probe_read.argtypes = [vp, ctypes.c_size_t, i32, i32, vp, vp]
@@ -356,6 +360,26 @@ def octopus_attn_decode_paged(cb, q, signs, k_pool, v_pool, block_table, seq_len
                                             _ptr(out), _ptr(workspace),
                                             int(workspace.numel() * workspace.element_size()), _stream_ptr(stream))
     _check(code, "octopus_attn_decode_paged")
+
+
+def octopus_attn_decode_paged_hybrid(cb, q, signs, k_pool, v_pool, block_table, seq_lens, max_len, k_window, win_lens,
+                                     scale, out, workspace, stream=None):
+    """octopus_attn_decode_paged plus a native-precision window: k_window device [n_seq, n_kv_heads, w_capacity, d]
+    contiguous (fp32 or bf16), win_lens device int32 [n_seq]; the window's values follow the compressed tokens' in
+    the sequence's value pages."""
+    assert q.is_contiguous() and v_pool.is_contiguous() and out.is_contiguous() and block_table.is_contiguous()
+    assert k_window.is_contiguous()
+    n_seq, n_q, n_qh, _ = q.shape
+    n_pages, n_kv = v_pool.shape[0], v_pool.shape[1]
+    assert block_table.shape[0] == n_seq and v_pool.shape[2] == 64 and _dtype_code(v_pool) == DTYPE_BF16
+    code = load().octopus_attn_decode_paged_hybrid(ctypes.byref(cb), _ptr(q), _dtype_code(q), n_seq, n_qh, n_kv, n_q,
+                                                   _ptr(signs), _ptr(k_pool), _ptr(v_pool), int(n_pages),
+                                                   _ptr(block_table), int(block_table.shape[1]), _ptr(seq_lens),
+                                                   int(max_len), _ptr(k_window), _dtype_code(k_window),
+                                                   int(k_window.shape[2]), _ptr(win_lens), float(scale), _ptr(out),
+                                                   _ptr(workspace), int(workspace.numel() * workspace.element_size()),
+                                                   _stream_ptr(stream))
+    _check(code, "octopus_attn_decode_paged_hybrid")
 
 
 def octopus_profile_events(before, after):

@@ -259,12 +259,12 @@ int launch_merge(const octopus_plan_t &plan, const DecodeShape &s, const float *
 template <int D>
 static int window_d(const DecodeShape &s, const void *q, int q_dtype, const void *k_win, int k_dtype,
                     int64_t w_capacity, const int32_t *win_lens, const void *v, int v_dtype, const int32_t *seq_lens,
-                    float scale, float *win_ml, float *win_acc, float *scores_out, hipStream_t stream) {
+                    float scale, float *win_ml, float *win_acc, float *scores_out, PageTable pt, hipStream_t stream) {
     const int64_t rows = static_cast<int64_t>(s.n_seq) * s.n_q * s.n_q_heads;
     auto go = [&](auto kernel) {
         hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(rows)), dim3(kWave), 0, stream, s, q,
                            q_dtype == OCTOPUS_DTYPE_BF16 ? 1 : 0, k_win, w_capacity, win_lens, v, seq_lens, scale, win_ml,
-                           win_acc, scores_out);
+                           win_acc, scores_out, pt);
     };
     const bool kb = k_dtype == OCTOPUS_DTYPE_BF16, vb = v_dtype == OCTOPUS_DTYPE_BF16;
     if (kb && vb) go(window_kernel<D, true, true>);
@@ -277,12 +277,12 @@ static int window_d(const DecodeShape &s, const void *q, int q_dtype, const void
 int launch_window(const octopus_plan_t &plan, const DecodeShape &s, const void *q, int q_dtype, const void *k_win,
                   int k_dtype, int64_t w_capacity, const int32_t *win_lens, const void *v, int v_dtype,
                   const int32_t *seq_lens, float scale, float *win_ml, float *win_acc, float *scores_out,
-                  void *stream) {
+                  void *stream, PageTable pt) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     switch (plan.head_dim) {
-        case 64: return window_d<64>(s, q, q_dtype, k_win, k_dtype, w_capacity, win_lens, v, v_dtype, seq_lens, scale, win_ml, win_acc, scores_out, st);
-        case 128: return window_d<128>(s, q, q_dtype, k_win, k_dtype, w_capacity, win_lens, v, v_dtype, seq_lens, scale, win_ml, win_acc, scores_out, st);
-        case 256: return window_d<256>(s, q, q_dtype, k_win, k_dtype, w_capacity, win_lens, v, v_dtype, seq_lens, scale, win_ml, win_acc, scores_out, st);
+        case 64: return window_d<64>(s, q, q_dtype, k_win, k_dtype, w_capacity, win_lens, v, v_dtype, seq_lens, scale, win_ml, win_acc, scores_out, pt, st);
+        case 128: return window_d<128>(s, q, q_dtype, k_win, k_dtype, w_capacity, win_lens, v, v_dtype, seq_lens, scale, win_ml, win_acc, scores_out, pt, st);
+        case 256: return window_d<256>(s, q, q_dtype, k_win, k_dtype, w_capacity, win_lens, v, v_dtype, seq_lens, scale, win_ml, win_acc, scores_out, pt, st);
         default: return static_cast<int>(hipErrorInvalidValue);
     }
 }

@@ -796,11 +796,11 @@ int octopus_encode_paged(const octopus_codebooks_t *cb, const void *keys, int32_
     return err == 0 ? OCTOPUS_OK : OCTOPUS_EHIP;
 }
 
-int octopus_attn_decode_paged(const octopus_codebooks_t *cb, const void *q, int32_t q_dtype, int32_t n_seq,
-                              int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q, const uint8_t *signs,
-                              const void *k_pool, const void *v_pool, int32_t n_pages, const int32_t *block_table,
-                              int32_t max_pages_per_seq, const int32_t *seq_lens, int64_t max_len, float scale,
-                              float *out, void *workspace, size_t workspace_bytes, void *stream) {
+static int attn_decode_paged(const octopus_codebooks_t *cb, const void *q, int32_t q_dtype, int32_t n_seq,
+                             int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q, const uint8_t *signs,
+                             const void *k_pool, const void *v_pool, int32_t n_pages, const int32_t *block_table,
+                             int32_t max_pages_per_seq, const int32_t *seq_lens, int64_t max_len, float scale,
+                             float *out, void *workspace, size_t workspace_bytes, void *stream, const WindowArgs *win) {
     void *ev_before = g_event_before, *ev_after = g_event_after;
     g_event_before = g_event_after = nullptr;
     const int ok = decode_args_ok(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len);
@@ -816,6 +816,11 @@ int octopus_attn_decode_paged(const octopus_codebooks_t *cb, const void *q, int3
     if (max_len > reach) return OCTOPUS_EINVAL;
     if (q_dtype != OCTOPUS_DTYPE_F32 && q_dtype != OCTOPUS_DTYPE_BF16) return OCTOPUS_EUNSUPPORTED;
     if (!aligned(q, 4) || !aligned(out, 4) || !std::isfinite(scale)) return OCTOPUS_EINVAL;
+    if (win != nullptr) {
+        if (win->k_window == nullptr || win->win_lens == nullptr || win->w_capacity < 1) return OCTOPUS_EINVAL;
+        if (win->k_dtype != OCTOPUS_DTYPE_F32 && win->k_dtype != OCTOPUS_DTYPE_BF16) return OCTOPUS_EUNSUPPORTED;
+        if (!aligned(win->k_window, 16)) return OCTOPUS_EINVAL;
+    }
     const DecodeShape s = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, reach, false);
     const Workspace w = make_workspace(cb->plan, s);
     const size_t required = std::max(w.total, octopus_attn_decode_workspace(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len));
@@ -832,8 +837,43 @@ int octopus_attn_decode_paged(const octopus_codebooks_t *cb, const void *q, int3
     if (err == 0)
         err = launch_decode_paged(*cb, s, q_rot, k_pool, v_pool, pt, seq_lens, part_ml, part_acc, work_plan, stream);
     if (err == 0 && ev_after != nullptr) err = record_event(ev_after, stream);
-    if (err == 0) err = launch_merge(cb->plan, s, part_ml, part_acc, work_plan, out, nullptr, nullptr, stream);
+    float *win_ml = nullptr, *win_acc = nullptr;
+    if (err == 0 && win != nullptr) {
+        // the window's value rows follow the compressed tokens in the sequence's pages
+        win_ml = reinterpret_cast<float *>(base + w.win_ml_off);
+        win_acc = reinterpret_cast<float *>(base + w.win_acc_off);
+        err = launch_window(cb->plan, s, q, q_dtype, win->k_window, win->k_dtype, win->w_capacity, win->win_lens, v_pool,
+                            OCTOPUS_DTYPE_BF16, seq_lens, scale, win_ml, win_acc, nullptr, stream, pt);
+    }
+    if (err == 0) err = launch_merge(cb->plan, s, part_ml, part_acc, work_plan, out, win_ml, win_acc, stream);
     return err == 0 ? OCTOPUS_OK : OCTOPUS_EHIP;
+}
+
+int octopus_attn_decode_paged(const octopus_codebooks_t *cb, const void *q, int32_t q_dtype, int32_t n_seq,
+                              int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q, const uint8_t *signs,
+                              const void *k_pool, const void *v_pool, int32_t n_pages, const int32_t *block_table,
+                              int32_t max_pages_per_seq, const int32_t *seq_lens, int64_t max_len, float scale,
+                              float *out, void *workspace, size_t workspace_bytes, void *stream) {
+    return attn_decode_paged(cb, q, q_dtype, n_seq, n_q_heads, n_kv_heads, n_q, signs, k_pool, v_pool, n_pages,
+                             block_table, max_pages_per_seq, seq_lens, max_len, scale, out, workspace, workspace_bytes,
+                             stream, nullptr);
+}
+
+int octopus_attn_decode_paged_hybrid(const octopus_codebooks_t *cb, const void *q, int32_t q_dtype, int32_t n_seq,
+                                     int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q, const uint8_t *signs,
+                                     const void *k_pool, const void *v_pool, int32_t n_pages,
+                                     const int32_t *block_table, int32_t max_pages_per_seq, const int32_t *seq_lens,
+                                     int64_t max_len, const void *k_window, int32_t k_dtype, int64_t w_capacity,
+                                     const int32_t *win_lens, float scale, float *out, void *workspace,
+                                     size_t workspace_bytes, void *stream) {
+    WindowArgs win;
+    win.k_window = k_window;
+    win.k_dtype = k_dtype;
+    win.w_capacity = w_capacity;
+    win.win_lens = win_lens;
+    return attn_decode_paged(cb, q, q_dtype, n_seq, n_q_heads, n_kv_heads, n_q, signs, k_pool, v_pool, n_pages,
+                             block_table, max_pages_per_seq, seq_lens, max_len, scale, out, workspace, workspace_bytes,
+                             stream, &win);
 }
 
 const char *octopus_strerror(int code) {

@@ -88,11 +88,11 @@ int qjl_rows_cap(const octopus_plan_t &plan);
 int launch_merge(const octopus_plan_t &plan, const DecodeShape &s, const float *part_ml, const float *part_acc,
                  const int32_t *work_plan, float *out, const float *win_ml, const float *win_acc, void *stream);
 // Attention partial (m, l, acc) per output row over the native-precision window that follows the
-// compressed tokens of each sequence.
+// compressed tokens of each sequence; pt: the value rows lie in pages (s.t_capacity = what the table addresses).
 int launch_window(const octopus_plan_t &plan, const DecodeShape &s, const void *q, int q_dtype, const void *k_win,
                   int k_dtype, int64_t w_capacity, const int32_t *win_lens, const void *v, int v_dtype,
                   const int32_t *seq_lens, float scale, float *win_ml, float *win_acc, float *scores_out,
-                  void *stream);
+                  void *stream, PageTable pt = PageTable{nullptr, 0, 0});
 int launch_encode(const octopus_codebooks_t &cb, const void *keys, int key_dtype, int64_t stride_seq,
                   int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
                   const uint8_t *signs, void *cache, int64_t t_capacity, const int32_t *start_pos,

@@ -10,7 +10,9 @@
 namespace octopus {
 
 // One wavefront per output row (sequence, query, query head).  Keys: [n_seq][n_kv_heads][w_capacity][D],
-// values: rows seq_lens[s] + j of the value buffer [n_seq][n_kv_heads][t_capacity][D] (bf16 or fp32 each).
+// values: rows seq_lens[s] + j of the value buffer [n_seq][n_kv_heads][t_capacity][D] (bf16 or fp32 each); with a
+// page table (pt.table not NULL) token t of sequence s is row t % 64 of [page][KV head] of a pool of value pages,
+// page = pt.table[s * pt.stride + t / 64] clamped to the pool, and t_capacity is what the table can address.
 // Chunks of 64 window tokens, one token per lane for the scores (the query sits in LDS), then every lane
 // accumulates its D / 64 channels over the chunk's tokens.
 template <int D, bool k_is_bf16, bool v_is_bf16>
@@ -20,7 +22,7 @@ __global__ __launch_bounds__(kWave) void window_kernel(DecodeShape shp, const vo
                                                        const void *__restrict__ v,
                                                        const int32_t *__restrict__ seq_lens, float scale,
                                                        float *__restrict__ win_ml, float *__restrict__ win_acc,
-                                                       float *__restrict__ scores_out) {
+                                                       float *__restrict__ scores_out, PageTable pt) {
     constexpr int CPT = D / kWave;  // channels per lane: c * 64 + lane
     __shared__ float qs[D];
     const int lane = threadIdx.x;
@@ -41,6 +43,13 @@ __global__ __launch_bounds__(kWave) void window_kernel(DecodeShape shp, const vo
     const int64_t n_win = max(int64_t{0}, min(min(static_cast<int64_t>(win_lens[seq]), w_capacity), shp.t_capacity - len));
     const int64_t pair = static_cast<int64_t>(seq) * shp.n_kv_heads + kvh;
     const int64_t k_row0 = pair * w_capacity, v_row0 = pair * shp.t_capacity + len;
+    // row of the value buffer (or pool) that holds window token j
+    auto v_row = [&](int64_t j) -> int64_t {
+        if (pt.table == nullptr) return v_row0 + j;
+        const int64_t t = len + j;
+        const int page = pt.table[static_cast<int64_t>(seq) * pt.stride + t / kWave];
+        return (static_cast<int64_t>(min(max(page, 0), pt.n_pages - 1)) * shp.n_kv_heads + kvh) * kWave + t % kWave;
+    };
 
     float m_run = -INFINITY, l_run = 0.0f, acc[CPT];
 #pragma unroll
@@ -92,7 +101,7 @@ __global__ __launch_bounds__(kWave) void window_kernel(DecodeShape shp, const vo
             for (int u = 0; u < 8; ++u)
 #pragma unroll
                 for (int c = 0; c < CPT; ++c)
-                    x[u][c] = load(v, v_is_bf16, (v_row0 + j0 + min(jb + u, nj - 1)) * D + c * kWave + lane);
+                    x[u][c] = load(v, v_is_bf16, v_row(j0 + min(jb + u, nj - 1)) * D + c * kWave + lane);
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const float pj = __shfl(p, min(jb + u, kWave - 1), kWave);   // p is zero in lanes >= nj

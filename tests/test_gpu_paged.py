@@ -207,3 +207,89 @@ def test_paged_encode_append_then_decode_end_to_end():
     for s in range(n_seq):
         for h in range(n_qh):
             check_out(out.cpu().numpy()[s, 0, h], ref_out[s, 0, h])
+
+
+def run_paged_hybrid_case(d, bits, n_seq, n_qh, n_kv, n_q, lens, win_lens, w_capacity, k_dtype, seed, spare_pages=4,
+                          reach=None):
+    """octopus_attn_decode_paged_hybrid against the oracle's dense definition over the reconstructed keys stacked
+    on the window's keys (the oracle knows only logical token order): the compressed tokens' records and ALL value
+    rows, the window's included, lie in randomly ordered pages."""
+    cb = binding.octopus_build_codebooks(d, bits)
+    plan = oracle.make_plan(d, bits)
+    rng = np.random.default_rng(seed)
+    tot = [int(a) + int(b) for a, b in zip(lens, win_lens)]
+    T = max(max(tot), 1)
+    cap = reach or -(-T // 64) * 64                       # tokens the block table can address (a multiple of 64)
+    max_pages = cap // 64
+    n_pages = n_seq * max_pages + spare_pages
+    keys, vals, signs = make_inputs(seed, n_seq, n_kv, T, d, "bf16")          # keys [n_seq, T, n_kv, d]
+    records = np.zeros((n_seq, n_kv, cap, plan.record_bytes), dtype=np.uint8)
+    k_win = np.zeros((n_seq, n_kv, w_capacity, d), dtype=np.float32)
+    for s in range(n_seq):
+        L, W = int(lens[s]), int(win_lens[s])
+        for h in range(n_kv):
+            if L:
+                records[s, h, :L] = oracle.encode(plan, keys[s, :L, h].astype(np.float64), signs[h])
+            k_win[s, h, :W] = keys[s, L:L + W, h]
+    q = synth.queries(seed, synth.Workload("t", n_seq, n_qh, n_kv, d, T, bits, "bf16", n_q=n_q))
+    v = np.zeros((n_seq, n_kv, cap, d), dtype=np.float32)
+    v[:, :, :min(T, cap)] = vals[:, :, :cap]
+    table = random_table(rng, n_seq, max_pages, n_pages)
+    k_pool, v_pool = pools_from_logical(cb, records, v, table, n_pages, cap)
+    scale = 1.0 / np.sqrt(d)
+    max_len = max(int(x) for x in lens)
+    ws = torch.empty(binding.octopus_attn_decode_workspace(cb, n_seq, n_qh, n_kv, n_q, max_len), dtype=torch.uint8,
+                     device=DEV)
+    out = torch.full((n_seq, n_q, n_qh, d), float("nan"), dtype=torch.float32, device=DEV)
+    binding.octopus_attn_decode_paged_hybrid(
+        cb, to_dev(q, "bf16"), sign_bits_dev(signs), torch.from_numpy(k_pool).to(DEV), to_dev(v_pool, "bf16"),
+        torch.from_numpy(table).to(DEV), torch.tensor(np.asarray(lens), dtype=torch.int32, device=DEV), max_len,
+        to_dev(k_win, k_dtype), torch.tensor(np.asarray(win_lens), dtype=torch.int32, device=DEV), scale, out, ws)
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    g = n_qh // n_kv
+    worst = 0.0
+    for s in range(n_seq):
+        L = int(lens[s])
+        W = min(int(win_lens[s]), w_capacity, cap - L)          # window tokens the table cannot address are ignored
+        for h in range(n_kv):
+            if L + W == 0:
+                assert np.all(out[s, :, h * g:(h + 1) * g] == 0.0)
+                continue
+            qq = q[s, :, h * g:(h + 1) * g, :].reshape(-1, d).astype(np.float64)
+            _, ref_o = oracle.attention_hybrid(plan, records[s, h, :L], signs[h], k_win[s, h, :W], qq,
+                                               v[s, h, :L + W].astype(np.float64), scale)
+            ref_o = ref_o.reshape(n_q, g, d)
+            for qi in range(n_q):
+                for j in range(g):
+                    worst = max(worst, check_out(out[s, qi, h * g + j], ref_o[qi, j]))
+    print(f"[paged hybrid] d={d} b={bits} lens={list(lens)} window={list(win_lens)}: worst out err {worst:.3g}")
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_paged_hybrid_gqa_window_32_d128(bits):
+    # windows that stay inside a page, straddle a page boundary, start on one, and are empty
+    run_paged_hybrid_case(128, bits, 4, 8, 2, 1, [300, 100, 128, 57], [32, 32, 17, 0], 32, "bf16", seed=1700 + int(bits))
+
+
+def test_paged_hybrid_other_head_dims_fp32_window_keys_and_several_queries():
+    run_paged_hybrid_case(64, 2.5, 3, 4, 4, 2, [130, 0, 64], [5, 40, 64], 64, "fp32", seed=1711)
+    run_paged_hybrid_case(256, 3, 2, 4, 1, 1, [200, 31], [33, 32], 48, "bf16", seed=1712)
+
+
+def test_paged_hybrid_window_clipped_at_the_tables_reach_and_argument_errors():
+    # sequence 0: 120 compressed + 30 window tokens, but two pages (128 tokens) per sequence: 8 window tokens count
+    run_paged_hybrid_case(128, 3, 2, 4, 2, 1, [120, 40], [30, 20], 32, "bf16", seed=1713, reach=128)
+    cb = binding.octopus_build_codebooks(128, 3)
+    q = torch.zeros((1, 1, 4, 128), dtype=torch.bfloat16, device=DEV)
+    pool = torch.zeros(binding.octopus_paged_pool_bytes(cb, 4, 2), dtype=torch.uint8, device=DEV)
+    v_pool = torch.zeros((4, 2, 64, 128), dtype=torch.bfloat16, device=DEV)
+    table = torch.zeros((1, 4), dtype=torch.int32, device=DEV)
+    lens = torch.tensor([200], dtype=torch.int32, device=DEV)
+    ws = torch.empty(binding.octopus_attn_decode_workspace(cb, 1, 4, 2, 1, 200), dtype=torch.uint8, device=DEV)
+    out = torch.zeros((1, 1, 4, 128), dtype=torch.float32, device=DEV)
+    signs = torch.zeros(2 * 16, dtype=torch.uint8, device=DEV)
+    k_win = torch.zeros((1, 2, 0, 128), dtype=torch.bfloat16, device=DEV)         # w_capacity 0
+    with pytest.raises(binding.OctopusError) as err:
+        binding.octopus_attn_decode_paged_hybrid(cb, q, signs, pool, v_pool, table, lens, 200, k_win, lens, 0.1, out, ws)
+    assert err.value.code == binding.EINVAL

@@ -284,6 +284,18 @@ def test_paged_cache_sizes_and_argument_checks(lib):
     assert dec(*dargs(max_len=4097)) == binding.EINVAL            # beyond what 64 pages of 64 tokens hold
     assert dec(*dargs(k_pool=ctypes.c_void_p(0x1004))) == binding.EINVAL
     assert dec(*dargs(ws_bytes=ws - 1)) == binding.EWORKSPACE
+    hyb = lib.octopus_attn_decode_paged_hybrid
+    hargs = lambda **k: [ctypes.byref(cb), fake, 1, 2, 32, 8, 1, fake, k.get("k_pool", fake), fake, 128, fake, 64, fake,
+                         k.get("max_len", 4096), k.get("k_window", fake), k.get("k_dtype", 1), k.get("w_capacity", 32),
+                         k.get("win_lens", fake), ctypes.c_float(0.1), fake, ctypes.c_void_p(0x10000),
+                         k.get("ws_bytes", ws), null]
+    assert hyb(*hargs(k_window=null)) == binding.EINVAL
+    assert hyb(*hargs(win_lens=null)) == binding.EINVAL
+    assert hyb(*hargs(w_capacity=0)) == binding.EINVAL
+    assert hyb(*hargs(k_dtype=5)) == binding.EUNSUPPORTED
+    assert hyb(*hargs(k_pool=null)) == binding.EINVAL
+    assert hyb(*hargs(max_len=4097)) == binding.EINVAL
+    assert hyb(*hargs(ws_bytes=ws - 1)) == binding.EWORKSPACE
     enc = lib.octopus_encode_paged
     eargs = lambda **k: [ctypes.byref(cb), fake, 1, 8 * 1024, 1024, 128, 2, 8, k.get("n_new", 64), fake,
                          k.get("k_pool", fake), k.get("n_pages", 128), k.get("table", fake), k.get("max_pages", 4),
