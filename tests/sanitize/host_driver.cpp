@@ -19,7 +19,7 @@ int qjl_rows_cap(const octopus_plan_t &) { return 4; }
 int launch_merge(const octopus_plan_t &, const DecodeShape &, const float *, const float *, const int32_t *, float *,
                  const float *, const float *, void *) { ++g_launches; return 0; }
 int launch_window(const octopus_plan_t &, const DecodeShape &, const void *, int, const void *, int, int64_t,
-                  const int32_t *, const void *, int, const int32_t *, float, float *, float *, float *, void *) { ++g_launches; return 0; }
+                  const int32_t *, const void *, int, const int32_t *, float, float *, float *, float *, void *, PageTable) { ++g_launches; return 0; }
 int launch_encode(const octopus_codebooks_t &, const void *, int, int64_t, int64_t, int64_t, int32_t, int32_t, int32_t,
                   const uint8_t *, void *, int64_t, const int32_t *, const uint8_t *, void *, void *) { ++g_launches; return 0; }
 int launch_encode_paged(const octopus_codebooks_t &, const void *, int, int64_t, int64_t, int64_t, int32_t, int32_t,
