@@ -68,7 +68,8 @@ def parse():
                          "single-query workloads only")
     ap.add_argument("--paged", action="store_true",
                     help="paged cache: 64-token pages handed out in a random order from pools (octopus_encode_paged + "
-                         "octopus_attn_decode_paged); single-query bf16 workloads, plain variant only")
+                         "octopus_attn_decode_paged); single-query bf16 workloads, plain variant or with --vq "
+                         "(octopus_encode_values_paged + octopus_attn_decode_paged_vq)")
     ap.add_argument("--read-probe", action="store_true",
                     help="instead of the benchmark: time a plain streaming read of 1.25 GiB (octopus_probe_read), with and "
                          "without the non-temporal hint, and print the rates: the read rate this machine reaches with "
@@ -290,11 +291,18 @@ class Run:
             self.v_pool[self.table.reshape(-1).long()] = (
                 self.vals.reshape(wl.n_seq, wl.n_kv_heads, tiles, 64, wl.head_dim).permute(0, 2, 1, 3, 4)
                 .reshape(-1, wl.n_kv_heads, 64, wl.head_dim))
+            if self.v_bits:   # quantised value pages instead (written by the encode phase)
+                self.v_pool = None
+                self.vq = torch.zeros(binding.octopus_vq_bytes(wl.head_dim, self.v_bits, self.v_group, n_pages,
+                                                               wl.n_kv_heads, 64), dtype=torch.uint8, device=dev)
 
     def encode(self):
         from paper_2605_21226_amd import binding
         cb, cap = self.cb, self.cap
-        if self.v_bits:
+        if self.v_bits and self.paged:
+            binding.octopus_encode_values_paged(self.vals_tok, self.v_bits, self.v_group, self.vq, self.wl.n_kv_heads,
+                                                self.table)
+        elif self.v_bits:
             binding.octopus_encode_values(self.vals_tok, self.v_bits, self.v_group, self.vq, cap)
         if self.qjl:
             binding.octopus_encode_qjl(cb, self.keys[:, self.first:], self.sbits, self.s2bits, self.cache, self.side, cap,
@@ -316,6 +324,10 @@ class Run:
         elif self.window:
             binding.octopus_attn_decode_hybrid(cb, self.q, self.sbits, self.cache, cap, self.vals, self.lens_dev,
                                                self.max_len, self.k_win, self.win_dev, self.scale, self.out, self.ws)
+        elif self.v_bits and self.paged:
+            binding.octopus_attn_decode_paged_vq(cb, self.q, self.sbits, self.k_pool, self.vq, self.v_bits, self.v_group,
+                                                 wl.n_kv_heads, self.table, self.lens_dev, self.max_len, self.scale,
+                                                 self.out, self.ws)
         elif self.v_bits:
             binding.octopus_attn_decode_vq(cb, self.q, self.sbits, self.cache, cap, self.vq, self.v_bits, self.v_group,
                                            wl.n_kv_heads, self.lens_dev, self.max_len, self.scale, self.out, self.ws)
@@ -530,8 +542,8 @@ def main():
     if args.window and (many_rows or args.qjl or args.vq):
         print("bench.py: --window times single-query workloads of the plain variant", file=sys.stderr)
         sys.exit(2)
-    if args.paged and (many_rows or args.qjl or args.vq or args.window or args.rounding != 1 or wl.dtype != "bf16"):
-        print("bench.py: --paged times single-query bf16 workloads of the plain variant", file=sys.stderr)
+    if args.paged and (many_rows or args.qjl or args.window or args.rounding != 1 or wl.dtype != "bf16"):
+        print("bench.py: --paged times single-query bf16 workloads of the plain variant or with --vq", file=sys.stderr)
         sys.exit(2)
     if args.qjl and args.rounding != 1:
         print("bench.py: --qjl goes with the default rounding", file=sys.stderr)

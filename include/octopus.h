@@ -11,7 +11,8 @@
  *   octopus_encode_qjl, octopus_attn_decode_qjl    the 1-bit QJL residual (Sec. 3.6)
  *   octopus_encode_values, octopus_attn_decode_vq  group-quantised values (Sec. 4, Alg. 2)
  *   octopus_attn_decode_hybrid                     native-precision window (Sec. 4)
- *   octopus_encode_paged, octopus_attn_decode_paged, octopus_attn_decode_paged_hybrid
+ *   octopus_encode_paged, octopus_attn_decode_paged, octopus_attn_decode_paged_hybrid,
+ *   octopus_encode_values_paged, octopus_attn_decode_paged_vq
  *                                                  the same codec and attention over a paged cache
  *
  * Conventions
@@ -430,12 +431,45 @@ int octopus_attn_decode_paged_hybrid(const octopus_codebooks_t *cb,
                                      void *workspace, size_t workspace_bytes,
                                      void *stream);
 
+/* Group-quantised values (octopus_encode_values, octopus_attn_decode_vq) in pages.
+ *   vq_pool     device, 16-byte aligned: [n_pages][n_kv_heads][64] rows of octopus_vq_row_bytes(head_dim,
+ *               bits, group) bytes (octopus_vq_bytes(head_dim, bits, group, n_pages, n_kv_heads, 64) in all);
+ *               token t of sequence s is row t % 64 of page block_table[s][t / 64].
+ * octopus_encode_values_paged: arguments as octopus_encode_values with (vq, t_capacity) replaced by the pool
+ * and the table; rows at or past max_pages_per_seq * 64 are dropped; the rows written are byte for byte those
+ * of octopus_encode_values.
+ * octopus_attn_decode_paged_vq: octopus_attn_decode_paged over such a pool instead of bf16 value pages
+ * (v_bits, v_group as for octopus_attn_decode_vq).  Served by the matrix-core kernel only: shapes it is not
+ * built for (octopus_vq_on_matrix_cores(...) == 0) are refused with EUNSUPPORTED, as are 32 or more query
+ * rows per KV head.  Other arguments, workspace and errors as octopus_attn_decode_paged. */
+int octopus_encode_values_paged(const void *v, int32_t v_dtype,
+                                int64_t stride_seq, int64_t stride_tok, int64_t stride_head,
+                                int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
+                                int32_t head_dim, int32_t bits, int32_t group,
+                                void *vq_pool, int32_t n_pages,
+                                const int32_t *block_table, int32_t max_pages_per_seq,
+                                const int32_t *start_pos,
+                                void *stream);
+
+int octopus_attn_decode_paged_vq(const octopus_codebooks_t *cb,
+                                 const void *q, int32_t q_dtype,
+                                 int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q,
+                                 const uint8_t *signs,
+                                 const void *k_pool, const void *vq_pool, int32_t v_bits, int32_t v_group,
+                                 int32_t n_pages,
+                                 const int32_t *block_table, int32_t max_pages_per_seq,
+                                 const int32_t *seq_lens, int64_t max_len,
+                                 float scale,
+                                 float *out,
+                                 void *workspace, size_t workspace_bytes,
+                                 void *stream);
+
 /* Static, human-readable name of an error code. */
 const char *octopus_strerror(int code);
 
 /* ---- measurement aids (not part of the method; nothing above depends on them) ----
  * octopus_profile_events: the next decode-attention call made by this thread (octopus_attn_decode, its _static,
- * _qjl, _vq and _hybrid forms, octopus_attn_decode_paged and its _hybrid form) records the HIP events `before` and `after` (hipEvent_t
+ * _qjl, _vq and _hybrid forms, octopus_attn_decode_paged and its _hybrid and _vq forms) records the HIP events `before` and `after` (hipEvent_t
  * passed as void*, caller-owned, created with timing enabled) on the call's stream immediately before and after
  * the launch of its fused decode kernel, i.e. around Alg. 2 proper without the query rotation and the split
  * merge.  The handles are per thread and are forgotten by that call whether it succeeds or not; NULL, NULL

@@ -4,4 +4,5 @@ from .binding import (Codebooks, OctopusError, Plan, load, octopus_attn_decode, 
                       octopus_profile_events, octopus_qjl_bytes, octopus_encode_qjl, octopus_attn_decode_qjl, octopus_encode_rounding, octopus_vq_row_bytes, octopus_vq_bytes,
                       octopus_encode_values, octopus_attn_decode_vq, octopus_attn_decode_hybrid,
                       octopus_attn_decode_static, octopus_paged_pool_bytes, octopus_encode_paged,
-                      octopus_attn_decode_paged, octopus_attn_decode_paged_hybrid, octopus_vq_on_matrix_cores)
+                      octopus_attn_decode_paged, octopus_attn_decode_paged_hybrid, octopus_encode_values_paged,
+                      octopus_attn_decode_paged_vq, octopus_vq_on_matrix_cores)

@@ -24,7 +24,7 @@ EXPORTS = ("octopus_build_codebooks", "octopus_build_codebooks_pair", "octopus_c
            "octopus_encode_rounding", "octopus_vq_row_bytes", "octopus_vq_bytes", "octopus_encode_values",
            "octopus_attn_decode_vq", "octopus_attn_decode_hybrid",
            "octopus_paged_pool_bytes", "octopus_encode_paged", "octopus_attn_decode_paged",
-           "octopus_attn_decode_paged_hybrid",
+           "octopus_attn_decode_paged_hybrid", "octopus_encode_values_paged", "octopus_attn_decode_paged_vq",
            "octopus_attn_decode_static", "octopus_probe_read", "octopus_vq_on_matrix_cores")
 
 
@@ -124,6 +124,11 @@ def load():
     lib.octopus_attn_decode_paged_hybrid.argtypes = [CB, vp, i32, i32, i32, i32, i32, vp, vp, vp, i32, vp, i32, vp, i64,
                                                      vp, i32, i64, vp, f32, vp, vp, ctypes.c_size_t, vp]
     lib.octopus_attn_decode_paged_hybrid.restype = ctypes.c_int
+    lib.octopus_encode_values_paged.argtypes = [vp, i32, i64, i64, i64, i32, i32, i32, i32, i32, i32, vp, i32, vp, i32, vp, vp]
+    lib.octopus_encode_values_paged.restype = ctypes.c_int
+    lib.octopus_attn_decode_paged_vq.argtypes = [CB, vp, i32, i32, i32, i32, i32, vp, vp, vp, i32, i32, i32, vp, i32, vp,
+                                                 i64, f32, vp, vp, ctypes.c_size_t, vp]
+    lib.octopus_attn_decode_paged_vq.restype = ctypes.c_int
     lib.octopus_vq_on_matrix_cores.argtypes = [ctypes.POINTER(Codebooks), i32, i32, i32, i32, i32]
     lib.octopus_vq_on_matrix_cores.restype = ctypes.c_int
     lib.octopus_probe_read.argtypes = [vp, ctypes.c_size_t, i32, i32, vp, vp]
@@ -380,6 +385,37 @@ def octopus_attn_decode_paged_hybrid(cb, q, signs, k_pool, v_pool, block_table, 
                                                    _ptr(workspace), int(workspace.numel() * workspace.element_size()),
                                                    _stream_ptr(stream))
     _check(code, "octopus_attn_decode_paged_hybrid")
+
+
+def octopus_encode_values_paged(v, bits, group, vq_pool, n_kv_heads, block_table, start_pos=None, stream=None):
+    """octopus_encode_values into pages: v device [n_seq, n_new, n_kv_heads, d] (any strides, last one 1), vq_pool
+    device uint8 of [n_pages][n_kv_heads][64] rows, block_table device int32 [n_seq, max_pages_per_seq]."""
+    assert v.stride(-1) == 1 and block_table.is_contiguous()
+    n_seq, n_new, n_kv, d = v.shape
+    assert n_kv == n_kv_heads
+    rb = octopus_vq_row_bytes(d, bits, group)
+    n_pages = vq_pool.numel() * vq_pool.element_size() // (n_kv * 64 * rb)
+    code = load().octopus_encode_values_paged(_ptr(v), _dtype_code(v), v.stride(0), v.stride(1), v.stride(2), n_seq, n_kv,
+                                              n_new, d, int(bits), int(group), _ptr(vq_pool), int(n_pages),
+                                              _ptr(block_table), int(block_table.shape[1]),
+                                              _ptr(start_pos), _stream_ptr(stream))
+    _check(code, "octopus_encode_values_paged")
+
+
+def octopus_attn_decode_paged_vq(cb, q, signs, k_pool, vq_pool, v_bits, v_group, n_kv_heads, block_table, seq_lens,
+                                 max_len, scale, out, workspace, stream=None):
+    """octopus_attn_decode_paged over group-quantised value pages (vq_pool as octopus_encode_values_paged wrote it)."""
+    assert q.is_contiguous() and out.is_contiguous() and block_table.is_contiguous()
+    n_seq, n_q, n_qh, d = q.shape
+    rb = octopus_vq_row_bytes(d, v_bits, v_group)
+    n_pages = vq_pool.numel() * vq_pool.element_size() // (n_kv_heads * 64 * rb)
+    assert block_table.shape[0] == n_seq
+    code = load().octopus_attn_decode_paged_vq(ctypes.byref(cb), _ptr(q), _dtype_code(q), n_seq, n_qh, int(n_kv_heads),
+                                               n_q, _ptr(signs), _ptr(k_pool), _ptr(vq_pool), int(v_bits), int(v_group),
+                                               int(n_pages), _ptr(block_table), int(block_table.shape[1]),
+                                               _ptr(seq_lens), int(max_len), float(scale), _ptr(out), _ptr(workspace),
+                                               int(workspace.numel() * workspace.element_size()), _stream_ptr(stream))
+    _check(code, "octopus_attn_decode_paged_vq")
 
 
 def octopus_profile_events(before, after):

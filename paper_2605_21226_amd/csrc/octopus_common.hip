@@ -25,7 +25,7 @@ bool plan_supported_d256(const octopus_plan_t &);
     int vq_mfma_available_d##D(const octopus_plan_t &, int, int, int);                                             \
     int launch_decode_vq_d##D(const octopus_codebooks_t &, const DecodeShape &, const float *, const void *,       \
                               const void *, int, int, const int32_t *, float *, float *, float *, int32_t *,       \
-                              void *);                                                                             \
+                              void *, const PageTable &);                                                          \
     int launch_encode_rounding_d##D(const octopus_codebooks_t &, const void *, int, int64_t, int64_t, int64_t,     \
                                     int32_t, int32_t, int32_t, const uint8_t *, void *, int64_t, const int32_t *,  \
                                     int32_t, void *);                                                              \
@@ -122,11 +122,11 @@ int launch_decode(const octopus_codebooks_t &cb, const DecodeShape &s, const flo
 
 int launch_decode_vq(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
                      const void *vq, int v_bits, int v_group, const int32_t *seq_lens, float *part_ml,
-                     float *part_acc, float *scores_out, int32_t *work_plan, void *stream) {
+                     float *part_acc, float *scores_out, int32_t *work_plan, void *stream, PageTable pt) {
     switch (cb.plan.head_dim) {
-        case 64: return launch_decode_vq_d64(cb, s, q_rot, cache, vq, v_bits, v_group, seq_lens, part_ml, part_acc, scores_out, work_plan, stream);
-        case 128: return launch_decode_vq_d128(cb, s, q_rot, cache, vq, v_bits, v_group, seq_lens, part_ml, part_acc, scores_out, work_plan, stream);
-        case 256: return launch_decode_vq_d256(cb, s, q_rot, cache, vq, v_bits, v_group, seq_lens, part_ml, part_acc, scores_out, work_plan, stream);
+        case 64: return launch_decode_vq_d64(cb, s, q_rot, cache, vq, v_bits, v_group, seq_lens, part_ml, part_acc, scores_out, work_plan, stream, pt);
+        case 128: return launch_decode_vq_d128(cb, s, q_rot, cache, vq, v_bits, v_group, seq_lens, part_ml, part_acc, scores_out, work_plan, stream, pt);
+        case 256: return launch_decode_vq_d256(cb, s, q_rot, cache, vq, v_bits, v_group, seq_lens, part_ml, part_acc, scores_out, work_plan, stream, pt);
         default: return static_cast<int>(hipErrorInvalidValue);
     }
 }

@@ -99,7 +99,10 @@ __global__ __launch_bounds__((vq_waves<P, RG, VB, VG>() * kWave))
     __attribute__((amdgpu_waves_per_eu(vq_waves<P, RG, VB, VG>() / 4, vq_waves<P, RG, VB, VG>() / 4))) void decode_kernel_vq_mfma(
     DeviceBooks books, DecodeShape shp, const float *__restrict__ q_rot, const uint4 *__restrict__ cache,
     const unsigned char *__restrict__ vq, const int32_t *__restrict__ seq_lens, float *__restrict__ part_ml,
-    float *__restrict__ part_acc, int32_t *__restrict__ plan) {
+    float *__restrict__ part_acc, int32_t *__restrict__ plan, PageTable pt) {
+    // pt.table (or NULL): `cache` and `vq` are pools of 64-token pages, [page][KV head] each a key tile of the cache
+    // layout and 64 value rows; logical tile j of sequence s lives in page pt.table[s * pt.stride + j] (ids outside
+    // the pool are clamped: a wrong table reads wrong pages, never outside the pools).
     using Gm = VqGeometry<P, RG, VB, VG>;
     static_assert(RG == 4 || RG == 8, "row groups of 4 or 8");
     constexpr int D = P::D, KPL = Gm::KPL, CPL = Gm::CPL, RP = Gm::RP, RB = Gm::RB, CB = Gm::CB;
@@ -146,7 +149,21 @@ __global__ __launch_bounds__((vq_waves<P, RG, VB, VG>() * kWave))
     const unsigned char *meta_lane = stage_w + lane * RB + CB;
     uint16_t *xs_key = &sm.xs[wave][0][0][0][ppos];
 
-    auto load_record = [&](int64_t tile, uint32_t (&w)[P::NWORDS]) {
+    const bool paged = pt.table != nullptr;
+    // The page of a step's tile is read one step before the step's loads are issued, through the vector memory path
+    // (every lane the same entry), so that nothing waits for the table right after asking it.
+    int lane_zero = 0;
+    asm volatile("" : "+v"(lane_zero));
+    auto page_ask = [&](int step) -> int {
+        const int tile = max(min(step * KPL, ww.n_tiles - 1), 0);
+        return pt.table[static_cast<int64_t>(ww.seq) * pt.stride + tile + lane_zero];
+    };
+    // position of a page's tile of this item's KV head in the pools, in tiles
+    auto page_slot = [&](int asked) -> int64_t {
+        const int id = __builtin_amdgcn_readfirstlane(asked);
+        return static_cast<int64_t>(min(max(id, 0), pt.n_pages - 1)) * shp.n_kv_heads + ww.kvh;
+    };
+    auto load_record = [&](const char *src, uint32_t (&w)[P::NWORDS]) {
         typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
         typedef uint32_t u32x3_t __attribute__((ext_vector_type(3)));
         typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
@@ -155,7 +172,6 @@ __global__ __launch_bounds__((vq_waves<P, RG, VB, VG>() * kWave))
         typedef const u32x2_t __attribute__((address_space(1))) *g2_t;
         typedef const uint32_t __attribute__((address_space(1))) *g1_t;
         constexpr int USED = (P::RECORD_BYTES + 3) / 4;
-        const char *src = k_region + tile * TILEB;
 #pragma unroll
         for (int g = 0; g < P::GRANULES; ++g) {
             const char *gp = src + g * (kWave * 16) + k_lane;
@@ -175,19 +191,22 @@ __global__ __launch_bounds__((vq_waves<P, RG, VB, VG>() * kWave))
             }
         }
     };
-    auto load_records = [&](int step, uint32_t (&w)[KPL][P::NWORDS]) {
-#pragma unroll
-        for (int k = 0; k < KPL; ++k) load_record(min(step * KPL + k, ww.n_tiles - 1), w[k]);
+    // slot: the pool position of the step's tile (paged cache only)
+    auto load_records = [&](int step, int64_t slot, uint32_t (&w)[KPL][P::NWORDS]) {
+        static_assert(KPL == 1, "one tile per step");
+        const int64_t tile = paged ? slot : static_cast<int64_t>(min(step * KPL, ww.n_tiles - 1));
+        load_record(k_region + tile * TILEB, w[0]);
     };
     // The value rows of a step come through a buffer descriptor that ends with the sequence's last token (rows
     // past it read as zeros: code 0, scale 0, zero point 0); the descriptor of a step that does not exist is
     // empty and its loads move nothing.  Streamed data: non-temporal.
-    auto load_rows = [&](int step, bool exists, uint4 (&rows)[NLS]) {
+    auto load_rows = [&](int step, int64_t slot, bool exists, uint4 (&rows)[NLS]) {
         typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
         const int t0 = step * (KPL * kWave);
         const int n_valid = exists ? min(KPL * kWave, ww.len - t0) : 0;
+        const int64_t first_row = paged ? slot * kWave : static_cast<int64_t>(t0);
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<char *>(v_pair + static_cast<int64_t>(t0) * RB), 0, n_valid * RB, 0x00020000);
+            const_cast<char *>(v_pair + first_row * RB), 0, n_valid * RB, 0x00020000);
 #pragma unroll
         for (int i = 0; i < NLS; ++i) {
             const u32x4_t x = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (i * kWave + lane) * 16, 0, kStreamPolicy);
@@ -299,6 +318,8 @@ __global__ __launch_bounds__((vq_waves<P, RG, VB, VG>() * kWave))
 
     uint4 rows[NLS];   // the value rows of the wave's next step, in flight; staged at the top of that step
     uint32_t w[KPL][P::NWORDS];   // the records of the wave's next step, in flight; replaced after the score pass
+    int64_t slot_nx = 0;          // paged cache: pool position of the next step's tile
+    int page_asked = 0;           // ... and the table entry of the step after it, on its way
     auto process_step = [&](int step) __attribute__((always_inline)) {
         const int t0 = step * (KPL * kWave);
         const int n_valid = min(KPL * kWave, ww.len - t0);
@@ -311,7 +332,11 @@ __global__ __launch_bounds__((vq_waves<P, RG, VB, VG>() * kWave))
         // ... and the next step's rows on their way (the row loads of a step that does not exist go through an
         // empty descriptor)
         const int step_nx = min(step + ww.step_stride, ww.step_last);
-        load_rows(step_nx, step + ww.step_stride < ww.step_end, rows);
+        if (paged) {
+            slot_nx = page_slot(page_asked);
+            page_asked = page_ask(min(step_nx + ww.step_stride, ww.step_last));   // used one step from here
+        }
+        load_rows(step_nx, slot_nx, step + ww.step_stride < ww.step_end, rows);
         asm volatile("" ::: "memory");
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -345,7 +370,7 @@ __global__ __launch_bounds__((vq_waves<P, RG, VB, VG>() * kWave))
         }
         // the records are used up: the next step's take their place (the wave's last step re-reads its own);
         // scales and zero points of this lane's keys for the products below
-        load_records(step_nx, w);
+        load_records(step_nx, slot_nx, w);
         float2 sz[KPL][G];
         load_meta(sz);
         // D5: online softmax, one running maximum per row for the whole wave; s becomes the probabilities
@@ -401,8 +426,8 @@ __global__ __launch_bounds__((vq_waves<P, RG, VB, VG>() * kWave))
     while (next_item(plan, &item_slot, tid, &taken, &it)) {
         item_work(shp, plan, seq_lens, it, wave, KPL, &ww);
         qg = q_rot + ww.group_id * (P::QS * RG);
-        k_region = reinterpret_cast<const char *>(cache) + ww.pair * shp.t_capacity * (P::GRANULES * 16);
-        v_pair = reinterpret_cast<const char *>(vq) + ww.pair * shp.t_capacity * RB;
+        k_region = reinterpret_cast<const char *>(cache) + (paged ? 0 : ww.pair * shp.t_capacity * (P::GRANULES * 16));
+        v_pair = reinterpret_cast<const char *>(vq) + (paged ? 0 : ww.pair * shp.t_capacity * RB);
         {   // the record pointer loses its "read-only" provenance: see decode_kernel_mfma
             const uint64_t bits = reinterpret_cast<uint64_t>(k_region);
             uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(bits));
@@ -423,8 +448,13 @@ __global__ __launch_bounds__((vq_waves<P, RG, VB, VG>() * kWave))
             for (int hh = 0; hh < NA; ++hh) acc[c][hh] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
 
         const bool any = ww.step_begin < ww.step_end;
-        if (any) load_records(ww.step_begin, w);
-        load_rows(ww.step_begin, any, rows);
+        int64_t slot_first = 0;
+        if (paged && any) {
+            slot_first = page_slot(page_ask(ww.step_begin));
+            page_asked = page_ask(min(ww.step_begin + ww.step_stride, ww.step_last));
+        }
+        if (any) load_records(ww.step_begin, slot_first, w);
+        load_rows(ww.step_begin, slot_first, any, rows);
         if (!tables_built) {   // workgroup-uniform
             build_tables<P, MX>(sm.tb, books, tid, NWV * kWave);
             tables_built = true;
@@ -498,14 +528,14 @@ __global__ __launch_bounds__((vq_waves<P, RG, VB, VG>() * kWave))
 template <class P, int RG, int VB, int VG>
 int launch_decode_vq_mfma_one(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
                               const void *vq, const int32_t *seq_lens, float *part_ml, float *part_acc, int32_t *plan,
-                              hipStream_t stream) {
+                              hipStream_t stream, const PageTable &pt) {
     if constexpr (vq_mfma_fits<P, RG, VB, VG>()) {
         const DeviceBooks books = device_books(cb);
         constexpr int NWV = VqGeometry<P, RG, VB, VG>::NWV;
         if (s.item_waves != NWV || s.tiles_per_step != 1) return static_cast<int>(hipErrorInvalidValue);
         hipLaunchKernelGGL((decode_kernel_vq_mfma<P, RG, VB, VG>), dim3(kDecodeWorkgroups), dim3(NWV * kWave), 0,
                            stream, books, s, q_rot, static_cast<const uint4 *>(cache),
-                           static_cast<const unsigned char *>(vq), seq_lens, part_ml, part_acc, plan);
+                           static_cast<const unsigned char *>(vq), seq_lens, part_ml, part_acc, plan, pt);
         return static_cast<int>(hipGetLastError());
     } else {
         return -1;
@@ -515,13 +545,13 @@ int launch_decode_vq_mfma_one(const octopus_codebooks_t &cb, const DecodeShape &
 template <class P, int VB>
 int launch_decode_vq_mfma_plan(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot,
                                const void *cache, const void *vq, int v_group, const int32_t *seq_lens, float *part_ml,
-                               float *part_acc, int32_t *plan, hipStream_t stream) {
+                               float *part_acc, int32_t *plan, hipStream_t stream, const PageTable &pt) {
     if (v_group == 32) {
-        if (s.rows_per_pass == 4) return launch_decode_vq_mfma_one<P, 4, VB, 32>(cb, s, q_rot, cache, vq, seq_lens, part_ml, part_acc, plan, stream);
-        if (s.rows_per_pass == 8) return launch_decode_vq_mfma_one<P, 8, VB, 32>(cb, s, q_rot, cache, vq, seq_lens, part_ml, part_acc, plan, stream);
+        if (s.rows_per_pass == 4) return launch_decode_vq_mfma_one<P, 4, VB, 32>(cb, s, q_rot, cache, vq, seq_lens, part_ml, part_acc, plan, stream, pt);
+        if (s.rows_per_pass == 8) return launch_decode_vq_mfma_one<P, 8, VB, 32>(cb, s, q_rot, cache, vq, seq_lens, part_ml, part_acc, plan, stream, pt);
     } else if (v_group == 16) {
-        if (s.rows_per_pass == 4) return launch_decode_vq_mfma_one<P, 4, VB, 16>(cb, s, q_rot, cache, vq, seq_lens, part_ml, part_acc, plan, stream);
-        if (s.rows_per_pass == 8) return launch_decode_vq_mfma_one<P, 8, VB, 16>(cb, s, q_rot, cache, vq, seq_lens, part_ml, part_acc, plan, stream);
+        if (s.rows_per_pass == 4) return launch_decode_vq_mfma_one<P, 4, VB, 16>(cb, s, q_rot, cache, vq, seq_lens, part_ml, part_acc, plan, stream, pt);
+        if (s.rows_per_pass == 8) return launch_decode_vq_mfma_one<P, 8, VB, 16>(cb, s, q_rot, cache, vq, seq_lens, part_ml, part_acc, plan, stream, pt);
     }
     return -1;
 }

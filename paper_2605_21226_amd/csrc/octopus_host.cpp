@@ -733,9 +733,10 @@ size_t octopus_vq_bytes(int32_t head_dim, int32_t bits, int32_t group, int32_t n
     return octopus_vq_row_bytes(head_dim, bits, group) * n_seq * n_kv_heads * static_cast<size_t>(t_capacity);
 }
 
-int octopus_encode_values(const void *v, int32_t v_dtype, int64_t stride_seq, int64_t stride_tok, int64_t stride_head,
-                          int32_t n_seq, int32_t n_kv_heads, int32_t n_new, int32_t head_dim, int32_t bits,
-                          int32_t group, void *vq, int64_t t_capacity, const int32_t *start_pos, void *stream) {
+static int encode_values(const void *v, int32_t v_dtype, int64_t stride_seq, int64_t stride_tok, int64_t stride_head,
+                         int32_t n_seq, int32_t n_kv_heads, int32_t n_new, int32_t head_dim, int32_t bits,
+                         int32_t group, void *vq, int64_t t_capacity, const int32_t *start_pos, void *stream,
+                         PageTable pt) {
     if (v == nullptr || vq == nullptr) return OCTOPUS_EINVAL;
     if (n_seq < 1 || n_kv_heads < 1 || n_new < 0 || t_capacity < 1) return OCTOPUS_EINVAL;
     if (v_dtype != OCTOPUS_DTYPE_F32 && v_dtype != OCTOPUS_DTYPE_BF16) return OCTOPUS_EUNSUPPORTED;
@@ -748,8 +749,15 @@ int octopus_encode_values(const void *v, int32_t v_dtype, int64_t stride_seq, in
     if (n_seq > 65535 || static_cast<int64_t>(n_kv_heads) * (head_dim / group) > 4096) return OCTOPUS_EINVAL;
     if (n_new == 0) return OCTOPUS_OK;
     const int err = launch_encode_values(v, v_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new,
-                                         head_dim, bits, group, vq, t_capacity, start_pos, stream);
+                                         head_dim, bits, group, vq, t_capacity, start_pos, stream, pt);
     return err == 0 ? OCTOPUS_OK : OCTOPUS_EHIP;
+}
+
+int octopus_encode_values(const void *v, int32_t v_dtype, int64_t stride_seq, int64_t stride_tok, int64_t stride_head,
+                          int32_t n_seq, int32_t n_kv_heads, int32_t n_new, int32_t head_dim, int32_t bits,
+                          int32_t group, void *vq, int64_t t_capacity, const int32_t *start_pos, void *stream) {
+    return encode_values(v, v_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, head_dim, bits, group,
+                         vq, t_capacity, start_pos, stream, PageTable{nullptr, 0, 0});
 }
 
 int octopus_attn_decode_vq(const octopus_codebooks_t *cb, const void *q, int32_t q_dtype, int32_t n_seq,
@@ -800,7 +808,9 @@ static int attn_decode_paged(const octopus_codebooks_t *cb, const void *q, int32
                              int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q, const uint8_t *signs,
                              const void *k_pool, const void *v_pool, int32_t n_pages, const int32_t *block_table,
                              int32_t max_pages_per_seq, const int32_t *seq_lens, int64_t max_len, float scale,
-                             float *out, void *workspace, size_t workspace_bytes, void *stream, const WindowArgs *win) {
+                             float *out, void *workspace, size_t workspace_bytes, void *stream, const WindowArgs *win,
+                             int32_t v_bits = 0, int32_t v_group = 0) {
+    // v_bits > 0: v_pool holds group-quantised rows (the matrix-core kernel over them; no window)
     void *ev_before = g_event_before, *ev_after = g_event_after;
     g_event_before = g_event_after = nullptr;
     const int ok = decode_args_ok(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len);
@@ -821,7 +831,14 @@ static int attn_decode_paged(const octopus_codebooks_t *cb, const void *q, int32
         if (win->k_dtype != OCTOPUS_DTYPE_F32 && win->k_dtype != OCTOPUS_DTYPE_BF16) return OCTOPUS_EUNSUPPORTED;
         if (!aligned(win->k_window, 16)) return OCTOPUS_EINVAL;
     }
-    const DecodeShape s = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, reach, false);
+    int32_t vq_waves = 0;
+    if (v_bits != 0) {
+        if (!vq_params_ok(cb->plan.head_dim, v_bits, v_group)) return OCTOPUS_EUNSUPPORTED;
+        // over pages only the matrix-core kernel serves quantised values
+        vq_waves = vq_mfma_available(cb->plan, vq_mfma_rows(n_q * (n_q_heads / n_kv_heads)), v_bits, v_group);
+        if (vq_waves <= 0) return OCTOPUS_EUNSUPPORTED;
+    }
+    const DecodeShape s = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, reach, false, 8, vq_waves);
     const Workspace w = make_workspace(cb->plan, s);
     const size_t required = std::max(w.total, octopus_attn_decode_workspace(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len));
     if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < required) return OCTOPUS_EWORKSPACE;
@@ -834,8 +851,13 @@ static int attn_decode_paged(const octopus_codebooks_t *cb, const void *q, int32
     int err = launch_rotate_queries(cb->plan, q, q_dtype, signs, s, scale, q_rot, seq_lens, work_plan, nullptr, nullptr,
                                     stream);
     if (err == 0 && ev_before != nullptr) err = record_event(ev_before, stream);
-    if (err == 0)
-        err = launch_decode_paged(*cb, s, q_rot, k_pool, v_pool, pt, seq_lens, part_ml, part_acc, work_plan, stream);
+    if (err == 0) {
+        if (v_bits != 0)
+            err = launch_decode_vq(*cb, s, q_rot, k_pool, v_pool, v_bits, v_group, seq_lens, part_ml, part_acc, nullptr,
+                                   work_plan, stream, pt);
+        else
+            err = launch_decode_paged(*cb, s, q_rot, k_pool, v_pool, pt, seq_lens, part_ml, part_acc, work_plan, stream);
+    }
     if (err == 0 && ev_after != nullptr) err = record_event(ev_after, stream);
     float *win_ml = nullptr, *win_acc = nullptr;
     if (err == 0 && win != nullptr) {
@@ -874,6 +896,29 @@ int octopus_attn_decode_paged_hybrid(const octopus_codebooks_t *cb, const void *
     return attn_decode_paged(cb, q, q_dtype, n_seq, n_q_heads, n_kv_heads, n_q, signs, k_pool, v_pool, n_pages,
                              block_table, max_pages_per_seq, seq_lens, max_len, scale, out, workspace, workspace_bytes,
                              stream, &win);
+}
+
+int octopus_encode_values_paged(const void *v, int32_t v_dtype, int64_t stride_seq, int64_t stride_tok,
+                                int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new, int32_t head_dim,
+                                int32_t bits, int32_t group, void *vq_pool, int32_t n_pages, const int32_t *block_table,
+                                int32_t max_pages_per_seq, const int32_t *start_pos, void *stream) {
+    if (!page_table_ok(vq_pool, n_pages, block_table, max_pages_per_seq)) return OCTOPUS_EINVAL;
+    // the table addresses max_pages_per_seq * 64 tokens per sequence: that is the capacity rows are dropped beyond
+    const int64_t reach = static_cast<int64_t>(max_pages_per_seq) * OCTOPUS_TILE;
+    return encode_values(v, v_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, head_dim, bits, group,
+                         vq_pool, reach, start_pos, stream, PageTable{block_table, max_pages_per_seq, n_pages});
+}
+
+int octopus_attn_decode_paged_vq(const octopus_codebooks_t *cb, const void *q, int32_t q_dtype, int32_t n_seq,
+                                 int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q, const uint8_t *signs,
+                                 const void *k_pool, const void *vq_pool, int32_t v_bits, int32_t v_group,
+                                 int32_t n_pages, const int32_t *block_table, int32_t max_pages_per_seq,
+                                 const int32_t *seq_lens, int64_t max_len, float scale, float *out, void *workspace,
+                                 size_t workspace_bytes, void *stream) {
+    if (v_bits == 0) return OCTOPUS_EUNSUPPORTED;
+    return attn_decode_paged(cb, q, q_dtype, n_seq, n_q_heads, n_kv_heads, n_q, signs, k_pool, vq_pool, n_pages,
+                             block_table, max_pages_per_seq, seq_lens, max_len, scale, out, workspace, workspace_bytes,
+                             stream, nullptr, v_bits, v_group);
 }
 
 const char *octopus_strerror(int code) {

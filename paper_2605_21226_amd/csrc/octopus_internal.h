@@ -117,10 +117,12 @@ int launch_encode_rounding(const octopus_codebooks_t &cb, const void *keys, int 
 // Value codec (group-quantised value rows) and decode attention over it.
 int launch_encode_values(const void *v, int v_dtype, int64_t stride_seq, int64_t stride_tok, int64_t stride_head,
                          int32_t n_seq, int32_t n_kv_heads, int32_t n_new, int32_t head_dim, int32_t bits,
-                         int32_t group, void *vq, int64_t t_capacity, const int32_t *start_pos, void *stream);
+                         int32_t group, void *vq, int64_t t_capacity, const int32_t *start_pos, void *stream,
+                         PageTable pt = PageTable{nullptr, 0, 0});   // pt: vq is a pool of [page][KV head][64] rows
 int launch_decode_vq(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
                      const void *vq, int v_bits, int v_group, const int32_t *seq_lens, float *part_ml,
-                     float *part_acc, float *scores_out, int32_t *work_plan, void *stream);
+                     float *part_acc, float *scores_out, int32_t *work_plan, void *stream,
+                     PageTable pt = PageTable{nullptr, 0, 0});   // pt: cache and vq are pools of pages
 
 // Measurement aid: plain streaming read of `bytes` bytes by n_blocks workgroups (non-temporal loads or not).
 int launch_probe_read(const void *data, int64_t bytes, int nontemporal, int n_blocks, void *sink, void *stream);

@@ -30,7 +30,8 @@ __global__ __launch_bounds__(256) void encode_values_kernel(const void *__restri
                                                              int64_t stride_tok, int64_t stride_head, int32_t n_seq,
                                                              int32_t n_kv_heads, int32_t n_new, int32_t d,
                                                              unsigned char *__restrict__ vq, int64_t t_capacity,
-                                                             const int32_t *__restrict__ start_pos, int vec16) {
+                                                             const int32_t *__restrict__ start_pos, int vec16,
+                                                             PageTable pt) {
     constexpr int LEVELS = (1 << B) - 1;
     constexpr int CODE_WORDS = G * B / 32 + ((G * B) % 32 ? 1 : 0);   // 1, 2, 3 or 4
     constexpr int CODE_BYTES = G * B / 8;                             // the group's codes: 4 .. 16 bytes
@@ -137,7 +138,14 @@ __global__ __launch_bounds__(256) void encode_values_kernel(const void *__restri
         if (sh + B > 32) words[wi + 1] |= code >> (32 - sh);
     }
     const int row_bytes = B * d / 8 + n_groups * 8;
-    unsigned char *row = vq + ((static_cast<int64_t>(seq) * n_kv_heads + kvh) * t_capacity + pos) * row_bytes;
+    // pt.table (or NULL): vq is a pool of [page][KV head][64] rows, token t of sequence s in page
+    // pt.table[s * pt.stride + t / 64] (clamped to the pool); t_capacity is then what the table addresses
+    int64_t row_index = (static_cast<int64_t>(seq) * n_kv_heads + kvh) * t_capacity + pos;
+    if (pt.table != nullptr) {
+        const int page = pt.table[static_cast<int64_t>(seq) * pt.stride + pos / 64];
+        row_index = (static_cast<int64_t>(min(max(page, 0), pt.n_pages - 1)) * n_kv_heads + kvh) * 64 + pos % 64;
+    }
+    unsigned char *row = vq + row_index * row_bytes;
     unsigned char *dst = row + grp * CODE_BYTES;
     if constexpr (CODE_BYTES % 4 == 0) {          // rows are multiples of 8 bytes: the group starts on a word
 #pragma unroll
@@ -153,7 +161,7 @@ __global__ __launch_bounds__(256) void encode_values_kernel(const void *__restri
 
 int launch_encode_values(const void *v, int v_dtype, int64_t stride_seq, int64_t stride_tok, int64_t stride_head,
                          int32_t n_seq, int32_t n_kv_heads, int32_t n_new, int32_t head_dim, int32_t bits,
-                         int32_t group, void *vq, int64_t t_capacity, const int32_t *start_pos, void *stream) {
+                         int32_t group, void *vq, int64_t t_capacity, const int32_t *start_pos, void *stream, PageTable pt) {
     const int64_t per_token = static_cast<int64_t>(n_kv_heads) * (head_dim / group);
     if (per_token > 4096 || n_seq > 65535) return static_cast<int>(hipErrorInvalidValue);
     if (n_seq == 0 || n_new == 0) return 0;
@@ -167,7 +175,7 @@ int launch_encode_values(const void *v, int v_dtype, int64_t stride_seq, int64_t
                        stride_head % per16 == 0) ? 1 : 0;
     auto go = [&](auto kernel) {
         hipLaunchKernelGGL(kernel, grid, dim3(256), 0, st, v, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new,
-                           head_dim, static_cast<unsigned char *>(vq), t_capacity, start_pos, vec16);
+                           head_dim, static_cast<unsigned char *>(vq), t_capacity, start_pos, vec16, pt);
     };
     const bool bf16 = v_dtype == OCTOPUS_DTYPE_BF16;
 #define OCTOPUS_CASE(B, G)                                                                                          \

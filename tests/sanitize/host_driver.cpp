@@ -29,9 +29,9 @@ int launch_decode_paged(const octopus_codebooks_t &, const DecodeShape &, const 
 int launch_encode_rounding(const octopus_codebooks_t &, const void *, int, int64_t, int64_t, int64_t, int32_t, int32_t,
                            int32_t, const uint8_t *, void *, int64_t, const int32_t *, int32_t, void *) { ++g_launches; return 0; }
 int launch_encode_values(const void *, int, int64_t, int64_t, int64_t, int32_t, int32_t, int32_t, int32_t, int32_t,
-                         int32_t, void *, int64_t, const int32_t *, void *) { ++g_launches; return 0; }
+                         int32_t, void *, int64_t, const int32_t *, void *, PageTable) { ++g_launches; return 0; }
 int launch_decode_vq(const octopus_codebooks_t &, const DecodeShape &, const float *, const void *, const void *, int,
-                     int, const int32_t *, float *, float *, float *, int32_t *, void *) { ++g_launches; return 0; }
+                     int, const int32_t *, float *, float *, float *, int32_t *, void *, PageTable) { ++g_launches; return 0; }
 int record_event(void *, void *) { return 0; }
 int launch_probe_read(const void *, int64_t, int, int, void *, void *) { ++g_launches; return 0; }
 bool plan_supported(const octopus_plan_t &p) { return p.b_dir[0] <= 5 && p.b_nrm[0] <= 3; }

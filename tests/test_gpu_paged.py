@@ -293,3 +293,116 @@ def test_paged_hybrid_window_clipped_at_the_tables_reach_and_argument_errors():
     with pytest.raises(binding.OctopusError) as err:
         binding.octopus_attn_decode_paged_hybrid(cb, q, signs, pool, v_pool, table, lens, 200, k_win, lens, 0.1, out, ws)
     assert err.value.code == binding.EINVAL
+
+
+# ---- group-quantised values in pages --------------------------------------------------------------------------
+def vq_pool_from_logical(vq_rows, table, n_pages, cap, fill=0x5A):
+    """vq_rows [n_seq, n_kv, cap, rb] -> pool [n_pages, n_kv, 64, rb]; unused pages hold `fill`"""
+    n_seq, n_kv, _, rb = vq_rows.shape
+    pool = np.full((n_pages, n_kv, 64, rb), fill, dtype=np.uint8)
+    for s in range(n_seq):
+        for j in range(cap // 64):
+            pool[table[s, j]] = vq_rows[s, :, 64 * j:64 * j + 64]
+    return pool
+
+
+@pytest.mark.parametrize("d,v_bits,group,dtype", [(128, 3, 32, "bf16"), (64, 2, 16, "fp32"), (256, 4, 32, "bf16")])
+def test_paged_encode_values_writes_the_oracles_rows_into_the_right_pages(d, v_bits, group, dtype):
+    n_seq, n_kv, n_tok, max_pages = 2, 2, 150, 4
+    rng = np.random.default_rng(40 + d)
+    _, vals, _ = make_inputs(41 + d, n_seq, n_kv, n_tok, d, dtype)                # vals [n_seq, n_kv, n_tok, d]
+    n_pages = n_seq * max_pages + 3
+    table = random_table(rng, n_seq, max_pages, n_pages)
+    rb = oracle.vq_row_bytes(d, v_bits, group)
+    pool = torch.full((n_pages * n_kv * 64 * rb,), 0xEE, dtype=torch.uint8, device=DEV)
+    start = [0, 70]                                                               # sequence 1 appends behind 70 tokens
+    v_dev = to_dev(vals, dtype).permute(0, 2, 1, 3)                               # [n_seq, n_tok, n_kv, d] view
+    binding.octopus_encode_values_paged(v_dev, v_bits, group, pool, n_kv, torch.from_numpy(table).to(DEV),
+                                        torch.tensor(start, dtype=torch.int32, device=DEV))
+    torch.cuda.synchronize()
+    got = pool.cpu().numpy().reshape(n_pages, n_kv, 64, rb)
+    touched = np.zeros((n_pages, n_kv, 64), dtype=bool)
+    for s in range(n_seq):
+        for h in range(n_kv):
+            ref = oracle.vq_encode(vals[s, h], v_bits, group)
+            for i in range(n_tok):
+                t = start[s] + i
+                if t >= max_pages * 64:
+                    continue                                                      # past what the table addresses: dropped
+                assert np.array_equal(got[table[s, t // 64], h, t % 64], ref[i]), (s, h, i)
+                touched[table[s, t // 64], h, t % 64] = True
+    assert np.all(got[~touched] == 0xEE)                                          # every other row is as it was
+
+
+def run_paged_vq_decode_case(d, bits, v_bits, group, n_seq, n_qh, n_kv, n_q, lens, seed, spare_pages=3):
+    """octopus_attn_decode_paged_vq against the oracle's attention over its own dequantised rows; records and
+    quantised rows are the oracle's, scattered over randomly ordered pages."""
+    cb = binding.octopus_build_codebooks(d, bits)
+    plan = oracle.make_plan(d, bits)
+    rng = np.random.default_rng(seed)
+    T = max(int(max(lens)), 1)
+    cap = -(-T // 64) * 64
+    max_pages = cap // 64
+    n_pages = n_seq * max_pages + spare_pages
+    keys, vals, signs = make_inputs(seed, n_seq, n_kv, T, d, "bf16")
+    records = np.zeros((n_seq, n_kv, cap, plan.record_bytes), dtype=np.uint8)
+    rb = oracle.vq_row_bytes(d, v_bits, group)
+    vq_rows = np.zeros((n_seq, n_kv, cap, rb), dtype=np.uint8)
+    for s in range(n_seq):
+        for h in range(n_kv):
+            records[s, h, :T] = oracle.encode(plan, keys[s, :, h].astype(np.float64), signs[h])
+            vq_rows[s, h, :T] = oracle.vq_encode(vals[s, h], v_bits, group)
+    q = synth.queries(seed, synth.Workload("t", n_seq, n_qh, n_kv, d, T, bits, "bf16", n_q=n_q))
+    table = random_table(rng, n_seq, max_pages, n_pages)
+    k_pool, _ = pools_from_logical(cb, records, np.zeros((n_seq, n_kv, cap, d), dtype=np.float32), table, n_pages, cap)
+    vq_pool = vq_pool_from_logical(vq_rows, table, n_pages, cap)
+    scale = 1.0 / np.sqrt(d)
+    ws = torch.empty(binding.octopus_attn_decode_workspace(cb, n_seq, n_qh, n_kv, n_q, T), dtype=torch.uint8, device=DEV)
+    out = torch.full((n_seq, n_q, n_qh, d), float("nan"), dtype=torch.float32, device=DEV)
+    binding.octopus_attn_decode_paged_vq(cb, to_dev(q, "bf16"), sign_bits_dev(signs), torch.from_numpy(k_pool).to(DEV),
+                                         torch.from_numpy(vq_pool.reshape(-1)).to(DEV), v_bits, group, n_kv,
+                                         torch.from_numpy(table).to(DEV),
+                                         torch.tensor(np.asarray(lens), dtype=torch.int32, device=DEV), T, scale, out, ws)
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    g = n_qh // n_kv
+    worst = 0.0
+    for s in range(n_seq):
+        L = int(lens[s])
+        for h in range(n_kv):
+            if L == 0:
+                assert np.all(out[s, :, h * g:(h + 1) * g] == 0.0)
+                continue
+            v_hat = oracle.vq_decode(vq_rows[s, h, :L], d, v_bits, group)
+            qq = q[s, :, h * g:(h + 1) * g, :].reshape(-1, d).astype(np.float64)
+            _, ref_o, _ = oracle.attention(plan, records[s, h, :L], signs[h], qq, v_hat, scale)
+            ref_o = ref_o.reshape(n_q, g, d)
+            for qi in range(n_q):
+                for j in range(g):
+                    worst = max(worst, check_out(out[s, qi, h * g + j], ref_o[qi, j]))
+    print(f"[paged attn-vq] d={d} b={bits} v_bits={v_bits} g={group} lens={list(lens)}: worst out err {worst:.3g}")
+
+
+@pytest.mark.parametrize("d,bits,v_bits,group,n_qh,n_kv,n_q", [
+    (128, 3, 3, 32, 8, 2, 1), (128, 2, 4, 32, 4, 2, 1), (128, 3, 3, 16, 4, 1, 1), (128, 4, 2, 32, 8, 1, 1),
+    (64, 2.5, 3, 16, 4, 2, 1), (64, 4, 4, 32, 2, 2, 3), (256, 3, 3, 32, 4, 1, 1), (256, 1.5, 2, 32, 8, 2, 1)])
+def test_paged_decode_over_quantised_value_pages(d, bits, v_bits, group, n_qh, n_kv, n_q):
+    run_paged_vq_decode_case(d, bits, v_bits, group, 3, n_qh, n_kv, n_q, [300, 129, 0],
+                             seed=int(1800 + d + 10 * bits + v_bits))
+
+
+def test_paged_decode_over_quantised_value_pages_long_sequence_and_refusals():
+    run_paged_vq_decode_case(128, 3, 3, 32, 2, 4, 1, 1, [9000, 3000], seed=1821)      # 141 pages, several items
+    cb = binding.octopus_build_codebooks(128, 3)
+    q = torch.zeros((1, 1, 64, 128), dtype=torch.bfloat16, device=DEV)               # 8 rows per KV head ...
+    pool = torch.zeros(binding.octopus_paged_pool_bytes(cb, 4, 8), dtype=torch.uint8, device=DEV)
+    vq_pool = torch.zeros(4 * 8 * 64 * binding.octopus_vq_row_bytes(128, 3, 16), dtype=torch.uint8, device=DEV)
+    table = torch.zeros((1, 4), dtype=torch.int32, device=DEV)
+    lens = torch.tensor([200], dtype=torch.int32, device=DEV)
+    ws = torch.empty(binding.octopus_attn_decode_workspace(cb, 1, 64, 8, 1, 200), dtype=torch.uint8, device=DEV)
+    out = torch.zeros((1, 1, 64, 128), dtype=torch.float32, device=DEV)
+    signs = torch.zeros(8 * 16, dtype=torch.uint8, device=DEV)
+    assert not binding.octopus_vq_on_matrix_cores(cb, 64, 8, 1, 3, 16)               # ... x groups of 16: no such build
+    with pytest.raises(binding.OctopusError) as err:
+        binding.octopus_attn_decode_paged_vq(cb, q, signs, pool, vq_pool, 3, 16, 8, table, lens, 200, 0.1, out, ws)
+    assert err.value.code == binding.EUNSUPPORTED

@@ -296,6 +296,26 @@ def test_paged_cache_sizes_and_argument_checks(lib):
     assert hyb(*hargs(k_pool=null)) == binding.EINVAL
     assert hyb(*hargs(max_len=4097)) == binding.EINVAL
     assert hyb(*hargs(ws_bytes=ws - 1)) == binding.EWORKSPACE
+    pvq = lib.octopus_attn_decode_paged_vq
+    vargs = lambda **k: [ctypes.byref(cb), fake, 1, 2, 32, 8, 1, fake, k.get("k_pool", fake), k.get("vq_pool", fake),
+                         k.get("bits", 3), k.get("group", 32), 128, k.get("table", fake), 64, fake, k.get("max_len", 4096),
+                         ctypes.c_float(0.1), fake, ctypes.c_void_p(0x10000), k.get("ws_bytes", ws), null]
+    assert pvq(*vargs(vq_pool=null)) == binding.EINVAL
+    assert pvq(*vargs(table=null)) == binding.EINVAL
+    assert pvq(*vargs(bits=0)) == binding.EUNSUPPORTED
+    assert pvq(*vargs(bits=5)) == binding.EUNSUPPORTED
+    assert pvq(*vargs(group=8)) == binding.EUNSUPPORTED
+    assert pvq(*vargs(max_len=4097)) == binding.EINVAL
+    assert pvq(*vargs(ws_bytes=ws - 1)) == binding.EWORKSPACE
+    pve = lib.octopus_encode_values_paged
+    veargs = lambda **k: [fake, 1, 1024, 1024, 128, 1, 8, k.get("n_new", 64), 128, k.get("bits", 3), 32,
+                          k.get("pool", fake), k.get("n_pages", 16), k.get("table", fake), 4, null, null]
+    assert pve(*veargs(pool=null)) == binding.EINVAL
+    assert pve(*veargs(table=null)) == binding.EINVAL
+    assert pve(*veargs(n_pages=0)) == binding.EINVAL
+    assert pve(*veargs(bits=5)) == binding.EUNSUPPORTED
+    assert pve(*veargs(n_new=257)) == binding.EINVAL              # more rows than 4 pages hold, no start positions
+    assert pve(*veargs(n_new=0)) == binding.OK
     enc = lib.octopus_encode_paged
     eargs = lambda **k: [ctypes.byref(cb), fake, 1, 8 * 1024, 1024, 128, 2, 8, k.get("n_new", 64), fake,
                          k.get("k_pool", fake), k.get("n_pages", 128), k.get("table", fake), k.get("max_pages", 4),
