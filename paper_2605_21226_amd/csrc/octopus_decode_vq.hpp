@@ -71,9 +71,15 @@ constexpr bool vq_lds_fits_n() {
 
 // Wavefronts per workgroup: two per SIMD up to d = 128 (each within 256 registers), whose different phases --
 // vector work, matrix-core work, LDS traffic -- the hardware overlaps, where the LDS of eight wavefronts fits (each
-// has its own staging buffer and probability rows); else, and at d = 256, one per SIMD.
+// has its own staging buffer and probability rows) and the kernel fits 256 registers: up to 8 accumulator tiles
+// (with 16 it spills, and one wavefront per SIMD with 512 registers is faster: row groups of eight at d = 128
+// 0.42 -> 0.33 ms, groups of 16 channels 0.30 -> 0.24 ms on the Llama-shaped batch); else, and at d = 256, one per
+// SIMD.
 template <class P, int RG, int VB, int VG>
-constexpr int vq_waves() { return (P::D <= 128 && vq_lds_fits_n<P, RG, VB, VG, 8>()) ? 8 : 4; }
+constexpr int vq_waves() {
+    using G8 = VqGeometryN<P, RG, VB, VG, 8>;
+    return (P::D <= 128 && G8::CPL * G8::NA <= 8 && vq_lds_fits_n<P, RG, VB, VG, 8>()) ? 8 : 4;
+}
 
 template <class P, int RG, int VB, int VG>
 using VqGeometry = VqGeometryN<P, RG, VB, VG, vq_waves<P, RG, VB, VG>()>;
