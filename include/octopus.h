@@ -12,7 +12,8 @@
  *   octopus_encode_values, octopus_attn_decode_vq  group-quantised values (Sec. 4, Alg. 2)
  *   octopus_attn_decode_hybrid                     native-precision window (Sec. 4)
  *   octopus_encode_paged, octopus_attn_decode_paged, octopus_attn_decode_paged_hybrid,
- *   octopus_encode_values_paged, octopus_attn_decode_paged_vq
+ *   octopus_encode_values_paged, octopus_attn_decode_paged_vq,
+ *   octopus_encode_qjl_paged, octopus_attn_decode_paged_qjl
  *                                                  the same codec and attention over a paged cache
  *
  * Conventions
@@ -464,12 +465,43 @@ int octopus_attn_decode_paged_vq(const octopus_codebooks_t *cb,
                                  void *workspace, size_t workspace_bytes,
                                  void *stream);
 
+/* The 1-bit QJL residual (octopus_encode_qjl, octopus_attn_decode_qjl) in pages.
+ *   qjl_pool    device, 4-byte aligned: [n_pages][n_kv_heads] side-car tiles of 64 tokens, each laid out
+ *               as a tile of the contiguous side-car (octopus_qjl_bytes(cb, n_pages, n_kv_heads, 64) in all);
+ *               the tile of tokens 64 j .. 64 j + 63 of sequence s is that of page block_table[s][j].
+ * octopus_encode_qjl_paged: octopus_encode_paged that also writes the side-car (signs2 as for
+ * octopus_encode_qjl); codes and side-car are byte for byte those of octopus_encode_qjl.
+ * octopus_attn_decode_paged_qjl: octopus_attn_decode_paged with the corrected score of
+ * octopus_attn_decode_qjl (bf16 value pages; row groups as there).  EINVAL if signs2 or qjl_pool is NULL;
+ * other arguments, workspace and errors as octopus_encode_paged / octopus_attn_decode_paged. */
+int octopus_encode_qjl_paged(const octopus_codebooks_t *cb,
+                             const void *keys, int32_t key_dtype,
+                             int64_t stride_seq, int64_t stride_tok, int64_t stride_head,
+                             int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
+                             const uint8_t *signs, const uint8_t *signs2,
+                             void *k_pool, void *qjl_pool, int32_t n_pages,
+                             const int32_t *block_table, int32_t max_pages_per_seq,
+                             const int32_t *start_pos,
+                             void *stream);
+
+int octopus_attn_decode_paged_qjl(const octopus_codebooks_t *cb,
+                                  const void *q, int32_t q_dtype,
+                                  int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q,
+                                  const uint8_t *signs, const uint8_t *signs2,
+                                  const void *k_pool, const void *qjl_pool, const void *v_pool, int32_t n_pages,
+                                  const int32_t *block_table, int32_t max_pages_per_seq,
+                                  const int32_t *seq_lens, int64_t max_len,
+                                  float scale,
+                                  float *out,
+                                  void *workspace, size_t workspace_bytes,
+                                  void *stream);
+
 /* Static, human-readable name of an error code. */
 const char *octopus_strerror(int code);
 
 /* ---- measurement aids (not part of the method; nothing above depends on them) ----
  * octopus_profile_events: the next decode-attention call made by this thread (octopus_attn_decode, its _static,
- * _qjl, _vq and _hybrid forms, octopus_attn_decode_paged and its _hybrid and _vq forms) records the HIP events `before` and `after` (hipEvent_t
+ * _qjl, _vq and _hybrid forms, octopus_attn_decode_paged and its _hybrid, _vq and _qjl forms) records the HIP events `before` and `after` (hipEvent_t
  * passed as void*, caller-owned, created with timing enabled) on the call's stream immediately before and after
  * the launch of its fused decode kernel, i.e. around Alg. 2 proper without the query rotation and the split
  * merge.  The handles are per thread and are forgotten by that call whether it succeeds or not; NULL, NULL

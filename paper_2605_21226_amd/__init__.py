@@ -5,4 +5,5 @@ from .binding import (Codebooks, OctopusError, Plan, load, octopus_attn_decode, 
                       octopus_encode_values, octopus_attn_decode_vq, octopus_attn_decode_hybrid,
                       octopus_attn_decode_static, octopus_paged_pool_bytes, octopus_encode_paged,
                       octopus_attn_decode_paged, octopus_attn_decode_paged_hybrid, octopus_encode_values_paged,
-                      octopus_attn_decode_paged_vq, octopus_vq_on_matrix_cores)
+                      octopus_attn_decode_paged_vq, octopus_encode_qjl_paged, octopus_attn_decode_paged_qjl,
+                      octopus_vq_on_matrix_cores)

@@ -25,6 +25,7 @@ EXPORTS = ("octopus_build_codebooks", "octopus_build_codebooks_pair", "octopus_c
            "octopus_attn_decode_vq", "octopus_attn_decode_hybrid",
            "octopus_paged_pool_bytes", "octopus_encode_paged", "octopus_attn_decode_paged",
            "octopus_attn_decode_paged_hybrid", "octopus_encode_values_paged", "octopus_attn_decode_paged_vq",
+           "octopus_encode_qjl_paged", "octopus_attn_decode_paged_qjl",
            "octopus_attn_decode_static", "octopus_probe_read", "octopus_vq_on_matrix_cores")
 
 
@@ -129,6 +130,11 @@ def load():
     lib.octopus_attn_decode_paged_vq.argtypes = [CB, vp, i32, i32, i32, i32, i32, vp, vp, vp, i32, i32, i32, vp, i32, vp,
                                                  i64, f32, vp, vp, ctypes.c_size_t, vp]
     lib.octopus_attn_decode_paged_vq.restype = ctypes.c_int
+    lib.octopus_encode_qjl_paged.argtypes = [CB, vp, i32, i64, i64, i64, i32, i32, i32, vp, vp, vp, vp, i32, vp, i32, vp, vp]
+    lib.octopus_encode_qjl_paged.restype = ctypes.c_int
+    lib.octopus_attn_decode_paged_qjl.argtypes = [CB, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp, i32, vp,
+                                                  i64, f32, vp, vp, ctypes.c_size_t, vp]
+    lib.octopus_attn_decode_paged_qjl.restype = ctypes.c_int
     lib.octopus_vq_on_matrix_cores.argtypes = [ctypes.POINTER(Codebooks), i32, i32, i32, i32, i32]
     lib.octopus_vq_on_matrix_cores.restype = ctypes.c_int
     lib.octopus_probe_read.argtypes = [vp, ctypes.c_size_t, i32, i32, vp, vp]
@@ -416,6 +422,33 @@ def octopus_attn_decode_paged_vq(cb, q, signs, k_pool, vq_pool, v_bits, v_group,
                                                _ptr(seq_lens), int(max_len), float(scale), _ptr(out), _ptr(workspace),
                                                int(workspace.numel() * workspace.element_size()), _stream_ptr(stream))
     _check(code, "octopus_attn_decode_paged_vq")
+
+
+def octopus_encode_qjl_paged(cb, keys, signs, signs2, k_pool, qjl_pool, n_pages, block_table, start_pos=None,
+                             stream=None):
+    """octopus_encode_paged that also writes the QJL side-car into qjl_pool ([n_pages][n_kv_heads] side-car tiles)."""
+    assert keys.stride(-1) == 1 and block_table.is_contiguous()
+    n_seq, n_new, n_kv, _ = keys.shape
+    code = load().octopus_encode_qjl_paged(ctypes.byref(cb), _ptr(keys), _dtype_code(keys), keys.stride(0),
+                                           keys.stride(1), keys.stride(2), n_seq, n_kv, n_new, _ptr(signs), _ptr(signs2),
+                                           _ptr(k_pool), _ptr(qjl_pool), int(n_pages), _ptr(block_table),
+                                           int(block_table.shape[1]), _ptr(start_pos), _stream_ptr(stream))
+    _check(code, "octopus_encode_qjl_paged")
+
+
+def octopus_attn_decode_paged_qjl(cb, q, signs, signs2, k_pool, qjl_pool, v_pool, block_table, seq_lens, max_len, scale,
+                                  out, workspace, stream=None):
+    """octopus_attn_decode_paged with the QJL-corrected score; qjl_pool as octopus_encode_qjl_paged wrote it."""
+    assert q.is_contiguous() and v_pool.is_contiguous() and out.is_contiguous() and block_table.is_contiguous()
+    n_seq, n_q, n_qh, _ = q.shape
+    n_pages, n_kv = v_pool.shape[0], v_pool.shape[1]
+    assert block_table.shape[0] == n_seq and v_pool.shape[2] == 64 and _dtype_code(v_pool) == DTYPE_BF16
+    code = load().octopus_attn_decode_paged_qjl(ctypes.byref(cb), _ptr(q), _dtype_code(q), n_seq, n_qh, n_kv, n_q,
+                                                _ptr(signs), _ptr(signs2), _ptr(k_pool), _ptr(qjl_pool), _ptr(v_pool),
+                                                int(n_pages), _ptr(block_table), int(block_table.shape[1]),
+                                                _ptr(seq_lens), int(max_len), float(scale), _ptr(out), _ptr(workspace),
+                                                int(workspace.numel() * workspace.element_size()), _stream_ptr(stream))
+    _check(code, "octopus_attn_decode_paged_qjl")
 
 
 def octopus_profile_events(before, after):

@@ -16,8 +16,8 @@ LIB = os.environ.get("OCTOPUS_LIB_OUT", os.path.join(HERE, "liboctopus.so"))
 # the slowest (d = 256, then the matrix-core decode kernels) first
 SOURCES = []
 for _d in ("256", "128", "64"):
-    SOURCES += [_family + _d + ".hip" for _family in ("octopus_d", "octopus_paged_d", "octopus_scores_d", "octopus_vq_d", "octopus_valu_d",
-                                                      "octopus_qjl_d", "octopus_enc_d", "octopus_round_d")]
+    SOURCES += [_family + _d + ".hip" for _family in ("octopus_d", "octopus_paged_d", "octopus_paged_qjl_d", "octopus_scores_d", "octopus_vq_d",
+                                                      "octopus_valu_d", "octopus_qjl_d", "octopus_enc_d", "octopus_round_d")]
     SOURCES += ["octopus_vqm_d" + _d + "_b" + _b + ".hip" for _b in ("4", "3", "2")]
 SOURCES += ["octopus_sweep_dec_d128.hip", "octopus_sweep_enc_d128.hip", "octopus_common.hip", "octopus_values.hip",
             "octopus_host.cpp"]

@@ -34,7 +34,10 @@ bool plan_supported_d256(const octopus_plan_t &);
                                  void *);                                                                          \
     int launch_encode_paged_d##D(const octopus_codebooks_t &, const void *, int, int64_t, int64_t, int64_t,        \
                                  int32_t, int32_t, int32_t, const uint8_t *, void *, const PageTable &,            \
-                                 const int32_t *, void *);
+                                 const int32_t *, const uint8_t *, void *, void *);                                \
+    int launch_decode_paged_qjl_d##D(const octopus_codebooks_t &, const DecodeShape &, const float *, const void *, \
+                                     const void *, const float *, const void *, const PageTable &, const int32_t *, \
+                                     float *, float *, int32_t *, void *);
 OCTOPUS_DECL(64)
 OCTOPUS_DECL(128)
 OCTOPUS_DECL(256)
@@ -192,11 +195,22 @@ int launch_decode_paged(const octopus_codebooks_t &cb, const DecodeShape &s, con
 int launch_encode_paged(const octopus_codebooks_t &cb, const void *keys, int key_dtype, int64_t stride_seq,
                         int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
                         const uint8_t *signs, void *k_pool, const PageTable &pt, const int32_t *start_pos,
-                        void *stream) {
+                        void *stream, const uint8_t *signs2, void *qjl_pool) {
     switch (cb.plan.head_dim) {
-        case 64: return launch_encode_paged_d64(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs, k_pool, pt, start_pos, stream);
-        case 128: return launch_encode_paged_d128(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs, k_pool, pt, start_pos, stream);
-        case 256: return launch_encode_paged_d256(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs, k_pool, pt, start_pos, stream);
+        case 64: return launch_encode_paged_d64(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs, k_pool, pt, start_pos, signs2, qjl_pool, stream);
+        case 128: return launch_encode_paged_d128(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs, k_pool, pt, start_pos, signs2, qjl_pool, stream);
+        case 256: return launch_encode_paged_d256(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs, k_pool, pt, start_pos, signs2, qjl_pool, stream);
+        default: return static_cast<int>(hipErrorInvalidValue);
+    }
+}
+
+int launch_decode_paged_qjl(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *k_pool,
+                            const void *qjl_pool, const float *q2, const void *v_pool, const PageTable &pt,
+                            const int32_t *seq_lens, float *part_ml, float *part_acc, int32_t *work_plan, void *stream) {
+    switch (cb.plan.head_dim) {
+        case 64: return launch_decode_paged_qjl_d64(cb, s, q_rot, k_pool, qjl_pool, q2, v_pool, pt, seq_lens, part_ml, part_acc, work_plan, stream);
+        case 128: return launch_decode_paged_qjl_d128(cb, s, q_rot, k_pool, qjl_pool, q2, v_pool, pt, seq_lens, part_ml, part_acc, work_plan, stream);
+        case 256: return launch_decode_paged_qjl_d256(cb, s, q_rot, k_pool, qjl_pool, q2, v_pool, pt, seq_lens, part_ml, part_acc, work_plan, stream);
         default: return static_cast<int>(hipErrorInvalidValue);
     }
 }

@@ -902,6 +902,17 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
             sc[k][QW] = *reinterpret_cast<const uint16_t *>(src + QW * (kWave * 4) + lane * 2);
         }
     };
+    // PAGED: the side-car is a pool of [page][KV head] tiles like the keys'; slot = page * n_kv_heads + KV head
+    auto load_sidecar_at = [&](const int64_t (&slot)[KPL], uint32_t (&sc)[KPL][QW + 1]) {
+#pragma unroll
+        for (int k = 0; k < KPL; ++k) {
+            const char *src = j_region + slot[k] * TQ;
+#pragma unroll
+            for (int wq = 0; wq < QW; ++wq)
+                sc[k][wq] = *reinterpret_cast<const uint32_t *>(src + wq * (kWave * 4) + lane * 4);
+            sc[k][QW] = *reinterpret_cast<const uint16_t *>(src + QW * (kWave * 4) + lane * 2);
+        }
+    };
     // Sum over the d / 8 sign bytes of a key of the table rows they select: q2 . sigma per query row.
     auto qjl_dot = [&](const uint32_t (&sc)[QW + 1], float (&corr)[RG]) {
 #pragma unroll
@@ -1036,12 +1047,13 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
         }
         if constexpr (PAGED) {
             load_records_at(slot_nxt, w_next);
+            if constexpr (QJL) load_sidecar_at(slot_nxt, sc_next);
 #pragma unroll
             for (int k = 0; k < KPL; ++k) slot_cur[k] = slot_nxt[k];
         } else {
             load_records(step_nx, w_next);
+            if constexpr (QJL) load_sidecar(min(step + ww.step_stride, ww.step_last), sc_next);
         }
-        if constexpr (QJL) load_sidecar(min(step + ww.step_stride, ww.step_last), sc_next);
         // The loads above feed the NEXT step, which sits behind a branch in the unrolled loop; without this
         // barrier the compiler sinks them into that branch, i.e. to the top of the step that uses them, and
         // every second step waits for a full memory round trip.
@@ -1163,7 +1175,7 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
                     qtab[(pos * 256 + tid) * RG + r] = t;
                 }
             __syncthreads();
-            j_region = reinterpret_cast<const char *>(qjl) + ww.pair * (shp.t_capacity / kWave) * TQ;
+            j_region = reinterpret_cast<const char *>(qjl) + (PAGED ? 0 : ww.pair * (shp.t_capacity / kWave) * TQ);
         }
         // Addresses are a wave-uniform base (scalar registers) plus a small per-lane byte offset.
         if constexpr (PAGED) {
@@ -1196,10 +1208,11 @@ __global__ __launch_bounds__(kDecodeWaves *kWave) __attribute__((amdgpu_waves_pe
                 page_ids(min(ww.step_begin + ww.step_stride, ww.step_last), page_nxt);
                 page_slots(page_first, slot_cur);
                 load_records_at(slot_cur, w_a);
+                if constexpr (QJL) load_sidecar_at(slot_cur, sc_a);
             } else {
                 load_records(ww.step_begin, w_a);
+                if constexpr (QJL) load_sidecar(ww.step_begin, sc_a);
             }
-            if constexpr (QJL) load_sidecar(ww.step_begin, sc_a);
         }
         if constexpr (AHEAD) {
             // The first step's P.V pieces multiply zeros (by whatever probabilities the previous item left in
@@ -1577,6 +1590,38 @@ int launch_decode_paged_plan(const octopus_codebooks_t &cb, const DecodeShape &s
         case 2: return launch_decode_paged_rg<P, 2>(cb, s, q_rot, k_pool, v_pool, pt, seq_lens, part_ml, part_acc, plan, stream);
         case 4: return launch_decode_paged_rg<P, 4>(cb, s, q_rot, k_pool, v_pool, pt, seq_lens, part_ml, part_acc, plan, stream);
         case 8: return launch_decode_paged_rg<P, 8>(cb, s, q_rot, k_pool, v_pool, pt, seq_lens, part_ml, part_acc, plan, stream);
+        default: return static_cast<int>(hipErrorInvalidValue);
+    }
+}
+
+// Paged pools with the QJL side-car in pages as well (a pool of [page][KV head] side-car tiles).
+template <class P, int RG>
+int launch_decode_paged_qjl_rg(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot,
+                               const void *k_pool, const void *qjl_pool, const float *q2, const void *v_pool,
+                               const PageTable &pt, const int32_t *seq_lens, float *part_ml, float *part_acc,
+                               int32_t *plan, hipStream_t stream) {
+    if constexpr (qjl_fits<P, RG>()) {
+        const DeviceBooks books = device_books(cb);
+        hipLaunchKernelGGL((decode_kernel_mfma<P, RG, true, true, true>), dim3(kDecodeWorkgroups),
+                           dim3(kDecodeWaves * kWave), 0, stream, books, s, q_rot, static_cast<const uint4 *>(k_pool),
+                           static_cast<const uint32_t *>(v_pool), seq_lens, part_ml, part_acc, nullptr, plan,
+                           static_cast<const unsigned char *>(qjl_pool), q2, pt.table, pt.stride, pt.n_pages);
+        return static_cast<int>(hipGetLastError());
+    } else {
+        return static_cast<int>(hipErrorInvalidValue);
+    }
+}
+
+template <class P>
+int launch_decode_paged_qjl_plan(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot,
+                                 const void *k_pool, const void *qjl_pool, const float *q2, const void *v_pool,
+                                 const PageTable &pt, const int32_t *seq_lens, float *part_ml, float *part_acc,
+                                 int32_t *plan, hipStream_t stream) {
+    switch (s.rows_per_pass) {
+        case 1: return launch_decode_paged_qjl_rg<P, 1>(cb, s, q_rot, k_pool, qjl_pool, q2, v_pool, pt, seq_lens, part_ml, part_acc, plan, stream);
+        case 2: return launch_decode_paged_qjl_rg<P, 2>(cb, s, q_rot, k_pool, qjl_pool, q2, v_pool, pt, seq_lens, part_ml, part_acc, plan, stream);
+        case 4: return launch_decode_paged_qjl_rg<P, 4>(cb, s, q_rot, k_pool, qjl_pool, q2, v_pool, pt, seq_lens, part_ml, part_acc, plan, stream);
+        case 8: return launch_decode_paged_qjl_rg<P, 8>(cb, s, q_rot, k_pool, qjl_pool, q2, v_pool, pt, seq_lens, part_ml, part_acc, plan, stream);
         default: return static_cast<int>(hipErrorInvalidValue);
     }
 }

@@ -557,6 +557,10 @@ void encode_kernel(DeviceBooks books, const void *__restrict__ keys,
             __syncthreads();
             constexpr int TQ = kWave * (D / 8 + 2);   // side-car bytes per tile
             unsigned char *qt = qjl + ((static_cast<int64_t>(seq) * n_kv_heads + kvh) * (t_capacity / kWave) + tile) * TQ;
+            if (pt.table != nullptr) {   // the side-car in pages: a pool of [page][KV head] tiles, like the keys'
+                const int page = pt.table[static_cast<int64_t>(seq) * pt.stride + tile];
+                qt = qjl + (static_cast<int64_t>(min(max(page, 0), pt.n_pages - 1)) * n_kv_heads + kvh) * TQ;
+            }
             const int64_t tok = tile * kWave + lane;
             const bool valid = tok >= tok_lo && tok < tok_hi;
             for (int wd = wave; wd < D / 32; wd += NWV) {

@@ -781,11 +781,13 @@ static bool page_table_ok(const void *pool, int32_t n_pages, const int32_t *bloc
            max_pages_per_seq <= (INT32_MAX / OCTOPUS_TILE) && aligned(pool, 16) && aligned(block_table, 4);
 }
 
-int octopus_encode_paged(const octopus_codebooks_t *cb, const void *keys, int32_t key_dtype, int64_t stride_seq,
-                         int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
-                         const uint8_t *signs, void *k_pool, int32_t n_pages, const int32_t *block_table,
-                         int32_t max_pages_per_seq, const int32_t *start_pos, void *stream) {
+static int encode_paged(const octopus_codebooks_t *cb, const void *keys, int32_t key_dtype, int64_t stride_seq,
+                        int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
+                        const uint8_t *signs, void *k_pool, int32_t n_pages, const int32_t *block_table,
+                        int32_t max_pages_per_seq, const int32_t *start_pos, void *stream, const uint8_t *signs2,
+                        void *qjl_pool) {
     if (cb == nullptr || keys == nullptr || signs == nullptr) return OCTOPUS_EINVAL;
+    if (qjl_pool != nullptr && !aligned(qjl_pool, 4)) return OCTOPUS_EINVAL;
     if (!page_table_ok(k_pool, n_pages, block_table, max_pages_per_seq)) return OCTOPUS_EINVAL;
     if (n_seq < 1 || n_kv_heads < 1 || n_new < 0) return OCTOPUS_EINVAL;
     if (n_seq > 65535 || n_kv_heads > 65535) return OCTOPUS_EINVAL;   // they are grid dimensions of the launch
@@ -800,8 +802,26 @@ int octopus_encode_paged(const octopus_codebooks_t *cb, const void *keys, int32_
     if (n_new == 0) return OCTOPUS_OK;
     const PageTable pt{block_table, max_pages_per_seq, n_pages};
     const int err = launch_encode_paged(*cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads,
-                                        n_new, signs, k_pool, pt, start_pos, stream);
+                                        n_new, signs, k_pool, pt, start_pos, stream, signs2, qjl_pool);
     return err == 0 ? OCTOPUS_OK : OCTOPUS_EHIP;
+}
+
+int octopus_encode_paged(const octopus_codebooks_t *cb, const void *keys, int32_t key_dtype, int64_t stride_seq,
+                         int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
+                         const uint8_t *signs, void *k_pool, int32_t n_pages, const int32_t *block_table,
+                         int32_t max_pages_per_seq, const int32_t *start_pos, void *stream) {
+    return encode_paged(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs, k_pool,
+                        n_pages, block_table, max_pages_per_seq, start_pos, stream, nullptr, nullptr);
+}
+
+int octopus_encode_qjl_paged(const octopus_codebooks_t *cb, const void *keys, int32_t key_dtype, int64_t stride_seq,
+                             int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
+                             const uint8_t *signs, const uint8_t *signs2, void *k_pool, void *qjl_pool, int32_t n_pages,
+                             const int32_t *block_table, int32_t max_pages_per_seq, const int32_t *start_pos,
+                             void *stream) {
+    if (signs2 == nullptr || qjl_pool == nullptr) return OCTOPUS_EINVAL;
+    return encode_paged(cb, keys, key_dtype, stride_seq, stride_tok, stride_head, n_seq, n_kv_heads, n_new, signs, k_pool,
+                        n_pages, block_table, max_pages_per_seq, start_pos, stream, signs2, qjl_pool);
 }
 
 static int attn_decode_paged(const octopus_codebooks_t *cb, const void *q, int32_t q_dtype, int32_t n_seq,
@@ -809,8 +829,11 @@ static int attn_decode_paged(const octopus_codebooks_t *cb, const void *q, int32
                              const void *k_pool, const void *v_pool, int32_t n_pages, const int32_t *block_table,
                              int32_t max_pages_per_seq, const int32_t *seq_lens, int64_t max_len, float scale,
                              float *out, void *workspace, size_t workspace_bytes, void *stream, const WindowArgs *win,
-                             int32_t v_bits = 0, int32_t v_group = 0) {
+                             int32_t v_bits = 0, int32_t v_group = 0, const uint8_t *signs2 = nullptr,
+                             const void *qjl_pool = nullptr) {
     // v_bits > 0: v_pool holds group-quantised rows (the matrix-core kernel over them; no window)
+    // qjl_pool: the QJL side-car in pages, scores corrected as in octopus_attn_decode_qjl (bf16 values, no window)
+    const bool with_qjl = qjl_pool != nullptr;
     void *ev_before = g_event_before, *ev_after = g_event_after;
     g_event_before = g_event_after = nullptr;
     const int ok = decode_args_ok(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len);
@@ -831,6 +854,9 @@ static int attn_decode_paged(const octopus_codebooks_t *cb, const void *q, int32
         if (win->k_dtype != OCTOPUS_DTYPE_F32 && win->k_dtype != OCTOPUS_DTYPE_BF16) return OCTOPUS_EUNSUPPORTED;
         if (!aligned(win->k_window, 16)) return OCTOPUS_EINVAL;
     }
+    if (with_qjl && (signs2 == nullptr || !aligned(qjl_pool, 4))) return OCTOPUS_EINVAL;
+    const int rows_cap = with_qjl ? qjl_rows_cap(cb->plan) : 8;
+    if (rows_cap <= 0) return OCTOPUS_EUNSUPPORTED;
     int32_t vq_waves = 0;
     if (v_bits != 0) {
         if (!vq_params_ok(cb->plan.head_dim, v_bits, v_group)) return OCTOPUS_EUNSUPPORTED;
@@ -838,7 +864,8 @@ static int attn_decode_paged(const octopus_codebooks_t *cb, const void *q, int32
         vq_waves = vq_mfma_available(cb->plan, vq_mfma_rows(n_q * (n_q_heads / n_kv_heads)), v_bits, v_group);
         if (vq_waves <= 0) return OCTOPUS_EUNSUPPORTED;
     }
-    const DecodeShape s = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, reach, false, 8, vq_waves);
+    const DecodeShape s = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, reach, false, rows_cap,
+                                            vq_waves);
     const Workspace w = make_workspace(cb->plan, s);
     const size_t required = std::max(w.total, octopus_attn_decode_workspace(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len));
     if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < required) return OCTOPUS_EWORKSPACE;
@@ -847,14 +874,18 @@ static int attn_decode_paged(const octopus_codebooks_t *cb, const void *q, int32
     float *part_ml = reinterpret_cast<float *>(base + w.part_ml_off);
     float *part_acc = reinterpret_cast<float *>(base + w.part_acc_off);
     int32_t *work_plan = reinterpret_cast<int32_t *>(base + w.plan_off);
+    float *q2 = with_qjl ? reinterpret_cast<float *>(base + w.q2_off) : nullptr;
     const PageTable pt{block_table, max_pages_per_seq, n_pages};
-    int err = launch_rotate_queries(cb->plan, q, q_dtype, signs, s, scale, q_rot, seq_lens, work_plan, nullptr, nullptr,
-                                    stream);
+    int err = launch_rotate_queries(cb->plan, q, q_dtype, signs, s, scale, q_rot, seq_lens, work_plan,
+                                    with_qjl ? signs2 : nullptr, q2, stream);
     if (err == 0 && ev_before != nullptr) err = record_event(ev_before, stream);
     if (err == 0) {
         if (v_bits != 0)
             err = launch_decode_vq(*cb, s, q_rot, k_pool, v_pool, v_bits, v_group, seq_lens, part_ml, part_acc, nullptr,
                                    work_plan, stream, pt);
+        else if (with_qjl)
+            err = launch_decode_paged_qjl(*cb, s, q_rot, k_pool, qjl_pool, q2, v_pool, pt, seq_lens, part_ml, part_acc,
+                                          work_plan, stream);
         else
             err = launch_decode_paged(*cb, s, q_rot, k_pool, v_pool, pt, seq_lens, part_ml, part_acc, work_plan, stream);
     }
@@ -919,6 +950,18 @@ int octopus_attn_decode_paged_vq(const octopus_codebooks_t *cb, const void *q, i
     return attn_decode_paged(cb, q, q_dtype, n_seq, n_q_heads, n_kv_heads, n_q, signs, k_pool, vq_pool, n_pages,
                              block_table, max_pages_per_seq, seq_lens, max_len, scale, out, workspace, workspace_bytes,
                              stream, nullptr, v_bits, v_group);
+}
+
+int octopus_attn_decode_paged_qjl(const octopus_codebooks_t *cb, const void *q, int32_t q_dtype, int32_t n_seq,
+                                  int32_t n_q_heads, int32_t n_kv_heads, int32_t n_q, const uint8_t *signs,
+                                  const uint8_t *signs2, const void *k_pool, const void *qjl_pool, const void *v_pool,
+                                  int32_t n_pages, const int32_t *block_table, int32_t max_pages_per_seq,
+                                  const int32_t *seq_lens, int64_t max_len, float scale, float *out, void *workspace,
+                                  size_t workspace_bytes, void *stream) {
+    if (signs2 == nullptr || qjl_pool == nullptr) return OCTOPUS_EINVAL;
+    return attn_decode_paged(cb, q, q_dtype, n_seq, n_q_heads, n_kv_heads, n_q, signs, k_pool, v_pool, n_pages,
+                             block_table, max_pages_per_seq, seq_lens, max_len, scale, out, workspace, workspace_bytes,
+                             stream, nullptr, 0, 0, signs2, qjl_pool);
 }
 
 const char *octopus_strerror(int code) {

@@ -103,10 +103,14 @@ int launch_encode(const octopus_codebooks_t &cb, const void *keys, int key_dtype
 int launch_encode_paged(const octopus_codebooks_t &cb, const void *keys, int key_dtype, int64_t stride_seq,
                         int64_t stride_tok, int64_t stride_head, int32_t n_seq, int32_t n_kv_heads, int32_t n_new,
                         const uint8_t *signs, void *k_pool, const PageTable &pt, const int32_t *start_pos,
-                        void *stream);
+                        void *stream, const uint8_t *signs2 = nullptr, void *qjl_pool = nullptr);   // qjl_pool: side-car pages
 int launch_decode_paged(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *k_pool,
                         const void *v_pool, const PageTable &pt, const int32_t *seq_lens, float *part_ml,
                         float *part_acc, int32_t *work_plan, void *stream);
+// ... with the QJL side-car in pages as well ([page][KV head] side-car tiles), q2 as for launch_decode_qjl
+int launch_decode_paged_qjl(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *k_pool,
+                            const void *qjl_pool, const float *q2, const void *v_pool, const PageTable &pt,
+                            const int32_t *seq_lens, float *part_ml, float *part_acc, int32_t *work_plan, void *stream);
 
 // The encoder with one of the rounding modes of App. E (OCTOPUS_ROUND_*), no side-car.
 int launch_encode_rounding(const octopus_codebooks_t &cb, const void *keys, int key_dtype, int64_t stride_seq,

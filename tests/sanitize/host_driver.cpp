@@ -23,7 +23,9 @@ int launch_window(const octopus_plan_t &, const DecodeShape &, const void *, int
 int launch_encode(const octopus_codebooks_t &, const void *, int, int64_t, int64_t, int64_t, int32_t, int32_t, int32_t,
                   const uint8_t *, void *, int64_t, const int32_t *, const uint8_t *, void *, void *) { ++g_launches; return 0; }
 int launch_encode_paged(const octopus_codebooks_t &, const void *, int, int64_t, int64_t, int64_t, int32_t, int32_t,
-                        int32_t, const uint8_t *, void *, const PageTable &, const int32_t *, void *) { ++g_launches; return 0; }
+                        int32_t, const uint8_t *, void *, const PageTable &, const int32_t *, void *, const uint8_t *, void *) { ++g_launches; return 0; }
+int launch_decode_paged_qjl(const octopus_codebooks_t &, const DecodeShape &, const float *, const void *, const void *,
+                            const float *, const void *, const PageTable &, const int32_t *, float *, float *, int32_t *, void *) { ++g_launches; return 0; }
 int launch_decode_paged(const octopus_codebooks_t &, const DecodeShape &, const float *, const void *, const void *,
                         const PageTable &, const int32_t *, float *, float *, int32_t *, void *) { ++g_launches; return 0; }
 int launch_encode_rounding(const octopus_codebooks_t &, const void *, int, int64_t, int64_t, int64_t, int32_t, int32_t,

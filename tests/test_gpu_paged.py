@@ -406,3 +406,131 @@ def test_paged_decode_over_quantised_value_pages_long_sequence_and_refusals():
     with pytest.raises(binding.OctopusError) as err:
         binding.octopus_attn_decode_paged_vq(cb, q, signs, pool, vq_pool, 3, 16, 8, table, lens, 200, 0.1, out, ws)
     assert err.value.code == binding.EUNSUPPORTED
+
+
+# ---- the 1-bit QJL residual in pages ------------------------------------------------------------------------------
+def qjl_pool_from_logical(side_img, table, n_pages, n_seq, n_kv, cap, d, fill=0x3C):
+    """contiguous side-car image (bytes, [n_seq][n_kv][cap / 64] tiles) -> pool [n_pages][n_kv] tiles"""
+    tq = 64 * (d // 8 + 2)
+    tiles = np.asarray(side_img, dtype=np.uint8).reshape(n_seq, n_kv, cap // 64, tq)
+    pool = np.full((n_pages, n_kv, tq), fill, dtype=np.uint8)
+    for s in range(n_seq):
+        for j in range(cap // 64):
+            pool[table[s, j]] = tiles[s, :, j]
+    return pool
+
+
+@pytest.mark.parametrize("d,bits,dtype", [(128, 3, "bf16"), (64, 2, "fp32"), (256, 2.5, "bf16")])
+def test_paged_encode_qjl_writes_the_contiguous_encoders_bytes_into_pages(d, bits, dtype):
+    """Records and side-car tiles written through the page table are byte for byte those octopus_encode_qjl writes
+    into a contiguous cache (whose parity with the oracle test_gpu_qjl.py covers); other pages stay as they were."""
+    from test_gpu_qjl import gpu_encode_qjl
+    n_seq, n_kv, n_tok, cap = 2, 2, 150, 256
+    max_pages = cap // 64
+    cb = binding.octopus_build_codebooks(d, bits)
+    rng = np.random.default_rng(50 + d)
+    keys, _, signs = make_inputs(51 + d, n_seq, n_kv, n_tok, d, dtype)
+    signs2 = synth.sign_vectors(52 + d, n_kv, d)
+    start = [0, 70]
+    _, _, _, cache, side = gpu_encode_qjl(cb, keys, dtype, signs, signs2, cap, start_pos=start)
+    n_pages = n_seq * max_pages + 3
+    table = random_table(rng, n_seq, max_pages, n_pages)
+    tb, tq = cb.plan.granules * 64 * 16, 64 * (d // 8 + 2)
+    k_pool = torch.full((n_pages * n_kv * tb,), 0xAB, dtype=torch.uint8, device=DEV)
+    q_pool = torch.full((n_pages * n_kv * tq,), 0xCD, dtype=torch.uint8, device=DEV)
+    assert q_pool.numel() == binding.octopus_qjl_bytes(cb, n_pages, n_kv, 64)
+    binding.octopus_encode_qjl_paged(cb, to_dev(keys, dtype), sign_bits_dev(signs), sign_bits_dev(signs2), k_pool, q_pool,
+                                     n_pages, torch.from_numpy(table).to(DEV),
+                                     torch.tensor(start, dtype=torch.int32, device=DEV))
+    torch.cuda.synchronize()
+    kp = k_pool.cpu().numpy().reshape(n_pages, n_kv, tb)
+    qp = q_pool.cpu().numpy().reshape(n_pages, n_kv, tq)
+    kc = cache.cpu().numpy().reshape(n_seq, n_kv, max_pages, tb)
+    qc = side.cpu().numpy().reshape(n_seq, n_kv, max_pages, tq)
+    used = set()
+    for s in range(n_seq):
+        first, last = start[s] // 64, (start[s] + n_tok - 1) // 64
+        for j in range(first, last + 1):
+            used.add(int(table[s, j]))
+            # a tile written in part keeps the pool's fill where the contiguous cache keeps its zeros: compare the
+            # slots of the tokens written
+            lo, hi = max(start[s], 64 * j) - 64 * j, min(start[s] + n_tok, 64 * j + 64) - 64 * j
+            for h in range(n_kv):
+                kt = kp[table[s, j], h].reshape(cb.plan.granules, 64, 16)
+                kr = kc[s, h, j].reshape(cb.plan.granules, 64, 16)
+                assert np.array_equal(kt[:, lo:hi], kr[:, lo:hi]), (s, h, j)
+                nw = d // 32
+                wt = qp[table[s, j], h, :nw * 256].reshape(nw, 64, 4)
+                wr = qc[s, h, j, :nw * 256].reshape(nw, 64, 4)
+                assert np.array_equal(wt[:, lo:hi], wr[:, lo:hi]), (s, h, j)
+                gt = qp[table[s, j], h, nw * 256:].reshape(64, 2)
+                gr = qc[s, h, j, nw * 256:].reshape(64, 2)
+                assert np.array_equal(gt[lo:hi], gr[lo:hi]), (s, h, j)
+    for pg in range(n_pages):
+        if pg not in used:
+            assert np.all(kp[pg] == 0xAB) and np.all(qp[pg] == 0xCD)
+
+
+def run_paged_qjl_decode_case(d, bits, n_seq, n_qh, n_kv, n_q, lens, seed, spare_pages=3):
+    """octopus_attn_decode_paged_qjl over the oracle's records and side-car scattered over pages, against the
+    oracle's corrected attention."""
+    cb = binding.octopus_build_codebooks(d, bits)
+    plan = oracle.make_plan(d, bits)
+    rng = np.random.default_rng(seed)
+    T = max(int(max(lens)), 1)
+    cap = -(-T // 64) * 64
+    max_pages = cap // 64
+    n_pages = n_seq * max_pages + spare_pages
+    keys, vals, signs = make_inputs(seed, n_seq, n_kv, T, d, "bf16")
+    signs2 = synth.sign_vectors(seed + 1000, n_kv, d)
+    records = np.zeros((n_seq, n_kv, cap, plan.record_bytes), dtype=np.uint8)
+    sigma = np.zeros((n_seq, n_kv, T, d), dtype=np.int8)
+    gamma_r = np.zeros((n_seq, n_kv, T), dtype=np.float64)
+    for s in range(n_seq):
+        for h in range(n_kv):
+            k = keys[s, :, h].astype(np.float64)
+            records[s, h, :T] = oracle.encode(plan, k, signs[h])
+            sigma[s, h], gamma_r[s, h] = oracle.qjl_encode(plan, k, signs[h], signs2[h], records[s, h, :T])
+    q = synth.queries(seed, synth.Workload("t", n_seq, n_qh, n_kv, d, T, bits, "bf16", n_q=n_q))
+    v = np.zeros((n_seq, n_kv, cap, d), dtype=np.float32)
+    v[:, :, :T] = vals
+    table = random_table(rng, n_seq, max_pages, n_pages)
+    k_pool, v_pool = pools_from_logical(cb, records, v, table, n_pages, cap)
+    sbits = np.packbits((sigma < 0).astype(np.uint8), axis=-1, bitorder="little")
+    side = layout.qjl_from_canonical(sbits, gamma_r.astype(np.float16), cap)
+    q_pool = qjl_pool_from_logical(side, table, n_pages, n_seq, n_kv, cap, d)
+    scale = 1.0 / np.sqrt(d)
+    ws = torch.empty(binding.octopus_attn_decode_workspace(cb, n_seq, n_qh, n_kv, n_q, T), dtype=torch.uint8, device=DEV)
+    out = torch.full((n_seq, n_q, n_qh, d), float("nan"), dtype=torch.float32, device=DEV)
+    binding.octopus_attn_decode_paged_qjl(cb, to_dev(q, "bf16"), sign_bits_dev(signs), sign_bits_dev(signs2),
+                                          torch.from_numpy(k_pool).to(DEV), torch.from_numpy(q_pool.reshape(-1)).to(DEV),
+                                          to_dev(v_pool, "bf16"), torch.from_numpy(table).to(DEV),
+                                          torch.tensor(np.asarray(lens), dtype=torch.int32, device=DEV), T, scale, out, ws)
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    g = n_qh // n_kv
+    worst = 0.0
+    for s in range(n_seq):
+        L = int(lens[s])
+        for h in range(n_kv):
+            if L == 0:
+                assert np.all(out[s, :, h * g:(h + 1) * g] == 0.0)
+                continue
+            qq = q[s, :, h * g:(h + 1) * g, :].reshape(-1, d).astype(np.float64)
+            _, ref_o = oracle.attention_qjl(plan, records[s, h, :L], signs[h], signs2[h], sigma[s, h, :L],
+                                            gamma_r[s, h, :L], qq, v[s, h, :L].astype(np.float64), scale)
+            ref_o = ref_o.reshape(n_q, g, d)
+            for qi in range(n_q):
+                for j in range(g):
+                    worst = max(worst, check_out(out[s, qi, h * g + j], ref_o[qi, j]))
+    print(f"[paged attn-qjl] d={d} b={bits} lens={list(lens)}: worst out err {worst:.3g}")
+
+
+@pytest.mark.parametrize("bits", [1, 1.5, 2, 2.5, 3, 4])
+def test_paged_decode_qjl_gqa_ragged_d128(bits):
+    run_paged_qjl_decode_case(128, bits, 3, 8, 2, 1, [0, 77, 1000], seed=int(1900 + 10 * bits))
+
+
+def test_paged_decode_qjl_other_head_dims_and_several_queries():
+    run_paged_qjl_decode_case(64, 2, 1, 3, 3, 5, [700], seed=1931)
+    run_paged_qjl_decode_case(256, 4, 2, 4, 2, 1, [513, 64], seed=1932)

@@ -296,6 +296,24 @@ def test_paged_cache_sizes_and_argument_checks(lib):
     assert hyb(*hargs(k_pool=null)) == binding.EINVAL
     assert hyb(*hargs(max_len=4097)) == binding.EINVAL
     assert hyb(*hargs(ws_bytes=ws - 1)) == binding.EWORKSPACE
+    pq = lib.octopus_attn_decode_paged_qjl
+    qargs = lambda **k: [ctypes.byref(cb), fake, 1, 2, 32, 8, 1, fake, k.get("signs2", fake), k.get("k_pool", fake),
+                         k.get("qjl_pool", fake), fake, 128, k.get("table", fake), 64, fake, k.get("max_len", 4096),
+                         ctypes.c_float(0.1), fake, ctypes.c_void_p(0x10000), k.get("ws_bytes", ws), null]
+    assert pq(*qargs(signs2=null)) == binding.EINVAL
+    assert pq(*qargs(qjl_pool=null)) == binding.EINVAL
+    assert pq(*qargs(qjl_pool=ctypes.c_void_p(0x1002))) == binding.EINVAL
+    assert pq(*qargs(table=null)) == binding.EINVAL
+    assert pq(*qargs(max_len=4097)) == binding.EINVAL
+    assert pq(*qargs(ws_bytes=ws - 1)) == binding.EWORKSPACE
+    eq = lib.octopus_encode_qjl_paged
+    qeargs = lambda **k: [ctypes.byref(cb), fake, 1, 8 * 1024, 1024, 128, 2, 8, k.get("n_new", 64), fake,
+                          k.get("signs2", fake), fake, k.get("qjl_pool", fake), k.get("n_pages", 128), fake, 4, null, null]
+    assert eq(*qeargs(signs2=null)) == binding.EINVAL
+    assert eq(*qeargs(qjl_pool=null)) == binding.EINVAL
+    assert eq(*qeargs(n_pages=0)) == binding.EINVAL
+    assert eq(*qeargs(n_new=257)) == binding.EINVAL
+    assert eq(*qeargs(n_new=0)) == binding.OK
     pvq = lib.octopus_attn_decode_paged_vq
     vargs = lambda **k: [ctypes.byref(cb), fake, 1, 2, 32, 8, 1, fake, k.get("k_pool", fake), k.get("vq_pool", fake),
                          k.get("bits", 3), k.get("group", 32), 128, k.get("table", fake), 64, fake, k.get("max_len", 4096),
