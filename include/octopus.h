@@ -381,10 +381,10 @@ int octopus_attn_decode_vq(const octopus_codebooks_t *cb,
  * octopus_encode_paged: arguments as octopus_encode with (cache, t_capacity) replaced by the pool and
  * the table; a sequence can hold max_pages_per_seq * 64 tokens, tokens past that are dropped.
  * octopus_attn_decode_paged: arguments as octopus_attn_decode (bf16 values only, no scores_out);
- * max_len <= max_pages_per_seq * 64; query rows are served in groups of at most 8 per KV head; 32 or more
- * query rows per KV head (n_q * n_q_heads / n_kv_heads) are refused with EUNSUPPORTED, because the many-row
- * kernel is not built for pages.  Workspace: octopus_attn_decode_workspace of the same
- * shapes.  Errors: EINVAL for NULL / misaligned pointers, n_pages < 1, max_pages_per_seq < 1 and the
+ * max_len <= max_pages_per_seq * 64; query rows are served in groups of at most 8 per KV head, 32 or more
+ * query rows per KV head (n_q * n_q_heads / n_kv_heads) by the many-row kernel up to head_dim 128 and refused
+ * with EUNSUPPORTED at head_dim 256 (as hundreds of row groups each would read the keys again).
+ * Workspace: octopus_attn_decode_workspace of the same shapes.  Errors: EINVAL for NULL / misaligned pointers, n_pages < 1, max_pages_per_seq < 1 and the
  * conditions of the contiguous calls; EUNSUPPORTED / EWORKSPACE / EHIP as there. */
 size_t octopus_paged_pool_bytes(const octopus_codebooks_t *cb, int32_t n_pages, int32_t n_kv_heads);
 
@@ -442,7 +442,8 @@ int octopus_attn_decode_paged_hybrid(const octopus_codebooks_t *cb,
  * octopus_attn_decode_paged_vq: octopus_attn_decode_paged over such a pool instead of bf16 value pages
  * (v_bits, v_group as for octopus_attn_decode_vq).  Served by the matrix-core kernel only: shapes it is not
  * built for (octopus_vq_on_matrix_cores(...) == 0) are refused with EUNSUPPORTED, as are 32 or more query
- * rows per KV head.  Other arguments, workspace and errors as octopus_attn_decode_paged. */
+ * rows per KV head (with quantised values or the QJL side-car over pages).  Other arguments, workspace and
+ * errors as octopus_attn_decode_paged. */
 int octopus_encode_values_paged(const void *v, int32_t v_dtype,
                                 int64_t stride_seq, int64_t stride_tok, int64_t stride_head,
                                 int32_t n_seq, int32_t n_kv_heads, int32_t n_new,

@@ -1552,7 +1552,8 @@ __global__ __launch_bounds__(kWave) void merge_kernel(DecodeShape shp, const flo
 // ---- launch helpers -----------------------------------------------------------------------------
 template <class P>
 int launch_decode_mq(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
-                     const void *v, const int32_t *seq_lens, float *part_ml, float *part_acc, hipStream_t stream);
+                     const void *v, const int32_t *seq_lens, float *part_ml, float *part_acc, hipStream_t stream,
+                     PageTable pt = PageTable{nullptr, 0, 0});   // pt: cache and v are pools of pages
 
 // bf16 values: the matrix-core kernels.  SCORES: the instantiation that also writes the scores (built in
 // a translation unit of its own).
@@ -1590,6 +1591,10 @@ int launch_decode_paged_plan(const octopus_codebooks_t &cb, const DecodeShape &s
         case 2: return launch_decode_paged_rg<P, 2>(cb, s, q_rot, k_pool, v_pool, pt, seq_lens, part_ml, part_acc, plan, stream);
         case 4: return launch_decode_paged_rg<P, 4>(cb, s, q_rot, k_pool, v_pool, pt, seq_lens, part_ml, part_acc, plan, stream);
         case 8: return launch_decode_paged_rg<P, 8>(cb, s, q_rot, k_pool, v_pool, pt, seq_lens, part_ml, part_acc, plan, stream);
+        case 128:
+        case 256:   // the many-row kernel (d <= 128), which takes the page table as an argument
+            if constexpr (P::D <= 128) return launch_decode_mq<P>(cb, s, q_rot, k_pool, v_pool, seq_lens, part_ml, part_acc, stream, pt);
+            return static_cast<int>(hipErrorInvalidValue);
         default: return static_cast<int>(hipErrorInvalidValue);
     }
 }

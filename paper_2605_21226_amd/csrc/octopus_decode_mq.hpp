@@ -52,7 +52,10 @@ __global__ __launch_bounds__(kWave *NW) __attribute__((amdgpu_waves_per_eu(P::D 
                                                          const uint4 *__restrict__ cache,
                                                          const uint16_t *__restrict__ v,
                                                          const int32_t *__restrict__ seq_lens,
-                                                         float *__restrict__ part_ml, float *__restrict__ part_acc) {
+                                                         float *__restrict__ part_ml, float *__restrict__ part_acc,
+                                                         PageTable pt) {
+    // pt.table (or NULL): `cache` and `v` are pools of 64-token pages, [page][KV head] each a key tile and 64 value
+    // rows; logical tile j of sequence s lives in page pt.table[s * pt.stride + j] (clamped to the pool)
     constexpr int D = P::D;
     constexpr int KK = D / 16;               // k-steps of the score product
     constexpr int NB = D / 32;               // 32-channel blocks of the output
@@ -92,8 +95,10 @@ __global__ __launch_bounds__(kWave *NW) __attribute__((amdgpu_waves_per_eu(P::D 
     const int tile_begin = split * base + min(split, rem);
     const int tile_end = tile_begin + base + (split < rem ? 1 : 0);
 
-    const char *k_region = reinterpret_cast<const char *>(cache) + pair * shp.t_capacity * (P::GRANULES * 16);
-    const char *v_pair = reinterpret_cast<const char *>(v) + pair * shp.t_capacity * ROWB;
+    const bool paged = pt.table != nullptr;
+    const int kvh = static_cast<int>(pair % shp.n_kv_heads);
+    const char *k_region = reinterpret_cast<const char *>(cache) + (paged ? 0 : pair * shp.t_capacity * (P::GRANULES * 16));
+    const char *v_pair = reinterpret_cast<const char *>(v) + (paged ? 0 : pair * shp.t_capacity * ROWB);
 
     // Q^T operands of this wave's 32 rows: lane (n, h) holds coordinates 16 kk + 8 h .. + 8 of row n as
     // bf16 hi and lo.  The rotated queries lie [coordinate][row] with the ROWS rows of the block adjacent.
@@ -118,7 +123,13 @@ __global__ __launch_bounds__(kWave *NW) __attribute__((amdgpu_waves_per_eu(P::D 
         typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
         typedef uint32_t u32x3_t __attribute__((ext_vector_type(3)));
         constexpr int USED = (P::RECORD_BYTES + 3) / 4;
-        const char *src = k_region + static_cast<int64_t>(tile) * TILEB + lane * 16;
+        // position of the tile in the cache (in tiles): the logical tile, or its page's tile of this KV head
+        int64_t slot = tile;
+        if (paged) {
+            const int page = pt.table[static_cast<int64_t>(seq) * pt.stride + tile];
+            slot = static_cast<int64_t>(min(max(page, 0), pt.n_pages - 1)) * shp.n_kv_heads + kvh;
+        }
+        const char *src = k_region + slot * TILEB + lane * 16;
 #pragma unroll
         for (int g = 0; g < P::GRANULES; ++g) {
             const char *gp = src + g * (kWave * 16);
@@ -138,8 +149,9 @@ __global__ __launch_bounds__(kWave *NW) __attribute__((amdgpu_waves_per_eu(P::D 
             }
         }
         // value rows past the sequence's end are replaced by its last row (their probabilities are zero)
+        // (that row is in the same tile, hence in the same page)
         const int row = min(tile * kWave + lane, len - 1);
-        const char *vrow = v_pair + static_cast<int64_t>(row) * ROWB;
+        const char *vrow = v_pair + (slot * kWave + (row - tile * kWave)) * ROWB;
 #pragma unroll
         for (int i = 0; i < VP; ++i) vp[i] = *reinterpret_cast<const uint4 *>(vrow + (wave + NW * i) * 16);
     };
@@ -334,13 +346,15 @@ __global__ __launch_bounds__(kWave *NW) __attribute__((amdgpu_waves_per_eu(P::D 
 
 template <class P>
 int launch_decode_mq(const octopus_codebooks_t &cb, const DecodeShape &s, const float *q_rot, const void *cache,
-                     const void *v, const int32_t *seq_lens, float *part_ml, float *part_acc, hipStream_t stream) {
+                     const void *v, const int32_t *seq_lens, float *part_ml, float *part_acc, hipStream_t stream,
+                     PageTable pt) {
     const DeviceBooks books = device_books(cb);
     const int64_t units = static_cast<int64_t>(s.n_seq) * s.n_kv_heads * s.n_splits;
     const int64_t wgs = (units + kXcds - 1) / kXcds * kXcds * s.n_row_groups;   // see the kernel's work mapping
     auto go = [&](auto kernel, int waves) {
         hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(wgs)), dim3(kWave * waves), 0, stream, books, s, q_rot,
-                           static_cast<const uint4 *>(cache), static_cast<const uint16_t *>(v), seq_lens, part_ml, part_acc);
+                           static_cast<const uint4 *>(cache), static_cast<const uint16_t *>(v), seq_lens, part_ml, part_acc,
+                           pt);
     };
     if (s.rows_per_pass == 128) {
         go(decode_kernel_mq<P, 4>, 4);

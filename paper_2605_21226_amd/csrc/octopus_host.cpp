@@ -839,9 +839,11 @@ static int attn_decode_paged(const octopus_codebooks_t *cb, const void *q, int32
     const int ok = decode_args_ok(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len);
     if (ok != OCTOPUS_OK) return ok;
     if (q == nullptr || signs == nullptr || seq_lens == nullptr || out == nullptr) return OCTOPUS_EINVAL;
-    // A chunk of many query rows per KV head belongs to the many-row kernel, which is not built for pages: refused
-    // rather than run as hundreds of row groups that each read the keys again.
-    if (static_cast<int64_t>(n_q) * (n_q_heads / n_kv_heads) >= 32) return OCTOPUS_EUNSUPPORTED;
+    // A chunk of many query rows per KV head belongs to the many-row kernel (bf16 value pages, d <= 128, no QJL
+    // side-car); where that does not serve, the call is refused rather than run as hundreds of row groups that
+    // each read the keys again.
+    const bool many_rows = many_rows_shape(cb->plan, n_q_heads, n_kv_heads, n_q) && v_bits == 0 && qjl_pool == nullptr;
+    if (static_cast<int64_t>(n_q) * (n_q_heads / n_kv_heads) >= 32 && !many_rows) return OCTOPUS_EUNSUPPORTED;
     if (!plan_supported(cb->plan)) return OCTOPUS_EUNSUPPORTED;   // (a pair of the App. D sweep: no paged kernels)
     if (!page_table_ok(k_pool, n_pages, block_table, max_pages_per_seq) || v_pool == nullptr || !aligned(v_pool, 16))
         return OCTOPUS_EINVAL;
@@ -864,8 +866,8 @@ static int attn_decode_paged(const octopus_codebooks_t *cb, const void *q, int32
         vq_waves = vq_mfma_available(cb->plan, vq_mfma_rows(n_q * (n_q_heads / n_kv_heads)), v_bits, v_group);
         if (vq_waves <= 0) return OCTOPUS_EUNSUPPORTED;
     }
-    const DecodeShape s = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, reach, false, rows_cap,
-                                            vq_waves);
+    const DecodeShape s = make_decode_shape(cb->plan, n_seq, n_q_heads, n_kv_heads, n_q, max_len, reach, many_rows,
+                                            rows_cap, vq_waves);
     const Workspace w = make_workspace(cb->plan, s);
     const size_t required = std::max(w.total, octopus_attn_decode_workspace(cb, n_seq, n_q_heads, n_kv_heads, n_q, max_len));
     if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < required) return OCTOPUS_EWORKSPACE;
@@ -873,7 +875,7 @@ static int attn_decode_paged(const octopus_codebooks_t *cb, const void *q, int32
     float *q_rot = reinterpret_cast<float *>(base + w.q_rot_off);
     float *part_ml = reinterpret_cast<float *>(base + w.part_ml_off);
     float *part_acc = reinterpret_cast<float *>(base + w.part_acc_off);
-    int32_t *work_plan = reinterpret_cast<int32_t *>(base + w.plan_off);
+    int32_t *work_plan = many_rows ? nullptr : reinterpret_cast<int32_t *>(base + w.plan_off);
     float *q2 = with_qjl ? reinterpret_cast<float *>(base + w.q2_off) : nullptr;
     const PageTable pt{block_table, max_pages_per_seq, n_pages};
     int err = launch_rotate_queries(cb->plan, q, q_dtype, signs, s, scale, q_rot, seq_lens, work_plan,

@@ -39,20 +39,41 @@ def pools_from_logical(cb, records, v, table, n_pages, cap):
     return k_pool, v_pool
 
 
-def test_paged_decode_refuses_chunks_of_many_query_rows():
-    """32 or more query rows per KV head are the many-row kernel's, which is not built for pages."""
-    cb = binding.octopus_build_codebooks(128, 3)
-    q = torch.zeros((1, 11, 6, 128), dtype=torch.bfloat16, device=DEV)           # 11 queries x 3 heads per KV head
+def test_paged_decode_refuses_chunks_of_many_query_rows_where_no_many_row_kernel_serves():
+    """32 or more query rows per KV head are the many-row kernel's: built up to head_dim 128, bf16 value pages."""
+    cb = binding.octopus_build_codebooks(256, 3)
+    q = torch.zeros((1, 11, 6, 256), dtype=torch.bfloat16, device=DEV)           # 11 queries x 3 heads per KV head
     pool = torch.zeros(binding.octopus_paged_pool_bytes(cb, 4, 2), dtype=torch.uint8, device=DEV)
-    v_pool = torch.zeros((4, 2, 64, 128), dtype=torch.bfloat16, device=DEV)
+    v_pool = torch.zeros((4, 2, 64, 256), dtype=torch.bfloat16, device=DEV)
     table = torch.zeros((1, 4), dtype=torch.int32, device=DEV)
     lens = torch.tensor([200], dtype=torch.int32, device=DEV)
+    ws = torch.empty(binding.octopus_attn_decode_workspace(cb, 1, 6, 2, 11, 200), dtype=torch.uint8, device=DEV)
+    out = torch.zeros((1, 11, 6, 256), dtype=torch.float32, device=DEV)
+    signs = torch.zeros(2 * 32, dtype=torch.uint8, device=DEV)
+    with pytest.raises(binding.OctopusError) as err:
+        binding.octopus_attn_decode_paged(cb, q, signs, pool, v_pool, table, lens, 200, 0.1, out, ws)
+    assert err.value.code == binding.EUNSUPPORTED
+    # quantised value pages: the matrix-core kernel over them serves row groups, not chunks
+    cb = binding.octopus_build_codebooks(128, 3)
+    q = torch.zeros((1, 11, 6, 128), dtype=torch.bfloat16, device=DEV)
+    pool = torch.zeros(binding.octopus_paged_pool_bytes(cb, 4, 2), dtype=torch.uint8, device=DEV)
+    vq_pool = torch.zeros(4 * 2 * 64 * binding.octopus_vq_row_bytes(128, 3, 32), dtype=torch.uint8, device=DEV)
     ws = torch.empty(binding.octopus_attn_decode_workspace(cb, 1, 6, 2, 11, 200), dtype=torch.uint8, device=DEV)
     out = torch.zeros((1, 11, 6, 128), dtype=torch.float32, device=DEV)
     signs = torch.zeros(2 * 16, dtype=torch.uint8, device=DEV)
     with pytest.raises(binding.OctopusError) as err:
-        binding.octopus_attn_decode_paged(cb, q, signs, pool, v_pool, table, lens, 200, 0.1, out, ws)
+        binding.octopus_attn_decode_paged_vq(cb, q, signs, pool, vq_pool, 3, 32, 2, table, lens, 200, 0.1, out, ws)
     assert err.value.code == binding.EUNSUPPORTED
+
+
+@pytest.mark.parametrize("d,bits,n_qh,n_kv,n_q,lens", [
+    (128, 3, 6, 2, 11, [300, 129]),          # 33 rows per KV head: one block of 128 rows, mostly padding
+    (64, 4, 4, 1, 70, [1000, 64, 0]),        # 280 rows: blocks of 256 rows, two of them
+    (128, 2, 8, 2, 40, [2500]),              # 160 rows: two blocks of 128; several splits
+    (64, 2.5, 2, 2, 50, [200, 700])])        # 50 rows per KV head
+def test_paged_decode_many_query_rows(d, bits, n_qh, n_kv, n_q, lens):
+    """A chunk of queries over pages goes to the many-row kernel, as over a contiguous cache."""
+    run_paged_decode_case(d, bits, len(lens), n_qh, n_kv, n_q, lens, seed=int(2000 + d + 10 * bits + n_q))
 
 
 def run_paged_decode_case(d, bits, n_seq, n_qh, n_kv, n_q, lens, seed, q_dtype="bf16", spare_pages=5):
@@ -275,6 +296,8 @@ def test_paged_hybrid_gqa_window_32_d128(bits):
 def test_paged_hybrid_other_head_dims_fp32_window_keys_and_several_queries():
     run_paged_hybrid_case(64, 2.5, 3, 4, 4, 2, [130, 0, 64], [5, 40, 64], 64, "fp32", seed=1711)
     run_paged_hybrid_case(256, 3, 2, 4, 1, 1, [200, 31], [33, 32], 48, "bf16", seed=1712)
+    # 40 query rows per KV head: the many-row kernel over pages, plus the window
+    run_paged_hybrid_case(128, 3, 2, 8, 2, 10, [300, 70], [32, 9], 32, "bf16", seed=1714)
 
 
 def test_paged_hybrid_window_clipped_at_the_tables_reach_and_argument_errors():
