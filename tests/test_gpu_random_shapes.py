@@ -78,7 +78,7 @@ def test_variant_entry_points_random_shapes(seed):
             values.run_decode_vq_case(d, bits, v_bits, group, n_seq, n_kv * g, n_kv, n_q, lens, case_seed,
                                       want_scores=want_scores)
         elif variant == "paged":
-            n_q = min(n_q, 31 // g)          # (32 or more query rows per KV head are refused for pages)
+            n_q = min(n_q, 31 // g)          # (chunks of 32 or more query rows per KV head over pages: the test below)
             print(f"{head} lens={lens} n_q={n_q}", flush=True)
             paged.run_paged_decode_case(d, bits, n_seq, n_kv * g, n_kv, n_q, lens, case_seed,
                                         q_dtype="bf16" if rng.random() < 0.7 else "fp32")
@@ -100,3 +100,42 @@ def test_variant_entry_points_random_shapes(seed):
             rec, pad, _ = gpu_encode(cb, keys, dtype, signs, cap)
             assert not pad.any() and not rec[:, :, n_tok:].any()
             parity.compare_records(plan, keys, signs, rec, head)
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_paged_variant_entry_points_random_shapes(seed):
+    """The paged forms of the variants: window, quantised values, QJL side-car, and chunks of many query rows."""
+    rng = np.random.default_rng(9800 + seed)
+    for i in range(12):
+        d, bits, n_kv, g, n_q, lens = draw_shape(rng, max_tokens=12000)
+        n_seq = len(lens)
+        case_seed = 9900 + 100 * seed + i
+        variant = ("hybrid", "vq", "qjl", "many")[i % 4]
+        rows = n_q * g
+        if variant == "many":
+            if d == 256:
+                d = 128                                       # (the many-row kernel is built up to d = 128)
+            n_q = max(n_q, -(-32 // g))
+        elif rows >= 32 and (variant != "hybrid" or d == 256):
+            n_q = max(1, 31 // g)                             # those chunks are refused over pages
+        head = f"paged {variant} seed={seed} case={i}: d={d} bits={bits} n_kv={n_kv} g={g} n_q={n_q}"
+        if variant == "hybrid":
+            w_cap = int(rng.choice([1, 32, 64, 100]))
+            win = [int(x) for x in rng.integers(0, w_cap + 1, size=n_seq)]
+            k_dtype = "bf16" if rng.random() < 0.7 else "fp32"
+            print(f"{head} {k_dtype} w_cap={w_cap} win={win} lens={lens}", flush=True)
+            paged.run_paged_hybrid_case(d, bits, n_seq, n_kv * g, n_kv, n_q, lens, win, w_cap, k_dtype, case_seed)
+        elif variant == "vq":
+            v_bits, group = int(rng.choice([2, 3, 4])), int(rng.choice([16, 32]))
+            cb = binding.octopus_build_codebooks(d, bits)
+            if not binding.octopus_vq_on_matrix_cores(cb, n_kv * g, n_kv, n_q, v_bits, group):
+                v_bits, group, n_q = 3, 32, max(1, min(n_q, 4 // g))     # a shape every plan has a build for
+            print(f"{head} v_bits={v_bits} group={group} n_q={n_q} lens={lens}", flush=True)
+            assert binding.octopus_vq_on_matrix_cores(cb, n_kv * g, n_kv, n_q, v_bits, group)
+            paged.run_paged_vq_decode_case(d, bits, v_bits, group, n_seq, n_kv * g, n_kv, n_q, lens, case_seed)
+        elif variant == "qjl":
+            print(f"{head} lens={lens}", flush=True)
+            paged.run_paged_qjl_decode_case(d, bits, n_seq, n_kv * g, n_kv, n_q, lens, case_seed)
+        else:
+            print(f"{head} lens={lens}", flush=True)
+            paged.run_paged_decode_case(d, bits, n_seq, n_kv * g, n_kv, n_q, lens, case_seed)
