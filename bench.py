@@ -14,7 +14,8 @@ bytes (per key: the 58-byte canonical record + the 256-byte bf16 value row; plus
 divided by the call's average duration over the timed steps, measured with events on the launch stream.
 `roofline` is the same byte count over the fused kernel's own duration (events recorded by the library
 around its launch), against the published 8 TB/s.  `workloads` holds the other named configurations
-(30 warm-up + 50 timed calls, median: the protocol of the paper's kernel table), `encode_roofline` the
+(30 warm-up + 50 timed calls, median: the protocol of the paper's kernel table), `variants_on_llama3_8b_decode` the
+optional pieces (QJL residual, quantised values, window, paged cache) on the headline shape, `encode_roofline` the
 encoder against the fp32 vector issue rate, `cpu_baseline` the oracle on the host cores.
 """
 import argparse
@@ -52,7 +53,7 @@ def parse():
                          "bit width (octopus_build_codebooks_pair); workloads of head_dim 128, plain variant")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
-                    help="skip the `workloads` block (the other named configurations)")
+                    help="skip the `workloads` block (the other named configurations) and the `variants_on_...` block")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--rounding", type=int, default=1,
                     help="encoder rounding mode (App. E): 0 seed only, 1 local 3x3 (default), 2 full grid, "
@@ -508,6 +509,29 @@ def extras(args, dev):
     return out
 
 
+def variant_block(args, dev):
+    """The optional pieces on the headline workload (same protocol as `workloads`): the QJL residual, quantised
+    values, the native-precision window and the paged cache, each through its own entry points."""
+    import torch
+    from paper_2605_21226_amd import synth
+    wl = synth.WORKLOADS["llama3_8b_decode"]
+    out = {}
+    plan = [("qjl", {"qjl": True}), ("vq3g32", {"vq": "3:32"}), ("vq3g16", {"vq": "3:16"}), ("window32", {"window": 32}),
+            ("paged", {"paged": True}), ("paged_vq3g32", {"paged": True, "vq": "3:32"})]
+    for name, flags in plan:
+        try:
+            run = Run(wl, argparse.Namespace(**{**vars(args), **flags}), dev, variants=True)
+            res = measure_extra(run, encode_calls=4)
+            res["kernel"] = run.dominant_kernel()
+            res["value_row_bytes"] = run.decode_bytes()[3]
+            out[name] = res
+        except Exception as exc:    # a failing variant must not take the headline line with it
+            out[name] = {"error": f"{type(exc).__name__}: {exc}"}
+        run = None
+        torch.cuda.empty_cache()
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -702,6 +726,7 @@ def main():
         result["protocol_of_workloads"] = (f"{PROTOCOL_WARMUP} warm-up + {PROTOCOL_TIMED} timed decode calls back to back on a "
                                            "cache encoded once, median; kernel_ms: the fused kernel alone, median of 20")
         result["workloads"] = extras(args, dev)
+        result["variants_on_llama3_8b_decode"] = variant_block(args, dev)
     print(json.dumps(result))
 
 
