@@ -405,6 +405,9 @@ void encode_kernel(DeviceBooks books, const void *__restrict__ keys,
         const int64_t tok_lo = max(tile * kWave, start);
         const int64_t tok_hi = min((tile + 1) * kWave, tok_end);
         if (tok_lo >= tok_hi) break;   // uniform over the workgroup
+        // paged cache: the tile's page is asked for now and used when the tile is stored, phases later
+        int page_asked = 0;
+        if (pt.table != nullptr) page_asked = pt.table[static_cast<int64_t>(seq) * pt.stride + tile];
         __syncthreads();               // the previous tile's records have been stored; tables are complete
         // word 0 (gamma) is written whole by the transform phase below; the code words are OR-ed into
         for (int e = kWave + tid; e < P::NWORDS * kWave; e += NT) sm.rec[e / kWave][e % kWave] = 0u;
@@ -514,7 +517,7 @@ void encode_kernel(DeviceBooks books, const void *__restrict__ keys,
         // pt.table[s * pt.stride + j] (clamped to the pool)
         uint4 *dst = region + tile * (P::GRANULES * kWave);
         if (pt.table != nullptr) {
-            const int page = pt.table[static_cast<int64_t>(seq) * pt.stride + tile];
+            const int page = page_asked;
             dst = cache + (static_cast<int64_t>(min(max(page, 0), pt.n_pages - 1)) * n_kv_heads + kvh) * (P::GRANULES * kWave);
         }
         for (int e = tid; e < P::GRANULES * kWave; e += NT) {
@@ -558,7 +561,7 @@ void encode_kernel(DeviceBooks books, const void *__restrict__ keys,
             constexpr int TQ = kWave * (D / 8 + 2);   // side-car bytes per tile
             unsigned char *qt = qjl + ((static_cast<int64_t>(seq) * n_kv_heads + kvh) * (t_capacity / kWave) + tile) * TQ;
             if (pt.table != nullptr) {   // the side-car in pages: a pool of [page][KV head] tiles, like the keys'
-                const int page = pt.table[static_cast<int64_t>(seq) * pt.stride + tile];
+                const int page = page_asked;
                 qt = qjl + (static_cast<int64_t>(min(max(page, 0), pt.n_pages - 1)) * n_kv_heads + kvh) * TQ;
             }
             const int64_t tok = tile * kWave + lane;
