@@ -521,7 +521,7 @@ def variant_block(args, dev):
     for name, flags in plan:
         try:
             run = Run(wl, argparse.Namespace(**{**vars(args), **flags}), dev, variants=True)
-            res = measure_extra(run, encode_calls=4)
+            res = measure_extra(run, encode_calls=8)
             res["kernel"] = run.dominant_kernel()
             res["value_row_bytes"] = run.decode_bytes()[3]
             out[name] = res
