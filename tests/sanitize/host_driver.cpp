@@ -98,6 +98,35 @@ int main() {
             EXPECT(octopus_attn_decode_paged(&cb, p, OCTOPUS_DTYPE_BF16, 3, 8, 2, 1, fake, p, p, 40, table, 15,
                                              reinterpret_cast<const int32_t *>(fake), 1000, 0.1f, reinterpret_cast<float *>(fake),
                                              wsp, ws, nullptr) == OCTOPUS_EINVAL);      // the table cannot hold max_len
+            // the paged forms of the variants: window, quantised values (3 bits, groups of 32: the stub's one build),
+            // the QJL side-car, a chunk of 40 query rows per KV head (the many-row kernel, up to head_dim 128)
+            const int32_t *ip = reinterpret_cast<const int32_t *>(fake);
+            float *fp = reinterpret_cast<float *>(fake);
+            EXPECT(octopus_attn_decode_paged_hybrid(&cb, p, OCTOPUS_DTYPE_BF16, 3, 8, 2, 1, fake, p, p, 40, table, 16, ip, 1000,
+                                                    p, OCTOPUS_DTYPE_BF16, 32, ip, 0.1f, fp, wsp, ws, nullptr) == OCTOPUS_OK);
+            EXPECT(octopus_attn_decode_paged_hybrid(&cb, p, OCTOPUS_DTYPE_BF16, 3, 8, 2, 1, fake, p, p, 40, table, 16, ip, 1000,
+                                                    p, OCTOPUS_DTYPE_BF16, 0, ip, 0.1f, fp, wsp, ws, nullptr) == OCTOPUS_EINVAL);
+            EXPECT(octopus_attn_decode_paged_vq(&cb, p, OCTOPUS_DTYPE_BF16, 3, 8, 2, 1, fake, p, p, 3, 32, 40, table, 16, ip, 1000,
+                                                0.1f, fp, wsp, ws, nullptr) == OCTOPUS_OK);
+            EXPECT(octopus_attn_decode_paged_vq(&cb, p, OCTOPUS_DTYPE_BF16, 3, 8, 2, 1, fake, p, p, 3, 16, 40, table, 16, ip, 1000,
+                                                0.1f, fp, wsp, ws, nullptr) == OCTOPUS_EUNSUPPORTED);   // (no such build in the stub)
+            EXPECT(octopus_attn_decode_paged_qjl(&cb, p, OCTOPUS_DTYPE_BF16, 3, 8, 2, 1, fake, fake, p, p, p, 40, table, 16, ip,
+                                                 1000, 0.1f, fp, wsp, ws, nullptr) == OCTOPUS_OK);
+            EXPECT(octopus_attn_decode_paged_qjl(&cb, p, OCTOPUS_DTYPE_BF16, 3, 8, 2, 1, fake, nullptr, p, p, p, 40, table, 16, ip,
+                                                 1000, 0.1f, fp, wsp, ws, nullptr) == OCTOPUS_EINVAL);
+            EXPECT(octopus_encode_qjl_paged(&cb, p, OCTOPUS_DTYPE_BF16, 8 * d, d, d, 1, 1, 8, fake, fake, p, p, 40, table, 16,
+                                            nullptr, nullptr) == OCTOPUS_OK);
+            EXPECT(octopus_encode_values_paged(p, OCTOPUS_DTYPE_BF16, 8 * d, d, d, 1, 1, 8, d, 3, 32, p, 40, table, 16, nullptr,
+                                               nullptr) == OCTOPUS_OK);
+            {
+                const size_t ws40 = octopus_attn_decode_workspace(&cb, 1, 8, 2, 10, 1000);
+                std::vector<unsigned char> buf40(ws40 + 512);
+                void *w40 = reinterpret_cast<void *>((reinterpret_cast<uintptr_t>(buf40.data()) + 255) & ~uintptr_t(255));
+                EXPECT(octopus_attn_decode_paged(&cb, p, OCTOPUS_DTYPE_BF16, 1, 8, 2, 10, fake, p, p, 40, table, 16, ip, 1000, 0.1f,
+                                                 fp, w40, ws40, nullptr) == (d <= 128 ? OCTOPUS_OK : OCTOPUS_EUNSUPPORTED));
+                EXPECT(octopus_attn_decode_paged_vq(&cb, p, OCTOPUS_DTYPE_BF16, 1, 8, 2, 10, fake, p, p, 3, 32, 40, table, 16, ip,
+                                                    1000, 0.1f, fp, w40, ws40, nullptr) == OCTOPUS_EUNSUPPORTED);
+            }
             EXPECT(octopus::g_launches > before);
             // the entry point on the static scratch: refused before any runtime call when the shapes exceed it;
             // otherwise it needs a device for the array's address and reports the runtime's refusal
