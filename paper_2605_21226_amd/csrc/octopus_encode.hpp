@@ -238,14 +238,18 @@ __device__ __forceinline__ void encode_triplet(float x, float y, float z, const 
             sc[3 * a + b] = fmaf(z, n.z, fmaf(yb[b], n.y, xa[a] * n.x));
         }
     }
-    const float best = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])),
-                             fmaxf(fmaxf(sc[4], sc[5]), fmaxf(fmaxf(sc[6], sc[7]), sc[8])));
-    // the winner as (dx + 1) + 4 (dy + 1): small constants through the selects, the code built once afterwards
-    uint32_t pick = 2u + 4u * 2u;
-#pragma unroll
-    for (int i = 7; i >= 0; --i) pick = (sc[i] == best) ? static_cast<uint32_t>(i / 3 + 4 * (i % 3)) : pick;
-    const int cx = min(max(jx + static_cast<int>(pick & 3u) - 1, 0), K - 1);
-    const int cy = min(max(jy + static_cast<int>(pick >> 2) - 1, 0), K - 1);
+    // the maximum per dx, then overall; the winner is the first dx whose maximum attains it and, of that dx's three
+    // candidates, the first that does (the order of Alg. 1's loop: dx outer, dy inner), found with two compares per
+    // level instead of one per candidate
+    const float row0 = fmaxf(fmaxf(sc[0], sc[1]), sc[2]), row1 = fmaxf(fmaxf(sc[3], sc[4]), sc[5]),
+                row2 = fmaxf(fmaxf(sc[6], sc[7]), sc[8]);
+    const float best = fmaxf(fmaxf(row0, row1), row2);
+    const bool in0 = row0 == best, in1 = row1 == best;
+    const int pick_x = in0 ? 0 : (in1 ? 1 : 2);
+    const float first = in0 ? sc[0] : (in1 ? sc[3] : sc[6]), second = in0 ? sc[1] : (in1 ? sc[4] : sc[7]);
+    const int pick_y = first == best ? 0 : (second == best ? 1 : 2);
+    const int cx = min(max(jx + pick_x - 1, 0), K - 1);
+    const int cy = min(max(jy + pick_y - 1, 0), K - 1);
     const uint32_t best_code = static_cast<uint32_t>(cx | (cy << BD));
     const float cs = fminf(fmaxf(best, 0.0f), 1.0f);
     int r = 0;
