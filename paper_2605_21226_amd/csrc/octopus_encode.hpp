@@ -76,7 +76,7 @@ struct EncodeSmem {
     float c_rho[2][kMaxLevels];
     float bnd_xi[2][kMaxLevels + 1];       // boundaries, +inf padded
     float bnd_rho[2][kMaxLevels];
-    float sumsq[kWave];                    // squared norm of each key of the tile
+    float sumsq[kWave];                    // squared norm of each key of the tile, then its scale factor 1 / (gamma sqrt(d))
     float res_sq[QJL ? encode_waves<P>() : 1][QJL ? kWave : 1];   // QJL side-car: squared residual norm, partial per wavefront
 };
 
@@ -445,11 +445,14 @@ void encode_kernel(DeviceBooks books, const void *__restrict__ keys,
         // E3: Walsh-Hadamard transform, one key per lane, two radix passes through LDS
         {
             constexpr int R2 = D / 16;
-            // the norm of this lane's key, once per key and wavefront (the load phase has 4 to 32 lanes per key,
-            // and a square root and a division cost as much there for one active lane as for 64)
-            const float gamma = sqrtf(sm.sumsq[lane]);
-            const float norm = (1.0f / fmaxf(gamma, kEps)) * inv_sqrt_dim<D>();
-            if (wave == 0) sm.rec[0][lane] = __float_as_uint(gamma);
+            // the norm of every key, once per key: by one wavefront, 64 keys at a time (the load phase has 4 to 32
+            // lanes per key, and a square root and a division cost as much there for one active lane as for 64); the
+            // scale factor replaces the sum of squares in LDS and is read by all after the barrier between the passes
+            if (wave == NWV - 1) {
+                const float gamma = sqrtf(sm.sumsq[lane]);
+                sm.rec[0][lane] = __float_as_uint(gamma);
+                sm.sumsq[lane] = (1.0f / fmaxf(gamma, kEps)) * inv_sqrt_dim<D>();
+            }
             for (int g = wave; g < D / 16; g += NWV) {
                 float x[16];
 #pragma unroll
@@ -459,6 +462,7 @@ void encode_kernel(DeviceBooks books, const void *__restrict__ keys,
                 for (int e = 0; e < 16; ++e) sm.u[g * 16 + e][lane] = x[e];
             }
             __syncthreads();
+            const float norm = sm.sumsq[lane];
             for (int lo = wave; lo < 16; lo += NWV) {
                 float x[R2];
 #pragma unroll
