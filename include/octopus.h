@@ -473,7 +473,8 @@ int octopus_attn_decode_paged_vq(const octopus_codebooks_t *cb,
  * octopus_encode_qjl_paged: octopus_encode_paged that also writes the side-car (signs2 as for
  * octopus_encode_qjl); codes and side-car are byte for byte those of octopus_encode_qjl.
  * octopus_attn_decode_paged_qjl: octopus_attn_decode_paged with the corrected score of
- * octopus_attn_decode_qjl (bf16 value pages; row groups as there).  EINVAL if signs2 or qjl_pool is NULL;
+ * octopus_attn_decode_qjl (bf16 value pages; row groups as there; 32 or more query rows per KV head are
+ * refused with EUNSUPPORTED).  EINVAL if signs2 or qjl_pool is NULL;
  * other arguments, workspace and errors as octopus_encode_paged / octopus_attn_decode_paged. */
 int octopus_encode_qjl_paged(const octopus_codebooks_t *cb,
                              const void *keys, int32_t key_dtype,
