@@ -50,8 +50,9 @@ def run_full_size(name, bits, pairs, q_rows, seed=0, chunked_encode=False, varia
     """pairs: (sequence, KV head) pairs to check, or "all"; q_rows: query positions (of n_q) to check;
     score_seqs: sequences whose scaled scores are checked as well (a second decode call, with score output, whose
     outputs are checked like the first call's);
-    variant: None, "qjl", ("vq", bits, group), ("window", tokens) or "paged" (the cache scattered over pages in a
-    random order, encoded once more straight into the pages, attention from the pages)"""
+    variant: None, "qjl", ("vq", bits, group), ("window", tokens), "paged" (the cache scattered over pages in a
+    random order, encoded once more straight into the pages, attention from the pages) or ("paged_vq", bits, group)
+    (the same with the values quantised straight into pages)"""
     base = synth.WORKLOADS[name]
     wl = synth.Workload(**{**base.__dict__, "bits": bits})
     cb = binding.octopus_build_codebooks(wl.head_dim, bits)
@@ -75,6 +76,9 @@ def run_full_size(name, bits, pairs, q_rows, seed=0, chunked_encode=False, varia
         signs2 = synth.sign_vectors(seed + 1, n_kv, d)
         s2bits = torch.from_numpy(synth.sign_bits(signs2)).to(DEV)
         side = torch.zeros(binding.octopus_qjl_bytes(cb, wl.n_seq, n_kv, cap), dtype=torch.uint8, device=DEV)
+    paged_vq = kind == "paged_vq"
+    if paged_vq:
+        kind = "vq"          # contiguous quantised rows are the reference layout; the decode call reads pages
     if kind == "vq":
         _, v_bits, v_group = variant
         vq = torch.zeros(binding.octopus_vq_bytes(d, v_bits, v_group, wl.n_seq, n_kv, cap), dtype=torch.uint8, device=DEV)
@@ -130,7 +134,7 @@ def run_full_size(name, bits, pairs, q_rows, seed=0, chunked_encode=False, varia
             side[(s * n_kv + h) * img.size:(s * n_kv + h + 1) * img.size] = torch.from_numpy(img).to(DEV)
     print(f"[full] {name} b={bits} {variant or ''}: decode attention", flush=True)
     lens_dev = torch.from_numpy(lens).to(DEV)
-    if kind == "paged":
+    if kind == "paged" or paged_vq:
         tiles = cap // 64
         n_pages = wl.n_seq * tiles + 7
         gen = torch.Generator(device="cpu").manual_seed(seed + 5)
@@ -149,8 +153,20 @@ def run_full_size(name, bits, pairs, q_rows, seed=0, chunked_encode=False, varia
             same[table[s].long(), h] = True
         assert bool(same.all()), "octopus_encode_paged and octopus_encode wrote different tiles"
         del k_pool2, same
+        if paged_vq:
+            # the values quantised straight into pages: every row equal to the contiguous encoder's
+            del v_pool
+            rb = binding.octopus_vq_row_bytes(d, v_bits, v_group)
+            vq_pool = torch.full((n_pages, n_kv, 64, rb), 0x5A, dtype=torch.uint8, device=DEV)
+            binding.octopus_encode_values_paged(vals.permute(0, 2, 1, 3), v_bits, v_group, vq_pool, n_kv, table)
+            want = vq.reshape(wl.n_seq, n_kv, tiles, 64, rb).permute(0, 2, 1, 3, 4).reshape(-1, n_kv, 64, rb)
+            assert torch.equal(vq_pool[flat], want), "octopus_encode_values_paged and octopus_encode_values wrote different rows"
+            del want
     if kind == "qjl":
         binding.octopus_attn_decode_qjl(cb, q, sbits, s2bits, cache, side, cap, vals, lens_dev, max_len, scale, out, ws)
+    elif paged_vq:
+        binding.octopus_attn_decode_paged_vq(cb, q, sbits, k_pool, vq_pool.reshape(-1), v_bits, v_group, n_kv, table,
+                                             lens_dev, max_len, scale, out, ws)
     elif kind == "vq":
         binding.octopus_attn_decode_vq(cb, q, sbits, cache, cap, vq, v_bits, v_group, n_kv, lens_dev, max_len, scale, out, ws)
     elif kind == "window":
@@ -260,3 +276,7 @@ def test_full_llama3_8b_decode_window():
 
 def test_full_llama3_8b_decode_paged():
     run_full_size("llama3_8b_decode", 3.0, [(3, 5), (15, 7)], [0], variant="paged")
+
+
+def test_full_llama3_8b_decode_paged_quantised_values():
+    run_full_size("llama3_8b_decode", 3.0, [(6, 1), (11, 4)], [0], variant=("paged_vq", 3, 32))
