@@ -479,6 +479,21 @@ void encode_kernel(DeviceBooks books, const void *__restrict__ keys,
             constexpr int CHUNK = (P::NTRI + NWV - 1) / NWV;
             const int i_end = min(P::NTRI, (wave + 1) * CHUNK);
             float rsq = 0.0f;
+            // The norm thresholds of the default encoder in registers where they are few (up to 3 norm bits; the loop's
+            // LDS atomics keep the compiler from hoisting the read itself, and LDS is this kernel's limit); with more
+            // levels they stay in LDS, as registers are what six wavefronts per SIMD have least of.
+            constexpr bool THR0_REG = P::BN0 <= 3, THR1_REG = P::NCLASS == 2 && P::BN1 >= 1 && P::BN1 <= 3;
+            float thr0_reg[THR0_REG ? (1 << P::BN0) : 1], thr1_reg[THR1_REG ? (1 << P::BN1) : 1];
+            if constexpr (THR0_REG) {
+#pragma unroll
+                for (int k = 0; k < (1 << P::BN0) - 1; ++k) thr0_reg[k] = sm.bnd_rho[0][k];
+            }
+            if constexpr (THR1_REG) {
+#pragma unroll
+                for (int k = 0; k < (1 << P::BN1) - 1; ++k) thr1_reg[k] = sm.bnd_rho[1][k];
+            }
+            const float *thr0 = THR0_REG ? thr0_reg : sm.bnd_rho[0];
+            const float *thr1 = THR1_REG ? thr1_reg : sm.bnd_rho[1];
             for (int i = wave * CHUNK; i < i_end; ++i) {
                 const float x = sm.u[3 * i][lane], y = sm.u[3 * i + 1][lane], z = sm.u[3 * i + 2][lane];
                 uint32_t dir_field, nrm_index;
@@ -490,7 +505,7 @@ void encode_kernel(DeviceBooks books, const void *__restrict__ keys,
                                                                       sm.bnd_rho[0], lane, mode, &dir_field, &nrm_index);
                     else
                         encode_triplet<P::BD0, P::BN0, REP, CREP>(x, y, z, sm.lut0, sm.cell0, sm.nbx0, sm.nby0,
-                                                                  sm.bnd_xi[0], sm.bnd_rho[0], lane, &dir_field, &nrm_index);
+                                                                  sm.bnd_xi[0], thr0, lane, &dir_field, &nrm_index);
                     or_bits(sm.rec, lane, P::DIR0_BIT + i * 2 * P::BD0, 2 * P::BD0, dir_field);
                     or_bits(sm.rec, lane, P::NRM0_BIT + i * P::BN0, P::BN0, nrm_index);
                     if constexpr (QJL) { nhat = dir_lookup<P::BD0, REP>(sm.lut0, dir_field, lane); rho = sm.c_rho[0][nrm_index]; }
@@ -501,7 +516,7 @@ void encode_kernel(DeviceBooks books, const void *__restrict__ keys,
                                                                           sm.bnd_rho[1], lane, mode, &dir_field, &nrm_index);
                         else
                             encode_triplet<P::BD1, P::BN1, REP, CREP>(x, y, z, sm.lut1, sm.cell1, sm.nbx1, sm.nby1,
-                                                                      sm.bnd_xi[1], sm.bnd_rho[1], lane, &dir_field, &nrm_index);
+                                                                      sm.bnd_xi[1], thr1, lane, &dir_field, &nrm_index);
                         or_bits(sm.rec, lane, P::DIR1_BIT + (i - P::NT0) * 2 * P::BD1, 2 * P::BD1, dir_field);
                         or_bits(sm.rec, lane, P::NRM1_BIT + (i - P::NT0) * P::BN1, P::BN1, nrm_index);
                         if constexpr (QJL) { nhat = dir_lookup<P::BD1, REP>(sm.lut1, dir_field, lane); rho = sm.c_rho[1][nrm_index]; }
