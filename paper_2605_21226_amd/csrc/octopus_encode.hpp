@@ -1,5 +1,5 @@
-// Online key encoder (Alg. 1 with the local 3x3 candidate set): a workgroup of 4 or 8 wavefronts takes four
-// consecutive 64-token cache tiles of one (sequence, KV head), one after the other.
+// Online key encoder (Alg. 1 with the local 3x3 candidate set): a workgroup of 4 or 8 wavefronts takes one to
+// eight consecutive 64-token cache tiles of one (sequence, KV head), one after the other.
 #ifndef OCTOPUS_ENCODE_HPP_
 #define OCTOPUS_ENCODE_HPP_
 
@@ -319,7 +319,15 @@ __device__ __forceinline__ void or_bits(uint32_t (*rec)[kWave], int key, int bit
     if (sh + nbits > 32) atomicOr(&rec[wi + 1][key], v >> (32 - sh));
 }
 
-constexpr int kEncodeTilesPerGroup = 4;  // consecutive cache tiles per workgroup (tables are built once)
+// Consecutive cache tiles one workgroup takes, its tables built once for all of them: eight where that still leaves
+// the launch several workgroups per place on the chip (a long prefill: the tables cost a fifth of a tile's time),
+// fewer for shorter calls, down to one, so that a short chunk still spreads over the compute units.
+inline int encode_tiles_per_group(int tiles, int n_kv_heads, int n_seq) {
+    constexpr int64_t kEnough = 3072;   // 256 compute units x 3 resident workgroups x 4
+    for (int t = 8; t > 1; t >>= 1)
+        if (static_cast<int64_t>((tiles + t - 1) / t) * n_kv_heads * n_seq >= kEnough) return t;
+    return 1;
+}
 
 // QJL: also write the optional side-car of Sec. 3.6 (1-bit QJL residual): the residual r = u - u^ of the
 // rotated unit key replaces u in LDS as the triplets are encoded, a second sign-flipped Hadamard
@@ -335,7 +343,8 @@ void encode_kernel(DeviceBooks books, const void *__restrict__ keys,
                                                       uint4 *__restrict__ cache, int64_t t_capacity,
                                                       const int32_t *__restrict__ start_pos, int32_t n_kv_heads,
                                                       const uint8_t *__restrict__ signs2,
-                                                      unsigned char *__restrict__ qjl, int32_t mode, PageTable pt) {
+                                                      unsigned char *__restrict__ qjl, int32_t mode, PageTable pt,
+                                                      int32_t tiles_per_group) {
     constexpr int D = P::D;
     constexpr int LPR = D / 8;        // threads per key row in the load phase
     constexpr int NWV = encode_waves<P>(), NT = encode_threads<P>();
@@ -349,7 +358,7 @@ void encode_kernel(DeviceBooks books, const void *__restrict__ keys,
     const int kvh = blockIdx.y, seq = blockIdx.z;
     const int64_t start = start_pos ? max(start_pos[seq], 0) : 0;   // (a negative position would write before the cache)
     const int64_t tok_end = min(start + n_new, t_capacity);
-    const int64_t first_tile = start / kWave + static_cast<int64_t>(blockIdx.x) * kEncodeTilesPerGroup;
+    const int64_t first_tile = start / kWave + static_cast<int64_t>(blockIdx.x) * tiles_per_group;
     if (max(first_tile * kWave, start) >= tok_end) return;
 
     const int64_t head_base = seq * stride_seq + kvh * stride_head;
@@ -404,7 +413,7 @@ void encode_kernel(DeviceBooks books, const void *__restrict__ keys,
     }
     for (int e = tid; e < (3 * P::NTRI - D) * kWave; e += NT) sm.u[D + e / kWave][e % kWave] = 0.0f;
 
-    for (int tg = 0; tg < kEncodeTilesPerGroup; ++tg) {
+    for (int tg = 0; tg < tiles_per_group; ++tg) {
         const int64_t tile = first_tile + tg;
         const int64_t tok_lo = max(tile * kWave, start);
         const int64_t tok_hi = min((tile + 1) * kWave, tok_end);
@@ -439,7 +448,7 @@ void encode_kernel(DeviceBooks books, const void *__restrict__ keys,
             for (int e = 0; e < 8; ++e) sm.u[col + e][key] = ((sbits >> e) & 1u) ? -x[e] : x[e];
             if (tid % LPR == 0) sm.sumsq[key] = ss;
         }
-        if (tg + 1 < kEncodeTilesPerGroup) fetch_tile(tile + 1);
+        if (tg + 1 < tiles_per_group) fetch_tile(tile + 1);
         __syncthreads();
 
         // E3: Walsh-Hadamard transform, one key per lane, two radix passes through LDS
@@ -614,12 +623,13 @@ int launch_encode_plan(const octopus_codebooks_t &cb, const void *keys, int key_
     const DeviceBooks books = device_books(cb);
     // a start that is not a multiple of 64 makes the new tokens straddle one more tile
     const int tiles = (n_new + kWave - 1) / kWave + (start_pos ? 1 : 0);
-    const dim3 grid((tiles + kEncodeTilesPerGroup - 1) / kEncodeTilesPerGroup, n_kv_heads, n_seq);
+    const int tpg = encode_tiles_per_group(tiles, n_kv_heads, n_seq);
+    const dim3 grid((tiles + tpg - 1) / tpg, n_kv_heads, n_seq);
     const bool bf16 = key_dtype == OCTOPUS_DTYPE_BF16;
     auto go = [&](auto kernel) {
         hipLaunchKernelGGL(kernel, grid, dim3(encode_threads<P>()), 0, stream, books, keys, stride_seq, stride_tok, stride_head, n_new,
                            signs, static_cast<uint4 *>(cache), t_capacity, start_pos, n_kv_heads, signs2,
-                           static_cast<unsigned char *>(qjl), 1, pt);
+                           static_cast<unsigned char *>(qjl), 1, pt, tpg);
     };
     if (qjl != nullptr) {
         if (bf16) go(encode_kernel<P, true, true>); else go(encode_kernel<P, false, true>);
@@ -637,11 +647,12 @@ int launch_encode_basic_plan(const octopus_codebooks_t &cb, const void *keys, in
                              hipStream_t stream) {
     const DeviceBooks books = device_books(cb);
     const int tiles = (n_new + kWave - 1) / kWave + (start_pos ? 1 : 0);
-    const dim3 grid((tiles + kEncodeTilesPerGroup - 1) / kEncodeTilesPerGroup, n_kv_heads, n_seq);
+    const int tpg = encode_tiles_per_group(tiles, n_kv_heads, n_seq);
+    const dim3 grid((tiles + tpg - 1) / tpg, n_kv_heads, n_seq);
     auto go = [&](auto kernel) {
         hipLaunchKernelGGL(kernel, grid, dim3(encode_threads<P>()), 0, stream, books, keys, stride_seq, stride_tok, stride_head, n_new,
                            signs, static_cast<uint4 *>(cache), t_capacity, start_pos, n_kv_heads, nullptr, nullptr, 1,
-                           PageTable{nullptr, 0, 0});
+                           PageTable{nullptr, 0, 0}, tpg);
     };
     if (key_dtype == OCTOPUS_DTYPE_BF16) go(encode_kernel<P, true, false>);
     else go(encode_kernel<P, false, false>);
@@ -656,11 +667,12 @@ int launch_encode_rounding_plan(const octopus_codebooks_t &cb, const void *keys,
                                 const int32_t *start_pos, int32_t mode, hipStream_t stream) {
     const DeviceBooks books = device_books(cb);
     const int tiles = (n_new + kWave - 1) / kWave + (start_pos ? 1 : 0);
-    const dim3 grid((tiles + kEncodeTilesPerGroup - 1) / kEncodeTilesPerGroup, n_kv_heads, n_seq);
+    const int tpg = encode_tiles_per_group(tiles, n_kv_heads, n_seq);
+    const dim3 grid((tiles + tpg - 1) / tpg, n_kv_heads, n_seq);
     auto go = [&](auto kernel) {
         hipLaunchKernelGGL(kernel, grid, dim3(encode_threads<P>()), 0, stream, books, keys, stride_seq, stride_tok, stride_head, n_new,
                            signs, static_cast<uint4 *>(cache), t_capacity, start_pos, n_kv_heads, nullptr, nullptr, mode,
-                           PageTable{nullptr, 0, 0});
+                           PageTable{nullptr, 0, 0}, tpg);
     };
     if (key_dtype == OCTOPUS_DTYPE_BF16) go(encode_kernel<P, true, false, true>);
     else go(encode_kernel<P, false, false, true>);
